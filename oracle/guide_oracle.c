@@ -1,0 +1,743 @@
+/*
+ * guide_oracle.c -- plain, slow, single-threaded fp64 CPU evaluator of the GUIDE
+ * deployment-optimiser hot path (arXiv 2412.04788).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is the reference the HIP library is checked
+ * against; only the tests, the smoke check and the benchmark's CPU-baseline
+ * leg may call it.  It shares no code, table or constant with the GPU path.
+ *
+ * What it follows.  The paper gives the structure of the model and leaves the
+ * per-operator terms open; where it is silent the reading taken here is
+ * written next to the function.
+ *   - Inference Engine, Step 1 (available memory = GPU memory - model slice,
+ *     max batch = available / kv per request) and Model Analyzer, "Dynamic
+ *     Batch Size Adjustment" (kv bytes per request = 2 N H S kv, B_max):
+ *     ora_memory().
+ *   - Model Analyzer sub-batch splitting and sequence segmenting ("Dynamic
+ *     Batch Size Adjustment", "Dynamic Sequence Length Adjustment"):
+ *     ora_prefill().
+ *   - Parallel Simulator, "Roofline Model for Performance Analysis" and "Time
+ *     Calculation" (compute time = load / power, read-write time = data / BW,
+ *     transfer time = transferred / comm BW): ora_pass().
+ *   - Inference Engine, Step 2 (task list of prefill and decode tasks; TPOT,
+ *     throughput = 1/TPOT; TTFT): ora_eval().
+ *   - Parallel Simulator, "Simulating Hybrid Parallelism" (enumerate all
+ *     configurations, minimise total time, keep the best three) and the
+ *     engine's "lowest inference time and highest throughput":
+ *     ora_select_topk(), ora_pareto_*().
+ *   - Overview ("simulates the dynamic batch processing and dynamic split
+ *     flow"): ora_simulate(); the paper names it only, the algorithm is the
+ *     documented step-level definition.
+ *
+ * Pins (tests/test_oracle_pins.py): parameter counts of public shapes,
+ * 2*params*tokens FLOPs, batch-1 decode = weight bytes / BW, the paper's
+ * printed kv formula and B_max, feasibility boundary, monotonicity, scaling
+ * laws, single-request simulation == analytic latency, brute-force select,
+ * numpy's Philox for the counter-based generator.  No function here is
+ * "parity unpinned".
+ *
+ * Build: gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC (no FMA
+ * contraction, so every expression rounds as written).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct { uint32_t L, d, n_h, n_kv, d_ff, V, E, k; } ora_model;
+typedef struct { double peak, bw, cap, link_bw, link_lat; } ora_hw;
+typedef struct { uint64_t b, s_in, s_out, p, wbits, blk, mbt; } ora_knobs;
+typedef struct {
+    double t_prefill, t_decode, t_batch, decode_tok_s, cost, tpot;
+    uint32_t b_max;
+    uint32_t feasible;
+} ora_metrics;
+
+enum { ORA_ROOFLINE = 0, ORA_ADDITIVE = 1 };
+enum { ORA_N_OPS = 8 };  /* qkv, attn, o-proj, ffn-up, ffn-down, router, norms, lm-head */
+
+static const double ACT_BYTES = 2.0;  /* activation bytes per element  */
+static const double KV_BYTES = 2.0;   /* bytes per cached K or V element */
+
+/* ---------------------------------------------------------------- parameters */
+
+static double p_attn(const ora_model *m) {
+    double d = m->d, dh = (double)(m->d / m->n_h);
+    double dq = m->n_h * dh, dkv = m->n_kv * dh;
+    return d * dq + 2.0 * d * dkv + dq * d;
+}
+static double p_f1(const ora_model *m) { return 2.0 * (double)m->d * (double)m->d_ff; } /* gate + up */
+static double p_f2(const ora_model *m) { return (double)m->d_ff * (double)m->d; }
+static double p_rt(const ora_model *m) { return m->E > 1 ? (double)m->d * (double)m->E : 0.0; }
+
+/* Total stored parameters: L layers (all experts) + embedding + untied LM head. */
+double ora_params_total(const ora_model *m) {
+    double layer = p_attn(m) + (double)m->E * (p_f1(m) + p_f2(m)) + p_rt(m);
+    return (double)m->L * layer + 2.0 * (double)m->V * (double)m->d;
+}
+/* Parameters one token touches in one layer (top-k experts only). */
+double ora_params_layer_active(const ora_model *m) {
+    return p_attn(m) + (double)m->k * (p_f1(m) + p_f2(m)) + p_rt(m);
+}
+
+/* ------------------------------------------------------------- one pass (task) */
+
+/* Roofline time of one task: the larger of compute time and read/write time
+ * (Parallel Simulator, Roofline Model); the additive variant sums them (Time
+ * Calculation). */
+static double op_time(double F, double B, double P, double BW, int time_model) {
+    double tc = F / P;
+    double tm = B / BW;
+    if (time_model == ORA_ADDITIVE) return tc + tm;
+    return tc > tm ? tc : tm;
+}
+
+/*
+ * One forward pass over T tokens with attention workload Q (query x context
+ * pairs), K (cached tokens read) and n_lm LM-head rows, on one GPU of a
+ * tensor-parallel group of p.  Fills per-operator FLOPs F[], bytes B[], times
+ * t[] for ONE layer (index 7 = LM head, once per pass), the all-reduce time
+ * t_ar of one collective, and returns the pass time
+ *     L * (sum of layer ops + 2 * t_ar) + t_lm.
+ */
+double ora_pass(const ora_model *m, const ora_hw *hw, double e_c, double e_b,
+                uint64_t p_, uint64_t wbits, int time_model,
+                double T, double Q, double K, double n_lm,
+                double *F, double *B, double *t, double *t_ar_out) {
+    double Fl[ORA_N_OPS], Bl[ORA_N_OPS], tl[ORA_N_OPS];
+    double p = (double)p_, w = (double)wbits / 8.0, a = ACT_BYTES, kap = KV_BYTES;
+    double d = m->d, dh = (double)(m->d / m->n_h);
+    double dq = m->n_h * dh, dkv = m->n_kv * dh;
+    double dff = m->d_ff, V = m->V, E = m->E, k = m->k;
+    double gkv = (double)((m->n_kv + p_ - 1) / p_) * dh;      /* KV heads replicate when n_kv < p */
+    double Pf1 = p_f1(m), Pf2 = p_f2(m), Prt = p_rt(m);
+    double Eld = (k * T < E) ? k * T : E;                     /* experts whose weights are read */
+    double P = hw->peak * e_c, BW = hw->bw * e_b;
+    int i;
+
+    Fl[0] = 2.0 * T * d * (dq + 2.0 * dkv) / p;
+    Bl[0] = w * d * (dq + 2.0 * dkv) / p + a * T * d + a * T * (dq + 2.0 * dkv) / p;
+    Fl[1] = 4.0 * dh * (double)m->n_h * Q / p;
+    Bl[1] = 2.0 * a * T * dq / p + 2.0 * kap * gkv * K;
+    Fl[2] = 2.0 * T * dq * d / p;
+    Bl[2] = w * dq * d / p + a * T * dq / p + a * T * d;
+    Fl[3] = 2.0 * T * k * Pf1 / p;
+    Bl[3] = w * Eld * Pf1 / p + a * T * d + 2.0 * a * T * k * dff / p;
+    Fl[4] = 2.0 * T * k * Pf2 / p;
+    Bl[4] = w * Eld * Pf2 / p + a * T * k * dff / p + a * T * d;
+    if (m->E > 1) {
+        Fl[5] = 2.0 * T * Prt;
+        Bl[5] = w * Prt + a * T * d + a * T * E;
+    } else {
+        Fl[5] = 0.0; Bl[5] = 0.0;
+    }
+    Fl[6] = 0.0;
+    Bl[6] = 4.0 * a * T * d;
+    if (n_lm > 0.0) {
+        Fl[7] = 2.0 * n_lm * d * V / p;
+        Bl[7] = w * d * V / p + a * n_lm * d + a * n_lm * V / p;
+    } else {
+        Fl[7] = 0.0; Bl[7] = 0.0;
+    }
+
+    double t_layer = 0.0;
+    for (i = 0; i < 7; ++i) {
+        tl[i] = op_time(Fl[i], Bl[i], P, BW, time_model);
+        t_layer += tl[i];
+    }
+    tl[7] = (n_lm > 0.0) ? op_time(Fl[7], Bl[7], P, BW, time_model) : 0.0;
+
+    /* ring all-reduce of the T x d activation: 2(p-1)/p of the message over the
+     * link plus 2(p-1) latency hops; two per layer, not overlapped. */
+    double t_ar = 0.0;
+    if (p_ > 1) t_ar = 2.0 * (p - 1.0) / p * (a * T * d) / hw->link_bw + 2.0 * (p - 1.0) * hw->link_lat;
+
+    if (F) memcpy(F, Fl, sizeof Fl);
+    if (B) memcpy(B, Bl, sizeof Bl);
+    if (t) memcpy(t, tl, sizeof tl);
+    if (t_ar_out) *t_ar_out = t_ar;
+    return (double)m->L * (t_layer + 2.0 * t_ar) + tl[7];
+}
+
+/* --------------------------------------------------------------------- memory */
+
+/* weight bytes held by one GPU: bits/8 * parameters / p  (model slice memory). */
+double ora_weight_bytes_gpu(const ora_model *m, uint64_t p, uint64_t wbits) {
+    return ((double)wbits / 8.0) * ora_params_total(m) / (double)p;
+}
+/* KV bytes per cached token per GPU: K and V, L layers, g_kv elements each. */
+double ora_kv_bytes_token(const ora_model *m, uint64_t p) {
+    double dh = (double)(m->d / m->n_h);
+    double gkv = (double)((m->n_kv + p - 1) / p) * dh;
+    return 2.0 * (double)m->L * gkv * KV_BYTES;
+}
+
+/* Available memory, block-rounded KV per request, feasibility (inclusive
+ * boundary) and B_max = floor(available / kv per request). */
+void ora_memory(const ora_model *m, const ora_hw *hw, const ora_knobs *kn,
+                double *kv_req_out, double *c_avail_out, uint32_t *feasible, uint32_t *b_max) {
+    double c_avail = hw->cap - ora_weight_bytes_gpu(m, kn->p, kn->wbits);
+    uint64_t tok = kn->s_in + kn->s_out;
+    uint64_t tok_req = (tok + kn->blk - 1) / kn->blk * kn->blk;
+    double kv_req = (double)tok_req * ora_kv_bytes_token(m, kn->p);
+    if (kv_req_out) *kv_req_out = kv_req;
+    if (c_avail_out) *c_avail_out = c_avail;
+    if (c_avail > 0.0) {
+        *feasible = ((double)kn->b * kv_req <= c_avail) ? 1u : 0u;
+        double q = floor(c_avail / kv_req);
+        *b_max = (q >= 4294967295.0) ? 4294967295u : (uint32_t)q;
+    } else {
+        *feasible = 0u;
+        *b_max = 0u;
+    }
+}
+
+/* -------------------------------------------------------------------- prefill */
+
+/* Static batch of b equal prompts under a token budget mbt per pass.
+ * s_in <= mbt: sub-batches of floor(mbt/s_in) requests, the remainder forms one
+ * more.  s_in > mbt: every request is cut into ceil(s_in/mbt) segments that run
+ * one after another. */
+double ora_prefill(const ora_model *m, const ora_hw *hw, const ora_knobs *kn,
+                   double e_c, double e_b, int time_model) {
+    double total = 0.0;
+    uint64_t b = kn->b, s = kn->s_in, mbt = kn->mbt;
+    if (s <= mbt) {
+        uint64_t r = mbt / s;
+        if (r > b) r = b;
+        uint64_t n_full = b / r, rem = b - n_full * r, i;
+        for (i = 0; i < n_full; ++i) {
+            double R = (double)r, S = (double)s;
+            total += ora_pass(m, hw, e_c, e_b, kn->p, kn->wbits, time_model,
+                              R * S, R * S * S, R * S, R, 0, 0, 0, 0);
+        }
+        if (rem > 0) {
+            double R = (double)rem, S = (double)s;
+            total += ora_pass(m, hw, e_c, e_b, kn->p, kn->wbits, time_model,
+                              R * S, R * S * S, R * S, R, 0, 0, 0, 0);
+        }
+    } else {
+        uint64_t n_seg = (s + mbt - 1) / mbt, req, j;
+        for (req = 0; req < b; ++req) {
+            for (j = 0; j < n_seg; ++j) {
+                uint64_t c = s - j * mbt;
+                if (c > mbt) c = mbt;
+                uint64_t ctx = j * mbt + c;
+                double n_lm = (j == n_seg - 1) ? 1.0 : 0.0;
+                total += ora_pass(m, hw, e_c, e_b, kn->p, kn->wbits, time_model,
+                                  (double)c, (double)c * (double)ctx, (double)ctx, n_lm, 0, 0, 0, 0);
+            }
+        }
+    }
+    return total;
+}
+
+/* --------------------------------------------------------------- one candidate */
+
+/* Prefill emits output token 1; decode steps j = 1..s_out-1 each run one pass
+ * with b tokens at context s_in + j.  Metrics are computed at the nominal batch
+ * even when it does not fit (flagged by feasible = 0). */
+void ora_eval(const ora_model *m, const ora_hw *hw, const ora_knobs *kn,
+              double e_c, double e_b, int time_model, ora_metrics *out) {
+    double b = (double)kn->b;
+    out->t_prefill = ora_prefill(m, hw, kn, e_c, e_b, time_model);
+    double td = 0.0;
+    uint64_t j;
+    for (j = 1; j + 1 <= kn->s_out; ++j) {
+        double ctx = (double)(kn->s_in + j);
+        td += ora_pass(m, hw, e_c, e_b, kn->p, kn->wbits, time_model, b, b * ctx, b * ctx, b, 0, 0, 0, 0);
+    }
+    out->t_decode = td;
+    out->t_batch = out->t_prefill + td;
+    if (kn->s_out > 1) {
+        double steps = (double)(kn->s_out - 1);
+        out->tpot = td / steps;
+        out->decode_tok_s = b * steps / td;
+    } else {
+        out->tpot = 0.0;
+        out->decode_tok_s = 0.0;
+    }
+    /* GPU-hours per million generated tokens */
+    out->cost = (double)kn->p * out->t_batch / 3600.0 * 1.0e6 / (b * (double)kn->s_out);
+    ora_memory(m, hw, kn, 0, 0, &out->feasible, &out->b_max);
+}
+
+/* ----------------------------------------------------------------------- grid */
+
+typedef struct {
+    const ora_model *models; uint32_t n_models;
+    const ora_hw *hws; uint32_t n_hws;
+    const uint64_t *axis[9];    /* model, hw, batch, s_in, s_out, tp, wbits, kv_block, mbt (slow -> fast) */
+    uint32_t count[9];
+} ora_grid;
+
+uint64_t ora_grid_size(const ora_grid *g) {
+    uint64_t n = 1; int a;
+    for (a = 0; a < 9; ++a) n *= g->count[a];
+    return n;
+}
+
+/* Flat index -> digits (fastest axis last) -> model, hardware and knobs. */
+int ora_grid_decode(const ora_grid *g, uint64_t idx, const ora_model **m, const ora_hw **hw, ora_knobs *kn) {
+    uint64_t v[9]; int a;
+    for (a = 8; a >= 0; --a) {
+        uint64_t dgt = idx % g->count[a];
+        idx /= g->count[a];
+        v[a] = g->axis[a][dgt];
+    }
+    if (idx != 0 || v[0] >= g->n_models || v[1] >= g->n_hws) return -1;
+    *m = &g->models[v[0]]; *hw = &g->hws[v[1]];
+    kn->b = v[2]; kn->s_in = v[3]; kn->s_out = v[4]; kn->p = v[5];
+    kn->wbits = v[6]; kn->blk = v[7]; kn->mbt = v[8];
+    return 0;
+}
+
+int ora_eval_grid(const ora_grid *g, uint64_t first, uint64_t count, double e_c, double e_b, int time_model,
+                  double *t_prefill, double *t_decode, double *t_batch, double *decode_tok_s, double *cost,
+                  uint32_t *b_max, uint8_t *feasible) {
+    uint64_t i;
+    for (i = 0; i < count; ++i) {
+        const ora_model *m; const ora_hw *hw; ora_knobs kn; ora_metrics r;
+        if (ora_grid_decode(g, first + i, &m, &hw, &kn)) return -1;
+        ora_eval(m, hw, &kn, e_c, e_b, time_model, &r);
+        if (t_prefill) t_prefill[i] = r.t_prefill;
+        if (t_decode) t_decode[i] = r.t_decode;
+        if (t_batch) t_batch[i] = r.t_batch;
+        if (decode_tok_s) decode_tok_s[i] = r.decode_tok_s;
+        if (cost) cost[i] = r.cost;
+        if (b_max) b_max[i] = r.b_max;
+        if (feasible) feasible[i] = (uint8_t)r.feasible;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------ uncertainty sweep */
+
+static int cmp_double(const void *a, const void *b) {
+    double x = *(const double *)a, y = *(const double *)b;
+    return (x > y) - (x < y);
+}
+
+/* n efficiency samples -> mean (summed in index order) and nearest-rank p10 /
+ * p90 (sorted[ceil(q n) - 1]) of TTFT and batch latency; cost from the mean
+ * batch latency.  stats[6] = ttft mean,p10,p90, t_batch mean,p10,p90. */
+void ora_eval_sweep(const ora_model *m, const ora_hw *hw, const ora_knobs *kn, uint32_t n,
+                    const double *e_c, const double *e_b, int time_model,
+                    double *stats, double *cost, uint32_t *b_max, uint32_t *feasible) {
+    double *x = (double *)malloc(sizeof(double) * 2 * n), *y = x + n;
+    double sx = 0.0, sy = 0.0;
+    uint32_t i, lo = (n + 9) / 10 - 1, hi = (9 * n + 9) / 10 - 1;
+    ora_metrics r;
+    for (i = 0; i < n; ++i) {
+        ora_eval(m, hw, kn, e_c[i], e_b[i], time_model, &r);
+        x[i] = r.t_prefill; y[i] = r.t_batch;
+        sx += x[i]; sy += y[i];
+    }
+    qsort(x, n, sizeof(double), cmp_double);
+    qsort(y, n, sizeof(double), cmp_double);
+    stats[0] = sx / (double)n; stats[1] = x[lo]; stats[2] = x[hi];
+    stats[3] = sy / (double)n; stats[4] = y[lo]; stats[5] = y[hi];
+    *cost = (double)kn->p * stats[3] / 3600.0 * 1.0e6 / ((double)kn->b * (double)kn->s_out);
+    *b_max = r.b_max; *feasible = r.feasible;
+    free(x);
+}
+
+int ora_eval_sweep_grid(const ora_grid *g, uint64_t first, uint64_t count, uint32_t n,
+                        const double *e_c, const double *e_b, int time_model,
+                        double *stats6 /* [6][count] column-major: stats6[c*count+i] */,
+                        double *cost, uint32_t *b_max, uint8_t *feasible) {
+    uint64_t i; int c;
+    for (i = 0; i < count; ++i) {
+        const ora_model *m; const ora_hw *hw; ora_knobs kn; double s[6], co; uint32_t bm, fe;
+        if (ora_grid_decode(g, first + i, &m, &hw, &kn)) return -1;
+        ora_eval_sweep(m, hw, &kn, n, e_c, e_b, time_model, s, &co, &bm, &fe);
+        for (c = 0; c < 6; ++c) stats6[(uint64_t)c * count + i] = s[c];
+        if (cost) cost[i] = co;
+        if (b_max) b_max[i] = bm;
+        if (feasible) feasible[i] = (uint8_t)fe;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------- continuous-batching simulation */
+
+enum { ORA_SIM_OK = 0, ORA_SIM_INFEASIBLE = 1 };
+
+typedef struct {
+    double ttft_p50, ttft_p99, mean_tpot, tokens_s;
+    uint32_t status;
+    uint64_t n_steps, n_request_steps;
+} ora_sim_out;
+
+/*
+ * Step-level simulation of one serving configuration: FCFS admission under a
+ * KV-block budget and a concurrent-sequence cap (lifetime block reservation,
+ * head-of-line blocking), then one engine step = decode token for every
+ * prefilled request + prompt chunks in admission order under the remaining
+ * token budget, advanced by the modelled pass time.
+ * Optional per-request outputs ttft[], first[], fin[] (n each) for invariants;
+ * min_free receives the smallest free-block count seen (as int64).
+ */
+void ora_simulate(const ora_model *m, const ora_hw *hw, uint64_t p, uint64_t wbits, uint64_t blk,
+                  uint64_t mbt, uint64_t max_seqs, double rate, int time_model,
+                  uint32_t n, const double *arr_unit, const uint32_t *n_in, const uint32_t *n_out,
+                  ora_sim_out *out, double *ttft, double *first, double *fin, int64_t *min_free_out) {
+    double c_avail = hw->cap - ora_weight_bytes_gpu(m, p, wbits);
+    double kv_tok = ora_kv_bytes_token(m, p);
+    double inf = INFINITY;
+    uint32_t i;
+    out->ttft_p50 = out->ttft_p99 = out->mean_tpot = inf; out->tokens_s = 0.0;
+    out->n_steps = out->n_request_steps = 0; out->status = ORA_SIM_INFEASIBLE;
+    if (ttft) for (i = 0; i < n; ++i) ttft[i] = first[i] = fin[i] = inf;
+    if (min_free_out) *min_free_out = 0;
+    if (n == 0 || max_seqs == 0) return;
+    if (!(c_avail > 0.0)) return;
+    double nb = floor(c_avail / ((double)blk * kv_tok));
+    int64_t n_blk = nb >= 9.0e18 ? INT64_MAX : (int64_t)nb;
+    int64_t *need = (int64_t *)malloc(sizeof(int64_t) * n);
+    for (i = 0; i < n; ++i) {
+        need[i] = (int64_t)(((uint64_t)n_in[i] + n_out[i] + blk - 1) / blk);
+        if (need[i] > n_blk) { free(need); return; }
+    }
+    double *arr = (double *)malloc(sizeof(double) * 4 * n);
+    double *t_first = arr + n, *t_fin = arr + 2 * n, *t_ttft = arr + 3 * n;
+    uint32_t *prefilled = (uint32_t *)calloc(4 * (size_t)n, sizeof(uint32_t));
+    uint32_t *gen = prefilled + n, *active = prefilled + 2 * n;   /* active[]: request ids in admission order */
+    uint32_t *chunk = prefilled + 3 * n;
+    for (i = 0; i < n; ++i) arr[i] = arr_unit[i] / rate;
+
+    double now = 0.0;
+    uint32_t next = 0, n_active = 0, n_done = 0;
+    int64_t free_blk = n_blk, min_free = n_blk;
+    uint64_t n_steps = 0, n_rs = 0;
+
+    while (n_done < n) {
+        uint32_t a;
+        /* 1. idle jump */
+        if (n_active == 0 && next < n && arr[next] > now) now = arr[next];
+        /* 2. FCFS admission, stop at the first request that cannot enter */
+        while (next < n && arr[next] <= now && n_active < max_seqs && need[next] <= free_blk) {
+            free_blk -= need[next];
+            if (free_blk < min_free) min_free = free_blk;
+            active[n_active++] = next;
+            prefilled[next] = 0; gen[next] = 0;
+            ++next;
+        }
+        /* 3. schedule: decoders first, then prompt chunks in admission order */
+        double T = 0.0, Q = 0.0, K = 0.0, n_lm = 0.0;
+        uint64_t n_dec = 0, n_chunks = 0;
+        for (a = 0; a < n_active; ++a) {
+            uint32_t r = active[a];
+            if (prefilled[r] == n_in[r]) {
+                double ctx = (double)n_in[r] + (double)gen[r];
+                ++n_dec; Q += ctx; K += ctx;
+            }
+        }
+        int64_t budget = (int64_t)mbt - (int64_t)n_dec;
+        T = (double)n_dec; n_lm = (double)n_dec;
+        memset(chunk, 0, sizeof(uint32_t) * n_active);   /* chunk[a]: prompt tokens given to active[a] this step */
+        for (a = 0; a < n_active; ++a) {
+            uint32_t r = active[a];
+            if (prefilled[r] < n_in[r] && budget > 0) {
+                int64_t c = (int64_t)(n_in[r] - prefilled[r]);
+                if (c > budget) c = budget;
+                budget -= c;
+                chunk[a] = (uint32_t)c;
+                double ctx = (double)prefilled[r] + (double)c;
+                T += (double)c; Q += (double)c * ctx; K += ctx;
+                if (prefilled[r] + c == n_in[r]) n_lm += 1.0;
+                ++n_chunks;
+            }
+        }
+        /* 4. one engine step */
+        now += ora_pass(m, hw, 1.0, 1.0, p, wbits, time_model, T, Q, K, n_lm, 0, 0, 0, 0);
+        /* 5. book-keeping at the new time */
+        uint32_t w = 0;
+        for (a = 0; a < n_active; ++a) {
+            uint32_t r = active[a];
+            int was_decoding = (prefilled[r] == n_in[r]);
+            if (was_decoding) {
+                gen[r] += 1;
+            } else if (chunk[a] > 0) {
+                prefilled[r] += chunk[a];
+                if (prefilled[r] == n_in[r]) {
+                    t_first[r] = now; gen[r] = 1; t_ttft[r] = now - arr[r];
+                }
+            }
+            if (prefilled[r] == n_in[r] && gen[r] == n_out[r]) {
+                t_fin[r] = now; free_blk += need[r]; ++n_done;
+            } else {
+                active[w++] = r;
+            }
+        }
+        n_active = w;
+        ++n_steps; n_rs += n_dec + n_chunks;
+    }
+
+    /* outputs: nearest-rank percentiles of TTFT, mean TPOT over requests that decode, tokens/s */
+    {
+        double *s = (double *)malloc(sizeof(double) * n);
+        double sum_tpot = 0.0, tokens = 0.0, max_fin = -inf, min_arr = inf;
+        uint32_t n_tpot = 0;
+        memcpy(s, t_ttft, sizeof(double) * n);
+        qsort(s, n, sizeof(double), cmp_double);
+        out->ttft_p50 = s[(n + 1) / 2 - 1];                 /* ceil(0.50 n) - 1 */
+        out->ttft_p99 = s[(99 * (uint64_t)n + 99) / 100 - 1]; /* ceil(0.99 n) - 1 */
+        for (i = 0; i < n; ++i) {
+            if (n_out[i] > 1) { sum_tpot += (t_fin[i] - t_first[i]) / (double)(n_out[i] - 1); ++n_tpot; }
+            tokens += (double)n_out[i];
+            if (t_fin[i] > max_fin) max_fin = t_fin[i];
+            if (arr[i] < min_arr) min_arr = arr[i];
+        }
+        out->mean_tpot = n_tpot ? sum_tpot / (double)n_tpot : 0.0;
+        out->tokens_s = tokens / (max_fin - min_arr);
+        free(s);
+    }
+    out->status = ORA_SIM_OK; out->n_steps = n_steps; out->n_request_steps = n_rs;
+    if (ttft) { memcpy(ttft, t_ttft, sizeof(double) * n); memcpy(first, t_first, sizeof(double) * n); memcpy(fin, t_fin, sizeof(double) * n); }
+    if (min_free_out) *min_free_out = min_free;
+    free(need); free(arr); free(prefilled);
+}
+
+int ora_simulate_grid(const ora_grid *g, const uint32_t *cfg_idx, const double *rate, uint32_t n_cfg, int time_model,
+                      uint32_t n, const double *arr_unit, const uint32_t *n_in, const uint32_t *n_out,
+                      ora_sim_out *out) {
+    uint32_t c;
+    for (c = 0; c < n_cfg; ++c) {
+        const ora_model *m; const ora_hw *hw; ora_knobs kn;
+        if (ora_grid_decode(g, cfg_idx[c], &m, &hw, &kn)) return -1;
+        ora_simulate(m, hw, kn.p, kn.wbits, kn.blk, kn.mbt, kn.b, rate[c], time_model, n, arr_unit, n_in, n_out,
+                     &out[c], 0, 0, 0, 0);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ selection */
+
+/* Row passes when feasible (mask may be NULL), every constraint column <= its
+ * cap, and the objective is not NaN. */
+static int row_passes(uint64_t i, const double *obj, const uint8_t *feasible,
+                      uint32_t n_con, const double *const *con, const double *cap) {
+    uint32_t c;
+    if (feasible && !feasible[i]) return 0;
+    if (obj[i] != obj[i]) return 0;
+    for (c = 0; c < n_con; ++c) if (!(con[c][i] <= cap[c])) return 0;
+    return 1;
+}
+
+/* Constrained top-k per group by linear scans in (objective asc, index asc)
+ * order.  idx_out/val_out are [n_groups][k]; empty slots hold UINT64_MAX / +inf;
+ * count_out[g] = passing rows of group g. */
+void ora_select_topk(uint64_t n, const double *obj, const uint8_t *feasible,
+                     uint32_t n_con, const double *const *con, const double *cap,
+                     const uint32_t *group, uint32_t n_groups, uint32_t k,
+                     uint64_t *idx_out, double *val_out, uint64_t *count_out) {
+    uint32_t g, j;
+    uint64_t i;
+    for (g = 0; g < n_groups; ++g) {
+        uint64_t cnt = 0;
+        for (i = 0; i < n; ++i)
+            if ((!group || group[i] == g) && row_passes(i, obj, feasible, n_con, con, cap)) ++cnt;
+        count_out[g] = cnt;
+        double last_v = -INFINITY; uint64_t last_i = 0; int have_last = 0;
+        for (j = 0; j < k; ++j) {
+            double best_v = INFINITY; uint64_t best_i = UINT64_MAX;
+            for (i = 0; i < n; ++i) {
+                if (group && group[i] != g) continue;
+                if (!row_passes(i, obj, feasible, n_con, con, cap)) continue;
+                /* strictly after the previous pick in (value, index) order */
+                if (have_last && !(obj[i] > last_v || (obj[i] == last_v && i > last_i))) continue;
+                if (best_i == UINT64_MAX || obj[i] < best_v) { best_v = obj[i]; best_i = i; }
+            }
+            idx_out[(uint64_t)g * k + j] = best_i;
+            val_out[(uint64_t)g * k + j] = best_v;
+            if (best_i == UINT64_MAX) { have_last = 1; last_v = INFINITY; last_i = UINT64_MAX; }
+            else { have_last = 1; last_v = best_v; last_i = best_i; }
+        }
+    }
+}
+
+/* Pareto front (minimise x and y) by the definition: row i is kept iff it passes
+ * and no passing row j has x_j <= x_i, y_j <= y_i with one strict.  O(n^2).
+ * Output indices sorted by (x, y, index).  Returns the front size (may exceed
+ * cap; only cap entries are stored). */
+typedef struct { double x, y; uint64_t i; } front_pt;
+static int cmp_front(const void *a, const void *b) {
+    const front_pt *p = (const front_pt *)a, *q = (const front_pt *)b;
+    if (p->x != q->x) return p->x < q->x ? -1 : 1;
+    if (p->y != q->y) return p->y < q->y ? -1 : 1;
+    return (p->i > q->i) - (p->i < q->i);
+}
+static int pareto_pass(uint64_t i, const double *x, const double *y, const uint8_t *mask) {
+    return (!mask || mask[i]) && x[i] == x[i] && y[i] == y[i];
+}
+
+uint64_t ora_pareto_brute(uint64_t n, const double *x, const double *y, const uint8_t *mask,
+                          uint64_t *out_idx, uint64_t cap) {
+    front_pt *f = (front_pt *)malloc(sizeof(front_pt) * (n ? n : 1));
+    uint64_t i, j, nf = 0;
+    for (i = 0; i < n; ++i) {
+        if (!pareto_pass(i, x, y, mask)) continue;
+        int dominated = 0;
+        for (j = 0; j < n && !dominated; ++j) {
+            if (j == i || !pareto_pass(j, x, y, mask)) continue;
+            if (x[j] <= x[i] && y[j] <= y[i] && (x[j] < x[i] || y[j] < y[i])) dominated = 1;
+        }
+        if (!dominated) { f[nf].x = x[i]; f[nf].y = y[i]; f[nf].i = i; ++nf; }
+    }
+    qsort(f, nf, sizeof(front_pt), cmp_front);
+    for (i = 0; i < nf && i < cap; ++i) out_idx[i] = f[i].i;
+    free(f);
+    return nf;
+}
+
+/* Same front by sort + sweep (for inputs too large for O(n^2)); checked against
+ * ora_pareto_brute on small inputs with crafted ties and duplicates. */
+uint64_t ora_pareto_sweep(uint64_t n, const double *x, const double *y, const uint8_t *mask,
+                          uint64_t *out_idx, uint64_t cap) {
+    front_pt *f = (front_pt *)malloc(sizeof(front_pt) * (n ? n : 1));
+    uint64_t i, m = 0, nf = 0;
+    for (i = 0; i < n; ++i)
+        if (pareto_pass(i, x, y, mask)) { f[m].x = x[i]; f[m].y = y[i]; f[m].i = i; ++m; }
+    qsort(f, m, sizeof(front_pt), cmp_front);
+    double best_y = INFINITY;      /* min y over strictly smaller x */
+    i = 0;
+    while (i < m) {
+        uint64_t j = i;
+        double gx = f[i].x, gy = f[i].y;   /* first of an equal-x run has the run's min y */
+        if (gy < best_y) {
+            while (j < m && f[j].x == gx && f[j].y == gy) {
+                if (nf < cap) out_idx[nf] = f[j].i;
+                ++nf; ++j;
+            }
+        }
+        while (j < m && f[j].x == gx) ++j;
+        if (gy < best_y) best_y = gy;
+        i = j;
+    }
+    free(f);
+    return nf;
+}
+
+/* --------------------------------------------------- counter-based generator */
+
+/* Philox4x64-10 (Salmon, Moraes, Dror, Shaw, "Parallel random numbers: as easy
+ * as 1, 2, 3", SC'11): 10 rounds of two 64x64->128 multiplies with the
+ * published multipliers; the key is bumped by the Weyl constants between
+ * rounds. */
+static void mulhilo64(uint64_t a, uint64_t b, uint64_t *hi, uint64_t *lo) {
+    unsigned __int128 pr = (unsigned __int128)a * b;
+    *hi = (uint64_t)(pr >> 64); *lo = (uint64_t)pr;
+}
+void ora_philox4x64_10(const uint64_t ctr[4], const uint64_t key[2], uint64_t out[4]) {
+    uint64_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+    int r;
+    for (r = 0; r < 10; ++r) {
+        uint64_t hi0, lo0, hi1, lo1;
+        if (r > 0) { k0 += 0x9E3779B97F4A7C15ull; k1 += 0xBB67AE8584CAA73Bull; }
+        mulhilo64(0xD2E7470EE14C6C93ull, c0, &hi0, &lo0);
+        mulhilo64(0xCA5A826395121157ull, c2, &hi1, &lo1);
+        uint64_t n0 = hi1 ^ c1 ^ k0, n1 = lo1, n2 = hi0 ^ c3 ^ k1, n3 = lo0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* ------------------------------------------------------------- sampled space */
+
+typedef struct {
+    const uint32_t *heads;  /* [1024] */
+    const double *peak;     /* [1024] */
+    const double *bw;       /* [1024] */
+    const double *cap;      /* [6]    */
+    const uint32_t *batch, *s_in, *s_out;   /* [1024] each */
+    const uint32_t *tp;      /* [4] */
+    const uint32_t *wbits;   /* [3] */
+    const uint32_t *kv_block;/* [2] */
+    const uint32_t *mbt;     /* [3] */
+    const uint32_t *kv_choices; /* [4], 0 = all heads */
+    uint32_t layers_lo, layers_n, ffn_lo_x2, ffn_span_x2, vocab;
+    double link_div;
+} ora_space;
+
+/* Candidate idx of the sampled space: one Philox block with counter (idx,0,0,0)
+ * and key (seed,0); draw j is the j-th 16-bit field (lowest field of word 0
+ * first); a draw u selects entry (u*n)>>16 of an n-entry table. */
+void ora_sample_config(const ora_space *sp, uint64_t seed, uint64_t idx,
+                       ora_model *m, ora_hw *hw, ora_knobs *kn) {
+    uint64_t ctr[4] = { idx, 0, 0, 0 }, key[2] = { seed, 0 }, r[4];
+    uint32_t u[16]; int j;
+    ora_philox4x64_10(ctr, key, r);
+    for (j = 0; j < 16; ++j) u[j] = (uint32_t)((r[j >> 2] >> (16 * (j & 3))) & 0xFFFFu);
+    m->L = sp->layers_lo + ((u[0] * sp->layers_n) >> 16);
+    m->n_h = sp->heads[(u[1] * 1024u) >> 16];
+    m->d = 128u * m->n_h;
+    uint32_t kvc = sp->kv_choices[(u[2] * 4u) >> 16];
+    m->n_kv = kvc ? kvc : m->n_h;
+    /* d_ff = 128 * floor(ratio * n_h + 1/2), ratio = (lo_x2 + span_x2 * u / 65536) / 2 */
+    uint64_t num = ((uint64_t)sp->ffn_lo_x2 * 65536u + (uint64_t)sp->ffn_span_x2 * u[3]) * m->n_h + 65536u;
+    m->d_ff = 128u * (uint32_t)(num >> 17);
+    m->V = sp->vocab; m->E = 1; m->k = 1;
+    hw->peak = sp->peak[(u[4] * 1024u) >> 16];
+    hw->bw = sp->bw[(u[5] * 1024u) >> 16];
+    hw->cap = sp->cap[(u[6] * 6u) >> 16];
+    hw->link_bw = hw->bw / sp->link_div;
+    hw->link_lat = 0.0;
+    kn->b = sp->batch[(u[7] * 1024u) >> 16];
+    kn->s_in = sp->s_in[(u[8] * 1024u) >> 16];
+    kn->s_out = sp->s_out[(u[9] * 1024u) >> 16];
+    kn->p = sp->tp[(u[10] * 4u) >> 16];
+    kn->wbits = sp->wbits[(u[11] * 3u) >> 16];
+    kn->blk = sp->kv_block[(u[12] * 2u) >> 16];
+    kn->mbt = sp->mbt[(u[13] * 3u) >> 16];
+}
+
+/* Bucket of a model by stored parameters: edges[j] = 2^j * 1e9; bucket = number
+ * of edges <= P_total. */
+uint32_t ora_bucket(double p_total, const double *edges, uint32_t n_edges) {
+    uint32_t b = 0, j;
+    for (j = 0; j < n_edges; ++j) if (p_total >= edges[j]) ++b;
+    return b;
+}
+
+/* 256 bins of latency from the fp64 bit pattern: 8 per octave (exponent and top
+ * three mantissa bits) over [2^-12, 2^20) s, clamped at both ends. */
+uint32_t ora_hist_bin(double t) {
+    uint64_t bits; memcpy(&bits, &t, 8);
+    int64_t b = (int64_t)(bits >> 49) - (int64_t)((1023 - 12) << 3);
+    if (b < 0) b = 0;
+    if (b > 255) b = 255;
+    return (uint32_t)b;
+}
+
+/* Reduced outputs over candidates [first, first+count): feasible count, per
+ * bucket the lowest cost among feasible rows with TTFT <= ttft_cap (lowest
+ * index on ties), histogram of batch latency over feasible rows.  Optional
+ * per-candidate columns for spot checks. */
+void ora_eval_sampled(const ora_space *sp, uint64_t seed, uint64_t first, uint64_t count, int time_model,
+                      const double *edges, uint32_t n_edges, double ttft_cap,
+                      uint64_t *feasible_count, double *win_val, uint64_t *win_idx, uint64_t *hist,
+                      double *t_prefill, double *t_batch, double *cost, uint32_t *b_max, uint8_t *feasible,
+                      uint32_t *bucket) {
+    uint64_t i; uint32_t j;
+    *feasible_count = 0;
+    for (j = 0; j <= n_edges; ++j) { win_val[j] = INFINITY; win_idx[j] = UINT64_MAX; }
+    memset(hist, 0, sizeof(uint64_t) * 256);
+    for (i = 0; i < count; ++i) {
+        ora_model m; ora_hw hw; ora_knobs kn; ora_metrics r;
+        ora_sample_config(sp, seed, first + i, &m, &hw, &kn);
+        ora_eval(&m, &hw, &kn, 1.0, 1.0, time_model, &r);
+        uint32_t bk = ora_bucket(ora_params_total(&m), edges, n_edges);
+        if (r.feasible) {
+            *feasible_count += 1;
+            hist[ora_hist_bin(r.t_batch)] += 1;
+            if (r.t_prefill <= ttft_cap && r.cost < win_val[bk]) { win_val[bk] = r.cost; win_idx[bk] = first + i; }
+        }
+        if (t_prefill) t_prefill[i] = r.t_prefill;
+        if (t_batch) t_batch[i] = r.t_batch;
+        if (cost) cost[i] = r.cost;
+        if (b_max) b_max[i] = r.b_max;
+        if (feasible) feasible[i] = (uint8_t)r.feasible;
+        if (bucket) bucket[i] = bk;
+    }
+}

@@ -1,0 +1,583 @@
+"""Pins of the CPU oracle against things other than itself: public parameter
+counts, closed forms, the paper's printed memory formulas, invariants, brute
+force, and numpy's Philox.  CPU only."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from paper_2412_04788_amd import workloads as wl
+from tests import bridge
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _gold(name):
+    vals = {}
+    with open(os.path.join(GOLD, name)) as fh:
+        for line in fh:
+            line = line.split("#")[0].strip()
+            if line:
+                k, v = line.split()
+                vals[k] = int(v)
+    return vals
+
+
+# ------------------------------------------------------------------ parameters
+
+def test_param_counts_of_public_shapes(ora):
+    """Stored parameters of the 7B shape plus its (2L+1)*d norm weights equal the
+    publicly stated 6 738 415 616; the other shapes are fixed by hand arithmetic."""
+    gold = _gold("param_counts.txt")
+    for m in wl.MODELS_FULL:
+        assert ora.params_total(bridge.ora_model(m)) == gold[m.name]
+    m = wl.DENSE_7B
+    assert ora.params_total(bridge.ora_model(m)) + (2 * m.L + 1) * m.d == gold["dense-7b-with-norms"]
+
+
+def test_param_count_formula_by_hand(ora):
+    for m in wl.MODELS_FULL:
+        dh = m.d // m.n_h
+        attn = m.d * m.n_h * dh * 2 + 2 * m.d * m.n_kv * dh
+        ffn = 3 * m.d * m.d_ff * m.E
+        router = m.d * m.E if m.E > 1 else 0
+        assert ora.params_total(bridge.ora_model(m)) == m.L * (attn + ffn + router) + 2 * m.V * m.d
+        assert ora.params_layer_active(bridge.ora_model(m)) == attn + 3 * m.d * m.d_ff * m.k + router
+
+
+# ----------------------------------------------------------------------- FLOPs
+
+@pytest.mark.parametrize("m", wl.MODELS_FULL, ids=lambda m: m.name)
+@pytest.mark.parametrize("p", [1, 2, 8])
+def test_linear_flops_are_two_params_tokens(ora, m, p):
+    """Sum of the matmul FLOPs of a pass (all ops but attention), times p GPUs,
+    is 2 * active parameters * tokens + 2 * LM-head rows * V * d."""
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+    T, n_lm = 777.0, 5.0
+    r = ora.pass_detail(om, oh, p, 16, T, T * 100, T * 3, n_lm)
+    lin = r["F"][[0, 2, 3, 4, 5]].sum() * p
+    if m.E > 1:  # router is replicated, not split
+        lin -= r["F"][5] * (p - 1)
+    assert lin == 2.0 * ora.params_layer_active(om) * T
+    assert r["F"][7] * p == 2.0 * n_lm * m.V * m.d
+    assert r["F"][6] == 0.0
+
+
+def test_attention_flops_and_kv_bytes(ora):
+    """Attention: 4 * d_h * n_h FLOPs per (query, context) pair (QK^T and PV, 2
+    FLOPs per MAC); KV read: K and V, 2 bytes each, g_kv elements per token."""
+    m = wl.DENSE_34B
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+    r = ora.pass_detail(om, oh, 1, 16, 1.0, 1000.0, 1000.0, 1.0)
+    assert r["F"][1] == 4 * m.d * 1000
+    dh = m.d // m.n_h
+    assert r["B"][1] == 2 * 2 * 1 * m.d + 2 * 2 * m.n_kv * dh * 1000
+    # TP 16 > 8 KV heads: each GPU still holds one full KV head
+    r = ora.pass_detail(om, oh, 16, 16, 1.0, 1000.0, 1000.0, 1.0)
+    assert r["B"][1] == 2 * 2 * m.d / 16 + 2 * 2 * dh * 1000
+
+
+# ------------------------------------------------------------ batch-1 decode
+
+def test_batch1_decode_step_is_weight_bytes_over_bandwidth(ora):
+    """Tiny profile (ridge 200 FLOP/B): every op of a batch-1 decode step is
+    memory bound, so step time * BW = weight bytes read + KV bytes + activation
+    bytes exactly; weight bytes of the 7B shape in fp16 = 13 214 154 752 (all
+    layers + LM head, embedding table not read)."""
+    gold = _gold("decode_bytes.txt")
+    m = wl.DENSE_7B
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+    ctx = 128.0
+    r = ora.pass_detail(om, oh, 1, 16, 1.0, ctx, ctx, 1.0)
+    w_read = 2 * (ora.params_total(om) - m.V * m.d)
+    assert w_read == gold["w_read_7b_fp16"]
+    kv = 2 * 2 * m.n_kv * (m.d // m.n_h) * m.L * ctx
+    assert kv == gold["kv_bytes_ctx128"]
+    act_layer = (2 * m.d + 2 * 3 * m.d) + (2 * 2 * m.d) + (2 * m.d + 2 * m.d) + (2 * m.d + 2 * 2 * m.d_ff) \
+        + (2 * m.d_ff + 2 * m.d) + 4 * 2 * m.d
+    act = m.L * act_layer + 2 * m.d + 2 * m.V
+    assert r["t_pass"] * wl.HW_TINY.hbm_bw == pytest.approx(w_read + kv + act, rel=1e-14)
+    # all ops memory bound
+    assert np.all(r["F"] / wl.HW_TINY.peak_flops <= r["B"] / wl.HW_TINY.hbm_bw)
+    assert abs(r["t_pass"] - w_read / wl.HW_TINY.hbm_bw) / r["t_pass"] < 0.01
+    assert w_read / wl.HW_TINY.hbm_bw == pytest.approx(2.6428309504e-3, rel=1e-12)
+
+
+def test_decode_sum_closed_form_when_memory_bound(ora):
+    """All-memory-bound decode: t_decode * BW = (s_out-1) * C0 + 4 g_kv L b * sum_{j}(s_in + j)."""
+    m = wl.DENSE_7B
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+    b, s_in, s_out = 2, 256, 300
+    r = ora.evaluate(om, oh, ora.knobs(b, s_in, s_out))
+    c0 = ora.pass_detail(om, oh, 1, 16, float(b), 0.0, 0.0, float(b))["t_pass"] * wl.HW_TINY.hbm_bw
+    n = s_out - 1
+    series = n * s_in + n * (n + 1) // 2
+    expect = n * c0 + 4 * m.d * m.L * b * series
+    assert r.t_decode * wl.HW_TINY.hbm_bw == pytest.approx(expect, rel=1e-12)
+    assert r.tpot == pytest.approx(r.t_decode / n, rel=1e-15)
+    assert r.decode_tok_s == pytest.approx(b * n / r.t_decode, rel=1e-15)
+    assert r.t_batch == r.t_prefill + r.t_decode
+    assert r.cost == pytest.approx(1 * r.t_batch / 3600 * 1e6 / (b * s_out), rel=1e-15)
+
+
+def test_compute_bound_prefill(ora):
+    """Large prefill on the tiny profile: matmul ops take F / P."""
+    m = wl.DENSE_7B
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+    T = 4096.0
+    r = ora.pass_detail(om, oh, 1, 16, T, T * T, T, 1.0)
+    for i in (0, 2, 3, 4):
+        assert r["t"][i] == r["F"][i] / wl.HW_TINY.peak_flops
+    assert r["t"][6] == r["B"][6] / wl.HW_TINY.hbm_bw     # norms are always bandwidth bound
+    # additive variant is the sum of both terms
+    ra = ora.pass_detail(om, oh, 1, 16, T, T * T, T, 1.0, time_model=ora.ADDITIVE)
+    np.testing.assert_allclose(ra["t"], r["F"] / wl.HW_TINY.peak_flops + r["B"] / wl.HW_TINY.hbm_bw, rtol=1e-15)
+
+
+def test_s_out_one_has_no_decode(ora):
+    om, oh = bridge.ora_model(wl.DENSE_7B), bridge.ora_hw(wl.HW_TINY)
+    r = ora.evaluate(om, oh, ora.knobs(4, 128, 1))
+    assert r.t_decode == 0.0 and r.tpot == 0.0 and r.decode_tok_s == 0.0 and r.t_batch == r.t_prefill
+
+
+# ---------------------------------------------------------------------- memory
+
+def test_kv_formula_reduces_to_the_papers(ora):
+    """MHA, p = 1, block 1: kv per request = 2 * N * H * S * kv (Dynamic Batch Size
+    Adjustment) and B_max = floor(C_available / that)."""
+    m = wl.DENSE_13B
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+    kn = ora.knobs(3, 700, 55, blk=1)
+    r = ora.memory(om, oh, kn)
+    assert r["kv_req"] == 2 * m.L * m.d * (700 + 55) * 2
+    c_avail = wl.HW_TINY.cap_bytes - 2 * ora.params_total(om)
+    assert r["c_avail"] == c_avail
+    assert r["b_max"] == int(c_avail // r["kv_req"])
+
+
+def test_kv_block_rounding_and_gqa_tp(ora):
+    m = wl.DENSE_70B
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+    r = ora.memory(om, oh, ora.knobs(1, 100, 29, p=4, blk=32))
+    dh = m.d // m.n_h
+    assert r["kv_req"] == 160 * 2 * m.L * (m.n_kv // 4) * dh * 2
+    assert ora.kv_bytes_token(om, 16) == 2 * m.L * dh * 2   # replicated head
+
+
+@pytest.mark.parametrize("p,wbits", [(1, 16), (2, 8), (8, 4)])
+def test_feasibility_boundary(ora, p, wbits):
+    m = wl.DENSE_34B
+    om = bridge.ora_model(m)
+    b, kn = 37, ora.knobs(37, 1000, 200, p=p, wbits=wbits, blk=16)
+    kv_req = ora.memory(om, bridge.ora_hw(wl.HW_TINY), kn)["kv_req"]
+    w_gpu = ora.weight_bytes_gpu(om, p, wbits)
+    assert w_gpu == wbits / 8 * ora.params_total(om) / p
+    cap = w_gpu + b * kv_req
+    h = wl.Hardware(1e15, 5e12, cap, 4e11)
+    r = ora.memory(om, bridge.ora_hw(h), kn)
+    assert r["feasible"] == 1 and r["b_max"] == b
+    h = wl.Hardware(1e15, 5e12, cap - 1.0, 4e11)
+    r = ora.memory(om, bridge.ora_hw(h), kn)
+    assert r["feasible"] == 0 and r["b_max"] == b - 1
+    h = wl.Hardware(1e15, 5e12, w_gpu, 4e11)           # nothing left for KV
+    r = ora.memory(om, bridge.ora_hw(h), kn)
+    assert r["feasible"] == 0 and r["b_max"] == 0
+
+
+# ---------------------------------------------------------- prefill structure
+
+def test_prefill_sub_batches_and_segments(ora):
+    m = wl.DENSE_7B
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+
+    def one(R, s):
+        return ora.pass_detail(om, oh, 1, 16, R * s, R * s * s, R * s, R)["t_pass"]
+
+    # 10 prompts of 1000 tokens under 4096 tokens per pass: 4 + 4 + 2
+    t = ora.prefill(om, oh, ora.knobs(10, 1000, 8, mbt=4096))
+    assert t == (one(4, 1000) + one(4, 1000)) + one(2, 1000)
+    # prompt longer than the budget: 3 segments of 2048, 2048, 904, per request
+    t = ora.prefill(om, oh, ora.knobs(2, 5000, 8, mbt=2048))
+    segs = [(2048, 2048, 0), (2048, 4096, 0), (904, 5000, 1)]
+    tot = 0.0
+    for _ in range(2):
+        for c, ctx, lm in segs:
+            tot += ora.pass_detail(om, oh, 1, 16, c, c * ctx, ctx, lm)["t_pass"]
+    assert t == tot
+    # everything fits one pass
+    assert ora.prefill(om, oh, ora.knobs(4, 512, 8, mbt=8192)) == one(4, 512)
+
+
+def test_monotone_in_lengths_and_batch(ora):
+    g = wl.grid_tiny()
+    r = ora.eval_grid(bridge.ora_grid(g))
+    shape = g.radices
+    for col in ("t_prefill", "t_batch"):
+        a = r[col].reshape(shape)
+        for ax in (2, 3, 4):          # batch, s_in, s_out
+            assert np.all(np.diff(a, axis=ax) >= 0), (col, ax)
+    assert np.all(np.diff(r["t_decode"].reshape(shape), axis=4) > 0)
+
+
+# ---------------------------------------------------------------- TP and comm
+
+def test_tp_scaling_and_comm_term(ora):
+    m = wl.DENSE_7B
+    om = bridge.ora_model(m)
+    h_inf = bridge.ora_hw(wl.Hardware(1e15, 5e12, 192 * wl.GIB, float("inf"), 0.0))
+    T, Q, K = 512.0, 512.0 * 512, 512.0
+    r1 = ora.pass_detail(om, h_inf, 1, 16, T, Q, K, 1.0)
+    assert r1["t_ar"] == 0.0
+    for p in (2, 4, 8):
+        rp = ora.pass_detail(om, h_inf, p, 16, T, Q, K, 1.0)
+        np.testing.assert_array_equal(rp["F"] * p, r1["F"])
+        assert rp["t_ar"] == 0.0
+        # weight and KV bytes scale 1/p: compare at zero tokens / pure KV
+        w1 = ora.pass_detail(om, h_inf, 1, 16, 0.0, 0.0, 0.0, 0.0)["B"]
+        wp = ora.pass_detail(om, h_inf, p, 16, 0.0, 0.0, 0.0, 0.0)["B"]
+        np.testing.assert_array_equal(wp * p, w1)
+    # ring all-reduce: 2(p-1)/p * bytes / link + 2(p-1) * latency
+    h = wl.Hardware(1e15, 5e12, 192 * wl.GIB, 4e11, 3e-6)
+    r = ora.pass_detail(om, bridge.ora_hw(h), 4, 16, T, Q, K, 1.0)
+    assert r["t_ar"] == pytest.approx(2 * 3 / 4 * (2 * T * m.d) / 4e11 + 2 * 3 * 3e-6, rel=1e-15)
+    assert r["t_pass"] == pytest.approx(m.L * (r["t"][:7].sum() + 2 * r["t_ar"]) + r["t"][7], rel=1e-15)
+
+
+# --------------------------------------------------------- uncertainty sweep
+
+def test_efficiency_scaling_and_percentiles(ora):
+    m = wl.DENSE_13B
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+    kn = ora.knobs(8, 512, 64)
+    base = ora.evaluate(om, oh, kn)
+    half = ora.evaluate(om, oh, kn, 0.5, 0.5)
+    assert half.t_prefill == pytest.approx(2 * base.t_prefill, rel=1e-14)
+    assert half.t_decode == pytest.approx(2 * base.t_decode, rel=1e-14)
+    g = bridge.ora_grid(wl.make_grid([m], [wl.HW_TINY], wl.Axis.table([8]), wl.Axis.table([512]), wl.Axis.table([64]),
+                                     wl.Axis.table([1]), wl.Axis.table([16]), wl.Axis.table([16]),
+                                     wl.Axis.table([8192])))
+    ones = np.ones(64)
+    s = ora.eval_sweep_grid(g, ones, ones)
+    assert s["ttft_p10"][0] == s["ttft_p90"][0] == base.t_prefill
+    assert s["ttft_mean"][0] == pytest.approx(base.t_prefill, rel=1e-15)
+    # distinct samples: e = 1/(i+1) scales every time by (i+1) -> sorted order known
+    e = 1.0 / np.arange(1, 65)
+    s = ora.eval_sweep_grid(g, e, e)
+    xs = np.array([ora.evaluate(om, oh, kn, ei, ei).t_batch for ei in e])
+    assert s["t_batch_p10"][0] == np.sort(xs)[6] and s["t_batch_p90"][0] == np.sort(xs)[57]
+    assert s["t_batch_mean"][0] == pytest.approx(xs.mean(), rel=1e-14)
+    assert s["t_batch_p10"][0] <= s["t_batch_mean"][0] <= s["t_batch_p90"][0]
+    assert s["cost"][0] == pytest.approx(s["t_batch_mean"][0] / 3600 * 1e6 / (8 * 64), rel=1e-15)
+    # nearest rank for n = 10: ceil(1) - 1 = 0 and ceil(9) - 1 = 8
+    e10 = 1.0 / np.arange(1, 11)
+    s = ora.eval_sweep_grid(g, e10, e10)
+    xs = np.sort([ora.evaluate(om, oh, kn, ei, ei).t_prefill for ei in e10])
+    assert s["ttft_p10"][0] == xs[0] and s["ttft_p90"][0] == xs[8]
+
+
+# ------------------------------------------------------------------ grid order
+
+def test_flat_index_order(ora):
+    g = wl.grid_full()
+    og = bridge.ora_grid(g)
+    assert og.size == 1900800 == g.size
+    rng = np.random.default_rng(3)
+    for idx in rng.integers(0, g.size, 20):
+        mi, hi, b, s_in, s_out, p, wb, blk, mbt = g.values_at(int(idx))
+        r = ora.eval_grid(og, int(idx), 1)
+        e = ora.evaluate(bridge.ora_model(g.models[mi]), bridge.ora_hw(g.hws[hi]),
+                         ora.knobs(b, s_in, s_out, p, wb, blk, mbt))
+        assert r["t_batch"][0] == e.t_batch and r["b_max"][0] == e.b_max
+    # fastest axis is max-batched-tokens, slowest the model
+    assert g.values_at(1)[8] == 4096 and g.values_at(0)[8] == 2048
+    assert g.values_at(g.size // 5)[0] == 1
+    with pytest.raises(ValueError):
+        ora.eval_grid(og, g.size - 1, 2)
+
+
+# ------------------------------------------------------------------ simulation
+
+def _one_req(n_in, n_out):
+    return np.array([0.0]), np.array([n_in], dtype=np.uint32), np.array([n_out], dtype=np.uint32)
+
+
+@pytest.mark.parametrize("n_in,n_out,mbt", [(700, 40, 2048), (5000, 17, 2048), (2048, 1, 2048), (16, 300, 8192)])
+def test_single_request_simulation_equals_analytic(ora, n_in, n_out, mbt):
+    m = wl.DENSE_34B
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+    arr, ins, outs = _one_req(n_in, n_out)
+    s = ora.simulate(om, oh, 2, 8, 16, mbt, 4, 1.0, arr, ins, outs, detail=True)
+    e = ora.evaluate(om, oh, ora.knobs(1, n_in, n_out, p=2, wbits=8, blk=16, mbt=mbt))
+    assert s["status"] == ora.SIM_OK
+    assert s["ttft"][0] == e.t_prefill
+    assert s["fin"][0] == pytest.approx(e.t_batch, rel=1e-13)
+    n_chunks = -(-n_in // mbt)
+    assert s["n_steps"] == n_chunks + n_out - 1 == s["n_request_steps"]
+    assert s["ttft_p50"] == s["ttft_p99"] == e.t_prefill
+    if n_out > 1:
+        assert s["mean_tpot"] == pytest.approx(e.tpot, rel=1e-13)
+    assert s["tokens_s"] == pytest.approx(n_out / s["fin"][0], rel=1e-15)
+
+
+def test_simulation_invariants(ora):
+    m = wl.DENSE_7B
+    om = bridge.ora_model(m)
+    h = wl.Hardware(1e15, 5e12, 40 * wl.GIB, 4e11)          # tight KV pool
+    oh = bridge.ora_hw(h)
+    tr = wl.request_trace(n=200)
+    for max_seqs, rate, mbt in [(1, 4.0, 2048), (8, 16.0, 2048), (64, 64.0, 8192), (256, 64.0, 4096)]:
+        s = ora.simulate(om, oh, 1, 16, 16, mbt, max_seqs, rate, tr.arrival_unit, tr.n_in, tr.n_out, detail=True)
+        assert s["status"] == ora.SIM_OK
+        assert s["min_free"] >= 0
+        arr = tr.arrival_unit / rate
+        assert np.all(s["first"] > arr) and np.all(s["fin"] >= s["first"])
+        assert np.all(np.diff(s["first"]) >= 0)            # FCFS: first tokens in arrival order
+        # every request emits out tokens: out-1 decode steps + its prompt chunks
+        assert s["n_request_steps"] >= int(tr.n_out.sum() - len(arr) + len(arr))
+        assert s["n_request_steps"] <= int((tr.n_out.astype(np.int64) - 1).sum() +
+                                           (-(-tr.n_in.astype(np.int64) // 1)).sum())
+        np.testing.assert_array_equal(s["ttft"], s["first"] - arr)
+        assert s["ttft_p50"] == np.sort(s["ttft"])[99] and s["ttft_p99"] == np.sort(s["ttft"])[197]
+        assert s["tokens_s"] == pytest.approx(tr.n_out.sum() / (s["fin"].max() - arr.min()), rel=1e-15)
+        if max_seqs == 1:
+            assert s["n_steps"] == s["n_request_steps"]
+
+
+def test_simulation_request_steps_exact_count(ora):
+    """max_seqs = 1 and prompts under the budget: each request takes exactly one
+    chunk and out-1 decode steps."""
+    om, oh = bridge.ora_model(wl.DENSE_7B), bridge.ora_hw(wl.HW_TINY)
+    tr = wl.request_trace(n=64)
+    s = ora.simulate(om, oh, 1, 16, 16, 8192, 1, 1.0, tr.arrival_unit, tr.n_in, tr.n_out)
+    assert s["n_request_steps"] == int(tr.n_out.sum()) == s["n_steps"]
+
+
+def test_simulation_spaced_and_serial_requests(ora):
+    m = wl.DENSE_7B
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+    ins = np.array([300, 5000, 64], dtype=np.uint32); outs = np.array([20, 5, 60], dtype=np.uint32)
+    singles = [ora.evaluate(om, oh, ora.knobs(1, int(i), int(o), mbt=2048)) for i, o in zip(ins, outs)]
+    # far apart: each request sees an empty engine
+    arr = np.array([0.0, 100.0, 200.0])
+    s = ora.simulate(om, oh, 1, 16, 16, 2048, 8, 1.0, arr, ins, outs, detail=True)
+    for i, e in enumerate(singles):
+        assert s["ttft"][i] == pytest.approx(e.t_prefill, rel=1e-12)
+        assert s["fin"][i] - arr[i] == pytest.approx(e.t_batch, rel=1e-12)
+    # all at time 0, one at a time: finish times are running sums
+    s = ora.simulate(om, oh, 1, 16, 16, 2048, 1, 1.0, np.zeros(3), ins, outs, detail=True)
+    run = np.cumsum([e.t_batch for e in singles])
+    np.testing.assert_allclose(s["fin"], run, rtol=1e-13)
+
+
+def test_simulation_batched_decode_by_hand(ora):
+    """Two identical requests at t=0, both admitted: one prefill pass with both
+    prompts, then out-1 decode steps with two tokens each."""
+    m = wl.DENSE_7B
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+    n_in, n_out = 100, 4
+    s = ora.simulate(om, oh, 1, 16, 16, 2048, 2, 1.0, np.zeros(2), np.array([n_in] * 2, dtype=np.uint32),
+                     np.array([n_out] * 2, dtype=np.uint32), detail=True)
+    t = ora.pass_detail(om, oh, 1, 16, 2 * n_in, 2 * n_in * n_in, 2 * n_in, 2)["t_pass"]
+    assert s["ttft"][0] == s["ttft"][1] == t
+    for j in range(1, n_out):
+        ctx = n_in + j
+        t += ora.pass_detail(om, oh, 1, 16, 2, 2 * ctx, 2 * ctx, 2)["t_pass"]
+    assert s["fin"][0] == s["fin"][1] == t
+    assert s["n_steps"] == n_out and s["n_request_steps"] == 2 * n_out
+    # chunked: budget 150 -> step 1 gives 100 + 50, step 2: decode of req 0 + 50 of req 1
+    s = ora.simulate(om, oh, 1, 16, 16, 150, 2, 1.0, np.zeros(2), np.array([n_in] * 2, dtype=np.uint32),
+                     np.array([n_out] * 2, dtype=np.uint32), detail=True)
+    t1 = ora.pass_detail(om, oh, 1, 16, 150, 100 * 100 + 50 * 50, 100 + 50, 1)["t_pass"]
+    assert s["ttft"][0] == t1
+    t2 = t1 + ora.pass_detail(om, oh, 1, 16, 1 + 50, 101 + 50 * 100, 101 + 100, 2)["t_pass"]
+    assert s["ttft"][1] == t2
+    assert s["n_request_steps"] == 2 + 2 + (n_out - 2) * 2 + 1
+
+
+def test_simulation_infeasible_and_blocking(ora):
+    m = wl.DENSE_7B
+    om = bridge.ora_model(m)
+    w = ora.weight_bytes_gpu(om, 1, 16)
+    kv_tok = ora.kv_bytes_token(om, 1)
+    ins = np.array([100, 100], dtype=np.uint32); outs = np.array([28, 28], dtype=np.uint32)
+    # pool of exactly 8 blocks: each request needs 8 -> strictly serial even with max_seqs 2
+    h = wl.Hardware(1e15, 5e12, w + 8 * 16 * kv_tok, 4e11)
+    s = ora.simulate(om, bridge.ora_hw(h), 1, 16, 16, 2048, 2, 1.0, np.zeros(2), ins, outs, detail=True)
+    assert s["status"] == ora.SIM_OK and s["min_free"] == 0
+    assert s["first"][1] > s["fin"][0]
+    # one block short: a request can never fit
+    h = wl.Hardware(1e15, 5e12, w + 8 * 16 * kv_tok - 1, 4e11)
+    s = ora.simulate(om, bridge.ora_hw(h), 1, 16, 16, 2048, 2, 1.0, np.zeros(2), ins, outs)
+    assert s["status"] == ora.SIM_INFEASIBLE and np.isinf(s["ttft_p50"]) and s["n_steps"] == 0
+    # weights do not fit
+    h = wl.Hardware(1e15, 5e12, w, 4e11)
+    assert ora.simulate(om, bridge.ora_hw(h), 1, 16, 16, 2048, 2, 1.0, np.zeros(2), ins, outs)["status"] == 1
+
+
+# ------------------------------------------------------------------- selection
+
+def _brute_topk(obj, ok, k):
+    cand = sorted((float(v), i) for i, v in enumerate(obj) if ok[i])
+    return cand[:k]
+
+
+def test_select_topk_against_full_sort(ora):
+    rng = np.random.default_rng(11)
+    n = 1500
+    obj = rng.integers(0, 40, n).astype(np.float64)      # many exact ties
+    obj[rng.integers(0, n, 30)] = np.nan
+    fe = (rng.random(n) < 0.7).astype(np.uint8)
+    c1 = rng.random(n); c2 = rng.random(n)
+    grp = rng.integers(0, 5, n).astype(np.uint32)
+    ok = (fe == 1) & (c1 <= 0.6) & (c2 <= 0.9) & ~np.isnan(obj)
+    idx, val, cnt = ora.select_topk(obj, fe, [(c1, 0.6), (c2, 0.9)], k=8)
+    exp = _brute_topk(obj, ok, 8)
+    assert [(v, i) for v, i in zip(val[0], idx[0])] == exp and cnt[0] == ok.sum()
+    idx, val, cnt = ora.select_topk(obj, fe, [(c1, 0.6), (c2, 0.9)], group=grp, n_groups=6, k=3)
+    for gi in range(6):
+        exp = _brute_topk(obj, ok & (grp == gi), 3)
+        got = [(v, i) for v, i in zip(val[gi], idx[gi]) if i != ora.NO_INDEX]
+        assert got == exp and cnt[gi] == (ok & (grp == gi)).sum()
+    assert np.all(idx[5] == ora.NO_INDEX) and np.all(np.isinf(val[5])) and cnt[5] == 0
+    # constraint boundary is inclusive; nothing passes -> sentinel
+    idx, val, cnt = ora.select_topk(np.array([3.0, 1.0, 2.0]), None, [(np.array([0.5, 0.7, 0.2]), 0.5)], k=2)
+    assert list(idx[0]) == [2, 0] and cnt[0] == 2
+    idx, val, cnt = ora.select_topk(np.array([3.0, 1.0]), np.zeros(2, dtype=np.uint8), k=1)
+    assert idx[0, 0] == ora.NO_INDEX and val[0, 0] == np.inf and cnt[0] == 0
+
+
+def test_tiny_grid_argmin_by_numpy(ora):
+    g = wl.grid_tiny()
+    r = ora.eval_grid(bridge.ora_grid(g))
+    ok = (r["feasible"] == 1) & (r["t_prefill"] <= wl.TTFT_CAP_S)
+    masked = np.where(ok, r["t_batch"], np.inf)
+    idx, val, cnt = ora.select_topk(r["t_batch"], r["feasible"], [(r["t_prefill"], wl.TTFT_CAP_S)])
+    assert idx[0, 0] == np.argmin(masked) and val[0, 0] == masked.min() and cnt[0] == ok.sum()
+
+
+def _pareto_def(x, y, ok):
+    keep = []
+    for i in range(len(x)):
+        if not ok[i]:
+            continue
+        dom = False
+        for j in range(len(x)):
+            if ok[j] and j != i and x[j] <= x[i] and y[j] <= y[i] and (x[j] < x[i] or y[j] < y[i]):
+                dom = True
+                break
+        if not dom:
+            keep.append(i)
+    return sorted(keep, key=lambda i: (x[i], y[i], i))
+
+
+def test_pareto_brute_and_sweep(ora):
+    rng = np.random.default_rng(5)
+    for trial in range(6):
+        n = 400
+        x = rng.integers(0, 25, n).astype(np.float64)
+        y = rng.integers(0, 25, n).astype(np.float64)
+        if trial == 1:
+            x[:] = 3.0                                       # one column constant
+        if trial == 2:
+            y = 30.0 - x                                     # everything on the front, duplicates kept
+        mask = (rng.random(n) < 0.8).astype(np.uint8)
+        if trial == 3:
+            x[5] = np.nan; y[9] = np.nan
+        ok = (mask == 1) & ~np.isnan(x) & ~np.isnan(y)
+        exp = _pareto_def(x, y, ok)
+        assert list(ora.pareto_brute(x, y, mask)) == exp
+        assert list(ora.pareto_sweep(x, y, mask)) == exp
+    assert len(ora.pareto_sweep(np.array([1.0]), np.array([1.0]), np.array([0], dtype=np.uint8))) == 0
+    x = rng.random(3000); y = rng.random(3000)
+    assert list(ora.pareto_sweep(x, y)) == list(ora.pareto_brute(x, y))
+
+
+# --------------------------------------------------------- sampled space / RNG
+
+def test_philox_against_numpy(ora):
+    """numpy's Philox is Philox4x64-10; it bumps the counter before producing a
+    block, so the block for counter c is what numpy emits from counter c - 1."""
+    rng = np.random.default_rng(7)
+    for _ in range(20):
+        key = rng.integers(0, 2 ** 63, 2, dtype=np.uint64)
+        ctr = rng.integers(1, 2 ** 63, 4, dtype=np.uint64)
+        prev = ctr.copy(); prev[0] -= np.uint64(1)
+        ref = np.random.Philox(key=key, counter=prev).random_raw(4)
+        np.testing.assert_array_equal(ora.philox4x64_10(ctr, key), ref)
+    ref = np.random.Philox(key=[wl.SEED, 0], counter=[41, 0, 0, 0]).random_raw(4)
+    np.testing.assert_array_equal(ora.philox4x64_10([42, 0, 0, 0], [wl.SEED, 0]), ref)
+
+
+def test_sampled_config_draws(ora):
+    sp = wl.sample_space()
+    osp = bridge.ora_space(sp)
+    seen_L, seen_kv = set(), set()
+    for idx in range(3000):
+        m, h, kn = ora.sample_config(osp, wl.SEED, idx)
+        raw = np.random.Philox(key=[wl.SEED, 0], counter=[idx - 1 if idx else 2 ** 64 - 1,
+                                                           0 if idx else 2 ** 64 - 1,
+                                                           0 if idx else 2 ** 64 - 1,
+                                                           0 if idx else 2 ** 64 - 1]).random_raw(4)
+        u = [int((int(raw[j >> 2]) >> (16 * (j & 3))) & 0xFFFF) for j in range(14)]
+        assert m.L == 16 + (u[0] * 81 >> 16)
+        n_h = int(sp.heads[u[1] >> 6])
+        assert (m.n_h, m.d) == (n_h, 128 * n_h)
+        kvc = [1, 4, 8, n_h][u[2] >> 14]
+        assert m.n_kv == kvc
+        ratio = 2.5 + 1.5 * u[3] / 65536.0
+        assert m.d_ff == 128 * int(np.floor(ratio * n_h + 0.5))
+        assert 2.5 * n_h - 0.5 <= m.d_ff / 128 <= 4.0 * n_h + 0.5
+        assert h.peak == sp.peak[u[4] >> 6] and h.bw == sp.bw[u[5] >> 6] and h.cap == sp.cap[u[6] * 6 >> 16]
+        assert h.link_bw == h.bw / 12.5 and h.link_lat == 0.0
+        assert (kn.b, kn.s_in, kn.s_out) == (sp.batch[u[7] >> 6], sp.s_in[u[8] >> 6], sp.s_out[u[9] >> 6])
+        assert (kn.p, kn.wbits, kn.blk, kn.mbt) == (sp.tp[u[10] >> 14], sp.wbits[u[11] * 3 >> 16],
+                                                    sp.kv_block[u[12] >> 15], sp.mbt[u[13] * 3 >> 16])
+        assert (m.V, m.E, m.k) == (32000, 1, 1)
+        seen_L.add(m.L); seen_kv.add(m.n_kv if m.n_kv in (1, 4, 8) else 0)
+    assert min(seen_L) == 16 and max(seen_L) == 96 and seen_kv == {0, 1, 4, 8}
+    # lattice end points
+    assert sp.heads[0] == 16 and sp.heads[-1] == 128 and sp.batch[0] == 1 and sp.batch[-1] == 1024
+    assert sp.s_in[0] == 64 and sp.s_in[-1] == 32768 and sp.s_out[-1] == 8192
+    assert sp.peak[0] == 1e14 and sp.peak[-1] == pytest.approx(2.5e15) and sp.bw[-1] == pytest.approx(8e12)
+
+
+def test_bucket_and_histogram_bins(ora):
+    edges = wl.BUCKET_EDGES
+    assert ora.bucket(0.99e9, edges) == 0 and ora.bucket(1e9, edges) == 1 and ora.bucket(6.7e9, edges) == 3
+    assert ora.bucket(2.56e11, edges) == 9 and ora.bucket(1e13, edges) == 9
+    assert ora.hist_bin(2.0 ** -12) == 0 and ora.hist_bin(1e-9) == 0
+    assert ora.hist_bin(np.nextafter(2.0 ** -11, 0)) == 7 and ora.hist_bin(2.0 ** -11) == 8
+    assert ora.hist_bin(1.0) == 96 and ora.hist_bin(1.125) == 97 and ora.hist_bin(1.9999) == 103
+    assert ora.hist_bin(2.0 ** 20) == 255 and ora.hist_bin(np.nextafter(2.0 ** 20, 0)) == 255
+    assert ora.hist_bin(2.0 ** 19) == 248
+
+
+def test_sampled_reductions_against_columns(ora):
+    sp = bridge.ora_space(wl.sample_space())
+    n = 4000
+    r = ora.eval_sampled(sp, wl.SEED, 100, n, wl.BUCKET_EDGES, wl.TTFT_CAP_S, columns=True)
+    fe = r["feasible"] == 1
+    assert r["feasible_count"] == fe.sum() == r["hist"].sum()
+    assert 0 < fe.sum() < n
+    bins = np.array([ora.hist_bin(t) for t in r["t_batch"][fe]])
+    np.testing.assert_array_equal(np.bincount(bins, minlength=256), r["hist"])
+    for b in range(wl.N_BUCKETS):
+        ok = fe & (r["bucket"] == b) & (r["t_prefill"] <= wl.TTFT_CAP_S)
+        if ok.any():
+            masked = np.where(ok, r["cost"], np.inf)
+            assert r["win_idx"][b] == 100 + np.argmin(masked) and r["win_val"][b] == masked.min()
+        else:
+            assert r["win_idx"][b] == ora.NO_INDEX and np.isinf(r["win_val"][b])
+    # per-candidate columns are the plain evaluator on the drawn candidate
+    for i in (0, 17, 3999):
+        m, h, kn = ora.sample_config(sp, wl.SEED, 100 + i)
+        e = ora.evaluate(m, h, kn)
+        assert (e.t_prefill, e.t_batch, e.cost, e.b_max) == (r["t_prefill"][i], r["t_batch"][i], r["cost"][i],
+                                                             r["b_max"][i])
+        assert r["bucket"][i] == ora.bucket(ora.params_total(m), wl.BUCKET_EDGES)
+    # two half ranges combine to the full range
+    a = ora.eval_sampled(sp, wl.SEED, 100, n // 2, wl.BUCKET_EDGES, wl.TTFT_CAP_S)
+    b = ora.eval_sampled(sp, wl.SEED, 100 + n // 2, n // 2, wl.BUCKET_EDGES, wl.TTFT_CAP_S)
+    np.testing.assert_array_equal(a["hist"] + b["hist"], r["hist"])
+    assert a["feasible_count"] + b["feasible_count"] == r["feasible_count"]
