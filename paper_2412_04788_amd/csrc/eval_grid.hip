@@ -1,0 +1,190 @@
+// Grid evaluation kernels: flat index -> mixed-radix digits -> candidate ->
+// metrics, one candidate per lane, spec tables staged in LDS, coalesced
+// structure-of-arrays stores.
+#include "kernels.hpp"
+#include "perf_model.hpp"
+
+namespace guide {
+
+struct GridLds {
+    uint32_t axis[kNumAxes][GUIDE_MAX_AXIS_VALUES];
+    guide_model models[GUIDE_MAX_MODELS];
+    HwRecip hw[GUIDE_MAX_HW];
+};
+
+__device__ inline void stage_grid_tables(GridLds &s, const GridDesc &g, const DevTables *__restrict__ tab) {
+    for (uint32_t i = threadIdx.x; i < kNumAxes * GUIDE_MAX_AXIS_VALUES; i += blockDim.x)
+        (&s.axis[0][0])[i] = (&tab->axis_vals[0][0])[i];
+    for (uint32_t i = threadIdx.x; i < g.n_models * 8u; i += blockDim.x)
+        ((uint32_t *)s.models)[i] = ((const uint32_t *)tab->models)[i];
+    for (uint32_t i = threadIdx.x; i < g.n_hw; i += blockDim.x) {
+        const guide_hw h = tab->hw[i];
+        HwRecip r;
+        r.r_peak = 1.0 / h.peak_flops;
+        r.r_bw = 1.0 / h.hbm_bw;
+        r.cap = h.cap_bytes;
+        r.r_link = 1.0 / h.link_bw;
+        r.lat = h.link_lat;
+        s.hw[i] = r;
+    }
+}
+
+struct Candidate {
+    uint32_t model, hw;
+    Knobs kn;
+};
+
+__device__ inline Candidate decode_index(const GridLds &s, const GridDesc &g, uint32_t idx) {
+    uint32_t v[kNumAxes];
+    uint32_t rem = idx;
+#pragma unroll
+    for (int a = kNumAxes - 1; a > 0; --a) {
+        const uint32_t q = div32(rem, g.div[a]);
+        v[a] = s.axis[a][rem - q * g.div[a].d];
+        rem = q;
+    }
+    v[0] = s.axis[0][rem];
+    Candidate c;
+    c.model = v[AX_MODEL];
+    c.hw = v[AX_HW];
+    c.kn.b = v[AX_BATCH];
+    c.kn.s_in = v[AX_SIN];
+    c.kn.s_out = v[AX_SOUT];
+    c.kn.p = v[AX_TP];
+    c.kn.wbits = v[AX_WBITS];
+    c.kn.blk = v[AX_BLK];
+    c.kn.mbt = v[AX_MBT];
+    return c;
+}
+
+// GPU-hours per million generated tokens.
+__device__ inline double cost_of(const Knobs &kn, double t_batch) {
+    return (double)kn.p * t_batch / 3600.0 * 1.0e6 / ((double)kn.b * (double)kn.s_out);
+}
+
+template <bool ADDITIVE>
+__global__ __launch_bounds__(kBlock) void eval_grid_kernel(GridDesc g, const DevTables *__restrict__ tab,
+                                                           uint32_t first, uint32_t count, double re_c, double re_b,
+                                                           guide_metrics out) {
+    __shared__ GridLds s;
+    stage_grid_tables(s, g, tab);
+    __syncthreads();
+    for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < count; i += gridDim.x * kBlock) {
+        const Candidate c = decode_index(s, g, first + i);
+        const Coef cf = make_coef(s.models[c.model], c.kn.p, c.kn.wbits);
+        const HwRecip hw = s.hw[c.hw];
+        const TimeCoef tc = make_time_coef(cf, hw.r_peak * re_c, hw.r_bw * re_b, hw.r_link, hw.lat);
+        const EvalResult r = evaluate_times<ADDITIVE>(tc, c.kn);
+        const MemResult m = memory_check(cf, hw.cap, c.kn.b, c.kn.s_in, c.kn.s_out, c.kn.blk);
+        const double t_batch = r.t_prefill + r.t_decode;
+        if (out.t_prefill) out.t_prefill[i] = r.t_prefill;
+        if (out.t_decode) out.t_decode[i] = r.t_decode;
+        if (out.t_batch) out.t_batch[i] = t_batch;
+        if (out.decode_tok_s) {
+            const double n = (double)(c.kn.s_out - 1);
+            out.decode_tok_s[i] = c.kn.s_out > 1 ? (double)c.kn.b * n / r.t_decode : 0.0;
+        }
+        if (out.cost) out.cost[i] = cost_of(c.kn, t_batch);
+        if (out.b_max) out.b_max[i] = m.b_max;
+        if (out.feasible) out.feasible[i] = m.feasible ? 1 : 0;
+    }
+}
+
+// Keeps the R smallest (or largest) values seen, sorted; R <= 7 covers the
+// nearest-rank p10 / p90 of up to 64 samples.
+constexpr int kRankMax = 7;
+struct SmallestK {
+    double v[kRankMax];
+    __device__ void init() {
+#pragma unroll
+        for (int i = 0; i < kRankMax; ++i) v[i] = INFINITY;
+    }
+    __device__ void push(double x) {
+#pragma unroll
+        for (int i = 0; i < kRankMax; ++i) {
+            const double lo = fmin(v[i], x);
+            x = fmax(v[i], x);
+            v[i] = lo;
+        }
+    }
+    __device__ double at(uint32_t r) const {   // r-th smallest, 0-based
+        double x = v[0];
+#pragma unroll
+        for (int i = 1; i < kRankMax; ++i) x = r == (uint32_t)i ? v[i] : x;
+        return x;
+    }
+};
+
+template <bool ADDITIVE>
+__global__ __launch_bounds__(kBlock) void eval_sweep_kernel(GridDesc g, const DevTables *__restrict__ tab,
+                                                            uint32_t first, uint32_t count, uint32_t n_eff,
+                                                            guide_stats out) {
+    __shared__ GridLds s;
+    __shared__ double s_rec[GUIDE_MAX_EFF], s_reb[GUIDE_MAX_EFF];
+    stage_grid_tables(s, g, tab);
+    for (uint32_t i = threadIdx.x; i < n_eff; i += blockDim.x) {
+        s_rec[i] = 1.0 / tab->eff_c[i];
+        s_reb[i] = 1.0 / tab->eff_b[i];
+    }
+    __syncthreads();
+    // nearest rank: p10 = sorted[ceil(n/10) - 1]; p90 = sorted[ceil(9n/10) - 1] = (n - ceil(9n/10))-th largest, 0-based
+    const uint32_t r_lo = (n_eff + 9) / 10 - 1;
+    const uint32_t r_hi = n_eff - (9 * n_eff + 9) / 10;
+    for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < count; i += gridDim.x * kBlock) {
+        const Candidate c = decode_index(s, g, first + i);
+        const Coef cf = make_coef(s.models[c.model], c.kn.p, c.kn.wbits);
+        const HwRecip hw = s.hw[c.hw];
+        SmallestK lo_p, hi_p, lo_b, hi_b;   // hi_* hold negated values: the largest become the smallest
+        lo_p.init(); hi_p.init(); lo_b.init(); hi_b.init();
+        double sum_p = 0.0, sum_b = 0.0;
+        for (uint32_t e = 0; e < n_eff; ++e) {
+            const TimeCoef tc = make_time_coef(cf, hw.r_peak * s_rec[e], hw.r_bw * s_reb[e], hw.r_link, hw.lat);
+            const EvalResult r = evaluate_times<ADDITIVE>(tc, c.kn);
+            const double tb = r.t_prefill + r.t_decode;
+            sum_p += r.t_prefill;
+            sum_b += tb;
+            lo_p.push(r.t_prefill); hi_p.push(-r.t_prefill);
+            lo_b.push(tb); hi_b.push(-tb);
+        }
+        const MemResult m = memory_check(cf, hw.cap, c.kn.b, c.kn.s_in, c.kn.s_out, c.kn.blk);
+        const double mean_b = sum_b / (double)n_eff;
+        if (out.ttft_mean) out.ttft_mean[i] = sum_p / (double)n_eff;
+        if (out.ttft_p10) out.ttft_p10[i] = lo_p.at(r_lo);
+        if (out.ttft_p90) out.ttft_p90[i] = -hi_p.at(r_hi);
+        if (out.t_batch_mean) out.t_batch_mean[i] = mean_b;
+        if (out.t_batch_p10) out.t_batch_p10[i] = lo_b.at(r_lo);
+        if (out.t_batch_p90) out.t_batch_p90[i] = -hi_b.at(r_hi);
+        if (out.cost) out.cost[i] = cost_of(c.kn, mean_b);
+        if (out.b_max) out.b_max[i] = m.b_max;
+        if (out.feasible) out.feasible[i] = m.feasible ? 1 : 0;
+    }
+}
+
+static uint32_t blocks_for(uint32_t count) {
+    const uint32_t need = (count + kBlock - 1) / kBlock;
+    const uint32_t cap = kNumCU * 8;
+    return need < cap ? need : cap;
+}
+
+hipError_t launch_eval_grid(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, double e_c,
+                            double e_b, bool additive, const guide_metrics &out, hipStream_t stream) {
+    const dim3 grid(blocks_for(count)), block(kBlock);
+    const double re_c = 1.0 / e_c, re_b = 1.0 / e_b;
+    if (additive)
+        hipLaunchKernelGGL(eval_grid_kernel<true>, grid, block, 0, stream, g, tab, first, count, re_c, re_b, out);
+    else
+        hipLaunchKernelGGL(eval_grid_kernel<false>, grid, block, 0, stream, g, tab, first, count, re_c, re_b, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_eval_sweep(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, uint32_t n_eff,
+                             bool additive, const guide_stats &out, hipStream_t stream) {
+    const dim3 grid(blocks_for(count)), block(kBlock);
+    if (additive)
+        hipLaunchKernelGGL(eval_sweep_kernel<true>, grid, block, 0, stream, g, tab, first, count, n_eff, out);
+    else
+        hipLaunchKernelGGL(eval_sweep_kernel<false>, grid, block, 0, stream, g, tab, first, count, n_eff, out);
+    return hipGetLastError();
+}
+
+}  // namespace guide

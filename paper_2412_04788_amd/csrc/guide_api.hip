@@ -1,0 +1,404 @@
+// C ABI of libguide: argument validation, context tables, kernel launches.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "kernels.hpp"
+
+using namespace guide;
+
+struct guide_ctx {
+    int device = 0;
+    uint32_t n_models = 0, n_hw = 0;
+    DevTables host_tab;              // staging copy of the device tables
+    DevTables *dev_tab = nullptr;
+    SpaceTables *dev_space = nullptr;
+    TraceDev *dev_trace = nullptr;
+    void *sampled_scratch = nullptr;
+    // Ring of pinned staging slots for the small per-call tables: the async copy
+    // reads the slot later, so a slot is reused only after its event has passed.
+    static constexpr int kSlots = 4;
+    static constexpr size_t kSlotBytes = sizeof(SpaceTables) > sizeof(TraceDev) ? sizeof(SpaceTables) : sizeof(TraceDev);
+    void *slot[kSlots] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t slot_ev[kSlots] = {nullptr, nullptr, nullptr, nullptr};
+    int next_slot = 0;
+    char err[256] = {0};
+};
+static_assert(guide_ctx::kSlotBytes >= sizeof(DevTables), "staging slot too small");
+
+namespace {
+
+int fail(guide_ctx *ctx, int code, const char *fmt, ...) {
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof ctx->err, fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+int hip_fail(guide_ctx *ctx, hipError_t e, const char *what) {
+    return fail(ctx, GUIDE_E_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define GUIDE_HIP(ctx, call)                                       \
+    do {                                                           \
+        hipError_t e_ = (call);                                    \
+        if (e_ != hipSuccess) return hip_fail(ctx, e_, #call);     \
+    } while (0)
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) == hipSuccess && (prev == dev || hipSetDevice(dev) == hipSuccess)) ok = true;
+        if (prev == dev) prev = -1;
+    }
+    ~DeviceGuard() {
+        if (prev >= 0) (void)hipSetDevice(prev);
+    }
+};
+
+const guide_axis *axis_of(const guide_grid *g, int a) {
+    const guide_axis *ax[kNumAxes] = {&g->model, &g->hw, &g->batch, &g->s_in, &g->s_out,
+                                      &g->tp,    &g->wbits, &g->kv_block, &g->mbt};
+    return ax[a];
+}
+
+const char *kAxisName[kNumAxes] = {"model", "hw", "batch", "s_in", "s_out", "tp", "wbits", "kv_block", "mbt"};
+
+// Validates the grid, fills the staging tables and the launch descriptor.
+int prepare_grid(guide_ctx *ctx, const guide_grid *grid, GridDesc *desc, uint64_t *size) {
+    if (!grid) return fail(ctx, GUIDE_E_ARG, "grid is NULL");
+    if (ctx->n_models == 0 || ctx->n_hw == 0)
+        return fail(ctx, GUIDE_E_ARG, "guide_set_models and guide_set_hardware must be called first");
+    uint64_t total = 1;
+    for (int a = 0; a < kNumAxes; ++a) {
+        const guide_axis *ax = axis_of(grid, a);
+        if (ax->count == 0 || ax->count > GUIDE_MAX_AXIS_VALUES)
+            return fail(ctx, GUIDE_E_ARG, "axis %s: count %u outside 1..%d", kAxisName[a], ax->count,
+                        GUIDE_MAX_AXIS_VALUES);
+        if (ax->kind != GUIDE_AXIS_GEOM2 && ax->kind != GUIDE_AXIS_TABLE)
+            return fail(ctx, GUIDE_E_ARG, "axis %s: unknown kind %u", kAxisName[a], ax->kind);
+        if (ax->kind == GUIDE_AXIS_TABLE && !ax->values)
+            return fail(ctx, GUIDE_E_ARG, "axis %s: TABLE axis without values", kAxisName[a]);
+        for (uint32_t i = 0; i < ax->count; ++i) {
+            uint64_t v;
+            if (ax->kind == GUIDE_AXIS_GEOM2) {
+                if (i >= 32 || (ax->start << i) >> i != ax->start)
+                    return fail(ctx, GUIDE_E_RANGE, "axis %s: start << %u overflows", kAxisName[a], i);
+                v = ax->start << i;
+            } else {
+                v = ax->values[i];
+            }
+            if (v > 0xFFFFFFFFull) return fail(ctx, GUIDE_E_RANGE, "axis %s: value does not fit 32 bits", kAxisName[a]);
+            if (a == AX_MODEL && v >= ctx->n_models)
+                return fail(ctx, GUIDE_E_RANGE, "model axis: index %llu >= %u models", (unsigned long long)v, ctx->n_models);
+            if (a == AX_HW && v >= ctx->n_hw)
+                return fail(ctx, GUIDE_E_RANGE, "hw axis: index %llu >= %u records", (unsigned long long)v, ctx->n_hw);
+            if (a >= AX_BATCH && v == 0) return fail(ctx, GUIDE_E_ARG, "axis %s: zero value", kAxisName[a]);
+            if ((a == AX_SIN || a == AX_SOUT) && v > 0x7FFFFFFFull)
+                return fail(ctx, GUIDE_E_RANGE, "axis %s: length above 2^31", kAxisName[a]);
+            ctx->host_tab.axis_vals[a][i] = (uint32_t)v;
+        }
+        desc->div[a] = make_div32(ax->count);
+        total *= ax->count;
+        if (total >= (1ull << 32)) return fail(ctx, GUIDE_E_RANGE, "grid has 2^32 or more configurations");
+    }
+    desc->n_models = ctx->n_models;
+    desc->n_hw = ctx->n_hw;
+    *size = total;
+    return GUIDE_OK;
+}
+
+// Stream-ordered upload of a small host table through a pinned slot.
+int stage_upload(guide_ctx *ctx, void *dst_dev, const void *src_host, size_t bytes, hipStream_t stream) {
+    const int i = ctx->next_slot;
+    ctx->next_slot = (i + 1) % guide_ctx::kSlots;
+    GUIDE_HIP(ctx, hipEventSynchronize(ctx->slot_ev[i]));
+    memcpy(ctx->slot[i], src_host, bytes);
+    GUIDE_HIP(ctx, hipMemcpyAsync(dst_dev, ctx->slot[i], bytes, hipMemcpyHostToDevice, stream));
+    GUIDE_HIP(ctx, hipEventRecord(ctx->slot_ev[i], stream));
+    return GUIDE_OK;
+}
+
+int upload_tables(guide_ctx *ctx, hipStream_t stream) {
+    return stage_upload(ctx, ctx->dev_tab, &ctx->host_tab, sizeof(DevTables), stream);
+}
+
+bool time_model_ok(uint32_t tm) { return tm == GUIDE_TIME_ROOFLINE || tm == GUIDE_TIME_ADDITIVE; }
+
+}  // namespace
+
+extern "C" {
+
+int guide_create(guide_ctx **out, int device) {
+    if (!out) return GUIDE_E_ARG;
+    *out = nullptr;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess || device < 0 || device >= n_dev) return GUIDE_E_DEVICE;
+    guide_ctx *ctx = new (std::nothrow) guide_ctx;
+    if (!ctx) return GUIDE_E_NOMEM;
+    ctx->device = device;
+    memset(&ctx->host_tab, 0, sizeof ctx->host_tab);
+    DeviceGuard guard(device);
+    if (!guard.ok || hipMalloc((void **)&ctx->dev_tab, sizeof(DevTables)) != hipSuccess ||
+        hipMalloc((void **)&ctx->dev_space, sizeof(SpaceTables)) != hipSuccess ||
+        hipMalloc((void **)&ctx->dev_trace, sizeof(TraceDev)) != hipSuccess ||
+        hipMalloc(&ctx->sampled_scratch, sampled_scratch_bytes()) != hipSuccess) {
+        guide_destroy(ctx);
+        return GUIDE_E_DEVICE;
+    }
+    for (int i = 0; i < guide_ctx::kSlots; ++i) {
+        if (hipHostMalloc(&ctx->slot[i], guide_ctx::kSlotBytes, hipHostMallocDefault) != hipSuccess ||
+            hipEventCreateWithFlags(&ctx->slot_ev[i], hipEventDisableTiming) != hipSuccess) {
+            guide_destroy(ctx);
+            return GUIDE_E_DEVICE;
+        }
+    }
+    *out = ctx;
+    return GUIDE_OK;
+}
+
+void guide_destroy(guide_ctx *ctx) {
+    if (!ctx) return;
+    DeviceGuard guard(ctx->device);
+    if (ctx->dev_tab) (void)hipFree(ctx->dev_tab);
+    if (ctx->dev_space) (void)hipFree(ctx->dev_space);
+    if (ctx->dev_trace) (void)hipFree(ctx->dev_trace);
+    if (ctx->sampled_scratch) (void)hipFree(ctx->sampled_scratch);
+    for (int i = 0; i < guide_ctx::kSlots; ++i) {
+        if (ctx->slot_ev[i]) { (void)hipEventSynchronize(ctx->slot_ev[i]); (void)hipEventDestroy(ctx->slot_ev[i]); }
+        if (ctx->slot[i]) (void)hipHostFree(ctx->slot[i]);
+    }
+    delete ctx;
+}
+
+const char *guide_last_error(const guide_ctx *ctx) { return ctx ? ctx->err : "guide: NULL context"; }
+
+int guide_set_models(guide_ctx *ctx, const guide_model *models, uint32_t n) {
+    if (!ctx) return GUIDE_E_ARG;
+    if (!models || n == 0 || n > GUIDE_MAX_MODELS) return fail(ctx, GUIDE_E_ARG, "models: need 1..%d rows", GUIDE_MAX_MODELS);
+    for (uint32_t i = 0; i < n; ++i) {
+        const guide_model &m = models[i];
+        if (!m.L || !m.d || !m.n_h || !m.n_kv || !m.d_ff || !m.V || !m.E || !m.k)
+            return fail(ctx, GUIDE_E_ARG, "model %u: zero field", i);
+        if (m.d % m.n_h) return fail(ctx, GUIDE_E_ARG, "model %u: n_h does not divide d", i);
+        if (m.k > m.E) return fail(ctx, GUIDE_E_ARG, "model %u: k > E", i);
+    }
+    memcpy(ctx->host_tab.models, models, sizeof(guide_model) * n);
+    ctx->n_models = n;
+    return GUIDE_OK;
+}
+
+int guide_set_hardware(guide_ctx *ctx, const guide_hw *hw, uint32_t n) {
+    if (!ctx) return GUIDE_E_ARG;
+    if (!hw || n == 0 || n > GUIDE_MAX_HW) return fail(ctx, GUIDE_E_ARG, "hardware: need 1..%d rows", GUIDE_MAX_HW);
+    for (uint32_t i = 0; i < n; ++i) {
+        const guide_hw &h = hw[i];
+        if (!(h.peak_flops > 0.0) || !(h.hbm_bw > 0.0) || !(h.cap_bytes > 0.0) || !(h.link_bw > 0.0) ||
+            !(h.link_lat >= 0.0))
+            return fail(ctx, GUIDE_E_ARG, "hardware %u: non-positive field", i);
+    }
+    memcpy(ctx->host_tab.hw, hw, sizeof(guide_hw) * n);
+    ctx->n_hw = n;
+    return GUIDE_OK;
+}
+
+int guide_eval_grid(guide_ctx *ctx, const guide_grid *grid, uint64_t first, uint64_t count, const guide_eff *eff,
+                    uint32_t time_model, const guide_metrics *out, const guide_stats *stats, void *stream_) {
+    if (!ctx) return GUIDE_E_ARG;
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!time_model_ok(time_model)) return fail(ctx, GUIDE_E_ARG, "unknown time model %u", time_model);
+    GridDesc desc;
+    uint64_t size = 0;
+    int rc = prepare_grid(ctx, grid, &desc, &size);
+    if (rc) return rc;
+    if (first > size || count > size - first)
+        return fail(ctx, GUIDE_E_RANGE, "range [%llu, +%llu) outside the grid of %llu", (unsigned long long)first,
+                    (unsigned long long)count, (unsigned long long)size);
+    const uint32_t n_eff = eff ? eff->n : 0;
+    if (n_eff > GUIDE_MAX_EFF) return fail(ctx, GUIDE_E_RANGE, "more than %d efficiency samples", GUIDE_MAX_EFF);
+    if (n_eff > 0 && (!eff->e_c || !eff->e_b)) return fail(ctx, GUIDE_E_ARG, "efficiency arrays are NULL");
+    for (uint32_t i = 0; i < n_eff; ++i)
+        if (!(eff->e_c[i] > 0.0) || !(eff->e_b[i] > 0.0) || std::isinf(eff->e_c[i]) || std::isinf(eff->e_b[i]))
+            return fail(ctx, GUIDE_E_ARG, "efficiency sample %u is not a positive finite number", i);
+    if (n_eff > 1 && !stats) return fail(ctx, GUIDE_E_ARG, "sweep needs a guide_stats");
+    if (n_eff <= 1 && !out) return fail(ctx, GUIDE_E_ARG, "guide_metrics is NULL");
+    if (count == 0) return GUIDE_OK;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
+    for (uint32_t i = 0; i < n_eff; ++i) {
+        ctx->host_tab.eff_c[i] = eff->e_c[i];
+        ctx->host_tab.eff_b[i] = eff->e_b[i];
+    }
+    rc = upload_tables(ctx, stream);
+    if (rc) return rc;
+    hipError_t e;
+    if (n_eff > 1) {
+        e = launch_eval_sweep(desc, ctx->dev_tab, (uint32_t)first, (uint32_t)count, n_eff,
+                              time_model == GUIDE_TIME_ADDITIVE, *stats, stream);
+    } else {
+        const double e_c = n_eff ? eff->e_c[0] : 1.0, e_b = n_eff ? eff->e_b[0] : 1.0;
+        e = launch_eval_grid(desc, ctx->dev_tab, (uint32_t)first, (uint32_t)count, e_c, e_b,
+                             time_model == GUIDE_TIME_ADDITIVE, *out, stream);
+    }
+    if (e != hipSuccess) return hip_fail(ctx, e, "eval_grid launch");
+    return GUIDE_OK;
+}
+
+size_t guide_select_workspace_bytes(const guide_select_spec *spec, uint64_t n) {
+    if (!spec) return 0;
+    return select_workspace_bytes(*spec, n);
+}
+
+int guide_select(guide_ctx *ctx, const guide_select_spec *spec, uint64_t n, const guide_select_out *out,
+                 void *workspace, size_t workspace_bytes, void *stream_) {
+    if (!ctx) return GUIDE_E_ARG;
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!spec || !out) return fail(ctx, GUIDE_E_ARG, "spec or out is NULL");
+    if (spec->mode != GUIDE_SELECT_TOPK && spec->mode != GUIDE_SELECT_PARETO)
+        return fail(ctx, GUIDE_E_ARG, "unknown select mode %u", spec->mode);
+    if (n >= (1ull << 32)) return fail(ctx, GUIDE_E_RANGE, "2^32 or more rows");
+    if (spec->n_constraints > GUIDE_MAX_CONSTRAINTS)
+        return fail(ctx, GUIDE_E_ARG, "more than %d constraints", GUIDE_MAX_CONSTRAINTS);
+    for (uint32_t c = 0; c < spec->n_constraints; ++c)
+        if (!spec->constraints[c].column && n) return fail(ctx, GUIDE_E_ARG, "constraint %u: NULL column", c);
+    if (!out->count) return fail(ctx, GUIDE_E_ARG, "out.count is NULL");
+    if (n && !spec->objective) return fail(ctx, GUIDE_E_ARG, "objective is NULL");
+    if (spec->mode == GUIDE_SELECT_TOPK) {
+        if (spec->k == 0 || spec->k > GUIDE_MAX_TOPK) return fail(ctx, GUIDE_E_ARG, "k outside 1..%d", GUIDE_MAX_TOPK);
+        if (spec->n_groups == 0 || spec->n_groups > GUIDE_MAX_GROUPS)
+            return fail(ctx, GUIDE_E_ARG, "n_groups outside 1..%d", GUIDE_MAX_GROUPS);
+        if (!out->idx || !out->val) return fail(ctx, GUIDE_E_ARG, "out.idx or out.val is NULL");
+    } else {
+        if (n && !spec->objective_y) return fail(ctx, GUIDE_E_ARG, "objective_y is NULL");
+        if (out->capacity && !out->idx) return fail(ctx, GUIDE_E_ARG, "out.idx is NULL");
+    }
+    const size_t need = select_workspace_bytes(*spec, n);
+    if (need && (!workspace || workspace_bytes < need))
+        return fail(ctx, GUIDE_E_NOMEM, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
+    const hipError_t e = spec->mode == GUIDE_SELECT_TOPK ? launch_select_topk(*spec, n, *out, workspace, stream)
+                                                         : launch_select_pareto(*spec, n, *out, workspace, stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "select launch");
+    return GUIDE_OK;
+}
+
+int guide_eval_sampled(guide_ctx *ctx, const guide_space *space, uint64_t seed, uint64_t first, uint64_t count,
+                       const double *bucket_edges, uint32_t n_edges, double ttft_cap, uint32_t time_model,
+                       const guide_sampled_out *out, void *stream_) {
+    if (!ctx) return GUIDE_E_ARG;
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!time_model_ok(time_model)) return fail(ctx, GUIDE_E_ARG, "unknown time model %u", time_model);
+    if (!space || !out) return fail(ctx, GUIDE_E_ARG, "space or out is NULL");
+    if (!space->heads || !space->peak || !space->bw || !space->cap || !space->batch || !space->s_in || !space->s_out ||
+        !space->tp || !space->wbits || !space->kv_block || !space->mbt || !space->kv_choices)
+        return fail(ctx, GUIDE_E_ARG, "space has a NULL table");
+    if (n_edges > GUIDE_MAX_BUCKET_EDGES || (n_edges && !bucket_edges))
+        return fail(ctx, GUIDE_E_ARG, "bucket edges: need 0..%d", GUIDE_MAX_BUCKET_EDGES);
+    if (!out->feasible_count || !out->win_val || !out->win_idx || !out->hist)
+        return fail(ctx, GUIDE_E_ARG, "a reduced output pointer is NULL");
+    if (count > (1ull << 40) || first > UINT64_MAX - count) return fail(ctx, GUIDE_E_RANGE, "count too large");
+    if (space->layers_n == 0 || space->layers_n > 65536 || !(space->link_div > 0.0) || space->vocab == 0)
+        return fail(ctx, GUIDE_E_ARG, "space: bad scalar field");
+    SpaceTables *t = new (std::nothrow) SpaceTables;
+    if (!t) return fail(ctx, GUIDE_E_NOMEM, "host allocation failed");
+    memset(t, 0, sizeof *t);
+    memcpy(t->heads, space->heads, sizeof t->heads);
+    memcpy(t->batch, space->batch, sizeof t->batch);
+    memcpy(t->s_in, space->s_in, sizeof t->s_in);
+    memcpy(t->s_out, space->s_out, sizeof t->s_out);
+    memcpy(t->peak, space->peak, sizeof t->peak);
+    memcpy(t->bw, space->bw, sizeof t->bw);
+    memcpy(t->cap, space->cap, sizeof(double) * 6);
+    memcpy(t->tp, space->tp, sizeof(uint32_t) * 4);
+    memcpy(t->wbits, space->wbits, sizeof(uint32_t) * 3);
+    memcpy(t->kv_block, space->kv_block, sizeof(uint32_t) * 2);
+    memcpy(t->mbt, space->mbt, sizeof(uint32_t) * 3);
+    memcpy(t->kv_choices, space->kv_choices, sizeof(uint32_t) * 4);
+    for (uint32_t i = 0; i < n_edges; ++i) t->edges[i] = bucket_edges[i];
+    t->n_edges = n_edges;
+    t->layers_lo = space->layers_lo; t->layers_n = space->layers_n;
+    t->ffn_lo_x2 = space->ffn_lo_x2; t->ffn_span_x2 = space->ffn_span_x2;
+    t->vocab = space->vocab; t->link_div = space->link_div;
+    int rc = GUIDE_OK;
+    for (uint32_t i = 0; i < GUIDE_LATTICE && rc == GUIDE_OK; ++i) {
+        if (t->heads[i] == 0 || t->heads[i] > 1024 || !t->batch[i] || !t->s_in[i] || !t->s_out[i] ||
+            t->s_in[i] > 0x7FFFFFFFu || t->s_out[i] > 0x7FFFFFFFu || !(t->peak[i] > 0.0) || !(t->bw[i] > 0.0))
+            rc = fail(ctx, GUIDE_E_ARG, "space: bad lattice entry %u", i);
+    }
+    for (uint32_t i = 0; i < 4 && rc == GUIDE_OK; ++i)
+        if (!t->tp[i] || (i < 3 && (!t->wbits[i] || !t->mbt[i])) || (i < 2 && !t->kv_block[i]))
+            rc = fail(ctx, GUIDE_E_ARG, "space: zero knob value");
+    if (rc) { delete t; return rc; }
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) { delete t; return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device); }
+    rc = stage_upload(ctx, ctx->dev_space, t, sizeof(SpaceTables), stream);
+    delete t;
+    if (rc) return rc;
+    hipError_t e = launch_eval_sampled(ctx->dev_space, seed, first, count, ttft_cap, time_model == GUIDE_TIME_ADDITIVE, *out,
+                            ctx->sampled_scratch, stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "eval_sampled launch");
+    return GUIDE_OK;
+}
+
+size_t guide_simulate_workspace_bytes(uint32_t n_cfg, uint32_t n_requests) {
+    return simulate_workspace_bytes(n_cfg, n_requests);
+}
+
+int guide_simulate(guide_ctx *ctx, const guide_grid *grid, const uint32_t *cfg_idx, const double *rate, uint32_t n_cfg,
+                   const guide_trace *trace, uint32_t time_model, const guide_sim_out *out, void *workspace,
+                   size_t workspace_bytes, void *stream_) {
+    if (!ctx) return GUIDE_E_ARG;
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!time_model_ok(time_model)) return fail(ctx, GUIDE_E_ARG, "unknown time model %u", time_model);
+    if (!trace || !out) return fail(ctx, GUIDE_E_ARG, "trace or out is NULL");
+    if (trace->n == 0 || trace->n > GUIDE_MAX_REQUESTS)
+        return fail(ctx, GUIDE_E_RANGE, "trace: need 1..%d requests", GUIDE_MAX_REQUESTS);
+    if (!trace->arrival_unit || !trace->n_in || !trace->n_out) return fail(ctx, GUIDE_E_ARG, "trace has a NULL array");
+    if (!out->ttft_p50 || !out->ttft_p99 || !out->mean_tpot || !out->tokens_s || !out->status || !out->n_steps ||
+        !out->n_request_steps)
+        return fail(ctx, GUIDE_E_ARG, "an output pointer is NULL");
+    GridDesc desc;
+    uint64_t size = 0;
+    int rc = prepare_grid(ctx, grid, &desc, &size);
+    if (rc) return rc;
+    if (n_cfg == 0) return GUIDE_OK;
+    if (!cfg_idx || !rate) return fail(ctx, GUIDE_E_ARG, "cfg_idx or rate is NULL");
+    TraceDev *t = new (std::nothrow) TraceDev;
+    if (!t) return fail(ctx, GUIDE_E_NOMEM, "host allocation failed");
+    memset(t, 0, sizeof *t);
+    double prev = -INFINITY;
+    for (uint32_t i = 0; i < trace->n && rc == GUIDE_OK; ++i) {
+        const double a = trace->arrival_unit[i];
+        if (!(a >= 0.0) || std::isinf(a) || a < prev) rc = fail(ctx, GUIDE_E_ARG, "trace: arrival %u not non-decreasing / finite", i);
+        if (trace->n_in[i] == 0 || trace->n_out[i] == 0 || trace->n_in[i] > (1u << 24) || trace->n_out[i] > (1u << 24))
+            rc = fail(ctx, GUIDE_E_ARG, "trace: request %u has a length outside 1..2^24", i);
+        prev = a;
+        t->arrival[i] = a; t->n_in[i] = trace->n_in[i]; t->n_out[i] = trace->n_out[i];
+    }
+    if (rc) { delete t; return rc; }
+    const size_t need = simulate_workspace_bytes(n_cfg, trace->n);
+    if (!workspace || workspace_bytes < need) {
+        delete t;
+        return fail(ctx, GUIDE_E_NOMEM, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    }
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) { delete t; return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device); }
+    rc = stage_upload(ctx, ctx->dev_trace, t, sizeof(TraceDev), stream);
+    delete t;
+    if (rc) return rc;
+    rc = upload_tables(ctx, stream);
+    if (rc) return rc;
+    hipError_t e = launch_simulate(desc, ctx->dev_tab, ctx->dev_trace, trace->n, cfg_idx, rate, n_cfg,
+                        time_model == GUIDE_TIME_ADDITIVE, *out, workspace, stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "simulate launch");
+    return GUIDE_OK;
+}
+
+}  // extern "C"

@@ -33,3 +33,39 @@ def rel_err(a, b):
     e[both_inf] = 0.0
     e[(a == 0) & (b == 0)] = 0.0
     return e
+
+
+# ------------------------------------------------------------- GPU-side glue
+
+def gpu_grid(grid: wl.Grid):
+    from paper_2412_04788_amd import guide
+    return guide.GridArg([(a.values, a.geom2_start) for a in grid.axes])
+
+
+def gpu_context(grid: wl.Grid):
+    from paper_2412_04788_amd import guide
+    ctx = guide.Context(0)
+    ctx.set_models(wl.models_array(grid.models))
+    ctx.set_hardware(wl.hw_array(grid.hws))
+    return ctx
+
+
+def gpu_space(sp: wl.SampleSpace) -> dict:
+    d = {f: getattr(sp, f) for f in ("heads", "peak", "bw", "cap", "batch", "s_in", "s_out", "tp", "wbits",
+                                      "kv_block", "mbt", "kv_choices")}
+    d.update(layers_lo=sp.layers_lo, layers_n=sp.layers_n, ffn_lo_x2=sp.ffn_lo_x2, ffn_span_x2=sp.ffn_span_x2,
+             vocab=sp.vocab, link_div=sp.link_div)
+    return d
+
+
+def metric_buffers(n, names=("t_prefill", "t_decode", "t_batch", "decode_tok_s", "cost", "b_max", "feasible")):
+    import torch
+    dt = {"b_max": torch.int32, "feasible": torch.uint8, "bucket": torch.int32}
+    return {k: torch.empty(n, dtype=dt.get(k, torch.float64), device="cuda") for k in names}
+
+
+def to_np(t, dtype=None):
+    a = t.cpu().numpy()
+    if dtype is not None:
+        a = a.view(dtype)
+    return a
