@@ -1,0 +1,171 @@
+"""GPU parity of the efficiency sweep, top-k with groups, and the Pareto front."""
+import numpy as np
+import pytest
+
+from paper_2412_04788_amd import workloads as wl
+from tests import bridge
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-9
+STAT_COLS = ("ttft_mean", "ttft_p10", "ttft_p90", "t_batch_mean", "t_batch_p10", "t_batch_p90", "cost")
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+def _dev(torch, a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.view(dtype)
+    return t.cuda()
+
+
+def _topk(torch, ctx, obj, k=1, feasible=None, constraints=(), group=None, n_groups=1):
+    from paper_2412_04788_amd import guide
+    n = obj.numel()
+    idx = torch.full((n_groups * k,), -7, dtype=torch.int64, device="cuda")
+    val = torch.full((n_groups * k,), -7.0, dtype=torch.float64, device="cuda")
+    cnt = torch.full((n_groups,), -7, dtype=torch.int64, device="cuda")
+    ws = torch.empty(ctx.select_workspace_bytes(guide.SELECT_TOPK, n, n_groups), dtype=torch.uint8, device="cuda")
+    ctx.select(guide.SELECT_TOPK, n, obj, idx, val, cnt, ws, feasible=feasible, constraints=constraints, group=group,
+               n_groups=n_groups, k=k)
+    torch.cuda.synchronize()
+    return (bridge.to_np(idx, np.uint64).reshape(n_groups, k), bridge.to_np(val).reshape(n_groups, k),
+            bridge.to_np(cnt, np.uint64))
+
+
+def _pareto(torch, ctx, x, y, feasible=None, constraints=(), capacity=None):
+    from paper_2412_04788_amd import guide
+    n = x.numel()
+    capacity = n if capacity is None else capacity
+    idx = torch.full((max(capacity, 1),), -7, dtype=torch.int64, device="cuda")
+    cnt = torch.full((1,), -7, dtype=torch.int64, device="cuda")
+    ws = torch.empty(ctx.select_workspace_bytes(guide.SELECT_PARETO, n), dtype=torch.uint8, device="cuda")
+    ctx.select(guide.SELECT_PARETO, n, x, idx, None, cnt, ws, objective_y=y, feasible=feasible,
+               constraints=constraints, capacity=capacity)
+    torch.cuda.synchronize()
+    m = int(bridge.to_np(cnt, np.uint64)[0])
+    return bridge.to_np(idx, np.uint64)[:min(m, capacity)], m
+
+
+def test_sweep_parity(ora, torch_cuda):
+    torch = torch_cuda
+    g = wl.grid_full()
+    ctx = bridge.gpu_context(g)
+    e_c, e_b = wl.efficiency_pairs()
+    og, gg = bridge.ora_grid(g), bridge.gpu_grid(g)
+    for first, count in [(0, 300), (1111111, 257), (g.size - 130, 130)]:
+        st = bridge.metric_buffers(count, names=STAT_COLS + ("b_max", "feasible"))
+        ctx.eval_grid(gg, first, count, stats=st, e_c=e_c, e_b=e_b)
+        torch.cuda.synchronize()
+        exp = ora.eval_sweep_grid(og, e_c, e_b, first, count)
+        for k in STAT_COLS:
+            e = bridge.rel_err(bridge.to_np(st[k]), exp[k])
+            assert e.max() <= TOL, (k, first, float(e.max()))
+        np.testing.assert_array_equal(bridge.to_np(st["b_max"], np.uint32), exp["b_max"])
+        np.testing.assert_array_equal(bridge.to_np(st["feasible"]), exp["feasible"])
+    # other sample counts exercise the nearest-rank positions: n = 2, 10, 33
+    for n in (2, 10, 33):
+        st = bridge.metric_buffers(64, names=STAT_COLS)
+        ctx.eval_grid(gg, 40000, 64, stats=st, e_c=e_c[:n], e_b=e_b[:n])
+        torch.cuda.synchronize()
+        exp = ora.eval_sweep_grid(og, e_c[:n], e_b[:n], 40000, 64)
+        for k in STAT_COLS:
+            assert bridge.rel_err(bridge.to_np(st[k]), exp[k]).max() <= TOL, (k, n)
+
+
+def test_topk_ties_groups_and_sentinels(ora, torch_cuda):
+    torch = torch_cuda
+    ctx = bridge.gpu_context(wl.grid_tiny())
+    rng = np.random.default_rng(21)
+    for n in (1, 63, 64, 65, 1000, 300001):
+        obj = rng.integers(-20, 20, n).astype(np.float64)          # heavy exact ties, negative values
+        obj[rng.integers(0, n, max(1, n // 50))] = np.nan
+        obj[rng.integers(0, n, max(1, n // 100))] = -0.0
+        fe = (rng.random(n) < 0.6).astype(np.uint8)
+        c1, c2 = rng.random(n), rng.random(n)
+        grp = rng.integers(0, 12, n).astype(np.uint32)             # ids 10, 11 fall outside n_groups = 10
+        d = dict(obj=_dev(torch, obj), fe=_dev(torch, fe), c1=_dev(torch, c1), c2=_dev(torch, c2),
+                 grp=_dev(torch, grp.view(np.int32)))
+        cons = [(d["c1"], 0.7), (d["c2"], 0.9)]
+        ocons = [(c1, 0.7), (c2, 0.9)]
+        for k in (1, 3, 8):
+            gi, gv, gc = _topk(torch, ctx, d["obj"], k, d["fe"], cons)
+            ei, ev, ec = ora.select_topk(obj, fe, ocons, k=k)
+            np.testing.assert_array_equal(gi, ei); np.testing.assert_array_equal(gv, ev)
+            np.testing.assert_array_equal(gc, ec)
+            gi, gv, gc = _topk(torch, ctx, d["obj"], k, d["fe"], cons, d["grp"], 10)
+            ei, ev, ec = ora.select_topk(obj, fe, ocons, group=grp, n_groups=10, k=k)
+            np.testing.assert_array_equal(gi, ei); np.testing.assert_array_equal(gv, ev)
+            np.testing.assert_array_equal(gc, ec)
+    # nothing passes
+    obj = _dev(torch, np.arange(10.0)); fe = _dev(torch, np.zeros(10, dtype=np.uint8))
+    gi, gv, gc = _topk(torch, ctx, obj, 2, fe)
+    assert np.all(gi == ora.NO_INDEX) and np.all(np.isinf(gv)) and gc[0] == 0
+    # +inf objective is a valid value and sorts last
+    obj = _dev(torch, np.array([np.inf, 3.0, np.inf]))
+    gi, gv, gc = _topk(torch, ctx, obj, 3)
+    assert list(gi[0]) == [1, 0, 2] and gc[0] == 3
+
+
+def test_pareto_small_with_ties(ora, torch_cuda):
+    torch = torch_cuda
+    ctx = bridge.gpu_context(wl.grid_tiny())
+    rng = np.random.default_rng(8)
+    for trial in range(8):
+        n = [1, 2, 64, 500, 2000, 2000, 2000, 5000][trial]
+        x = rng.integers(0, 30, n).astype(np.float64)
+        y = rng.integers(0, 30, n).astype(np.float64)
+        if trial == 4:
+            x[:] = 5.0
+        if trial == 5:
+            y = 100.0 - x
+        if trial == 6:
+            x = rng.random(n) * 1e-3; y = 1.0 / (x + 1e-4) * (1 + 0.01 * rng.random(n)); x[7] = np.nan
+        fe = (rng.random(n) < 0.8).astype(np.uint8)
+        got, m = _pareto(torch, ctx, _dev(torch, x), _dev(torch, y), _dev(torch, fe))
+        exp = ora.pareto_brute(x, y, fe)
+        assert m == len(exp)
+        np.testing.assert_array_equal(got, exp)
+    # constraint column and capacity smaller than the front
+    n = 3000
+    x = rng.random(n); y = 1.0 - x; c = rng.random(n)
+    got, m = _pareto(torch, ctx, _dev(torch, x), _dev(torch, y), None, [(_dev(torch, c), 0.5)], capacity=10)
+    exp = ora.pareto_brute(x, y, (c <= 0.5).astype(np.uint8))
+    assert m == len(exp) > 10
+    np.testing.assert_array_equal(got, exp[:10])
+    # no row passes
+    got, m = _pareto(torch, ctx, _dev(torch, x), _dev(torch, y), _dev(torch, np.zeros(n, dtype=np.uint8)))
+    assert m == 0 and len(got) == 0
+
+
+def test_full_grid_select_and_pareto_on_gpu_columns(ora, torch_cuda):
+    """Selection over the 1.9M-row grid: the GPU's choice must equal the oracle's
+    choice on the same (GPU-computed) columns bit for bit, and the oracle's choice on
+    oracle-computed columns except at near-ties (none expected here)."""
+    torch = torch_cuda
+    g = wl.grid_full()
+    ctx = bridge.gpu_context(g)
+    out = bridge.metric_buffers(g.size)
+    ctx.eval_grid(bridge.gpu_grid(g), 0, g.size, out=out)
+    torch.cuda.synchronize()
+    host = {k: bridge.to_np(v) for k, v in out.items()}
+    for cap in wl.SLO_CAPS_S:
+        gi, gv, gc = _topk(torch, ctx, out["cost"], 3, out["feasible"], [(out["t_prefill"], cap)])
+        ei, ev, ec = ora.select_topk(host["cost"], host["feasible"], [(host["t_prefill"], cap)], k=3)
+        np.testing.assert_array_equal(gi, ei); np.testing.assert_array_equal(gv, ev)
+        np.testing.assert_array_equal(gc, ec)
+    # per-model winners through the group path
+    grp = (np.arange(g.size) // (g.size // len(g.models))).astype(np.int32)
+    gi, gv, gc = _topk(torch, ctx, out["t_batch"], 2, out["feasible"], [(out["t_prefill"], 0.2)], _dev(torch, grp), 5)
+    ei, ev, ec = ora.select_topk(host["t_batch"], host["feasible"], [(host["t_prefill"], 0.2)],
+                                 group=grp.view(np.uint32), n_groups=5, k=2)
+    np.testing.assert_array_equal(gi, ei); np.testing.assert_array_equal(gv, ev); np.testing.assert_array_equal(gc, ec)
+    got, m = _pareto(torch, ctx, out["t_prefill"], out["cost"], out["feasible"])
+    exp = ora.pareto_sweep(host["t_prefill"], host["cost"], host["feasible"])
+    assert m == len(exp) > 0
+    np.testing.assert_array_equal(got, exp)
