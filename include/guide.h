@@ -62,7 +62,7 @@ typedef enum {
 enum { GUIDE_TIME_ROOFLINE = 0, GUIDE_TIME_ADDITIVE = 1 };
 enum { GUIDE_AXIS_GEOM2 = 0, GUIDE_AXIS_TABLE = 1 };
 enum { GUIDE_SELECT_TOPK = 0, GUIDE_SELECT_PARETO = 1 };
-enum { GUIDE_SIM_OK = 0, GUIDE_SIM_INFEASIBLE = 1 };
+enum { GUIDE_SIM_OK = 0, GUIDE_SIM_INFEASIBLE = 1, GUIDE_SIM_BAD_INPUT = 2, GUIDE_SIM_INTERNAL = 3 };
 
 #define GUIDE_MAX_MODELS 8
 #define GUIDE_MAX_HW 64
@@ -193,8 +193,9 @@ int guide_eval_sampled(guide_ctx *ctx, const guide_space *space, uint64_t seed, 
  * admission order under the remaining mbt budget; advance time by t_pass.
  * Outputs (DEVICE, n_cfg each): nearest-rank p50 / p99 of TTFT, mean TPOT over
  * requests with n_out > 1, generated tokens / (last finish - first arrival),
- * status (GUIDE_SIM_INFEASIBLE when weights or one request do not fit: times
- * +inf, tokens_s 0), engine steps, and request-steps (sum over steps of decode
+ * status (GUIDE_SIM_INFEASIBLE when weights or one request do not fit,
+ * GUIDE_SIM_BAD_INPUT for an index outside the grid or a rate <= 0: times +inf,
+ * tokens_s 0), engine steps, and request-steps (sum over steps of decode
  * tokens + prompt chunks scheduled).
  * workspace: DEVICE, guide_simulate_workspace_bytes(n_cfg, n) bytes.
  */

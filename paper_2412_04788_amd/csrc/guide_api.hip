@@ -342,7 +342,7 @@ int guide_eval_sampled(guide_ctx *ctx, const guide_space *space, uint64_t seed, 
     delete t;
     if (rc) return rc;
     hipError_t e = launch_eval_sampled(ctx->dev_space, seed, first, count, ttft_cap, time_model == GUIDE_TIME_ADDITIVE, *out,
-                            ctx->sampled_scratch, stream);
+                            ctx->sampled_scratch, stream, n_edges);
     if (e != hipSuccess) return hip_fail(ctx, e, "eval_sampled launch");
     return GUIDE_OK;
 }

@@ -24,13 +24,13 @@ struct SpaceTables {
     double edges[GUIDE_MAX_BUCKET_EDGES + 1];
     uint32_t tp[4], wbits[4], kv_block[2], mbt[4], kv_choices[4];
     uint32_t layers_lo, layers_n, ffn_lo_x2, ffn_span_x2, vocab, n_edges;
-    double r_link_div;   // link_bw = bw / link_div
-    double link_div;
+    double link_div;     // link_bw = bw / link_div
 };
 constexpr uint32_t kSampledMaxBlocks = 2048;
 size_t sampled_scratch_bytes();
 hipError_t launch_eval_sampled(const SpaceTables *tab, uint64_t seed, uint64_t first, uint64_t count, double ttft_cap,
-                               bool additive, const guide_sampled_out &out, void *scratch, hipStream_t stream);
+                               bool additive, const guide_sampled_out &out, void *scratch, hipStream_t stream,
+                               uint32_t n_edges);
 
 size_t simulate_workspace_bytes(uint32_t n_cfg, uint32_t n_req);
 struct TraceDev {

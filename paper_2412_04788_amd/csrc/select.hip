@@ -6,42 +6,13 @@
 // the least total time (Simulating Hybrid Parallelism); the engine keeps the top
 // three by inference time / throughput (Inference Engine, Step 2).
 #include "kernels.hpp"
+#include "reduce.hpp"
 
 namespace guide {
 
 namespace {
 
 constexpr uint32_t kSelBlocks = 1024;      // upper bound of blocks per reduction pass
-constexpr uint64_t kNone = ~0ull;
-
-// Order-preserving map double -> u64 (-0 folded into +0; NaN never reaches here).
-__device__ inline uint64_t key_of(double x) {
-    const uint64_t b = (uint64_t)__double_as_longlong(x + 0.0);
-    return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
-}
-__device__ inline double value_of(uint64_t k) {
-    const uint64_t b = (k >> 63) ? (k & 0x7FFFFFFFFFFFFFFFull) : ~k;
-    return __longlong_as_double((long long)b);
-}
-
-struct Pair {
-    uint64_t key, idx;
-};
-__device__ inline bool less_than(const Pair &a, const Pair &b) {
-    return a.key < b.key || (a.key == b.key && a.idx < b.idx);
-}
-__device__ inline Pair pair_min(const Pair &a, const Pair &b) { return less_than(b, a) ? b : a; }
-
-__device__ inline Pair wave_min(Pair p) {
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-        Pair o;
-        o.key = __shfl_xor(p.key, off, kWave);
-        o.idx = __shfl_xor(p.idx, off, kWave);
-        p = pair_min(p, o);
-    }
-    return p;
-}
 
 struct RowFilter {
     const uint8_t *feasible;
@@ -145,19 +116,7 @@ __global__ __launch_bounds__(kBlock) void topk_round_kernel(const double *__rest
             if (round == 0 && p.idx != kNone) ++cnt;
         } else {
             if (round == 0 && p.idx != kNone) atomicAdd(&s_cnt[wave][g], 1u);
-            uint64_t prev = kNone, cur = kNone;
-            if (ok) {
-                prev = __hip_atomic_load(&s_key[wave][g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                __hip_atomic_fetch_min(&s_key[wave][g], p.key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            }
-            __builtin_amdgcn_wave_barrier();
-            if (ok) cur = __hip_atomic_load(&s_key[wave][g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            const bool winner = ok && p.key == cur;
-            if (winner && cur < prev)
-                __hip_atomic_store(&s_idx[wave][g], kNone, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            __builtin_amdgcn_wave_barrier();
-            if (winner) __hip_atomic_fetch_min(&s_idx[wave][g], p.idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            __builtin_amdgcn_wave_barrier();
+            slot_update(s_key[wave], s_idx[wave], g, ok, p);
         }
     }
     if (!GROUPED) {

@@ -1,6 +1,285 @@
+// Step-level continuous-batching simulation, one serving configuration per
+// lane, and the per-configuration TTFT percentiles.
+//
+// The paper states that the frameworks' dynamic batching and split flow are
+// simulated (Overview) without giving the procedure; the scheduler simulated
+// here is documented in guide.h.  The engine state is kept in aggregated form:
+//   - admission is FCFS, so admitted requests are the index range [.., next);
+//   - prompt chunks are handed out in admission order, so at most the head of
+//     the prefill queue [pf_head, next) is partially prefilled;
+//   - a request that finished its prompt decodes on every later step, so its
+//     finishing step is known when its prompt completes: decoders live in a
+//     per-lane binary min-heap keyed by finishing step, and their number and
+//     total context are two running integers.
+// One step therefore costs one pass-time evaluation plus O(1) integer updates;
+// heap traffic is O(log n) per request, not per step.
 #include "kernels.hpp"
+#include "perf_model.hpp"
+
 namespace guide {
-size_t simulate_workspace_bytes(uint32_t, uint32_t) { return 256; }
-hipError_t launch_simulate(const GridDesc &, const DevTables *, const TraceDev *, uint32_t, const uint32_t *,
-                           const double *, uint32_t, bool, const guide_sim_out &, void *, hipStream_t) { return hipErrorNotSupported; }
+
+namespace {
+
+constexpr uint32_t kSimBlock = kWave;    // one wave per block: configurations diverge in step count
+constexpr uint32_t kPctBlock = 256;
+
+struct SimLds {
+    uint32_t axis[kNumAxes][GUIDE_MAX_AXIS_VALUES];
+    guide_model models[GUIDE_MAX_MODELS];
+    double arrival[GUIDE_MAX_REQUESTS];
+    uint32_t n_in[GUIDE_MAX_REQUESTS];
+    uint32_t n_out[GUIDE_MAX_REQUESTS];
+};
+
+// Workspace: heap[slot][cfg] (u64 key = finishing step << 10 | request), first[cfg][req], ttft[cfg][req].
+struct SimWs {
+    uint64_t *heap;
+    double *first;
+    double *ttft;
+};
+SimWs sim_ws(void *ws, uint32_t n_cfg, uint32_t n_req) {
+    SimWs w;
+    w.heap = (uint64_t *)ws;
+    w.first = (double *)(w.heap + (size_t)n_cfg * n_req);
+    w.ttft = w.first + (size_t)n_cfg * n_req;
+    return w;
 }
+
+template <bool ADDITIVE>
+__global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const DevTables *__restrict__ tab,
+                                                             const TraceDev *__restrict__ trace, uint32_t n_req,
+                                                             const uint32_t *__restrict__ cfg_idx,
+                                                             const double *__restrict__ rate_in, uint32_t n_cfg,
+                                                             guide_sim_out out, SimWs ws) {
+    __shared__ SimLds s;
+    for (uint32_t i = threadIdx.x; i < kNumAxes * GUIDE_MAX_AXIS_VALUES; i += blockDim.x)
+        (&s.axis[0][0])[i] = (&tab->axis_vals[0][0])[i];
+    for (uint32_t i = threadIdx.x; i < g.n_models * 8u; i += blockDim.x)
+        ((uint32_t *)s.models)[i] = ((const uint32_t *)tab->models)[i];
+    for (uint32_t i = threadIdx.x; i < n_req; i += blockDim.x) {
+        s.arrival[i] = trace->arrival[i];
+        s.n_in[i] = trace->n_in[i];
+        s.n_out[i] = trace->n_out[i];
+    }
+    __syncthreads();
+    const uint32_t c = blockIdx.x * kSimBlock + threadIdx.x;
+    if (c >= n_cfg) return;
+
+    // decode the grid index (s_in / s_out digits are ignored)
+    uint32_t v[kNumAxes];
+    bool bad_index;
+    {
+        uint32_t rem = cfg_idx[c];
+#pragma unroll
+        for (int a = kNumAxes - 1; a > 0; --a) {
+            const uint32_t q = div32(rem, g.div[a]);
+            v[a] = s.axis[a][rem - q * g.div[a].d];
+            rem = q;
+        }
+        bad_index = rem >= g.div[0].d;
+        v[0] = s.axis[0][bad_index ? 0 : rem];
+    }
+    const uint32_t max_seqs = v[AX_BATCH], p = v[AX_TP], wbits = v[AX_WBITS], blk = v[AX_BLK], mbt = v[AX_MBT];
+    const guide_hw hw = tab->hw[v[AX_HW]];
+    const double rate = rate_in[c];
+    const Coef cf = make_coef(s.models[v[AX_MODEL]], p, wbits);
+    const TimeCoef tc = make_time_coef(cf, 1.0 / hw.peak_flops, 1.0 / hw.hbm_bw, 1.0 / hw.link_bw, hw.link_lat);
+
+    // KV pool in blocks; every request must fit on its own
+    const double c_avail = hw.cap_bytes - cf.w_gpu;
+    uint32_t max_tok = 0;
+    uint64_t step_bound = n_req;
+    for (uint32_t i = 0; i < n_req; ++i) {
+        const uint32_t t = s.n_in[i] + s.n_out[i];
+        max_tok = t > max_tok ? t : max_tok;
+        step_bound += t;
+    }
+    long long n_blk = 0;
+    if (c_avail > 0.0) {
+        const double nb = floor(c_avail / ((double)blk * cf.kv_tok));
+        n_blk = nb >= 9.0e18 ? 0x7FFFFFFFFFFFFFFFll : (long long)nb;
+    }
+    const long long need_max = (long long)((max_tok + blk - 1) / blk);
+    if (bad_index || !(c_avail > 0.0) || need_max > n_blk || !(rate > 0.0)) {
+        out.ttft_p50[c] = INFINITY; out.ttft_p99[c] = INFINITY; out.mean_tpot[c] = INFINITY; out.tokens_s[c] = 0.0;
+        out.status[c] = (bad_index || !(rate > 0.0)) ? GUIDE_SIM_BAD_INPUT : GUIDE_SIM_INFEASIBLE;
+        out.n_steps[c] = 0; out.n_request_steps[c] = 0;
+        for (uint32_t i = 0; i < n_req; ++i) ws.ttft[(size_t)c * n_req + i] = INFINITY;
+        return;
+    }
+
+    uint64_t *heap = ws.heap + c;          // element j at heap[j * n_cfg]
+    double *first = ws.first + (size_t)c * n_req;
+    double *ttft = ws.ttft + (size_t)c * n_req;
+    const size_t hs = n_cfg;
+
+    double now = 0.0, sum_tpot = 0.0, max_fin = -INFINITY;
+    uint32_t next = 0, pf_head = 0, pf_done = 0, n_dec = 0, heap_n = 0, n_done = 0, n_tpot = 0;
+    uint64_t s_ctx = 0, step = 0, n_rs = 0, top_step = ~0ull;
+    long long free_blk = n_blk;
+    uint32_t status = GUIDE_SIM_OK;
+    double arr_next = s.arrival[0] / rate;   // arrival time of request `next`
+
+    while (n_done < n_req) {
+        uint32_t n_active = (next - pf_head) + n_dec;
+        // 1. idle jump to the next arrival
+        if (n_active == 0 && next < n_req) now = arr_next > now ? arr_next : now;
+        // 2. FCFS admission; stop at the first request that cannot enter
+        while (next < n_req && n_active < max_seqs && arr_next <= now) {
+            const long long need = (long long)((s.n_in[next] + s.n_out[next] + blk - 1) / blk);
+            if (need > free_blk) break;
+            free_blk -= need;
+            ++next;
+            ++n_active;
+            arr_next = next < n_req ? s.arrival[next] / rate : INFINITY;
+        }
+        // 3. schedule: one token per decoder, then prompt chunks in admission order
+        double T = (double)n_dec, Q = (double)s_ctx, K = (double)s_ctx, n_lm = (double)n_dec;
+        long long budget = (long long)mbt - (long long)n_dec;
+        uint32_t h = pf_head, done = pf_done, chunks = 0;
+        while (h < next && budget > 0) {
+            const long long rem = (long long)(s.n_in[h] - done);
+            const long long ch = rem < budget ? rem : budget;
+            budget -= ch;
+            const double C = (double)ch, ctx = (double)(done + (uint32_t)ch);
+            T += C;
+            Q = fma(C, ctx, Q);
+            K += ctx;
+            ++chunks;
+            if (ch == rem) {
+                n_lm += 1.0;
+                ++h;
+                done = 0;
+            } else {
+                done += (uint32_t)ch;
+            }
+        }
+        // 4. one engine step
+        now += pass_time<ADDITIVE>(tc, T, Q, K, n_lm);
+        ++step;
+        n_rs += n_dec + chunks;
+        // 5. book-keeping: decoders emitted a token; those at their last one leave
+        s_ctx += n_dec;
+        while (top_step == step) {
+            const uint64_t key = heap[0];
+            const uint32_t r = (uint32_t)(key & 1023u);
+            // pop
+            --heap_n;
+            const uint64_t last = heap[heap_n * hs];
+            uint32_t i = 0;
+            for (;;) {
+                const uint32_t l = 2 * i + 1;
+                if (l >= heap_n) break;
+                uint64_t ck = heap[l * hs];
+                uint32_t ci = l;
+                if (l + 1 < heap_n) {
+                    const uint64_t rk = heap[(l + 1) * hs];
+                    if (rk < ck) { ck = rk; ci = l + 1; }
+                }
+                if (ck >= last) break;
+                heap[i * hs] = ck;
+                i = ci;
+            }
+            if (heap_n) heap[i * hs] = last;
+            top_step = heap_n ? heap[0] >> 10 : ~0ull;
+            // request r is done
+            const uint32_t r_in = s.n_in[r], r_out = s.n_out[r];
+            free_blk += (long long)((r_in + r_out + blk - 1) / blk);
+            --n_dec;
+            s_ctx -= (uint64_t)r_in + r_out;
+            ++n_done;
+            sum_tpot += (now - first[r]) / (double)(r_out - 1);
+            ++n_tpot;
+            max_fin = now;
+        }
+        // prompts completed in this step emit their first token
+        for (uint32_t r = pf_head; r < h; ++r) {
+            const uint32_t r_in = s.n_in[r], r_out = s.n_out[r];
+            ttft[r] = now - s.arrival[r] / rate;
+            if (r_out == 1) {
+                free_blk += (long long)((r_in + 1 + blk - 1) / blk);
+                ++n_done;
+                max_fin = now;
+            } else {
+                first[r] = now;
+                ++n_dec;
+                s_ctx += (uint64_t)r_in + 1;
+                // push (finishing step, request)
+                const uint64_t key = ((step + r_out - 1) << 10) | r;
+                uint32_t i = heap_n++;
+                while (i > 0) {
+                    const uint32_t par = (i - 1) / 2;
+                    const uint64_t pk = heap[par * hs];
+                    if (pk <= key) break;
+                    heap[i * hs] = pk;
+                    i = par;
+                }
+                heap[i * hs] = key;
+                top_step = (i == 0) ? key >> 10 : top_step;
+            }
+        }
+        pf_head = h;
+        pf_done = done;
+        if (step > step_bound) {   // every step consumes at least one token of some request
+            status = GUIDE_SIM_INTERNAL;
+            break;
+        }
+    }
+
+    double tokens = 0.0;
+    for (uint32_t i = 0; i < n_req; ++i) tokens += (double)s.n_out[i];
+    out.mean_tpot[c] = n_tpot ? sum_tpot / (double)n_tpot : 0.0;
+    out.tokens_s[c] = tokens / (max_fin - s.arrival[0] / rate);
+    out.status[c] = status;
+    out.n_steps[c] = step;
+    out.n_request_steps[c] = n_rs;
+    if (status != GUIDE_SIM_OK)
+        for (uint32_t i = 0; i < n_req; ++i) ttft[i] = INFINITY;
+}
+
+// One block per configuration: bitonic sort of its TTFTs in LDS, nearest-rank
+// p50 = sorted[ceil(n/2) - 1] and p99 = sorted[ceil(0.99 n) - 1].
+__global__ __launch_bounds__(kPctBlock) void percentile_kernel(const double *__restrict__ ttft, uint32_t n_req,
+                                                               guide_sim_out out) {
+    __shared__ double v[GUIDE_MAX_REQUESTS];
+    const uint32_t c = blockIdx.x;
+    for (uint32_t i = threadIdx.x; i < GUIDE_MAX_REQUESTS; i += kPctBlock)
+        v[i] = i < n_req ? ttft[(size_t)c * n_req + i] : INFINITY;
+    __syncthreads();
+    for (uint32_t k = 2; k <= GUIDE_MAX_REQUESTS; k <<= 1) {
+        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+            for (uint32_t i = threadIdx.x; i < GUIDE_MAX_REQUESTS; i += kPctBlock) {
+                const uint32_t l = i ^ j;
+                if (l > i) {
+                    const double a = v[i], b = v[l];
+                    const bool up = (i & k) == 0;
+                    if ((a > b) == up) { v[i] = b; v[l] = a; }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    if (threadIdx.x == 0) {
+        out.ttft_p50[c] = v[(n_req + 1) / 2 - 1];
+        out.ttft_p99[c] = v[(99ull * n_req + 99) / 100 - 1];
+    }
+}
+
+}  // namespace
+
+size_t simulate_workspace_bytes(uint32_t n_cfg, uint32_t n_req) { return (size_t)n_cfg * n_req * 24 + 256; }
+
+hipError_t launch_simulate(const GridDesc &g, const DevTables *tab, const TraceDev *trace, uint32_t n_req,
+                           const uint32_t *cfg_idx, const double *rate, uint32_t n_cfg, bool additive,
+                           const guide_sim_out &out, void *ws_, hipStream_t stream) {
+    const SimWs ws = sim_ws(ws_, n_cfg, n_req);
+    const dim3 grid((n_cfg + kSimBlock - 1) / kSimBlock), block(kSimBlock);
+    if (additive)
+        hipLaunchKernelGGL(simulate_kernel<true>, grid, block, 0, stream, g, tab, trace, n_req, cfg_idx, rate, n_cfg, out, ws);
+    else
+        hipLaunchKernelGGL(simulate_kernel<false>, grid, block, 0, stream, g, tab, trace, n_req, cfg_idx, rate, n_cfg, out, ws);
+    hipLaunchKernelGGL(percentile_kernel, dim3(n_cfg), dim3(kPctBlock), 0, stream, (const double *)ws.ttft, n_req, out);
+    return hipGetLastError();
+}
+
+}  // namespace guide

@@ -18,7 +18,7 @@ OK, E_ARG, E_RANGE, E_NOMEM, E_DEVICE, E_CAPACITY = 0, -1, -2, -3, -4, -5
 TIME_ROOFLINE, TIME_ADDITIVE = 0, 1
 AXIS_GEOM2, AXIS_TABLE = 0, 1
 SELECT_TOPK, SELECT_PARETO = 0, 1
-SIM_OK, SIM_INFEASIBLE = 0, 1
+SIM_OK, SIM_INFEASIBLE, SIM_BAD_INPUT, SIM_INTERNAL = 0, 1, 2, 3
 NO_INDEX = 2 ** 64 - 1
 MAX_CONSTRAINTS = 4
 
