@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the GUIDE optimiser hot path on one MI355X.
+
+One step = one pass of the hot path over the full factorial grid (1 900 800
+configurations): guide_eval_grid (all seven columns), guide_select top-3 by cost
+under the 200 ms TTFT cap, and the (TTFT, cost) Pareto front.  The headline
+value is configurations per second over the timed steps, inputs resident in
+HBM.  The other kernels (efficiency sweep, sampled space, serving simulation)
+are timed once each after the steps and reported under "extra".
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+ALU_PEAK_GINST = 39321.6        # 256 CU x 4 SIMD x 16 lanes x 2.4 GHz: vector lane-instructions per ns * 1e... (G/s)
+BYTES_PER_CONFIG = 45           # 5 fp64 + u32 + u8 written per configuration, nothing read
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-extra", action="store_true", help="skip the sweep / sampled / simulation timings")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2412_04788_amd import guide, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    g = wl.grid_full()
+    n = g.size
+    ctx = guide.Context(0)
+    ctx.set_models(wl.models_array(g.models))
+    ctx.set_hardware(wl.hw_array(g.hws))
+    gg = guide.GridArg([(a.values, a.geom2_start) for a in g.axes])
+    dt = {"b_max": torch.int32, "feasible": torch.uint8}
+    out = {k: torch.empty(n, dtype=dt.get(k, torch.float64), device="cuda") for k in guide.METRIC_COLUMNS}
+    k_top = 3
+    sel_idx = torch.empty(k_top, dtype=torch.int64, device="cuda")
+    sel_val = torch.empty(k_top, dtype=torch.float64, device="cuda")
+    sel_cnt = torch.empty(1, dtype=torch.int64, device="cuda")
+    par_cap = 1 << 16
+    par_idx = torch.empty(par_cap, dtype=torch.int64, device="cuda")
+    par_cnt = torch.empty(1, dtype=torch.int64, device="cuda")
+    ws_top = torch.empty(ctx.select_workspace_bytes(guide.SELECT_TOPK, n), dtype=torch.uint8, device="cuda")
+    ws_par = torch.empty(ctx.select_workspace_bytes(guide.SELECT_PARETO, n), dtype=torch.uint8, device="cuda")
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        ctx.eval_grid(gg, 0, n, out=out)
+        if ev:
+            ev[1].record()
+        ctx.select(guide.SELECT_TOPK, n, out["cost"], sel_idx, sel_val, sel_cnt, ws_top, feasible=out["feasible"],
+                   constraints=[(out["t_prefill"], wl.TTFT_CAP_S)], k=k_top)
+        if ev:
+            ev[2].record()
+        ctx.select(guide.SELECT_PARETO, n, out["t_prefill"], par_idx, None, par_cnt, ws_par,
+                   objective_y=out["cost"], feasible=out["feasible"], capacity=par_cap)
+        if ev:
+            ev[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    total = t1 - t0
+    ms_eval = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    ms_topk = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    ms_pareto = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
+    value = n * args.steps / total
+    achieved = BYTES_PER_CONFIG * n / (ms_eval * 1e-3) / 1e9
+
+    result = {
+        "metric": "configs evaluated/sec (fp64 grid)", "value": value, "unit": "configs/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": total / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "full factorial grid, 1900800 configs (5 models x 6 hw x 11 batch x 10 s_in x 8 s_out "
+                               "x 4 tp x 3 wbits x 2 kv_block x 3 mbt): eval_grid + top-3 under 200 ms TTFT + Pareto",
+                   "configs_per_step": n, "top_k": k_top,
+                   "selected": [int(v) for v in sel_idx.cpu().numpy().view(np.uint64)],
+                   "pareto_front_size": int(par_cnt.item())},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "eval_grid_kernel",
+                     "kernel_ms": ms_eval, "bytes_per_config": BYTES_PER_CONFIG},
+        "phases_ms": {"eval_grid": ms_eval, "select_topk": ms_topk, "select_pareto": ms_pareto},
+    }
+
+    if not args.no_extra:
+        result["extra"] = extra_timings(ctx, gg, g, torch, np, guide, wl)
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(g, np, wl)
+    print(json.dumps(result))
+
+
+def _timed(torch, fn, reps=1):
+    fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps * 1e-3
+
+
+def extra_timings(ctx, gg, g, torch, np, guide, wl):
+    """Sweep (1.9M x 64 samples), sampled space (2^28), serving simulation (65 536 x 1024 requests)."""
+    n = g.size
+    extra = {}
+    e_c, e_b = wl.efficiency_pairs()
+    dt = {"b_max": torch.int32, "feasible": torch.uint8}
+    st = {k: torch.empty(n, dtype=dt.get(k, torch.float64), device="cuda") for k in guide.STATS_COLUMNS}
+    s = _timed(torch, lambda: ctx.eval_grid(gg, 0, n, stats=st, e_c=e_c, e_b=e_b))
+    extra["sweep"] = {"evaluations_per_s": n * 64 / s, "configs_per_s": n / s, "seconds": s, "samples": 64}
+    del st
+
+    sp = wl.sample_space()
+    space = {f: getattr(sp, f) for f in ("heads", "peak", "bw", "cap", "batch", "s_in", "s_out", "tp", "wbits",
+                                         "kv_block", "mbt", "kv_choices", "layers_lo", "layers_n", "ffn_lo_x2",
+                                         "ffn_span_x2", "vocab", "link_div")}
+    so = dict(feasible_count=torch.empty(1, dtype=torch.int64, device="cuda"),
+              win_val=torch.empty(wl.N_BUCKETS, dtype=torch.float64, device="cuda"),
+              win_idx=torch.empty(wl.N_BUCKETS, dtype=torch.int64, device="cuda"),
+              hist=torch.empty(256, dtype=torch.int64, device="cuda"))
+    n_s = 1 << 28
+    s = _timed(torch, lambda: ctx.eval_sampled(space, wl.SEED, 0, n_s, wl.BUCKET_EDGES, wl.TTFT_CAP_S, so))
+    extra["sampled"] = {"configs_per_s": n_s / s, "seconds": s, "candidates": n_s,
+                        "feasible": int(so["feasible_count"].item())}
+
+    n_cfg = 65536
+    idx, rate = wl.sim_configs(g, n_cfg)
+    tr = wl.request_trace()
+    d_idx = torch.from_numpy(idx.view(np.int32)).cuda()
+    d_rate = torch.from_numpy(rate).cuda()
+    sim = {k: torch.empty(n_cfg, dtype=torch.float64, device="cuda") for k in ("ttft_p50", "ttft_p99", "mean_tpot", "tokens_s")}
+    sim["status"] = torch.empty(n_cfg, dtype=torch.int32, device="cuda")
+    sim["n_steps"] = torch.empty(n_cfg, dtype=torch.int64, device="cuda")
+    sim["n_request_steps"] = torch.empty(n_cfg, dtype=torch.int64, device="cuda")
+    ws = torch.empty(ctx.simulate_workspace_bytes(n_cfg, len(tr.n_in)), dtype=torch.uint8, device="cuda")
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    ctx.simulate(gg, d_idx, d_rate, (tr.arrival_unit, tr.n_in, tr.n_out), sim, ws)
+    b.record()
+    torch.cuda.synchronize()
+    s = a.elapsed_time(b) * 1e-3
+    rs = int(sim["n_request_steps"].sum().item())
+    steps = int(sim["n_steps"].sum().item())
+    extra["simulate"] = {"request_steps_per_s": rs / s, "engine_steps_per_s": steps / s, "seconds": s,
+                         "configs": n_cfg, "requests_per_config": len(tr.n_in), "request_steps": rs,
+                         "feasible_configs": int((sim["status"] == 0).sum().item())}
+    return extra
+
+
+def cpu_baseline(g, np, wl):
+    """The oracle as it stands, single thread, on 96 blocks of 1024 rows spread evenly over the grid."""
+    from oracle import guide_oracle as ora
+    og = ora.Grid(wl.models_array(g.models), wl.hw_array(g.hws), [a.array() for a in g.axes])
+    blocks, rows = 96, 1024
+    firsts = np.linspace(0, g.size - rows, blocks).astype(np.int64)
+    ora.eval_grid(og, 0, 16)
+    t0 = time.perf_counter()
+    for f in firsts:
+        ora.eval_grid(og, int(f), rows)
+    dt_ = time.perf_counter() - t0
+    return {"value": blocks * rows / dt_, "unit": "configs/s", "cores": 1, "kind": "oracle",
+            "sample": f"{blocks} blocks of {rows} consecutive configurations spread evenly over the 1900800-row grid "
+                      f"(eval_grid only), {dt_:.1f} s", "host_cores_available": os.cpu_count()}
+
+
+if __name__ == "__main__":
+    main()

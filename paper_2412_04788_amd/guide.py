@@ -112,6 +112,9 @@ def load() -> C.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} is missing: build it with paper_2412_04788_amd/build.py")
+        # torch ships its own HIP runtime; it must be in the process before libguide's
+        # dependency on libamdhip64 is resolved, or two runtimes would be loaded
+        import torch  # noqa: F401
         lib = C.CDLL(LIB_PATH)
         lib.guide_create.argtypes = [C.POINTER(C.c_void_p), C.c_int]
         lib.guide_destroy.argtypes = [C.c_void_p]
