@@ -90,6 +90,134 @@ __global__ __launch_bounds__(kBlock) void eval_grid_kernel(GridDesc g, const Dev
     }
 }
 
+// ---------------------------------------------------------------- tiled variant
+//
+// The two fastest axes (KV block, max batched tokens) change only part of the
+// model: the decode series does not depend on either, the prefill only on the
+// token budget, the memory check only on the block size.  A lane therefore takes
+// one *tile* = all NB x NM combinations of those two axes for one setting of the
+// seven slower axes (NB*NM consecutive flat indices), evaluates the shared parts
+// once, and the wave transposes each output column through LDS so that global
+// stores stay coalesced (lane l stores index base + 64*it + l).
+
+struct TileLds {
+    GridLds g;
+    double r_tp[GUIDE_MAX_AXIS_VALUES];     // 1 / tp
+    double r_sin[GUIDE_MAX_AXIS_VALUES];    // nudged reciprocals for exact floor division
+    double r_blk[GUIDE_MAX_AXIS_VALUES];
+    double r_mbt[GUIDE_MAX_AXIS_VALUES];
+};
+
+template <bool ADDITIVE, int NB, int NM>
+__global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const DevTables *__restrict__ tab,
+                                                           uint32_t first, uint32_t count, double re_c, double re_b,
+                                                           guide_metrics out) {
+    constexpr int TS = NB * NM;
+    constexpr int kWaves = kBlock / kWave;
+    __shared__ TileLds s;
+    __shared__ double s_x[kWaves][kWave * TS];
+    stage_grid_tables(s.g, g, tab);
+    for (uint32_t i = threadIdx.x; i < GUIDE_MAX_AXIS_VALUES; i += blockDim.x) {
+        s.r_tp[i] = 1.0 / (double)max(tab->axis_vals[AX_TP][i], 1u);
+        s.r_sin[i] = recip_up(1.0 / (double)max(tab->axis_vals[AX_SIN][i], 1u));
+        s.r_blk[i] = recip_up(1.0 / (double)max(tab->axis_vals[AX_BLK][i], 1u));
+        s.r_mbt[i] = recip_up(1.0 / (double)max(tab->axis_vals[AX_MBT][i], 1u));
+    }
+    __syncthreads();
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    double *xw = s_x[wave];
+    const uint32_t t_first = first / TS;
+    const uint32_t n_tiles = (first + count - 1) / TS - t_first + 1;
+    const uint32_t last = first + count;                       // exclusive; count > 0, no overflow (grid < 2^32)
+    for (uint32_t tb = (blockIdx.x * kWaves + wave) * kWave; tb < n_tiles; tb += gridDim.x * kWaves * kWave) {
+        const uint32_t tl = tb + lane < n_tiles ? tb + lane : n_tiles - 1;   // idle lanes repeat the last tile
+        // digits of the seven slow axes
+        uint32_t dg[AX_BLK];
+        uint32_t rem = t_first + tl;
+#pragma unroll
+        for (int a = AX_BLK - 1; a > 0; --a) {
+            const uint32_t q = div32(rem, g.div[a]);
+            dg[a] = rem - q * g.div[a].d;
+            rem = q;
+        }
+        dg[0] = rem;
+        Knobs kn;
+        kn.b = s.g.axis[AX_BATCH][dg[AX_BATCH]];
+        kn.s_in = s.g.axis[AX_SIN][dg[AX_SIN]];
+        kn.s_out = s.g.axis[AX_SOUT][dg[AX_SOUT]];
+        kn.p = s.g.axis[AX_TP][dg[AX_TP]];
+        kn.wbits = s.g.axis[AX_WBITS][dg[AX_WBITS]];
+        const Coef cf = make_coef(s.g.models[s.g.axis[AX_MODEL][dg[AX_MODEL]]], kn.p, kn.wbits, s.r_tp[dg[AX_TP]]);
+        const HwRecip hw = s.g.hw[s.g.axis[AX_HW][dg[AX_HW]]];
+        const TimeCoef tc = make_time_coef(cf, hw.r_peak * re_c, hw.r_bw * re_b, hw.r_link, hw.lat);
+
+        const double t_decode = decode_time_fast<ADDITIVE>(tc, kn.b, kn.s_in, kn.s_out - 1);
+        double t_prefill[NM];
+#pragma unroll
+        for (int m = 0; m < NM; ++m)
+            t_prefill[m] = prefill_time_fast<ADDITIVE>(tc, kn.b, kn.s_in, s.g.axis[AX_MBT][m], s.r_sin[dg[AX_SIN]],
+                                                        s.r_mbt[m]);
+        MemResult mem[NB];
+        {
+            const double c_avail = hw.cap - cf.w_gpu;
+            const uint32_t tok = kn.s_in + kn.s_out;
+#pragma unroll
+            for (int k = 0; k < NB; ++k) {
+                const uint32_t blk = s.g.axis[AX_BLK][k];
+                const uint32_t tok_req = floor_div(tok + blk - 1, s.r_blk[k]) * blk;
+                const double kv_req = (double)tok_req * cf.kv_tok;
+                const double q = floor(c_avail / kv_req);
+                const bool room = c_avail > 0.0;
+                mem[k].feasible = room && (double)kn.b * kv_req <= c_avail;
+                mem[k].b_max = !room ? 0u : (q >= 4294967295.0 ? 4294967295u : (uint32_t)q);
+            }
+        }
+        const double bs = (double)kn.b * (double)kn.s_out;
+        const double cost_f = (double)kn.p * (1.0e6 / 3600.0) * fast_recip(bs);
+        const double tok_s = kn.s_out > 1 ? (double)kn.b * (double)(kn.s_out - 1) * fast_recip(t_decode) : 0.0;
+
+        // coalesced stores: element e of the wave's 64*TS consecutive indices sits in lane e / TS, slot e % TS
+        const uint32_t cfg0 = (t_first + tb) * TS;             // flat index of the wave's first element
+        auto store_f64 = [&](double *col, auto value_of_slot) {
+            if (!col) return;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+            for (int j = 0; j < TS; ++j) xw[lane * TS + j] = value_of_slot(j);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+            for (int it = 0; it < TS; ++it) {
+                const uint32_t cfg = cfg0 + it * kWave + lane;
+                const double v = xw[it * kWave + lane];
+                if (cfg >= first && cfg < last && tb + (it * kWave + lane) / TS < n_tiles) col[cfg - first] = v;
+            }
+        };
+        store_f64(out.t_prefill, [&](int j) { return t_prefill[j % NM]; });
+        store_f64(out.t_decode, [&](int) { return t_decode; });
+        store_f64(out.t_batch, [&](int j) { return t_prefill[j % NM] + t_decode; });
+        store_f64(out.decode_tok_s, [&](int) { return tok_s; });
+        store_f64(out.cost, [&](int j) { return (t_prefill[j % NM] + t_decode) * cost_f; });
+        if (out.b_max || out.feasible) {
+            uint32_t *xi = (uint32_t *)xw;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+            for (int j = 0; j < TS; ++j) {
+                xi[lane * TS + j] = mem[j / NM].b_max;
+                xi[kWave * TS + lane * TS + j] = mem[j / NM].feasible ? 1u : 0u;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+            for (int it = 0; it < TS; ++it) {
+                const uint32_t cfg = cfg0 + it * kWave + lane;
+                const uint32_t bm = xi[it * kWave + lane], fe = xi[kWave * TS + it * kWave + lane];
+                if (cfg >= first && cfg < last && tb + (it * kWave + lane) / TS < n_tiles) {
+                    if (out.b_max) out.b_max[cfg - first] = bm;
+                    if (out.feasible) out.feasible[cfg - first] = (uint8_t)fe;
+                }
+            }
+        }
+    }
+}
+
 // Keeps the R smallest (or largest) values seen, sorted; R <= 7 covers the
 // nearest-rank p10 / p90 of up to 64 samples.
 constexpr int kRankMax = 7;
@@ -166,10 +294,38 @@ static uint32_t blocks_for(uint32_t count) {
     return need < cap ? need : cap;
 }
 
+template <bool ADDITIVE, int NB, int NM>
+static void launch_tile(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, double re_c,
+                        double re_b, const guide_metrics &out, hipStream_t stream) {
+    const uint32_t ts = NB * NM;
+    const uint32_t n_tiles = (first + count - 1) / ts - first / ts + 1;
+    const dim3 grid(blocks_for(n_tiles)), block(kBlock);
+    hipLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM>), grid, block, 0, stream, g, tab, first, count, re_c, re_b, out);
+}
+
+// Tile shapes with a compiled kernel; other grids take the one-index-per-lane kernel.
+template <bool ADDITIVE>
+static bool dispatch_tile(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, double re_c,
+                          double re_b, const guide_metrics &out, hipStream_t stream) {
+    const uint32_t nb = g.div[AX_BLK].d, nm = g.div[AX_MBT].d;
+#define GUIDE_TILE(NB, NM)                                                               \
+    if (nb == NB && nm == NM) {                                                          \
+        launch_tile<ADDITIVE, NB, NM>(g, tab, first, count, re_c, re_b, out, stream);    \
+        return true;                                                                     \
+    }
+    GUIDE_TILE(2, 3) GUIDE_TILE(1, 3) GUIDE_TILE(2, 1) GUIDE_TILE(2, 2) GUIDE_TILE(1, 2) GUIDE_TILE(3, 3)
+    GUIDE_TILE(1, 4) GUIDE_TILE(2, 4)
+#undef GUIDE_TILE
+    return false;
+}
+
 hipError_t launch_eval_grid(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, double e_c,
                             double e_b, bool additive, const guide_metrics &out, hipStream_t stream) {
     const dim3 grid(blocks_for(count)), block(kBlock);
     const double re_c = 1.0 / e_c, re_b = 1.0 / e_b;
+    if (additive ? dispatch_tile<true>(g, tab, first, count, re_c, re_b, out, stream)
+                 : dispatch_tile<false>(g, tab, first, count, re_c, re_b, out, stream))
+        return hipGetLastError();
     if (additive)
         hipLaunchKernelGGL(eval_grid_kernel<true>, grid, block, 0, stream, g, tab, first, count, re_c, re_b, out);
     else

@@ -13,10 +13,14 @@ struct guide_ctx {
     int device = 0;
     uint32_t n_models = 0, n_hw = 0;
     DevTables host_tab;              // staging copy of the device tables
+    DevTables sent_tab;              // what dev_tab holds (valid when sent_valid), enqueued on sent_stream
+    bool sent_valid = false;
+    hipStream_t sent_stream = nullptr;
     DevTables *dev_tab = nullptr;
     SpaceTables *dev_space = nullptr;
     TraceDev *dev_trace = nullptr;
     void *sampled_scratch = nullptr;
+    void *select_scratch = nullptr;   // neutral between calls, see select.hip
     // Ring of pinned staging slots for the small per-call tables: the async copy
     // reads the slot later, so a slot is reused only after its event has passed.
     static constexpr int kSlots = 4;
@@ -125,8 +129,18 @@ int stage_upload(guide_ctx *ctx, void *dst_dev, const void *src_host, size_t byt
     return GUIDE_OK;
 }
 
+// The grid tables rarely change between calls: skip the copy when the device
+// already holds (or, in stream order, will hold) the same bytes.
 int upload_tables(guide_ctx *ctx, hipStream_t stream) {
-    return stage_upload(ctx, ctx->dev_tab, &ctx->host_tab, sizeof(DevTables), stream);
+    if (ctx->sent_valid && ctx->sent_stream == stream && memcmp(&ctx->sent_tab, &ctx->host_tab, sizeof(DevTables)) == 0)
+        return GUIDE_OK;
+    ctx->sent_valid = false;
+    const int rc = stage_upload(ctx, ctx->dev_tab, &ctx->host_tab, sizeof(DevTables), stream);
+    if (rc) return rc;
+    memcpy(&ctx->sent_tab, &ctx->host_tab, sizeof(DevTables));
+    ctx->sent_valid = true;
+    ctx->sent_stream = stream;
+    return GUIDE_OK;
 }
 
 bool time_model_ok(uint32_t tm) { return tm == GUIDE_TIME_ROOFLINE || tm == GUIDE_TIME_ADDITIVE; }
@@ -144,11 +158,15 @@ int guide_create(guide_ctx **out, int device) {
     if (!ctx) return GUIDE_E_NOMEM;
     ctx->device = device;
     memset(&ctx->host_tab, 0, sizeof ctx->host_tab);
+    memset(&ctx->sent_tab, 0, sizeof ctx->sent_tab);
     DeviceGuard guard(device);
     if (!guard.ok || hipMalloc((void **)&ctx->dev_tab, sizeof(DevTables)) != hipSuccess ||
         hipMalloc((void **)&ctx->dev_space, sizeof(SpaceTables)) != hipSuccess ||
         hipMalloc((void **)&ctx->dev_trace, sizeof(TraceDev)) != hipSuccess ||
-        hipMalloc(&ctx->sampled_scratch, sampled_scratch_bytes()) != hipSuccess) {
+        hipMalloc(&ctx->sampled_scratch, sampled_scratch_bytes()) != hipSuccess ||
+        hipMalloc(&ctx->select_scratch, select_scratch_bytes()) != hipSuccess ||
+        launch_select_scratch_init(ctx->select_scratch, nullptr) != hipSuccess ||
+        hipStreamSynchronize(nullptr) != hipSuccess) {
         guide_destroy(ctx);
         return GUIDE_E_DEVICE;
     }
@@ -170,6 +188,7 @@ void guide_destroy(guide_ctx *ctx) {
     if (ctx->dev_space) (void)hipFree(ctx->dev_space);
     if (ctx->dev_trace) (void)hipFree(ctx->dev_trace);
     if (ctx->sampled_scratch) (void)hipFree(ctx->sampled_scratch);
+    if (ctx->select_scratch) (void)hipFree(ctx->select_scratch);
     for (int i = 0; i < guide_ctx::kSlots; ++i) {
         if (ctx->slot_ev[i]) { (void)hipEventSynchronize(ctx->slot_ev[i]); (void)hipEventDestroy(ctx->slot_ev[i]); }
         if (ctx->slot[i]) (void)hipHostFree(ctx->slot[i]);
@@ -283,8 +302,9 @@ int guide_select(guide_ctx *ctx, const guide_select_spec *spec, uint64_t n, cons
         return fail(ctx, GUIDE_E_NOMEM, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
-    const hipError_t e = spec->mode == GUIDE_SELECT_TOPK ? launch_select_topk(*spec, n, *out, workspace, stream)
-                                                         : launch_select_pareto(*spec, n, *out, workspace, stream);
+    const hipError_t e = spec->mode == GUIDE_SELECT_TOPK
+                             ? launch_select_topk(*spec, n, *out, workspace, ctx->select_scratch, stream)
+                             : launch_select_pareto(*spec, n, *out, workspace, ctx->select_scratch, stream);
     if (e != hipSuccess) return hip_fail(ctx, e, "select launch");
     return GUIDE_OK;
 }

@@ -48,14 +48,14 @@ struct HwRecip {
     double r_peak, r_bw, cap, r_link, lat;
 };
 
-__device__ inline Coef make_coef(const guide_model &md, uint32_t p_, uint32_t wbits) {
+// rp = 1 / p_ (correctly rounded).
+__device__ inline Coef make_coef(const guide_model &md, uint32_t p_, uint32_t wbits, double rp) {
     Coef c;
     const double p = (double)p_, w = (double)wbits * 0.125, a = kActBytes;
     const double d = (double)md.d, dh = (double)(md.d / md.n_h);
     const double dq = (double)md.n_h * dh, dkv = (double)md.n_kv * dh;
     const double dff = (double)md.d_ff, V = (double)md.V, E = (double)md.E, k = (double)md.k;
     const double gkv = (double)((md.n_kv + p_ - 1) / p_) * dh;   // KV heads replicate when n_kv < p
-    const double rp = 1.0 / p;
     const double pf1 = 2.0 * d * dff, pf2 = dff * d, prt = md.E > 1 ? d * E : 0.0;
     const double pattn = d * dq + 2.0 * d * dkv + dq * d;
     c.L = (double)md.L;
@@ -89,6 +89,10 @@ __device__ inline Coef make_coef(const guide_model &md, uint32_t p_, uint32_t wb
     c.E = E;
     c.k = k;
     return c;
+}
+
+__device__ inline Coef make_coef(const guide_model &md, uint32_t p_, uint32_t wbits) {
+    return make_coef(md, p_, wbits, 1.0 / (double)p_);
 }
 
 // r_peak / r_bw already include the efficiency sample.
@@ -184,6 +188,37 @@ __device__ inline double ctx_sum(double s, double j0, double j1) {
     return (j1 - j0) * s + 0.5 * (j1 * (j1 + 1.0) - j0 * (j0 + 1.0));
 }
 
+// Reciprocal nudged upwards so that floor(a * r) == a / s exactly for integers
+// a < 2^47, s >= 1: the product never falls below the true quotient and
+// overshoots it by less than 1/s.  `approx` may be off by a few ulp.
+__device__ inline double recip_up(double approx) { return approx * (1.0 + 0x1p-48); }
+__device__ inline uint32_t floor_div(uint32_t a, double r_up) { return (uint32_t)((double)a * r_up); }
+
+// 1/x to about an ulp: hardware seed plus two Newton steps (x > 0, normal).
+__device__ inline double fast_recip(double x) {
+    double r = __builtin_amdgcn_rcp(x);
+    r = fma(fma(-x, r, 1.0), r, r);
+    r = fma(fma(-x, r, 1.0), r, r);
+    return r;
+}
+
+// sum_{j=1}^{n} max(alpha c_j, beta c_j + gamma) over contexts c_j = s + u j
+// (r_u ~ 1/u): both sides are linear in c, so the series splits at one
+// crossover; a step that lands within rounding of the crossover has equal
+// sides, so an off-by-one there does not change the sum beyond an ulp.
+template <bool ADDITIVE>
+__device__ inline double attention_series(double alpha, double beta, double gamma, double s, double u, double r_u,
+                                          double n) {
+    const double tri = 0.5 * n * (n + 1.0);
+    const double all = fma(u, tri, n * s);               // sum of c_j
+    if (ADDITIVE) return fma(alpha + beta, all, n * gamma);
+    if (alpha <= beta) return fma(beta, all, n * gamma); // bandwidth bound at every context
+    double jm = floor((gamma * fast_recip(alpha - beta) - s) * r_u);
+    jm = fmin(fmax(jm, 0.0), n);
+    const double low = fma(u, 0.5 * jm * (jm + 1.0), jm * s);
+    return fma(beta, low, fma(jm, gamma, alpha * (all - low)));
+}
+
 // Decode: steps j = 1..n with b tokens at context s + j.  Everything but
 // attention is the same every step; attention is max(alpha ctx, beta ctx + gamma)
 // with both sides linear in ctx, so the series splits at one crossover.
@@ -204,6 +239,44 @@ __device__ inline double decode_time(const TimeCoef &t, uint32_t b_, uint32_t s_
         jm = fmin(fmax(jm, 0.0), n);
         att = beta * ctx_sum(s, 0.0, jm) + jm * gamma + alpha * ctx_sum(s, jm, n);
     }
+    return fma(n, base, t.L * att);
+}
+
+// Same prefill with the segment loop of long prompts summed in closed form and
+// the integer divisions replaced by nudged reciprocals (r_s ~ 1/s, r_mbt ~ 1/mbt,
+// both from recip_up).
+template <bool ADDITIVE>
+__device__ inline double prefill_time_fast(const TimeCoef &t, uint32_t b, uint32_t s, uint32_t mbt, double r_s,
+                                           double r_mbt) {
+    const double S = (double)s;
+    if (s <= mbt) {
+        uint32_t r = floor_div(mbt, r_s);
+        r = r < b ? r : b;
+        const uint32_t n_full = r == b ? 1u : floor_div(b, recip_up(fast_recip((double)r)));
+        const uint32_t rem = b - n_full * r;
+        double R = (double)r;
+        double total = (double)n_full * pass_time<ADDITIVE>(t, R * S, R * S * S, R * S, R);
+        if (rem > 0) {
+            R = (double)rem;
+            total += pass_time<ADDITIVE>(t, R * S, R * S * S, R * S, R);
+        }
+        return total;
+    }
+    // n_fs full segments of mbt tokens at contexts mbt, 2 mbt, ..; then the rest with the LM head
+    const uint32_t n_seg = floor_div(s + mbt - 1, r_mbt);
+    const double M = (double)mbt, n_fs = (double)(n_seg - 1);
+    const double c_last = S - n_fs * M;
+    const double att = attention_series<ADDITIVE>(M * t.c_att, t.m_att_k, M * t.m_att_t, 0.0, M, r_mbt, n_fs);
+    const double one = fma(t.L, fma(n_fs, layer_base<ADDITIVE>(t, M), att), pass_time<ADDITIVE>(t, c_last, c_last * S, S, 1.0));
+    return (double)b * one;
+}
+
+template <bool ADDITIVE>
+__device__ inline double decode_time_fast(const TimeCoef &t, uint32_t b_, uint32_t s_, uint32_t n_) {
+    if (n_ == 0) return 0.0;
+    const double b = (double)b_, n = (double)n_;
+    const double base = fma(t.L, layer_base<ADDITIVE>(t, b), lm_head<ADDITIVE>(t, b));
+    const double att = attention_series<ADDITIVE>(b * t.c_att, b * t.m_att_k, b * t.m_att_t, (double)s_, 1.0, 1.0, n);
     return fma(n, base, t.L * att);
 }
 

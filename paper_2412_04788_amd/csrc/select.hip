@@ -12,7 +12,8 @@ namespace guide {
 
 namespace {
 
-constexpr uint32_t kSelBlocks = 1024;      // upper bound of blocks per reduction pass
+constexpr uint32_t kSelBlocks = 1024;      // blocks of a streaming pass (four per CU)
+constexpr int kWaves = kBlock / kWave;
 
 struct RowFilter {
     const uint8_t *feasible;
@@ -27,6 +28,41 @@ __device__ inline bool row_passes(const RowFilter &f, uint32_t i) {
     for (uint32_t c = 0; c < GUIDE_MAX_CONSTRAINTS; ++c)
         if (c < f.n_con) ok = ok && (f.col[c][i] <= f.cap[c]);
     return ok;
+}
+
+// All loads of a row are issued unconditionally (index clamped when the row is
+// past the end) so that several rows can be in flight at once.
+struct Row {
+    double x, y;
+    bool pass;
+};
+template <bool WITH_Y>
+__device__ inline Row load_row(const double *__restrict__ x, const double *__restrict__ y, const RowFilter &f,
+                               uint32_t i, uint32_t n) {
+    const bool valid = i < n;
+    const uint32_t j = valid ? i : 0;
+    Row r;
+    r.x = x[j];
+    r.y = WITH_Y ? y[j] : 0.0;
+    const uint8_t fe = f.feasible ? f.feasible[j] : (uint8_t)1;
+    double c[GUIDE_MAX_CONSTRAINTS];
+#pragma unroll
+    for (uint32_t k = 0; k < GUIDE_MAX_CONSTRAINTS; ++k) c[k] = k < f.n_con ? f.col[k][j] : 0.0;
+    bool ok = valid && fe != 0 && (r.x == r.x) && (!WITH_Y || r.y == r.y);
+#pragma unroll
+    for (uint32_t k = 0; k < GUIDE_MAX_CONSTRAINTS; ++k)
+        if (k < f.n_con) ok = ok && (c[k] <= f.cap[k]);
+    r.pass = ok;
+    return r;
+}
+
+// Block b owns the contiguous rows [b * per, (b + 1) * per); per is a multiple of
+// kBlock * kUnroll so that every lane of a wave runs the same trip count.
+constexpr uint32_t kUnroll = 4;
+__device__ inline uint32_t rows_per_block(uint32_t n) {
+    const uint32_t unit = kBlock * kUnroll;
+    const uint32_t per = (n + gridDim.x - 1) / gridDim.x;
+    return (per + unit - 1) / unit * unit;
 }
 
 RowFilter make_filter(const guide_select_spec &s) {
@@ -46,7 +82,180 @@ uint32_t blocks_for(uint64_t n) {
     return (uint32_t)(need < kSelBlocks ? need : kSelBlocks);
 }
 
-// ------------------------------------------------------------------- top-k
+// Context-owned device scratch of the Pareto kernels.  Between calls it is in its
+// neutral state (counters 0, bin_min all-ones, bin_cnt 0): the finishing kernel
+// puts back what the call changed, so no call starts with a clearing pass.
+constexpr uint32_t kBins = 4096;
+struct SelectScratch {
+    uint32_t counters[4];          // [0] survivors appended
+    uint64_t sample_lo[64];        // per sample block: least x key of passing sample rows
+    Pair sample_best[64];          // per sample block: (least y key, its x key)
+    uint64_t bin_min[kBins];       // least y key per x bin
+    uint32_t bin_cnt[kBins];       // survivors per bin
+    uint32_t bin_off[kBins + 1], bin_foff[kBins + 1], bin_cur[kBins];   // large-front path only
+};
+
+__global__ void select_scratch_init_kernel(SelectScratch *sc) {
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < kBins; i += gridDim.x * blockDim.x) {
+        sc->bin_min[i] = kNone;
+        sc->bin_cnt[i] = 0;
+        sc->bin_cur[i] = 0;
+        sc->bin_off[i] = 0;
+        sc->bin_foff[i] = 0;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < 4) sc->counters[threadIdx.x] = 0;
+}
+
+// ------------------------------------------------------- top-k, one group
+
+// Sorted list of the K least (key, row) pairs seen by one lane.
+template <int K>
+struct TopList {
+    Pair v[K];
+    __device__ void init() {
+#pragma unroll
+        for (int i = 0; i < K; ++i) v[i] = Pair{kNone, kNone};
+    }
+    __device__ void insert(const Pair &p) {
+        if (!less_than(p, v[K - 1])) return;
+        v[K - 1] = p;
+#pragma unroll
+        for (int i = K - 1; i > 0; --i) {
+            if (less_than(v[i], v[i - 1])) {
+                const Pair t = v[i];
+                v[i] = v[i - 1];
+                v[i - 1] = t;
+            }
+        }
+    }
+    __device__ void pop() {
+#pragma unroll
+        for (int i = 0; i + 1 < K; ++i) v[i] = v[i + 1];
+        v[K - 1] = Pair{kNone, kNone};
+    }
+};
+
+// The K least pairs over all lanes of the block, in order, into res[] of thread 0
+// (every lane of wave 0 holds them).  Rows are unique, so the lane whose head
+// equals the wave minimum is the one that pops.
+template <int K>
+__device__ inline void block_topk(TopList<K> &l, Pair (*s_pairs)[K], Pair *res) {
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+#pragma unroll
+    for (int r = 0; r < K; ++r) {
+        const Pair w = wave_min(l.v[0]);
+        if (w.idx != kNone && l.v[0].idx == w.idx && l.v[0].key == w.key) l.pop();
+        if (lane == 0) s_pairs[wave][r] = w;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        Pair c = lane < kWaves * K ? s_pairs[lane / K][lane % K] : Pair{kNone, kNone};
+#pragma unroll
+        for (int r = 0; r < K; ++r) {
+            const Pair w = wave_min(c);
+            if (w.idx != kNone && c.idx == w.idx && c.key == w.key) c = Pair{kNone, kNone};
+            res[r] = w;
+        }
+    }
+}
+
+// Workspace: part_key[B*K], part_idx[B*K], part_cnt[B].
+struct Top1Ws {
+    uint64_t *key, *idx, *cnt;
+};
+Top1Ws top1_ws(void *ws) {
+    Top1Ws w;
+    w.key = (uint64_t *)ws;
+    w.idx = w.key + (size_t)kSelBlocks * GUIDE_MAX_TOPK;
+    w.cnt = w.idx + (size_t)kSelBlocks * GUIDE_MAX_TOPK;
+    return w;
+}
+size_t top1_ws_bytes() { return sizeof(uint64_t) * ((size_t)kSelBlocks * (2 * GUIDE_MAX_TOPK + 1)); }
+
+// One pass over the rows: every lane keeps its K best, the block merges them.
+template <int K>
+__global__ __launch_bounds__(kBlock) void topk_pass_kernel(const double *__restrict__ obj, RowFilter f, uint32_t n,
+                                                           Top1Ws w) {
+    __shared__ Pair s_pairs[kWaves][K];
+    __shared__ uint64_t s_cnt[kWaves];
+    TopList<K> l;
+    l.init();
+    uint64_t cnt = 0;
+    const uint32_t per = rows_per_block(n);
+    const uint64_t begin = (uint64_t)blockIdx.x * per;
+    for (uint64_t base = begin + threadIdx.x; base < begin + per && base < n; base += kBlock * kUnroll) {
+        Row r[kUnroll];
+#pragma unroll
+        for (uint32_t u = 0; u < kUnroll; ++u) r[u] = load_row<false>(obj, nullptr, f, (uint32_t)base + u * kBlock, n);
+#pragma unroll
+        for (uint32_t u = 0; u < kUnroll; ++u) {
+            if (r[u].pass) {
+                ++cnt;
+                l.insert(Pair{key_of(r[u].x), (uint32_t)base + u * kBlock});
+            }
+        }
+    }
+    for (int off = kWave / 2; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, kWave);
+    if (threadIdx.x % kWave == 0) s_cnt[threadIdx.x / kWave] = cnt;
+    Pair res[K];
+    block_topk<K>(l, s_pairs, res);
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int r = 0; r < K; ++r) {
+            w.key[(size_t)blockIdx.x * K + r] = res[r].key;
+            w.idx[(size_t)blockIdx.x * K + r] = res[r].idx;
+        }
+        uint64_t c = 0;
+        for (int wv = 0; wv < kWaves; ++wv) c += s_cnt[wv];
+        w.cnt[blockIdx.x] = c;
+    }
+}
+
+// One block: the K least of the block partials, and the total count.
+template <int K>
+__global__ __launch_bounds__(kBlock) void topk_merge_kernel(Top1Ws w, uint32_t n_blocks, uint32_t k, uint64_t *out_idx,
+                                                            double *out_val, uint64_t *out_cnt) {
+    __shared__ Pair s_pairs[kWaves][K];
+    __shared__ uint64_t s_cnt[kWaves];
+    constexpr uint32_t kPer = kSelBlocks * K / kBlock;       // all loads first: one memory latency
+    Pair c[kPer];
+#pragma unroll
+    for (uint32_t q = 0; q < kPer; ++q) {
+        const uint32_t i = q * kBlock + threadIdx.x;
+        c[q] = i < n_blocks * K ? Pair{w.key[i], w.idx[i]} : Pair{kNone, kNone};
+    }
+    uint64_t pc[kSelBlocks / kBlock];
+#pragma unroll
+    for (uint32_t q = 0; q < kSelBlocks / kBlock; ++q) {
+        const uint32_t i = q * kBlock + threadIdx.x;
+        pc[q] = i < n_blocks ? w.cnt[i] : 0;
+    }
+    TopList<K> l;
+    l.init();
+    uint64_t cnt = 0;
+#pragma unroll
+    for (uint32_t q = 0; q < kPer; ++q) l.insert(c[q]);
+#pragma unroll
+    for (uint32_t q = 0; q < kSelBlocks / kBlock; ++q) cnt += pc[q];
+    for (int off = kWave / 2; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, kWave);
+    if (threadIdx.x % kWave == 0) s_cnt[threadIdx.x / kWave] = cnt;
+    Pair res[K];
+    block_topk<K>(l, s_pairs, res);
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int r = 0; r < K; ++r) {
+            if ((uint32_t)r < k) {
+                out_idx[r] = res[r].idx;
+                out_val[r] = res[r].idx == kNone ? INFINITY : value_of(res[r].key);
+            }
+        }
+        uint64_t t = 0;
+        for (int wv = 0; wv < kWaves; ++wv) t += s_cnt[wv];
+        out_cnt[0] = t;
+    }
+}
+
+// ------------------------------------------------------- top-k, with groups
 
 // Workspace layout (u64 units): after_key[G], after_idx[G], part_key[B*G], part_idx[B*G], part_cnt[B*G].
 struct TopkWs {
@@ -65,27 +274,20 @@ TopkWs topk_ws(void *ws, uint32_t G) {
 size_t topk_ws_bytes(uint32_t G) { return sizeof(uint64_t) * (2 * GUIDE_MAX_GROUPS + 3 * (size_t)kSelBlocks * G); }
 
 // One round: per block and group, the least (key, row) pair strictly after the
-// group's previous pick; round 0 also counts passing rows.
-// Grouped candidates meet in per-wave LDS slots.  A wave's LDS operations
-// execute in program order for all its lanes, so: read the slot, atomic-min the
-// key, read back; lanes that hold the new minimum reset the row slot when the
-// minimum strictly improved and then atomic-min their row into it.
-template <bool GROUPED>
+// group's previous pick; round 0 also counts passing rows.  Candidates of one
+// group meet in per-wave LDS slots (slot_update).
 __global__ __launch_bounds__(kBlock) void topk_round_kernel(const double *__restrict__ obj, RowFilter f,
                                                             const uint32_t *__restrict__ group, uint32_t G,
                                                             uint32_t n, uint32_t round, TopkWs w) {
-    constexpr int kWaves = kBlock / kWave;
     __shared__ uint64_t s_key[kWaves][GUIDE_MAX_GROUPS], s_idx[kWaves][GUIDE_MAX_GROUPS];
     __shared__ uint32_t s_cnt[kWaves][GUIDE_MAX_GROUPS];
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int wave = threadIdx.x / kWave;
     for (uint32_t i = threadIdx.x; i < kWaves * GUIDE_MAX_GROUPS; i += kBlock) {
         (&s_key[0][0])[i] = kNone;
         (&s_idx[0][0])[i] = kNone;
         (&s_cnt[0][0])[i] = 0;
     }
     __syncthreads();
-    Pair best = {kNone, kNone};
-    uint32_t cnt = 0;
     // every lane of a wave runs the same number of iterations (uniform trip count)
     const uint32_t stride = gridDim.x * kBlock;
     const uint32_t iters = (n + stride - 1) / stride;
@@ -96,37 +298,20 @@ __global__ __launch_bounds__(kBlock) void topk_round_kernel(const double *__rest
         uint32_t g = 0;
         if (ok) {
             x = obj[i];
-            ok = (x == x) && row_passes(f, i);
-            if (GROUPED) {
-                g = group[i];
-                ok = ok && g < G;
-            }
+            g = group[i];
+            ok = (x == x) && g < G && row_passes(f, i);
         }
         Pair p = {kNone, kNone};
         if (ok) {
             p.key = key_of(x);
             p.idx = i;
+            if (round == 0) atomicAdd(&s_cnt[wave][g], 1u);
             if (round > 0) {
                 const Pair after = {w.after_key[g], w.after_idx[g]};
                 ok = less_than(after, p);
             }
         }
-        if (!GROUPED) {
-            if (ok) best = pair_min(best, p);
-            if (round == 0 && p.idx != kNone) ++cnt;
-        } else {
-            if (round == 0 && p.idx != kNone) atomicAdd(&s_cnt[wave][g], 1u);
-            slot_update(s_key[wave], s_idx[wave], g, ok, p);
-        }
-    }
-    if (!GROUPED) {
-        best = wave_min(best);
-        for (int off = kWave / 2; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, kWave);
-        if (lane == 0) {
-            s_key[wave][0] = best.key;
-            s_idx[wave][0] = best.idx;
-            s_cnt[wave][0] = cnt;
-        }
+        slot_update(s_key[wave], s_idx[wave], g, ok, p);
     }
     __syncthreads();
     for (uint32_t g = threadIdx.x; g < G; g += kBlock) {
@@ -147,7 +332,7 @@ __global__ __launch_bounds__(kBlock) void topk_round_kernel(const double *__rest
 __global__ __launch_bounds__(kBlock) void topk_final_kernel(TopkWs w, uint32_t G, uint32_t n_blocks, uint32_t round,
                                                             uint32_t k, uint64_t *out_idx, double *out_val,
                                                             uint64_t *out_cnt) {
-    __shared__ uint64_t s_key[kBlock / kWave], s_idx[kBlock / kWave], s_cnt[kBlock / kWave];
+    __shared__ uint64_t s_key[kWaves], s_idx[kWaves], s_cnt[kWaves];
     const uint32_t g = blockIdx.x;
     Pair best = {kNone, kNone};
     uint64_t cnt = 0;
@@ -165,7 +350,7 @@ __global__ __launch_bounds__(kBlock) void topk_final_kernel(TopkWs w, uint32_t G
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        for (int wv = 1; wv < kBlock / kWave; ++wv) {
+        for (int wv = 1; wv < kWaves; ++wv) {
             const Pair o = {s_key[wv], s_idx[wv]};
             best = pair_min(best, o);
             cnt += s_cnt[wv];
@@ -181,280 +366,461 @@ __global__ __launch_bounds__(kBlock) void topk_final_kernel(TopkWs w, uint32_t G
 }
 
 // --------------------------------------------------------------------- Pareto
+//
+// Four launches.
+// Prepare: a strided sample of rows fixes the stretch of x that the bins slice.
+// Staircase: every block builds in LDS the least y per x-bin over its rows (kBins
+// equal slices of that stretch, clamped at both ends, so a lower bin means a
+// strictly smaller x) and merges it into the global table with atomic-min.
+// Survivors: a row survives when its y beats every row of every strictly lower
+// bin (exclusive prefix-min of the table) -- only survivors of its own bin can
+// still dominate it.  Survivors are appended as (row, keys).
+// Finish (one block): survivors are grouped by bin, tested exactly inside their
+// bin, and front members are written at (front members of lower bins) + (rank
+// inside the bin), which orders the output by (x, y, row).
 
-constexpr uint32_t kBins = 1u << 16;
+constexpr uint32_t kStage = 4096;        // survivors whose records the finishing block holds in LDS
+constexpr uint32_t kFinishThreads = 1024;
 
-// Workspace of the Pareto path.
+// Caller workspace of the Pareto path.
 struct ParetoWs {
-    uint64_t *range;      // [2]: min key, max key of x over passing rows
-    uint64_t *bin_min;    // [kBins]: least y key per x bin
-    uint64_t *bin_lower;  // [kBins]: least y key over strictly lower bins
-    uint32_t *bin_cnt;    // [kBins]: survivors per bin
-    uint32_t *bin_off;    // [kBins + 1]
-    uint32_t *bin_cur;    // [kBins]: scatter cursors
-    uint32_t *bin_front;  // [kBins]: front members per bin
-    uint32_t *bin_foff;   // [kBins + 1]
-    uint32_t *counters;   // [4]: survivors, front size
+    uint64_t *skx, *sky;  // [n]: keys of surviving rows
     uint32_t *surv;       // [n]: surviving rows, arbitrary order
-    uint32_t *grouped;    // [n]: surviving rows grouped by bin
-    uint8_t *on_front;    // [n]: flag per grouped survivor
+    uint32_t *grouped;    // [n]: positions into surv, grouped by bin (large-front path)
+    uint8_t *on_front;    // [n]: flag per grouped survivor (large-front path)
 };
-size_t pareto_ws_bytes(uint64_t n) {
-    size_t b = sizeof(uint64_t) * (2 + 2 * (size_t)kBins) + sizeof(uint32_t) * (5 * (size_t)kBins + 2 + 4);
-    b += sizeof(uint32_t) * 2 * n + n;
-    return b + 256;
-}
+size_t pareto_ws_bytes(uint64_t n) { return (size_t)n * (8 + 8 + 4 + 4 + 1) + 256; }
 ParetoWs pareto_ws(void *ws, uint64_t n) {
     ParetoWs w;
-    uint64_t *p = (uint64_t *)ws;
-    w.range = p; p += 2;
-    w.bin_min = p; p += kBins;
-    w.bin_lower = p; p += kBins;
-    uint32_t *q = (uint32_t *)p;
-    w.bin_cnt = q; q += kBins;
-    w.bin_off = q; q += kBins + 1;
-    w.bin_cur = q; q += kBins;
-    w.bin_front = q; q += kBins;
-    w.bin_foff = q; q += kBins + 1;
-    w.counters = q; q += 4;
-    w.surv = q; q += n;
-    w.grouped = q; q += n;
-    w.on_front = (uint8_t *)q;
+    w.skx = (uint64_t *)ws;
+    w.sky = w.skx + n;
+    w.surv = (uint32_t *)(w.sky + n);
+    w.grouped = w.surv + n;
+    w.on_front = (uint8_t *)(w.grouped + n);
     return w;
 }
 
-__global__ __launch_bounds__(kBlock) void pareto_init_kernel(ParetoWs w) {
-    const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
-    if (i < kBins) {
-        w.bin_min[i] = kNone;
-        w.bin_cnt[i] = 0;
-        w.bin_cur[i] = 0;
-        w.bin_front[i] = 0;
+struct Binning {
+    uint64_t lo;
+    uint32_t shift;
+    __device__ uint32_t operator()(uint64_t kx) const {
+        if (kx <= lo) return 0;
+        const uint64_t b = (kx - lo) >> shift;
+        return b < kBins ? (uint32_t)b : kBins - 1;
     }
-    if (i == 0) {
-        w.range[0] = kNone;
-        w.range[1] = 0;
-    }
-    if (i < 4) w.counters[i] = 0;
-}
-
-__device__ inline bool pareto_row(const double *x, const double *y, const RowFilter &f, uint32_t i, uint64_t *kx,
-                                  uint64_t *ky) {
-    const double xv = x[i], yv = y[i];
-    if (!(xv == xv) || !(yv == yv) || !row_passes(f, i)) return false;
-    *kx = key_of(xv);
-    *ky = key_of(yv);
-    return true;
-}
-
-__global__ __launch_bounds__(kBlock) void pareto_range_kernel(const double *__restrict__ x, const double *__restrict__ y,
-                                                              RowFilter f, uint32_t n, ParetoWs w) {
-    uint64_t lo = kNone, hi = 0;
-    for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < n; i += gridDim.x * kBlock) {
-        uint64_t kx, ky;
-        if (pareto_row(x, y, f, i, &kx, &ky)) {
-            lo = kx < lo ? kx : lo;
-            hi = kx > hi ? kx : hi;
-        }
-    }
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-        const uint64_t ol = __shfl_xor(lo, off, kWave), oh = __shfl_xor(hi, off, kWave);
-        lo = ol < lo ? ol : lo;
-        hi = oh > hi ? oh : hi;
-    }
-    if (threadIdx.x % kWave == 0 && lo != kNone) {
-        atomicMin((unsigned long long *)&w.range[0], (unsigned long long)lo);
-        atomicMax((unsigned long long *)&w.range[1], (unsigned long long)hi);
-    }
-}
-
-// Bins are equal slices of the key range of x, so a lower bin means a strictly smaller x.
-__device__ inline uint32_t bin_of(uint64_t kx, uint64_t lo, uint32_t shift) { return (uint32_t)((kx - lo) >> shift); }
-__device__ inline uint32_t shift_of(uint64_t lo, uint64_t hi) {
+};
+__device__ inline Binning binning_of(uint64_t lo, uint64_t hi) {
+    Binning b;
+    b.lo = lo;
     const uint64_t span = hi - lo;
     uint32_t s = 0;
-    while (s < 64 && (span >> s) >= kBins) ++s;
-    return s;
+    while (s < 63 && (span >> s) >= kBins) ++s;
+    b.shift = s;
+    return b;
 }
 
-__global__ __launch_bounds__(kBlock) void pareto_binmin_kernel(const double *__restrict__ x, const double *__restrict__ y,
-                                                               RowFilter f, uint32_t n, ParetoWs w) {
-    const uint64_t lo = w.range[0], hi = w.range[1];
-    if (lo == kNone) return;
-    const uint32_t shift = shift_of(lo, hi);
-    for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < n; i += gridDim.x * kBlock) {
-        uint64_t kx, ky;
-        if (!pareto_row(x, y, f, i, &kx, &ky)) continue;
-        const uint32_t b = bin_of(kx, lo, shift);
-        // the stored minimum only decreases, so a stale read can only let an extra atomic through
-        if (ky < __hip_atomic_load(&w.bin_min[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
-            atomicMin((unsigned long long *)&w.bin_min[b], (unsigned long long)ky);
+// Range that the bins slice, from a strided sample of rows: low end = least x of
+// passing sample rows, high end = x of the sample row with the least y (rows
+// beyond it are dominated by that row unless their y is smaller still; they share
+// the last bin).  Any monotone binning is correct -- the sample only decides how
+// finely the interesting stretch of x is resolved.
+constexpr uint32_t kSampleBlocks = 64;
+__global__ __launch_bounds__(kBlock) void pareto_prepare_kernel(const double *__restrict__ x,
+                                                                const double *__restrict__ y, RowFilter f, uint32_t n,
+                                                                SelectScratch *sc) {
+    __shared__ uint64_t s_lo[kWaves];
+    __shared__ Pair s_best[kWaves];
+    const uint32_t k = blockIdx.x * kBlock + threadIdx.x;           // sample number
+    const uint32_t n_samples = kSampleBlocks * kBlock;
+    const uint32_t stride = n > n_samples ? n / n_samples : 1;
+    const Row r = load_row<true>(x, y, f, (uint64_t)k * stride < n ? k * stride : n, n);
+    uint64_t lo = kNone;
+    Pair best = {kNone, kNone};                                     // (y key, x key) of the least y
+    if (r.pass) {
+        lo = key_of(r.x);
+        best = Pair{key_of(r.y), lo};
     }
-}
-
-// Exclusive prefix (min of bin_min, sum of a count array) over the bins, one block.
-__global__ __launch_bounds__(1024) void pareto_scan_min_kernel(ParetoWs w) {
-    __shared__ uint64_t s[1024];
-    constexpr uint32_t per = kBins / 1024;
-    const uint32_t t = threadIdx.x;
-    uint64_t m = kNone;
-    for (uint32_t j = 0; j < per; ++j) {
-        const uint64_t v = w.bin_min[t * per + j];
-        m = v < m ? v : m;
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        const uint64_t ol = __shfl_xor(lo, off, kWave);
+        lo = ol < lo ? ol : lo;
     }
-    s[t] = m;
+    best = wave_min(best);
+    if (threadIdx.x % kWave == 0) {
+        s_lo[threadIdx.x / kWave] = lo;
+        s_best[threadIdx.x / kWave] = best;
+    }
     __syncthreads();
-    for (uint32_t off = 1; off < 1024; off <<= 1) {
-        const uint64_t o = t >= off ? s[t - off] : kNone;
-        __syncthreads();
-        s[t] = o < s[t] ? o : s[t];
-        __syncthreads();
-    }
-    uint64_t run = t > 0 ? s[t - 1] : kNone;
-    for (uint32_t j = 0; j < per; ++j) {
-        w.bin_lower[t * per + j] = run;
-        const uint64_t v = w.bin_min[t * per + j];
-        run = v < run ? v : run;
+    if (threadIdx.x == 0) {
+        for (int wv = 1; wv < kWaves; ++wv) {
+            lo = s_lo[wv] < lo ? s_lo[wv] : lo;
+            best = pair_min(best, s_best[wv]);
+        }
+        sc->sample_lo[blockIdx.x] = lo;
+        sc->sample_best[blockIdx.x] = best;
     }
 }
 
-__global__ __launch_bounds__(1024) void scan_sum_kernel(const uint32_t *__restrict__ cnt, uint32_t *__restrict__ off) {
-    __shared__ uint32_t s[1024];
-    constexpr uint32_t per = kBins / 1024;
-    const uint32_t t = threadIdx.x;
-    uint32_t m = 0;
-    for (uint32_t j = 0; j < per; ++j) m += cnt[t * per + j];
-    s[t] = m;
+// Combines the per-block sample partials (the same result in every block): the
+// first wave loads one partial per lane and reduces; s_rng (2 entries) carries
+// the result to the other waves.  Contains a block barrier.
+__device__ inline Binning sampled_binning(const SelectScratch *sc, uint64_t *s_rng) {
+    if (threadIdx.x < kWave) {
+        static_assert(kSampleBlocks == kWave, "one sample partial per lane");
+        uint64_t lo = sc->sample_lo[threadIdx.x];
+        Pair best = sc->sample_best[threadIdx.x];
+        for (int off = kWave / 2; off > 0; off >>= 1) {
+            const uint64_t ol = __shfl_xor(lo, off, kWave);
+            lo = ol < lo ? ol : lo;
+        }
+        best = wave_min(best);
+        uint64_t hi = best.idx;
+        if (lo == kNone || hi < lo) {   // no passing sample row: one slice per 2^52 keys
+            lo = 0;
+            hi = kNone;
+        }
+        if (threadIdx.x == 0) {
+            s_rng[0] = lo;
+            s_rng[1] = hi;
+        }
+    }
     __syncthreads();
-    for (uint32_t o = 1; o < 1024; o <<= 1) {
-        const uint32_t v = t >= o ? s[t - o] : 0;
-        __syncthreads();
-        s[t] += v;
-        __syncthreads();
-    }
-    uint32_t run = t > 0 ? s[t - 1] : 0;
-    for (uint32_t j = 0; j < per; ++j) {
-        off[t * per + j] = run;
-        run += cnt[t * per + j];
-    }
-    if (t == 1023) off[kBins] = run;
+    return binning_of(s_rng[0], s_rng[1]);
 }
 
-// A row survives when its y beats every row of every strictly lower bin; only
-// survivors of its own bin can still dominate it.
+// Exclusive prefix-min over a kBins-entry table in LDS by the NT threads of the
+// block (thread t owns kBins / NT consecutive entries): serial in the thread,
+// shuffle scan in the wave, wave totals through LDS.  s_tmp: NT / kWave entries.
+template <uint32_t NT>
+__device__ inline void scan_min_excl(uint64_t *s_io, uint64_t *s_tmp) {
+    constexpr uint32_t per = kBins / NT, nw = NT / kWave;
+    const uint32_t t = threadIdx.x, lane = t % kWave, wave = t / kWave;
+    uint64_t v[per], m = kNone;
+#pragma unroll
+    for (uint32_t j = 0; j < per; ++j) {
+        v[j] = s_io[t * per + j];
+        m = v[j] < m ? v[j] : m;
+    }
+    uint64_t inc = m;                                   // inclusive scan of thread minima in the wave
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const uint64_t o = __shfl_up(inc, off, kWave);
+        if ((int)lane >= off) inc = o < inc ? o : inc;
+    }
+    if (lane == kWave - 1) s_tmp[wave] = inc;
+    uint64_t run = __shfl_up(inc, 1, kWave);            // exclusive within the wave
+    if (lane == 0) run = kNone;
+    __syncthreads();
+    for (uint32_t wv = 0; wv < nw; ++wv)
+        if (wv < wave) run = s_tmp[wv] < run ? s_tmp[wv] : run;
+#pragma unroll
+    for (uint32_t j = 0; j < per; ++j) {
+        s_io[t * per + j] = run;
+        run = v[j] < run ? v[j] : run;
+    }
+    __syncthreads();
+}
+
+// Exclusive prefix-sum over a kBins-entry table (LDS or global), in place, by the
+// NT threads of the block (io[kBins] receives the total).  s_tmp: NT / kWave entries.
+template <uint32_t NT>
+__device__ inline void scan_sum_excl(uint32_t *io, uint32_t *s_tmp) {
+    constexpr uint32_t per = kBins / NT, nw = NT / kWave;
+    const uint32_t t = threadIdx.x, lane = t % kWave, wave = t / kWave;
+    uint32_t v[per], m = 0;
+#pragma unroll
+    for (uint32_t j = 0; j < per; ++j) {
+        v[j] = io[t * per + j];
+        m += v[j];
+    }
+    uint32_t inc = m;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const uint32_t o = __shfl_up(inc, off, kWave);
+        if ((int)lane >= off) inc += o;
+    }
+    if (lane == kWave - 1) s_tmp[wave] = inc;
+    uint32_t run = inc - m;
+    __syncthreads();
+    uint32_t total = 0;
+    for (uint32_t wv = 0; wv < nw; ++wv) {
+        if (wv < wave) run += s_tmp[wv];
+        total += s_tmp[wv];
+    }
+#pragma unroll
+    for (uint32_t j = 0; j < per; ++j) {
+        io[t * per + j] = run;
+        run += v[j];
+    }
+    if (t == 0) io[kBins] = total;
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__restrict__ x, const double *__restrict__ y,
+                                                              RowFilter f, uint32_t n, SelectScratch *sc) {
+    __shared__ uint64_t s_min[kBins], s_rng[2];
+    const Binning bin = sampled_binning(sc, s_rng);
+    for (uint32_t i = threadIdx.x; i < kBins; i += kBlock) s_min[i] = kNone;
+    __syncthreads();
+    const uint32_t per = rows_per_block(n);
+    const uint64_t begin = (uint64_t)blockIdx.x * per;
+    for (uint64_t base = begin + threadIdx.x; base < begin + per && base < n; base += kBlock * kUnroll) {
+        Row r[kUnroll];
+#pragma unroll
+        for (uint32_t u = 0; u < kUnroll; ++u) r[u] = load_row<true>(x, y, f, (uint32_t)base + u * kBlock, n);
+#pragma unroll
+        for (uint32_t u = 0; u < kUnroll; ++u) {
+            if (!r[u].pass) continue;
+            const uint32_t b = bin(key_of(r[u].x));
+            const uint64_t ky = key_of(r[u].y);
+            // the slot only decreases, so a stale read can only let an extra atomic through
+            if (ky < s_min[b]) atomicMin((unsigned long long *)&s_min[b], (unsigned long long)ky);
+        }
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < kBins; i += kBlock) {
+        const uint64_t v = s_min[i];
+        // the global slot only decreases: a stale read can only let an extra atomic through
+        if (v != kNone && v < __hip_atomic_load(&sc->bin_min[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+            atomicMin((unsigned long long *)&sc->bin_min[i], (unsigned long long)v);
+    }
+}
+
 __global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *__restrict__ x,
                                                                   const double *__restrict__ y, RowFilter f, uint32_t n,
-                                                                  ParetoWs w) {
-    const uint64_t lo = w.range[0], hi = w.range[1];
-    if (lo == kNone) return;
-    const uint32_t shift = shift_of(lo, hi);
-    const uint32_t stride = gridDim.x * kBlock;
-    const uint32_t iters = (n + stride - 1) / stride;
-    for (uint32_t it = 0; it < iters; ++it) {
-        const uint32_t i = it * stride + blockIdx.x * kBlock + threadIdx.x;
-        uint64_t kx, ky;
-        bool keep = false;
-        uint32_t b = 0;
-        if (i < n && pareto_row(x, y, f, i, &kx, &ky)) {
-            b = bin_of(kx, lo, shift);
-            keep = ky < w.bin_lower[b];
-        }
-        // wave-aggregated append
-        const uint64_t mask = __ballot(keep);
-        if (mask) {
-            const int lane = threadIdx.x % kWave;
-            const int leader = __ffsll((long long)mask) - 1;
-            uint32_t base = 0;
-            if (lane == leader) base = atomicAdd(&w.counters[0], (uint32_t)__popcll(mask));
-            base = __shfl(base, leader, kWave);
-            if (keep) {
-                w.surv[base + __popcll(mask & ((1ull << lane) - 1))] = i;
-                atomicAdd(&w.bin_cnt[b], 1u);
+                                                                  ParetoWs w, SelectScratch *sc) {
+    __shared__ uint64_t s_lower[kBins], s_tmp[kWaves], s_rng[2];
+    const Binning bin = sampled_binning(sc, s_rng);
+    for (uint32_t i = threadIdx.x; i < kBins; i += kBlock) s_lower[i] = sc->bin_min[i];
+    __syncthreads();
+    scan_min_excl<kBlock>(s_lower, s_tmp);              // least y over strictly lower bins
+    const int lane = threadIdx.x % kWave;
+    const uint32_t per = rows_per_block(n);
+    const uint64_t begin = (uint64_t)blockIdx.x * per;
+    // wave-uniform trip count: the ballots below need every lane
+    for (uint64_t base = begin; base < begin + per && base < n; base += kBlock * kUnroll) {
+        Row r[kUnroll];
+#pragma unroll
+        for (uint32_t u = 0; u < kUnroll; ++u)
+            r[u] = load_row<true>(x, y, f, (uint32_t)base + threadIdx.x + u * kBlock, n);
+#pragma unroll
+        for (uint32_t u = 0; u < kUnroll; ++u) {
+            const uint32_t i = (uint32_t)base + threadIdx.x + u * kBlock;
+            uint32_t b = 0;
+            uint64_t kx = 0, ky = 0;
+            bool keep = false;
+            if (r[u].pass) {
+                kx = key_of(r[u].x);
+                ky = key_of(r[u].y);
+                b = bin(kx);
+                keep = ky < s_lower[b];
+            }
+            const uint64_t mask = __ballot(keep);       // wave-aggregated append
+            if (mask) {
+                const int leader = __ffsll((long long)mask) - 1;
+                uint32_t at = 0;
+                if (lane == leader) at = atomicAdd(&sc->counters[0], (uint32_t)__popcll(mask));
+                at = __shfl(at, leader, kWave) + __popcll(mask & ((1ull << lane) - 1));
+                if (keep) {
+                    w.surv[at] = i;
+                    w.skx[at] = kx;
+                    w.sky[at] = ky;
+                    atomicAdd(&sc->bin_cnt[b], 1u);
+                }
             }
         }
     }
 }
 
-__global__ __launch_bounds__(kBlock) void pareto_group_kernel(const double *__restrict__ x, ParetoWs w) {
-    const uint32_t m = w.counters[0];
-    const uint64_t lo = w.range[0], hi = w.range[1];
-    const uint32_t shift = shift_of(lo, hi);
-    for (uint32_t s = blockIdx.x * kBlock + threadIdx.x; s < m; s += gridDim.x * kBlock) {
-        const uint32_t i = w.surv[s];
-        const uint32_t b = bin_of(key_of(x[i]), lo, shift);
-        w.grouped[w.bin_off[b] + atomicAdd(&w.bin_cur[b], 1u)] = i;
-    }
-}
-
-// Exact dominance test against the survivors of the same bin.
-__global__ __launch_bounds__(kBlock) void pareto_mark_kernel(const double *__restrict__ x, const double *__restrict__ y,
-                                                             ParetoWs w) {
-    const uint32_t m = w.counters[0];
-    const uint64_t lo = w.range[0], hi = w.range[1];
-    const uint32_t shift = shift_of(lo, hi);
-    for (uint32_t s = blockIdx.x * kBlock + threadIdx.x; s < m; s += gridDim.x * kBlock) {
-        const uint32_t i = w.grouped[s];
-        const uint64_t kx = key_of(x[i]), ky = key_of(y[i]);
-        const uint32_t b = bin_of(kx, lo, shift);
-        bool dominated = false;
-        for (uint32_t t = w.bin_off[b]; t < w.bin_off[b + 1] && !dominated; ++t) {
-            const uint32_t j = w.grouped[t];
-            const uint64_t jx = key_of(x[j]), jy = key_of(y[j]);
-            dominated = jx <= kx && jy <= ky && (jx < kx || jy < ky);
+__global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs w, SelectScratch *sc, uint64_t *out_idx,
+                                                                        uint64_t capacity, uint64_t *out_count) {
+    __shared__ uint32_t s_off[kBins + 1], s_foff[kBins + 1], s_cur[kBins], s_tmp[kFinishThreads / kWave];
+    __shared__ uint64_t s_kx[kStage], s_ky[kStage];
+    __shared__ uint32_t s_row[kStage];
+    __shared__ uint16_t s_bin[kStage];
+    __shared__ uint8_t s_flag[kStage];
+    const uint32_t t = threadIdx.x;
+    __shared__ uint64_t s_rng[2];
+    const uint32_t m = sc->counters[0];
+    const Binning bin = sampled_binning(sc, s_rng);
+    if (m <= kStage) {
+        // records staged in LDS, grouped by bin
+        for (uint32_t i = t; i < kBins; i += kFinishThreads) {
+            s_off[i] = sc->bin_cnt[i];
+            s_cur[i] = 0;
+            s_foff[i] = 0;
         }
-        w.on_front[s] = dominated ? 0 : 1;
-        if (!dominated) atomicAdd(&w.bin_front[b], 1u);
-    }
-}
-
-// Position of a front member = front members of lower bins + members of its own
-// bin that precede it in (x, y, row) order.
-__global__ __launch_bounds__(kBlock) void pareto_emit_kernel(const double *__restrict__ x, const double *__restrict__ y,
-                                                             ParetoWs w, uint64_t *out_idx, uint64_t capacity,
-                                                             uint64_t *out_count) {
-    const uint32_t m = w.counters[0];
-    const uint64_t lo = w.range[0], hi = w.range[1];
-    const uint32_t shift = shift_of(lo, hi);
-    if (blockIdx.x == 0 && threadIdx.x == 0) out_count[0] = lo == kNone ? 0 : w.bin_foff[kBins];
-    for (uint32_t s = blockIdx.x * kBlock + threadIdx.x; s < m; s += gridDim.x * kBlock) {
-        if (!w.on_front[s]) continue;
-        const uint32_t i = w.grouped[s];
-        const uint64_t kx = key_of(x[i]), ky = key_of(y[i]);
-        const uint32_t b = bin_of(kx, lo, shift);
-        uint32_t rank = 0;
-        for (uint32_t t = w.bin_off[b]; t < w.bin_off[b + 1]; ++t) {
-            if (!w.on_front[t]) continue;
-            const uint32_t j = w.grouped[t];
-            const uint64_t jx = key_of(x[j]), jy = key_of(y[j]);
-            if (jx < kx || (jx == kx && (jy < ky || (jy == ky && j < i)))) ++rank;
+        constexpr uint32_t kPer = kStage / kFinishThreads;
+        uint64_t rx[kPer], ry[kPer];
+        uint32_t rr[kPer];
+#pragma unroll
+        for (uint32_t q = 0; q < kPer; ++q) {           // all loads first: one memory latency
+            const uint32_t j = q * kFinishThreads + t;
+            rx[q] = j < m ? w.skx[j] : 0;
+            ry[q] = j < m ? w.sky[j] : 0;
+            rr[q] = j < m ? w.surv[j] : 0;
         }
-        const uint64_t pos = (uint64_t)w.bin_foff[b] + rank;
-        if (pos < capacity) out_idx[pos] = i;
+        __syncthreads();
+        scan_sum_excl<kFinishThreads>(s_off, s_tmp);
+#pragma unroll
+        for (uint32_t q = 0; q < kPer; ++q) {
+            if (q * kFinishThreads + t < m) {
+                const uint32_t b = bin(rx[q]);
+                const uint32_t pos = s_off[b] + atomicAdd(&s_cur[b], 1u);
+                s_kx[pos] = rx[q]; s_ky[pos] = ry[q]; s_row[pos] = rr[q]; s_bin[pos] = (uint16_t)b;
+            }
+        }
+        __syncthreads();
+        // eight lanes per survivor: they share out the survivors of its bin and
+        // meet through a wave ballot (each survivor's chain of dependent LDS reads
+        // is long, so many survivors are kept in flight)
+        constexpr uint32_t kGroup = 8;
+        const uint32_t lane = t % kWave, sub = lane % kGroup, shift = lane - sub;
+        const uint32_t q_step = kFinishThreads / kGroup;
+        const uint32_t m_pad = (m + q_step - 1) / q_step * q_step;   // wave-uniform trip count for the ballots
+        for (uint32_t q = t / kGroup; q < m_pad; q += q_step) {
+            const bool live = q < m;
+            const uint64_t kx = live ? s_kx[q] : 0, ky = live ? s_ky[q] : 0;
+            const uint32_t b = live ? s_bin[q] : 0;
+            const uint32_t beg = live ? s_off[b] : 0, end = live ? s_off[b + 1] : 0;
+            uint32_t len = end - beg;
+            for (int off = kWave / 2; off > 0; off >>= 1) {          // longest bin in the wave
+                const uint32_t o = __shfl_xor(len, off, kWave);
+                len = o > len ? o : len;
+            }
+            bool dom = false;
+            for (uint32_t j0 = 0; j0 < len; j0 += kGroup) {
+                const uint32_t j = beg + j0 + sub;
+                if (j < end) dom = dom || (s_kx[j] <= kx && s_ky[j] <= ky && (s_kx[j] < kx || s_ky[j] < ky));
+            }
+            const bool dominated = ((__ballot(dom) >> shift) & ((1u << kGroup) - 1)) != 0;
+            if (live && sub == 0) {
+                s_flag[q] = dominated ? 0 : 1;
+                if (!dominated) atomicAdd(&s_foff[b], 1u);
+            }
+        }
+        __syncthreads();
+        scan_sum_excl<kFinishThreads>(s_foff, s_tmp);
+        if (t == 0) out_count[0] = s_foff[kBins];
+        for (uint32_t q = t / kGroup; q < m_pad; q += q_step) {
+            const bool live = q < m && s_flag[q];
+            const uint64_t kx = live ? s_kx[q] : 0, ky = live ? s_ky[q] : 0;
+            const uint32_t b = live ? s_bin[q] : 0, i = live ? s_row[q] : 0;
+            const uint32_t beg = live ? s_off[b] : 0, end = live ? s_off[b + 1] : 0;
+            uint32_t len = end - beg;
+            for (int off = kWave / 2; off > 0; off >>= 1) {
+                const uint32_t o = __shfl_xor(len, off, kWave);
+                len = o > len ? o : len;
+            }
+            uint32_t rank = 0;
+            for (uint32_t j0 = 0; j0 < len; j0 += kGroup) {
+                const uint32_t j = beg + j0 + sub;
+                bool before = false;
+                if (j < end && s_flag[j]) {
+                    const uint64_t jx = s_kx[j], jy = s_ky[j];
+                    before = jx < kx || (jx == kx && (jy < ky || (jy == ky && s_row[j] < i)));
+                }
+                rank += (uint32_t)__popcll((__ballot(before) >> shift) & ((1ull << kGroup) - 1));
+            }
+            const uint64_t pos = (uint64_t)s_foff[b] + rank;
+            if (live && sub == 0 && pos < capacity) out_idx[pos] = i;
+        }
+    } else {
+        // large front: the same steps through global tables
+        for (uint32_t i = t; i < kBins; i += kFinishThreads) {
+            sc->bin_off[i] = sc->bin_cnt[i];
+            sc->bin_cur[i] = 0;
+            sc->bin_foff[i] = 0;
+        }
+        __syncthreads();
+        scan_sum_excl<kFinishThreads>(sc->bin_off, s_tmp);
+        for (uint32_t q = t; q < m; q += kFinishThreads) {
+            const uint32_t b = bin(w.skx[q]);
+            w.grouped[sc->bin_off[b] + atomicAdd(&sc->bin_cur[b], 1u)] = q;
+        }
+        __syncthreads();
+        for (uint32_t g = t; g < m; g += kFinishThreads) {
+            const uint32_t q = w.grouped[g];
+            const uint64_t kx = w.skx[q], ky = w.sky[q];
+            const uint32_t b = bin(kx);
+            bool dominated = false;
+            for (uint32_t h = sc->bin_off[b]; h < sc->bin_off[b + 1] && !dominated; ++h) {
+                const uint64_t jx = w.skx[w.grouped[h]], jy = w.sky[w.grouped[h]];
+                dominated = jx <= kx && jy <= ky && (jx < kx || jy < ky);
+            }
+            w.on_front[g] = dominated ? 0 : 1;
+            if (!dominated) atomicAdd(&sc->bin_foff[b], 1u);
+        }
+        __syncthreads();
+        scan_sum_excl<kFinishThreads>(sc->bin_foff, s_tmp);
+        if (t == 0) out_count[0] = sc->bin_foff[kBins];
+        for (uint32_t g = t; g < m; g += kFinishThreads) {
+            if (!w.on_front[g]) continue;
+            const uint32_t q = w.grouped[g];
+            const uint64_t kx = w.skx[q], ky = w.sky[q];
+            const uint32_t b = bin(kx), i = w.surv[q];
+            uint32_t rank = 0;
+            for (uint32_t h = sc->bin_off[b]; h < sc->bin_off[b + 1]; ++h) {
+                if (!w.on_front[h]) continue;
+                const uint32_t qj = w.grouped[h];
+                const uint64_t jx = w.skx[qj], jy = w.sky[qj];
+                if (jx < kx || (jx == kx && (jy < ky || (jy == ky && w.surv[qj] < i)))) ++rank;
+            }
+            const uint64_t pos = (uint64_t)sc->bin_foff[b] + rank;
+            if (pos < capacity) out_idx[pos] = i;
+        }
     }
+    __syncthreads();
+    // back to neutral for the next call
+    for (uint32_t i = t; i < kBins; i += kFinishThreads) {
+        sc->bin_min[i] = kNone;
+        sc->bin_cnt[i] = 0;
+    }
+    if (t == 0) sc->counters[0] = 0;
 }
 
 __global__ void pareto_empty_kernel(uint64_t *out_count) { out_count[0] = 0; }
 
+template <int K>
+void launch_top1(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws, hipStream_t stream) {
+    const Top1Ws w = top1_ws(ws);
+    const uint32_t nb = blocks_for(n);
+    hipLaunchKernelGGL(topk_pass_kernel<K>, dim3(nb), dim3(kBlock), 0, stream, spec.objective, make_filter(spec),
+                       (uint32_t)n, w);
+    hipLaunchKernelGGL(topk_merge_kernel<K>, dim3(1), dim3(kBlock), 0, stream, w, nb, spec.k, out.idx, out.val, out.count);
+}
+
 }  // namespace
+
+size_t select_scratch_bytes() { return sizeof(SelectScratch); }
+
+hipError_t launch_select_scratch_init(void *scratch, hipStream_t stream) {
+    hipLaunchKernelGGL(select_scratch_init_kernel, dim3(16), dim3(kBlock), 0, stream, (SelectScratch *)scratch);
+    return hipGetLastError();
+}
 
 size_t select_workspace_bytes(const guide_select_spec &spec, uint64_t n) {
     if (spec.mode == GUIDE_SELECT_PARETO) return pareto_ws_bytes(n);
-    return topk_ws_bytes(spec.n_groups ? spec.n_groups : 1);
+    const size_t a = topk_ws_bytes(spec.n_groups ? spec.n_groups : 1), b = top1_ws_bytes();
+    return a > b ? a : b;
 }
 
 hipError_t launch_select_topk(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
-                              hipStream_t stream) {
+                              void *scratch, hipStream_t stream) {
+    (void)scratch;
+    if (!spec.group) {
+        if (spec.k == 1) launch_top1<1>(spec, n, out, ws, stream);
+        else if (spec.k == 2) launch_top1<2>(spec, n, out, ws, stream);
+        else if (spec.k <= 4) launch_top1<4>(spec, n, out, ws, stream);
+        else launch_top1<8>(spec, n, out, ws, stream);
+        return hipGetLastError();
+    }
     const uint32_t G = spec.n_groups;
     const TopkWs w = topk_ws(ws, G);
     const RowFilter f = make_filter(spec);
     const uint32_t nb = blocks_for(n);
     for (uint32_t round = 0; round < spec.k; ++round) {
-        if (spec.group)
-            hipLaunchKernelGGL(topk_round_kernel<true>, dim3(nb), dim3(kBlock), 0, stream, spec.objective, f, spec.group,
-                               G, (uint32_t)n, round, w);
-        else
-            hipLaunchKernelGGL(topk_round_kernel<false>, dim3(nb), dim3(kBlock), 0, stream, spec.objective, f,
-                               (const uint32_t *)nullptr, G, (uint32_t)n, round, w);
+        hipLaunchKernelGGL(topk_round_kernel, dim3(nb), dim3(kBlock), 0, stream, spec.objective, f, spec.group, G,
+                           (uint32_t)n, round, w);
         hipLaunchKernelGGL(topk_final_kernel, dim3(G), dim3(kBlock), 0, stream, w, G, nb, round, spec.k, out.idx, out.val,
                            out.count);
     }
@@ -462,25 +828,21 @@ hipError_t launch_select_topk(const guide_select_spec &spec, uint64_t n, const g
 }
 
 hipError_t launch_select_pareto(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
-                                hipStream_t stream) {
+                                void *scratch, hipStream_t stream) {
     if (n == 0) {
         hipLaunchKernelGGL(pareto_empty_kernel, dim3(1), dim3(1), 0, stream, out.count);
         return hipGetLastError();
     }
+    SelectScratch *sc = (SelectScratch *)scratch;
     const ParetoWs w = pareto_ws(ws, n);
     const RowFilter f = make_filter(spec);
     const uint32_t nb = blocks_for(n), n32 = (uint32_t)n;
     const double *x = spec.objective, *y = spec.objective_y;
-    hipLaunchKernelGGL(pareto_init_kernel, dim3(kBins / kBlock), dim3(kBlock), 0, stream, w);
-    hipLaunchKernelGGL(pareto_range_kernel, dim3(nb), dim3(kBlock), 0, stream, x, y, f, n32, w);
-    hipLaunchKernelGGL(pareto_binmin_kernel, dim3(nb), dim3(kBlock), 0, stream, x, y, f, n32, w);
-    hipLaunchKernelGGL(pareto_scan_min_kernel, dim3(1), dim3(1024), 0, stream, w);
-    hipLaunchKernelGGL(pareto_survivors_kernel, dim3(nb), dim3(kBlock), 0, stream, x, y, f, n32, w);
-    hipLaunchKernelGGL(scan_sum_kernel, dim3(1), dim3(1024), 0, stream, (const uint32_t *)w.bin_cnt, w.bin_off);
-    hipLaunchKernelGGL(pareto_group_kernel, dim3(nb), dim3(kBlock), 0, stream, x, w);
-    hipLaunchKernelGGL(pareto_mark_kernel, dim3(nb), dim3(kBlock), 0, stream, x, y, w);
-    hipLaunchKernelGGL(scan_sum_kernel, dim3(1), dim3(1024), 0, stream, (const uint32_t *)w.bin_front, w.bin_foff);
-    hipLaunchKernelGGL(pareto_emit_kernel, dim3(nb), dim3(kBlock), 0, stream, x, y, w, out.idx, out.capacity, out.count);
+    hipLaunchKernelGGL(pareto_prepare_kernel, dim3(kSampleBlocks), dim3(kBlock), 0, stream, x, y, f, n32, sc);
+    hipLaunchKernelGGL(pareto_stair_kernel, dim3(nb), dim3(kBlock), 0, stream, x, y, f, n32, sc);
+    hipLaunchKernelGGL(pareto_survivors_kernel, dim3(nb), dim3(kBlock), 0, stream, x, y, f, n32, w, sc);
+    hipLaunchKernelGGL(pareto_finish_kernel, dim3(1), dim3(kFinishThreads), 0, stream, w, sc, out.idx, out.capacity,
+                       out.count);
     return hipGetLastError();
 }
 

@@ -141,6 +141,22 @@ def load() -> C.CDLL:
     return _lib
 
 
+class _Ref:
+    """byref() of a ctypes struct that also keeps the struct (and what it points to) alive."""
+
+    def __init__(self, struct, keep=None):
+        self.struct, self.keep = struct, keep
+        self._as_parameter_ = C.byref(struct)
+
+
+class _Ptr:
+    """Address of a host numpy array, kept alive."""
+
+    def __init__(self, array):
+        self.array = array
+        self._as_parameter_ = C.c_void_p(array.ctypes.data)
+
+
 def _dev_ptr(t) -> Optional[int]:
     """data_ptr() of a contiguous CUDA tensor (None passes NULL)."""
     if t is None:
@@ -223,6 +239,27 @@ class Context:
         a = np.ascontiguousarray(rows, dtype=np.float64).reshape(-1, 5)
         self._check(self._lib.guide_set_hardware(self._h, a.ctypes.data, len(a)))
 
+    def prepared(self, method: str, *args, **kw):
+        """Marshals the arguments of `method` once and returns a zero-argument callable that
+        repeats the same C call (for loops that re-issue one call many times; the stream is
+        the one current at preparation time)."""
+        calls = []
+        real = self._invoke
+        self._invoke = lambda fn, *a: calls.append((fn, a))
+        try:
+            getattr(self, method)(*args, **kw)
+        finally:
+            self._invoke = real
+        (fn, a), = calls
+        keep = (args, kw)
+
+        def run(_fn=fn, _a=a, _keep=keep, _check=self._check):
+            _check(_fn(*_a))
+        return run
+
+    def _invoke(self, fn, *a):
+        self._check(fn(*a))
+
     def eval_grid(self, grid: GridArg, first: int, count: int, out: dict = None, stats: dict = None,
                   e_c=None, e_b=None, time_model: int = TIME_ROOFLINE, stream=None):
         """out / stats: dicts column name -> CUDA tensor (missing = not written)."""
@@ -236,10 +273,9 @@ class Context:
             cm = CMetrics(*[_dev_ptr(out.get(k)) for k in METRIC_COLUMNS])
         if stats is not None:
             cs = CStats(*[_dev_ptr(stats.get(k)) for k in STATS_COLUMNS])
-        self._check(self._lib.guide_eval_grid(self._h, C.byref(grid.c), first, count,
-                                              C.byref(eff) if eff else None, time_model,
-                                              C.byref(cm) if cm else None, C.byref(cs) if cs else None,
-                                              _stream_ptr(stream)))
+        self._invoke(self._lib.guide_eval_grid, self._h, _Ref(grid.c, grid), first, count,
+                     _Ref(eff, (e_c, e_b)) if eff else None, time_model,
+                     _Ref(cm) if cm else None, _Ref(cs) if cs else None, _stream_ptr(stream))
 
     def eval_sampled(self, space: dict, seed: int, first: int, count: int, edges, ttft_cap: float, out: dict,
                      time_model: int = TIME_ROOFLINE, stream=None):
@@ -257,8 +293,8 @@ class Context:
         cs.link_div = float(space["link_div"])
         edges = np.ascontiguousarray(edges, dtype=np.float64)
         co = CSampledOut(*[_dev_ptr(out.get(k)) for k in SAMPLED_COLUMNS])
-        self._check(self._lib.guide_eval_sampled(self._h, C.byref(cs), seed, first, count, edges.ctypes.data,
-                                                 len(edges), ttft_cap, time_model, C.byref(co), _stream_ptr(stream)))
+        self._invoke(self._lib.guide_eval_sampled, self._h, _Ref(cs, keep), seed, first, count,
+                     _Ptr(edges), len(edges), ttft_cap, time_model, _Ref(co), _stream_ptr(stream))
 
     def simulate_workspace_bytes(self, n_cfg: int, n_requests: int) -> int:
         return self._lib.guide_simulate_workspace_bytes(n_cfg, n_requests)
@@ -271,10 +307,9 @@ class Context:
         n_out = np.ascontiguousarray(trace[2], dtype=np.uint32)
         ct = CTrace(len(arr), arr.ctypes.data, n_in.ctypes.data, n_out.ctypes.data)
         co = CSimOut(*[_dev_ptr(out.get(k)) for k in SIM_COLUMNS])
-        self._check(self._lib.guide_simulate(self._h, C.byref(grid.c), _dev_ptr(cfg_idx), _dev_ptr(rate),
-                                             cfg_idx.numel(), C.byref(ct), time_model, C.byref(co),
-                                             _dev_ptr(workspace), workspace.numel() * workspace.element_size(),
-                                             _stream_ptr(stream)))
+        self._invoke(self._lib.guide_simulate, self._h, _Ref(grid.c, grid), _dev_ptr(cfg_idx), _dev_ptr(rate),
+                     cfg_idx.numel(), _Ref(ct, (arr, n_in, n_out)), time_model, _Ref(co),
+                     _dev_ptr(workspace), workspace.numel() * workspace.element_size(), _stream_ptr(stream))
 
     def _select_spec(self, mode, objective, objective_y, feasible, constraints, group, n_groups, k):
         s = CSelectSpec()
@@ -302,5 +337,5 @@ class Context:
         s = self._select_spec(mode, objective, objective_y, feasible, list(constraints), group, n_groups, k)
         o = CSelectOut(_dev_ptr(out_idx), _dev_ptr(out_val), _dev_ptr(out_count), capacity)
         ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-        self._check(self._lib.guide_select(self._h, C.byref(s), n, C.byref(o), _dev_ptr(workspace), ws_bytes,
-                                           _stream_ptr(stream)))
+        self._invoke(self._lib.guide_select, self._h, _Ref(s), n, _Ref(o), _dev_ptr(workspace), ws_bytes,
+                     _stream_ptr(stream))

@@ -28,7 +28,8 @@ def ora_hw(h: wl.Hardware) -> go.Hw:
 def rel_err(a, b):
     a = np.asarray(a, dtype=np.float64); b = np.asarray(b, dtype=np.float64)
     den = np.maximum(np.abs(b), np.finfo(np.float64).tiny)
-    e = np.abs(a - b) / den
+    with np.errstate(invalid="ignore"):
+        e = np.abs(a - b) / den
     both_inf = np.isinf(a) & np.isinf(b) & (np.sign(a) == np.sign(b))
     e[both_inf] = 0.0
     e[(a == 0) & (b == 0)] = 0.0
