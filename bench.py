@@ -31,6 +31,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-extra", action="store_true", help="skip the sweep / sampled / simulation timings")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--probe", action="store_true",
+                    help="counter probe for rocprofv3 --pmc: 10 grid evaluations, then 10 plain device copies of "
+                         "512 MiB (a kernel of known traffic that calibrates FETCH_SIZE / WRITE_SIZE), no timing")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
@@ -74,6 +77,17 @@ def main():
             ev[1].record()
         call_topk()
         call_pareto()
+
+    if args.probe:
+        src = torch.ones(1 << 26, dtype=torch.float64, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            call_eval()
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"probe": "10 x eval_grid over %d configs, 10 x device copy of %d bytes" % (n, src.numel() * 8)}))
+        return
 
     for _ in range(args.warmup):
         step()

@@ -100,8 +100,10 @@ __global__ __launch_bounds__(kBlock) void eval_grid_kernel(GridDesc g, const Dev
 // once, and the wave transposes each output column through LDS so that global
 // stores stay coalesced (lane l stores index base + 64*it + l).
 
+constexpr uint32_t kCoefRows = 96;          // (model, tp, precision) rows of per-op coefficients kept in LDS
 struct TileLds {
     GridLds g;
+    Coef coef[kCoefRows];
     double r_tp[GUIDE_MAX_AXIS_VALUES];     // 1 / tp
     double r_sin[GUIDE_MAX_AXIS_VALUES];    // nudged reciprocals for exact floor division
     double r_blk[GUIDE_MAX_AXIS_VALUES];
@@ -122,6 +124,18 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
         s.r_sin[i] = recip_up(1.0 / (double)max(tab->axis_vals[AX_SIN][i], 1u));
         s.r_blk[i] = recip_up(1.0 / (double)max(tab->axis_vals[AX_BLK][i], 1u));
         s.r_mbt[i] = recip_up(1.0 / (double)max(tab->axis_vals[AX_MBT][i], 1u));
+    }
+    // per-op FLOPs / bytes of every (model, tp, precision) combination of the grid, once per block
+    const uint32_t n_tp = g.div[AX_TP].d, n_w = g.div[AX_WBITS].d;
+    const uint32_t n_rows = g.div[AX_MODEL].d * n_tp * n_w;
+    const bool coef_in_lds = n_rows <= kCoefRows;
+    if (coef_in_lds) {
+        for (uint32_t r = threadIdx.x; r < n_rows; r += blockDim.x) {
+            const uint32_t dw = r % n_w, dt = (r / n_w) % n_tp, dm = r / (n_w * n_tp);
+            const uint32_t p = tab->axis_vals[AX_TP][dt];
+            s.coef[r] = make_coef(tab->models[tab->axis_vals[AX_MODEL][dm]], p, tab->axis_vals[AX_WBITS][dw],
+                                  1.0 / (double)p);
+        }
     }
     __syncthreads();
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
@@ -147,18 +161,40 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
         kn.s_out = s.g.axis[AX_SOUT][dg[AX_SOUT]];
         kn.p = s.g.axis[AX_TP][dg[AX_TP]];
         kn.wbits = s.g.axis[AX_WBITS][dg[AX_WBITS]];
-        const Coef cf = make_coef(s.g.models[s.g.axis[AX_MODEL][dg[AX_MODEL]]], kn.p, kn.wbits, s.r_tp[dg[AX_TP]]);
+        const Coef cf = coef_in_lds
+                            ? s.coef[(dg[AX_MODEL] * n_tp + dg[AX_TP]) * n_w + dg[AX_WBITS]]
+                            : make_coef(s.g.models[s.g.axis[AX_MODEL][dg[AX_MODEL]]], kn.p, kn.wbits, s.r_tp[dg[AX_TP]]);
         const HwRecip hw = s.g.hw[s.g.axis[AX_HW][dg[AX_HW]]];
         const TimeCoef tc = make_time_coef(cf, hw.r_peak * re_c, hw.r_bw * re_b, hw.r_link, hw.lat);
 
-        const double t_decode = decode_time_fast<ADDITIVE>(tc, kn.b, kn.s_in, kn.s_out - 1);
-        double t_prefill[NM];
+        // coalesced stores: element e of the wave's 64*TS consecutive indices sits in lane e / TS, slot e % TS.
+        // Columns leave as soon as their values exist so that stores overlap the remaining arithmetic.
+        const uint32_t cfg0 = (t_first + tb) * TS;             // flat index of the wave's first element
+        // every element of the wave inside [first, last): no per-element checks (wave-uniform)
+        const bool full = tb + kWave <= n_tiles && cfg0 >= first && cfg0 + kWave * TS <= last;
+        auto store_f64 = [&](double *col, auto value_of_slot) {
+            if (!col) return;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 #pragma unroll
-        for (int m = 0; m < NM; ++m)
-            t_prefill[m] = prefill_time_fast<ADDITIVE>(tc, kn.b, kn.s_in, s.g.axis[AX_MBT][m], s.r_sin[dg[AX_SIN]],
-                                                        s.r_mbt[m]);
-        MemResult mem[NB];
-        {
+            for (int j = 0; j < TS; ++j) xw[lane * TS + j] = value_of_slot(j);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            if (full) {
+                double *dst = col + (cfg0 - first) + lane;
+#pragma unroll
+                for (int it = 0; it < TS; ++it) dst[it * kWave] = xw[it * kWave + lane];
+            } else {
+#pragma unroll
+                for (int it = 0; it < TS; ++it) {
+                    const uint32_t cfg = cfg0 + it * kWave + lane;
+                    const double v = xw[it * kWave + lane];
+                    if (cfg >= first && cfg < last && tb + (it * kWave + lane) / TS < n_tiles) col[cfg - first] = v;
+                }
+            }
+        };
+
+        // memory check: depends on the block size only
+        if (out.b_max || out.feasible) {
+            MemResult mem[NB];
             const double c_avail = hw.cap - cf.w_gpu;
             const uint32_t tok = kn.s_in + kn.s_out;
 #pragma unroll
@@ -171,32 +207,6 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
                 mem[k].feasible = room && (double)kn.b * kv_req <= c_avail;
                 mem[k].b_max = !room ? 0u : (q >= 4294967295.0 ? 4294967295u : (uint32_t)q);
             }
-        }
-        const double bs = (double)kn.b * (double)kn.s_out;
-        const double cost_f = (double)kn.p * (1.0e6 / 3600.0) * fast_recip(bs);
-        const double tok_s = kn.s_out > 1 ? (double)kn.b * (double)(kn.s_out - 1) * fast_recip(t_decode) : 0.0;
-
-        // coalesced stores: element e of the wave's 64*TS consecutive indices sits in lane e / TS, slot e % TS
-        const uint32_t cfg0 = (t_first + tb) * TS;             // flat index of the wave's first element
-        auto store_f64 = [&](double *col, auto value_of_slot) {
-            if (!col) return;
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-#pragma unroll
-            for (int j = 0; j < TS; ++j) xw[lane * TS + j] = value_of_slot(j);
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-#pragma unroll
-            for (int it = 0; it < TS; ++it) {
-                const uint32_t cfg = cfg0 + it * kWave + lane;
-                const double v = xw[it * kWave + lane];
-                if (cfg >= first && cfg < last && tb + (it * kWave + lane) / TS < n_tiles) col[cfg - first] = v;
-            }
-        };
-        store_f64(out.t_prefill, [&](int j) { return t_prefill[j % NM]; });
-        store_f64(out.t_decode, [&](int) { return t_decode; });
-        store_f64(out.t_batch, [&](int j) { return t_prefill[j % NM] + t_decode; });
-        store_f64(out.decode_tok_s, [&](int) { return tok_s; });
-        store_f64(out.cost, [&](int j) { return (t_prefill[j % NM] + t_decode) * cost_f; });
-        if (out.b_max || out.feasible) {
             uint32_t *xi = (uint32_t *)xw;
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 #pragma unroll
@@ -209,12 +219,30 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
             for (int it = 0; it < TS; ++it) {
                 const uint32_t cfg = cfg0 + it * kWave + lane;
                 const uint32_t bm = xi[it * kWave + lane], fe = xi[kWave * TS + it * kWave + lane];
-                if (cfg >= first && cfg < last && tb + (it * kWave + lane) / TS < n_tiles) {
+                if (full || (cfg >= first && cfg < last && tb + (it * kWave + lane) / TS < n_tiles)) {
                     if (out.b_max) out.b_max[cfg - first] = bm;
                     if (out.feasible) out.feasible[cfg - first] = (uint8_t)fe;
                 }
             }
         }
+
+        // decode series: depends on neither tile axis
+        const double t_decode = decode_time_fast<ADDITIVE>(tc, kn.b, kn.s_in, kn.s_out - 1);
+        const double tok_s = kn.s_out > 1 ? (double)kn.b * (double)(kn.s_out - 1) * fast_recip(t_decode) : 0.0;
+        store_f64(out.t_decode, [&](int) { return t_decode; });
+        store_f64(out.decode_tok_s, [&](int) { return tok_s; });
+
+        // prefill: depends on the token budget only
+        double t_prefill[NM];
+#pragma unroll
+        for (int m = 0; m < NM; ++m)
+            t_prefill[m] = prefill_time_fast<ADDITIVE>(tc, kn.b, kn.s_in, s.g.axis[AX_MBT][m], s.r_sin[dg[AX_SIN]],
+                                                        s.r_mbt[m]);
+        const double bs = (double)kn.b * (double)kn.s_out;
+        const double cost_f = (double)kn.p * (1.0e6 / 3600.0) * fast_recip(bs);
+        store_f64(out.t_prefill, [&](int j) { return t_prefill[j % NM]; });
+        store_f64(out.t_batch, [&](int j) { return t_prefill[j % NM] + t_decode; });
+        store_f64(out.cost, [&](int j) { return (t_prefill[j % NM] + t_decode) * cost_f; });
     }
 }
 
@@ -299,7 +327,10 @@ static void launch_tile(const GridDesc &g, const DevTables *tab, uint32_t first,
                         double re_b, const guide_metrics &out, hipStream_t stream) {
     const uint32_t ts = NB * NM;
     const uint32_t n_tiles = (first + count - 1) / ts - first / ts + 1;
-    const dim3 grid(blocks_for(n_tiles)), block(kBlock);
+    // two persistent blocks per compute unit: every wave loops over several batches of 64 tiles, so the
+    // stores of one batch overlap the arithmetic of the next (measured best among 1..8 blocks per CU)
+    const uint32_t need = (n_tiles + kBlock - 1) / kBlock, cap = 2 * kNumCU;
+    const dim3 grid(need < cap ? need : cap), block(kBlock);
     hipLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM>), grid, block, 0, stream, g, tab, first, count, re_c, re_b, out);
 }
 
