@@ -34,6 +34,9 @@ def main():
     ap.add_argument("--probe", action="store_true",
                     help="counter probe for rocprofv3 --pmc: 10 grid evaluations, then 10 plain device copies of "
                          "512 MiB (a kernel of known traffic that calibrates FETCH_SIZE / WRITE_SIZE), no timing")
+    ap.add_argument("--probe-extra", action="store_true",
+                    help="counter probe: the sweep (1.9M x 64), the sampled space (2^24) and the simulation "
+                         "(4096 configs) once each")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
@@ -78,6 +81,10 @@ def main():
         call_topk()
         call_pareto()
 
+    if args.probe_extra:
+        extra = extra_timings(ctx, gg, g, torch, np, guide, wl, n_sampled=1 << 24, n_sim=4096)
+        print(json.dumps({"probe_extra": extra}))
+        return
     if args.probe:
         src = torch.ones(1 << 26, dtype=torch.float64, device="cuda")
         dst = torch.empty_like(src)
@@ -153,7 +160,7 @@ def _timed(torch, fn, reps=1):
     return a.elapsed_time(b) / reps * 1e-3
 
 
-def extra_timings(ctx, gg, g, torch, np, guide, wl):
+def extra_timings(ctx, gg, g, torch, np, guide, wl, n_sampled=1 << 28, n_sim=65536):
     """Sweep (1.9M x 64 samples), sampled space (2^28), serving simulation (65 536 x 1024 requests)."""
     n = g.size
     extra = {}
@@ -172,12 +179,12 @@ def extra_timings(ctx, gg, g, torch, np, guide, wl):
               win_val=torch.empty(wl.N_BUCKETS, dtype=torch.float64, device="cuda"),
               win_idx=torch.empty(wl.N_BUCKETS, dtype=torch.int64, device="cuda"),
               hist=torch.empty(256, dtype=torch.int64, device="cuda"))
-    n_s = 1 << 28
+    n_s = n_sampled
     s = _timed(torch, lambda: ctx.eval_sampled(space, wl.SEED, 0, n_s, wl.BUCKET_EDGES, wl.TTFT_CAP_S, so))
     extra["sampled"] = {"configs_per_s": n_s / s, "seconds": s, "candidates": n_s,
                         "feasible": int(so["feasible_count"].item())}
 
-    n_cfg = 65536
+    n_cfg = n_sim
     idx, rate = wl.sim_configs(g, n_cfg)
     tr = wl.request_trace()
     d_idx = torch.from_numpy(idx.view(np.int32)).cuda()

@@ -31,19 +31,110 @@ struct SimLds {
     uint32_t n_out[GUIDE_MAX_REQUESTS];
 };
 
-// Workspace: heap[slot][cfg] (u64 key = finishing step << 10 | request), first[cfg][req], ttft[cfg][req].
+constexpr uint32_t kKeyBins = 1024;      // buckets of the expected-step-count ordering
+
+// Workspace: heap[slot][position] (u64 key = finishing step << 10 | request), first[cfg][req],
+// ttft[cfg][req], then the launch order: perm[position] = configuration, bucket counters.
 struct SimWs {
     uint64_t *heap;
     double *first;
     double *ttft;
+    uint32_t *perm;
+    uint32_t *bucket;     // [n_cfg]: bucket of each configuration
+    uint32_t *bins;       // [kKeyBins]: counts, then scatter cursors
 };
 SimWs sim_ws(void *ws, uint32_t n_cfg, uint32_t n_req) {
     SimWs w;
     w.heap = (uint64_t *)ws;
     w.first = (double *)(w.heap + (size_t)n_cfg * n_req);
     w.ttft = w.first + (size_t)n_cfg * n_req;
+    w.perm = (uint32_t *)(w.ttft + (size_t)n_cfg * n_req);
+    w.bucket = w.perm + n_cfg;
+    w.bins = w.bucket + n_cfg;
     return w;
 }
+
+// Grid index -> axis values (s_in / s_out digits are decoded but unused by the simulator).
+__device__ inline bool decode_sim_index(const uint32_t (*axis)[GUIDE_MAX_AXIS_VALUES], const GridDesc &g, uint32_t idx,
+                                        uint32_t *v) {
+    uint32_t rem = idx;
+#pragma unroll
+    for (int a = kNumAxes - 1; a > 0; --a) {
+        const uint32_t q = div32(rem, g.div[a]);
+        v[a] = axis[a][rem - q * g.div[a].d];
+        rem = q;
+    }
+    const bool bad = rem >= g.div[0].d;
+    v[0] = axis[0][bad ? 0 : rem];
+    return bad;
+}
+
+// Lanes of a wave run until their slowest configuration ends, so configurations
+// are launched in order of a rough estimate of their engine steps: generated
+// tokens / concurrency, with concurrency from Little's law (arrival rate x
+// latency of a lone request), clamped to [1, sequence cap].  Only the order
+// depends on it, never a result.
+template <bool ADDITIVE>
+__global__ __launch_bounds__(kBlock) void sim_order_count_kernel(GridDesc g, const DevTables *__restrict__ tab,
+                                                                 const TraceDev *__restrict__ trace, uint32_t n_req,
+                                                                 const uint32_t *__restrict__ cfg_idx,
+                                                                 const double *__restrict__ rate_in, uint32_t n_cfg,
+                                                                 SimWs ws) {
+    __shared__ double s_sum[2];
+    if (threadIdx.x == 0) {
+        double si = 0.0, so = 0.0;
+        for (uint32_t i = 0; i < n_req; ++i) {
+            si += (double)trace->n_in[i];
+            so += (double)trace->n_out[i];
+        }
+        s_sum[0] = si;
+        s_sum[1] = so;
+    }
+    __syncthreads();
+    const uint32_t c = blockIdx.x * kBlock + threadIdx.x;
+    if (c >= n_cfg) return;
+    uint32_t v[kNumAxes];
+    const bool bad = decode_sim_index(tab->axis_vals, g, cfg_idx[c], v);
+    uint32_t b = 0;
+    const double rate = rate_in[c];
+    if (!bad && rate > 0.0) {
+        const guide_hw hw = tab->hw[v[AX_HW]];
+        const Coef cf = make_coef(tab->models[v[AX_MODEL]], v[AX_TP], v[AX_WBITS]);
+        const TimeCoef tc = make_time_coef(cf, 1.0 / hw.peak_flops, 1.0 / hw.hbm_bw, 1.0 / hw.link_bw, hw.link_lat);
+        const double mean_in = s_sum[0] / (double)n_req, mean_out = s_sum[1] / (double)n_req;
+        const double ctx = mean_in + 0.5 * mean_out;
+        const double lone = mean_out * pass_time<ADDITIVE>(tc, 1.0, ctx, ctx, 1.0) +
+                            pass_time<ADDITIVE>(tc, mean_in, mean_in * mean_in, mean_in, 1.0);
+        const double conc = fmin(fmax(rate * lone, 1.0), (double)v[AX_BATCH]);
+        const float steps = (float)(s_sum[1] / conc);
+        const int k = (int)((__log2f(fmaxf(steps, 1.0f)) - 6.0f) * 64.0f);
+        b = (uint32_t)(k < 0 ? 0 : (k > (int)kKeyBins - 1 ? (int)kKeyBins - 1 : k));
+    }
+    ws.bucket[c] = b;
+    atomicAdd(&ws.bins[b], 1u);
+}
+
+__global__ __launch_bounds__(kKeyBins) void sim_order_scan_kernel(SimWs ws) {
+    __shared__ uint32_t s[kKeyBins];
+    const uint32_t t = threadIdx.x;
+    s[t] = ws.bins[t];
+    __syncthreads();
+    for (uint32_t off = 1; off < kKeyBins; off <<= 1) {
+        const uint32_t o = t >= off ? s[t - off] : 0;
+        __syncthreads();
+        s[t] += o;
+        __syncthreads();
+    }
+    // longest first: bucket b starts after all higher buckets
+    ws.bins[t] = s[kKeyBins - 1] - s[t];
+}
+
+__global__ __launch_bounds__(kBlock) void sim_order_scatter_kernel(uint32_t n_cfg, SimWs ws) {
+    const uint32_t c = blockIdx.x * kBlock + threadIdx.x;
+    if (c < n_cfg) ws.perm[atomicAdd(&ws.bins[ws.bucket[c]], 1u)] = c;
+}
+
+__global__ __launch_bounds__(kKeyBins) void sim_order_clear_kernel(SimWs ws) { ws.bins[threadIdx.x] = 0; }
 
 template <bool ADDITIVE>
 __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const DevTables *__restrict__ tab,
@@ -62,23 +153,12 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
         s.n_out[i] = trace->n_out[i];
     }
     __syncthreads();
-    const uint32_t c = blockIdx.x * kSimBlock + threadIdx.x;
-    if (c >= n_cfg) return;
+    const uint32_t pos = blockIdx.x * kSimBlock + threadIdx.x;     // launch position; its configuration is perm[pos]
+    if (pos >= n_cfg) return;
+    const uint32_t c = ws.perm[pos];
 
-    // decode the grid index (s_in / s_out digits are ignored)
     uint32_t v[kNumAxes];
-    bool bad_index;
-    {
-        uint32_t rem = cfg_idx[c];
-#pragma unroll
-        for (int a = kNumAxes - 1; a > 0; --a) {
-            const uint32_t q = div32(rem, g.div[a]);
-            v[a] = s.axis[a][rem - q * g.div[a].d];
-            rem = q;
-        }
-        bad_index = rem >= g.div[0].d;
-        v[0] = s.axis[0][bad_index ? 0 : rem];
-    }
+    const bool bad_index = decode_sim_index(s.axis, g, cfg_idx[c], v);
     const uint32_t max_seqs = v[AX_BATCH], p = v[AX_TP], wbits = v[AX_WBITS], blk = v[AX_BLK], mbt = v[AX_MBT];
     const guide_hw hw = tab->hw[v[AX_HW]];
     const double rate = rate_in[c];
@@ -108,7 +188,7 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
         return;
     }
 
-    uint64_t *heap = ws.heap + c;          // element j at heap[j * n_cfg]
+    uint64_t *heap = ws.heap + pos;        // element j at heap[j * n_cfg]: neighbouring lanes, neighbouring words
     double *first = ws.first + (size_t)c * n_req;
     double *ttft = ws.ttft + (size_t)c * n_req;
     const size_t hs = n_cfg;
@@ -119,6 +199,8 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
     long long free_blk = n_blk;
     uint32_t status = GUIDE_SIM_OK;
     double arr_next = s.arrival[0] / rate;   // arrival time of request `next`
+    double kept_base = 0.0, kept_lm = 0.0;   // layer_base / lm_head of the last decode-only step
+    uint32_t kept_dec = 0;                   // its token count (0 = nothing kept)
 
     while (n_done < n_req) {
         uint32_t n_active = (next - pf_head) + n_dec;
@@ -154,8 +236,19 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
                 done += (uint32_t)ch;
             }
         }
-        // 4. one engine step
-        now += pass_time<ADDITIVE>(tc, T, Q, K, n_lm);
+        // 4. one engine step.  A step with decode tokens only repeats the previous step's token count
+        // unless a request joined or left, so the part of the pass that depends on the token count alone
+        // is kept from step to step (same operations, same rounding, as evaluating the whole pass)
+        if (chunks == 0) {
+            if (n_dec != kept_dec) {
+                kept_base = layer_base<ADDITIVE>(tc, T);
+                kept_lm = lm_head<ADDITIVE>(tc, n_lm);
+                kept_dec = n_dec;
+            }
+            now += fma(tc.L, kept_base + attention<ADDITIVE>(tc, T, Q, K), kept_lm);
+        } else {
+            now += pass_time<ADDITIVE>(tc, T, Q, K, n_lm);
+        }
         ++step;
         n_rs += n_dec + chunks;
         // 5. book-keeping: decoders emitted a token; those at their last one leave
@@ -267,13 +360,23 @@ __global__ __launch_bounds__(kPctBlock) void percentile_kernel(const double *__r
 
 }  // namespace
 
-size_t simulate_workspace_bytes(uint32_t n_cfg, uint32_t n_req) { return (size_t)n_cfg * n_req * 24 + 256; }
+size_t simulate_workspace_bytes(uint32_t n_cfg, uint32_t n_req) {
+    return (size_t)n_cfg * n_req * 24 + (size_t)n_cfg * 8 + kKeyBins * 4 + 256;
+}
 
 hipError_t launch_simulate(const GridDesc &g, const DevTables *tab, const TraceDev *trace, uint32_t n_req,
                            const uint32_t *cfg_idx, const double *rate, uint32_t n_cfg, bool additive,
                            const guide_sim_out &out, void *ws_, hipStream_t stream) {
     const SimWs ws = sim_ws(ws_, n_cfg, n_req);
     const dim3 grid((n_cfg + kSimBlock - 1) / kSimBlock), block(kSimBlock);
+    const dim3 ogrid((n_cfg + kBlock - 1) / kBlock), oblock(kBlock);
+    hipLaunchKernelGGL(sim_order_clear_kernel, dim3(1), dim3(kKeyBins), 0, stream, ws);
+    if (additive)
+        hipLaunchKernelGGL(sim_order_count_kernel<true>, ogrid, oblock, 0, stream, g, tab, trace, n_req, cfg_idx, rate, n_cfg, ws);
+    else
+        hipLaunchKernelGGL(sim_order_count_kernel<false>, ogrid, oblock, 0, stream, g, tab, trace, n_req, cfg_idx, rate, n_cfg, ws);
+    hipLaunchKernelGGL(sim_order_scan_kernel, dim3(1), dim3(kKeyBins), 0, stream, ws);
+    hipLaunchKernelGGL(sim_order_scatter_kernel, ogrid, oblock, 0, stream, n_cfg, ws);
     if (additive)
         hipLaunchKernelGGL(simulate_kernel<true>, grid, block, 0, stream, g, tab, trace, n_req, cfg_idx, rate, n_cfg, out, ws);
     else
