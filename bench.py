@@ -20,7 +20,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-ALU_PEAK_GINST = 39321.6        # 256 CU x 4 SIMD x 16 lanes x 2.4 GHz: vector lane-instructions per ns * 1e... (G/s)
+# HBM bytes per launch of the grid kernel from rocprofv3 counters (profiles/eval_tile_kernel_full_grid_pmc.md):
+# WRITE_SIZE 83531.25 KiB x 1.0 + FETCH_SIZE 138.16 KiB x 2.0 (scales from a 512 MiB device copy).
+# Set to None whenever eval_tile_kernel changes after the counters were taken.
+TRAFFIC_BYTES_PER_LAUNCH = 85_818_952
 BYTES_PER_CONFIG = 45           # 5 fp64 + u32 + u8 written per configuration, nothing read
 
 
@@ -35,8 +38,8 @@ def main():
                     help="counter probe for rocprofv3 --pmc: 10 grid evaluations, then 10 plain device copies of "
                          "512 MiB (a kernel of known traffic that calibrates FETCH_SIZE / WRITE_SIZE), no timing")
     ap.add_argument("--probe-extra", action="store_true",
-                    help="counter probe: the sweep (1.9M x 64), the sampled space (2^24) and the simulation "
-                         "(4096 configs) once each")
+                    help="counter probe: the sweep (1.9M x 64), the sampled space (2^28) and the simulation "
+                         "(65 536 configs) only")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
@@ -82,7 +85,7 @@ def main():
         call_pareto()
 
     if args.probe_extra:
-        extra = extra_timings(ctx, gg, g, torch, np, guide, wl, n_sampled=1 << 24, n_sim=4096)
+        extra = extra_timings(ctx, gg, g, torch, np, guide, wl)
         print(json.dumps({"probe_extra": extra}))
         return
     if args.probe:
@@ -136,7 +139,8 @@ def main():
                    "selected": [int(v) for v in sel_idx.cpu().numpy().view(np.uint64)],
                    "pareto_front_size": int(par_cnt.item())},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "eval_grid_kernel",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH,
+                     "kernel": "eval_tile_kernel<false,2,3>",
                      "kernel_ms": ms_eval, "bytes_per_config": BYTES_PER_CONFIG},
         "phases_ms": {"eval_grid": ms_eval, "select_topk": ms_topk, "select_pareto": ms_pareto},
     }
