@@ -112,6 +112,14 @@ def main():
     t1 = time.perf_counter()
     total = t1 - t0
     ms_eval = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    # the same kernel launched back to back between one pair of events (no markers between launches)
+    ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev2[0].record()
+    for _ in range(50):
+        call_eval()
+    ev2[1].record()
+    torch.cuda.synchronize()
+    ms_eval_b2b = ev2[0].elapsed_time(ev2[1]) / 50
     # phase split of the selections, outside the timed region
     ev3 = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
     reps = 20
@@ -141,7 +149,8 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH,
                      "kernel": "eval_tile_kernel<false,2,3>",
-                     "kernel_ms": ms_eval, "bytes_per_config": BYTES_PER_CONFIG},
+                     "kernel_ms": ms_eval, "kernel_ms_back_to_back": ms_eval_b2b,
+                     "bytes_per_config": BYTES_PER_CONFIG},
         "phases_ms": {"eval_grid": ms_eval, "select_topk": ms_topk, "select_pareto": ms_pareto},
     }
 

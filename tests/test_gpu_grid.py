@@ -170,3 +170,33 @@ def test_argument_errors(torch_cuda):
         fresh.set_models(np.zeros((1, 8), dtype=np.uint32))
     with pytest.raises(guide.GuideError):
         fresh.set_hardware(np.zeros((1, 5)))
+
+
+def test_tile_shapes_generic_path_and_table_limits(ora, torch_cuda):
+    """Every compiled tile shape, a shape without one (generic kernel), the largest model / hardware
+    tables (more coefficient rows than the LDS table holds) and a 64-value axis."""
+    torch = torch_cuda
+    hws = [wl.Hardware(1e14 * (1 + i), 1e12 * (1 + 0.1 * i), (24 + i) * wl.GIB, 1e11 * (1 + i % 5), 1e-6 * (i % 3))
+           for i in range(64)]
+    models = list(wl.MODELS_FULL) + [wl.Model("m6", 24, 2048, 16, 4, 8192), wl.Model("m7", 60, 6144, 48, 48, 16384),
+                                     wl.Model("m8", 16, 1024, 8, 2, 4096, E=4, k=1)]
+    shapes = [(2, 3), (1, 3), (2, 1), (2, 2), (1, 2), (3, 3), (1, 4), (2, 4), (4, 5), (1, 1)]
+    for nb, nm in shapes:
+        blks = [16, 32, 8, 64][:nb]
+        mbts = [2048, 512, 8192, 300, 4096][:nm]
+        g = wl.make_grid(models, hws[:3], wl.Axis.table([2, 9]), wl.Axis.table([100, 3000]), wl.Axis.table([1, 40]),
+                         wl.Axis.table([1, 2, 3, 4, 8]), wl.Axis.table([16, 8, 4]), wl.Axis.table(blks),
+                         wl.Axis.table(mbts))
+        ctx = bridge.gpu_context(g)
+        first, count = 7, g.size - 20
+        out = bridge.metric_buffers(count)
+        ctx.eval_grid(bridge.gpu_grid(g), first, count, out=out)
+        torch.cuda.synchronize()
+        _compare(out, ora.eval_grid(bridge.ora_grid(g), first, count), ("shape", nb, nm))
+    g = wl.make_grid(models, hws, wl.Axis.table(list(range(1, 65))), wl.Axis.table([640]), wl.Axis.table([33]),
+                     wl.Axis.table([2]), wl.Axis.table([16]), wl.Axis.table([16, 32]), wl.Axis.table([2048, 4096, 8192]))
+    ctx = bridge.gpu_context(g)
+    out = bridge.metric_buffers(g.size)
+    ctx.eval_grid(bridge.gpu_grid(g), 0, g.size, out=out)
+    torch.cuda.synchronize()
+    _compare(out, ora.eval_grid(bridge.ora_grid(g)), "max tables")

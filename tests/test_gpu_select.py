@@ -169,3 +169,35 @@ def test_full_grid_select_and_pareto_on_gpu_columns(ora, torch_cuda):
     exp = ora.pareto_sweep(host["t_prefill"], host["cost"], host["feasible"])
     assert m == len(exp) > 0
     np.testing.assert_array_equal(got, exp)
+
+
+def test_select_on_zero_rows(torch_cuda):
+    torch = torch_cuda
+    ctx = bridge.gpu_context(wl.grid_tiny())
+    empty = torch.empty(0, dtype=torch.float64, device="cuda")
+    gi, gv, gc = _topk(torch, ctx, empty, 3)
+    assert np.all(gi == 2 ** 64 - 1) and np.all(np.isinf(gv)) and gc[0] == 0
+    got, m = _pareto(torch, ctx, empty, empty, capacity=4)
+    assert m == 0 and len(got) == 0
+
+
+def test_pareto_large_front_and_repeated_calls(ora, torch_cuda):
+    """A front larger than what the finishing block stages in LDS (global-table path), rows outside the
+    sampled range, and several calls in a row on one context (the scratch tables return to neutral)."""
+    torch = torch_cuda
+    ctx = bridge.gpu_context(wl.grid_tiny())
+    rng = np.random.default_rng(17)
+    n = 40000
+    x = rng.random(n) * 100.0
+    x[::997] *= 1e6                                      # far outside the bulk: clamped into the last bin
+    x[5::991] *= 1e-9
+    y = 1.0e9 - 7.0 * x                                  # strictly decreasing in x: every passing row is on the front
+    for rep in range(3):
+        fe = (rng.random(n) < 0.9).astype(np.uint8)
+        got, m = _pareto(torch, ctx, _dev(torch, x), _dev(torch, y), _dev(torch, fe))
+        exp = ora.pareto_sweep(x, y, fe)
+        assert m == len(exp) > 4096
+        np.testing.assert_array_equal(got, exp)
+        xs = rng.integers(0, 50, 3000).astype(np.float64); ys = rng.integers(0, 50, 3000).astype(np.float64)
+        got, m = _pareto(torch, ctx, _dev(torch, xs), _dev(torch, ys))
+        np.testing.assert_array_equal(got, ora.pareto_brute(xs, ys))
