@@ -217,7 +217,15 @@ def extra_timings(ctx, gg, g, torch, np, guide, wl, n_sampled=1 << 28, n_sim=655
     steps = int(sim["n_steps"].sum().item())
     extra["simulate"] = {"request_steps_per_s": rs / s, "engine_steps_per_s": steps / s, "seconds": s,
                          "configs": n_cfg, "requests_per_config": len(tr.n_in), "request_steps": rs,
-                         "feasible_configs": int((sim["status"] == 0).sum().item())}
+                         "feasible_configs": int((sim["status"] == 0).sum().item()), "scheduler": "split-fuse"}
+    a.record()
+    ctx.simulate(gg, d_idx, d_rate, (tr.arrival_unit, tr.n_in, tr.n_out), sim, ws, scheduler=guide.SCHED_PREFILL_FIRST)
+    b.record()
+    torch.cuda.synchronize()
+    s = a.elapsed_time(b) * 1e-3
+    rs = int(sim["n_request_steps"].sum().item())
+    extra["simulate_prefill_first"] = {"request_steps_per_s": rs / s, "seconds": s, "request_steps": rs,
+                                       "engine_steps_per_s": int(sim["n_steps"].sum().item()) / s}
     return extra
 
 

@@ -63,6 +63,7 @@ enum { GUIDE_TIME_ROOFLINE = 0, GUIDE_TIME_ADDITIVE = 1 };
 enum { GUIDE_AXIS_GEOM2 = 0, GUIDE_AXIS_TABLE = 1 };
 enum { GUIDE_SELECT_TOPK = 0, GUIDE_SELECT_PARETO = 1 };
 enum { GUIDE_SIM_OK = 0, GUIDE_SIM_INFEASIBLE = 1, GUIDE_SIM_BAD_INPUT = 2, GUIDE_SIM_INTERNAL = 3 };
+enum { GUIDE_SCHED_SPLIT_FUSE = 0, GUIDE_SCHED_PREFILL_FIRST = 1 };
 
 #define GUIDE_MAX_MODELS 8
 #define GUIDE_MAX_HW 64
@@ -189,8 +190,16 @@ int guide_eval_sampled(guide_ctx *ctx, const guide_space *space, uint64_t seed, 
  * Each loop: jump to the next arrival if idle; admit FCFS while arrived, under
  * the sequence cap and with ceil((in+out)/kv_block) free KV blocks (reserved
  * for the request's lifetime; stop at the first that cannot enter); run one
- * pass = one decode token for every prefilled request + prompt chunks in
- * admission order under the remaining mbt budget; advance time by t_pass.
+ * pass; advance time by t_pass.  The pass depends on `scheduler`, the two
+ * framework behaviours the paper models (Inference Engine, Step 2):
+ *   GUIDE_SCHED_SPLIT_FUSE    one decode token for every prefilled request +
+ *                             prompt chunks in admission order under the
+ *                             remaining mbt budget (dynamic split flow);
+ *   GUIDE_SCHED_PREFILL_FIRST while admitted prompts wait: whole prompts only,
+ *                             in admission order, as many as fit mbt (the first
+ *                             always, even if longer), decoders pause; otherwise
+ *                             one decode token for every running request
+ *                             (dynamic batching without chunking).
  * Outputs (DEVICE, n_cfg each): nearest-rank p50 / p99 of TTFT, mean TPOT over
  * requests with n_out > 1, generated tokens / (last finish - first arrival),
  * status (GUIDE_SIM_INFEASIBLE when weights or one request do not fit,
@@ -208,8 +217,8 @@ typedef struct {
 
 size_t guide_simulate_workspace_bytes(uint32_t n_cfg, uint32_t n_requests);
 int guide_simulate(guide_ctx *ctx, const guide_grid *grid, const uint32_t *cfg_idx, const double *rate,
-                   uint32_t n_cfg, const guide_trace *trace, uint32_t time_model, const guide_sim_out *out,
-                   void *workspace, size_t workspace_bytes, void *stream);
+                   uint32_t n_cfg, const guide_trace *trace, uint32_t time_model, uint32_t scheduler,
+                   const guide_sim_out *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Selection over n rows of DEVICE columns (the engine keeps the configurations

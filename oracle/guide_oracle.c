@@ -362,6 +362,10 @@ int ora_eval_sweep_grid(const ora_grid *g, uint64_t first, uint64_t count, uint3
 /* ------------------------------------------------- continuous-batching simulation */
 
 enum { ORA_SIM_OK = 0, ORA_SIM_INFEASIBLE = 1 };
+/* Split-fuse: decoders first, then prompt chunks under the remaining token budget (FastGen-style dynamic
+ * split).  Prefill-first: while admitted prompts wait, a step runs whole prompts only (vLLM-style dynamic
+ * batching): as many, in admission order, as fit the token budget -- the first always -- and decoders pause. */
+enum { ORA_SCHED_SPLIT_FUSE = 0, ORA_SCHED_PREFILL_FIRST = 1 };
 
 typedef struct {
     double ttft_p50, ttft_p99, mean_tpot, tokens_s;
@@ -379,7 +383,7 @@ typedef struct {
  * min_free receives the smallest free-block count seen (as int64).
  */
 void ora_simulate(const ora_model *m, const ora_hw *hw, uint64_t p, uint64_t wbits, uint64_t blk,
-                  uint64_t mbt, uint64_t max_seqs, double rate, int time_model,
+                  uint64_t mbt, uint64_t max_seqs, double rate, int time_model, int scheduler,
                   uint32_t n, const double *arr_unit, const uint32_t *n_in, const uint32_t *n_out,
                   ora_sim_out *out, double *ttft, double *first, double *fin, int64_t *min_free_out) {
     double c_avail = hw->cap - ora_weight_bytes_gpu(m, p, wbits);
@@ -423,30 +427,53 @@ void ora_simulate(const ora_model *m, const ora_hw *hw, uint64_t p, uint64_t wbi
             prefilled[next] = 0; gen[next] = 0;
             ++next;
         }
-        /* 3. schedule: decoders first, then prompt chunks in admission order */
+        /* 3. schedule */
         double T = 0.0, Q = 0.0, K = 0.0, n_lm = 0.0;
         uint64_t n_dec = 0, n_chunks = 0;
-        for (a = 0; a < n_active; ++a) {
-            uint32_t r = active[a];
-            if (prefilled[r] == n_in[r]) {
-                double ctx = (double)n_in[r] + (double)gen[r];
-                ++n_dec; Q += ctx; K += ctx;
-            }
-        }
-        int64_t budget = (int64_t)mbt - (int64_t)n_dec;
-        T = (double)n_dec; n_lm = (double)n_dec;
+        int decoders_run = 1;
         memset(chunk, 0, sizeof(uint32_t) * n_active);   /* chunk[a]: prompt tokens given to active[a] this step */
-        for (a = 0; a < n_active; ++a) {
-            uint32_t r = active[a];
-            if (prefilled[r] < n_in[r] && budget > 0) {
-                int64_t c = (int64_t)(n_in[r] - prefilled[r]);
-                if (c > budget) c = budget;
-                budget -= c;
-                chunk[a] = (uint32_t)c;
-                double ctx = (double)prefilled[r] + (double)c;
-                T += (double)c; Q += (double)c * ctx; K += ctx;
-                if (prefilled[r] + c == n_in[r]) n_lm += 1.0;
-                ++n_chunks;
+        if (scheduler == ORA_SCHED_PREFILL_FIRST) {
+            /* whole prompts in admission order while they fit the budget (the first always) */
+            int64_t used = 0;
+            for (a = 0; a < n_active; ++a) {
+                uint32_t r = active[a];
+                if (prefilled[r] < n_in[r]) {
+                    if (n_chunks > 0 && used + (int64_t)n_in[r] > (int64_t)mbt) break;
+                    used += (int64_t)n_in[r];
+                    chunk[a] = n_in[r];
+                    double len = (double)n_in[r];
+                    T += len; Q += len * len; K += len; n_lm += 1.0;
+                    ++n_chunks;
+                }
+            }
+            if (n_chunks > 0) decoders_run = 0;
+        }
+        if (decoders_run) {
+            /* one token per decoder ... */
+            for (a = 0; a < n_active; ++a) {
+                uint32_t r = active[a];
+                if (prefilled[r] == n_in[r]) {
+                    double ctx = (double)n_in[r] + (double)gen[r];
+                    ++n_dec; Q += ctx; K += ctx;
+                }
+            }
+            T = (double)n_dec; n_lm = (double)n_dec;
+        }
+        if (scheduler == ORA_SCHED_SPLIT_FUSE) {
+            /* ... then prompt chunks in admission order under the remaining budget */
+            int64_t budget = (int64_t)mbt - (int64_t)n_dec;
+            for (a = 0; a < n_active; ++a) {
+                uint32_t r = active[a];
+                if (prefilled[r] < n_in[r] && budget > 0) {
+                    int64_t c = (int64_t)(n_in[r] - prefilled[r]);
+                    if (c > budget) c = budget;
+                    budget -= c;
+                    chunk[a] = (uint32_t)c;
+                    double ctx = (double)prefilled[r] + (double)c;
+                    T += (double)c; Q += (double)c * ctx; K += ctx;
+                    if (prefilled[r] + c == n_in[r]) n_lm += 1.0;
+                    ++n_chunks;
+                }
             }
         }
         /* 4. one engine step */
@@ -457,14 +484,14 @@ void ora_simulate(const ora_model *m, const ora_hw *hw, uint64_t p, uint64_t wbi
             uint32_t r = active[a];
             int was_decoding = (prefilled[r] == n_in[r]);
             if (was_decoding) {
-                gen[r] += 1;
+                if (decoders_run) gen[r] += 1;
             } else if (chunk[a] > 0) {
                 prefilled[r] += chunk[a];
                 if (prefilled[r] == n_in[r]) {
                     t_first[r] = now; gen[r] = 1; t_ttft[r] = now - arr[r];
                 }
             }
-            if (prefilled[r] == n_in[r] && gen[r] == n_out[r]) {
+            if (prefilled[r] == n_in[r] && gen[r] == n_out[r] && (decoders_run || !was_decoding)) {
                 t_fin[r] = now; free_blk += need[r]; ++n_done;
             } else {
                 active[w++] = r;
@@ -500,14 +527,15 @@ void ora_simulate(const ora_model *m, const ora_hw *hw, uint64_t p, uint64_t wbi
 }
 
 int ora_simulate_grid(const ora_grid *g, const uint32_t *cfg_idx, const double *rate, uint32_t n_cfg, int time_model,
+                      int scheduler,
                       uint32_t n, const double *arr_unit, const uint32_t *n_in, const uint32_t *n_out,
                       ora_sim_out *out) {
     uint32_t c;
     for (c = 0; c < n_cfg; ++c) {
         const ora_model *m; const ora_hw *hw; ora_knobs kn;
         if (ora_grid_decode(g, cfg_idx[c], &m, &hw, &kn)) return -1;
-        ora_simulate(m, hw, kn.p, kn.wbits, kn.blk, kn.mbt, kn.b, rate[c], time_model, n, arr_unit, n_in, n_out,
-                     &out[c], 0, 0, 0, 0);
+        ora_simulate(m, hw, kn.p, kn.wbits, kn.blk, kn.mbt, kn.b, rate[c], time_model, scheduler, n, arr_unit, n_in,
+                     n_out, &out[c], 0, 0, 0, 0);
     }
     return 0;
 }

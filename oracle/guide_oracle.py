@@ -19,6 +19,7 @@ GCC_FLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra", "
 
 ROOFLINE, ADDITIVE = 0, 1
 SIM_OK, SIM_INFEASIBLE = 0, 1
+SCHED_SPLIT_FUSE, SCHED_PREFILL_FIRST = 0, 1
 NO_INDEX = 2 ** 64 - 1
 
 
@@ -98,9 +99,10 @@ def lib():
                                              C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                              C.c_void_p]
         _lib.ora_simulate.argtypes = [C.POINTER(Model), C.POINTER(Hw), C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64,
-                                      C.c_uint64, C.c_double, C.c_int, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p,
-                                      C.POINTER(SimOut), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
-        _lib.ora_simulate_grid.argtypes = [C.POINTER(GridC), C.c_void_p, C.c_void_p, C.c_uint32, C.c_int, C.c_uint32,
+                                      C.c_uint64, C.c_double, C.c_int, C.c_int, C.c_uint32, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.POINTER(SimOut), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib.ora_simulate_grid.argtypes = [C.POINTER(GridC), C.c_void_p, C.c_void_p, C.c_uint32, C.c_int, C.c_int,
+                                           C.c_uint32,
                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib.ora_select_topk.argtypes = [C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -224,7 +226,8 @@ def eval_sweep_grid(g: Grid, e_c, e_b, first=0, count=None, time_model=ROOFLINE)
     return out
 
 
-def simulate(m, h, p, wbits, blk, mbt, max_seqs, rate, arr_unit, n_in, n_out, time_model=ROOFLINE, detail=False):
+def simulate(m, h, p, wbits, blk, mbt, max_seqs, rate, arr_unit, n_in, n_out, time_model=ROOFLINE, detail=False,
+             scheduler=SCHED_SPLIT_FUSE):
     arr_unit = np.ascontiguousarray(arr_unit, dtype=np.float64)
     n_in = np.ascontiguousarray(n_in, dtype=np.uint32); n_out = np.ascontiguousarray(n_out, dtype=np.uint32)
     n = len(arr_unit)
@@ -233,7 +236,7 @@ def simulate(m, h, p, wbits, blk, mbt, max_seqs, rate, arr_unit, n_in, n_out, ti
     mf = C.c_int64(0)
     if detail:
         ttft = np.empty(n); first = np.empty(n); fin = np.empty(n)
-    lib().ora_simulate(C.byref(m), C.byref(h), p, wbits, blk, mbt, max_seqs, float(rate), time_model, n,
+    lib().ora_simulate(C.byref(m), C.byref(h), p, wbits, blk, mbt, max_seqs, float(rate), time_model, scheduler, n,
                        _ptr(arr_unit), _ptr(n_in), _ptr(n_out), C.byref(o), _ptr(ttft), _ptr(first), _ptr(fin),
                        C.cast(C.byref(mf), C.c_void_p))
     res = dict(ttft_p50=o.ttft_p50, ttft_p99=o.ttft_p99, mean_tpot=o.mean_tpot, tokens_s=o.tokens_s,
@@ -243,12 +246,13 @@ def simulate(m, h, p, wbits, blk, mbt, max_seqs, rate, arr_unit, n_in, n_out, ti
     return res
 
 
-def simulate_grid(g: Grid, cfg_idx, rate, arr_unit, n_in, n_out, time_model=ROOFLINE):
+def simulate_grid(g: Grid, cfg_idx, rate, arr_unit, n_in, n_out, time_model=ROOFLINE, scheduler=SCHED_SPLIT_FUSE):
     cfg_idx = np.ascontiguousarray(cfg_idx, dtype=np.uint32); rate = np.ascontiguousarray(rate, dtype=np.float64)
     arr_unit = np.ascontiguousarray(arr_unit, dtype=np.float64)
     n_in = np.ascontiguousarray(n_in, dtype=np.uint32); n_out = np.ascontiguousarray(n_out, dtype=np.uint32)
     outs = (SimOut * len(cfg_idx))()
-    rc = lib().ora_simulate_grid(C.byref(g.c), _ptr(cfg_idx), _ptr(rate), len(cfg_idx), time_model, len(arr_unit),
+    rc = lib().ora_simulate_grid(C.byref(g.c), _ptr(cfg_idx), _ptr(rate), len(cfg_idx), time_model, scheduler,
+                                 len(arr_unit),
                                  _ptr(arr_unit), _ptr(n_in), _ptr(n_out), C.cast(outs, C.c_void_p))
     if rc:
         raise ValueError("oracle: index outside the grid")

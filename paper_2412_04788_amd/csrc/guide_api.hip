@@ -372,11 +372,13 @@ size_t guide_simulate_workspace_bytes(uint32_t n_cfg, uint32_t n_requests) {
 }
 
 int guide_simulate(guide_ctx *ctx, const guide_grid *grid, const uint32_t *cfg_idx, const double *rate, uint32_t n_cfg,
-                   const guide_trace *trace, uint32_t time_model, const guide_sim_out *out, void *workspace,
-                   size_t workspace_bytes, void *stream_) {
+                   const guide_trace *trace, uint32_t time_model, uint32_t scheduler, const guide_sim_out *out,
+                   void *workspace, size_t workspace_bytes, void *stream_) {
     if (!ctx) return GUIDE_E_ARG;
     hipStream_t stream = (hipStream_t)stream_;
     if (!time_model_ok(time_model)) return fail(ctx, GUIDE_E_ARG, "unknown time model %u", time_model);
+    if (scheduler != GUIDE_SCHED_SPLIT_FUSE && scheduler != GUIDE_SCHED_PREFILL_FIRST)
+        return fail(ctx, GUIDE_E_ARG, "unknown scheduler %u", scheduler);
     if (!trace || !out) return fail(ctx, GUIDE_E_ARG, "trace or out is NULL");
     if (trace->n == 0 || trace->n > GUIDE_MAX_REQUESTS)
         return fail(ctx, GUIDE_E_RANGE, "trace: need 1..%d requests", GUIDE_MAX_REQUESTS);
@@ -416,7 +418,8 @@ int guide_simulate(guide_ctx *ctx, const guide_grid *grid, const uint32_t *cfg_i
     rc = upload_tables(ctx, stream);
     if (rc) return rc;
     hipError_t e = launch_simulate(desc, ctx->dev_tab, ctx->dev_trace, trace->n, cfg_idx, rate, n_cfg,
-                        time_model == GUIDE_TIME_ADDITIVE, *out, workspace, stream);
+                        time_model == GUIDE_TIME_ADDITIVE, scheduler == GUIDE_SCHED_PREFILL_FIRST, *out, workspace,
+                        stream);
     if (e != hipSuccess) return hip_fail(ctx, e, "simulate launch");
     return GUIDE_OK;
 }

@@ -141,7 +141,7 @@ __global__ __launch_bounds__(kBlock) void sim_order_scatter_kernel(uint32_t n_cf
 
 __global__ __launch_bounds__(kKeyBins) void sim_order_clear_kernel(SimWs ws) { ws.bins[threadIdx.x] = 0; }
 
-template <bool ADDITIVE>
+template <bool ADDITIVE, bool PREFILL_FIRST>
 __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const DevTables *__restrict__ tab,
                                                              const TraceDev *__restrict__ trace, uint32_t n_req,
                                                              const uint32_t *__restrict__ cfg_idx,
@@ -201,7 +201,7 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
 
     double now = 0.0, sum_tpot = 0.0, max_fin = -INFINITY;
     uint32_t next = 0, pf_head = 0, pf_done = 0, n_dec = 0, heap_n = 0, n_done = 0, n_tpot = 0;
-    uint64_t s_ctx = 0, step = 0, n_rs = 0;
+    uint64_t s_ctx = 0, step = 0, dstep = 0, n_rs = 0;   // dstep counts the steps in which decoders ran
     long long free_blk = n_blk;
     uint32_t status = GUIDE_SIM_OK;
     double arr_next = s.arrival[0] / rate;   // arrival time of request `next`
@@ -221,12 +221,13 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
             const double T = (double)n_dec;
             double ctx = (double)s_ctx;                       // integers below 2^53: exact in fp64
             uint64_t run = 0;
-            while (run < max_run && step + run + 1 < stop && !(arr_stop <= now)) {
+            while (run < max_run && dstep + run + 1 < stop && !(arr_stop <= now)) {
                 now += fma(tc.L, kept_base + attention<ADDITIVE>(tc, T, ctx, ctx), kept_lm);
                 ctx += T;
                 ++run;
             }
             step += run;
+            dstep += run;
             n_rs += run * n_dec;
             s_ctx += run * n_dec;
         }
@@ -242,10 +243,30 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
             ++n_active;
             arr_next = next < n_req ? s.arrival[next] / rate : INFINITY;
         }
-        // 3. schedule: one token per decoder, then prompt chunks in admission order
-        double T = (double)n_dec, Q = (double)s_ctx, K = (double)s_ctx, n_lm = (double)n_dec;
+        // 3. schedule.  Split-fuse: one token per decoder, then prompt chunks in admission order under
+        // the remaining budget.  Prefill-first: while prompts wait, whole prompts only (as many as fit the
+        // budget, the first always) and the decoders pause.
+        const bool decoders_run = !(PREFILL_FIRST && pf_head < next);
+        double T = 0.0, Q = 0.0, K = 0.0, n_lm = 0.0;
+        if (decoders_run) {
+            T = (double)n_dec; Q = (double)s_ctx; K = (double)s_ctx; n_lm = (double)n_dec;
+        }
         long long budget = (long long)mbt - (long long)n_dec;
         uint32_t h = pf_head, done = pf_done, chunks = 0;
+        if (PREFILL_FIRST) {
+            long long used = 0;
+            while (h < next && (chunks == 0 || used + (long long)s.n_in[h] <= (long long)mbt)) {
+                const double len = (double)s.n_in[h];
+                used += (long long)s.n_in[h];
+                T += len;
+                Q = fma(len, len, Q);
+                K += len;
+                n_lm += 1.0;
+                ++chunks;
+                ++h;
+            }
+            budget = 0;
+        }
         while (h < next && budget > 0) {
             const long long rem = (long long)(s.n_in[h] - done);
             const long long ch = rem < budget ? rem : budget;
@@ -277,10 +298,13 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
             now += pass_time<ADDITIVE>(tc, T, Q, K, n_lm);
         }
         ++step;
-        n_rs += n_dec + chunks;
+        n_rs += (decoders_run ? n_dec : 0u) + chunks;
         // 5. book-keeping: decoders emitted a token; those at their last one leave
-        s_ctx += n_dec;
-        while (heap_n > 0 && (top.key >> 10) == step) {
+        if (decoders_run) {
+            ++dstep;
+            s_ctx += n_dec;
+        }
+        while (decoders_run && heap_n > 0 && (top.key >> 10) == dstep) {
             const uint32_t r = (uint32_t)(top.key & 1023u);
             const double r_first = top.first;
             // pop: the last node sinks from the root
@@ -330,7 +354,7 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
                 ++n_dec;
                 s_ctx += (uint64_t)r_in + 1;
                 // push (finishing step, request): the new node rises from the end
-                const HeapEnt e = {((step + r_out - 1) << 10) | r, now};
+                const HeapEnt e = {((dstep + r_out - 1) << 10) | r, now};
                 uint32_t i = heap_n++;
                 while (i > 0) {
                     const uint32_t par = (i - 1) >> 2;
@@ -397,7 +421,7 @@ size_t simulate_workspace_bytes(uint32_t n_cfg, uint32_t n_req) {
 
 hipError_t launch_simulate(const GridDesc &g, const DevTables *tab, const TraceDev *trace, uint32_t n_req,
                            const uint32_t *cfg_idx, const double *rate, uint32_t n_cfg, bool additive,
-                           const guide_sim_out &out, void *ws_, hipStream_t stream) {
+                           bool prefill_first, const guide_sim_out &out, void *ws_, hipStream_t stream) {
     const SimWs ws = sim_ws(ws_, n_cfg, n_req);
     // Lanes wait for the longest run of their wave before the next general step, so runs are capped:
     // 64 steps measured best among 4..128 and unbounded on the 65 536-configuration mix.
@@ -411,10 +435,15 @@ hipError_t launch_simulate(const GridDesc &g, const DevTables *tab, const TraceD
         hipLaunchKernelGGL(sim_order_count_kernel<false>, ogrid, oblock, 0, stream, g, tab, trace, n_req, cfg_idx, rate, n_cfg, ws);
     hipLaunchKernelGGL(sim_order_scan_kernel, dim3(1), dim3(kKeyBins), 0, stream, ws);
     hipLaunchKernelGGL(sim_order_scatter_kernel, ogrid, oblock, 0, stream, n_cfg, ws);
-    if (additive)
-        hipLaunchKernelGGL(simulate_kernel<true>, grid, block, 0, stream, g, tab, trace, n_req, cfg_idx, rate, n_cfg, out, ws, max_run);
-    else
-        hipLaunchKernelGGL(simulate_kernel<false>, grid, block, 0, stream, g, tab, trace, n_req, cfg_idx, rate, n_cfg, out, ws, max_run);
+#define GUIDE_SIM(A, P)                                                                                          \
+    hipLaunchKernelGGL((simulate_kernel<A, P>), grid, block, 0, stream, g, tab, trace, n_req, cfg_idx, rate, n_cfg, \
+                       out, ws, max_run)
+    if (additive) {
+        if (prefill_first) GUIDE_SIM(true, true); else GUIDE_SIM(true, false);
+    } else {
+        if (prefill_first) GUIDE_SIM(false, true); else GUIDE_SIM(false, false);
+    }
+#undef GUIDE_SIM
     hipLaunchKernelGGL(percentile_kernel, dim3(n_cfg), dim3(kPctBlock), 0, stream, (const double *)ws.ttft, n_req, out);
     return hipGetLastError();
 }

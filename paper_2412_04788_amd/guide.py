@@ -19,6 +19,7 @@ TIME_ROOFLINE, TIME_ADDITIVE = 0, 1
 AXIS_GEOM2, AXIS_TABLE = 0, 1
 SELECT_TOPK, SELECT_PARETO = 0, 1
 SIM_OK, SIM_INFEASIBLE, SIM_BAD_INPUT, SIM_INTERNAL = 0, 1, 2, 3
+SCHED_SPLIT_FUSE, SCHED_PREFILL_FIRST = 0, 1
 NO_INDEX = 2 ** 64 - 1
 MAX_CONSTRAINTS = 4
 
@@ -131,8 +132,8 @@ def load() -> C.CDLL:
         lib.guide_simulate_workspace_bytes.argtypes = [C.c_uint32, C.c_uint32]
         lib.guide_simulate_workspace_bytes.restype = C.c_size_t
         lib.guide_simulate.argtypes = [C.c_void_p, C.POINTER(CGrid), C.c_void_p, C.c_void_p, C.c_uint32,
-                                       C.POINTER(CTrace), C.c_uint32, C.POINTER(CSimOut), C.c_void_p, C.c_size_t,
-                                       C.c_void_p]
+                                       C.POINTER(CTrace), C.c_uint32, C.c_uint32, C.POINTER(CSimOut), C.c_void_p,
+                                       C.c_size_t, C.c_void_p]
         lib.guide_select_workspace_bytes.argtypes = [C.POINTER(CSelectSpec), C.c_uint64]
         lib.guide_select_workspace_bytes.restype = C.c_size_t
         lib.guide_select.argtypes = [C.c_void_p, C.POINTER(CSelectSpec), C.c_uint64, C.POINTER(CSelectOut),
@@ -300,7 +301,7 @@ class Context:
         return self._lib.guide_simulate_workspace_bytes(n_cfg, n_requests)
 
     def simulate(self, grid: GridArg, cfg_idx, rate, trace, out: dict, workspace, time_model: int = TIME_ROOFLINE,
-                 stream=None):
+                 scheduler: int = SCHED_SPLIT_FUSE, stream=None):
         """cfg_idx (u32) / rate (f64): CUDA tensors; trace: (arrival_unit, n_in, n_out) host arrays."""
         arr = np.ascontiguousarray(trace[0], dtype=np.float64)
         n_in = np.ascontiguousarray(trace[1], dtype=np.uint32)
@@ -308,7 +309,7 @@ class Context:
         ct = CTrace(len(arr), arr.ctypes.data, n_in.ctypes.data, n_out.ctypes.data)
         co = CSimOut(*[_dev_ptr(out.get(k)) for k in SIM_COLUMNS])
         self._invoke(self._lib.guide_simulate, self._h, _Ref(grid.c, grid), _dev_ptr(cfg_idx), _dev_ptr(rate),
-                     cfg_idx.numel(), _Ref(ct, (arr, n_in, n_out)), time_model, _Ref(co),
+                     cfg_idx.numel(), _Ref(ct, (arr, n_in, n_out)), time_model, scheduler, _Ref(co),
                      _dev_ptr(workspace), workspace.numel() * workspace.element_size(), _stream_ptr(stream))
 
     def _select_spec(self, mode, objective, objective_y, feasible, constraints, group, n_groups, k):

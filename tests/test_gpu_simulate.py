@@ -17,7 +17,7 @@ def torch_cuda():
     return torch
 
 
-def _run(torch, ctx, grid, cfg_idx, rate, trace, time_model=0):
+def _run(torch, ctx, grid, cfg_idx, rate, trace, time_model=0, scheduler=0):
     n_cfg = len(cfg_idx)
     out = {k: torch.full((n_cfg,), -1.0, dtype=torch.float64, device="cuda") for k in FLOATS}
     out["status"] = torch.full((n_cfg,), -1, dtype=torch.int32, device="cuda")
@@ -27,7 +27,7 @@ def _run(torch, ctx, grid, cfg_idx, rate, trace, time_model=0):
     d_idx = torch.from_numpy(np.ascontiguousarray(cfg_idx).view(np.int32)).cuda()
     d_rate = torch.from_numpy(np.ascontiguousarray(rate)).cuda()
     ctx.simulate(bridge.gpu_grid(grid), d_idx, d_rate, (trace.arrival_unit, trace.n_in, trace.n_out), out, ws,
-                 time_model=time_model)
+                 time_model=time_model, scheduler=scheduler)
     torch.cuda.synchronize()
     res = {k: bridge.to_np(out[k]) for k in FLOATS}
     res["status"] = bridge.to_np(out["status"], np.uint32)
@@ -74,6 +74,30 @@ def test_full_trace_2048_configs(ora, torch_cuda):
     assert got["n_request_steps"][ok].min() >= tr.n_out.sum()
 
 
+def test_prefill_first_scheduler(ora, torch_cuda):
+    """The whole-prompt, decoders-pause variant on the full trace and on a tight pool."""
+    torch = torch_cuda
+    g = wl.grid_full()
+    ctx = bridge.gpu_context(g)
+    tr = wl.request_trace()
+    idx, rate = wl.sim_configs(g, 1024, seed=wl.SEED + 9)
+    got = _run(torch, ctx, g, idx, rate, tr, scheduler=1)
+    exp = ora.simulate_grid(bridge.ora_grid(g), idx, rate, tr.arrival_unit, tr.n_in, tr.n_out, scheduler=1)
+    _compare(got, exp)
+    ok = exp["status"] == 0
+    assert ok.sum() > 500
+    assert np.all(got["n_request_steps"][ok] == tr.n_out.sum())     # one prompt pass + out - 1 decode tokens each
+    split = _run(torch, ctx, g, idx, rate, tr, scheduler=0)
+    assert np.any(split["ttft_p99"][ok] != got["ttft_p99"][ok])
+    for n_req, n_cfg, tm in [(1, 5, 0), (50, 70, 1)]:
+        tr2 = wl.request_trace(n=n_req, seed=3)
+        idx2, rate2 = wl.sim_configs(g, n_cfg, seed=77)
+        got = _run(torch, ctx, g, idx2, rate2, tr2, time_model=tm, scheduler=1)
+        exp = ora.simulate_grid(bridge.ora_grid(g), idx2, rate2, tr2.arrival_unit, tr2.n_in, tr2.n_out, time_model=tm,
+                                scheduler=1)
+        _compare(got, exp)
+
+
 def test_tight_pool_odd_values_additive(ora, torch_cuda):
     """Head-of-line blocking on a tight KV pool, odd TP / block / budget values, one-token
     generations, link latency, additive time model."""
@@ -90,9 +114,10 @@ def test_tight_pool_odd_values_additive(ora, torch_cuda):
     tr = wl.Trace(tr.arrival_unit, tr.n_in, n_out)
     idx = np.arange(g.size, dtype=np.uint32)
     rate = np.array([3.0 if i % 2 else 50.0 for i in range(g.size)])
-    for tm in (0, 1):
-        got = _run(torch, ctx, g, idx, rate, tr, time_model=tm)
-        exp = ora.simulate_grid(bridge.ora_grid(g), idx, rate, tr.arrival_unit, tr.n_in, tr.n_out, time_model=tm)
+    for tm, sched in ((0, 0), (1, 0), (0, 1)):
+        got = _run(torch, ctx, g, idx, rate, tr, time_model=tm, scheduler=sched)
+        exp = ora.simulate_grid(bridge.ora_grid(g), idx, rate, tr.arrival_unit, tr.n_in, tr.n_out, time_model=tm,
+                                scheduler=sched)
         _compare(got, exp)
 
 

@@ -581,3 +581,68 @@ def test_sampled_reductions_against_columns(ora):
     b = ora.eval_sampled(sp, wl.SEED, 100 + n // 2, n // 2, wl.BUCKET_EDGES, wl.TTFT_CAP_S)
     np.testing.assert_array_equal(a["hist"] + b["hist"], r["hist"])
     assert a["feasible_count"] + b["feasible_count"] == r["feasible_count"]
+
+
+# ------------------------------------------------ prefill-first scheduler variant
+
+@pytest.mark.parametrize("n_in,n_out,mbt", [(700, 40, 2048), (5000, 17, 2048), (2048, 1, 2048)])
+def test_prefill_first_single_request(ora, n_in, n_out, mbt):
+    """One request: the whole prompt runs in one pass (no chunking even beyond the budget), then
+    out - 1 decode passes."""
+    m = wl.DENSE_34B
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+    arr, ins, outs = _one_req(n_in, n_out)
+    s = ora.simulate(om, oh, 2, 8, 16, mbt, 4, 1.0, arr, ins, outs, detail=True, scheduler=ora.SCHED_PREFILL_FIRST)
+    t = ora.pass_detail(om, oh, 2, 8, n_in, n_in * n_in, n_in, 1)["t_pass"]
+    assert s["ttft"][0] == t
+    for j in range(1, n_out):
+        t += ora.pass_detail(om, oh, 2, 8, 1, n_in + j, n_in + j, 1)["t_pass"]
+    assert s["fin"][0] == pytest.approx(t, rel=1e-14)
+    assert s["n_steps"] == n_out == s["n_request_steps"]
+
+
+def test_prefill_first_two_requests_by_hand(ora):
+    m = wl.DENSE_7B
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+    ins = np.array([100, 100], dtype=np.uint32); outs = np.array([3, 3], dtype=np.uint32)
+    one = ora.pass_detail(om, oh, 1, 16, 100, 100 * 100, 100, 1)["t_pass"]
+    # budget 150: the prompts run in two prefill-only steps; the first request's decoding waits for the second
+    s = ora.simulate(om, oh, 1, 16, 16, 150, 2, 1.0, np.zeros(2), ins, outs, detail=True,
+                     scheduler=ora.SCHED_PREFILL_FIRST)
+    assert s["ttft"][0] == one and s["ttft"][1] == one + one
+    t = one + one
+    for ctx in (101, 102):
+        t += ora.pass_detail(om, oh, 1, 16, 2, 2 * ctx, 2 * ctx, 2)["t_pass"]
+    assert s["fin"][0] == s["fin"][1] == t
+    assert s["n_steps"] == 4 and s["n_request_steps"] == 6
+    # budget 250: both prompts share one pass
+    s = ora.simulate(om, oh, 1, 16, 16, 250, 2, 1.0, np.zeros(2), ins, outs, detail=True,
+                     scheduler=ora.SCHED_PREFILL_FIRST)
+    both = ora.pass_detail(om, oh, 1, 16, 200, 2 * 100 * 100, 200, 2)["t_pass"]
+    assert s["ttft"][0] == s["ttft"][1] == both and s["n_steps"] == 3
+    # an arrival during decoding interrupts it with a prefill-only step
+    s = ora.simulate(om, oh, 1, 16, 16, 250, 2, 1.0, np.array([0.0, 1.5 * one]), ins, outs, detail=True,
+                     scheduler=ora.SCHED_PREFILL_FIRST)
+    d1 = ora.pass_detail(om, oh, 1, 16, 1, 101, 101, 1)["t_pass"]
+    assert s["ttft"][0] == one
+    assert s["first"][1] == pytest.approx(one + d1 + one, rel=1e-15)      # decode step, then the second prompt
+    assert s["n_request_steps"] == 6
+
+
+def test_prefill_first_invariants_and_relation_to_split_fuse(ora):
+    m = wl.DENSE_7B
+    om = bridge.ora_model(m)
+    oh = bridge.ora_hw(wl.Hardware(1e15, 5e12, 40 * wl.GIB, 4e11))
+    tr = wl.request_trace(n=200)
+    for max_seqs, rate, mbt in [(1, 4.0, 8192), (8, 16.0, 2048), (64, 64.0, 8192), (256, 64.0, 512)]:
+        a = ora.simulate(om, oh, 1, 16, 16, mbt, max_seqs, rate, tr.arrival_unit, tr.n_in, tr.n_out, detail=True,
+                         scheduler=ora.SCHED_PREFILL_FIRST)
+        assert a["status"] == ora.SIM_OK and a["min_free"] >= 0
+        assert a["n_request_steps"] == int(tr.n_out.sum())      # one prompt pass + out - 1 decode tokens each
+        assert np.all(np.diff(a["first"]) >= 0)
+        b = ora.simulate(om, oh, 1, 16, 16, mbt, max_seqs, rate, tr.arrival_unit, tr.n_in, tr.n_out, detail=True)
+        if max_seqs == 1:       # one request at a time, prompts within the budget: the two schedulers coincide
+            np.testing.assert_array_equal(a["fin"], b["fin"])
+            np.testing.assert_array_equal(a["ttft"], b["ttft"])
+        else:
+            assert not np.array_equal(a["fin"], b["fin"])
