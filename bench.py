@@ -233,16 +233,24 @@ def cpu_baseline(g, np, wl):
     """The oracle as it stands, single thread, on 96 blocks of 1024 rows spread evenly over the grid."""
     from oracle import guide_oracle as ora
     og = ora.Grid(wl.models_array(g.models), wl.hw_array(g.hws), [a.array() for a in g.axes])
-    blocks, rows = 96, 1024
+    blocks, rows = 192, 1024
     firsts = np.linspace(0, g.size - rows, blocks).astype(np.int64)
     ora.eval_grid(og, 0, 16)
     t0 = time.perf_counter()
     for f in firsts:
         ora.eval_grid(og, int(f), rows)
     dt_ = time.perf_counter() - t0
+    # the serving simulation on the first 512 of the benchmark's 65 536 configurations
+    idx, rate = wl.sim_configs(g, 65536)
+    tr = wl.request_trace()
+    t0 = time.perf_counter()
+    sim = ora.simulate_grid(og, idx[:512], rate[:512], tr.arrival_unit, tr.n_in, tr.n_out)
+    dt_sim = time.perf_counter() - t0
     return {"value": blocks * rows / dt_, "unit": "configs/s", "cores": 1, "kind": "oracle",
             "sample": f"{blocks} blocks of {rows} consecutive configurations spread evenly over the 1900800-row grid "
-                      f"(eval_grid only), {dt_:.1f} s", "host_cores_available": os.cpu_count()}
+                      f"(eval_grid only), {dt_:.1f} s", "host_cores_available": os.cpu_count(),
+            "simulate_request_steps_per_s": float(sim["n_request_steps"].sum()) / dt_sim,
+            "simulate_sample": f"first 512 of the 65536 simulated configurations x 1024 requests, {dt_sim:.1f} s"}
 
 
 if __name__ == "__main__":
