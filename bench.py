@@ -184,6 +184,15 @@ def extra_timings(ctx, gg, g, torch, np, guide, wl, n_sampled=1 << 28, n_sim=655
     extra["sweep"] = {"evaluations_per_s": n * 64 / s, "configs_per_s": n / s, "seconds": s, "samples": 64}
     del st
 
+    ex = dict(s_max=torch.empty(n, dtype=torch.int32, device="cuda"),
+              dp_max=torch.empty(n, dtype=torch.int32, device="cuda"),
+              max_parallelism=torch.empty(n, dtype=torch.int64, device="cuda"),
+              cluster_tok_s=torch.empty(n, dtype=torch.float64, device="cuda"),
+              paper_tok_s=torch.empty(n, dtype=torch.float64, device="cuda"))
+    s = _timed(torch, lambda: ctx.eval_extras(gg, 0, n, 8, ex), reps=5)
+    extra["cluster_extras"] = {"configs_per_s": n / s, "seconds": s, "n_gpus": 8, "bytes_per_config": 32}
+    del ex
+
     sp = wl.sample_space()
     space = {f: getattr(sp, f) for f in ("heads", "peak", "bw", "cap", "batch", "s_in", "s_out", "tp", "wbits",
                                          "kv_block", "mbt", "kv_choices", "layers_lo", "layers_n", "ffn_lo_x2",

@@ -141,6 +141,30 @@ int guide_eval_grid(guide_ctx *ctx, const guide_grid *grid, uint64_t first, uint
                     const guide_metrics *out, const guide_stats *stats, void *stream);
 
 /*
+ * Cluster-level columns for configurations [first, first + count) under a budget
+ * of n_gpus identical GPUs (DEVICE, count elements each, NULL = skip):
+ *   s_max            longest sequence that fits the batch: floor(available /
+ *                    (b * KV bytes per token)), the paper's S_max = floor(C_available
+ *                    / (2 N H B kv)) (Dynamic Sequence Length Adjustment); 0 when
+ *                    the weights do not fit; saturates at UINT32_MAX;
+ *   dp_max           data-parallel replicas: floor(n_gpus / tp);
+ *   max_parallelism  dp_max * b_max (Inference Engine Step 1: Maximum Parallelism =
+ *                    DP x available memory / kv per request);
+ *   cluster_tok_s    dp_max * decode throughput (replicas are independent);
+ *   paper_tok_s      the paper's multi-GPU throughput N * T_single / (1 + log2 P_TP)
+ *                    with N = dp_max * tp GPUs in use, P_TP = tp and T_single the
+ *                    decode throughput of the same configuration at tp = 1.
+ */
+typedef struct {
+    uint32_t *s_max, *dp_max;
+    uint64_t *max_parallelism;
+    double *cluster_tok_s, *paper_tok_s;
+} guide_extras;
+
+int guide_eval_extras(guide_ctx *ctx, const guide_grid *grid, uint64_t first, uint64_t count, uint32_t n_gpus,
+                      uint32_t time_model, const guide_extras *out, void *stream);
+
+/*
  * Random-sampled space.  Candidate i draws fourteen 16-bit fields from one
  * Philox4x64-10 block (counter (i,0,0,0), key (seed,0)); field u picks entry
  * (u * n) >> 16 of an n-entry table.  All table pointers are HOST; the three

@@ -262,6 +262,38 @@ void ora_eval(const ora_model *m, const ora_hw *hw, const ora_knobs *kn,
     ora_memory(m, hw, kn, 0, 0, &out->feasible, &out->b_max);
 }
 
+/* --------------------------------------------------------- cluster-level extras */
+
+typedef struct {
+    uint32_t s_max;            /* longest sequence that fits: floor(available / (2 N H B kv)), per GPU form */
+    uint32_t dp_max;           /* data-parallel replicas under the GPU budget: floor(n_gpus / tp) */
+    uint64_t max_parallelism;  /* DP x (available memory / kv per request) = dp_max * b_max */
+    double cluster_tok_s;      /* replicas are independent: dp_max x decode throughput */
+    double paper_tok_s;        /* N T_single / (1 + log2 P_TP) with N = dp_max * tp GPUs in use, P_TP = tp */
+} ora_extras;
+
+/* Inference Engine Step 1 (maximum parallelism, max batch = parallelism / DP), Step 2 (multi-GPU
+ * throughput heuristic), Model Analyzer "Dynamic Sequence Length Adjustment" (S_max). */
+void ora_eval_extras(const ora_model *m, const ora_hw *hw, const ora_knobs *kn, uint32_t n_gpus, int time_model,
+                     ora_extras *out) {
+    ora_metrics r, r1;
+    ora_knobs k1 = *kn;
+    k1.p = 1;
+    ora_eval(m, hw, kn, 1.0, 1.0, time_model, &r);
+    ora_eval(m, hw, &k1, 1.0, 1.0, time_model, &r1);     /* the same candidate on one GPU */
+    double c_avail = hw->cap - ora_weight_bytes_gpu(m, kn->p, kn->wbits);
+    if (c_avail > 0.0) {
+        double q = floor(c_avail / ((double)kn->b * ora_kv_bytes_token(m, kn->p)));
+        out->s_max = q >= 4294967295.0 ? 4294967295u : (uint32_t)q;
+    } else {
+        out->s_max = 0;
+    }
+    out->dp_max = (uint32_t)(n_gpus / kn->p);
+    out->max_parallelism = (uint64_t)out->dp_max * (uint64_t)r.b_max;
+    out->cluster_tok_s = (double)out->dp_max * r.decode_tok_s;
+    out->paper_tok_s = ((double)out->dp_max * (double)kn->p) * r1.decode_tok_s / (1.0 + log2((double)kn->p));
+}
+
 /* ----------------------------------------------------------------------- grid */
 
 typedef struct {
@@ -307,6 +339,20 @@ int ora_eval_grid(const ora_grid *g, uint64_t first, uint64_t count, double e_c,
         if (cost) cost[i] = r.cost;
         if (b_max) b_max[i] = r.b_max;
         if (feasible) feasible[i] = (uint8_t)r.feasible;
+    }
+    return 0;
+}
+
+int ora_eval_extras_grid(const ora_grid *g, uint64_t first, uint64_t count, uint32_t n_gpus, int time_model,
+                         uint32_t *s_max, uint32_t *dp_max, uint64_t *max_par, double *cluster_tok_s,
+                         double *paper_tok_s) {
+    uint64_t i;
+    for (i = 0; i < count; ++i) {
+        const ora_model *m; const ora_hw *hw; ora_knobs kn; ora_extras e;
+        if (ora_grid_decode(g, first + i, &m, &hw, &kn)) return -1;
+        ora_eval_extras(m, hw, &kn, n_gpus, time_model, &e);
+        s_max[i] = e.s_max; dp_max[i] = e.dp_max; max_par[i] = e.max_parallelism;
+        cluster_tok_s[i] = e.cluster_tok_s; paper_tok_s[i] = e.paper_tok_s;
     }
     return 0;
 }

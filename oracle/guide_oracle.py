@@ -92,6 +92,8 @@ def lib():
         _lib.ora_grid_size.restype = C.c_uint64
         _lib.ora_eval_grid.argtypes = [C.POINTER(GridC), C.c_uint64, C.c_uint64, C.c_double, C.c_double, C.c_int] + \
                                       [C.c_void_p] * 7
+        _lib.ora_eval_extras_grid.argtypes = [C.POINTER(GridC), C.c_uint64, C.c_uint64, C.c_uint32, C.c_int] + \
+                                             [C.c_void_p] * 5
         _lib.ora_eval_sweep.argtypes = [C.POINTER(Model), C.POINTER(Hw), C.POINTER(Knobs), C.c_uint32,
                                         C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
                                         C.POINTER(C.c_double), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
@@ -209,6 +211,19 @@ def eval_grid(g: Grid, first=0, count=None, e_c=1.0, e_b=1.0, time_model=ROOFLIN
     if rc:
         raise ValueError("oracle: index outside the grid")
     return cols
+
+
+def eval_extras_grid(g: Grid, n_gpus, first=0, count=None, time_model=ROOFLINE):
+    count = g.size - first if count is None else count
+    out = dict(s_max=np.empty(count, dtype=np.uint32), dp_max=np.empty(count, dtype=np.uint32),
+               max_parallelism=np.empty(count, dtype=np.uint64), cluster_tok_s=np.empty(count),
+               paper_tok_s=np.empty(count))
+    rc = lib().ora_eval_extras_grid(C.byref(g.c), first, count, n_gpus, time_model,
+                                    *[_ptr(out[k]) for k in ("s_max", "dp_max", "max_parallelism", "cluster_tok_s",
+                                                             "paper_tok_s")])
+    if rc:
+        raise ValueError("oracle: index outside the grid")
+    return out
 
 
 def eval_sweep_grid(g: Grid, e_c, e_b, first=0, count=None, time_model=ROOFLINE):

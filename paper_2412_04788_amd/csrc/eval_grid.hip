@@ -316,6 +316,46 @@ __global__ __launch_bounds__(kBlock) void eval_sweep_kernel(GridDesc g, const De
     }
 }
 
+// Cluster-level columns under a GPU budget (one index per lane; not on the timed path).
+template <bool ADDITIVE>
+__global__ __launch_bounds__(kBlock) void eval_extras_kernel(GridDesc g, const DevTables *__restrict__ tab,
+                                                             uint32_t first, uint32_t count, uint32_t n_gpus,
+                                                             guide_extras out) {
+    __shared__ GridLds s;
+    stage_grid_tables(s, g, tab);
+    __syncthreads();
+    for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < count; i += gridDim.x * kBlock) {
+        const Candidate c = decode_index(s, g, first + i);
+        const HwRecip hw = s.hw[c.hw];
+        const Coef cf = make_coef(s.models[c.model], c.kn.p, c.kn.wbits);
+        const uint32_t dp = n_gpus / c.kn.p;
+        const double n = (double)(c.kn.s_out - 1);
+        double tok_s = 0.0, tok_s1 = 0.0;
+        if (c.kn.s_out > 1 && (out.cluster_tok_s || out.paper_tok_s)) {
+            const TimeCoef tc = make_time_coef(cf, hw.r_peak, hw.r_bw, hw.r_link, hw.lat);
+            tok_s = (double)c.kn.b * n / decode_time<ADDITIVE>(tc, c.kn.b, c.kn.s_in, c.kn.s_out - 1);
+            if (out.paper_tok_s) {
+                const Coef c1 = make_coef(s.models[c.model], 1u, c.kn.wbits);      // the same candidate on one GPU
+                const TimeCoef t1 = make_time_coef(c1, hw.r_peak, hw.r_bw, hw.r_link, hw.lat);
+                tok_s1 = (double)c.kn.b * n / decode_time<ADDITIVE>(t1, c.kn.b, c.kn.s_in, c.kn.s_out - 1);
+            }
+        }
+        const double c_avail = hw.cap - cf.w_gpu;
+        if (out.s_max) {
+            const double q = floor(c_avail / ((double)c.kn.b * cf.kv_tok));
+            out.s_max[i] = !(c_avail > 0.0) ? 0u : (q >= 4294967295.0 ? 4294967295u : (uint32_t)q);
+        }
+        if (out.dp_max) out.dp_max[i] = dp;
+        if (out.max_parallelism) {
+            const MemResult m = memory_check(cf, hw.cap, c.kn.b, c.kn.s_in, c.kn.s_out, c.kn.blk);
+            out.max_parallelism[i] = (uint64_t)dp * (uint64_t)m.b_max;
+        }
+        if (out.cluster_tok_s) out.cluster_tok_s[i] = (double)dp * tok_s;
+        if (out.paper_tok_s)
+            out.paper_tok_s[i] = ((double)dp * (double)c.kn.p) * tok_s1 / (1.0 + log2((double)c.kn.p));
+    }
+}
+
 static uint32_t blocks_for(uint32_t count) {
     const uint32_t need = (count + kBlock - 1) / kBlock;
     const uint32_t cap = kNumCU * 8;
@@ -361,6 +401,16 @@ hipError_t launch_eval_grid(const GridDesc &g, const DevTables *tab, uint32_t fi
         hipLaunchKernelGGL(eval_grid_kernel<true>, grid, block, 0, stream, g, tab, first, count, re_c, re_b, out);
     else
         hipLaunchKernelGGL(eval_grid_kernel<false>, grid, block, 0, stream, g, tab, first, count, re_c, re_b, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_eval_extras(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, uint32_t n_gpus,
+                              bool additive, const guide_extras &out, hipStream_t stream) {
+    const dim3 grid(blocks_for(count)), block(kBlock);
+    if (additive)
+        hipLaunchKernelGGL(eval_extras_kernel<true>, grid, block, 0, stream, g, tab, first, count, n_gpus, out);
+    else
+        hipLaunchKernelGGL(eval_extras_kernel<false>, grid, block, 0, stream, g, tab, first, count, n_gpus, out);
     return hipGetLastError();
 }
 

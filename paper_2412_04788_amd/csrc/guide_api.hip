@@ -269,6 +269,31 @@ int guide_eval_grid(guide_ctx *ctx, const guide_grid *grid, uint64_t first, uint
     return GUIDE_OK;
 }
 
+int guide_eval_extras(guide_ctx *ctx, const guide_grid *grid, uint64_t first, uint64_t count, uint32_t n_gpus,
+                      uint32_t time_model, const guide_extras *out, void *stream_) {
+    if (!ctx) return GUIDE_E_ARG;
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!time_model_ok(time_model)) return fail(ctx, GUIDE_E_ARG, "unknown time model %u", time_model);
+    if (!out) return fail(ctx, GUIDE_E_ARG, "guide_extras is NULL");
+    if (n_gpus == 0) return fail(ctx, GUIDE_E_ARG, "n_gpus is zero");
+    GridDesc desc;
+    uint64_t size = 0;
+    int rc = prepare_grid(ctx, grid, &desc, &size);
+    if (rc) return rc;
+    if (first > size || count > size - first)
+        return fail(ctx, GUIDE_E_RANGE, "range [%llu, +%llu) outside the grid of %llu", (unsigned long long)first,
+                    (unsigned long long)count, (unsigned long long)size);
+    if (count == 0) return GUIDE_OK;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
+    rc = upload_tables(ctx, stream);
+    if (rc) return rc;
+    const hipError_t e = launch_eval_extras(desc, ctx->dev_tab, (uint32_t)first, (uint32_t)count, n_gpus,
+                                            time_model == GUIDE_TIME_ADDITIVE, *out, stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "eval_extras launch");
+    return GUIDE_OK;
+}
+
 size_t guide_select_workspace_bytes(const guide_select_spec *spec, uint64_t n) {
     if (!spec) return 0;
     return select_workspace_bytes(*spec, n);

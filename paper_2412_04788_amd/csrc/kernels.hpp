@@ -11,6 +11,9 @@ hipError_t launch_eval_sweep(const GridDesc &g, const DevTables *tab, uint32_t f
                              bool additive, const guide_stats &out, hipStream_t stream);
 
 size_t select_workspace_bytes(const guide_select_spec &spec, uint64_t n);
+hipError_t launch_eval_extras(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, uint32_t n_gpus,
+                              bool additive, const guide_extras &out, hipStream_t stream);
+
 size_t select_scratch_bytes();
 hipError_t launch_select_scratch_init(void *scratch, hipStream_t stream);
 hipError_t launch_select_topk(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,

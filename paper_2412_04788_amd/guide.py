@@ -24,7 +24,7 @@ NO_INDEX = 2 ** 64 - 1
 MAX_CONSTRAINTS = 4
 
 EXPORTS = ("guide_create", "guide_destroy", "guide_last_error", "guide_set_models", "guide_set_hardware",
-           "guide_eval_grid", "guide_eval_sampled", "guide_simulate_workspace_bytes", "guide_simulate",
+           "guide_eval_grid", "guide_eval_extras", "guide_eval_sampled", "guide_simulate_workspace_bytes", "guide_simulate",
            "guide_select_workspace_bytes", "guide_select")
 
 
@@ -57,6 +57,7 @@ class CEff(C.Structure):
 METRIC_COLUMNS = ("t_prefill", "t_decode", "t_batch", "decode_tok_s", "cost", "b_max", "feasible")
 STATS_COLUMNS = ("ttft_mean", "ttft_p10", "ttft_p90", "t_batch_mean", "t_batch_p10", "t_batch_p90", "cost", "b_max",
                  "feasible")
+EXTRAS_COLUMNS = ("s_max", "dp_max", "max_parallelism", "cluster_tok_s", "paper_tok_s")
 SAMPLED_COLUMNS = ("feasible_count", "win_val", "win_idx", "hist", "t_prefill", "t_batch", "cost", "b_max",
                    "feasible", "bucket")
 SIM_COLUMNS = ("ttft_p50", "ttft_p99", "mean_tpot", "tokens_s", "status", "n_steps", "n_request_steps")
@@ -68,6 +69,10 @@ class CMetrics(C.Structure):
 
 class CStats(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in STATS_COLUMNS]
+
+
+class CExtras(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in EXTRAS_COLUMNS]
 
 
 class CSpace(C.Structure):
@@ -126,6 +131,8 @@ def load() -> C.CDLL:
         lib.guide_set_hardware.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32]
         lib.guide_eval_grid.argtypes = [C.c_void_p, C.POINTER(CGrid), C.c_uint64, C.c_uint64, C.POINTER(CEff),
                                         C.c_uint32, C.POINTER(CMetrics), C.POINTER(CStats), C.c_void_p]
+        lib.guide_eval_extras.argtypes = [C.c_void_p, C.POINTER(CGrid), C.c_uint64, C.c_uint64, C.c_uint32,
+                                          C.c_uint32, C.POINTER(CExtras), C.c_void_p]
         lib.guide_eval_sampled.argtypes = [C.c_void_p, C.POINTER(CSpace), C.c_uint64, C.c_uint64, C.c_uint64,
                                            C.c_void_p, C.c_uint32, C.c_double, C.c_uint32, C.POINTER(CSampledOut),
                                            C.c_void_p]
@@ -277,6 +284,12 @@ class Context:
         self._invoke(self._lib.guide_eval_grid, self._h, _Ref(grid.c, grid), first, count,
                      _Ref(eff, (e_c, e_b)) if eff else None, time_model,
                      _Ref(cm) if cm else None, _Ref(cs) if cs else None, _stream_ptr(stream))
+
+    def eval_extras(self, grid: GridArg, first: int, count: int, n_gpus: int, out: dict,
+                    time_model: int = TIME_ROOFLINE, stream=None):
+        ce = CExtras(*[_dev_ptr(out.get(k)) for k in EXTRAS_COLUMNS])
+        self._invoke(self._lib.guide_eval_extras, self._h, _Ref(grid.c, grid), first, count, n_gpus, time_model,
+                     _Ref(ce), _stream_ptr(stream))
 
     def eval_sampled(self, space: dict, seed: int, first: int, count: int, edges, ttft_cap: float, out: dict,
                      time_model: int = TIME_ROOFLINE, stream=None):

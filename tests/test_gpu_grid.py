@@ -200,3 +200,33 @@ def test_tile_shapes_generic_path_and_table_limits(ora, torch_cuda):
     ctx.eval_grid(bridge.gpu_grid(g), 0, g.size, out=out)
     torch.cuda.synchronize()
     _compare(out, ora.eval_grid(bridge.ora_grid(g)), "max tables")
+
+
+def test_cluster_extras(ora, torch_cuda):
+    torch = torch_cuda
+    hws = [wl.HW_TINY, wl.Hardware(3.0e14, 6.0e12, 48 * wl.GIB, 4.5e11, 2.5e-6)]
+    g = wl.make_grid(wl.MODELS_FULL, hws, wl.Axis.table([1, 7, 64]), wl.Axis.table([100, 4000]),
+                     wl.Axis.table([1, 2, 500]), wl.Axis.table([1, 2, 3, 8, 16]), wl.Axis.table([16, 4]),
+                     wl.Axis.table([16, 48]), wl.Axis.table([2048]))
+    ctx = bridge.gpu_context(g)
+    for n_gpus, tm in ((8, 0), (3, 1)):
+        first, count = 5, g.size - 9
+        out = dict(s_max=torch.empty(count, dtype=torch.int32, device="cuda"),
+                   dp_max=torch.empty(count, dtype=torch.int32, device="cuda"),
+                   max_parallelism=torch.empty(count, dtype=torch.int64, device="cuda"),
+                   cluster_tok_s=torch.empty(count, dtype=torch.float64, device="cuda"),
+                   paper_tok_s=torch.empty(count, dtype=torch.float64, device="cuda"))
+        ctx.eval_extras(bridge.gpu_grid(g), first, count, n_gpus, out, time_model=tm)
+        torch.cuda.synchronize()
+        exp = ora.eval_extras_grid(bridge.ora_grid(g), n_gpus, first, count, time_model=tm)
+        np.testing.assert_array_equal(bridge.to_np(out["s_max"], np.uint32), exp["s_max"])
+        np.testing.assert_array_equal(bridge.to_np(out["dp_max"], np.uint32), exp["dp_max"])
+        np.testing.assert_array_equal(bridge.to_np(out["max_parallelism"], np.uint64), exp["max_parallelism"])
+        for k in ("cluster_tok_s", "paper_tok_s"):
+            assert bridge.rel_err(bridge.to_np(out[k]), exp[k]).max() <= TOL, k
+    # NULL columns are skipped
+    only = dict(dp_max=torch.empty(16, dtype=torch.int32, device="cuda"))
+    ctx.eval_extras(bridge.gpu_grid(g), 0, 16, 8, only)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(bridge.to_np(only["dp_max"], np.uint32),
+                                  ora.eval_extras_grid(bridge.ora_grid(g), 8, 0, 16)["dp_max"])

@@ -646,3 +646,44 @@ def test_prefill_first_invariants_and_relation_to_split_fuse(ora):
             np.testing.assert_array_equal(a["ttft"], b["ttft"])
         else:
             assert not np.array_equal(a["fin"], b["fin"])
+
+
+# ------------------------------------------------------------ cluster-level extras
+
+def test_extras_by_hand(ora):
+    """S_max is the paper's floor(C_available / (2 N H B kv)) for MHA on one GPU; the boundary is exact;
+    maximum parallelism = DP x B_max; the multi-GPU heuristic is N T_single / (1 + log2 P_TP)."""
+    m = wl.DENSE_13B
+    om = bridge.ora_model(m)
+    b, tp = 6, 1
+    w = 2 * ora.params_total(om)
+    s_fit = 3000
+    cap = w + b * (2 * m.L * m.d * 2) * s_fit            # exactly s_fit tokens per sequence fit
+    for delta, s_exp in ((0.0, s_fit), (-1.0, s_fit - 1)):
+        h = wl.Hardware(1e15, 5e12, cap + delta, 4e11)
+        g = bridge.ora_grid(wl.make_grid([m], [h], wl.Axis.table([b]), wl.Axis.table([512]), wl.Axis.table([64]),
+                                         wl.Axis.table([tp]), wl.Axis.table([16]), wl.Axis.table([16]),
+                                         wl.Axis.table([8192])))
+        e = ora.eval_extras_grid(g, 8)
+        assert e["s_max"][0] == s_exp
+    h = wl.HW_TINY
+    g = wl.make_grid([m], [h], wl.Axis.table([b]), wl.Axis.table([512]), wl.Axis.table([64]),
+                     wl.Axis.table([1, 2, 3, 8, 16]), wl.Axis.table([16]), wl.Axis.table([16]), wl.Axis.table([8192]))
+    og = bridge.ora_grid(g)
+    e = ora.eval_extras_grid(og, 8)
+    r = ora.eval_grid(og)
+    t_single = r["decode_tok_s"][0]
+    for i, p in enumerate([1, 2, 3, 8, 16]):
+        dp = 8 // p
+        assert e["dp_max"][i] == dp
+        assert e["max_parallelism"][i] == dp * int(r["b_max"][i])
+        assert e["cluster_tok_s"][i] == dp * r["decode_tok_s"][i]
+        assert e["paper_tok_s"][i] == pytest.approx(dp * p * t_single / (1 + np.log2(p)), rel=1e-15)
+    assert e["paper_tok_s"][0] == 8 * t_single and e["paper_tok_s"][1] == pytest.approx(8 * t_single / 2, rel=1e-15)
+    assert e["dp_max"][4] == 0 and e["cluster_tok_s"][4] == 0.0
+    # weights do not fit: nothing fits
+    g0 = bridge.ora_grid(wl.make_grid([wl.DENSE_70B], [wl.Hardware(1e15, 5e12, 24 * wl.GIB, 4e11)], wl.Axis.table([1]),
+                                      wl.Axis.table([64]), wl.Axis.table([64]), wl.Axis.table([1]), wl.Axis.table([16]),
+                                      wl.Axis.table([16]), wl.Axis.table([2048])))
+    e = ora.eval_extras_grid(g0, 4)
+    assert e["s_max"][0] == 0 and e["max_parallelism"][0] == 0
