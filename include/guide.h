@@ -29,6 +29,19 @@
  *   Model for Performance Analysis) or F / peak + B / bandwidth under
  *   GUIDE_TIME_ADDITIVE (Time Calculation), and the all-reduce is the transfer
  *   term: 2(p-1)/p * bytes / link_bw + 2(p-1) * link_lat.
+ *   Tasks of one layer (d_h = d / n_h, dq = n_h d_h, dkv = n_kv d_h, w = wbits / 8
+ *   bytes per weight, activations and cached K/V 2 bytes per element, g_kv =
+ *   ceil(n_kv / p) d_h, E_ld = min(E, k T) experts whose weights are read):
+ *     qkv        F = 2 T d (dq + 2 dkv) / p     B = w d (dq + 2 dkv) / p + 2 T d + 2 T (dq + 2 dkv) / p
+ *     attention  F = 4 dq Q / p                 B = 4 T dq / p + 4 g_kv K
+ *     out-proj   F = 2 T dq d / p               B = w dq d / p + 2 T dq / p + 2 T d
+ *     ffn-up     F = 2 T k (2 d d_ff) / p       B = w E_ld (2 d d_ff) / p + 2 T d + 4 T k d_ff / p
+ *     ffn-down   F = 2 T k (d_ff d) / p         B = w E_ld (d_ff d) / p + 2 T k d_ff / p + 2 T d
+ *     router     F = 2 T d E                    B = w d E + 2 T d + 2 T E        (only when E > 1)
+ *     norms      F = 0                          B = 8 T d
+ *   and once per pass the LM head over n_lm rows: F = 2 n_lm d V / p,
+ *   B = w d V / p + 2 n_lm d + 2 n_lm V / p.  Stored parameters: L (2 d dq + 2 d dkv +
+ *   3 E d d_ff + [E > 1] d E) + 2 V d; weights per GPU = w * parameters / p.
  *   Prefill of a static batch runs in sub-batches of floor(mbt / s_in) requests,
  *   or, for prompts longer than mbt, in ceil(s_in / mbt) segments per request
  *   (Model Analyzer, Dynamic Batch Size / Sequence Length Adjustment).  Decode

@@ -33,3 +33,13 @@ def test_binding_structs_match_header_sizes():
 def test_binding_has_no_cpu_fallback():
     src = open(os.path.join(ROOT, "paper_2412_04788_amd", "guide.py")).read()
     assert "oracle" not in src.replace("no CPU fallback", "")
+
+
+def test_context_creation_fails_loudly_without_a_gpu():
+    import pytest
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(guide.GuideError) as e:
+        guide.Context(0)
+    assert e.value.code == guide.E_DEVICE
