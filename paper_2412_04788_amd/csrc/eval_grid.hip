@@ -271,6 +271,10 @@ struct SmallestK {
     }
 };
 
+// Efficiency sweep.  Neither latency depends on the KV block size, so one lane evaluates the samples
+// for all block sizes of a configuration at once (rows that differ only in the kv_block digit) and
+// only the memory check is repeated per block size; the split of the prefill into passes does not
+// depend on the sample and is planned once.
 template <bool ADDITIVE>
 __global__ __launch_bounds__(kBlock) void eval_sweep_kernel(GridDesc g, const DevTables *__restrict__ tab,
                                                             uint32_t first, uint32_t count, uint32_t n_eff,
@@ -286,33 +290,53 @@ __global__ __launch_bounds__(kBlock) void eval_sweep_kernel(GridDesc g, const De
     // nearest rank: p10 = sorted[ceil(n/10) - 1]; p90 = sorted[ceil(9n/10) - 1] = (n - ceil(9n/10))-th largest, 0-based
     const uint32_t r_lo = (n_eff + 9) / 10 - 1;
     const uint32_t r_hi = n_eff - (9 * n_eff + 9) / 10;
-    for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < count; i += gridDim.x * kBlock) {
-        const Candidate c = decode_index(s, g, first + i);
+    // work item u = (index with the kv_block digit removed): rows (hi * NB + k) * NM + m for k < NB
+    const uint32_t NB = g.div[AX_BLK].d, NM = g.div[AX_MBT].d, TS = NB * NM;
+    const uint32_t t_first = first / TS;
+    const uint32_t n_items = ((first + count - 1) / TS - t_first + 1) * NM;
+    const uint32_t last = first + count;
+    for (uint32_t u = blockIdx.x * kBlock + threadIdx.x; u < n_items; u += gridDim.x * kBlock) {
+        const uint32_t hi = t_first + u / NM, m_digit = u % NM;
+        const uint32_t row0 = hi * TS + m_digit;                  // the row with kv_block digit 0
+        // none of this item's rows inside [first, last)?  (only at the ragged ends)
+        if (row0 + (NB - 1) * NM < first || row0 >= last) continue;
+        const Candidate c = decode_index(s, g, row0);
         const Coef cf = make_coef(s.models[c.model], c.kn.p, c.kn.wbits);
         const HwRecip hw = s.hw[c.hw];
+        const PrefillPlan plan = make_prefill_plan(c.kn.b, c.kn.s_in, c.kn.mbt, recip_up(1.0 / (double)c.kn.s_in),
+                                                   recip_up(1.0 / (double)c.kn.mbt));
         SmallestK lo_p, hi_p, lo_b, hi_b;   // hi_* hold negated values: the largest become the smallest
         lo_p.init(); hi_p.init(); lo_b.init(); hi_b.init();
         double sum_p = 0.0, sum_b = 0.0;
         for (uint32_t e = 0; e < n_eff; ++e) {
             const TimeCoef tc = make_time_coef(cf, hw.r_peak * s_rec[e], hw.r_bw * s_reb[e], hw.r_link, hw.lat);
-            const EvalResult r = evaluate_times<ADDITIVE>(tc, c.kn);
-            const double tb = r.t_prefill + r.t_decode;
-            sum_p += r.t_prefill;
+            const double tp = prefill_time_plan<ADDITIVE>(tc, plan, c.kn.b);
+            const double tb = tp + decode_time_fast<ADDITIVE>(tc, c.kn.b, c.kn.s_in, c.kn.s_out - 1);
+            sum_p += tp;
             sum_b += tb;
-            lo_p.push(r.t_prefill); hi_p.push(-r.t_prefill);
+            lo_p.push(tp); hi_p.push(-tp);
             lo_b.push(tb); hi_b.push(-tb);
         }
-        const MemResult m = memory_check(cf, hw.cap, c.kn.b, c.kn.s_in, c.kn.s_out, c.kn.blk);
-        const double mean_b = sum_b / (double)n_eff;
-        if (out.ttft_mean) out.ttft_mean[i] = sum_p / (double)n_eff;
-        if (out.ttft_p10) out.ttft_p10[i] = lo_p.at(r_lo);
-        if (out.ttft_p90) out.ttft_p90[i] = -hi_p.at(r_hi);
-        if (out.t_batch_mean) out.t_batch_mean[i] = mean_b;
-        if (out.t_batch_p10) out.t_batch_p10[i] = lo_b.at(r_lo);
-        if (out.t_batch_p90) out.t_batch_p90[i] = -hi_b.at(r_hi);
-        if (out.cost) out.cost[i] = cost_of(c.kn, mean_b);
-        if (out.b_max) out.b_max[i] = m.b_max;
-        if (out.feasible) out.feasible[i] = m.feasible ? 1 : 0;
+        const double mean_p = sum_p / (double)n_eff, mean_b = sum_b / (double)n_eff;
+        const double p10_p = lo_p.at(r_lo), p90_p = -hi_p.at(r_hi), p10_b = lo_b.at(r_lo), p90_b = -hi_b.at(r_hi);
+        const double cost = cost_of(c.kn, mean_b);
+        for (uint32_t k = 0; k < NB; ++k) {
+            const uint32_t row = row0 + k * NM;
+            if (row < first || row >= last) continue;
+            const uint32_t i = row - first;
+            if (out.ttft_mean) out.ttft_mean[i] = mean_p;
+            if (out.ttft_p10) out.ttft_p10[i] = p10_p;
+            if (out.ttft_p90) out.ttft_p90[i] = p90_p;
+            if (out.t_batch_mean) out.t_batch_mean[i] = mean_b;
+            if (out.t_batch_p10) out.t_batch_p10[i] = p10_b;
+            if (out.t_batch_p90) out.t_batch_p90[i] = p90_b;
+            if (out.cost) out.cost[i] = cost;
+            if (out.b_max || out.feasible) {
+                const MemResult mem = memory_check(cf, hw.cap, c.kn.b, c.kn.s_in, c.kn.s_out, s.axis[AX_BLK][k]);
+                if (out.b_max) out.b_max[i] = mem.b_max;
+                if (out.feasible) out.feasible[i] = mem.feasible ? 1 : 0;
+            }
+        }
     }
 }
 
@@ -416,7 +440,9 @@ hipError_t launch_eval_extras(const GridDesc &g, const DevTables *tab, uint32_t 
 
 hipError_t launch_eval_sweep(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, uint32_t n_eff,
                              bool additive, const guide_stats &out, hipStream_t stream) {
-    const dim3 grid(blocks_for(count)), block(kBlock);
+    const uint32_t ts = g.div[AX_BLK].d * g.div[AX_MBT].d;
+    const uint32_t n_items = ((first + count - 1) / ts - first / ts + 1) * g.div[AX_MBT].d;
+    const dim3 grid(blocks_for(n_items)), block(kBlock);
     if (additive)
         hipLaunchKernelGGL(eval_sweep_kernel<true>, grid, block, 0, stream, g, tab, first, count, n_eff, out);
     else

@@ -271,6 +271,46 @@ __device__ inline double prefill_time_fast(const TimeCoef &t, uint32_t b, uint32
     return (double)b * one;
 }
 
+// The sample-independent part of a prefill: how the batch splits into passes.
+struct PrefillPlan {
+    bool segmented;      // prompt longer than the budget
+    double n_full, R, rem, S;          // sub-batches: n_full passes of R prompts, then one of rem (0 = none)
+    double n_fs, M, c_last, r_mbt;     // segments: n_fs full ones of M tokens, then c_last tokens with the LM head
+};
+__device__ inline PrefillPlan make_prefill_plan(uint32_t b, uint32_t s, uint32_t mbt, double r_s, double r_mbt) {
+    PrefillPlan p;
+    p.S = (double)s;
+    p.segmented = s > mbt;
+    p.n_full = p.R = p.rem = p.n_fs = p.c_last = 0.0;
+    p.M = (double)mbt;
+    p.r_mbt = r_mbt;
+    if (!p.segmented) {
+        uint32_t r = floor_div(mbt, r_s);
+        r = r < b ? r : b;
+        const uint32_t n_full = r == b ? 1u : floor_div(b, recip_up(fast_recip((double)r)));
+        p.n_full = (double)n_full;
+        p.R = (double)r;
+        p.rem = (double)(b - n_full * r);
+    } else {
+        const uint32_t n_seg = floor_div(s + mbt - 1, r_mbt);
+        p.n_fs = (double)(n_seg - 1);
+        p.c_last = p.S - p.n_fs * p.M;
+    }
+    return p;
+}
+template <bool ADDITIVE>
+__device__ inline double prefill_time_plan(const TimeCoef &t, const PrefillPlan &p, uint32_t b) {
+    if (!p.segmented) {
+        double total = p.n_full * pass_time<ADDITIVE>(t, p.R * p.S, p.R * p.S * p.S, p.R * p.S, p.R);
+        if (p.rem > 0.0) total += pass_time<ADDITIVE>(t, p.rem * p.S, p.rem * p.S * p.S, p.rem * p.S, p.rem);
+        return total;
+    }
+    const double att = attention_series<ADDITIVE>(p.M * t.c_att, t.m_att_k, p.M * t.m_att_t, 0.0, p.M, p.r_mbt, p.n_fs);
+    const double one = fma(t.L, fma(p.n_fs, layer_base<ADDITIVE>(t, p.M), att),
+                           pass_time<ADDITIVE>(t, p.c_last, p.c_last * p.S, p.S, 1.0));
+    return (double)b * one;
+}
+
 template <bool ADDITIVE>
 __device__ inline double decode_time_fast(const TimeCoef &t, uint32_t b_, uint32_t s_, uint32_t n_) {
     if (n_ == 0) return 0.0;

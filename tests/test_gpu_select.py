@@ -201,3 +201,23 @@ def test_pareto_large_front_and_repeated_calls(ora, torch_cuda):
         xs = rng.integers(0, 50, 3000).astype(np.float64); ys = rng.integers(0, 50, 3000).astype(np.float64)
         got, m = _pareto(torch, ctx, _dev(torch, xs), _dev(torch, ys))
         np.testing.assert_array_equal(got, ora.pareto_brute(xs, ys))
+
+
+def test_sweep_other_tile_shapes_and_additive(ora, torch_cuda):
+    torch = torch_cuda
+    hws = [wl.Hardware(3.0e14, 6.0e12, 141 * wl.GIB, 4.5e11, 2.5e-6)]
+    g = wl.make_grid(wl.MODELS_FULL[2:], hws, wl.Axis.table([1, 5, 300]), wl.Axis.table([17, 1000, 20001]),
+                     wl.Axis.table([1, 77]), wl.Axis.table([1, 3, 16]), wl.Axis.table([16, 4]),
+                     wl.Axis.table([1, 16, 48]), wl.Axis.table([512, 8192]))
+    ctx = bridge.gpu_context(g)
+    e_c, e_b = wl.efficiency_pairs(n=17)
+    for first, count, tm in [(0, g.size, 0), (5, g.size - 11, 1), (100, 1, 0), (7, 6, 0)]:
+        st = bridge.metric_buffers(count, names=STAT_COLS + ("b_max", "feasible"))
+        ctx.eval_grid(bridge.gpu_grid(g), first, count, stats=st, e_c=e_c, e_b=e_b, time_model=tm)
+        torch.cuda.synchronize()
+        exp = ora.eval_sweep_grid(bridge.ora_grid(g), e_c, e_b, first, count, time_model=tm)
+        for k in STAT_COLS:
+            e = bridge.rel_err(bridge.to_np(st[k]), exp[k])
+            assert e.max() <= TOL, (k, first, float(e.max()))
+        np.testing.assert_array_equal(bridge.to_np(st["b_max"], np.uint32), exp["b_max"])
+        np.testing.assert_array_equal(bridge.to_np(st["feasible"]), exp["feasible"])
