@@ -116,10 +116,13 @@ __global__ __launch_bounds__(kBlock) void eval_sampled_kernel(const SpaceTables 
 
             const Coef cf = make_coef(md, kn.p, kn.wbits);
             const TimeCoef tc = make_time_coef(cf, r_peak, r_bw, link_div * r_bw, 0.0);
-            const EvalResult ev = evaluate_times<ADDITIVE>(tc, kn);
+            EvalResult ev;
+            ev.t_prefill = prefill_time_fast<ADDITIVE>(tc, kn.b, kn.s_in, kn.mbt, recip_up(fast_recip((double)kn.s_in)),
+                                                       recip_up(fast_recip((double)kn.mbt)));
+            ev.t_decode = decode_time_fast<ADDITIVE>(tc, kn.b, kn.s_in, kn.s_out - 1);
             const MemResult mem = memory_check(cf, cap, kn.b, kn.s_in, kn.s_out, kn.blk);
             const double t_batch = ev.t_prefill + ev.t_decode;
-            const double cost = (double)kn.p * t_batch / 3600.0 * 1.0e6 / ((double)kn.b * (double)kn.s_out);
+            const double cost = (double)kn.p * (1.0e6 / 3600.0) * t_batch * fast_recip((double)kn.b * (double)kn.s_out);
             for (uint32_t e = 0; e < n_edges; ++e) bucket += cf.p_total >= tab->edges[e] ? 1u : 0u;
             feasible = mem.feasible;
             if (feasible) {
