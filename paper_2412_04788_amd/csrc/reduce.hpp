@@ -25,17 +25,69 @@ __device__ inline bool less_than(const Pair &a, const Pair &b) {
 }
 __device__ inline Pair pair_min(const Pair &a, const Pair &b) { return less_than(b, a) ? b : a; }
 
-__device__ inline Pair wave_min(Pair p) {
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-        Pair o;
-        o.key = __shfl_xor(p.key, off, kWave);
-        o.idx = __shfl_xor(p.idx, off, kWave);
-        p = pair_min(p, o);
-    }
-    return p;
+// Cross-lane moves in the vector ALU (data-parallel primitives, no LDS traffic).  A lane whose
+// source lane does not exist for the pattern, or whose row is masked out, receives `old`.
+// Patterns used: 0xB1 / 0x4E swap neighbours / pairs inside each group of four lanes, 0x141 / 0x140
+// mirror each half-row / row of 16 lanes, 0x110 + n shifts a row right by n lanes, 0x142 / 0x143
+// broadcast lane 15 of each row to the next row / lane 31 to the upper two rows.
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ inline uint32_t dpp_u32(uint32_t old, uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)old, (int)v, CTRL, ROW_MASK, 0xf, false);
 }
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ inline uint64_t dpp_keep(uint64_t v) {       // lanes without a source keep their own value
+    const uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+    return ((uint64_t)dpp_u32<CTRL, ROW_MASK>(hi, hi) << 32) | dpp_u32<CTRL, ROW_MASK>(lo, lo);
+}
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ inline Pair dpp_keep(const Pair &p) {
+    return Pair{dpp_keep<CTRL, ROW_MASK>(p.key), dpp_keep<CTRL, ROW_MASK>(p.idx)};
+}
+__device__ inline uint64_t read_lane63(uint64_t v) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, kWave - 1);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), kWave - 1);
+    return ((uint64_t)hi << 32) | lo;
+}
+__device__ inline uint64_t min_u64(uint64_t a, uint64_t b) { return b < a ? b : a; }
 
+// Least pair of the wave, in every lane.  Every lane of the wave must be active.
+__device__ inline Pair wave_min(Pair p) {
+    p = pair_min(p, dpp_keep<0xB1>(p));
+    p = pair_min(p, dpp_keep<0x4E>(p));
+    p = pair_min(p, dpp_keep<0x141>(p));
+    p = pair_min(p, dpp_keep<0x140>(p));          // every lane holds the minimum of its row
+    p = pair_min(p, dpp_keep<0x142, 0xa>(p));
+    p = pair_min(p, dpp_keep<0x143, 0xc>(p));     // lane 63 holds the minimum of the wave
+    return Pair{read_lane63(p.key), read_lane63(p.idx)};
+}
+__device__ inline uint64_t wave_min(uint64_t v) {
+    v = min_u64(v, dpp_keep<0xB1>(v));
+    v = min_u64(v, dpp_keep<0x4E>(v));
+    v = min_u64(v, dpp_keep<0x141>(v));
+    v = min_u64(v, dpp_keep<0x140>(v));
+    v = min_u64(v, dpp_keep<0x142, 0xa>(v));
+    v = min_u64(v, dpp_keep<0x143, 0xc>(v));
+    return read_lane63(v);
+}
+// Inclusive scans over the lanes of a wave (every lane active).
+__device__ inline uint64_t wave_scan_min(uint64_t v) {
+    v = min_u64(v, dpp_keep<0x111>(v));
+    v = min_u64(v, dpp_keep<0x112>(v));
+    v = min_u64(v, dpp_keep<0x114>(v));
+    v = min_u64(v, dpp_keep<0x118>(v));
+    v = min_u64(v, dpp_keep<0x142, 0xa>(v));
+    v = min_u64(v, dpp_keep<0x143, 0xc>(v));
+    return v;
+}
+__device__ inline uint32_t wave_scan_sum(uint32_t v) {
+    v += dpp_u32<0x111>(0u, v);
+    v += dpp_u32<0x112>(0u, v);
+    v += dpp_u32<0x114>(0u, v);
+    v += dpp_u32<0x118>(0u, v);
+    v += dpp_u32<0x142, 0xa>(0u, v);
+    v += dpp_u32<0x143, 0xc>(0u, v);
+    return v;
+}
 
 // Per-wave LDS slots holding the least (key, row) pair per group.  A wave's LDS
 // operations execute in program order for all its lanes, so one update is: read

@@ -8,6 +8,8 @@
 #include "kernels.hpp"
 #include "reduce.hpp"
 
+#include <type_traits>
+
 namespace guide {
 
 namespace {
@@ -31,34 +33,59 @@ __device__ inline bool row_passes(const RowFilter &f, uint32_t i) {
 }
 
 // All loads of a row are issued unconditionally (index clamped when the row is
-// past the end) so that several rows can be in flight at once.
+// past the end) and nothing is computed from them here, so that many rows can be
+// in flight while the kernel does other work; row_of() turns the loaded values
+// into the row's coordinates and its filter verdict.
+// MAXC: constraint columns the kernel variant can hold (n_con <= MAXC); variants with fewer keep
+// fewer registers busy per row in flight.
+template <uint32_t MAXC>
+struct RawRow {
+    double x, y;
+    double c[MAXC ? MAXC : 1];
+    uint8_t fe;
+    bool valid;
+};
 struct Row {
     double x, y;
     bool pass;
 };
-template <bool WITH_Y>
-__device__ inline Row load_row(const double *__restrict__ x, const double *__restrict__ y, const RowFilter &f,
-                               uint32_t i, uint32_t n) {
-    const bool valid = i < n;
-    const uint32_t j = valid ? i : 0;
-    Row r;
+template <bool WITH_Y, uint32_t MAXC>
+__device__ inline RawRow<MAXC> load_raw(const double *__restrict__ x, const double *__restrict__ y, const RowFilter &f,
+                                        uint32_t i, uint32_t n) {
+    RawRow<MAXC> r;
+    r.valid = i < n;
+    const uint32_t j = r.valid ? i : 0;
     r.x = x[j];
     r.y = WITH_Y ? y[j] : 0.0;
-    const uint8_t fe = f.feasible ? f.feasible[j] : (uint8_t)1;
-    double c[GUIDE_MAX_CONSTRAINTS];
+    r.fe = f.feasible ? f.feasible[j] : (uint8_t)1;
 #pragma unroll
-    for (uint32_t k = 0; k < GUIDE_MAX_CONSTRAINTS; ++k) c[k] = k < f.n_con ? f.col[k][j] : 0.0;
-    bool ok = valid && fe != 0 && (r.x == r.x) && (!WITH_Y || r.y == r.y);
-#pragma unroll
-    for (uint32_t k = 0; k < GUIDE_MAX_CONSTRAINTS; ++k)
-        if (k < f.n_con) ok = ok && (c[k] <= f.cap[k]);
-    r.pass = ok;
+    for (uint32_t k = 0; k < MAXC; ++k) r.c[k] = k < f.n_con ? f.col[k][j] : 0.0;
     return r;
+}
+template <bool WITH_Y, uint32_t MAXC>
+__device__ inline Row row_of(const RawRow<MAXC> &w, const RowFilter &f) {
+    bool ok = w.valid && w.fe != 0 && (w.x == w.x) && (!WITH_Y || w.y == w.y);
+#pragma unroll
+    for (uint32_t k = 0; k < MAXC; ++k)
+        if (k < f.n_con) ok = ok && (w.c[k] <= f.cap[k]);
+    return Row{w.x, w.y, ok};
+}
+template <bool WITH_Y, uint32_t MAXC>
+__device__ inline Row load_row(const double *__restrict__ x, const double *__restrict__ y, const RowFilter &f,
+                               uint32_t i, uint32_t n) {
+    return row_of<WITH_Y, MAXC>(load_raw<WITH_Y, MAXC>(x, y, f, i, n), f);
+}
+// Launches fn.template operator()<MAXC>() for the least supported MAXC >= n_con.
+template <typename F>
+void with_max_constraints(uint32_t n_con, F &&fn) {
+    if (n_con == 0) fn(std::integral_constant<uint32_t, 0>{});
+    else if (n_con == 1) fn(std::integral_constant<uint32_t, 1>{});
+    else fn(std::integral_constant<uint32_t, GUIDE_MAX_CONSTRAINTS>{});
 }
 
 // Block b owns the contiguous rows [b * per, (b + 1) * per); per is a multiple of
 // kBlock * kUnroll so that every lane of a wave runs the same trip count.
-constexpr uint32_t kUnroll = 4;
+constexpr uint32_t kUnroll = 8;
 __device__ inline uint32_t rows_per_block(uint32_t n) {
     const uint32_t unit = kBlock * kUnroll;
     const uint32_t per = (n + gridDim.x - 1) / gridDim.x;
@@ -90,7 +117,7 @@ struct SelectScratch {
     uint32_t counters[4];          // [0] survivors appended
     uint64_t sample_lo[64];        // per sample block: least x key of passing sample rows
     Pair sample_best[64];          // per sample block: (least y key, its x key)
-    uint64_t bin_min[kBins];       // least y key per x bin
+    uint64_t bin_min[kBins];       // y keys per x bin whose exclusive prefix-min is that of the least y per bin
     uint32_t bin_cnt[kBins];       // survivors per bin
     uint32_t bin_off[kBins + 1], bin_foff[kBins + 1], bin_cur[kBins];   // large-front path only
 };
@@ -173,7 +200,7 @@ Top1Ws top1_ws(void *ws) {
 size_t top1_ws_bytes() { return sizeof(uint64_t) * ((size_t)kSelBlocks * (2 * GUIDE_MAX_TOPK + 1)); }
 
 // One pass over the rows: every lane keeps its K best, the block merges them.
-template <int K>
+template <int K, uint32_t MAXC>
 __global__ __launch_bounds__(kBlock) void topk_pass_kernel(const double *__restrict__ obj, RowFilter f, uint32_t n,
                                                            Top1Ws w) {
     __shared__ Pair s_pairs[kWaves][K];
@@ -186,7 +213,7 @@ __global__ __launch_bounds__(kBlock) void topk_pass_kernel(const double *__restr
     for (uint64_t base = begin + threadIdx.x; base < begin + per && base < n; base += kBlock * kUnroll) {
         Row r[kUnroll];
 #pragma unroll
-        for (uint32_t u = 0; u < kUnroll; ++u) r[u] = load_row<false>(obj, nullptr, f, (uint32_t)base + u * kBlock, n);
+        for (uint32_t u = 0; u < kUnroll; ++u) r[u] = load_row<false, MAXC>(obj, nullptr, f, (uint32_t)base + u * kBlock, n);
 #pragma unroll
         for (uint32_t u = 0; u < kUnroll; ++u) {
             if (r[u].pass) {
@@ -413,9 +440,11 @@ __device__ inline Binning binning_of(uint64_t lo, uint64_t hi) {
     Binning b;
     b.lo = lo;
     const uint64_t span = hi - lo;
-    uint32_t s = 0;
-    while (s < 63 && (span >> s) >= kBins) ++s;
-    b.shift = s;
+    // least shift with (span >> shift) < kBins
+    const uint32_t bits = span ? 64u - (uint32_t)__builtin_clzll(span) : 0u;   // span < 2^bits
+    constexpr uint32_t kBinBits = 12;
+    static_assert((1u << kBinBits) == kBins, "kBins is a power of two");
+    b.shift = bits > kBinBits ? bits - kBinBits : 0u;
     return b;
 }
 
@@ -433,17 +462,14 @@ __global__ __launch_bounds__(kBlock) void pareto_prepare_kernel(const double *__
     const uint32_t k = blockIdx.x * kBlock + threadIdx.x;           // sample number
     const uint32_t n_samples = kSampleBlocks * kBlock;
     const uint32_t stride = n > n_samples ? n / n_samples : 1;
-    const Row r = load_row<true>(x, y, f, (uint64_t)k * stride < n ? k * stride : n, n);
+    const Row r = load_row<true, GUIDE_MAX_CONSTRAINTS>(x, y, f, (uint64_t)k * stride < n ? k * stride : n, n);
     uint64_t lo = kNone;
     Pair best = {kNone, kNone};                                     // (y key, x key) of the least y
     if (r.pass) {
         lo = key_of(r.x);
         best = Pair{key_of(r.y), lo};
     }
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-        const uint64_t ol = __shfl_xor(lo, off, kWave);
-        lo = ol < lo ? ol : lo;
-    }
+    lo = wave_min(lo);
     best = wave_min(best);
     if (threadIdx.x % kWave == 0) {
         s_lo[threadIdx.x / kWave] = lo;
@@ -468,10 +494,7 @@ __device__ inline Binning sampled_binning(const SelectScratch *sc, uint64_t *s_r
         static_assert(kSampleBlocks == kWave, "one sample partial per lane");
         uint64_t lo = sc->sample_lo[threadIdx.x];
         Pair best = sc->sample_best[threadIdx.x];
-        for (int off = kWave / 2; off > 0; off >>= 1) {
-            const uint64_t ol = __shfl_xor(lo, off, kWave);
-            lo = ol < lo ? ol : lo;
-        }
+        lo = wave_min(lo);
         best = wave_min(best);
         uint64_t hi = best.idx;
         if (lo == kNone || hi < lo) {   // no passing sample row: one slice per 2^52 keys
@@ -487,57 +510,68 @@ __device__ inline Binning sampled_binning(const SelectScratch *sc, uint64_t *s_r
     return binning_of(s_rng[0], s_rng[1]);
 }
 
-// Exclusive prefix-min over a kBins-entry table in LDS by the NT threads of the
-// block (thread t owns kBins / NT consecutive entries): serial in the thread,
-// shuffle scan in the wave, wave totals through LDS.  s_tmp: NT / kWave entries.
+// kBins-entry tables in LDS that a block scans are stored with one unused slot after every PER
+// entries (PER = entries per thread of the scan): thread t's entries then start at slot t * (PER + 1),
+// and the lanes of a wave reach different banks when each reads its own j-th entry.
+template <uint32_t PER>
+__device__ inline uint32_t padded(uint32_t i) { return i + i / PER; }
+template <uint32_t PER>
+constexpr uint32_t padded_size() { return kBins + kBins / PER + 1; }
+constexpr uint32_t kPerPass = kBins / kBlock;             // table entries per thread of a streaming block
+constexpr uint32_t kPerFinish = kBins / 1024;             // ... of the finishing block
+
+// Thread t of the NT-thread block owns the kBins / NT consecutive entries v[] of a
+// kBins-entry table; returns the minimum over all entries before its first one
+// (scan in the wave, wave totals through LDS; one block barrier).
+// s_tmp: NT / kWave entries.
 template <uint32_t NT>
-__device__ inline void scan_min_excl(uint64_t *s_io, uint64_t *s_tmp) {
+__device__ inline uint64_t prefix_min_before(const uint64_t (&v)[kBins / NT], uint64_t *s_tmp) {
     constexpr uint32_t per = kBins / NT, nw = NT / kWave;
     const uint32_t t = threadIdx.x, lane = t % kWave, wave = t / kWave;
-    uint64_t v[per], m = kNone;
+    uint64_t m = kNone;
 #pragma unroll
-    for (uint32_t j = 0; j < per; ++j) {
-        v[j] = s_io[t * per + j];
-        m = v[j] < m ? v[j] : m;
-    }
-    uint64_t inc = m;                                   // inclusive scan of thread minima in the wave
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const uint64_t o = __shfl_up(inc, off, kWave);
-        if ((int)lane >= off) inc = o < inc ? o : inc;
-    }
+    for (uint32_t j = 0; j < per; ++j) m = min_u64(m, v[j]);
+    const uint64_t inc = wave_scan_min(m);              // inclusive scan of thread minima in the wave
     if (lane == kWave - 1) s_tmp[wave] = inc;
     uint64_t run = __shfl_up(inc, 1, kWave);            // exclusive within the wave
     if (lane == 0) run = kNone;
     __syncthreads();
     for (uint32_t wv = 0; wv < nw; ++wv)
-        if (wv < wave) run = s_tmp[wv] < run ? s_tmp[wv] : run;
+        if (wv < wave) run = min_u64(run, s_tmp[wv]);
+    return run;
+}
+
+// Exclusive prefix-min over a (padded) kBins-entry table in LDS, in place, by the NT threads of the block.
+template <uint32_t NT>
+__device__ inline void scan_min_excl(uint64_t *s_io, uint64_t *s_tmp) {
+    constexpr uint32_t per = kBins / NT;
+    const uint32_t t = threadIdx.x;
+    uint64_t v[per];
+#pragma unroll
+    for (uint32_t j = 0; j < per; ++j) v[j] = s_io[t * (per + 1) + j];
+    uint64_t run = prefix_min_before<NT>(v, s_tmp);
 #pragma unroll
     for (uint32_t j = 0; j < per; ++j) {
-        s_io[t * per + j] = run;
-        run = v[j] < run ? v[j] : run;
+        s_io[t * (per + 1) + j] = run;
+        run = min_u64(run, v[j]);
     }
     __syncthreads();
 }
 
-// Exclusive prefix-sum over a kBins-entry table (LDS or global), in place, by the
-// NT threads of the block (io[kBins] receives the total).  s_tmp: NT / kWave entries.
-template <uint32_t NT>
+// Exclusive prefix-sum over a kBins-entry table, in place, by the NT threads of the block; the total
+// goes to entry kBins.  PAD: the table is a padded LDS table; otherwise plain (global memory).
+// s_tmp: NT / kWave entries.
+template <uint32_t NT, bool PAD>
 __device__ inline void scan_sum_excl(uint32_t *io, uint32_t *s_tmp) {
-    constexpr uint32_t per = kBins / NT, nw = NT / kWave;
+    constexpr uint32_t per = kBins / NT, nw = NT / kWave, pitch = PAD ? per + 1 : per;
     const uint32_t t = threadIdx.x, lane = t % kWave, wave = t / kWave;
     uint32_t v[per], m = 0;
 #pragma unroll
     for (uint32_t j = 0; j < per; ++j) {
-        v[j] = io[t * per + j];
+        v[j] = io[t * pitch + j];
         m += v[j];
     }
-    uint32_t inc = m;
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const uint32_t o = __shfl_up(inc, off, kWave);
-        if ((int)lane >= off) inc += o;
-    }
+    const uint32_t inc = wave_scan_sum(m);
     if (lane == kWave - 1) s_tmp[wave] = inc;
     uint32_t run = inc - m;
     __syncthreads();
@@ -548,71 +582,103 @@ __device__ inline void scan_sum_excl(uint32_t *io, uint32_t *s_tmp) {
     }
 #pragma unroll
     for (uint32_t j = 0; j < per; ++j) {
-        io[t * per + j] = run;
+        io[t * pitch + j] = run;
         run += v[j];
     }
-    if (t == 0) io[kBins] = total;
+    if (t == 0) io[PAD ? padded<per>(kBins) : kBins] = total;
     __syncthreads();
 }
 
+template <uint32_t MAXC>
 __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__restrict__ x, const double *__restrict__ y,
                                                               RowFilter f, uint32_t n, SelectScratch *sc) {
-    __shared__ uint64_t s_min[kBins], s_rng[2];
-    const Binning bin = sampled_binning(sc, s_rng);
-    for (uint32_t i = threadIdx.x; i < kBins; i += kBlock) s_min[i] = kNone;
-    __syncthreads();
+    __shared__ uint64_t s_min[padded_size<kPerPass>()], s_tmp[kWaves], s_rng[2];
     const uint32_t per = rows_per_block(n);
     const uint64_t begin = (uint64_t)blockIdx.x * per;
-    for (uint64_t base = begin + threadIdx.x; base < begin + per && base < n; base += kBlock * kUnroll) {
-        Row r[kUnroll];
+    const uint64_t end = begin + per < n ? begin + per : n;
+    // the first batch of rows is requested before the set-up below, so that its latency overlaps it
+    RawRow<MAXC> r[kUnroll];
+    uint64_t base = begin;
+    if (base < end) {
 #pragma unroll
-        for (uint32_t u = 0; u < kUnroll; ++u) r[u] = load_row<true>(x, y, f, (uint32_t)base + u * kBlock, n);
+        for (uint32_t u = 0; u < kUnroll; ++u)
+            r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)base + threadIdx.x + u * kBlock, n);
+    }
+    for (uint32_t i = threadIdx.x; i < padded_size<kPerPass>(); i += kBlock) s_min[i] = kNone;
+    const Binning bin = sampled_binning(sc, s_rng);     // its barrier also covers the table above
+    while (base < end) {
 #pragma unroll
         for (uint32_t u = 0; u < kUnroll; ++u) {
-            if (!r[u].pass) continue;
-            const uint32_t b = bin(key_of(r[u].x));
-            const uint64_t ky = key_of(r[u].y);
+            const Row q = row_of<true, MAXC>(r[u], f);
+            if (!q.pass) continue;
+            const uint32_t b = padded<kPerPass>(bin(key_of(q.x)));
+            const uint64_t ky = key_of(q.y);
             // the slot only decreases, so a stale read can only let an extra atomic through
             if (ky < s_min[b]) atomicMin((unsigned long long *)&s_min[b], (unsigned long long)ky);
         }
+        base += kBlock * kUnroll;
+        if (base < end) {
+#pragma unroll
+            for (uint32_t u = 0; u < kUnroll; ++u)
+                r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)base + threadIdx.x + u * kBlock, n);
+        }
     }
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < kBins; i += kBlock) {
-        const uint64_t v = s_min[i];
-        // the global slot only decreases: a stale read can only let an extra atomic through
-        if (v != kNone && v < __hip_atomic_load(&sc->bin_min[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
-            atomicMin((unsigned long long *)&sc->bin_min[i], (unsigned long long)v);
+    // The table is only read through its exclusive prefix-min, and only a block's running minima
+    // (entries below everything in its lower bins) can lower that: the others are not sent.  The
+    // atomics return nothing, so no lane waits for them.
+    uint64_t v[kPerPass];
+#pragma unroll
+    for (uint32_t j = 0; j < kPerPass; ++j) v[j] = s_min[threadIdx.x * (kPerPass + 1) + j];
+    uint64_t run = prefix_min_before<kBlock>(v, s_tmp);
+#pragma unroll
+    for (uint32_t j = 0; j < kPerPass; ++j) {
+        if (v[j] < run) {
+            atomicMin((unsigned long long *)&sc->bin_min[threadIdx.x * kPerPass + j], (unsigned long long)v[j]);
+            run = v[j];
+        }
     }
 }
 
+template <uint32_t MAXC>
 __global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *__restrict__ x,
                                                                   const double *__restrict__ y, RowFilter f, uint32_t n,
                                                                   ParetoWs w, SelectScratch *sc) {
-    __shared__ uint64_t s_lower[kBins], s_tmp[kWaves], s_rng[2];
-    const Binning bin = sampled_binning(sc, s_rng);
-    for (uint32_t i = threadIdx.x; i < kBins; i += kBlock) s_lower[i] = sc->bin_min[i];
-    __syncthreads();
-    scan_min_excl<kBlock>(s_lower, s_tmp);              // least y over strictly lower bins
+    __shared__ uint64_t s_lower[padded_size<kPerPass>()], s_tmp[kWaves], s_rng[2];
     const int lane = threadIdx.x % kWave;
     const uint32_t per = rows_per_block(n);
     const uint64_t begin = (uint64_t)blockIdx.x * per;
-    // wave-uniform trip count: the ballots below need every lane
-    for (uint64_t base = begin; base < begin + per && base < n; base += kBlock * kUnroll) {
-        Row r[kUnroll];
+    const uint64_t end = begin + per < n ? begin + per : n;
+    // requested first, and in this order: the table, then the first batch of rows, whose latency
+    // overlaps the scan of the table
+    uint64_t tbl[kPerPass];
+#pragma unroll
+    for (uint32_t j = 0; j < kPerPass; ++j) tbl[j] = sc->bin_min[j * kBlock + threadIdx.x];
+    RawRow<MAXC> r[kUnroll];
+    uint64_t base = begin;
+    if (base < end) {
 #pragma unroll
         for (uint32_t u = 0; u < kUnroll; ++u)
-            r[u] = load_row<true>(x, y, f, (uint32_t)base + threadIdx.x + u * kBlock, n);
+            r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)base + threadIdx.x + u * kBlock, n);
+    }
+#pragma unroll
+    for (uint32_t j = 0; j < kPerPass; ++j) s_lower[padded<kPerPass>(j * kBlock + threadIdx.x)] = tbl[j];
+    const Binning bin = sampled_binning(sc, s_rng);     // its barrier also covers the table above
+    scan_min_excl<kBlock>(s_lower, s_tmp);              // least y over strictly lower bins
+    // wave-uniform trip count: the ballots below need every lane
+    while (base < end) {
 #pragma unroll
         for (uint32_t u = 0; u < kUnroll; ++u) {
             const uint32_t i = (uint32_t)base + threadIdx.x + u * kBlock;
+            const Row q = row_of<true, MAXC>(r[u], f);
             uint32_t b = 0;
             uint64_t kx = 0, ky = 0;
             bool keep = false;
-            if (r[u].pass) {
-                kx = key_of(r[u].x);
-                ky = key_of(r[u].y);
+            if (q.pass) {
+                kx = key_of(q.x);
+                ky = key_of(q.y);
                 b = bin(kx);
-                keep = ky < s_lower[b];
+                keep = ky < s_lower[padded<kPerPass>(b)];
             }
             const uint64_t mask = __ballot(keep);       // wave-aggregated append
             if (mask) {
@@ -628,12 +694,20 @@ __global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *
                 }
             }
         }
+        base += kBlock * kUnroll;
+        if (base < end) {
+#pragma unroll
+            for (uint32_t u = 0; u < kUnroll; ++u)
+                r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)base + threadIdx.x + u * kBlock, n);
+        }
     }
 }
 
 __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs w, SelectScratch *sc, uint64_t *out_idx,
                                                                         uint64_t capacity, uint64_t *out_count) {
-    __shared__ uint32_t s_off[kBins + 1], s_foff[kBins + 1], s_cur[kBins], s_tmp[kFinishThreads / kWave];
+    static_assert(kFinishThreads == 1024, "kPerFinish assumes 1024 threads");
+    constexpr uint32_t P = kPerFinish;
+    __shared__ uint32_t s_off[padded_size<P>()], s_foff[padded_size<P>()], s_cur[kBins], s_tmp[kFinishThreads / kWave];
     __shared__ uint64_t s_kx[kStage], s_ky[kStage];
     __shared__ uint32_t s_row[kStage];
     __shared__ uint16_t s_bin[kStage];
@@ -645,9 +719,9 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
     if (m <= kStage) {
         // records staged in LDS, grouped by bin
         for (uint32_t i = t; i < kBins; i += kFinishThreads) {
-            s_off[i] = sc->bin_cnt[i];
+            s_off[padded<P>(i)] = sc->bin_cnt[i];
             s_cur[i] = 0;
-            s_foff[i] = 0;
+            s_foff[padded<P>(i)] = 0;
         }
         constexpr uint32_t kPer = kStage / kFinishThreads;
         uint64_t rx[kPer], ry[kPer];
@@ -660,12 +734,12 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
             rr[q] = j < m ? w.surv[j] : 0;
         }
         __syncthreads();
-        scan_sum_excl<kFinishThreads>(s_off, s_tmp);
+        scan_sum_excl<kFinishThreads, true>(s_off, s_tmp);
 #pragma unroll
         for (uint32_t q = 0; q < kPer; ++q) {
             if (q * kFinishThreads + t < m) {
                 const uint32_t b = bin(rx[q]);
-                const uint32_t pos = s_off[b] + atomicAdd(&s_cur[b], 1u);
+                const uint32_t pos = s_off[padded<P>(b)] + atomicAdd(&s_cur[b], 1u);
                 s_kx[pos] = rx[q]; s_ky[pos] = ry[q]; s_row[pos] = rr[q]; s_bin[pos] = (uint16_t)b;
             }
         }
@@ -681,7 +755,7 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
             const bool live = q < m;
             const uint64_t kx = live ? s_kx[q] : 0, ky = live ? s_ky[q] : 0;
             const uint32_t b = live ? s_bin[q] : 0;
-            const uint32_t beg = live ? s_off[b] : 0, end = live ? s_off[b + 1] : 0;
+            const uint32_t beg = live ? s_off[padded<P>(b)] : 0, end = live ? s_off[padded<P>(b + 1)] : 0;
             uint32_t len = end - beg;
             for (int off = kWave / 2; off > 0; off >>= 1) {          // longest bin in the wave
                 const uint32_t o = __shfl_xor(len, off, kWave);
@@ -695,17 +769,17 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
             const bool dominated = ((__ballot(dom) >> shift) & ((1u << kGroup) - 1)) != 0;
             if (live && sub == 0) {
                 s_flag[q] = dominated ? 0 : 1;
-                if (!dominated) atomicAdd(&s_foff[b], 1u);
+                if (!dominated) atomicAdd(&s_foff[padded<P>(b)], 1u);
             }
         }
         __syncthreads();
-        scan_sum_excl<kFinishThreads>(s_foff, s_tmp);
-        if (t == 0) out_count[0] = s_foff[kBins];
+        scan_sum_excl<kFinishThreads, true>(s_foff, s_tmp);
+        if (t == 0) out_count[0] = s_foff[padded<P>(kBins)];
         for (uint32_t q = t / kGroup; q < m_pad; q += q_step) {
             const bool live = q < m && s_flag[q];
             const uint64_t kx = live ? s_kx[q] : 0, ky = live ? s_ky[q] : 0;
             const uint32_t b = live ? s_bin[q] : 0, i = live ? s_row[q] : 0;
-            const uint32_t beg = live ? s_off[b] : 0, end = live ? s_off[b + 1] : 0;
+            const uint32_t beg = live ? s_off[padded<P>(b)] : 0, end = live ? s_off[padded<P>(b + 1)] : 0;
             uint32_t len = end - beg;
             for (int off = kWave / 2; off > 0; off >>= 1) {
                 const uint32_t o = __shfl_xor(len, off, kWave);
@@ -721,7 +795,7 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
                 }
                 rank += (uint32_t)__popcll((__ballot(before) >> shift) & ((1ull << kGroup) - 1));
             }
-            const uint64_t pos = (uint64_t)s_foff[b] + rank;
+            const uint64_t pos = (uint64_t)s_foff[padded<P>(b)] + rank;
             if (live && sub == 0 && pos < capacity) out_idx[pos] = i;
         }
     } else {
@@ -732,7 +806,7 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
             sc->bin_foff[i] = 0;
         }
         __syncthreads();
-        scan_sum_excl<kFinishThreads>(sc->bin_off, s_tmp);
+        scan_sum_excl<kFinishThreads, false>(sc->bin_off, s_tmp);
         for (uint32_t q = t; q < m; q += kFinishThreads) {
             const uint32_t b = bin(w.skx[q]);
             w.grouped[sc->bin_off[b] + atomicAdd(&sc->bin_cur[b], 1u)] = q;
@@ -751,7 +825,7 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
             if (!dominated) atomicAdd(&sc->bin_foff[b], 1u);
         }
         __syncthreads();
-        scan_sum_excl<kFinishThreads>(sc->bin_foff, s_tmp);
+        scan_sum_excl<kFinishThreads, false>(sc->bin_foff, s_tmp);
         if (t == 0) out_count[0] = sc->bin_foff[kBins];
         for (uint32_t g = t; g < m; g += kFinishThreads) {
             if (!w.on_front[g]) continue;
@@ -784,8 +858,10 @@ template <int K>
 void launch_top1(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws, hipStream_t stream) {
     const Top1Ws w = top1_ws(ws);
     const uint32_t nb = blocks_for(n);
-    hipLaunchKernelGGL(topk_pass_kernel<K>, dim3(nb), dim3(kBlock), 0, stream, spec.objective, make_filter(spec),
-                       (uint32_t)n, w);
+    with_max_constraints(spec.n_constraints, [&](auto maxc) {
+        hipLaunchKernelGGL((topk_pass_kernel<K, decltype(maxc)::value>), dim3(nb), dim3(kBlock), 0, stream,
+                           spec.objective, make_filter(spec), (uint32_t)n, w);
+    });
     hipLaunchKernelGGL(topk_merge_kernel<K>, dim3(1), dim3(kBlock), 0, stream, w, nb, spec.k, out.idx, out.val, out.count);
 }
 
@@ -839,8 +915,11 @@ hipError_t launch_select_pareto(const guide_select_spec &spec, uint64_t n, const
     const uint32_t nb = blocks_for(n), n32 = (uint32_t)n;
     const double *x = spec.objective, *y = spec.objective_y;
     hipLaunchKernelGGL(pareto_prepare_kernel, dim3(kSampleBlocks), dim3(kBlock), 0, stream, x, y, f, n32, sc);
-    hipLaunchKernelGGL(pareto_stair_kernel, dim3(nb), dim3(kBlock), 0, stream, x, y, f, n32, sc);
-    hipLaunchKernelGGL(pareto_survivors_kernel, dim3(nb), dim3(kBlock), 0, stream, x, y, f, n32, w, sc);
+    with_max_constraints(f.n_con, [&](auto maxc) {
+        constexpr uint32_t MAXC = decltype(maxc)::value;
+        hipLaunchKernelGGL(pareto_stair_kernel<MAXC>, dim3(nb), dim3(kBlock), 0, stream, x, y, f, n32, sc);
+        hipLaunchKernelGGL(pareto_survivors_kernel<MAXC>, dim3(nb), dim3(kBlock), 0, stream, x, y, f, n32, w, sc);
+    });
     hipLaunchKernelGGL(pareto_finish_kernel, dim3(1), dim3(kFinishThreads), 0, stream, w, sc, out.idx, out.capacity,
                        out.count);
     return hipGetLastError();
