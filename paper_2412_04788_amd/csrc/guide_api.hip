@@ -20,7 +20,7 @@ struct guide_ctx {
     SpaceTables *dev_space = nullptr;
     TraceDev *dev_trace = nullptr;
     void *sampled_scratch = nullptr;
-    void *select_scratch = nullptr;   // neutral between calls, see select.hip
+    void *select_scratch = nullptr;   // tables of the Pareto kernels, see select.hip
     // Ring of pinned staging slots for the small per-call tables: the async copy
     // reads the slot later, so a slot is reused only after its event has passed.
     static constexpr int kSlots = 4;
@@ -165,7 +165,6 @@ int guide_create(guide_ctx **out, int device) {
         hipMalloc((void **)&ctx->dev_trace, sizeof(TraceDev)) != hipSuccess ||
         hipMalloc(&ctx->sampled_scratch, sampled_scratch_bytes()) != hipSuccess ||
         hipMalloc(&ctx->select_scratch, select_scratch_bytes()) != hipSuccess ||
-        launch_select_scratch_init(ctx->select_scratch, nullptr) != hipSuccess ||
         hipStreamSynchronize(nullptr) != hipSuccess) {
         guide_destroy(ctx);
         return GUIDE_E_DEVICE;

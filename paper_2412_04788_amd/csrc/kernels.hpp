@@ -15,7 +15,6 @@ hipError_t launch_eval_extras(const GridDesc &g, const DevTables *tab, uint32_t 
                               bool additive, const guide_extras &out, hipStream_t stream);
 
 size_t select_scratch_bytes();
-hipError_t launch_select_scratch_init(void *scratch, hipStream_t stream);
 hipError_t launch_select_topk(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
                               void *scratch, hipStream_t stream);
 hipError_t launch_select_pareto(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,

@@ -69,6 +69,16 @@ __device__ inline uint64_t wave_min(uint64_t v) {
     v = min_u64(v, dpp_keep<0x143, 0xc>(v));
     return read_lane63(v);
 }
+__device__ inline uint32_t wave_max(uint32_t v) {
+    uint32_t o;
+    o = dpp_u32<0xB1>(v, v); v = o > v ? o : v;
+    o = dpp_u32<0x4E>(v, v); v = o > v ? o : v;
+    o = dpp_u32<0x141>(v, v); v = o > v ? o : v;
+    o = dpp_u32<0x140>(v, v); v = o > v ? o : v;
+    o = dpp_u32<0x142, 0xa>(v, v); v = o > v ? o : v;
+    o = dpp_u32<0x143, 0xc>(v, v); v = o > v ? o : v;
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, kWave - 1);
+}
 // Inclusive scans over the lanes of a wave (every lane active).
 __device__ inline uint64_t wave_scan_min(uint64_t v) {
     v = min_u64(v, dpp_keep<0x111>(v));

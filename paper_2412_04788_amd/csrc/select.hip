@@ -109,9 +109,10 @@ uint32_t blocks_for(uint64_t n) {
     return (uint32_t)(need < kSelBlocks ? need : kSelBlocks);
 }
 
-// Context-owned device scratch of the Pareto kernels.  Between calls it is in its
-// neutral state (counters 0, bin_min all-ones, bin_cnt 0): the finishing kernel
-// puts back what the call changed, so no call starts with a clearing pass.
+// Context-owned device scratch of the Pareto kernels.  The first kernel of a call
+// (prepare) puts the tables that the later ones accumulate into (bin_min, bin_cnt,
+// the survivor counter) into their neutral state, so the scratch needs no set-up
+// and no call depends on how the previous one ended.
 constexpr uint32_t kBins = 4096;
 struct SelectScratch {
     uint32_t counters[4];          // [0] survivors appended
@@ -121,17 +122,6 @@ struct SelectScratch {
     uint32_t bin_cnt[kBins];       // survivors per bin
     uint32_t bin_off[kBins + 1], bin_foff[kBins + 1], bin_cur[kBins];   // large-front path only
 };
-
-__global__ void select_scratch_init_kernel(SelectScratch *sc) {
-    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < kBins; i += gridDim.x * blockDim.x) {
-        sc->bin_min[i] = kNone;
-        sc->bin_cnt[i] = 0;
-        sc->bin_cur[i] = 0;
-        sc->bin_off[i] = 0;
-        sc->bin_foff[i] = 0;
-    }
-    if (blockIdx.x == 0 && threadIdx.x < 4) sc->counters[threadIdx.x] = 0;
-}
 
 // ------------------------------------------------------- top-k, one group
 
@@ -162,27 +152,40 @@ struct TopList {
     }
 };
 
-// The K least pairs over all lanes of the block, in order, into res[] of thread 0
-// (every lane of wave 0 holds them).  Rows are unique, so the lane whose head
-// equals the wave minimum is the one that pops.
-template <int K>
-__device__ inline void block_topk(TopList<K> &l, Pair (*s_pairs)[K], Pair *res) {
+// The K least pairs over all lanes of the block, in order: emit(r, pair) is called once for every
+// r < K by some lane of wave 0 (an empty pair when fewer than r + 1 exist).  NW = waves of the block.
+// Stage 1, per wave: K rounds of a key-only minimum; the owner is found by ballot, and only tied
+// keys need a second reduction over rows.  Rows are unique, so one lane pops per round.
+// Stage 2, wave 0: each of the NW * K candidates counts the candidates before it (lane index
+// breaks the tie between empty ones) -- its rank is its output slot.
+template <int K, int NW, typename Emit>
+__device__ inline void block_topk(TopList<K> &l, Pair (*s_pairs)[K], Emit &&emit) {
+    static_assert(NW * K <= kWave, "stage 2 holds one candidate per lane of a wave");
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
 #pragma unroll
     for (int r = 0; r < K; ++r) {
-        const Pair w = wave_min(l.v[0]);
-        if (w.idx != kNone && l.v[0].idx == w.idx && l.v[0].key == w.key) l.pop();
-        if (lane == 0) s_pairs[wave][r] = w;
+        const uint64_t mk = wave_min(l.v[0].key);
+        const bool mine = l.v[0].key == mk && l.v[0].idx != kNone;
+        const uint64_t tied = __ballot(mine);
+        uint64_t mi = kNone;
+        if (__popcll(tied) == 1)
+            mi = __shfl(l.v[0].idx, __ffsll((long long)tied) - 1, kWave);
+        else if (tied)
+            mi = wave_min(mine ? l.v[0].idx : kNone);
+        if (mine && l.v[0].idx == mi) l.pop();
+        if (lane == 0) s_pairs[wave][r] = Pair{mi == kNone ? kNone : mk, mi};
     }
     __syncthreads();
     if (wave == 0) {
-        Pair c = lane < kWaves * K ? s_pairs[lane / K][lane % K] : Pair{kNone, kNone};
+        const Pair *flat = &s_pairs[0][0];
+        const Pair c = lane < NW * K ? flat[lane] : Pair{kNone, kNone};
+        int rank = 0;
 #pragma unroll
-        for (int r = 0; r < K; ++r) {
-            const Pair w = wave_min(c);
-            if (w.idx != kNone && c.idx == w.idx && c.key == w.key) c = Pair{kNone, kNone};
-            res[r] = w;
+        for (int j = 0; j < NW * K; ++j) {
+            const Pair o = flat[j];
+            rank += (less_than(o, c) || (o.key == c.key && o.idx == c.idx && j < lane)) ? 1 : 0;
         }
+        if (lane < NW * K && rank < K) emit(rank, c);
     }
 }
 
@@ -224,14 +227,11 @@ __global__ __launch_bounds__(kBlock) void topk_pass_kernel(const double *__restr
     }
     for (int off = kWave / 2; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, kWave);
     if (threadIdx.x % kWave == 0) s_cnt[threadIdx.x / kWave] = cnt;
-    Pair res[K];
-    block_topk<K>(l, s_pairs, res);
+    block_topk<K, kWaves>(l, s_pairs, [&](int r, const Pair &p) {
+        w.key[(size_t)blockIdx.x * K + r] = p.key;
+        w.idx[(size_t)blockIdx.x * K + r] = p.idx;
+    });                                                 // (contains the barrier that publishes s_cnt)
     if (threadIdx.x == 0) {
-#pragma unroll
-        for (int r = 0; r < K; ++r) {
-            w.key[(size_t)blockIdx.x * K + r] = res[r].key;
-            w.idx[(size_t)blockIdx.x * K + r] = res[r].idx;
-        }
         uint64_t c = 0;
         for (int wv = 0; wv < kWaves; ++wv) c += s_cnt[wv];
         w.cnt[blockIdx.x] = c;
@@ -239,22 +239,24 @@ __global__ __launch_bounds__(kBlock) void topk_pass_kernel(const double *__restr
 }
 
 // One block: the K least of the block partials, and the total count.
+constexpr uint32_t kMergeThreads = 512;
 template <int K>
-__global__ __launch_bounds__(kBlock) void topk_merge_kernel(Top1Ws w, uint32_t n_blocks, uint32_t k, uint64_t *out_idx,
-                                                            double *out_val, uint64_t *out_cnt) {
-    __shared__ Pair s_pairs[kWaves][K];
-    __shared__ uint64_t s_cnt[kWaves];
-    constexpr uint32_t kPer = kSelBlocks * K / kBlock;       // all loads first: one memory latency
+__global__ __launch_bounds__(kMergeThreads) void topk_merge_kernel(Top1Ws w, uint32_t n_blocks, uint32_t k,
+                                                                   uint64_t *out_idx, double *out_val, uint64_t *out_cnt) {
+    constexpr int kNW = kMergeThreads / kWave;
+    __shared__ Pair s_pairs[kNW][K];
+    __shared__ uint64_t s_cnt[kNW];
+    constexpr uint32_t kPer = kSelBlocks * K / kMergeThreads;       // all loads first: one memory latency
     Pair c[kPer];
 #pragma unroll
     for (uint32_t q = 0; q < kPer; ++q) {
-        const uint32_t i = q * kBlock + threadIdx.x;
+        const uint32_t i = q * kMergeThreads + threadIdx.x;
         c[q] = i < n_blocks * K ? Pair{w.key[i], w.idx[i]} : Pair{kNone, kNone};
     }
-    uint64_t pc[kSelBlocks / kBlock];
+    uint64_t pc[kSelBlocks / kMergeThreads];
 #pragma unroll
-    for (uint32_t q = 0; q < kSelBlocks / kBlock; ++q) {
-        const uint32_t i = q * kBlock + threadIdx.x;
+    for (uint32_t q = 0; q < kSelBlocks / kMergeThreads; ++q) {
+        const uint32_t i = q * kMergeThreads + threadIdx.x;
         pc[q] = i < n_blocks ? w.cnt[i] : 0;
     }
     TopList<K> l;
@@ -263,21 +265,18 @@ __global__ __launch_bounds__(kBlock) void topk_merge_kernel(Top1Ws w, uint32_t n
 #pragma unroll
     for (uint32_t q = 0; q < kPer; ++q) l.insert(c[q]);
 #pragma unroll
-    for (uint32_t q = 0; q < kSelBlocks / kBlock; ++q) cnt += pc[q];
+    for (uint32_t q = 0; q < kSelBlocks / kMergeThreads; ++q) cnt += pc[q];
     for (int off = kWave / 2; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, kWave);
     if (threadIdx.x % kWave == 0) s_cnt[threadIdx.x / kWave] = cnt;
-    Pair res[K];
-    block_topk<K>(l, s_pairs, res);
-    if (threadIdx.x == 0) {
-#pragma unroll
-        for (int r = 0; r < K; ++r) {
-            if ((uint32_t)r < k) {
-                out_idx[r] = res[r].idx;
-                out_val[r] = res[r].idx == kNone ? INFINITY : value_of(res[r].key);
-            }
+    block_topk<K, kNW>(l, s_pairs, [&](int r, const Pair &p) {
+        if ((uint32_t)r < k) {
+            out_idx[r] = p.idx;
+            out_val[r] = p.idx == kNone ? INFINITY : value_of(p.key);
         }
+    });
+    if (threadIdx.x == 0) {
         uint64_t t = 0;
-        for (int wv = 0; wv < kWaves; ++wv) t += s_cnt[wv];
+        for (int wv = 0; wv < kNW; ++wv) t += s_cnt[wv];
         out_cnt[0] = t;
     }
 }
@@ -461,6 +460,12 @@ __global__ __launch_bounds__(kBlock) void pareto_prepare_kernel(const double *__
     __shared__ Pair s_best[kWaves];
     const uint32_t k = blockIdx.x * kBlock + threadIdx.x;           // sample number
     const uint32_t n_samples = kSampleBlocks * kBlock;
+    static_assert(kSampleBlocks * kBlock >= kBins, "one table entry per thread");
+    if (k < kBins) {                                                // neutral state for the kernels that follow
+        sc->bin_min[k] = kNone;
+        sc->bin_cnt[k] = 0;
+    }
+    if (k == 0) sc->counters[0] = 0;
     const uint32_t stride = n > n_samples ? n / n_samples : 1;
     const Row r = load_row<true, GUIDE_MAX_CONSTRAINTS>(x, y, f, (uint64_t)k * stride < n ? k * stride : n, n);
     uint64_t lo = kNone;
@@ -712,8 +717,10 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
     __shared__ uint32_t s_row[kStage];
     __shared__ uint16_t s_bin[kStage];
     __shared__ uint8_t s_flag[kStage];
+    __shared__ uint32_t s_nfront;
     const uint32_t t = threadIdx.x;
     __shared__ uint64_t s_rng[2];
+    if (threadIdx.x == 0) s_nfront = 0;
     const uint32_t m = sc->counters[0];
     const Binning bin = sampled_binning(sc, s_rng);
     if (m <= kStage) {
@@ -756,11 +763,7 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
             const uint64_t kx = live ? s_kx[q] : 0, ky = live ? s_ky[q] : 0;
             const uint32_t b = live ? s_bin[q] : 0;
             const uint32_t beg = live ? s_off[padded<P>(b)] : 0, end = live ? s_off[padded<P>(b + 1)] : 0;
-            uint32_t len = end - beg;
-            for (int off = kWave / 2; off > 0; off >>= 1) {          // longest bin in the wave
-                const uint32_t o = __shfl_xor(len, off, kWave);
-                len = o > len ? o : len;
-            }
+            const uint32_t len = wave_max(end - beg);               // longest bin in the wave
             bool dom = false;
             for (uint32_t j0 = 0; j0 < len; j0 += kGroup) {
                 const uint32_t j = beg + j0 + sub;
@@ -769,22 +772,24 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
             const bool dominated = ((__ballot(dom) >> shift) & ((1u << kGroup) - 1)) != 0;
             if (live && sub == 0) {
                 s_flag[q] = dominated ? 0 : 1;
-                if (!dominated) atomicAdd(&s_foff[padded<P>(b)], 1u);
+                if (!dominated) {
+                    atomicAdd(&s_foff[padded<P>(b)], 1u);
+                    s_cur[atomicAdd(&s_nfront, 1u)] = q;            // s_cur is free again: list of front members
+                }
             }
         }
         __syncthreads();
         scan_sum_excl<kFinishThreads, true>(s_foff, s_tmp);
         if (t == 0) out_count[0] = s_foff[padded<P>(kBins)];
-        for (uint32_t q = t / kGroup; q < m_pad; q += q_step) {
-            const bool live = q < m && s_flag[q];
+        const uint32_t nf = s_nfront;
+        const uint32_t f_pad = (nf + q_step - 1) / q_step * q_step;
+        for (uint32_t qf = t / kGroup; qf < f_pad; qf += q_step) {
+            const bool live = qf < nf;
+            const uint32_t q = live ? s_cur[qf] : 0;
             const uint64_t kx = live ? s_kx[q] : 0, ky = live ? s_ky[q] : 0;
             const uint32_t b = live ? s_bin[q] : 0, i = live ? s_row[q] : 0;
             const uint32_t beg = live ? s_off[padded<P>(b)] : 0, end = live ? s_off[padded<P>(b + 1)] : 0;
-            uint32_t len = end - beg;
-            for (int off = kWave / 2; off > 0; off >>= 1) {
-                const uint32_t o = __shfl_xor(len, off, kWave);
-                len = o > len ? o : len;
-            }
+            const uint32_t len = wave_max(end - beg);
             uint32_t rank = 0;
             for (uint32_t j0 = 0; j0 < len; j0 += kGroup) {
                 const uint32_t j = beg + j0 + sub;
@@ -843,13 +848,6 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
             if (pos < capacity) out_idx[pos] = i;
         }
     }
-    __syncthreads();
-    // back to neutral for the next call
-    for (uint32_t i = t; i < kBins; i += kFinishThreads) {
-        sc->bin_min[i] = kNone;
-        sc->bin_cnt[i] = 0;
-    }
-    if (t == 0) sc->counters[0] = 0;
 }
 
 __global__ void pareto_empty_kernel(uint64_t *out_count) { out_count[0] = 0; }
@@ -862,17 +860,14 @@ void launch_top1(const guide_select_spec &spec, uint64_t n, const guide_select_o
         hipLaunchKernelGGL((topk_pass_kernel<K, decltype(maxc)::value>), dim3(nb), dim3(kBlock), 0, stream,
                            spec.objective, make_filter(spec), (uint32_t)n, w);
     });
-    hipLaunchKernelGGL(topk_merge_kernel<K>, dim3(1), dim3(kBlock), 0, stream, w, nb, spec.k, out.idx, out.val, out.count);
+    hipLaunchKernelGGL(topk_merge_kernel<K>, dim3(1), dim3(kMergeThreads), 0, stream, w, nb, spec.k, out.idx, out.val,
+                       out.count);
 }
 
 }  // namespace
 
 size_t select_scratch_bytes() { return sizeof(SelectScratch); }
 
-hipError_t launch_select_scratch_init(void *scratch, hipStream_t stream) {
-    hipLaunchKernelGGL(select_scratch_init_kernel, dim3(16), dim3(kBlock), 0, stream, (SelectScratch *)scratch);
-    return hipGetLastError();
-}
 
 size_t select_workspace_bytes(const guide_select_spec &spec, uint64_t n) {
     if (spec.mode == GUIDE_SELECT_PARETO) return pareto_ws_bytes(n);
