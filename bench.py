@@ -2,10 +2,10 @@
 """Benchmark of the GUIDE optimiser hot path on one MI355X.
 
 One step = one pass of the hot path over the full factorial grid (1 900 800
-configurations): guide_eval_grid (all seven columns), guide_select top-3 by cost
-under the 200 ms TTFT cap, and the (TTFT, cost) Pareto front.  The headline
-value is configurations per second over the timed steps, inputs resident in
-HBM.  The other kernels (efficiency sweep, sampled space, serving simulation)
+configurations) through one guide_eval_select call: all seven columns are
+evaluated and stored, the top-3 by cost under the 200 ms TTFT cap are selected,
+and the (TTFT, cost) Pareto front is extracted.  The headline value is
+configurations per second over the timed steps, inputs resident in HBM.  The other kernels (efficiency sweep, sampled space, serving simulation)
 are timed once each after the steps and reported under "extra".
 Prints ONE JSON line.
 """
@@ -20,10 +20,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the grid kernel from rocprofv3 counters (profiles/eval_tile_kernel_full_grid_pmc.md):
-# WRITE_SIZE 83531.25 KiB x 1.0 + FETCH_SIZE 138.16 KiB x 2.0 (scales from a 512 MiB device copy).
-# Set to None whenever eval_tile_kernel changes after the counters were taken.
-TRAFFIC_BYTES_PER_LAUNCH = 85_818_952
+# HBM bytes per launch of the grid kernel from rocprofv3 counters (profiles/eval_tile_kernel_full_grid_pmc.md),
+# or None when the kernel has changed since the counters were taken.
+TRAFFIC_BYTES_PER_LAUNCH = None
 BYTES_PER_CONFIG = 45           # 5 fp64 + u32 + u8 written per configuration, nothing read
 
 
@@ -35,7 +34,7 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the sweep / sampled / simulation timings")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--probe", action="store_true",
-                    help="counter probe for rocprofv3 --pmc: 10 grid evaluations, then 10 plain device copies of "
+                    help="counter probe for rocprofv3 --pmc: 10 steps, 10 plain grid evaluations, then 10 plain device copies of "
                          "512 MiB (a kernel of known traffic that calibrates FETCH_SIZE / WRITE_SIZE), no timing")
     ap.add_argument("--probe-extra", action="store_true",
                     help="counter probe: the sweep (1.9M x 64), the sampled space (2^28) and the simulation "
@@ -68,21 +67,21 @@ def main():
     ws_top = torch.empty(ctx.select_workspace_bytes(guide.SELECT_TOPK, n), dtype=torch.uint8, device="cuda")
     ws_par = torch.empty(ctx.select_workspace_bytes(guide.SELECT_PARETO, n), dtype=torch.uint8, device="cuda")
 
-    # the three C calls of a step, arguments marshalled once
+    # one C call per step, arguments marshalled once
+    selections = [
+        ctx.column_select(guide.SELECT_TOPK, "cost", sel_idx, sel_val, sel_cnt, use_feasible=True,
+                          constraints=[("t_prefill", wl.TTFT_CAP_S)], k=k_top),
+        ctx.column_select(guide.SELECT_PARETO, "t_prefill", par_idx, None, par_cnt, objective_y="cost",
+                          use_feasible=True, capacity=par_cap),
+    ]
+    ws_step = torch.empty(ctx.eval_select_workspace_bytes(selections, n), dtype=torch.uint8, device="cuda")
+    step = ctx.prepared("eval_select", gg, 0, n, out, selections, ws_step)
+    # the same work as three separate calls (timed outside the timed region, for the phase split)
     call_eval = ctx.prepared("eval_grid", gg, 0, n, out=out)
     call_topk = ctx.prepared("select", guide.SELECT_TOPK, n, out["cost"], sel_idx, sel_val, sel_cnt, ws_top,
                              feasible=out["feasible"], constraints=[(out["t_prefill"], wl.TTFT_CAP_S)], k=k_top)
     call_pareto = ctx.prepared("select", guide.SELECT_PARETO, n, out["t_prefill"], par_idx, None, par_cnt, ws_par,
                                objective_y=out["cost"], feasible=out["feasible"], capacity=par_cap)
-
-    def step(ev=None):
-        if ev:
-            ev[0].record()
-        call_eval()
-        if ev:
-            ev[1].record()
-        call_topk()
-        call_pareto()
 
     if args.probe_extra:
         extra = extra_timings(ctx, gg, g, torch, np, guide, wl)
@@ -92,27 +91,30 @@ def main():
         src = torch.ones(1 << 26, dtype=torch.float64, device="cuda")
         dst = torch.empty_like(src)
         for _ in range(10):
+            step()
+        for _ in range(10):
             call_eval()
         for _ in range(10):
             dst.copy_(src)
         torch.cuda.synchronize()
-        print(json.dumps({"probe": "10 x eval_grid over %d configs, 10 x device copy of %d bytes" % (n, src.numel() * 8)}))
+        print(json.dumps({"probe": "10 x eval_select and 10 x eval_grid over %d configs, 10 x device copy of %d bytes" % (n, src.numel() * 8)}))
         return
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # timed region: K steps; HIP events (torch's current stream is the launch stream) bracket the
-    # grid-evaluation kernel of every step
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    # timed region: K steps; the library brackets the grid-evaluation kernel of every step with a
+    # pair of HIP events on the launch stream (guide_profile_enable)
+    ctx.profile_enable(args.steps)
     t0 = time.perf_counter()
     for k in range(args.steps):
-        step(events[k])
+        step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     total = t1 - t0
-    ms_eval = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
-    # the same kernel launched back to back between one pair of events (no markers between launches)
+    ms_eval = float(np.mean(ctx.profile_read(args.steps)))
+    ctx.profile_enable(0)
+    # the plain evaluation kernel launched back to back between one pair of events (no markers between launches)
     ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     ev2[0].record()
     for _ in range(50):
@@ -120,20 +122,27 @@ def main():
     ev2[1].record()
     torch.cuda.synchronize()
     ms_eval_b2b = ev2[0].elapsed_time(ev2[1]) / 50
-    # phase split of the selections, outside the timed region
-    ev3 = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    # the same step as three separate calls, and the two selections alone
+    ev3 = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
     reps = 20
-    call_eval()
     ev3[0].record()
     for _ in range(reps):
+        call_eval()
         call_topk()
+        call_pareto()
     ev3[1].record()
     for _ in range(reps):
-        call_pareto()
+        call_topk()
     ev3[2].record()
+    for _ in range(reps):
+        call_pareto()
+    ev3[3].record()
     torch.cuda.synchronize()
-    ms_topk = ev3[0].elapsed_time(ev3[1]) / reps
-    ms_pareto = ev3[1].elapsed_time(ev3[2]) / reps
+    ms_separate = ev3[0].elapsed_time(ev3[1]) / reps
+    ms_topk = ev3[1].elapsed_time(ev3[2]) / reps
+    ms_pareto = ev3[2].elapsed_time(ev3[3]) / reps
+    step()
+    torch.cuda.synchronize()
     value = n * args.steps / total
     achieved = BYTES_PER_CONFIG * n / (ms_eval * 1e-3) / 1e9
 
@@ -142,16 +151,18 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": total / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": "full factorial grid, 1900800 configs (5 models x 6 hw x 11 batch x 10 s_in x 8 s_out "
-                               "x 4 tp x 3 wbits x 2 kv_block x 3 mbt): eval_grid + top-3 under 200 ms TTFT + Pareto",
+                               "x 4 tp x 3 wbits x 2 kv_block x 3 mbt): evaluate all columns + top-3 by cost under 200 ms TTFT + "
+                               "(TTFT, cost) Pareto front, one guide_eval_select call",
                    "configs_per_step": n, "top_k": k_top,
                    "selected": [int(v) for v in sel_idx.cpu().numpy().view(np.uint64)],
                    "pareto_front_size": int(par_cnt.item())},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH,
-                     "kernel": "eval_tile_kernel<false,2,3>",
+                     "kernel": "eval_tile_kernel<false,2,3,true>",
                      "kernel_ms": ms_eval, "kernel_ms_back_to_back": ms_eval_b2b,
                      "bytes_per_config": BYTES_PER_CONFIG},
-        "phases_ms": {"eval_grid": ms_eval, "select_topk": ms_topk, "select_pareto": ms_pareto},
+        "phases_ms": {"eval_kernel_in_step": ms_eval, "step_as_three_calls": ms_separate,
+                      "select_topk_alone": ms_topk, "select_pareto_alone": ms_pareto},
     }
 
     if not args.no_extra:

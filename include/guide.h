@@ -293,6 +293,53 @@ size_t guide_select_workspace_bytes(const guide_select_spec *spec, uint64_t n);
 int guide_select(guide_ctx *ctx, const guide_select_spec *spec, uint64_t n, const guide_select_out *out,
                  void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Evaluate and select in one call: the same results as guide_eval_grid(out) with
+ * one efficiency sample followed by guide_select for each of the n_sel
+ * selections on the columns of `out` (rows = the `count` evaluated
+ * configurations, one group) -- the engine's "evaluate every configuration, keep
+ * the best" (Inference Engine Step 2; Simulating Hybrid Parallelism) without a
+ * pass of its own over the columns where the library can avoid one: for a grid
+ * whose two fastest axes have a tile kernel, a top-k selection with k <= 4 is
+ * reduced inside the evaluation kernel, and the Pareto selection's row sample is
+ * taken there.  Columns are named by GUIDE_COL_*.  At most one selection per mode
+ * (n_sel <= 2; n_sel = 0 is a plain evaluation).  Every column that a selection
+ * refers to, and `feasible` when use_feasible is set, must be present in `out`
+ * (GUIDE_E_ARG otherwise), except for a top-k reduced inside the evaluation,
+ * which needs none of them stored.
+ * workspace: DEVICE, guide_eval_select_workspace_bytes(sel, n_sel, count) bytes.
+ */
+enum { GUIDE_COL_T_PREFILL = 0, GUIDE_COL_T_DECODE = 1, GUIDE_COL_T_BATCH = 2, GUIDE_COL_DECODE_TOK_S = 3,
+       GUIDE_COL_COST = 4, GUIDE_NUM_COLS = 5 };
+typedef struct { uint32_t column; uint32_t reserved; double cap; } guide_column_constraint;
+typedef struct {
+    uint32_t mode;          /* GUIDE_SELECT_TOPK | GUIDE_SELECT_PARETO */
+    uint32_t objective;     /* GUIDE_COL_*, minimised */
+    uint32_t objective_y;   /* Pareto only */
+    uint32_t use_feasible;  /* != 0: rows with feasible == 0 do not pass */
+    uint32_t n_constraints;
+    uint32_t k;             /* top-k only, <= GUIDE_MAX_TOPK */
+    guide_column_constraint constraints[GUIDE_MAX_CONSTRAINTS];
+    guide_select_out out;   /* as for guide_select */
+} guide_column_select;
+
+size_t guide_eval_select_workspace_bytes(const guide_column_select *sel, uint32_t n_sel, uint64_t count);
+int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, uint64_t count, const guide_eff *eff,
+                      uint32_t time_model, const guide_metrics *out, const guide_column_select *sel, uint32_t n_sel,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Kernel timing aid.  After guide_profile_enable(ctx, capacity) every grid
+ * evaluation kernel launched by guide_eval_grid (one sample) or guide_eval_select
+ * is bracketed by a pair of HIP events recorded on the call's stream, for up to
+ * `capacity` launches (later ones are not timed); capacity 0 switches it off.
+ * guide_profile_read waits for the recorded events, writes the elapsed
+ * milliseconds of each timed launch to ms[0 .. *n) (HOST, room for `capacity`
+ * values) and starts over.
+ */
+int guide_profile_enable(guide_ctx *ctx, uint32_t capacity);
+int guide_profile_read(guide_ctx *ctx, float *ms, uint32_t *n);
+
 #ifdef __cplusplus
 }
 #endif

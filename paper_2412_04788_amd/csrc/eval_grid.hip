@@ -3,6 +3,7 @@
 // structure-of-arrays stores.
 #include "kernels.hpp"
 #include "perf_model.hpp"
+#include "select_shared.hpp"
 
 namespace guide {
 
@@ -100,41 +101,76 @@ __global__ __launch_bounds__(kBlock) void eval_grid_kernel(GridDesc g, const Dev
 // once, and the wave transposes each output column through LDS so that global
 // stores stay coalesced (lane l stores index base + 64*it + l).
 
+// What a block needs besides the index range is the same for every block and every call on an
+// unchanged grid: the axis values, models and hardware reciprocals, the nudged reciprocals of the
+// divisors, and the per-op FLOPs / bytes of every (model, tp, precision) combination.  A one-block
+// kernel derives them once into device memory (when the context's tables change); the evaluation
+// blocks copy them into LDS.
 constexpr uint32_t kCoefRows = 96;          // (model, tp, precision) rows of per-op coefficients kept in LDS
-struct TileLds {
+struct alignas(16) TileLds {
     GridLds g;
-    Coef coef[kCoefRows];
     double r_tp[GUIDE_MAX_AXIS_VALUES];     // 1 / tp
     double r_sin[GUIDE_MAX_AXIS_VALUES];    // nudged reciprocals for exact floor division
     double r_blk[GUIDE_MAX_AXIS_VALUES];
     double r_mbt[GUIDE_MAX_AXIS_VALUES];
+    Coef coef[kCoefRows];                   // last: only the rows in use are copied
 };
+static_assert(offsetof(TileLds, coef) % 16 == 0 && sizeof(Coef) % 8 == 0, "copied in 8-byte words");
 
-template <bool ADDITIVE, int NB, int NM>
+__global__ __launch_bounds__(kBlock) void tile_tables_kernel(GridDesc g, const DevTables *__restrict__ tab,
+                                                             TileLds *__restrict__ dst) {
+    stage_grid_tables(dst->g, g, tab);
+    for (uint32_t i = threadIdx.x; i < GUIDE_MAX_AXIS_VALUES; i += blockDim.x) {
+        dst->r_tp[i] = 1.0 / (double)max(tab->axis_vals[AX_TP][i], 1u);
+        dst->r_sin[i] = recip_up(1.0 / (double)max(tab->axis_vals[AX_SIN][i], 1u));
+        dst->r_blk[i] = recip_up(1.0 / (double)max(tab->axis_vals[AX_BLK][i], 1u));
+        dst->r_mbt[i] = recip_up(1.0 / (double)max(tab->axis_vals[AX_MBT][i], 1u));
+    }
+    const uint32_t n_tp = g.div[AX_TP].d, n_w = g.div[AX_WBITS].d;
+    const uint32_t n_rows = g.div[AX_MODEL].d * n_tp * n_w;
+    if (n_rows <= kCoefRows) {
+        for (uint32_t r = threadIdx.x; r < n_rows; r += blockDim.x) {
+            const uint32_t dw = r % n_w, dt = (r / n_w) % n_tp, dm = r / (n_w * n_tp);
+            const uint32_t p = tab->axis_vals[AX_TP][dt];
+            dst->coef[r] = make_coef(tab->models[tab->axis_vals[AX_MODEL][dm]], p, tab->axis_vals[AX_WBITS][dw],
+                                     1.0 / (double)p);
+        }
+    }
+}
+
+// FUSED: selections folded in (FusedSelect); every block then writes its top-K partials and / or its
+// sample partial, also when it owns no tile.
+template <bool ADDITIVE, int NB, int NM, bool FUSED>
 __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const DevTables *__restrict__ tab,
                                                            uint32_t first, uint32_t count, double re_c, double re_b,
-                                                           guide_metrics out) {
+                                                           guide_metrics out, FusedSelect fs, Div32 stride_div,
+                                                           uint32_t n_samples, const TileLds *__restrict__ derived) {
     constexpr int TS = NB * NM;
     constexpr int kWaves = kBlock / kWave;
     __shared__ TileLds s;
     __shared__ double s_x[kWaves][kWave * TS];
-    stage_grid_tables(s.g, g, tab);
-    for (uint32_t i = threadIdx.x; i < GUIDE_MAX_AXIS_VALUES; i += blockDim.x) {
-        s.r_tp[i] = 1.0 / (double)max(tab->axis_vals[AX_TP][i], 1u);
-        s.r_sin[i] = recip_up(1.0 / (double)max(tab->axis_vals[AX_SIN][i], 1u));
-        s.r_blk[i] = recip_up(1.0 / (double)max(tab->axis_vals[AX_BLK][i], 1u));
-        s.r_mbt[i] = recip_up(1.0 / (double)max(tab->axis_vals[AX_MBT][i], 1u));
-    }
-    // per-op FLOPs / bytes of every (model, tp, precision) combination of the grid, once per block
     const uint32_t n_tp = g.div[AX_TP].d, n_w = g.div[AX_WBITS].d;
     const uint32_t n_rows = g.div[AX_MODEL].d * n_tp * n_w;
     const bool coef_in_lds = n_rows <= kCoefRows;
-    if (coef_in_lds) {
-        for (uint32_t r = threadIdx.x; r < n_rows; r += blockDim.x) {
-            const uint32_t dw = r % n_w, dt = (r / n_w) % n_tp, dm = r / (n_w * n_tp);
-            const uint32_t p = tab->axis_vals[AX_TP][dt];
-            s.coef[r] = make_coef(tab->models[tab->axis_vals[AX_MODEL][dm]], p, tab->axis_vals[AX_WBITS][dw],
-                                  1.0 / (double)p);
+    {
+        const uint32_t words = (uint32_t)(offsetof(TileLds, coef) + (coef_in_lds ? n_rows : 0u) * sizeof(Coef)) / 8;
+        const uint64_t *src = (const uint64_t *)derived;
+        uint64_t *dst = (uint64_t *)&s;
+        for (uint32_t i = threadIdx.x; i < words; i += kBlock) dst[i] = src[i];
+    }
+    TopList<kFusedTopK> top;
+    uint64_t n_pass = 0, smp_lo = kNone, top_bound = kNone;
+    uint32_t batch = 0;
+    Pair smp_best = {kNone, kNone};
+    if (FUSED) {
+        top.init();
+        if (fs.pareto) {                                         // neutral state for the Pareto kernels that follow
+            SelectScratch *sc = (SelectScratch *)fs.scratch;
+            for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < kBins; i += gridDim.x * kBlock) {
+                sc->bin_min[i] = kNone;
+                sc->bin_cnt[i] = 0;
+            }
+            if (blockIdx.x == 0 && threadIdx.x == 0) sc->counters[0] = 0;
         }
     }
     __syncthreads();
@@ -193,8 +229,11 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
         };
 
         // memory check: depends on the block size only
-        if (out.b_max || out.feasible) {
-            MemResult mem[NB];
+        MemResult mem[NB];
+        const bool need_mem = out.b_max || out.feasible ||
+                              (FUSED && ((fs.topk && fs.topk_filter.use_feasible) ||
+                                         (fs.pareto && fs.pareto_filter.use_feasible)));
+        if (need_mem) {
             const double c_avail = hw.cap - cf.w_gpu;
             const uint32_t tok = kn.s_in + kn.s_out;
 #pragma unroll
@@ -207,6 +246,8 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
                 mem[k].feasible = room && (double)kn.b * kv_req <= c_avail;
                 mem[k].b_max = !room ? 0u : (q >= 4294967295.0 ? 4294967295u : (uint32_t)q);
             }
+        }
+        if (out.b_max || out.feasible) {
             uint32_t *xi = (uint32_t *)xw;
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 #pragma unroll
@@ -240,9 +281,140 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
                                                         s.r_mbt[m]);
         const double bs = (double)kn.b * (double)kn.s_out;
         const double cost_f = (double)kn.p * (1.0e6 / 3600.0) * fast_recip(bs);
+        double t_batch[NM], cost[NM];
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+            t_batch[m] = t_prefill[m] + t_decode;
+            cost[m] = t_batch[m] * cost_f;
+        }
         store_f64(out.t_prefill, [&](int j) { return t_prefill[j % NM]; });
-        store_f64(out.t_batch, [&](int j) { return t_prefill[j % NM] + t_decode; });
-        store_f64(out.cost, [&](int j) { return (t_prefill[j % NM] + t_decode) * cost_f; });
+        store_f64(out.t_batch, [&](int j) { return t_batch[j % NM]; });
+        store_f64(out.cost, [&](int j) { return cost[j % NM]; });
+
+        if (FUSED) {
+            // The selections see exactly the values stored above.  A column's value depends on the
+            // token-budget digit m at most and feasibility on the block-size digit k only, so the
+            // filters and keys are worked out once per m and each row costs a few compares.
+            const bool tile_real = tb + lane < n_tiles;
+            const uint32_t row0 = (t_first + tl) * TS;
+            auto col = [&](uint32_t id, int m) {
+                return id == GUIDE_COL_T_PREFILL ? t_prefill[m]
+                       : id == GUIDE_COL_T_DECODE ? t_decode
+                       : id == GUIDE_COL_T_BATCH ? t_batch[m]
+                       : id == GUIDE_COL_DECODE_TOK_S ? tok_s : cost[m];
+            };
+            auto passes = [&](const FusedFilter &f, int m) {
+                bool ok = true;
+                for (uint32_t c = 0; c < f.n_con; ++c) ok = ok && (col(f.col[c], m) <= f.cap[c]);
+                return ok;
+            };
+            if (fs.topk) {
+                uint64_t key[NM];
+                bool ok_m[NM], cand = false;
+                uint32_t n_ok = 0;
+#pragma unroll
+                for (int m = 0; m < NM; ++m) {
+                    const double v = col(fs.topk_obj, m);
+                    key[m] = key_of(v);
+                    ok_m[m] = tile_real && v == v && passes(fs.topk_filter, m);
+                    n_ok += ok_m[m] ? 1u : 0u;
+                    cand = cand || (ok_m[m] && key[m] <= top_bound);
+                }
+                auto feas = [&](int k) { return !fs.topk_filter.use_feasible || mem[k].feasible; };
+                if (full) {
+                    // every row of the wave's tiles is in range: passing rows are counted per tile, and the
+                    // rows are visited only when one of them can still enter the list
+                    uint32_t n_f = 0;
+#pragma unroll
+                    for (int k = 0; k < NB; ++k) n_f += feas(k) ? 1u : 0u;
+                    n_pass += n_ok * n_f;
+                    if (cand) {
+#pragma unroll
+                        for (int j = 0; j < TS; ++j) {
+                            const int k = j / NM, m = j % NM;
+                            if (ok_m[m] && feas(k) && key[m] <= top_bound)
+                                top.insert(Pair{key[m], (uint64_t)(row0 + j - first)});
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < TS; ++j) {
+                        const int k = j / NM, m = j % NM;
+                        const uint32_t row = row0 + j;
+                        if (ok_m[m] && row >= first && row < last && feas(k)) {
+                            ++n_pass;
+                            if (key[m] <= top_bound) top.insert(Pair{key[m], (uint64_t)(row - first)});
+                        }
+                    }
+                }
+                // Some lane already holds K keys at or below the least K-th key of the wave's lanes, so a
+                // row above it cannot be among the block's K least.  The bound tightens fast at first and
+                // slowly later: refreshed after each of the first four batches, then after every fourth.
+                if (batch < 4 || (batch & 3) == 0) top_bound = wave_min(top.v[kFusedTopK - 1].key);
+                ++batch;
+            }
+            if (fs.pareto) {
+                // sample rows are the multiples of the stride (relative to `first`): visit those inside the tile
+                const uint32_t stride = stride_div.d;
+                const uint32_t lo_row = row0 > first ? row0 : first;              // first candidate row of the tile
+                const uint32_t hi_row = row0 + TS < last ? row0 + TS : last;      // exclusive
+                if (tile_real && lo_row < hi_row) {
+                    uint32_t q = div32(lo_row - first + stride - 1, stride_div);  // first multiple at or after lo_row
+                    for (uint32_t i = q * stride; i < hi_row - first && q < n_samples; i += stride, ++q) {
+                        const int j = (int)(i + first - row0), k = j / NM, m = j % NM;
+                        const double x = col(fs.pareto_x, m), y = col(fs.pareto_y, m);
+                        bool feas = true;
+#pragma unroll
+                        for (int kk = 0; kk < NB; ++kk) feas = kk == k ? mem[kk].feasible : feas;
+                        if (x == x && y == y && passes(fs.pareto_filter, m) && (!fs.pareto_filter.use_feasible || feas)) {
+                            const uint64_t kx = key_of(x);
+                            smp_lo = min_u64(smp_lo, kx);
+                            smp_best = pair_min(smp_best, Pair{key_of(y), kx});
+                        }
+                    }
+                }
+            }
+        }
+    }
+    if (FUSED) {
+        constexpr int kCap = 8;
+        __shared__ Pair s_pairs[kWaves][kFusedTopK], s_cand[kWaves][kCap];
+        __shared__ uint32_t s_n[kWaves];
+        __shared__ uint64_t s_cnt[kWaves], s_lo[kWaves];
+        __shared__ Pair s_best[kWaves];
+        if (fs.topk) {
+            const Top1Ws w = top1_ws(fs.topk_ws);
+            for (int off = kWave / 2; off > 0; off >>= 1) n_pass += __shfl_xor(n_pass, off, kWave);
+            if (lane == 0) s_cnt[wave] = n_pass;
+            top_bound = wave_min(top.v[kFusedTopK - 1].key);
+            block_topk_bounded<kFusedTopK, kWaves, kCap>(top, top_bound, s_cand, s_n, s_pairs, [&](int r, const Pair &p) {
+                w.key[(size_t)blockIdx.x * kFusedTopK + r] = p.key;
+                w.idx[(size_t)blockIdx.x * kFusedTopK + r] = p.idx;
+            });                                          // (contains the barrier that publishes s_cnt)
+            if (threadIdx.x == 0) {
+                uint64_t c = 0;
+                for (int wv = 0; wv < kWaves; ++wv) c += s_cnt[wv];
+                w.cnt[blockIdx.x] = c;
+            }
+        }
+        if (fs.pareto) {
+            SelectScratch *sc = (SelectScratch *)fs.scratch;
+            smp_lo = wave_min(smp_lo);
+            smp_best = wave_min(smp_best);
+            if (lane == 0) {
+                s_lo[wave] = smp_lo;
+                s_best[wave] = smp_best;
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                for (int wv = 1; wv < kWaves; ++wv) {
+                    smp_lo = min_u64(smp_lo, s_lo[wv]);
+                    smp_best = pair_min(smp_best, s_best[wv]);
+                }
+                sc->sample_lo[blockIdx.x] = smp_lo;
+                sc->sample_best[blockIdx.x] = smp_best;
+            }
+        }
     }
 }
 
@@ -386,40 +558,84 @@ static uint32_t blocks_for(uint32_t count) {
     return need < cap ? need : cap;
 }
 
-template <bool ADDITIVE, int NB, int NM>
-static void launch_tile(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, double re_c,
-                        double re_b, const guide_metrics &out, hipStream_t stream) {
-    const uint32_t ts = NB * NM;
+static uint32_t tile_blocks(uint32_t first, uint32_t count, uint32_t ts) {
     const uint32_t n_tiles = (first + count - 1) / ts - first / ts + 1;
     // two persistent blocks per compute unit: every wave loops over several batches of 64 tiles, so the
     // stores of one batch overlap the arithmetic of the next (measured best among 1..8 blocks per CU)
     const uint32_t need = (n_tiles + kBlock - 1) / kBlock, cap = 2 * kNumCU;
-    const dim3 grid(need < cap ? need : cap), block(kBlock);
-    hipLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM>), grid, block, 0, stream, g, tab, first, count, re_c, re_b, out);
+    return need < cap ? need : cap;
+}
+
+// Sampling of rows for the Pareto bin range: row i is a sample when i = q * stride with q < kSampleRows.
+constexpr uint32_t kSampleRows = 16384;
+
+template <bool ADDITIVE, int NB, int NM>
+static void launch_tile(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
+                        uint32_t count, double re_c, double re_b, const guide_metrics &out, const FusedSelect *fs,
+                        hipStream_t stream) {
+    const dim3 grid(tile_blocks(first, count, NB * NM)), block(kBlock);
+    static_assert(2 * kNumCU <= kMaxSamplePartials && 2 * kNumCU <= kSelBlocks, "one partial per block");
+    if (fs) {
+        const uint32_t stride = count > kSampleRows ? count / kSampleRows : 1;
+        hipLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM, true>), grid, block, 0, stream, g, tab, first, count, re_c,
+                           re_b, out, *fs, make_div32(stride), kSampleRows, (const TileLds *)tile_tables);
+    } else {
+        hipLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM, false>), grid, block, 0, stream, g, tab, first, count, re_c,
+                           re_b, out, FusedSelect{}, Div32{}, 0u, (const TileLds *)tile_tables);
+    }
 }
 
 // Tile shapes with a compiled kernel; other grids take the one-index-per-lane kernel.
+#define GUIDE_TILE_SHAPES(X) X(2, 3) X(1, 3) X(2, 1) X(2, 2) X(1, 2) X(3, 3) X(1, 4) X(2, 4)
+
 template <bool ADDITIVE>
-static bool dispatch_tile(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, double re_c,
-                          double re_b, const guide_metrics &out, hipStream_t stream) {
+static bool dispatch_tile(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
+                          uint32_t count, double re_c, double re_b, const guide_metrics &out, const FusedSelect *fs,
+                          hipStream_t stream, uint32_t *n_blocks) {
     const uint32_t nb = g.div[AX_BLK].d, nm = g.div[AX_MBT].d;
-#define GUIDE_TILE(NB, NM)                                                               \
-    if (nb == NB && nm == NM) {                                                          \
-        launch_tile<ADDITIVE, NB, NM>(g, tab, first, count, re_c, re_b, out, stream);    \
-        return true;                                                                     \
+#define GUIDE_TILE(NB, NM)                                                                   \
+    if (nb == NB && nm == NM) {                                                              \
+        launch_tile<ADDITIVE, NB, NM>(g, tab, tile_tables, first, count, re_c, re_b, out, fs, stream); \
+        if (n_blocks) *n_blocks = tile_blocks(first, count, NB * NM);                        \
+        return true;                                                                         \
     }
-    GUIDE_TILE(2, 3) GUIDE_TILE(1, 3) GUIDE_TILE(2, 1) GUIDE_TILE(2, 2) GUIDE_TILE(1, 2) GUIDE_TILE(3, 3)
-    GUIDE_TILE(1, 4) GUIDE_TILE(2, 4)
+    GUIDE_TILE_SHAPES(GUIDE_TILE)
 #undef GUIDE_TILE
     return false;
 }
 
-hipError_t launch_eval_grid(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, double e_c,
-                            double e_b, bool additive, const guide_metrics &out, hipStream_t stream) {
+bool eval_grid_can_fuse(const GridDesc &g) {
+    const uint32_t nb = g.div[AX_BLK].d, nm = g.div[AX_MBT].d;
+#define GUIDE_TILE(NB, NM) if (nb == NB && nm == NM) return true;
+    GUIDE_TILE_SHAPES(GUIDE_TILE)
+#undef GUIDE_TILE
+    return false;
+}
+
+size_t tile_tables_bytes() { return sizeof(TileLds); }
+
+hipError_t launch_tile_tables(const GridDesc &g, const DevTables *tab, void *tile_tables, hipStream_t stream) {
+    hipLaunchKernelGGL(tile_tables_kernel, dim3(1), dim3(kBlock), 0, stream, g, tab, (TileLds *)tile_tables);
+    return hipGetLastError();
+}
+
+hipError_t launch_eval_grid_fused(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
+                                  uint32_t count, double e_c, double e_b, bool additive, const guide_metrics &out,
+                                  const FusedSelect &fs, hipStream_t stream, uint32_t *n_blocks) {
+    const double re_c = 1.0 / e_c, re_b = 1.0 / e_b;
+    const bool done =
+        additive ? dispatch_tile<true>(g, tab, tile_tables, first, count, re_c, re_b, out, &fs, stream, n_blocks)
+                 : dispatch_tile<false>(g, tab, tile_tables, first, count, re_c, re_b, out, &fs, stream, n_blocks);
+    return done ? hipGetLastError() : hipErrorNotSupported;
+}
+
+hipError_t launch_eval_grid(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
+                            uint32_t count, double e_c, double e_b, bool additive, const guide_metrics &out,
+                            hipStream_t stream) {
     const dim3 grid(blocks_for(count)), block(kBlock);
     const double re_c = 1.0 / e_c, re_b = 1.0 / e_b;
-    if (additive ? dispatch_tile<true>(g, tab, first, count, re_c, re_b, out, stream)
-                 : dispatch_tile<false>(g, tab, first, count, re_c, re_b, out, stream))
+    if (additive ? dispatch_tile<true>(g, tab, tile_tables, first, count, re_c, re_b, out, nullptr, stream, nullptr)
+                 : dispatch_tile<false>(g, tab, tile_tables, first, count, re_c, re_b, out, nullptr, stream, nullptr))
         return hipGetLastError();
     if (additive)
         hipLaunchKernelGGL(eval_grid_kernel<true>, grid, block, 0, stream, g, tab, first, count, re_c, re_b, out);

@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "kernels.hpp"
 
@@ -17,6 +18,10 @@ struct guide_ctx {
     bool sent_valid = false;
     hipStream_t sent_stream = nullptr;
     DevTables *dev_tab = nullptr;
+    uint64_t tab_gen = 0;            // counts uploads of dev_tab
+    void *dev_tile = nullptr;        // tables derived from (grid description, dev_tab) for the tile kernels
+    GridDesc tile_desc;              // what dev_tile was derived from: this description ...
+    uint64_t tile_gen = 0;           // ... and this upload of dev_tab (0 = never)
     SpaceTables *dev_space = nullptr;
     TraceDev *dev_trace = nullptr;
     void *sampled_scratch = nullptr;
@@ -28,6 +33,10 @@ struct guide_ctx {
     void *slot[kSlots] = {nullptr, nullptr, nullptr, nullptr};
     hipEvent_t slot_ev[kSlots] = {nullptr, nullptr, nullptr, nullptr};
     int next_slot = 0;
+    // kernel timing aid: event pairs around evaluation kernels (guide_profile_enable)
+    std::vector<hipEvent_t> prof_ev;     // 2 * capacity events
+    uint32_t prof_used = 0;              // timed launches since the last read
+    hipStream_t prof_stream = nullptr;
     char err[256] = {0};
 };
 static_assert(guide_ctx::kSlotBytes >= sizeof(DevTables), "staging slot too small");
@@ -140,10 +149,94 @@ int upload_tables(guide_ctx *ctx, hipStream_t stream) {
     memcpy(&ctx->sent_tab, &ctx->host_tab, sizeof(DevTables));
     ctx->sent_valid = true;
     ctx->sent_stream = stream;
+    ++ctx->tab_gen;
+    return GUIDE_OK;
+}
+
+// upload_tables, then the derived tables of the tile kernels when the upload or the grid's radices
+// are new (a new stream re-uploads, so the derivation is ordered on the stream that reads it).
+int upload_grid_tables(guide_ctx *ctx, const GridDesc &desc, hipStream_t stream) {
+    const int rc = upload_tables(ctx, stream);
+    if (rc) return rc;
+    if (ctx->tile_gen == ctx->tab_gen && memcmp(&ctx->tile_desc, &desc, sizeof desc) == 0) return GUIDE_OK;
+    const hipError_t e = launch_tile_tables(desc, ctx->dev_tab, ctx->dev_tile, stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "tile tables launch");
+    memcpy(&ctx->tile_desc, &desc, sizeof desc);
+    ctx->tile_gen = ctx->tab_gen;
     return GUIDE_OK;
 }
 
 bool time_model_ok(uint32_t tm) { return tm == GUIDE_TIME_ROOFLINE || tm == GUIDE_TIME_ADDITIVE; }
+
+// Event pair around one evaluation kernel, when timing is enabled and a pair is left.
+struct KernelTimer {
+    guide_ctx *ctx;
+    hipStream_t stream;
+    bool on;
+    KernelTimer(guide_ctx *c, hipStream_t s) : ctx(c), stream(s), on(2 * (size_t)c->prof_used + 1 < c->prof_ev.size()) {
+        if (on) (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_used], stream);
+    }
+    ~KernelTimer() {
+        if (on) {
+            (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_used + 1], stream);
+            ++ctx->prof_used;
+        }
+    }
+};
+
+const double *metric_column(const guide_metrics &m, uint32_t id) {
+    switch (id) {
+        case GUIDE_COL_T_PREFILL: return m.t_prefill;
+        case GUIDE_COL_T_DECODE: return m.t_decode;
+        case GUIDE_COL_T_BATCH: return m.t_batch;
+        case GUIDE_COL_DECODE_TOK_S: return m.decode_tok_s;
+        case GUIDE_COL_COST: return m.cost;
+        default: return nullptr;
+    }
+}
+
+size_t round_up_256(size_t b) { return (b + 255) / 256 * 256; }
+
+// guide_select's description of a column selection (column pointers from `out`; NULL where not stored).
+guide_select_spec spec_of(const guide_column_select &c, const guide_metrics &out) {
+    guide_select_spec s;
+    memset(&s, 0, sizeof s);
+    s.mode = c.mode;
+    s.objective = metric_column(out, c.objective);
+    s.objective_y = c.mode == GUIDE_SELECT_PARETO ? metric_column(out, c.objective_y) : nullptr;
+    s.feasible = c.use_feasible ? out.feasible : nullptr;
+    s.n_constraints = c.n_constraints;
+    for (uint32_t i = 0; i < c.n_constraints && i < GUIDE_MAX_CONSTRAINTS; ++i) {
+        s.constraints[i].column = metric_column(out, c.constraints[i].column);
+        s.constraints[i].cap = c.constraints[i].cap;
+    }
+    s.group = nullptr;
+    s.n_groups = 1;
+    s.k = c.k;
+    return s;
+}
+
+bool columns_present(const guide_column_select &c, const guide_metrics &out) {
+    const guide_select_spec s = spec_of(c, out);
+    if (!s.objective) return false;
+    if (c.mode == GUIDE_SELECT_PARETO && !s.objective_y) return false;
+    if (c.use_feasible && !out.feasible) return false;
+    for (uint32_t i = 0; i < c.n_constraints; ++i)
+        if (!s.constraints[i].column) return false;
+    return true;
+}
+
+FusedFilter filter_of(const guide_column_select &c) {
+    FusedFilter f;
+    memset(&f, 0, sizeof f);
+    f.use_feasible = c.use_feasible ? 1u : 0u;
+    f.n_con = c.n_constraints;
+    for (uint32_t i = 0; i < c.n_constraints; ++i) {
+        f.col[i] = c.constraints[i].column;
+        f.cap[i] = c.constraints[i].cap;
+    }
+    return f;
+}
 
 }  // namespace
 
@@ -159,12 +252,14 @@ int guide_create(guide_ctx **out, int device) {
     ctx->device = device;
     memset(&ctx->host_tab, 0, sizeof ctx->host_tab);
     memset(&ctx->sent_tab, 0, sizeof ctx->sent_tab);
+    memset(&ctx->tile_desc, 0, sizeof ctx->tile_desc);
     DeviceGuard guard(device);
     if (!guard.ok || hipMalloc((void **)&ctx->dev_tab, sizeof(DevTables)) != hipSuccess ||
         hipMalloc((void **)&ctx->dev_space, sizeof(SpaceTables)) != hipSuccess ||
         hipMalloc((void **)&ctx->dev_trace, sizeof(TraceDev)) != hipSuccess ||
         hipMalloc(&ctx->sampled_scratch, sampled_scratch_bytes()) != hipSuccess ||
         hipMalloc(&ctx->select_scratch, select_scratch_bytes()) != hipSuccess ||
+        hipMalloc(&ctx->dev_tile, tile_tables_bytes()) != hipSuccess ||
         hipStreamSynchronize(nullptr) != hipSuccess) {
         guide_destroy(ctx);
         return GUIDE_E_DEVICE;
@@ -188,10 +283,12 @@ void guide_destroy(guide_ctx *ctx) {
     if (ctx->dev_trace) (void)hipFree(ctx->dev_trace);
     if (ctx->sampled_scratch) (void)hipFree(ctx->sampled_scratch);
     if (ctx->select_scratch) (void)hipFree(ctx->select_scratch);
+    if (ctx->dev_tile) (void)hipFree(ctx->dev_tile);
     for (int i = 0; i < guide_ctx::kSlots; ++i) {
         if (ctx->slot_ev[i]) { (void)hipEventSynchronize(ctx->slot_ev[i]); (void)hipEventDestroy(ctx->slot_ev[i]); }
         if (ctx->slot[i]) (void)hipHostFree(ctx->slot[i]);
     }
+    for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
     delete ctx;
 }
 
@@ -253,7 +350,7 @@ int guide_eval_grid(guide_ctx *ctx, const guide_grid *grid, uint64_t first, uint
         ctx->host_tab.eff_c[i] = eff->e_c[i];
         ctx->host_tab.eff_b[i] = eff->e_b[i];
     }
-    rc = upload_tables(ctx, stream);
+    rc = n_eff > 1 ? upload_tables(ctx, stream) : upload_grid_tables(ctx, desc, stream);
     if (rc) return rc;
     hipError_t e;
     if (n_eff > 1) {
@@ -261,10 +358,174 @@ int guide_eval_grid(guide_ctx *ctx, const guide_grid *grid, uint64_t first, uint
                               time_model == GUIDE_TIME_ADDITIVE, *stats, stream);
     } else {
         const double e_c = n_eff ? eff->e_c[0] : 1.0, e_b = n_eff ? eff->e_b[0] : 1.0;
-        e = launch_eval_grid(desc, ctx->dev_tab, (uint32_t)first, (uint32_t)count, e_c, e_b,
+        KernelTimer timer(ctx, stream);
+        e = launch_eval_grid(desc, ctx->dev_tab, ctx->dev_tile, (uint32_t)first, (uint32_t)count, e_c, e_b,
                              time_model == GUIDE_TIME_ADDITIVE, *out, stream);
     }
     if (e != hipSuccess) return hip_fail(ctx, e, "eval_grid launch");
+    return GUIDE_OK;
+}
+
+size_t guide_eval_select_workspace_bytes(const guide_column_select *sel, uint32_t n_sel, uint64_t count) {
+    if (!sel) return 0;
+    size_t total = 0;
+    for (uint32_t i = 0; i < n_sel; ++i) {
+        guide_select_spec s;
+        memset(&s, 0, sizeof s);
+        s.mode = sel[i].mode;
+        s.n_groups = 1;
+        s.k = sel[i].k;
+        size_t b = select_workspace_bytes(s, count);
+        if (sel[i].mode == GUIDE_SELECT_TOPK && b < topk_partials_bytes()) b = topk_partials_bytes();
+        total += round_up_256(b);
+    }
+    return total;
+}
+
+int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, uint64_t count, const guide_eff *eff,
+                      uint32_t time_model, const guide_metrics *out, const guide_column_select *sel, uint32_t n_sel,
+                      void *workspace, size_t workspace_bytes, void *stream_) {
+    if (!ctx) return GUIDE_E_ARG;
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!time_model_ok(time_model)) return fail(ctx, GUIDE_E_ARG, "unknown time model %u", time_model);
+    if (!out) return fail(ctx, GUIDE_E_ARG, "guide_metrics is NULL");
+    if (n_sel > 2 || (n_sel && !sel)) return fail(ctx, GUIDE_E_ARG, "at most two selections, one per mode");
+    GridDesc desc;
+    uint64_t size = 0;
+    int rc = prepare_grid(ctx, grid, &desc, &size);
+    if (rc) return rc;
+    if (first > size || count > size - first)
+        return fail(ctx, GUIDE_E_RANGE, "range [%llu, +%llu) outside the grid of %llu", (unsigned long long)first,
+                    (unsigned long long)count, (unsigned long long)size);
+    const uint32_t n_eff = eff ? eff->n : 0;
+    if (n_eff > 1) return fail(ctx, GUIDE_E_ARG, "evaluate-and-select takes one efficiency sample");
+    if (n_eff == 1 && (!eff->e_c || !eff->e_b)) return fail(ctx, GUIDE_E_ARG, "efficiency arrays are NULL");
+    if (n_eff == 1 && (!(eff->e_c[0] > 0.0) || !(eff->e_b[0] > 0.0) || std::isinf(eff->e_c[0]) || std::isinf(eff->e_b[0])))
+        return fail(ctx, GUIDE_E_ARG, "efficiency sample is not a positive finite number");
+    const bool can_fuse = count > 0 && eval_grid_can_fuse(desc);
+    const guide_column_select *topk = nullptr, *pareto = nullptr;
+    bool topk_folded = false;
+    for (uint32_t i = 0; i < n_sel; ++i) {
+        const guide_column_select &c = sel[i];
+        if (c.mode != GUIDE_SELECT_TOPK && c.mode != GUIDE_SELECT_PARETO)
+            return fail(ctx, GUIDE_E_ARG, "selection %u: unknown mode %u", i, c.mode);
+        if ((c.mode == GUIDE_SELECT_TOPK ? topk : pareto) != nullptr)
+            return fail(ctx, GUIDE_E_ARG, "two selections of the same mode");
+        if (c.objective >= GUIDE_NUM_COLS || (c.mode == GUIDE_SELECT_PARETO && c.objective_y >= GUIDE_NUM_COLS))
+            return fail(ctx, GUIDE_E_ARG, "selection %u: unknown column", i);
+        if (c.n_constraints > GUIDE_MAX_CONSTRAINTS)
+            return fail(ctx, GUIDE_E_ARG, "selection %u: more than %d constraints", i, GUIDE_MAX_CONSTRAINTS);
+        for (uint32_t k = 0; k < c.n_constraints; ++k)
+            if (c.constraints[k].column >= GUIDE_NUM_COLS)
+                return fail(ctx, GUIDE_E_ARG, "selection %u: constraint %u names an unknown column", i, k);
+        if (!c.out.count) return fail(ctx, GUIDE_E_ARG, "selection %u: out.count is NULL", i);
+        if (c.mode == GUIDE_SELECT_TOPK) {
+            if (c.k == 0 || c.k > GUIDE_MAX_TOPK)
+                return fail(ctx, GUIDE_E_ARG, "selection %u: k outside 1..%d", i, GUIDE_MAX_TOPK);
+            if (!c.out.idx || !c.out.val) return fail(ctx, GUIDE_E_ARG, "selection %u: out.idx or out.val is NULL", i);
+            topk = &c;
+            topk_folded = can_fuse && c.k <= (uint32_t)kFusedTopK;
+        } else {
+            if (c.out.capacity && !c.out.idx) return fail(ctx, GUIDE_E_ARG, "selection %u: out.idx is NULL", i);
+            pareto = &c;
+        }
+        const bool reads_columns = count > 0 && !(c.mode == GUIDE_SELECT_TOPK && topk_folded);
+        if (reads_columns && !columns_present(c, *out))
+            return fail(ctx, GUIDE_E_ARG, "selection %u: a column it reads is not stored (NULL in guide_metrics)", i);
+    }
+    const size_t need = guide_eval_select_workspace_bytes(sel, n_sel, count);
+    if (need && (!workspace || workspace_bytes < need))
+        return fail(ctx, GUIDE_E_NOMEM, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    // workspace slices, in selection order
+    void *ws_of[2] = {nullptr, nullptr};
+    {
+        char *p = (char *)workspace;
+        for (uint32_t i = 0; i < n_sel; ++i) {
+            ws_of[i] = p;
+            p += guide_eval_select_workspace_bytes(sel + i, 1, count);
+        }
+    }
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
+    uint32_t n_blocks = 0;
+    const bool fold = can_fuse && (topk_folded || pareto);
+    if (count > 0) {
+        if (n_eff) {
+            ctx->host_tab.eff_c[0] = eff->e_c[0];
+            ctx->host_tab.eff_b[0] = eff->e_b[0];
+        }
+        rc = upload_grid_tables(ctx, desc, stream);
+        if (rc) return rc;
+        const double e_c = n_eff ? eff->e_c[0] : 1.0, e_b = n_eff ? eff->e_b[0] : 1.0;
+        const bool additive = time_model == GUIDE_TIME_ADDITIVE;
+        hipError_t e;
+        KernelTimer timer(ctx, stream);
+        if (fold) {
+            FusedSelect fs;
+            memset(&fs, 0, sizeof fs);
+            if (topk_folded) {
+                fs.topk = 1;
+                fs.topk_obj = topk->objective;
+                fs.topk_filter = filter_of(*topk);
+                fs.topk_ws = ws_of[topk - sel];
+            }
+            if (pareto) {
+                fs.pareto = 1;
+                fs.pareto_x = pareto->objective;
+                fs.pareto_y = pareto->objective_y;
+                fs.pareto_filter = filter_of(*pareto);
+                fs.scratch = ctx->select_scratch;
+            }
+            e = launch_eval_grid_fused(desc, ctx->dev_tab, ctx->dev_tile, (uint32_t)first, (uint32_t)count, e_c, e_b,
+                                       additive, *out, fs, stream, &n_blocks);
+        } else {
+            e = launch_eval_grid(desc, ctx->dev_tab, ctx->dev_tile, (uint32_t)first, (uint32_t)count, e_c, e_b, additive,
+                                 *out, stream);
+        }
+        if (e != hipSuccess) return hip_fail(ctx, e, "eval_select launch");
+    }
+    for (uint32_t i = 0; i < n_sel; ++i) {
+        const guide_column_select &c = sel[i];
+        const guide_select_spec spec = spec_of(c, *out);
+        hipError_t e;
+        if (c.mode == GUIDE_SELECT_TOPK)
+            e = topk_folded ? launch_topk_merge(ws_of[i], n_blocks, c.k, c.out, stream)
+                            : launch_select_topk(spec, count, c.out, ws_of[i], ctx->select_scratch, stream);
+        else
+            e = fold && count > 0 ? launch_pareto_sampled(spec, count, c.out, ws_of[i], ctx->select_scratch, n_blocks, stream)
+                                  : launch_select_pareto(spec, count, c.out, ws_of[i], ctx->select_scratch, stream);
+        if (e != hipSuccess) return hip_fail(ctx, e, "eval_select selection launch");
+    }
+    return GUIDE_OK;
+}
+
+int guide_profile_enable(guide_ctx *ctx, uint32_t capacity) {
+    if (!ctx) return GUIDE_E_ARG;
+    if (capacity > (1u << 20)) return fail(ctx, GUIDE_E_RANGE, "more than 2^20 timed launches");
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
+    for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
+    ctx->prof_ev.clear();
+    ctx->prof_used = 0;
+    for (uint32_t i = 0; i < 2 * capacity; ++i) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return fail(ctx, GUIDE_E_DEVICE, "cannot create a timing event");
+        ctx->prof_ev.push_back(e);
+    }
+    return GUIDE_OK;
+}
+
+int guide_profile_read(guide_ctx *ctx, float *ms, uint32_t *n) {
+    if (!ctx) return GUIDE_E_ARG;
+    if (!ms || !n) return fail(ctx, GUIDE_E_ARG, "ms or n is NULL");
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
+    for (uint32_t i = 0; i < ctx->prof_used; ++i) {
+        GUIDE_HIP(ctx, hipEventSynchronize(ctx->prof_ev[2 * i + 1]));
+        GUIDE_HIP(ctx, hipEventElapsedTime(&ms[i], ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]));
+    }
+    *n = ctx->prof_used;
+    ctx->prof_used = 0;
     return GUIDE_OK;
 }
 

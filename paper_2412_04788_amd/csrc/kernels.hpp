@@ -5,10 +5,44 @@
 
 namespace guide {
 
-hipError_t launch_eval_grid(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, double e_c,
-                            double e_b, bool additive, const guide_metrics &out, hipStream_t stream);
+// Tables derived from (grid description, device tables) that the tile kernels copy into LDS; they
+// are recomputed by launch_tile_tables whenever either changes.
+size_t tile_tables_bytes();
+hipError_t launch_tile_tables(const GridDesc &g, const DevTables *tab, void *tile_tables, hipStream_t stream);
+hipError_t launch_eval_grid(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
+                            uint32_t count, double e_c, double e_b, bool additive, const guide_metrics &out,
+                            hipStream_t stream);
 hipError_t launch_eval_sweep(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, uint32_t n_eff,
                              bool additive, const guide_stats &out, hipStream_t stream);
+
+// Selections folded into the grid evaluation (guide_eval_select): while a row's values are still
+// in registers the evaluation feeds a per-lane top-K list and / or the row sample that fixes the
+// bin range of the Pareto kernels, so neither needs a pass of its own over the columns.
+constexpr int kFusedTopK = 4;
+struct FusedFilter {
+    uint32_t use_feasible, n_con;
+    uint32_t col[GUIDE_MAX_CONSTRAINTS];        // GUIDE_COL_*
+    double cap[GUIDE_MAX_CONSTRAINTS];
+};
+struct FusedSelect {
+    uint32_t topk, topk_obj;                    // topk != 0: least kFusedTopK rows by column topk_obj
+    FusedFilter topk_filter;
+    void *topk_ws;                              // block partials, layout of the top-k pass
+    uint32_t pareto, pareto_x, pareto_y;        // pareto != 0: sample (x, y) rows, reset the bin tables
+    FusedFilter pareto_filter;
+    void *scratch;                              // scratch of the Pareto kernels
+};
+// True when the grid's two fastest axes have a compiled tile kernel (the only one that folds selections in).
+bool eval_grid_can_fuse(const GridDesc &g);
+// As launch_eval_grid; *n_blocks receives the number of blocks that wrote partials.
+hipError_t launch_eval_grid_fused(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
+                                  uint32_t count, double e_c, double e_b, bool additive, const guide_metrics &out,
+                                  const FusedSelect &fs, hipStream_t stream, uint32_t *n_blocks);
+// Second halves of the folded selections.
+hipError_t launch_topk_merge(void *ws, uint32_t n_blocks, uint32_t k, const guide_select_out &out, hipStream_t stream);
+hipError_t launch_pareto_sampled(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
+                                 void *scratch, uint32_t n_partials, hipStream_t stream);
+size_t topk_partials_bytes();
 
 size_t select_workspace_bytes(const guide_select_spec &spec, uint64_t n);
 hipError_t launch_eval_extras(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, uint32_t n_gpus,

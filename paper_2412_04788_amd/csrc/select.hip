@@ -7,6 +7,7 @@
 // three by inference time / throughput (Inference Engine, Step 2).
 #include "kernels.hpp"
 #include "reduce.hpp"
+#include "select_shared.hpp"
 
 #include <type_traits>
 
@@ -14,7 +15,6 @@ namespace guide {
 
 namespace {
 
-constexpr uint32_t kSelBlocks = 1024;      // blocks of a streaming pass (four per CU)
 constexpr int kWaves = kBlock / kWave;
 
 struct RowFilter {
@@ -109,98 +109,7 @@ uint32_t blocks_for(uint64_t n) {
     return (uint32_t)(need < kSelBlocks ? need : kSelBlocks);
 }
 
-// Context-owned device scratch of the Pareto kernels.  The first kernel of a call
-// (prepare) puts the tables that the later ones accumulate into (bin_min, bin_cnt,
-// the survivor counter) into their neutral state, so the scratch needs no set-up
-// and no call depends on how the previous one ended.
-constexpr uint32_t kBins = 4096;
-struct SelectScratch {
-    uint32_t counters[4];          // [0] survivors appended
-    uint64_t sample_lo[64];        // per sample block: least x key of passing sample rows
-    Pair sample_best[64];          // per sample block: (least y key, its x key)
-    uint64_t bin_min[kBins];       // y keys per x bin whose exclusive prefix-min is that of the least y per bin
-    uint32_t bin_cnt[kBins];       // survivors per bin
-    uint32_t bin_off[kBins + 1], bin_foff[kBins + 1], bin_cur[kBins];   // large-front path only
-};
-
 // ------------------------------------------------------- top-k, one group
-
-// Sorted list of the K least (key, row) pairs seen by one lane.
-template <int K>
-struct TopList {
-    Pair v[K];
-    __device__ void init() {
-#pragma unroll
-        for (int i = 0; i < K; ++i) v[i] = Pair{kNone, kNone};
-    }
-    __device__ void insert(const Pair &p) {
-        if (!less_than(p, v[K - 1])) return;
-        v[K - 1] = p;
-#pragma unroll
-        for (int i = K - 1; i > 0; --i) {
-            if (less_than(v[i], v[i - 1])) {
-                const Pair t = v[i];
-                v[i] = v[i - 1];
-                v[i - 1] = t;
-            }
-        }
-    }
-    __device__ void pop() {
-#pragma unroll
-        for (int i = 0; i + 1 < K; ++i) v[i] = v[i + 1];
-        v[K - 1] = Pair{kNone, kNone};
-    }
-};
-
-// The K least pairs over all lanes of the block, in order: emit(r, pair) is called once for every
-// r < K by some lane of wave 0 (an empty pair when fewer than r + 1 exist).  NW = waves of the block.
-// Stage 1, per wave: K rounds of a key-only minimum; the owner is found by ballot, and only tied
-// keys need a second reduction over rows.  Rows are unique, so one lane pops per round.
-// Stage 2, wave 0: each of the NW * K candidates counts the candidates before it (lane index
-// breaks the tie between empty ones) -- its rank is its output slot.
-template <int K, int NW, typename Emit>
-__device__ inline void block_topk(TopList<K> &l, Pair (*s_pairs)[K], Emit &&emit) {
-    static_assert(NW * K <= kWave, "stage 2 holds one candidate per lane of a wave");
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-#pragma unroll
-    for (int r = 0; r < K; ++r) {
-        const uint64_t mk = wave_min(l.v[0].key);
-        const bool mine = l.v[0].key == mk && l.v[0].idx != kNone;
-        const uint64_t tied = __ballot(mine);
-        uint64_t mi = kNone;
-        if (__popcll(tied) == 1)
-            mi = __shfl(l.v[0].idx, __ffsll((long long)tied) - 1, kWave);
-        else if (tied)
-            mi = wave_min(mine ? l.v[0].idx : kNone);
-        if (mine && l.v[0].idx == mi) l.pop();
-        if (lane == 0) s_pairs[wave][r] = Pair{mi == kNone ? kNone : mk, mi};
-    }
-    __syncthreads();
-    if (wave == 0) {
-        const Pair *flat = &s_pairs[0][0];
-        const Pair c = lane < NW * K ? flat[lane] : Pair{kNone, kNone};
-        int rank = 0;
-#pragma unroll
-        for (int j = 0; j < NW * K; ++j) {
-            const Pair o = flat[j];
-            rank += (less_than(o, c) || (o.key == c.key && o.idx == c.idx && j < lane)) ? 1 : 0;
-        }
-        if (lane < NW * K && rank < K) emit(rank, c);
-    }
-}
-
-// Workspace: part_key[B*K], part_idx[B*K], part_cnt[B].
-struct Top1Ws {
-    uint64_t *key, *idx, *cnt;
-};
-Top1Ws top1_ws(void *ws) {
-    Top1Ws w;
-    w.key = (uint64_t *)ws;
-    w.idx = w.key + (size_t)kSelBlocks * GUIDE_MAX_TOPK;
-    w.cnt = w.idx + (size_t)kSelBlocks * GUIDE_MAX_TOPK;
-    return w;
-}
-size_t top1_ws_bytes() { return sizeof(uint64_t) * ((size_t)kSelBlocks * (2 * GUIDE_MAX_TOPK + 1)); }
 
 // One pass over the rows: every lane keeps its K best, the block merges them.
 template <int K, uint32_t MAXC>
@@ -491,14 +400,28 @@ __global__ __launch_bounds__(kBlock) void pareto_prepare_kernel(const double *__
     }
 }
 
-// Combines the per-block sample partials (the same result in every block): the
-// first wave loads one partial per lane and reduces; s_rng (2 entries) carries
-// the result to the other waves.  Contains a block barrier.
-__device__ inline Binning sampled_binning(const SelectScratch *sc, uint64_t *s_rng) {
+// Combines the n_partials per-block sample partials (the same result in every block): the
+// first wave loads them, a few per lane, and reduces; s_rng (2 entries) carries the result to
+// the other waves.  Contains a block barrier.
+__device__ inline Binning sampled_binning(const SelectScratch *sc, uint32_t n_partials, uint64_t *s_rng) {
     if (threadIdx.x < kWave) {
-        static_assert(kSampleBlocks == kWave, "one sample partial per lane");
-        uint64_t lo = sc->sample_lo[threadIdx.x];
-        Pair best = sc->sample_best[threadIdx.x];
+        constexpr uint32_t kPer = kMaxSamplePartials / kWave;
+        uint64_t plo[kPer];
+        Pair pbest[kPer];
+#pragma unroll
+        for (uint32_t q = 0; q < kPer; ++q) {                // all loads first: one memory latency
+            const uint32_t i = q * kWave + threadIdx.x;
+            const bool live = i < n_partials;
+            plo[q] = live ? sc->sample_lo[i] : kNone;
+            pbest[q] = live ? sc->sample_best[i] : Pair{kNone, kNone};
+        }
+        uint64_t lo = plo[0];
+        Pair best = pbest[0];
+#pragma unroll
+        for (uint32_t q = 1; q < kPer; ++q) {
+            lo = min_u64(lo, plo[q]);
+            best = pair_min(best, pbest[q]);
+        }
         lo = wave_min(lo);
         best = wave_min(best);
         uint64_t hi = best.idx;
@@ -596,7 +519,7 @@ __device__ inline void scan_sum_excl(uint32_t *io, uint32_t *s_tmp) {
 
 template <uint32_t MAXC>
 __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__restrict__ x, const double *__restrict__ y,
-                                                              RowFilter f, uint32_t n, SelectScratch *sc) {
+                                                              RowFilter f, uint32_t n, SelectScratch *sc, uint32_t n_partials) {
     __shared__ uint64_t s_min[padded_size<kPerPass>()], s_tmp[kWaves], s_rng[2];
     const uint32_t per = rows_per_block(n);
     const uint64_t begin = (uint64_t)blockIdx.x * per;
@@ -610,7 +533,7 @@ __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__re
             r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)base + threadIdx.x + u * kBlock, n);
     }
     for (uint32_t i = threadIdx.x; i < padded_size<kPerPass>(); i += kBlock) s_min[i] = kNone;
-    const Binning bin = sampled_binning(sc, s_rng);     // its barrier also covers the table above
+    const Binning bin = sampled_binning(sc, n_partials, s_rng);     // its barrier also covers the table above
     while (base < end) {
 #pragma unroll
         for (uint32_t u = 0; u < kUnroll; ++u) {
@@ -648,7 +571,7 @@ __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__re
 template <uint32_t MAXC>
 __global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *__restrict__ x,
                                                                   const double *__restrict__ y, RowFilter f, uint32_t n,
-                                                                  ParetoWs w, SelectScratch *sc) {
+                                                                  ParetoWs w, SelectScratch *sc, uint32_t n_partials) {
     __shared__ uint64_t s_lower[padded_size<kPerPass>()], s_tmp[kWaves], s_rng[2];
     const int lane = threadIdx.x % kWave;
     const uint32_t per = rows_per_block(n);
@@ -668,7 +591,7 @@ __global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *
     }
 #pragma unroll
     for (uint32_t j = 0; j < kPerPass; ++j) s_lower[padded<kPerPass>(j * kBlock + threadIdx.x)] = tbl[j];
-    const Binning bin = sampled_binning(sc, s_rng);     // its barrier also covers the table above
+    const Binning bin = sampled_binning(sc, n_partials, s_rng);     // its barrier also covers the table above
     scan_min_excl<kBlock>(s_lower, s_tmp);              // least y over strictly lower bins
     // wave-uniform trip count: the ballots below need every lane
     while (base < end) {
@@ -708,8 +631,9 @@ __global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *
     }
 }
 
-__global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs w, SelectScratch *sc, uint64_t *out_idx,
-                                                                        uint64_t capacity, uint64_t *out_count) {
+__global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs w, SelectScratch *sc, uint32_t n_partials,
+                                                                        uint64_t *out_idx, uint64_t capacity,
+                                                                        uint64_t *out_count) {
     static_assert(kFinishThreads == 1024, "kPerFinish assumes 1024 threads");
     constexpr uint32_t P = kPerFinish;
     __shared__ uint32_t s_off[padded_size<P>()], s_foff[padded_size<P>()], s_cur[kBins], s_tmp[kFinishThreads / kWave];
@@ -722,7 +646,7 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
     __shared__ uint64_t s_rng[2];
     if (threadIdx.x == 0) s_nfront = 0;
     const uint32_t m = sc->counters[0];
-    const Binning bin = sampled_binning(sc, s_rng);
+    const Binning bin = sampled_binning(sc, n_partials, s_rng);
     if (m <= kStage) {
         // records staged in LDS, grouped by bin
         for (uint32_t i = t; i < kBins; i += kFinishThreads) {
@@ -898,6 +822,23 @@ hipError_t launch_select_topk(const guide_select_spec &spec, uint64_t n, const g
     return hipGetLastError();
 }
 
+static hipError_t launch_pareto_passes(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
+                                       SelectScratch *sc, uint32_t n_partials, hipStream_t stream) {
+    const ParetoWs w = pareto_ws(ws, n);
+    const RowFilter f = make_filter(spec);
+    const uint32_t nb = blocks_for(n), n32 = (uint32_t)n;
+    const double *x = spec.objective, *y = spec.objective_y;
+    with_max_constraints(f.n_con, [&](auto maxc) {
+        constexpr uint32_t MAXC = decltype(maxc)::value;
+        hipLaunchKernelGGL(pareto_stair_kernel<MAXC>, dim3(nb), dim3(kBlock), 0, stream, x, y, f, n32, sc, n_partials);
+        hipLaunchKernelGGL(pareto_survivors_kernel<MAXC>, dim3(nb), dim3(kBlock), 0, stream, x, y, f, n32, w, sc,
+                           n_partials);
+    });
+    hipLaunchKernelGGL(pareto_finish_kernel, dim3(1), dim3(kFinishThreads), 0, stream, w, sc, n_partials, out.idx,
+                       out.capacity, out.count);
+    return hipGetLastError();
+}
+
 hipError_t launch_select_pareto(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
                                 void *scratch, hipStream_t stream) {
     if (n == 0) {
@@ -905,18 +846,23 @@ hipError_t launch_select_pareto(const guide_select_spec &spec, uint64_t n, const
         return hipGetLastError();
     }
     SelectScratch *sc = (SelectScratch *)scratch;
-    const ParetoWs w = pareto_ws(ws, n);
-    const RowFilter f = make_filter(spec);
-    const uint32_t nb = blocks_for(n), n32 = (uint32_t)n;
-    const double *x = spec.objective, *y = spec.objective_y;
-    hipLaunchKernelGGL(pareto_prepare_kernel, dim3(kSampleBlocks), dim3(kBlock), 0, stream, x, y, f, n32, sc);
-    with_max_constraints(f.n_con, [&](auto maxc) {
-        constexpr uint32_t MAXC = decltype(maxc)::value;
-        hipLaunchKernelGGL(pareto_stair_kernel<MAXC>, dim3(nb), dim3(kBlock), 0, stream, x, y, f, n32, sc);
-        hipLaunchKernelGGL(pareto_survivors_kernel<MAXC>, dim3(nb), dim3(kBlock), 0, stream, x, y, f, n32, w, sc);
-    });
-    hipLaunchKernelGGL(pareto_finish_kernel, dim3(1), dim3(kFinishThreads), 0, stream, w, sc, out.idx, out.capacity,
-                       out.count);
+    hipLaunchKernelGGL(pareto_prepare_kernel, dim3(kSampleBlocks), dim3(kBlock), 0, stream, spec.objective,
+                       spec.objective_y, make_filter(spec), (uint32_t)n, sc);
+    return launch_pareto_passes(spec, n, out, ws, sc, kSampleBlocks, stream);
+}
+
+// The passes after the sample, for a caller whose own kernel has sampled the rows and reset the tables.
+hipError_t launch_pareto_sampled(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
+                                 void *scratch, uint32_t n_partials, hipStream_t stream) {
+    return launch_pareto_passes(spec, n, out, ws, (SelectScratch *)scratch, n_partials, stream);
+}
+
+size_t topk_partials_bytes() { return top1_ws_bytes(); }
+
+// Merge of n_blocks block partials of kFusedTopK pairs each.
+hipError_t launch_topk_merge(void *ws, uint32_t n_blocks, uint32_t k, const guide_select_out &out, hipStream_t stream) {
+    hipLaunchKernelGGL(topk_merge_kernel<kFusedTopK>, dim3(1), dim3(kMergeThreads), 0, stream, top1_ws(ws), n_blocks, k,
+                       out.idx, out.val, out.count);
     return hipGetLastError();
 }
 

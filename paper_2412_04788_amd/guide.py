@@ -25,7 +25,8 @@ MAX_CONSTRAINTS = 4
 
 EXPORTS = ("guide_create", "guide_destroy", "guide_last_error", "guide_set_models", "guide_set_hardware",
            "guide_eval_grid", "guide_eval_extras", "guide_eval_sampled", "guide_simulate_workspace_bytes", "guide_simulate",
-           "guide_select_workspace_bytes", "guide_select")
+           "guide_select_workspace_bytes", "guide_select", "guide_eval_select_workspace_bytes", "guide_eval_select",
+           "guide_profile_enable", "guide_profile_read")
 
 
 class GuideError(RuntimeError):
@@ -109,6 +110,19 @@ class CSelectOut(C.Structure):
     _fields_ = [("idx", C.c_void_p), ("val", C.c_void_p), ("count", C.c_void_p), ("capacity", C.c_uint64)]
 
 
+COLUMN_IDS = {"t_prefill": 0, "t_decode": 1, "t_batch": 2, "decode_tok_s": 3, "cost": 4}
+
+
+class CColumnConstraint(C.Structure):
+    _fields_ = [("column", C.c_uint32), ("reserved", C.c_uint32), ("cap", C.c_double)]
+
+
+class CColumnSelect(C.Structure):
+    _fields_ = [("mode", C.c_uint32), ("objective", C.c_uint32), ("objective_y", C.c_uint32),
+                ("use_feasible", C.c_uint32), ("n_constraints", C.c_uint32), ("k", C.c_uint32),
+                ("constraints", CColumnConstraint * MAX_CONSTRAINTS), ("out", CSelectOut)]
+
+
 _lib = None
 
 
@@ -145,6 +159,13 @@ def load() -> C.CDLL:
         lib.guide_select_workspace_bytes.restype = C.c_size_t
         lib.guide_select.argtypes = [C.c_void_p, C.POINTER(CSelectSpec), C.c_uint64, C.POINTER(CSelectOut),
                                      C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.guide_eval_select_workspace_bytes.argtypes = [C.c_void_p, C.c_uint32, C.c_uint64]
+        lib.guide_eval_select_workspace_bytes.restype = C.c_size_t
+        lib.guide_eval_select.argtypes = [C.c_void_p, C.POINTER(CGrid), C.c_uint64, C.c_uint64, C.POINTER(CEff),
+                                          C.c_uint32, C.POINTER(CMetrics), C.c_void_p, C.c_uint32, C.c_void_p,
+                                          C.c_size_t, C.c_void_p]
+        lib.guide_profile_enable.argtypes = [C.c_void_p, C.c_uint32]
+        lib.guide_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_uint32)]
         _lib = lib
     return _lib
 
@@ -155,6 +176,14 @@ class _Ref:
     def __init__(self, struct, keep=None):
         self.struct, self.keep = struct, keep
         self._as_parameter_ = C.byref(struct)
+
+
+class _Arr:
+    """Address of a ctypes array, kept alive together with what its elements point to."""
+
+    def __init__(self, arr, keep=None):
+        self.arr, self.keep = arr, keep
+        self._as_parameter_ = C.cast(arr, C.c_void_p)
 
 
 class _Ptr:
@@ -284,6 +313,54 @@ class Context:
         self._invoke(self._lib.guide_eval_grid, self._h, _Ref(grid.c, grid), first, count,
                      _Ref(eff, (e_c, e_b)) if eff else None, time_model,
                      _Ref(cm) if cm else None, _Ref(cs) if cs else None, _stream_ptr(stream))
+
+    @staticmethod
+    def column_select(mode: int, objective: str, out_idx, out_val, out_count, objective_y: str = None,
+                      use_feasible: bool = True, constraints=(), k: int = 1, capacity: int = 0) -> CColumnSelect:
+        """guide_column_select from column names; constraints = [(column name, cap), ...]."""
+        c = CColumnSelect()
+        c.mode = mode
+        c.objective = COLUMN_IDS[objective]
+        c.objective_y = COLUMN_IDS[objective_y] if objective_y is not None else 0
+        c.use_feasible = 1 if use_feasible else 0
+        c.n_constraints = len(constraints)
+        for i, (col, cap) in enumerate(list(constraints)[:MAX_CONSTRAINTS]):
+            c.constraints[i].column = COLUMN_IDS[col]
+            c.constraints[i].cap = float(cap)
+        c.k = k
+        c.out = CSelectOut(_dev_ptr(out_idx), _dev_ptr(out_val), _dev_ptr(out_count), capacity)
+        c._keep = (out_idx, out_val, out_count)
+        return c
+
+    def eval_select_workspace_bytes(self, selections: Sequence[CColumnSelect], count: int) -> int:
+        arr = (CColumnSelect * max(len(selections), 1))(*selections)
+        return self._lib.guide_eval_select_workspace_bytes(C.cast(arr, C.c_void_p), len(selections), count)
+
+    def eval_select(self, grid: GridArg, first: int, count: int, out: dict, selections: Sequence[CColumnSelect],
+                    workspace, e_c=None, e_b=None, time_model: int = TIME_ROOFLINE, stream=None):
+        """guide_eval_select: evaluate [first, first + count) into `out` and run the selections on it."""
+        eff = None
+        if e_c is not None:
+            e_c = np.ascontiguousarray([e_c], dtype=np.float64).reshape(-1)
+            e_b = np.ascontiguousarray([e_b], dtype=np.float64).reshape(-1)
+            eff = CEff(len(e_c), e_c.ctypes.data, e_b.ctypes.data)
+        cm = CMetrics(*[_dev_ptr(out.get(k)) for k in METRIC_COLUMNS])
+        arr = (CColumnSelect * max(len(selections), 1))(*selections)
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        self._invoke(self._lib.guide_eval_select, self._h, _Ref(grid.c, grid), first, count,
+                     _Ref(eff, (e_c, e_b)) if eff else None, time_model, _Ref(cm, out),
+                     _Arr(arr, selections), len(selections),
+                     _dev_ptr(workspace), ws_bytes, _stream_ptr(stream))
+
+    def profile_enable(self, capacity: int):
+        self._check(self._lib.guide_profile_enable(self._h, capacity))
+
+    def profile_read(self, capacity: int) -> np.ndarray:
+        """Elapsed milliseconds of the evaluation kernels timed since the last read."""
+        ms = np.zeros(max(capacity, 1), dtype=np.float32)
+        n = C.c_uint32(0)
+        self._check(self._lib.guide_profile_read(self._h, ms.ctypes.data, C.byref(n)))
+        return ms[:n.value].copy()
 
     def eval_extras(self, grid: GridArg, first: int, count: int, n_gpus: int, out: dict,
                     time_model: int = TIME_ROOFLINE, stream=None):

@@ -30,6 +30,25 @@ def test_binding_structs_match_header_sizes():
     assert ctypes.sizeof(guide.CExtras) == 5 * 8
 
 
+def test_binding_structs_match_the_c_compiler(tmp_path):
+    """sizeof of every struct of the header, as gcc lays it out, against the ctypes mirror."""
+    import subprocess
+    pairs = [("guide_model", guide.CModel), ("guide_hw", guide.CHw), ("guide_axis", guide.CAxis),
+             ("guide_grid", guide.CGrid), ("guide_eff", guide.CEff), ("guide_metrics", guide.CMetrics),
+             ("guide_stats", guide.CStats), ("guide_extras", guide.CExtras), ("guide_space", guide.CSpace),
+             ("guide_sampled_out", guide.CSampledOut), ("guide_trace", guide.CTrace), ("guide_sim_out", guide.CSimOut),
+             ("guide_constraint", guide.CConstraint), ("guide_select_spec", guide.CSelectSpec),
+             ("guide_select_out", guide.CSelectOut), ("guide_column_constraint", guide.CColumnConstraint),
+             ("guide_column_select", guide.CColumnSelect)]
+    src = tmp_path / "sizes.c"
+    src.write_text('#include <stdio.h>\n#include "guide.h"\nint main(void) {\n' +
+                   "".join(f'    printf("%zu\\n", sizeof({c}));\n' for c, _ in pairs) + "    return 0;\n}\n")
+    exe = tmp_path / "sizes"
+    subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
+    got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
+    assert got == [ctypes.sizeof(t) for _, t in pairs], list(zip([c for c, _ in pairs], got))
+
+
 def test_binding_has_no_cpu_fallback():
     src = open(os.path.join(ROOT, "paper_2412_04788_amd", "guide.py")).read()
     assert "oracle" not in src.replace("no CPU fallback", "")
