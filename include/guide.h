@@ -298,15 +298,16 @@ int guide_select(guide_ctx *ctx, const guide_select_spec *spec, uint64_t n, cons
  * one efficiency sample followed by guide_select for each of the n_sel
  * selections on the columns of `out` (rows = the `count` evaluated
  * configurations, one group) -- the engine's "evaluate every configuration, keep
- * the best" (Inference Engine Step 2; Simulating Hybrid Parallelism) without a
- * pass of its own over the columns where the library can avoid one: for a grid
- * whose two fastest axes have a tile kernel, a top-k selection with k <= 4 is
- * reduced inside the evaluation kernel, and the Pareto selection's row sample is
- * taken there.  Columns are named by GUIDE_COL_*.  At most one selection per mode
- * (n_sel <= 2; n_sel = 0 is a plain evaluation).  Every column that a selection
- * refers to, and `feasible` when use_feasible is set, must be present in `out`
- * (GUIDE_E_ARG otherwise), except for a top-k reduced inside the evaluation,
- * which needs none of them stored.
+ * the best" (Inference Engine Step 2; Simulating Hybrid Parallelism) -- in fewer
+ * launches: with a top-k and a Pareto selection, the small kernels of one ride
+ * along with the large kernels of the other.  Columns are named by GUIDE_COL_*.
+ * At most one selection per mode (n_sel <= 2; n_sel = 0 is a plain evaluation).
+ * Every column that a selection refers to, and `feasible` when use_feasible is
+ * set, must be present in `out` (GUIDE_E_ARG otherwise), with one exception: for
+ * a grid whose two fastest axes have a tile kernel, a top-k selection with
+ * k <= 4 whose columns are not all stored is reduced inside the evaluation
+ * kernel instead, so the best configurations can be found without storing the
+ * grid.
  * workspace: DEVICE, guide_eval_select_workspace_bytes(sel, n_sel, count) bytes.
  */
 enum { GUIDE_COL_T_PREFILL = 0, GUIDE_COL_T_DECODE = 1, GUIDE_COL_T_BATCH = 2, GUIDE_COL_DECODE_TOK_S = 3,
@@ -329,15 +330,17 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Kernel timing aid.  After guide_profile_enable(ctx, capacity) every grid
- * evaluation kernel launched by guide_eval_grid (one sample) or guide_eval_select
- * is bracketed by a pair of HIP events recorded on the call's stream, for up to
- * `capacity` launches (later ones are not timed); capacity 0 switches it off.
- * guide_profile_read waits for the recorded events, writes the elapsed
- * milliseconds of each timed launch to ms[0 .. *n) (HOST, room for `capacity`
- * values) and starts over.
+ * Kernel timing aid.  After guide_profile_enable(ctx, capacity, every), every
+ * `every`-th grid evaluation kernel launched by guide_eval_grid (one sample) or
+ * guide_eval_select (the first, the every+1-th, ...) is bracketed by a pair of
+ * HIP events recorded on the call's stream, for up to `capacity` timed launches
+ * (later ones are not timed); capacity 0 switches it off.  An event pair delays
+ * the launches around it by a few microseconds, which is why a caller that also
+ * measures throughput times a subset.  guide_profile_read waits for the recorded
+ * events, writes the elapsed milliseconds of each timed launch to ms[0 .. *n)
+ * (HOST, room for `capacity` values) and starts over.
  */
-int guide_profile_enable(guide_ctx *ctx, uint32_t capacity);
+int guide_profile_enable(guide_ctx *ctx, uint32_t capacity, uint32_t every);
 int guide_profile_read(guide_ctx *ctx, float *ms, uint32_t *n);
 
 #ifdef __cplusplus

@@ -36,6 +36,7 @@ struct guide_ctx {
     // kernel timing aid: event pairs around evaluation kernels (guide_profile_enable)
     std::vector<hipEvent_t> prof_ev;     // 2 * capacity events
     uint32_t prof_used = 0;              // timed launches since the last read
+    uint32_t prof_every = 1, prof_seen = 0;   // every prof_every-th launch is timed
     hipStream_t prof_stream = nullptr;
     char err[256] = {0};
 };
@@ -173,7 +174,9 @@ struct KernelTimer {
     guide_ctx *ctx;
     hipStream_t stream;
     bool on;
-    KernelTimer(guide_ctx *c, hipStream_t s) : ctx(c), stream(s), on(2 * (size_t)c->prof_used + 1 < c->prof_ev.size()) {
+    KernelTimer(guide_ctx *c, hipStream_t s) : ctx(c), stream(s), on(false) {
+        if (c->prof_ev.empty()) return;
+        on = c->prof_seen++ % c->prof_every == 0 && 2 * (size_t)c->prof_used + 1 < c->prof_ev.size();
         if (on) (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_used], stream);
     }
     ~KernelTimer() {
@@ -424,7 +427,8 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
                 return fail(ctx, GUIDE_E_ARG, "selection %u: k outside 1..%d", i, GUIDE_MAX_TOPK);
             if (!c.out.idx || !c.out.val) return fail(ctx, GUIDE_E_ARG, "selection %u: out.idx or out.val is NULL", i);
             topk = &c;
-            topk_folded = can_fuse && c.k <= (uint32_t)kFusedTopK;
+            // reduced inside the evaluation only when it has to be: a column it refers to is not stored
+            topk_folded = can_fuse && c.k <= (uint32_t)kFusedTopK && !columns_present(c, *out);
         } else {
             if (c.out.capacity && !c.out.idx) return fail(ctx, GUIDE_E_ARG, "selection %u: out.idx is NULL", i);
             pareto = &c;
@@ -448,7 +452,7 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
     uint32_t n_blocks = 0;
-    const bool fold = can_fuse && (topk_folded || pareto);
+    const bool fold = topk_folded;                      // then the Pareto row sample is taken there as well
     if (count > 0) {
         if (n_eff) {
             ctx->host_tab.eff_c[0] = eff->e_c[0];
@@ -463,12 +467,10 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
         if (fold) {
             FusedSelect fs;
             memset(&fs, 0, sizeof fs);
-            if (topk_folded) {
-                fs.topk = 1;
-                fs.topk_obj = topk->objective;
-                fs.topk_filter = filter_of(*topk);
-                fs.topk_ws = ws_of[topk - sel];
-            }
+            fs.topk = 1;
+            fs.topk_obj = topk->objective;
+            fs.topk_filter = filter_of(*topk);
+            fs.topk_ws = ws_of[topk - sel];
             if (pareto) {
                 fs.pareto = 1;
                 fs.pareto_x = pareto->objective;
@@ -484,29 +486,44 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
         }
         if (e != hipSuccess) return hip_fail(ctx, e, "eval_select launch");
     }
-    for (uint32_t i = 0; i < n_sel; ++i) {
-        const guide_column_select &c = sel[i];
-        const guide_select_spec spec = spec_of(c, *out);
-        hipError_t e;
-        if (c.mode == GUIDE_SELECT_TOPK)
-            e = topk_folded ? launch_topk_merge(ws_of[i], n_blocks, c.k, c.out, stream)
-                            : launch_select_topk(spec, count, c.out, ws_of[i], ctx->select_scratch, stream);
-        else
-            e = fold && count > 0 ? launch_pareto_sampled(spec, count, c.out, ws_of[i], ctx->select_scratch, n_blocks, stream)
-                                  : launch_select_pareto(spec, count, c.out, ws_of[i], ctx->select_scratch, stream);
-        if (e != hipSuccess) return hip_fail(ctx, e, "eval_select selection launch");
+    hipError_t e = hipSuccess;
+    if (topk && pareto && count > 0 && !fold) {
+        // both selections read stored columns: four launches, the small kernels ride along with the large ones
+        e = launch_select_both(spec_of(*topk, *out), topk->out, ws_of[topk - sel], spec_of(*pareto, *out), pareto->out,
+                               ws_of[pareto - sel], count, ctx->select_scratch, stream);
+    } else {
+        for (uint32_t i = 0; i < n_sel && e == hipSuccess; ++i) {
+            const guide_column_select &c = sel[i];
+            const guide_select_spec spec = spec_of(c, *out);
+            if (c.mode == GUIDE_SELECT_TOPK) {
+                if (!fold)
+                    e = launch_select_topk(spec, count, c.out, ws_of[i], ctx->select_scratch, stream);
+                else if (!pareto)
+                    e = launch_topk_merge(ws_of[i], n_blocks, c.k, c.out, stream);
+                // else: merged beside the Pareto front's finishing kernel, below
+            } else if (fold) {
+                e = launch_pareto_sampled(spec, count, c.out, ws_of[i], ctx->select_scratch, n_blocks, ws_of[topk - sel],
+                                          n_blocks, topk->k, &topk->out, stream);
+            } else {
+                e = launch_select_pareto(spec, count, c.out, ws_of[i], ctx->select_scratch, stream);
+            }
+        }
     }
+    if (e != hipSuccess) return hip_fail(ctx, e, "eval_select selection launch");
     return GUIDE_OK;
 }
 
-int guide_profile_enable(guide_ctx *ctx, uint32_t capacity) {
+int guide_profile_enable(guide_ctx *ctx, uint32_t capacity, uint32_t every) {
     if (!ctx) return GUIDE_E_ARG;
     if (capacity > (1u << 20)) return fail(ctx, GUIDE_E_RANGE, "more than 2^20 timed launches");
+    if (capacity && every == 0) return fail(ctx, GUIDE_E_ARG, "every must be at least 1");
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
     for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
     ctx->prof_ev.clear();
     ctx->prof_used = 0;
+    ctx->prof_seen = 0;
+    ctx->prof_every = every ? every : 1;
     for (uint32_t i = 0; i < 2 * capacity; ++i) {
         hipEvent_t e;
         if (hipEventCreate(&e) != hipSuccess) return fail(ctx, GUIDE_E_DEVICE, "cannot create a timing event");
@@ -526,6 +543,7 @@ int guide_profile_read(guide_ctx *ctx, float *ms, uint32_t *n) {
     }
     *n = ctx->prof_used;
     ctx->prof_used = 0;
+    ctx->prof_seen = 0;
     return GUIDE_OK;
 }
 

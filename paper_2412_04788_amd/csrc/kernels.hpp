@@ -41,8 +41,12 @@ hipError_t launch_eval_grid_fused(const GridDesc &g, const DevTables *tab, const
 // Second halves of the folded selections.
 hipError_t launch_topk_merge(void *ws, uint32_t n_blocks, uint32_t k, const guide_select_out &out, hipStream_t stream);
 hipError_t launch_pareto_sampled(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
-                                 void *scratch, uint32_t n_partials, hipStream_t stream);
+                                 void *scratch, uint32_t n_partials, void *merge_ws, uint32_t merge_blocks,
+                                 uint32_t merge_k, const guide_select_out *merge_out, hipStream_t stream);
 size_t topk_partials_bytes();
+hipError_t launch_select_both(const guide_select_spec &topk, const guide_select_out &topk_out, void *topk_ws,
+                              const guide_select_spec &pareto, const guide_select_out &pareto_out, void *pareto_ws,
+                              uint64_t n, void *scratch, hipStream_t stream);
 
 size_t select_workspace_bytes(const guide_select_spec &spec, uint64_t n);
 hipError_t launch_eval_extras(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, uint32_t n_gpus,

@@ -83,12 +83,12 @@ void with_max_constraints(uint32_t n_con, F &&fn) {
     else fn(std::integral_constant<uint32_t, GUIDE_MAX_CONSTRAINTS>{});
 }
 
-// Block b owns the contiguous rows [b * per, (b + 1) * per); per is a multiple of
+// Block b of the n_blocks row blocks owns the contiguous rows [b * per, (b + 1) * per); per is a multiple of
 // kBlock * kUnroll so that every lane of a wave runs the same trip count.
 constexpr uint32_t kUnroll = 8;
-__device__ inline uint32_t rows_per_block(uint32_t n) {
+__device__ inline uint32_t rows_per_block(uint32_t n, uint32_t n_blocks) {
     const uint32_t unit = kBlock * kUnroll;
-    const uint32_t per = (n + gridDim.x - 1) / gridDim.x;
+    const uint32_t per = (n + n_blocks - 1) / n_blocks;
     return (per + unit - 1) / unit * unit;
 }
 
@@ -111,16 +111,41 @@ uint32_t blocks_for(uint64_t n) {
 
 // ------------------------------------------------------- top-k, one group
 
-// One pass over the rows: every lane keeps its K best, the block merges them.
+// Independent work of another selection that rides along with a launch as extra blocks, so that it
+// does not pay for a launch of its own.  SampleRider: the row sample of a Pareto selection
+// (kSampleBlocks blocks after the host kernel's own).  MergeRider: the merge of top-k block partials
+// (one block).  n_blocks = 0 / on = 0: none.
+struct SampleRider {
+    uint32_t on;
+    const double *x, *y;
+    RowFilter f;
+    SelectScratch *sc;
+};
+struct MergeRider {
+    Top1Ws w;
+    uint32_t n_blocks, k, K;       // K: pairs per block partial (1, 2 or 4)
+    uint64_t *out_idx;
+    double *out_val;
+    uint64_t *out_cnt;
+};
+__device__ void pareto_prepare_body(uint32_t block, const double *__restrict__ x, const double *__restrict__ y,
+                                    const RowFilter &f, uint32_t n, SelectScratch *sc);
+
+// One pass over the rows: every lane keeps its K best, the block merges them.  Blocks
+// [0, n_row_blocks) take the rows.
 template <int K, uint32_t MAXC>
 __global__ __launch_bounds__(kBlock) void topk_pass_kernel(const double *__restrict__ obj, RowFilter f, uint32_t n,
-                                                           Top1Ws w) {
+                                                           Top1Ws w, uint32_t n_row_blocks, SampleRider sample) {
+    if (blockIdx.x >= n_row_blocks) {
+        pareto_prepare_body(blockIdx.x - n_row_blocks, sample.x, sample.y, sample.f, n, sample.sc);
+        return;
+    }
     __shared__ Pair s_pairs[kWaves][K];
     __shared__ uint64_t s_cnt[kWaves];
     TopList<K> l;
     l.init();
     uint64_t cnt = 0;
-    const uint32_t per = rows_per_block(n);
+    const uint32_t per = rows_per_block(n, n_row_blocks);
     const uint64_t begin = (uint64_t)blockIdx.x * per;
     for (uint64_t base = begin + threadIdx.x; base < begin + per && base < n; base += kBlock * kUnroll) {
         Row r[kUnroll];
@@ -147,25 +172,25 @@ __global__ __launch_bounds__(kBlock) void topk_pass_kernel(const double *__restr
     }
 }
 
-// One block: the K least of the block partials, and the total count.
+// One block of NT threads: the K least of the block partials, and the total count.
 constexpr uint32_t kMergeThreads = 512;
-template <int K>
-__global__ __launch_bounds__(kMergeThreads) void topk_merge_kernel(Top1Ws w, uint32_t n_blocks, uint32_t k,
-                                                                   uint64_t *out_idx, double *out_val, uint64_t *out_cnt) {
-    constexpr int kNW = kMergeThreads / kWave;
+template <int K, uint32_t NT>
+__device__ inline void topk_merge_body(Top1Ws w, uint32_t n_blocks, uint32_t k, uint64_t *out_idx, double *out_val,
+                                       uint64_t *out_cnt) {
+    constexpr int kNW = NT / kWave;
     __shared__ Pair s_pairs[kNW][K];
     __shared__ uint64_t s_cnt[kNW];
-    constexpr uint32_t kPer = kSelBlocks * K / kMergeThreads;       // all loads first: one memory latency
+    constexpr uint32_t kPer = kSelBlocks * K / NT;       // all loads first: one memory latency
     Pair c[kPer];
 #pragma unroll
     for (uint32_t q = 0; q < kPer; ++q) {
-        const uint32_t i = q * kMergeThreads + threadIdx.x;
+        const uint32_t i = q * NT + threadIdx.x;
         c[q] = i < n_blocks * K ? Pair{w.key[i], w.idx[i]} : Pair{kNone, kNone};
     }
-    uint64_t pc[kSelBlocks / kMergeThreads];
+    uint64_t pc[kSelBlocks / NT];
 #pragma unroll
-    for (uint32_t q = 0; q < kSelBlocks / kMergeThreads; ++q) {
-        const uint32_t i = q * kMergeThreads + threadIdx.x;
+    for (uint32_t q = 0; q < kSelBlocks / NT; ++q) {
+        const uint32_t i = q * NT + threadIdx.x;
         pc[q] = i < n_blocks ? w.cnt[i] : 0;
     }
     TopList<K> l;
@@ -174,7 +199,7 @@ __global__ __launch_bounds__(kMergeThreads) void topk_merge_kernel(Top1Ws w, uin
 #pragma unroll
     for (uint32_t q = 0; q < kPer; ++q) l.insert(c[q]);
 #pragma unroll
-    for (uint32_t q = 0; q < kSelBlocks / kMergeThreads; ++q) cnt += pc[q];
+    for (uint32_t q = 0; q < kSelBlocks / NT; ++q) cnt += pc[q];
     for (int off = kWave / 2; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, kWave);
     if (threadIdx.x % kWave == 0) s_cnt[threadIdx.x / kWave] = cnt;
     block_topk<K, kNW>(l, s_pairs, [&](int r, const Pair &p) {
@@ -189,6 +214,13 @@ __global__ __launch_bounds__(kMergeThreads) void topk_merge_kernel(Top1Ws w, uin
         out_cnt[0] = t;
     }
 }
+
+template <int K>
+__global__ __launch_bounds__(kMergeThreads) void topk_merge_kernel(Top1Ws w, uint32_t n_blocks, uint32_t k,
+                                                                   uint64_t *out_idx, double *out_val, uint64_t *out_cnt) {
+    topk_merge_body<K, kMergeThreads>(w, n_blocks, k, out_idx, out_val, out_cnt);
+}
+
 
 // ------------------------------------------------------- top-k, with groups
 
@@ -362,12 +394,11 @@ __device__ inline Binning binning_of(uint64_t lo, uint64_t hi) {
 // the last bin).  Any monotone binning is correct -- the sample only decides how
 // finely the interesting stretch of x is resolved.
 constexpr uint32_t kSampleBlocks = 64;
-__global__ __launch_bounds__(kBlock) void pareto_prepare_kernel(const double *__restrict__ x,
-                                                                const double *__restrict__ y, RowFilter f, uint32_t n,
-                                                                SelectScratch *sc) {
+__device__ void pareto_prepare_body(uint32_t block, const double *__restrict__ x, const double *__restrict__ y,
+                                    const RowFilter &f, uint32_t n, SelectScratch *sc) {
     __shared__ uint64_t s_lo[kWaves];
     __shared__ Pair s_best[kWaves];
-    const uint32_t k = blockIdx.x * kBlock + threadIdx.x;           // sample number
+    const uint32_t k = block * kBlock + threadIdx.x;                // sample number
     const uint32_t n_samples = kSampleBlocks * kBlock;
     static_assert(kSampleBlocks * kBlock >= kBins, "one table entry per thread");
     if (k < kBins) {                                                // neutral state for the kernels that follow
@@ -395,9 +426,14 @@ __global__ __launch_bounds__(kBlock) void pareto_prepare_kernel(const double *__
             lo = s_lo[wv] < lo ? s_lo[wv] : lo;
             best = pair_min(best, s_best[wv]);
         }
-        sc->sample_lo[blockIdx.x] = lo;
-        sc->sample_best[blockIdx.x] = best;
+        sc->sample_lo[block] = lo;
+        sc->sample_best[block] = best;
     }
+}
+__global__ __launch_bounds__(kBlock) void pareto_prepare_kernel(const double *__restrict__ x,
+                                                                const double *__restrict__ y, RowFilter f, uint32_t n,
+                                                                SelectScratch *sc) {
+    pareto_prepare_body(blockIdx.x, x, y, f, n, sc);
 }
 
 // Combines the n_partials per-block sample partials (the same result in every block): the
@@ -521,7 +557,7 @@ template <uint32_t MAXC>
 __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__restrict__ x, const double *__restrict__ y,
                                                               RowFilter f, uint32_t n, SelectScratch *sc, uint32_t n_partials) {
     __shared__ uint64_t s_min[padded_size<kPerPass>()], s_tmp[kWaves], s_rng[2];
-    const uint32_t per = rows_per_block(n);
+    const uint32_t per = rows_per_block(n, gridDim.x);
     const uint64_t begin = (uint64_t)blockIdx.x * per;
     const uint64_t end = begin + per < n ? begin + per : n;
     // the first batch of rows is requested before the set-up below, so that its latency overlaps it
@@ -574,7 +610,7 @@ __global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *
                                                                   ParetoWs w, SelectScratch *sc, uint32_t n_partials) {
     __shared__ uint64_t s_lower[padded_size<kPerPass>()], s_tmp[kWaves], s_rng[2];
     const int lane = threadIdx.x % kWave;
-    const uint32_t per = rows_per_block(n);
+    const uint32_t per = rows_per_block(n, gridDim.x);
     const uint64_t begin = (uint64_t)blockIdx.x * per;
     const uint64_t end = begin + per < n ? begin + per : n;
     // requested first, and in this order: the table, then the first batch of rows, whose latency
@@ -633,7 +669,16 @@ __global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *
 
 __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs w, SelectScratch *sc, uint32_t n_partials,
                                                                         uint64_t *out_idx, uint64_t capacity,
-                                                                        uint64_t *out_count) {
+                                                                        uint64_t *out_count, MergeRider rider) {
+    if (blockIdx.x == 1) {                              // second block, launched only with a waiting top-k merge
+        if (rider.K == 1)
+            topk_merge_body<1, kFinishThreads>(rider.w, rider.n_blocks, rider.k, rider.out_idx, rider.out_val, rider.out_cnt);
+        else if (rider.K == 2)
+            topk_merge_body<2, kFinishThreads>(rider.w, rider.n_blocks, rider.k, rider.out_idx, rider.out_val, rider.out_cnt);
+        else
+            topk_merge_body<4, kFinishThreads>(rider.w, rider.n_blocks, rider.k, rider.out_idx, rider.out_val, rider.out_cnt);
+        return;
+    }
     static_assert(kFinishThreads == 1024, "kPerFinish assumes 1024 threads");
     constexpr uint32_t P = kPerFinish;
     __shared__ uint32_t s_off[padded_size<P>()], s_foff[padded_size<P>()], s_cur[kBins], s_tmp[kFinishThreads / kWave];
@@ -777,15 +822,32 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
 __global__ void pareto_empty_kernel(uint64_t *out_count) { out_count[0] = 0; }
 
 template <int K>
-void launch_top1(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws, hipStream_t stream) {
-    const Top1Ws w = top1_ws(ws);
+void launch_top1_pass(const guide_select_spec &spec, uint64_t n, void *ws, const SampleRider &sample, hipStream_t stream) {
     const uint32_t nb = blocks_for(n);
     with_max_constraints(spec.n_constraints, [&](auto maxc) {
-        hipLaunchKernelGGL((topk_pass_kernel<K, decltype(maxc)::value>), dim3(nb), dim3(kBlock), 0, stream,
-                           spec.objective, make_filter(spec), (uint32_t)n, w);
+        hipLaunchKernelGGL((topk_pass_kernel<K, decltype(maxc)::value>), dim3(nb + (sample.on ? kSampleBlocks : 0)),
+                           dim3(kBlock), 0, stream, spec.objective, make_filter(spec), (uint32_t)n, top1_ws(ws), nb, sample);
     });
-    hipLaunchKernelGGL(topk_merge_kernel<K>, dim3(1), dim3(kMergeThreads), 0, stream, w, nb, spec.k, out.idx, out.val,
-                       out.count);
+}
+// Pairs per block partial for a request of k (the pass kernel's template argument).
+int partial_width(uint32_t k) { return k == 1 ? 1 : k == 2 ? 2 : k <= 4 ? 4 : 8; }
+void launch_top1_pass(const guide_select_spec &spec, uint64_t n, void *ws, const SampleRider &sample, hipStream_t stream) {
+    switch (partial_width(spec.k)) {
+        case 1: launch_top1_pass<1>(spec, n, ws, sample, stream); break;
+        case 2: launch_top1_pass<2>(spec, n, ws, sample, stream); break;
+        case 4: launch_top1_pass<4>(spec, n, ws, sample, stream); break;
+        default: launch_top1_pass<8>(spec, n, ws, sample, stream); break;
+    }
+}
+void launch_top1_merge(int K, void *ws, uint32_t n_blocks, uint32_t k, const guide_select_out &out, hipStream_t stream) {
+    const Top1Ws w = top1_ws(ws);
+    const dim3 one(1), nt(kMergeThreads);
+    switch (K) {
+        case 1: hipLaunchKernelGGL(topk_merge_kernel<1>, one, nt, 0, stream, w, n_blocks, k, out.idx, out.val, out.count); break;
+        case 2: hipLaunchKernelGGL(topk_merge_kernel<2>, one, nt, 0, stream, w, n_blocks, k, out.idx, out.val, out.count); break;
+        case 4: hipLaunchKernelGGL(topk_merge_kernel<4>, one, nt, 0, stream, w, n_blocks, k, out.idx, out.val, out.count); break;
+        default: hipLaunchKernelGGL(topk_merge_kernel<8>, one, nt, 0, stream, w, n_blocks, k, out.idx, out.val, out.count); break;
+    }
 }
 
 }  // namespace
@@ -803,10 +865,8 @@ hipError_t launch_select_topk(const guide_select_spec &spec, uint64_t n, const g
                               void *scratch, hipStream_t stream) {
     (void)scratch;
     if (!spec.group) {
-        if (spec.k == 1) launch_top1<1>(spec, n, out, ws, stream);
-        else if (spec.k == 2) launch_top1<2>(spec, n, out, ws, stream);
-        else if (spec.k <= 4) launch_top1<4>(spec, n, out, ws, stream);
-        else launch_top1<8>(spec, n, out, ws, stream);
+        launch_top1_pass(spec, n, ws, SampleRider{}, stream);
+        launch_top1_merge(partial_width(spec.k), ws, blocks_for(n), spec.k, out, stream);
         return hipGetLastError();
     }
     const uint32_t G = spec.n_groups;
@@ -823,7 +883,8 @@ hipError_t launch_select_topk(const guide_select_spec &spec, uint64_t n, const g
 }
 
 static hipError_t launch_pareto_passes(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
-                                       SelectScratch *sc, uint32_t n_partials, hipStream_t stream) {
+                                       SelectScratch *sc, uint32_t n_partials, const MergeRider &rider,
+                                       hipStream_t stream) {
     const ParetoWs w = pareto_ws(ws, n);
     const RowFilter f = make_filter(spec);
     const uint32_t nb = blocks_for(n), n32 = (uint32_t)n;
@@ -834,8 +895,8 @@ static hipError_t launch_pareto_passes(const guide_select_spec &spec, uint64_t n
         hipLaunchKernelGGL(pareto_survivors_kernel<MAXC>, dim3(nb), dim3(kBlock), 0, stream, x, y, f, n32, w, sc,
                            n_partials);
     });
-    hipLaunchKernelGGL(pareto_finish_kernel, dim3(1), dim3(kFinishThreads), 0, stream, w, sc, n_partials, out.idx,
-                       out.capacity, out.count);
+    hipLaunchKernelGGL(pareto_finish_kernel, dim3(rider.n_blocks ? 2 : 1), dim3(kFinishThreads), 0, stream, w, sc,
+                       n_partials, out.idx, out.capacity, out.count, rider);
     return hipGetLastError();
 }
 
@@ -848,21 +909,45 @@ hipError_t launch_select_pareto(const guide_select_spec &spec, uint64_t n, const
     SelectScratch *sc = (SelectScratch *)scratch;
     hipLaunchKernelGGL(pareto_prepare_kernel, dim3(kSampleBlocks), dim3(kBlock), 0, stream, spec.objective,
                        spec.objective_y, make_filter(spec), (uint32_t)n, sc);
-    return launch_pareto_passes(spec, n, out, ws, sc, kSampleBlocks, stream);
+    return launch_pareto_passes(spec, n, out, ws, sc, kSampleBlocks, MergeRider{}, stream);
+}
+
+// A top-k selection (one group) and a Pareto selection over the same n > 0 rows in four launches
+// instead of six: the Pareto row sample rides along with the top-k pass, and the top-k merge with the
+// finishing kernel of the Pareto front (for block partials of up to 4 pairs; wider ones merge alone).
+hipError_t launch_select_both(const guide_select_spec &topk, const guide_select_out &topk_out, void *topk_ws,
+                              const guide_select_spec &pareto, const guide_select_out &pareto_out, void *pareto_ws_,
+                              uint64_t n, void *scratch, hipStream_t stream) {
+    SelectScratch *sc = (SelectScratch *)scratch;
+    const SampleRider sample{1u, pareto.objective, pareto.objective_y, make_filter(pareto), sc};
+    launch_top1_pass(topk, n, topk_ws, sample, stream);
+    const int K = partial_width(topk.k);
+    MergeRider rider{};
+    if (K <= 4)
+        rider = MergeRider{top1_ws(topk_ws), blocks_for(n), topk.k, (uint32_t)K, topk_out.idx, topk_out.val, topk_out.count};
+    else
+        launch_top1_merge(K, topk_ws, blocks_for(n), topk.k, topk_out, stream);
+    return launch_pareto_passes(pareto, n, pareto_out, pareto_ws_, sc, kSampleBlocks, rider, stream);
 }
 
 // The passes after the sample, for a caller whose own kernel has sampled the rows and reset the tables.
+// merge_ws != nullptr: the merge of a folded top-k (merge_blocks block partials of kFusedTopK pairs) rides
+// along with the finishing kernel instead of taking a launch of its own.
 hipError_t launch_pareto_sampled(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
-                                 void *scratch, uint32_t n_partials, hipStream_t stream) {
-    return launch_pareto_passes(spec, n, out, ws, (SelectScratch *)scratch, n_partials, stream);
+                                 void *scratch, uint32_t n_partials, void *merge_ws, uint32_t merge_blocks,
+                                 uint32_t merge_k, const guide_select_out *merge_out, hipStream_t stream) {
+    MergeRider rider{};
+    if (merge_ws)
+        rider = MergeRider{top1_ws(merge_ws), merge_blocks, merge_k, (uint32_t)kFusedTopK, merge_out->idx, merge_out->val,
+                           merge_out->count};
+    return launch_pareto_passes(spec, n, out, ws, (SelectScratch *)scratch, n_partials, rider, stream);
 }
 
 size_t topk_partials_bytes() { return top1_ws_bytes(); }
 
 // Merge of n_blocks block partials of kFusedTopK pairs each.
 hipError_t launch_topk_merge(void *ws, uint32_t n_blocks, uint32_t k, const guide_select_out &out, hipStream_t stream) {
-    hipLaunchKernelGGL(topk_merge_kernel<kFusedTopK>, dim3(1), dim3(kMergeThreads), 0, stream, top1_ws(ws), n_blocks, k,
-                       out.idx, out.val, out.count);
+    launch_top1_merge(kFusedTopK, ws, n_blocks, k, out, stream);
     return hipGetLastError();
 }
 

@@ -164,7 +164,7 @@ def load() -> C.CDLL:
         lib.guide_eval_select.argtypes = [C.c_void_p, C.POINTER(CGrid), C.c_uint64, C.c_uint64, C.POINTER(CEff),
                                           C.c_uint32, C.POINTER(CMetrics), C.c_void_p, C.c_uint32, C.c_void_p,
                                           C.c_size_t, C.c_void_p]
-        lib.guide_profile_enable.argtypes = [C.c_void_p, C.c_uint32]
+        lib.guide_profile_enable.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32]
         lib.guide_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_uint32)]
         _lib = lib
     return _lib
@@ -352,8 +352,8 @@ class Context:
                      _Arr(arr, selections), len(selections),
                      _dev_ptr(workspace), ws_bytes, _stream_ptr(stream))
 
-    def profile_enable(self, capacity: int):
-        self._check(self._lib.guide_profile_enable(self._h, capacity))
+    def profile_enable(self, capacity: int, every: int = 1):
+        self._check(self._lib.guide_profile_enable(self._h, capacity, every))
 
     def profile_read(self, capacity: int) -> np.ndarray:
         """Elapsed milliseconds of the evaluation kernels timed since the last read."""

@@ -174,6 +174,23 @@ def test_topk_without_stored_columns_and_errors(ora, torch_cuda):
     torch.cuda.synchronize()
     host = {k: bridge.to_np(v) for k, v in out.items()}
     _assert_selections(ora, host, topk, None, rt, None)
+    # top-k on a column that is not stored (reduced inside the evaluation, which then also takes the Pareto
+    # row sample) together with a Pareto front on stored columns
+    part = {k: out[k] for k in ("t_prefill", "cost", "feasible")}
+    tk = dict(objective="t_batch", k=4, constraints=[("t_decode", 30.0)])
+    pa = dict(x="t_prefill", y="cost")
+    for fst, cnt_ in [(first, count), (17, 100003)]:
+        sub = {k: v[:cnt_] for k, v in part.items()}
+        rt, rp = _run(torch, ctx, gg, fst, cnt_, sub, tk, pa)
+        full = bridge.metric_buffers(cnt_)
+        ctx.eval_grid(gg, fst, cnt_, out=full)
+        torch.cuda.synchronize()
+        hostf = {k: bridge.to_np(v) for k, v in full.items()}
+        for k in sub:
+            assert torch.equal(sub[k], full[k]), k
+        _assert_selections(ora, hostf, tk, pa, rt, rp)
+    ctx.eval_grid(gg, first, count, out=out)
+    torch.cuda.synchronize()
     # the Pareto passes read their columns: missing ones are an argument error
     with pytest.raises(guide.GuideError) as e:
         _run(torch, ctx, gg, first, count, {"cost": out["cost"]}, pareto=dict(x="t_prefill", y="cost"))
@@ -207,6 +224,10 @@ def test_profile_aid_times_the_evaluation_kernel(torch_cuda):
     ms = ctx.profile_read(3)
     assert len(ms) == 3 and np.all(ms > 0.005) and np.all(ms < 5.0)
     assert len(ctx.profile_read(3)) == 0
+    ctx.profile_enable(4, every=3)                        # launches 0, 3, 6 of 7 are timed
+    for _ in range(7):
+        ctx.eval_grid(gg, 0, g.size, out=out)
+    assert len(ctx.profile_read(4)) == 3
     ctx.profile_enable(0)
     ctx.eval_grid(gg, 0, g.size, out=out)
     torch.cuda.synchronize()
