@@ -667,9 +667,10 @@ __global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *
     }
 }
 
-__global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs w, SelectScratch *sc, uint32_t n_partials,
-                                                                        uint64_t *out_idx, uint64_t capacity,
-                                                                        uint64_t *out_count, MergeRider rider) {
+__global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs w, uint32_t n, SelectScratch *sc,
+                                                                        uint32_t n_partials, uint64_t *out_idx,
+                                                                        uint64_t capacity, uint64_t *out_count,
+                                                                        MergeRider rider) {
     if (blockIdx.x == 1) {                              // second block, launched only with a waiting top-k merge
         if (rider.K == 1)
             topk_merge_body<1, kFinishThreads>(rider.w, rider.n_blocks, rider.k, rider.out_idx, rider.out_val, rider.out_cnt);
@@ -690,24 +691,31 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
     const uint32_t t = threadIdx.x;
     __shared__ uint64_t s_rng[2];
     if (threadIdx.x == 0) s_nfront = 0;
+    // Everything the block reads from global memory is requested at once, before the survivor count is
+    // known: the first kStage survivor records (index clamped to the workspace's n rows; entries at or
+    // beyond the count are ignored later), the count, the bin counts and the sample partials.
+    constexpr uint32_t kPer = kStage / kFinishThreads;
+    uint64_t rx[kPer], ry[kPer];
+    uint32_t rr[kPer], cnt_in[kPerFinish];
+#pragma unroll
+    for (uint32_t q = 0; q < kPer; ++q) {
+        const uint32_t j = q * kFinishThreads + t, jc = j < n ? j : n - 1;
+        rx[q] = w.skx[jc];
+        ry[q] = w.sky[jc];
+        rr[q] = w.surv[jc];
+    }
+#pragma unroll
+    for (uint32_t q = 0; q < kPerFinish; ++q) cnt_in[q] = sc->bin_cnt[q * kFinishThreads + t];
     const uint32_t m = sc->counters[0];
     const Binning bin = sampled_binning(sc, n_partials, s_rng);
     if (m <= kStage) {
         // records staged in LDS, grouped by bin
-        for (uint32_t i = t; i < kBins; i += kFinishThreads) {
-            s_off[padded<P>(i)] = sc->bin_cnt[i];
+#pragma unroll
+        for (uint32_t q = 0; q < kPerFinish; ++q) {
+            const uint32_t i = q * kFinishThreads + t;
+            s_off[padded<P>(i)] = cnt_in[q];
             s_cur[i] = 0;
             s_foff[padded<P>(i)] = 0;
-        }
-        constexpr uint32_t kPer = kStage / kFinishThreads;
-        uint64_t rx[kPer], ry[kPer];
-        uint32_t rr[kPer];
-#pragma unroll
-        for (uint32_t q = 0; q < kPer; ++q) {           // all loads first: one memory latency
-            const uint32_t j = q * kFinishThreads + t;
-            rx[q] = j < m ? w.skx[j] : 0;
-            ry[q] = j < m ? w.sky[j] : 0;
-            rr[q] = j < m ? w.surv[j] : 0;
         }
         __syncthreads();
         scan_sum_excl<kFinishThreads, true>(s_off, s_tmp);
@@ -720,30 +728,41 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
             }
         }
         __syncthreads();
-        // eight lanes per survivor: they share out the survivors of its bin and
-        // meet through a wave ballot (each survivor's chain of dependent LDS reads
-        // is long, so many survivors are kept in flight)
-        constexpr uint32_t kGroup = 8;
-        const uint32_t lane = t % kWave, sub = lane % kGroup, shift = lane - sub;
-        const uint32_t q_step = kFinishThreads / kGroup;
-        const uint32_t m_pad = (m + q_step - 1) / q_step * q_step;   // wave-uniform trip count for the ballots
-        for (uint32_t q = t / kGroup; q < m_pad; q += q_step) {
-            const bool live = q < m;
-            const uint64_t kx = live ? s_kx[q] : 0, ky = live ? s_ky[q] : 0;
-            const uint32_t b = live ? s_bin[q] : 0;
-            const uint32_t beg = live ? s_off[padded<P>(b)] : 0, end = live ? s_off[padded<P>(b + 1)] : 0;
-            const uint32_t len = wave_max(end - beg);               // longest bin in the wave
-            bool dom = false;
-            for (uint32_t j0 = 0; j0 < len; j0 += kGroup) {
-                const uint32_t j = beg + j0 + sub;
-                if (j < end) dom = dom || (s_kx[j] <= kx && s_ky[j] <= ky && (s_kx[j] < kx || s_ky[j] < ky));
-            }
-            const bool dominated = ((__ballot(dom) >> shift) & ((1u << kGroup) - 1)) != 0;
-            if (live && sub == 0) {
-                s_flag[q] = dominated ? 0 : 1;
-                if (!dominated) {
-                    atomicAdd(&s_foff[padded<P>(b)], 1u);
-                    s_cur[atomicAdd(&s_nfront, 1u)] = q;            // s_cur is free again: list of front members
+        // Eight lanes per survivor: they share out the members of its bin, four LDS reads in flight each,
+        // and meet through a wave ballot.  A survivor's test is a chain of dependent LDS reads, so many
+        // survivors are kept in flight; fewer lanes per survivor (one round over all survivors, longer
+        // chains) measured slower.
+        constexpr uint32_t group = 8;
+        const uint32_t lane = t % kWave;
+        {
+            const uint32_t sub = lane % group, shift = lane - sub, q_step = kFinishThreads / group;
+            constexpr uint64_t group_mask = (1ull << group) - 1;
+            const uint32_t m_pad = (m + q_step - 1) / q_step * q_step;   // wave-uniform trip count for the ballot
+            for (uint32_t q = t / group; q < m_pad; q += q_step) {
+                const bool live = q < m;
+                const uint64_t kx = live ? s_kx[q] : 0, ky = live ? s_ky[q] : 0;
+                const uint32_t b = live ? s_bin[q] : 0;
+                const uint32_t beg = live ? s_off[padded<P>(b)] : 0, end = live ? s_off[padded<P>(b + 1)] : 0;
+                bool dom = false;
+                for (uint32_t j = beg + sub; j < end; j += 4 * group) {
+                    uint64_t jx[4], jy[4];
+#pragma unroll
+                    for (uint32_t u = 0; u < 4; ++u) {      // past the end: the bin's first member once more
+                        const uint32_t jj = j + u * group < end ? j + u * group : beg;
+                        jx[u] = s_kx[jj];
+                        jy[u] = s_ky[jj];
+                    }
+#pragma unroll
+                    for (uint32_t u = 0; u < 4; ++u)
+                        dom = dom || (jx[u] <= kx && jy[u] <= ky && (jx[u] < kx || jy[u] < ky));
+                }
+                const bool dominated = ((__ballot(dom) >> shift) & group_mask) != 0;
+                if (live && sub == 0) {
+                    s_flag[q] = dominated ? 0 : 1;
+                    if (!dominated) {
+                        atomicAdd(&s_foff[padded<P>(b)], 1u);
+                        s_cur[atomicAdd(&s_nfront, 1u)] = q;        // s_cur is free again: list of front members
+                    }
                 }
             }
         }
@@ -751,26 +770,38 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
         scan_sum_excl<kFinishThreads, true>(s_foff, s_tmp);
         if (t == 0) out_count[0] = s_foff[padded<P>(kBins)];
         const uint32_t nf = s_nfront;
-        const uint32_t f_pad = (nf + q_step - 1) / q_step * q_step;
-        for (uint32_t qf = t / kGroup; qf < f_pad; qf += q_step) {
-            const bool live = qf < nf;
-            const uint32_t q = live ? s_cur[qf] : 0;
-            const uint64_t kx = live ? s_kx[q] : 0, ky = live ? s_ky[q] : 0;
-            const uint32_t b = live ? s_bin[q] : 0, i = live ? s_row[q] : 0;
-            const uint32_t beg = live ? s_off[padded<P>(b)] : 0, end = live ? s_off[padded<P>(b + 1)] : 0;
-            const uint32_t len = wave_max(end - beg);
-            uint32_t rank = 0;
-            for (uint32_t j0 = 0; j0 < len; j0 += kGroup) {
-                const uint32_t j = beg + j0 + sub;
-                bool before = false;
-                if (j < end && s_flag[j]) {
-                    const uint64_t jx = s_kx[j], jy = s_ky[j];
-                    before = jx < kx || (jx == kx && (jy < ky || (jy == ky && s_row[j] < i)));
+        {
+            const uint32_t sub = lane % group, q_step = kFinishThreads / group;
+            const uint32_t f_pad = (nf + q_step - 1) / q_step * q_step;  // wave-uniform trip count for the shuffles
+            for (uint32_t qf = t / group; qf < f_pad; qf += q_step) {
+                const bool live = qf < nf;
+                const uint32_t q = live ? s_cur[qf] : 0;
+                const uint64_t kx = live ? s_kx[q] : 0, ky = live ? s_ky[q] : 0;
+                const uint32_t b = live ? s_bin[q] : 0, i = live ? s_row[q] : 0;
+                const uint32_t beg = live ? s_off[padded<P>(b)] : 0, end = live ? s_off[padded<P>(b + 1)] : 0;
+                uint32_t rank = 0;                          // front members of the bin that come before this one
+                for (uint32_t j = beg + sub; j < end; j += 4 * group) {
+                    uint64_t jx[4], jy[4];
+                    uint32_t jr[4];
+                    bool on[4];
+#pragma unroll
+                    for (uint32_t u = 0; u < 4; ++u) {
+                        const uint32_t jj = j + u * group;
+                        on[u] = jj < end;
+                        const uint32_t jc = on[u] ? jj : beg;
+                        on[u] = on[u] && s_flag[jc];
+                        jx[u] = s_kx[jc];
+                        jy[u] = s_ky[jc];
+                        jr[u] = s_row[jc];
+                    }
+#pragma unroll
+                    for (uint32_t u = 0; u < 4; ++u)
+                        rank += (on[u] && (jx[u] < kx || (jx[u] == kx && (jy[u] < ky || (jy[u] == ky && jr[u] < i))))) ? 1u : 0u;
                 }
-                rank += (uint32_t)__popcll((__ballot(before) >> shift) & ((1ull << kGroup) - 1));
+                for (uint32_t off = 1; off < group; off <<= 1) rank += __shfl_xor(rank, off, kWave);
+                const uint64_t pos = (uint64_t)s_foff[padded<P>(b)] + rank;
+                if (live && sub == 0 && pos < capacity) out_idx[pos] = i;
             }
-            const uint64_t pos = (uint64_t)s_foff[padded<P>(b)] + rank;
-            if (live && sub == 0 && pos < capacity) out_idx[pos] = i;
         }
     } else {
         // large front: the same steps through global tables
@@ -895,7 +926,7 @@ static hipError_t launch_pareto_passes(const guide_select_spec &spec, uint64_t n
         hipLaunchKernelGGL(pareto_survivors_kernel<MAXC>, dim3(nb), dim3(kBlock), 0, stream, x, y, f, n32, w, sc,
                            n_partials);
     });
-    hipLaunchKernelGGL(pareto_finish_kernel, dim3(rider.n_blocks ? 2 : 1), dim3(kFinishThreads), 0, stream, w, sc,
+    hipLaunchKernelGGL(pareto_finish_kernel, dim3(rider.n_blocks ? 2 : 1), dim3(kFinishThreads), 0, stream, w, n32, sc,
                        n_partials, out.idx, out.capacity, out.count, rider);
     return hipGetLastError();
 }
