@@ -585,8 +585,11 @@ static void launch_tile(const GridDesc &g, const DevTables *tab, const void *til
     }
 }
 
-// Tile shapes with a compiled kernel; other grids take the one-index-per-lane kernel.
-#define GUIDE_TILE_SHAPES(X) X(2, 3) X(1, 3) X(2, 1) X(2, 2) X(1, 2) X(3, 3) X(1, 4) X(2, 4)
+// Tile shapes with a compiled kernel (up to four values on each of the two fastest axes); other grids take the
+// one-index-per-lane kernel.
+#define GUIDE_TILE_SHAPES(X)                                                                     \
+    X(2, 3) X(1, 1) X(1, 2) X(1, 3) X(1, 4) X(2, 1) X(2, 2) X(2, 4) X(3, 1) X(3, 2) X(3, 3) X(3, 4) \
+    X(4, 1) X(4, 2) X(4, 3) X(4, 4)
 
 template <bool ADDITIVE>
 static bool dispatch_tile(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,

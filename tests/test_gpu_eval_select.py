@@ -213,6 +213,28 @@ def test_topk_without_stored_columns_and_errors(ora, torch_cuda):
     assert np.all(rt[0] == ora.NO_INDEX) and rt[2] == 0 and rp[1] == 0
 
 
+def test_topk_reduced_inside_the_evaluation_for_other_tile_shapes(ora, torch_cuda):
+    """Top-k on columns that are not stored, for several tile shapes, ranges that cut tiles, and both time models."""
+    torch = torch_cuda
+    hws = [wl.Hardware(1e14 * (1 + i), 1e12 * (1 + 0.3 * i), (40 + 30 * i) * wl.GIB, 1e11 * (1 + i), 1e-6 * i) for i in range(3)]
+    for nb, nm in [(1, 1), (3, 2), (4, 4), (2, 2), (1, 4), (4, 1)]:
+        g = wl.make_grid(wl.MODELS_FULL[:3], hws, wl.Axis.table([1, 4, 64]), wl.Axis.table([100, 3000, 20000]),
+                         wl.Axis.table([1, 40, 500]), wl.Axis.table([1, 2, 8]), wl.Axis.table([16, 4]),
+                         wl.Axis.table([16, 32, 8, 64][:nb]), wl.Axis.table([2048, 512, 8192, 300][:nm]))
+        ctx, gg = bridge.gpu_context(g), bridge.gpu_grid(g)
+        for first, count, tm in [(0, g.size, 0), (5, g.size - 9, 1), (g.size // 2 + 1, 77, 0)]:
+            tk = dict(objective="cost", k=4, constraints=[("t_prefill", 0.5), ("t_batch", 100.0)])
+            rt, _ = _run(torch, ctx, gg, first, count, {}, topk=tk, time_model=tm)
+            out = bridge.metric_buffers(count)
+            ctx.eval_grid(gg, first, count, out=out, time_model=tm)
+            torch.cuda.synchronize()
+            host, _ = _check_columns(ora, g, first, count, out, time_model=tm)
+            _assert_selections(ora, host, tk, None, rt, None)
+            tk1 = dict(objective="decode_tok_s", k=1, use_feasible=False)        # ties: 0 tokens/s when s_out = 1
+            rt, _ = _run(torch, ctx, gg, first, count, {}, topk=tk1, time_model=tm)
+            _assert_selections(ora, host, tk1, None, rt, None)
+
+
 def test_profile_aid_times_the_evaluation_kernel(torch_cuda):
     torch = torch_cuda
     g = wl.grid_full()

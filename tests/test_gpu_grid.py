@@ -180,9 +180,9 @@ def test_tile_shapes_generic_path_and_table_limits(ora, torch_cuda):
            for i in range(64)]
     models = list(wl.MODELS_FULL) + [wl.Model("m6", 24, 2048, 16, 4, 8192), wl.Model("m7", 60, 6144, 48, 48, 16384),
                                      wl.Model("m8", 16, 1024, 8, 2, 4096, E=4, k=1)]
-    shapes = [(2, 3), (1, 3), (2, 1), (2, 2), (1, 2), (3, 3), (1, 4), (2, 4), (4, 5), (1, 1)]
+    shapes = [(nb, nm) for nb in (1, 2, 3, 4) for nm in (1, 2, 3, 4)] + [(4, 5), (5, 1)]   # the last two: generic kernel
     for nb, nm in shapes:
-        blks = [16, 32, 8, 64][:nb]
+        blks = [16, 32, 8, 64, 128][:nb]
         mbts = [2048, 512, 8192, 300, 4096][:nm]
         g = wl.make_grid(models, hws[:3], wl.Axis.table([2, 9]), wl.Axis.table([100, 3000]), wl.Axis.table([1, 40]),
                          wl.Axis.table([1, 2, 3, 4, 8]), wl.Axis.table([16, 8, 4]), wl.Axis.table(blks),
