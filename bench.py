@@ -42,7 +42,7 @@ def main():
                          "(65 536 configs) only")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
+        sys.exit("bench.py: the library runs on ONE GPU (no sharding, no collectives); use --gpus 1")
 
     import numpy as np
     import torch

@@ -115,7 +115,7 @@ struct alignas(16) TileLds {
     double r_mbt[GUIDE_MAX_AXIS_VALUES];
     Coef coef[kCoefRows];                   // last: only the rows in use are copied
 };
-static_assert(offsetof(TileLds, coef) % 16 == 0 && sizeof(Coef) % 8 == 0, "copied in 8-byte words");
+static_assert(offsetof(TileLds, coef) % 16 == 0 && sizeof(TileLds) % 16 == 0, "copied in 16-byte words");
 
 __global__ __launch_bounds__(kBlock) void tile_tables_kernel(GridDesc g, const DevTables *__restrict__ tab,
                                                              TileLds *__restrict__ dst) {
@@ -153,10 +153,22 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
     const uint32_t n_rows = g.div[AX_MODEL].d * n_tp * n_w;
     const bool coef_in_lds = n_rows <= kCoefRows;
     {
-        const uint32_t words = (uint32_t)(offsetof(TileLds, coef) + (coef_in_lds ? n_rows : 0u) * sizeof(Coef)) / 8;
-        const uint64_t *src = (const uint64_t *)derived;
-        uint64_t *dst = (uint64_t *)&s;
-        for (uint32_t i = threadIdx.x; i < words; i += kBlock) dst[i] = src[i];
+        // every load is issued before the first LDS write, so the copy costs one memory latency
+        const uint32_t vecs = (uint32_t)(offsetof(TileLds, coef) + (coef_in_lds ? n_rows : 0u) * sizeof(Coef) + 15) / 16;
+        constexpr uint32_t kPer = (sizeof(TileLds) / 16 + kBlock - 1) / kBlock;
+        const uint4 *src = (const uint4 *)derived;
+        uint4 *dst = (uint4 *)&s;
+        uint4 t[kPer];
+#pragma unroll
+        for (uint32_t q = 0; q < kPer; ++q) {
+            const uint32_t i = q * kBlock + threadIdx.x;
+            t[q] = i < vecs ? src[i] : uint4{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (uint32_t q = 0; q < kPer; ++q) {
+            const uint32_t i = q * kBlock + threadIdx.x;
+            if (i < vecs) dst[i] = t[q];
+        }
     }
     TopList<kFusedTopK> top;
     uint64_t n_pass = 0, smp_lo = kNone, top_bound = kNone;

@@ -1,6 +1,7 @@
 // Selection kernels: constrained per-group top-k by (objective, row) order and
-// the two-objective Pareto front.  Reductions run in registers / wave shuffles,
-// then LDS per block, then a small second pass over the block partials.
+// the two-objective Pareto front.  Reductions run in registers and across lanes
+// in the vector ALU, then through LDS per block, then in a small second pass over
+// the block partials.
 //
 // Paper: the simulator evaluates every configuration and keeps the one(s) with
 // the least total time (Simulating Hybrid Parallelism); the engine keeps the top
@@ -334,11 +335,12 @@ __global__ __launch_bounds__(kBlock) void topk_final_kernel(TopkWs w, uint32_t G
 
 // --------------------------------------------------------------------- Pareto
 //
-// Four launches.
-// Prepare: a strided sample of rows fixes the stretch of x that the bins slice.
+// Four launches (the first can ride along with a top-k pass, and a top-k merge with the last).
+// Prepare: a strided sample of rows fixes the stretch of x that the bins slice; it also resets
+// the tables that the next two kernels accumulate into.
 // Staircase: every block builds in LDS the least y per x-bin over its rows (kBins
 // equal slices of that stretch, clamped at both ends, so a lower bin means a
-// strictly smaller x) and merges it into the global table with atomic-min.
+// strictly smaller x) and merges its running minima into the global table with atomic-min.
 // Survivors: a row survives when its y beats every row of every strictly lower
 // bin (exclusive prefix-min of the table) -- only survivors of its own bin can
 // still dominate it.  Survivors are appended as (row, keys).
