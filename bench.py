@@ -21,9 +21,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the grid kernel from rocprofv3 counters (profiles/eval_tile_kernel_full_grid_pmc.md):
-# WRITE_SIZE 83531.42 KiB x 1.0 + FETCH_SIZE 195.23 KiB x 2.0 (scales from a 512 MiB device copy).
+# WRITE_SIZE 83531.33 KiB x 1.0 + FETCH_SIZE 198.23 KiB x 2.0 (scales from a 512 MiB device copy).
 # Set to None whenever eval_tile_kernel changes after the counters were taken.
-TRAFFIC_BYTES_PER_LAUNCH = 85_936_005
+TRAFFIC_BYTES_PER_LAUNCH = 85_942_057
 BYTES_PER_CONFIG = 45           # 5 fp64 + u32 + u8 written per configuration, nothing read
 
 
