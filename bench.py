@@ -167,6 +167,7 @@ def main():
                      "kernel": "eval_tile_kernel<false,2,3,false>",
                      "kernel_ms": ms_eval, "kernel_launches_timed": n_timed,
                      "plain_eval_kernel_ms_back_to_back": ms_eval_b2b,
+                     "frac_back_to_back": BYTES_PER_CONFIG * n / (ms_eval_b2b * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "bytes_per_config": BYTES_PER_CONFIG},
         "phases_ms": {"eval_kernel_in_step": ms_eval, "step_as_three_calls": ms_separate,
                       "select_topk_alone": ms_topk, "select_pareto_alone": ms_pareto},
@@ -244,7 +245,9 @@ def extra_timings(ctx, gg, g, torch, np, guide, wl, n_sampled=1 << 28, n_sim=655
     steps = int(sim["n_steps"].sum().item())
     extra["simulate"] = {"request_steps_per_s": rs / s, "engine_steps_per_s": steps / s, "seconds": s,
                          "configs": n_cfg, "requests_per_config": len(tr.n_in), "request_steps": rs,
-                         "feasible_configs": int((sim["status"] == 0).sum().item()), "scheduler": "split-fuse"}
+                         "feasible_configs": int((sim["status"] == 0).sum().item()), "scheduler": "split-fuse",
+                         # from rocprofv3 counters, not measured in this run (profiles/extra_kernels_valu_pmc.md)
+                         "vector_issue_frac_profiled": 0.178}
     a.record()
     ctx.simulate(gg, d_idx, d_rate, (tr.arrival_unit, tr.n_in, tr.n_out), sim, ws, scheduler=guide.SCHED_PREFILL_FIRST)
     b.record()
