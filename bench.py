@@ -201,6 +201,26 @@ def extra_timings(ctx, gg, g, torch, np, guide, wl, n_sampled=1 << 28, n_sim=655
     st = {k: torch.empty(n, dtype=dt.get(k, torch.float64), device="cuda") for k in guide.STATS_COLUMNS}
     s = _timed(torch, lambda: ctx.eval_grid(gg, 0, n, stats=st, e_c=e_c, e_b=e_b))
     extra["sweep"] = {"evaluations_per_s": n * 64 / s, "configs_per_s": n / s, "seconds": s, "samples": 64}
+    # the whole uncertainty pipeline: sweep, (p90 TTFT, cost) front, cheapest configuration under each p90-TTFT cap
+    p_idx = torch.empty(1 << 16, dtype=torch.int64, device="cuda")
+    p_cnt = torch.empty(1, dtype=torch.int64, device="cuda")
+    a_idx = torch.empty(len(wl.SLO_CAPS_S), dtype=torch.int64, device="cuda")
+    a_val = torch.empty(len(wl.SLO_CAPS_S), dtype=torch.float64, device="cuda")
+    a_cnt = torch.empty(len(wl.SLO_CAPS_S), dtype=torch.int64, device="cuda")
+    ws_p = torch.empty(ctx.select_workspace_bytes(guide.SELECT_PARETO, n), dtype=torch.uint8, device="cuda")
+    ws_t = torch.empty(ctx.select_workspace_bytes(guide.SELECT_TOPK, n), dtype=torch.uint8, device="cuda")
+
+    def pipeline():
+        ctx.eval_grid(gg, 0, n, stats=st, e_c=e_c, e_b=e_b)
+        ctx.select(guide.SELECT_PARETO, n, st["ttft_p90"], p_idx, None, p_cnt, ws_p, objective_y=st["cost"],
+                   feasible=st["feasible"], capacity=1 << 16)
+        for j, cap in enumerate(wl.SLO_CAPS_S):
+            ctx.select(guide.SELECT_TOPK, n, st["cost"], a_idx[j:j + 1], a_val[j:j + 1], a_cnt[j:j + 1], ws_t,
+                       feasible=st["feasible"], constraints=[(st["ttft_p90"], cap)], k=1)
+    s = _timed(torch, pipeline, reps=3)
+    extra["sweep_pipeline"] = {"configs_per_s": n / s, "seconds": s, "front_size": int(p_cnt.item()),
+                               "argmin_under_p90_ttft_caps": [int(v) for v in a_idx.cpu().numpy().view(np.uint64)],
+                               "caps_s": list(wl.SLO_CAPS_S)}
     del st
 
     ex = dict(s_max=torch.empty(n, dtype=torch.int32, device="cuda"),

@@ -171,6 +171,35 @@ def test_full_grid_select_and_pareto_on_gpu_columns(ora, torch_cuda):
     np.testing.assert_array_equal(got, exp)
 
 
+def test_full_grid_sweep_then_front_and_slo_argmins(ora, torch_cuda):
+    """The uncertainty pipeline at full size: 64-sample sweep over the 1.9M-row grid, the (p90 TTFT, cost) front and
+    the cheapest configuration under each p90-TTFT cap.  Selections: GPU against the oracle on the same (GPU-computed)
+    columns, bit for bit; columns: blocks of rows against the oracle's sweep."""
+    torch = torch_cuda
+    g = wl.grid_full()
+    ctx = bridge.gpu_context(g)
+    e_c, e_b = wl.efficiency_pairs()
+    st = bridge.metric_buffers(g.size, names=STAT_COLS + ("b_max", "feasible"))
+    ctx.eval_grid(bridge.gpu_grid(g), 0, g.size, stats=st, e_c=e_c, e_b=e_b)
+    torch.cuda.synchronize()
+    host = {k: bridge.to_np(v) for k, v in st.items()}
+    og = bridge.ora_grid(g)
+    for first in (0, 777_777, g.size - 96):
+        exp = ora.eval_sweep_grid(og, e_c, e_b, first, 96)
+        for k in STAT_COLS:
+            assert bridge.rel_err(host[k][first:first + 96], exp[k]).max() <= TOL, (k, first)
+        np.testing.assert_array_equal(host["feasible"][first:first + 96], exp["feasible"])
+    got, m = _pareto(torch, ctx, st["ttft_p90"], st["cost"], st["feasible"])
+    exp = ora.pareto_sweep(host["ttft_p90"], host["cost"], host["feasible"])
+    assert m == len(exp) > 0
+    np.testing.assert_array_equal(got, exp)
+    for cap in wl.SLO_CAPS_S:
+        gi, gv, gc = _topk(torch, ctx, st["cost"], 1, st["feasible"], [(st["ttft_p90"], cap)])
+        ei, ev, ec = ora.select_topk(host["cost"], host["feasible"], [(host["ttft_p90"], cap)], k=1)
+        np.testing.assert_array_equal(gi, ei); np.testing.assert_array_equal(gv, ev)
+        np.testing.assert_array_equal(gc, ec)
+
+
 def test_select_on_zero_rows(torch_cuda):
     torch = torch_cuda
     ctx = bridge.gpu_context(wl.grid_tiny())
