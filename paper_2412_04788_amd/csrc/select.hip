@@ -10,6 +10,7 @@
 #include "reduce.hpp"
 #include "select_shared.hpp"
 
+#include <cstring>
 #include <type_traits>
 
 namespace guide {
@@ -555,10 +556,28 @@ __device__ inline void scan_sum_excl(uint32_t *io, uint32_t *s_tmp) {
     __syncthreads();
 }
 
-template <uint32_t MAXC>
+// A top-k selection over the same rows that reads nothing but the Pareto selection's two columns and its
+// flag column: the staircase kernel has those values in registers anyway and keeps the per-lane lists
+// beside its own work, so the top-k needs no pass of its own.
+struct SharedTopk {
+    uint32_t obj_is_y;             // objective: 0 = the x column, 1 = the y column
+    uint32_t use_feasible;         // rows with flag 0 do not pass
+    uint32_t n_con;                // <= 2 constraints, each on x or y
+    uint32_t con_is_y[2];
+    double cap[2];
+    Top1Ws w;                      // block partials, as written by the top-k pass
+};
+
+// KT: pairs per block partial of the shared top-k (0 = none; then `topk` is ignored).
+template <uint32_t MAXC, int KT>
 __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__restrict__ x, const double *__restrict__ y,
-                                                              RowFilter f, uint32_t n, SelectScratch *sc, uint32_t n_partials) {
+                                                              RowFilter f, uint32_t n, SelectScratch *sc, uint32_t n_partials,
+                                                              SharedTopk topk) {
     __shared__ uint64_t s_min[padded_size<kPerPass>()], s_tmp[kWaves], s_rng[2];
+    constexpr int KL = KT ? KT : 1;
+    TopList<KL> list;
+    uint64_t n_pass = 0;
+    if (KT) list.init();
     const uint32_t per = rows_per_block(n, gridDim.x);
     const uint64_t begin = (uint64_t)blockIdx.x * per;
     const uint64_t end = begin + per < n ? begin + per : n;
@@ -576,11 +595,23 @@ __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__re
 #pragma unroll
         for (uint32_t u = 0; u < kUnroll; ++u) {
             const Row q = row_of<true, MAXC>(r[u], f);
-            if (!q.pass) continue;
-            const uint32_t b = padded<kPerPass>(bin(key_of(q.x)));
-            const uint64_t ky = key_of(q.y);
-            // the slot only decreases, so a stale read can only let an extra atomic through
-            if (ky < s_min[b]) atomicMin((unsigned long long *)&s_min[b], (unsigned long long)ky);
+            if (q.pass) {
+                const uint32_t b = padded<kPerPass>(bin(key_of(q.x)));
+                const uint64_t ky = key_of(q.y);
+                // the slot only decreases, so a stale read can only let an extra atomic through
+                if (ky < s_min[b]) atomicMin((unsigned long long *)&s_min[b], (unsigned long long)ky);
+            }
+            if (KT) {
+                const double obj = topk.obj_is_y ? r[u].y : r[u].x;
+                bool ok = r[u].valid && (!topk.use_feasible || r[u].fe != 0) && obj == obj;
+#pragma unroll
+                for (uint32_t c = 0; c < 2; ++c)
+                    if (c < topk.n_con) ok = ok && ((topk.con_is_y[c] ? r[u].y : r[u].x) <= topk.cap[c]);
+                if (ok) {
+                    ++n_pass;
+                    list.insert(Pair{key_of(obj), (uint64_t)((uint32_t)base + threadIdx.x + u * kBlock)});
+                }
+            }
         }
         base += kBlock * kUnroll;
         if (base < end) {
@@ -602,6 +633,21 @@ __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__re
         if (v[j] < run) {
             atomicMin((unsigned long long *)&sc->bin_min[threadIdx.x * kPerPass + j], (unsigned long long)v[j]);
             run = v[j];
+        }
+    }
+    if (KT) {
+        __shared__ Pair s_pairs[kWaves][KL];
+        __shared__ uint64_t s_cnt[kWaves];
+        for (int off = kWave / 2; off > 0; off >>= 1) n_pass += __shfl_xor(n_pass, off, kWave);
+        if (threadIdx.x % kWave == 0) s_cnt[threadIdx.x / kWave] = n_pass;
+        block_topk<KL, kWaves>(list, s_pairs, [&](int rk, const Pair &p) {
+            topk.w.key[(size_t)blockIdx.x * KL + rk] = p.key;
+            topk.w.idx[(size_t)blockIdx.x * KL + rk] = p.idx;
+        });                                             // (contains the barrier that publishes s_cnt)
+        if (threadIdx.x == 0) {
+            uint64_t c = 0;
+            for (int wv = 0; wv < kWaves; ++wv) c += s_cnt[wv];
+            topk.w.cnt[blockIdx.x] = c;
         }
     }
 }
@@ -917,16 +963,24 @@ hipError_t launch_select_topk(const guide_select_spec &spec, uint64_t n, const g
 
 static hipError_t launch_pareto_passes(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
                                        SelectScratch *sc, uint32_t n_partials, const MergeRider &rider,
-                                       hipStream_t stream) {
+                                       hipStream_t stream, const SharedTopk *shared = nullptr, int shared_k = 0) {
     const ParetoWs w = pareto_ws(ws, n);
     const RowFilter f = make_filter(spec);
     const uint32_t nb = blocks_for(n), n32 = (uint32_t)n;
     const double *x = spec.objective, *y = spec.objective_y;
+    const dim3 grid(nb), block(kBlock);
+    if (shared) {       // only offered for a Pareto selection without constraint columns
+        const SharedTopk t = *shared;
+        if (shared_k == 1) hipLaunchKernelGGL((pareto_stair_kernel<0, 1>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t);
+        else if (shared_k == 2) hipLaunchKernelGGL((pareto_stair_kernel<0, 2>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t);
+        else hipLaunchKernelGGL((pareto_stair_kernel<0, 4>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t);
+    }
     with_max_constraints(f.n_con, [&](auto maxc) {
         constexpr uint32_t MAXC = decltype(maxc)::value;
-        hipLaunchKernelGGL(pareto_stair_kernel<MAXC>, dim3(nb), dim3(kBlock), 0, stream, x, y, f, n32, sc, n_partials);
-        hipLaunchKernelGGL(pareto_survivors_kernel<MAXC>, dim3(nb), dim3(kBlock), 0, stream, x, y, f, n32, w, sc,
-                           n_partials);
+        if (!shared)
+            hipLaunchKernelGGL((pareto_stair_kernel<MAXC, 0>), grid, block, 0, stream, x, y, f, n32, sc, n_partials,
+                               SharedTopk{});
+        hipLaunchKernelGGL(pareto_survivors_kernel<MAXC>, grid, block, 0, stream, x, y, f, n32, w, sc, n_partials);
     });
     hipLaunchKernelGGL(pareto_finish_kernel, dim3(rider.n_blocks ? 2 : 1), dim3(kFinishThreads), 0, stream, w, n32, sc,
                        n_partials, out.idx, out.capacity, out.count, rider);
@@ -945,22 +999,54 @@ hipError_t launch_select_pareto(const guide_select_spec &spec, uint64_t n, const
     return launch_pareto_passes(spec, n, out, ws, sc, kSampleBlocks, MergeRider{}, stream);
 }
 
+// True when the top-k selection reads only the Pareto selection's x, y and flag columns (and the Pareto
+// selection has no constraint columns); fills the description for the staircase kernel.
+static bool shares_columns(const guide_select_spec &topk, const guide_select_spec &pareto, SharedTopk *t) {
+    const double *x = pareto.objective, *y = pareto.objective_y;
+    if (pareto.n_constraints != 0 || topk.n_constraints > 2 || topk.k > 4) return false;
+    if (topk.objective != x && topk.objective != y) return false;
+    if (topk.feasible && topk.feasible != pareto.feasible) return false;
+    memset(t, 0, sizeof *t);
+    t->obj_is_y = topk.objective == y ? 1u : 0u;
+    t->use_feasible = topk.feasible ? 1u : 0u;
+    t->n_con = topk.n_constraints;
+    for (uint32_t c = 0; c < topk.n_constraints; ++c) {
+        const double *col = topk.constraints[c].column;
+        if (col != x && col != y) return false;
+        t->con_is_y[c] = col == y ? 1u : 0u;
+        t->cap[c] = topk.constraints[c].cap;
+    }
+    return true;
+}
+
 // A top-k selection (one group) and a Pareto selection over the same n > 0 rows in four launches
-// instead of six: the Pareto row sample rides along with the top-k pass, and the top-k merge with the
-// finishing kernel of the Pareto front (for block partials of up to 4 pairs; wider ones merge alone).
+// instead of six.  The top-k merge rides along with the finishing kernel of the Pareto front (for block
+// partials of up to 4 pairs; wider ones merge alone).  When the top-k reads only the Pareto selection's
+// columns, its pass is folded into the staircase kernel (sample, staircase + lists, survivors, finish +
+// merge); otherwise the Pareto row sample rides along with the top-k pass (pass + sample, staircase,
+// survivors, finish + merge).
 hipError_t launch_select_both(const guide_select_spec &topk, const guide_select_out &topk_out, void *topk_ws,
                               const guide_select_spec &pareto, const guide_select_out &pareto_out, void *pareto_ws_,
                               uint64_t n, void *scratch, hipStream_t stream) {
     SelectScratch *sc = (SelectScratch *)scratch;
-    const SampleRider sample{1u, pareto.objective, pareto.objective_y, make_filter(pareto), sc};
-    launch_top1_pass(topk, n, topk_ws, sample, stream);
     const int K = partial_width(topk.k);
+    SharedTopk shared;
+    const bool folded = shares_columns(topk, pareto, &shared);
+    if (folded) {
+        shared.w = top1_ws(topk_ws);
+        hipLaunchKernelGGL(pareto_prepare_kernel, dim3(kSampleBlocks), dim3(kBlock), 0, stream, pareto.objective,
+                           pareto.objective_y, make_filter(pareto), (uint32_t)n, sc);
+    } else {
+        const SampleRider sample{1u, pareto.objective, pareto.objective_y, make_filter(pareto), sc};
+        launch_top1_pass(topk, n, topk_ws, sample, stream);
+    }
     MergeRider rider{};
     if (K <= 4)
         rider = MergeRider{top1_ws(topk_ws), blocks_for(n), topk.k, (uint32_t)K, topk_out.idx, topk_out.val, topk_out.count};
     else
         launch_top1_merge(K, topk_ws, blocks_for(n), topk.k, topk_out, stream);
-    return launch_pareto_passes(pareto, n, pareto_out, pareto_ws_, sc, kSampleBlocks, rider, stream);
+    return launch_pareto_passes(pareto, n, pareto_out, pareto_ws_, sc, kSampleBlocks, rider, stream,
+                                folded ? &shared : nullptr, K);
 }
 
 // The passes after the sample, for a caller whose own kernel has sampled the rows and reset the tables.

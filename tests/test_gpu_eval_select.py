@@ -118,6 +118,15 @@ def test_tiny_grid_ranges_and_modes(ora, torch_cuda):
     rt, rp = _run(torch, ctx, gg, 0, g.size, out, topk=dict(objective="t_prefill", k=2), pareto=pa)
     host, _ = _check_columns(ora, g, 0, g.size, out)
     _assert_selections(ora, host, dict(objective="t_prefill", k=2), pa, rt, rp)
+    # a top-k that reads only the front's two columns is folded into the staircase kernel: objective on either
+    # column, constraints on both, with and without the flag column, every partial width
+    pa2 = dict(x="t_prefill", y="cost")
+    for obj, cons, fe, k in [("cost", [("t_prefill", 0.3), ("cost", 1.0)], True, 4), ("t_prefill", [("cost", 0.05)], False, 1),
+                             ("t_prefill", [], True, 2), ("cost", [("cost", -1.0)], True, 3)]:
+        tk = dict(objective=obj, k=k, use_feasible=fe, constraints=cons)
+        rt, rp = _run(torch, ctx, gg, 0, g.size, out, topk=tk, pareto=pa2)
+        host, _ = _check_columns(ora, g, 0, g.size, out)
+        _assert_selections(ora, host, tk, pa2, rt, rp)
     # an efficiency sample
     rt, rp = _run(torch, ctx, gg, 0, g.size, out, topk, pareto, eff=(0.83, 1.21))
     host, _ = _check_columns(ora, g, 0, g.size, out, eff=(0.83, 1.21))
