@@ -345,7 +345,7 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
                         for (int j = 0; j < TS; ++j) {
                             const int k = j / NM, m = j % NM;
                             if (ok_m[m] && feas(k) && key[m] <= top_bound)
-                                top.insert(Pair{key[m], (uint64_t)(row0 + j - first)});
+                                top.insert_ascending(Pair{key[m], (uint64_t)(row0 + j - first)});
                         }
                     }
                 } else {
@@ -355,7 +355,7 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
                         const uint32_t row = row0 + j;
                         if (ok_m[m] && row >= first && row < last && feas(k)) {
                             ++n_pass;
-                            if (key[m] <= top_bound) top.insert(Pair{key[m], (uint64_t)(row - first)});
+                            if (key[m] <= top_bound) top.insert_ascending(Pair{key[m], (uint64_t)(row - first)});
                         }
                     }
                 }

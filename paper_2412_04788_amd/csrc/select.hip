@@ -125,7 +125,7 @@ struct SampleRider {
 };
 struct MergeRider {
     Top1Ws w;
-    uint32_t n_blocks, k, K;       // K: pairs per block partial (1, 2 or 4)
+    uint32_t n_blocks, k, K;       // K: pairs per block partial (1 .. 4)
     uint64_t *out_idx;
     double *out_val;
     uint64_t *out_cnt;
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(kBlock) void topk_pass_kernel(const double *__restr
         for (uint32_t u = 0; u < kUnroll; ++u) {
             if (r[u].pass) {
                 ++cnt;
-                l.insert(Pair{key_of(r[u].x), (uint32_t)base + u * kBlock});
+                l.insert_ascending(Pair{key_of(r[u].x), (uint32_t)base + u * kBlock});
             }
         }
     }
@@ -609,7 +609,7 @@ __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__re
                     if (c < topk.n_con) ok = ok && ((topk.con_is_y[c] ? r[u].y : r[u].x) <= topk.cap[c]);
                 if (ok) {
                     ++n_pass;
-                    list.insert(Pair{key_of(obj), (uint64_t)((uint32_t)base + threadIdx.x + u * kBlock)});
+                    list.insert_ascending(Pair{key_of(obj), (uint64_t)((uint32_t)base + threadIdx.x + u * kBlock)});
                 }
             }
         }
@@ -724,6 +724,8 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
             topk_merge_body<1, kFinishThreads>(rider.w, rider.n_blocks, rider.k, rider.out_idx, rider.out_val, rider.out_cnt);
         else if (rider.K == 2)
             topk_merge_body<2, kFinishThreads>(rider.w, rider.n_blocks, rider.k, rider.out_idx, rider.out_val, rider.out_cnt);
+        else if (rider.K == 3)
+            topk_merge_body<3, kFinishThreads>(rider.w, rider.n_blocks, rider.k, rider.out_idx, rider.out_val, rider.out_cnt);
         else
             topk_merge_body<4, kFinishThreads>(rider.w, rider.n_blocks, rider.k, rider.out_idx, rider.out_val, rider.out_cnt);
         return;
@@ -909,11 +911,12 @@ void launch_top1_pass(const guide_select_spec &spec, uint64_t n, void *ws, const
     });
 }
 // Pairs per block partial for a request of k (the pass kernel's template argument).
-int partial_width(uint32_t k) { return k == 1 ? 1 : k == 2 ? 2 : k <= 4 ? 4 : 8; }
+int partial_width(uint32_t k) { return k <= 4 ? (int)k : 8; }
 void launch_top1_pass(const guide_select_spec &spec, uint64_t n, void *ws, const SampleRider &sample, hipStream_t stream) {
     switch (partial_width(spec.k)) {
         case 1: launch_top1_pass<1>(spec, n, ws, sample, stream); break;
         case 2: launch_top1_pass<2>(spec, n, ws, sample, stream); break;
+        case 3: launch_top1_pass<3>(spec, n, ws, sample, stream); break;
         case 4: launch_top1_pass<4>(spec, n, ws, sample, stream); break;
         default: launch_top1_pass<8>(spec, n, ws, sample, stream); break;
     }
@@ -924,6 +927,7 @@ void launch_top1_merge(int K, void *ws, uint32_t n_blocks, uint32_t k, const gui
     switch (K) {
         case 1: hipLaunchKernelGGL(topk_merge_kernel<1>, one, nt, 0, stream, w, n_blocks, k, out.idx, out.val, out.count); break;
         case 2: hipLaunchKernelGGL(topk_merge_kernel<2>, one, nt, 0, stream, w, n_blocks, k, out.idx, out.val, out.count); break;
+        case 3: hipLaunchKernelGGL(topk_merge_kernel<3>, one, nt, 0, stream, w, n_blocks, k, out.idx, out.val, out.count); break;
         case 4: hipLaunchKernelGGL(topk_merge_kernel<4>, one, nt, 0, stream, w, n_blocks, k, out.idx, out.val, out.count); break;
         default: hipLaunchKernelGGL(topk_merge_kernel<8>, one, nt, 0, stream, w, n_blocks, k, out.idx, out.val, out.count); break;
     }
@@ -973,6 +977,7 @@ static hipError_t launch_pareto_passes(const guide_select_spec &spec, uint64_t n
         const SharedTopk t = *shared;
         if (shared_k == 1) hipLaunchKernelGGL((pareto_stair_kernel<0, 1>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t);
         else if (shared_k == 2) hipLaunchKernelGGL((pareto_stair_kernel<0, 2>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t);
+        else if (shared_k == 3) hipLaunchKernelGGL((pareto_stair_kernel<0, 3>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t);
         else hipLaunchKernelGGL((pareto_stair_kernel<0, 4>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t);
     }
     with_max_constraints(f.n_con, [&](auto maxc) {

@@ -44,6 +44,23 @@ struct TopList {
             }
         }
     }
+    // insert() for a caller whose rows arrive in ascending order: the new row is larger than every row
+    // in the list, so it goes before exactly the entries with a larger key.  No branches inside: every
+    // position takes its left neighbour, the new pair or itself.
+    __device__ void insert_ascending(const Pair &p) {
+        if (p.key < v[K - 1].key) {
+#pragma unroll
+            for (int i = K - 1; i > 0; --i) {
+                const bool shift = p.key < v[i - 1].key;    // the neighbour moves up into position i
+                const bool here = p.key < v[i].key;         // (and not shift:) the new pair lands at i
+                v[i].key = shift ? v[i - 1].key : (here ? p.key : v[i].key);
+                v[i].idx = shift ? v[i - 1].idx : (here ? p.idx : v[i].idx);
+            }
+            const bool first = p.key < v[0].key;
+            v[0].key = first ? p.key : v[0].key;
+            v[0].idx = first ? p.idx : v[0].idx;
+        }
+    }
     __device__ void pop() {
 #pragma unroll
         for (int i = 0; i + 1 < K; ++i) v[i] = v[i + 1];
