@@ -50,24 +50,30 @@ __device__ inline uint64_t read_lane63(uint64_t v) {
 }
 __device__ inline uint64_t min_u64(uint64_t a, uint64_t b) { return b < a ? b : a; }
 
-// Least pair of the wave, in every lane.  Every lane of the wave must be active.
-__device__ inline Pair wave_min(Pair p) {
-    p = pair_min(p, dpp_keep<0xB1>(p));
-    p = pair_min(p, dpp_keep<0x4E>(p));
-    p = pair_min(p, dpp_keep<0x141>(p));
-    p = pair_min(p, dpp_keep<0x140>(p));          // every lane holds the minimum of its row
-    p = pair_min(p, dpp_keep<0x142, 0xa>(p));
-    p = pair_min(p, dpp_keep<0x143, 0xc>(p));     // lane 63 holds the minimum of the wave
-    return Pair{read_lane63(p.key), read_lane63(p.idx)};
+// Least value of the wave, in every lane.  Every lane of the wave must be active.  Wider values are
+// reduced 32 bits at a time, most significant first: lanes that do not hold the minimum so far drop
+// out of the next pass (a 32-bit step is one move-and-minimum; a 64-bit compare-and-select is five).
+__device__ inline uint32_t wave_min(uint32_t v) {
+    uint32_t o;
+    o = dpp_u32<0xB1>(v, v); v = o < v ? o : v;
+    o = dpp_u32<0x4E>(v, v); v = o < v ? o : v;
+    o = dpp_u32<0x141>(v, v); v = o < v ? o : v;
+    o = dpp_u32<0x140>(v, v); v = o < v ? o : v;          // every lane holds the minimum of its row
+    o = dpp_u32<0x142, 0xa>(v, v); v = o < v ? o : v;
+    o = dpp_u32<0x143, 0xc>(v, v); v = o < v ? o : v;     // lane 63 holds the minimum of the wave
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, kWave - 1);
 }
 __device__ inline uint64_t wave_min(uint64_t v) {
-    v = min_u64(v, dpp_keep<0xB1>(v));
-    v = min_u64(v, dpp_keep<0x4E>(v));
-    v = min_u64(v, dpp_keep<0x141>(v));
-    v = min_u64(v, dpp_keep<0x140>(v));
-    v = min_u64(v, dpp_keep<0x142, 0xa>(v));
-    v = min_u64(v, dpp_keep<0x143, 0xc>(v));
-    return read_lane63(v);
+    const uint32_t hi = (uint32_t)(v >> 32), lo = (uint32_t)v;
+    const uint32_t m_hi = wave_min(hi);
+    const uint32_t m_lo = wave_min(hi == m_hi ? lo : 0xFFFFFFFFu);
+    return ((uint64_t)m_hi << 32) | m_lo;
+}
+// Least (key, idx) pair of the wave in lexicographic order.
+__device__ inline Pair wave_min(Pair p) {
+    const uint64_t m_key = wave_min(p.key);
+    const uint64_t m_idx = wave_min(p.key == m_key ? p.idx : kNone);
+    return Pair{m_key, m_idx};
 }
 __device__ inline uint32_t wave_max(uint32_t v) {
     uint32_t o;
