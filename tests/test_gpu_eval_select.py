@@ -127,6 +127,13 @@ def test_tiny_grid_ranges_and_modes(ora, torch_cuda):
         rt, rp = _run(torch, ctx, gg, 0, g.size, out, topk=tk, pareto=pa2)
         host, _ = _check_columns(ora, g, 0, g.size, out)
         _assert_selections(ora, host, tk, pa2, rt, rp)
+    # k above 4 beside a front: the pass keeps its own launch (with the row sample riding along) and merges alone;
+    # a top-k on a third column beside a front: pass + sample rider, merge beside the finishing kernel
+    for tk in (dict(objective="cost", k=8, constraints=[("t_prefill", 0.3)]), dict(objective="t_batch", k=3),
+               dict(objective="cost", k=5, use_feasible=False)):
+        rt, rp = _run(torch, ctx, gg, 0, g.size, out, topk=tk, pareto=pa2)
+        host, _ = _check_columns(ora, g, 0, g.size, out)
+        _assert_selections(ora, host, tk, pa2, rt, rp)
     # an efficiency sample
     rt, rp = _run(torch, ctx, gg, 0, g.size, out, topk, pareto, eff=(0.83, 1.21))
     host, _ = _check_columns(ora, g, 0, g.size, out, eff=(0.83, 1.21))
