@@ -104,10 +104,10 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # timed region: K steps; the library brackets the grid-evaluation kernel of every fifth step with a
+    # timed region: K steps; the library brackets the grid-evaluation kernel of every tenth step with a
     # pair of HIP events on the launch stream (an event pair delays the launches around it by a few
     # microseconds, so not every step carries one)
-    every = 5 if args.steps >= 10 else 1
+    every = 10 if args.steps >= 20 else 1
     n_timed = (args.steps + every - 1) // every
     ctx.profile_enable(n_timed, every)
     t0 = time.perf_counter()
