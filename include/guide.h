@@ -300,7 +300,10 @@ int guide_select(guide_ctx *ctx, const guide_select_spec *spec, uint64_t n, cons
  * configurations, one group) -- the engine's "evaluate every configuration, keep
  * the best" (Inference Engine Step 2; Simulating Hybrid Parallelism) -- in fewer
  * launches: with a top-k and a Pareto selection, the small kernels of one ride
- * along with the large kernels of the other.  Columns are named by GUIDE_COL_*.
+ * along with the large kernels of the other, and a top-k (k <= 4) that refers only
+ * to the Pareto selection's two columns has no pass of its own.  Columns are named
+ * by GUIDE_COL_*; a tile kernel exists for up to four values on each of the two
+ * fastest axes.
  * At most one selection per mode (n_sel <= 2; n_sel = 0 is a plain evaluation).
  * Every column that a selection refers to, and `feasible` when use_feasible is
  * set, must be present in `out` (GUIDE_E_ARG otherwise), with one exception: for
