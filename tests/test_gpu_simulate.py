@@ -74,6 +74,37 @@ def test_full_trace_2048_configs(ora, torch_cuda):
     assert got["n_request_steps"][ok].min() >= tr.n_out.sum()
 
 
+def test_benchmark_size_sampled_configs_and_invariants(ora, torch_cuda):
+    """The benchmark's launch: 65 536 configurations x 1024 requests, both schedulers.  256 configurations spread
+    over the list are checked one by one against the oracle; the rest through invariants that hold for any
+    schedule (every request emits all its tokens, steps are bounded by tokens, the first 2048 configurations are the
+    ones of the 2048-configuration run)."""
+    torch = torch_cuda
+    g = wl.grid_full()
+    ctx = bridge.gpu_context(g)
+    og = bridge.ora_grid(g)
+    tr = wl.request_trace()
+    n_cfg = 65536
+    idx, rate = wl.sim_configs(g, n_cfg)
+    pick = np.linspace(0, n_cfg - 1, 256).astype(np.int64)
+    for sched in (0, 1):
+        got = _run(torch, ctx, g, idx, rate, tr, scheduler=sched)
+        exp = ora.simulate_grid(og, idx[pick], rate[pick], tr.arrival_unit, tr.n_in, tr.n_out, scheduler=sched)
+        _compare({k: v[pick] for k, v in got.items()}, exp)
+        ok = got["status"] == 0
+        assert ok.sum() > 50000 and set(np.unique(got["status"])) <= {0, 1}
+        # decode tokens: every request's n_out - 1 decode steps, plus at least one prompt chunk each
+        assert (got["n_request_steps"][ok] >= int((tr.n_out - 1).sum()) + len(tr.n_in)).all()
+        assert (got["n_steps"][ok] <= int((tr.n_in + tr.n_out).sum()) + len(tr.n_in)).all()
+        assert (got["n_steps"][ok] >= int(tr.n_out.max()) - 1).all()
+        assert np.isfinite(got["ttft_p99"][ok]).all() and (got["ttft_p50"][ok] <= got["ttft_p99"][ok]).all()
+        assert (got["tokens_s"][ok] > 0).all() and np.isinf(got["ttft_p50"][~ok]).all() and (got["n_steps"][~ok] == 0).all()
+        if sched == 0:
+            first = _run(torch, ctx, g, idx[:2048], rate[:2048], tr)
+            for k in first:
+                np.testing.assert_array_equal(first[k], got[k][:2048])
+
+
 def test_prefill_first_scheduler(ora, torch_cuda):
     """The whole-prompt, decoders-pause variant on the full trace and on a tight pool."""
     torch = torch_cuda
