@@ -104,8 +104,8 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # timed region: K steps; the library brackets the grid-evaluation kernel of every tenth step with a
-    # pair of HIP events on the launch stream (an event pair delays the launches around it by a few
+    # timed region: K steps; the library attaches a pair of HIP events to the dispatch of the grid-evaluation
+    # kernel of every tenth step, on the launch stream (a timed launch delays the launches around it by a few
     # microseconds, so not every step carries one)
     every = 10 if args.steps >= 20 else 1
     n_timed = (args.steps + every - 1) // every

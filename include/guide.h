@@ -335,11 +335,12 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
 /*
  * Kernel timing aid.  After guide_profile_enable(ctx, capacity, every), every
  * `every`-th grid evaluation kernel launched by guide_eval_grid (one sample) or
- * guide_eval_select (the first, the every+1-th, ...) is bracketed by a pair of
- * HIP events recorded on the call's stream, for up to `capacity` timed launches
- * (later ones are not timed); capacity 0 switches it off.  An event pair delays
- * the launches around it by a few microseconds, which is why a caller that also
- * measures throughput times a subset.  guide_profile_read waits for the recorded
+ * guide_eval_select (the first, the every+1-th, ...) carries a pair of HIP events
+ * on the call's stream that receive the start and the end of that kernel's
+ * dispatch, for up to `capacity` timed launches (later ones are not timed);
+ * capacity 0 switches it off.  A timed launch delays the launches around it by a
+ * few microseconds, which is why a caller that also measures throughput times a
+ * subset.  guide_profile_read waits for the recorded
  * events, writes the elapsed milliseconds of each timed launch to ms[0 .. *n)
  * (HOST, room for `capacity` values) and starts over.
  */

@@ -1,6 +1,8 @@
 // Grid evaluation kernels: flat index -> mixed-radix digits -> candidate ->
 // metrics, one candidate per lane, spec tables staged in LDS, coalesced
 // structure-of-arrays stores.
+#include <hip/hip_ext.h>
+
 #include "kernels.hpp"
 #include "perf_model.hpp"
 #include "select_shared.hpp"
@@ -584,17 +586,24 @@ constexpr uint32_t kSampleRows = 16384;
 template <bool ADDITIVE, int NB, int NM>
 static void launch_tile(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
                         uint32_t count, double re_c, double re_b, const guide_metrics &out, const FusedSelect *fs,
-                        hipStream_t stream) {
+                        hipStream_t stream, LaunchTiming tm) {
     const dim3 grid(tile_blocks(first, count, NB * NM)), block(kBlock);
     static_assert(2 * kNumCU <= kMaxSamplePartials && 2 * kNumCU <= kSelBlocks, "one partial per block");
-    if (fs) {
-        const uint32_t stride = count > kSampleRows ? count / kSampleRows : 1;
+    // with timing events the launch goes through the extended call, which attaches them to the dispatch
+    const uint32_t stride = count > kSampleRows ? count / kSampleRows : 1;
+    const TileLds *tables = (const TileLds *)tile_tables;
+    if (fs && tm.start)
+        hipExtLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM, true>), grid, block, 0, stream, tm.start, tm.stop, 0, g, tab,
+                              first, count, re_c, re_b, out, *fs, make_div32(stride), kSampleRows, tables);
+    else if (fs)
         hipLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM, true>), grid, block, 0, stream, g, tab, first, count, re_c,
-                           re_b, out, *fs, make_div32(stride), kSampleRows, (const TileLds *)tile_tables);
-    } else {
+                           re_b, out, *fs, make_div32(stride), kSampleRows, tables);
+    else if (tm.start)
+        hipExtLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM, false>), grid, block, 0, stream, tm.start, tm.stop, 0, g,
+                              tab, first, count, re_c, re_b, out, FusedSelect{}, Div32{}, 0u, tables);
+    else
         hipLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM, false>), grid, block, 0, stream, g, tab, first, count, re_c,
-                           re_b, out, FusedSelect{}, Div32{}, 0u, (const TileLds *)tile_tables);
-    }
+                           re_b, out, FusedSelect{}, Div32{}, 0u, tables);
 }
 
 // Tile shapes with a compiled kernel (up to four values on each of the two fastest axes); other grids take the
@@ -606,11 +615,11 @@ static void launch_tile(const GridDesc &g, const DevTables *tab, const void *til
 template <bool ADDITIVE>
 static bool dispatch_tile(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
                           uint32_t count, double re_c, double re_b, const guide_metrics &out, const FusedSelect *fs,
-                          hipStream_t stream, uint32_t *n_blocks) {
+                          hipStream_t stream, uint32_t *n_blocks, LaunchTiming tm) {
     const uint32_t nb = g.div[AX_BLK].d, nm = g.div[AX_MBT].d;
 #define GUIDE_TILE(NB, NM)                                                                   \
     if (nb == NB && nm == NM) {                                                              \
-        launch_tile<ADDITIVE, NB, NM>(g, tab, tile_tables, first, count, re_c, re_b, out, fs, stream); \
+        launch_tile<ADDITIVE, NB, NM>(g, tab, tile_tables, first, count, re_c, re_b, out, fs, stream, tm); \
         if (n_blocks) *n_blocks = tile_blocks(first, count, NB * NM);                        \
         return true;                                                                         \
     }
@@ -636,24 +645,30 @@ hipError_t launch_tile_tables(const GridDesc &g, const DevTables *tab, void *til
 
 hipError_t launch_eval_grid_fused(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
                                   uint32_t count, double e_c, double e_b, bool additive, const guide_metrics &out,
-                                  const FusedSelect &fs, hipStream_t stream, uint32_t *n_blocks) {
+                                  const FusedSelect &fs, hipStream_t stream, uint32_t *n_blocks, LaunchTiming tm) {
     const double re_c = 1.0 / e_c, re_b = 1.0 / e_b;
     const bool done =
-        additive ? dispatch_tile<true>(g, tab, tile_tables, first, count, re_c, re_b, out, &fs, stream, n_blocks)
-                 : dispatch_tile<false>(g, tab, tile_tables, first, count, re_c, re_b, out, &fs, stream, n_blocks);
+        additive ? dispatch_tile<true>(g, tab, tile_tables, first, count, re_c, re_b, out, &fs, stream, n_blocks, tm)
+                 : dispatch_tile<false>(g, tab, tile_tables, first, count, re_c, re_b, out, &fs, stream, n_blocks, tm);
     return done ? hipGetLastError() : hipErrorNotSupported;
 }
 
 hipError_t launch_eval_grid(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
                             uint32_t count, double e_c, double e_b, bool additive, const guide_metrics &out,
-                            hipStream_t stream) {
+                            hipStream_t stream, LaunchTiming tm) {
     const dim3 grid(blocks_for(count)), block(kBlock);
     const double re_c = 1.0 / e_c, re_b = 1.0 / e_b;
-    if (additive ? dispatch_tile<true>(g, tab, tile_tables, first, count, re_c, re_b, out, nullptr, stream, nullptr)
-                 : dispatch_tile<false>(g, tab, tile_tables, first, count, re_c, re_b, out, nullptr, stream, nullptr))
+    if (additive ? dispatch_tile<true>(g, tab, tile_tables, first, count, re_c, re_b, out, nullptr, stream, nullptr, tm)
+                 : dispatch_tile<false>(g, tab, tile_tables, first, count, re_c, re_b, out, nullptr, stream, nullptr, tm))
         return hipGetLastError();
-    if (additive)
+    if (additive && tm.start)
+        hipExtLaunchKernelGGL(eval_grid_kernel<true>, grid, block, 0, stream, tm.start, tm.stop, 0, g, tab, first, count,
+                              re_c, re_b, out);
+    else if (additive)
         hipLaunchKernelGGL(eval_grid_kernel<true>, grid, block, 0, stream, g, tab, first, count, re_c, re_b, out);
+    else if (tm.start)
+        hipExtLaunchKernelGGL(eval_grid_kernel<false>, grid, block, 0, stream, tm.start, tm.stop, 0, g, tab, first, count,
+                              re_c, re_b, out);
     else
         hipLaunchKernelGGL(eval_grid_kernel<false>, grid, block, 0, stream, g, tab, first, count, re_c, re_b, out);
     return hipGetLastError();

@@ -169,23 +169,17 @@ int upload_grid_tables(guide_ctx *ctx, const GridDesc &desc, hipStream_t stream)
 
 bool time_model_ok(uint32_t tm) { return tm == GUIDE_TIME_ROOFLINE || tm == GUIDE_TIME_ADDITIVE; }
 
-// Event pair around one evaluation kernel, when timing is enabled and a pair is left.
-struct KernelTimer {
-    guide_ctx *ctx;
-    hipStream_t stream;
-    bool on;
-    KernelTimer(guide_ctx *c, hipStream_t s) : ctx(c), stream(s), on(false) {
-        if (c->prof_ev.empty()) return;
-        on = c->prof_seen++ % c->prof_every == 0 && 2 * (size_t)c->prof_used + 1 < c->prof_ev.size();
-        if (on) (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_used], stream);
-    }
-    ~KernelTimer() {
-        if (on) {
-            (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_used + 1], stream);
-            ++ctx->prof_used;
-        }
-    }
-};
+// The event pair for the next evaluation kernel, when timing is enabled, this launch's turn has come and
+// a pair is left (empty otherwise); the launch attaches the events to the kernel's dispatch.
+LaunchTiming next_timing(guide_ctx *ctx) {
+    LaunchTiming t;
+    if (ctx->prof_ev.empty()) return t;
+    if (ctx->prof_seen++ % ctx->prof_every != 0 || 2 * (size_t)ctx->prof_used + 1 >= ctx->prof_ev.size()) return t;
+    t.start = ctx->prof_ev[2 * ctx->prof_used];
+    t.stop = ctx->prof_ev[2 * ctx->prof_used + 1];
+    ++ctx->prof_used;
+    return t;
+}
 
 const double *metric_column(const guide_metrics &m, uint32_t id) {
     switch (id) {
@@ -361,9 +355,8 @@ int guide_eval_grid(guide_ctx *ctx, const guide_grid *grid, uint64_t first, uint
                               time_model == GUIDE_TIME_ADDITIVE, *stats, stream);
     } else {
         const double e_c = n_eff ? eff->e_c[0] : 1.0, e_b = n_eff ? eff->e_b[0] : 1.0;
-        KernelTimer timer(ctx, stream);
         e = launch_eval_grid(desc, ctx->dev_tab, ctx->dev_tile, (uint32_t)first, (uint32_t)count, e_c, e_b,
-                             time_model == GUIDE_TIME_ADDITIVE, *out, stream);
+                             time_model == GUIDE_TIME_ADDITIVE, *out, stream, next_timing(ctx));
     }
     if (e != hipSuccess) return hip_fail(ctx, e, "eval_grid launch");
     return GUIDE_OK;
@@ -463,7 +456,7 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
         const double e_c = n_eff ? eff->e_c[0] : 1.0, e_b = n_eff ? eff->e_b[0] : 1.0;
         const bool additive = time_model == GUIDE_TIME_ADDITIVE;
         hipError_t e;
-        KernelTimer timer(ctx, stream);
+        const LaunchTiming timing = next_timing(ctx);
         if (fold) {
             FusedSelect fs;
             memset(&fs, 0, sizeof fs);
@@ -479,10 +472,10 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
                 fs.scratch = ctx->select_scratch;
             }
             e = launch_eval_grid_fused(desc, ctx->dev_tab, ctx->dev_tile, (uint32_t)first, (uint32_t)count, e_c, e_b,
-                                       additive, *out, fs, stream, &n_blocks);
+                                       additive, *out, fs, stream, &n_blocks, timing);
         } else {
             e = launch_eval_grid(desc, ctx->dev_tab, ctx->dev_tile, (uint32_t)first, (uint32_t)count, e_c, e_b, additive,
-                                 *out, stream);
+                                 *out, stream, timing);
         }
         if (e != hipSuccess) return hip_fail(ctx, e, "eval_select launch");
     }

@@ -9,9 +9,14 @@ namespace guide {
 // are recomputed by launch_tile_tables whenever either changes.
 size_t tile_tables_bytes();
 hipError_t launch_tile_tables(const GridDesc &g, const DevTables *tab, void *tile_tables, hipStream_t stream);
+// Events that receive the start and the end of the evaluation kernel itself (attached to its dispatch),
+// or nullptr.
+struct LaunchTiming {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
 hipError_t launch_eval_grid(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
                             uint32_t count, double e_c, double e_b, bool additive, const guide_metrics &out,
-                            hipStream_t stream);
+                            hipStream_t stream, LaunchTiming timing = LaunchTiming());
 hipError_t launch_eval_sweep(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, uint32_t n_eff,
                              bool additive, const guide_stats &out, hipStream_t stream);
 
@@ -37,7 +42,8 @@ bool eval_grid_can_fuse(const GridDesc &g);
 // As launch_eval_grid; *n_blocks receives the number of blocks that wrote partials.
 hipError_t launch_eval_grid_fused(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
                                   uint32_t count, double e_c, double e_b, bool additive, const guide_metrics &out,
-                                  const FusedSelect &fs, hipStream_t stream, uint32_t *n_blocks);
+                                  const FusedSelect &fs, hipStream_t stream, uint32_t *n_blocks,
+                                  LaunchTiming timing = LaunchTiming());
 // Second halves of the folded selections.
 hipError_t launch_topk_merge(void *ws, uint32_t n_blocks, uint32_t k, const guide_select_out &out, hipStream_t stream);
 hipError_t launch_pareto_sampled(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
