@@ -30,11 +30,14 @@
  *     documented step-level definition.
  *
  * Pins (tests/test_oracle_pins.py): parameter counts of public shapes,
- * 2*params*tokens FLOPs, batch-1 decode = weight bytes / BW, the paper's
- * printed kv formula and B_max, feasibility boundary, monotonicity, scaling
- * laws, single-request simulation == analytic latency, brute-force select,
- * numpy's Philox for the counter-based generator.  No function here is
- * "parity unpinned".
+ * 2*params*tokens FLOPs, batch-1 decode = weight bytes / BW, hand-computed
+ * per-operator bytes for the operator terms the MHA shape cannot show (experts
+ * read = min(E, k T), router bytes, the qkv width of grouped-query shapes, whole
+ * KV heads per GPU when p does not divide n_kv, LM-head rows), efficiency factors
+ * that leave the link alone, the paper's printed kv formula and B_max,
+ * feasibility boundary, monotonicity, scaling laws, single-request simulation
+ * == analytic latency, brute-force select, numpy's Philox for the counter-based
+ * generator.  Each function has at least one such pin; none is "parity unpinned".
  *
  * Build: gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC (no FMA
  * contraction, so every expression rounds as written).

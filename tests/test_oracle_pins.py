@@ -62,6 +62,9 @@ def test_linear_flops_are_two_params_tokens(ora, m, p):
     assert lin == 2.0 * ora.params_layer_active(om) * T
     assert r["F"][7] * p == 2.0 * n_lm * m.V * m.d
     assert r["F"][6] == 0.0
+    # the LM head reads its d x V slice and moves n_lm rows (not T) in and out
+    assert r["B"][7] == 2 * m.d * m.V / p + 2 * n_lm * m.d + 2 * n_lm * m.V / p
+    assert r["B"][6] == 8 * T * m.d
 
 
 def test_attention_flops_and_kv_bytes(ora):
@@ -242,6 +245,114 @@ def test_tp_scaling_and_comm_term(ora):
     r = ora.pass_detail(om, bridge.ora_hw(h), 4, 16, T, Q, K, 1.0)
     assert r["t_ar"] == pytest.approx(2 * 3 / 4 * (2 * T * m.d) / 4e11 + 2 * 3 * 3e-6, rel=1e-15)
     assert r["t_pass"] == pytest.approx(m.L * (r["t"][:7].sum() + 2 * r["t_ar"]) + r["t"][7], rel=1e-15)
+
+
+# ------------------------------------- MoE expert loading, router, GQA, head split
+
+@pytest.mark.parametrize("T", [1, 3, 8])
+def test_moe_expert_and_router_bytes(ora, T):
+    """A pass over T tokens reads min(E, k*T) experts' FFN weights (2, 6, 8 of the 8 top-2 experts for
+    T = 1, 3, 8); the router reads its d x E matrix, the T x d input and writes T x E scores."""
+    gold = _gold("op_bytes.txt")
+    m = wl.MOE_8X
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+    r = ora.pass_detail(om, oh, 1, 16, float(T), 100.0 * T, 100.0 * T, float(T))
+    assert r["B"][3] == gold[f"moe_up_bytes_T{T}"]
+    assert r["B"][4] == gold[f"moe_down_bytes_T{T}"]
+    assert r["B"][5] == gold[f"moe_router_bytes_T{T}"]
+    assert r["F"][5] == 2 * T * m.d * m.E
+    if T in (1, 8):
+        assert r["F"][5] == gold[f"moe_router_flops_T{T}"]
+    n_exp = min(m.E, m.k * T)
+    assert r["B"][3] == 2 * n_exp * 2 * m.d * m.d_ff + 2 * T * m.d + 4 * T * m.k * m.d_ff
+    assert r["B"][5] == 2 * m.d * m.E + 2 * T * m.d + 2 * T * m.E
+
+
+def test_moe_bytes_quantised_and_split(ora):
+    """int4 weights on 2 GPUs: expert weights are split, the router is replicated."""
+    gold = _gold("op_bytes.txt")
+    om, oh = bridge.ora_model(wl.MOE_8X), bridge.ora_hw(wl.HW_TINY)
+    r = ora.pass_detail(om, oh, 2, 4, 1.0, 100.0, 100.0, 1.0)
+    assert r["B"][3] == gold["moe_up_bytes_T1_int4_tp2"]
+    assert r["B"][4] == gold["moe_down_bytes_T1_int4_tp2"]
+    assert r["B"][5] == gold["moe_router_bytes_T1_int4_tp2"]
+
+
+@pytest.mark.parametrize("T", [1, 8])
+def test_moe_decode_step_is_bytes_over_bandwidth(ora, T):
+    """Decode step of the MoE shape with batch T on the tiny profile: every op is memory bound (ridge 200 FLOP/B),
+    so step time * BW is every byte the step moves -- 2 (T = 1) or all 8 (T = 8) experts per layer."""
+    gold = _gold("op_bytes.txt")
+    m = wl.MOE_8X
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+    ctx = 256.0
+    r = ora.pass_detail(om, oh, 1, 16, float(T), T * ctx, T * ctx, float(T))
+    assert np.all(r["F"] / wl.HW_TINY.peak_flops <= r["B"] / wl.HW_TINY.hbm_bw)
+    assert r["t_pass"] * wl.HW_TINY.hbm_bw == pytest.approx(gold[f"moe_step_bytes_T{T}_ctx256"], rel=1e-14)
+    # the same through the candidate evaluator: two decode passes at contexts 255 + 1 and 255 + 2
+    e = ora.evaluate(om, oh, ora.knobs(T, 255, 3))
+    r2 = ora.pass_detail(om, oh, 1, 16, float(T), T * 257.0, T * 257.0, float(T))
+    assert e.t_decode == r["t_pass"] + r2["t_pass"]
+
+
+@pytest.mark.parametrize("m", [wl.DENSE_34B, wl.DENSE_70B], ids=lambda m: m.name)
+def test_gqa_qkv_projection(ora, m):
+    """With 8 KV heads of 128 the qkv projection has dq + 2 dkv = 10 240 output columns."""
+    gold = _gold("op_bytes.txt")
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+    for p, wbits, T, tag in ((1, 16, 1, "fp16_tp1_T1"), (4, 8, 512, "int8_tp4_T512"), (8, 4, 64, "int4_tp8_T64")):
+        r = ora.pass_detail(om, oh, p, wbits, float(T), 7.0 * T, 7.0 * T, 1.0)
+        assert r["F"][0] == gold[f"gqa_qkv_flops_{tag}"]
+        assert r["B"][0] == gold[f"gqa_qkv_bytes_{tag}"]
+    # MHA for contrast: 3 d columns
+    r = ora.pass_detail(bridge.ora_model(wl.DENSE_7B), oh, 1, 16, 1.0, 7.0, 7.0, 1.0)
+    assert r["B"][0] == 2 * 4096 * 3 * 4096 + 2 * 4096 + 2 * 3 * 4096
+
+
+def test_kv_heads_per_gpu_when_tp_does_not_divide(ora):
+    """ceil(n_kv / p) whole KV heads per GPU: 8 heads over 3, 5, 6 GPUs leave 3, 2, 2."""
+    gold = _gold("op_bytes.txt")
+    o70, o34 = bridge.ora_model(wl.DENSE_70B), bridge.ora_model(wl.DENSE_34B)
+    oh = bridge.ora_hw(wl.HW_TINY)
+    for p in (1, 2, 3, 4, 5, 6, 8, 16):
+        assert ora.kv_bytes_token(o70, p) == gold[f"kv_token_bytes_70b_tp{p}"]
+    assert ora.kv_bytes_token(o34, 3) == gold["kv_token_bytes_34b_tp3"]
+    assert ora.kv_bytes_token(o34, 6) == gold["kv_token_bytes_34b_tp6"]
+    # the attention op reads that many bytes per cached token and layer: 2 (K, V) * heads * 128 * 2 B
+    for p, heads in ((3, 3), (5, 2), (6, 2), (16, 1)):
+        r = ora.pass_detail(o70, oh, p, 16, 1.0, 1000.0, 1000.0, 1.0)
+        assert r["B"][1] == pytest.approx(4 * 8192 / p + 4 * heads * 128 * 1000, rel=1e-15)
+    # and the memory check sizes a request with it
+    r = ora.memory(o70, oh, ora.knobs(1, 100, 28, p=3, blk=16))
+    assert r["kv_req"] == 128 * gold["kv_token_bytes_70b_tp3"]
+    r = ora.memory(o70, oh, ora.knobs(1, 100, 28, p=6, blk=16))
+    assert r["kv_req"] == 128 * gold["kv_token_bytes_70b_tp6"]
+
+
+def test_efficiency_does_not_scale_the_link(ora):
+    """Efficiency factors scale peak and memory bandwidth only: at p = 4 with a finite link, e_c = e_b = 1/2
+    doubles every op time and leaves the all-reduce time as it was."""
+    m = wl.DENSE_13B
+    om = bridge.ora_model(m)
+    h = wl.Hardware(1e15, 5e12, 192 * wl.GIB, 4e11, 3e-6)
+    oh = bridge.ora_hw(h)
+    T, Q, K = 640.0, 640.0 * 640, 640.0
+    base = ora.pass_detail(om, oh, 4, 16, T, Q, K, 1.0)
+    half = ora.pass_detail(om, oh, 4, 16, T, Q, K, 1.0, 0.5, 0.5)
+    t_ar = 2 * 3 / 4 * (2 * T * m.d) / 4e11 + 2 * 3 * 3e-6
+    assert base["t_ar"] == pytest.approx(t_ar, rel=1e-15) and half["t_ar"] == base["t_ar"]
+    np.testing.assert_allclose(half["t"], 2 * base["t"], rtol=1e-15)
+    assert half["t_pass"] == pytest.approx(m.L * (2 * base["t"][:7].sum() + 2 * t_ar) + 2 * base["t"][7], rel=1e-14)
+    assert half["t_pass"] < 2 * base["t_pass"] * (1 - 1e-3)      # the comm share is visible at this size
+    # only bandwidth scaled: memory-bound ops double, compute-bound ones stay, comm stays
+    bw_half = ora.pass_detail(om, oh, 4, 16, T, Q, K, 1.0, 1.0, 0.5)
+    assert bw_half["t_ar"] == base["t_ar"]
+    assert bw_half["t"][6] == pytest.approx(2 * base["t"][6], rel=1e-15)
+    # through the candidate evaluator as well
+    kn = ora.knobs(8, 512, 64, p=4)
+    e1, e2 = ora.evaluate(om, oh, kn), ora.evaluate(om, oh, kn, 0.5, 0.5)
+    comm_prefill = m.L * 2 * (2 * 3 / 4 * (2 * 8 * 512 * m.d) / 4e11 + 6 * 3e-6)
+    assert e2.t_prefill - comm_prefill == pytest.approx(2 * (e1.t_prefill - comm_prefill), rel=1e-12)
 
 
 # --------------------------------------------------------- uncertainty sweep
