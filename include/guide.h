@@ -294,6 +294,26 @@ int guide_select(guide_ctx *ctx, const guide_select_spec *spec, uint64_t n, cons
                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * guide_select for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  The same selection and the same outputs as guide_select; the
+ * workspace and the Pareto tables live in one static device array inside the
+ * library (about 50 MiB on every GPU the library runs on, held until the
+ * process ends; its address is taken once per device in guide_create).  The
+ * call allocates and frees nothing.  Limits: the selection's workspace
+ * (guide_select_workspace_bytes) must fit the array, which holds a Pareto
+ * selection over GUIDE_STATIC_SELECT_MAX_ROWS rows and a top-k selection of
+ * any size; beyond that GUIDE_E_RANGE is returned and nothing is enqueued.
+ * Every call on one GPU, from any context, uses that GPU's one array: the kernels
+ * of a call rewrite every part of it before reading it, so it needs no clearing
+ * between calls and keeps nothing from the last one, but two calls that overlap
+ * on one GPU (different streams, different contexts) race.
+ */
+#define GUIDE_STATIC_SELECT_MAX_ROWS (1ull << 21)
+int guide_select_static(guide_ctx *ctx, const guide_select_spec *spec, uint64_t n, const guide_select_out *out,
+                        void *stream);
+
+/*
  * Evaluate and select in one call: the same results as guide_eval_grid(out) with
  * one efficiency sample followed by guide_select for each of the n_sel
  * selections on the columns of `out` (rows = the `count` evaluated

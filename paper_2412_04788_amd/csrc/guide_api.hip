@@ -42,6 +42,16 @@ struct guide_ctx {
 };
 static_assert(guide_ctx::kSlotBytes >= sizeof(DevTables), "staging slot too small");
 
+// Device memory of guide_select_static, which may not allocate: the tables of the Pareto kernels
+// (kSelectScratchMax bytes) followed by the selection workspace (kStaticWsBytes, enough for a Pareto
+// selection over GUIDE_STATIC_SELECT_MAX_ROWS rows or any top-k selection).  Every GPU holds its own copy
+// at its own address: host code never uses the array's name as a pointer, only the address that
+// hipGetSymbolAddress returned for the device (static_scratch_of).
+constexpr size_t kStaticWsBytes = (size_t)GUIDE_STATIC_SELECT_MAX_ROWS * 25 + 256;
+static __device__ __align__(256) unsigned char scratch[kSelectScratchMax + kStaticWsBytes];
+constexpr int kMaxDevices = 64;
+static void *g_static_scratch[kMaxDevices];      // per device: address of `scratch` there, set by guide_create
+
 namespace {
 
 int fail(guide_ctx *ctx, int code, const char *fmt, ...) {
@@ -260,6 +270,15 @@ int guide_create(guide_ctx **out, int device) {
         hipStreamSynchronize(nullptr) != hipSuccess) {
         guide_destroy(ctx);
         return GUIDE_E_DEVICE;
+    }
+    // address of this device's copy of the static scratch (the device is current here)
+    if (device < kMaxDevices && !g_static_scratch[device]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            guide_destroy(ctx);
+            return GUIDE_E_DEVICE;
+        }
+        g_static_scratch[device] = p;
     }
     for (int i = 0; i < guide_ctx::kSlots; ++i) {
         if (hipHostMalloc(&ctx->slot[i], guide_ctx::kSlotBytes, hipHostMallocDefault) != hipSuccess ||
@@ -570,10 +589,50 @@ size_t guide_select_workspace_bytes(const guide_select_spec *spec, uint64_t n) {
     return select_workspace_bytes(*spec, n);
 }
 
+// Argument checks shared by guide_select and guide_select_static.
+static int check_select_args(guide_ctx *ctx, const guide_select_spec *spec, uint64_t n, const guide_select_out *out);
+
+int guide_select_static(guide_ctx *ctx, const guide_select_spec *spec, uint64_t n, const guide_select_out *out,
+                        void *stream_) {
+    if (!ctx) return GUIDE_E_ARG;
+    hipStream_t stream = (hipStream_t)stream_;
+    const int rc = check_select_args(ctx, spec, n, out);
+    if (rc) return rc;
+    const size_t need = select_workspace_bytes(*spec, n);
+    if (need > kStaticWsBytes)
+        return fail(ctx, GUIDE_E_RANGE, "selection needs %zu bytes of workspace, the static scratch holds %zu "
+                    "(Pareto: at most %llu rows)", need, kStaticWsBytes, (unsigned long long)GUIDE_STATIC_SELECT_MAX_ROWS);
+    if (ctx->device >= kMaxDevices || !g_static_scratch[ctx->device])
+        return fail(ctx, GUIDE_E_DEVICE, "no static scratch on device %d", ctx->device);
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
+    unsigned char *base = (unsigned char *)g_static_scratch[ctx->device];
+    void *tables = base, *workspace = base + kSelectScratchMax;
+    const hipError_t e = spec->mode == GUIDE_SELECT_TOPK ? launch_select_topk(*spec, n, *out, workspace, tables, stream)
+                                                         : launch_select_pareto(*spec, n, *out, workspace, tables, stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "select launch");
+    return GUIDE_OK;
+}
+
 int guide_select(guide_ctx *ctx, const guide_select_spec *spec, uint64_t n, const guide_select_out *out,
                  void *workspace, size_t workspace_bytes, void *stream_) {
     if (!ctx) return GUIDE_E_ARG;
     hipStream_t stream = (hipStream_t)stream_;
+    const int rc_args = check_select_args(ctx, spec, n, out);
+    if (rc_args) return rc_args;
+    const size_t need = select_workspace_bytes(*spec, n);
+    if (need && (!workspace || workspace_bytes < need))
+        return fail(ctx, GUIDE_E_NOMEM, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
+    const hipError_t e = spec->mode == GUIDE_SELECT_TOPK
+                             ? launch_select_topk(*spec, n, *out, workspace, ctx->select_scratch, stream)
+                             : launch_select_pareto(*spec, n, *out, workspace, ctx->select_scratch, stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "select launch");
+    return GUIDE_OK;
+}
+
+static int check_select_args(guide_ctx *ctx, const guide_select_spec *spec, uint64_t n, const guide_select_out *out) {
     if (!spec || !out) return fail(ctx, GUIDE_E_ARG, "spec or out is NULL");
     if (spec->mode != GUIDE_SELECT_TOPK && spec->mode != GUIDE_SELECT_PARETO)
         return fail(ctx, GUIDE_E_ARG, "unknown select mode %u", spec->mode);
@@ -593,15 +652,6 @@ int guide_select(guide_ctx *ctx, const guide_select_spec *spec, uint64_t n, cons
         if (n && !spec->objective_y) return fail(ctx, GUIDE_E_ARG, "objective_y is NULL");
         if (out->capacity && !out->idx) return fail(ctx, GUIDE_E_ARG, "out.idx is NULL");
     }
-    const size_t need = select_workspace_bytes(*spec, n);
-    if (need && (!workspace || workspace_bytes < need))
-        return fail(ctx, GUIDE_E_NOMEM, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
-    DeviceGuard guard(ctx->device);
-    if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
-    const hipError_t e = spec->mode == GUIDE_SELECT_TOPK
-                             ? launch_select_topk(*spec, n, *out, workspace, ctx->select_scratch, stream)
-                             : launch_select_pareto(*spec, n, *out, workspace, ctx->select_scratch, stream);
-    if (e != hipSuccess) return hip_fail(ctx, e, "select launch");
     return GUIDE_OK;
 }
 

@@ -59,6 +59,7 @@ hipError_t launch_eval_extras(const GridDesc &g, const DevTables *tab, uint32_t 
                               bool additive, const guide_extras &out, hipStream_t stream);
 
 size_t select_scratch_bytes();
+constexpr size_t kSelectScratchMax = 128 * 1024;   // upper bound of select_scratch_bytes(), for static storage
 hipError_t launch_select_topk(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
                               void *scratch, hipStream_t stream);
 hipError_t launch_select_pareto(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,

@@ -935,6 +935,7 @@ void launch_top1_merge(int K, void *ws, uint32_t n_blocks, uint32_t k, const gui
 
 }  // namespace
 
+static_assert(sizeof(SelectScratch) <= kSelectScratchMax, "kSelectScratchMax is too small");
 size_t select_scratch_bytes() { return sizeof(SelectScratch); }
 
 

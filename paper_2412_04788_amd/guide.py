@@ -22,10 +22,12 @@ SIM_OK, SIM_INFEASIBLE, SIM_BAD_INPUT, SIM_INTERNAL = 0, 1, 2, 3
 SCHED_SPLIT_FUSE, SCHED_PREFILL_FIRST = 0, 1
 NO_INDEX = 2 ** 64 - 1
 MAX_CONSTRAINTS = 4
+STATIC_SELECT_MAX_ROWS = 1 << 21
 
 EXPORTS = ("guide_create", "guide_destroy", "guide_last_error", "guide_set_models", "guide_set_hardware",
            "guide_eval_grid", "guide_eval_extras", "guide_eval_sampled", "guide_simulate_workspace_bytes", "guide_simulate",
-           "guide_select_workspace_bytes", "guide_select", "guide_eval_select_workspace_bytes", "guide_eval_select",
+           "guide_select_workspace_bytes", "guide_select", "guide_select_static",
+           "guide_eval_select_workspace_bytes", "guide_eval_select",
            "guide_profile_enable", "guide_profile_read")
 
 
@@ -159,6 +161,8 @@ def load() -> C.CDLL:
         lib.guide_select_workspace_bytes.restype = C.c_size_t
         lib.guide_select.argtypes = [C.c_void_p, C.POINTER(CSelectSpec), C.c_uint64, C.POINTER(CSelectOut),
                                      C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.guide_select_static.argtypes = [C.c_void_p, C.POINTER(CSelectSpec), C.c_uint64, C.POINTER(CSelectOut),
+                                            C.c_void_p]
         lib.guide_eval_select_workspace_bytes.argtypes = [C.c_void_p, C.c_uint32, C.c_uint64]
         lib.guide_eval_select_workspace_bytes.restype = C.c_size_t
         lib.guide_eval_select.argtypes = [C.c_void_p, C.POINTER(CGrid), C.c_uint64, C.c_uint64, C.POINTER(CEff),
@@ -430,3 +434,11 @@ class Context:
         ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
         self._invoke(self._lib.guide_select, self._h, _Ref(s), n, _Ref(o), _dev_ptr(workspace), ws_bytes,
                      _stream_ptr(stream))
+
+    def select_static(self, mode: int, n: int, objective, out_idx, out_val, out_count, objective_y=None,
+                      feasible=None, constraints=(), group=None, n_groups: int = 1, k: int = 1, capacity: int = 0,
+                      stream=None):
+        """guide_select_static: guide_select on the library's static device scratch (no workspace, no allocation)."""
+        s = self._select_spec(mode, objective, objective_y, feasible, list(constraints), group, n_groups, k)
+        o = CSelectOut(_dev_ptr(out_idx), _dev_ptr(out_val), _dev_ptr(out_count), capacity)
+        self._invoke(self._lib.guide_select_static, self._h, _Ref(s), n, _Ref(o), _stream_ptr(stream))
