@@ -70,3 +70,63 @@ def to_np(t, dtype=None):
     if dtype is not None:
         a = a.view(dtype)
     return a
+
+
+# --------------------------------------------- the oracle on all host cores
+
+def host_workers() -> int:
+    """Threads for oracle sweeps: the oracle's C entry points hold no global state and ctypes releases the
+    interpreter lock during a call, so independent ranges run side by side (16 = a GPU machine's CPU share)."""
+    import os
+    return max(1, min(16, os.cpu_count() or 1))
+
+
+def _chunks(total, chunk):
+    return [(a, min(chunk, total - a)) for a in range(0, total, chunk)]
+
+
+def ora_eval_grid_all(og: go.Grid, first=0, count=None, chunk=4096, **kw):
+    """go.eval_grid over [first, first + count), ranges spread over the host cores."""
+    from concurrent.futures import ThreadPoolExecutor
+    count = og.size - first if count is None else count
+    parts = _chunks(count, chunk)
+    with ThreadPoolExecutor(host_workers()) as ex:
+        res = list(ex.map(lambda p: go.eval_grid(og, first + p[0], p[1], **kw), parts))
+    return {k: np.concatenate([r[k] for r in res]) for k in res[0]}
+
+
+def ora_eval_sweep_grid_rows(og: go.Grid, e_c, e_b, starts, length, **kw):
+    """go.eval_sweep_grid on the ranges [s, s + length) for s in starts; columns concatenated in that order."""
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(host_workers()) as ex:
+        res = list(ex.map(lambda s: go.eval_sweep_grid(og, e_c, e_b, int(s), length, **kw), starts))
+    return {k: np.concatenate([r[k] for r in res]) for k in res[0]}
+
+
+def ora_simulate_grid_all(og: go.Grid, cfg_idx, rate, trace, chunk=32, **kw):
+    from concurrent.futures import ThreadPoolExecutor
+    parts = _chunks(len(cfg_idx), chunk)
+    with ThreadPoolExecutor(host_workers()) as ex:
+        res = list(ex.map(lambda p: go.simulate_grid(og, cfg_idx[p[0]:p[0] + p[1]], rate[p[0]:p[0] + p[1]],
+                                                     trace.arrival_unit, trace.n_in, trace.n_out, **kw), parts))
+    return {k: np.concatenate([r[k] for r in res]) for k in res[0]}
+
+
+def ora_eval_sampled_all(osp: go.Space, seed, first, count, edges, ttft_cap, chunk=1 << 14, columns=True):
+    """go.eval_sampled over a long range: per-range results merged in ascending order (sums; a bucket's winner is
+    the first range's unless a later one is strictly cheaper, which keeps the lowest index on ties)."""
+    from concurrent.futures import ThreadPoolExecutor
+    parts = _chunks(count, chunk)
+    with ThreadPoolExecutor(host_workers()) as ex:
+        res = list(ex.map(lambda p: go.eval_sampled(osp, seed, first + p[0], p[1], edges, ttft_cap, columns=columns),
+                          parts))
+    out = dict(feasible_count=sum(r["feasible_count"] for r in res), hist=sum(r["hist"] for r in res),
+               win_val=res[0]["win_val"].copy(), win_idx=res[0]["win_idx"].copy())
+    for r in res[1:]:
+        better = r["win_val"] < out["win_val"]
+        out["win_val"][better] = r["win_val"][better]
+        out["win_idx"][better] = r["win_idx"][better]
+    if columns:
+        for k in ("t_prefill", "t_batch", "cost", "b_max", "feasible", "bucket"):
+            out[k] = np.concatenate([r[k] for r in res])
+    return out

@@ -1,0 +1,342 @@
+"""Every-row parity at the benchmarked sizes: the whole 1.9M-row grid, all 65 536 simulated configurations
+under both schedulers, 2^22 candidates of the sampled space and an every-row uncertainty sweep, each against
+the CPU oracle running on all host cores; and the selections compared with the oracle's selection on the
+ORACLE's columns, where a difference is accepted only when the deciding comparison lies within 1e-9 relative
+and is then listed as a near-tie."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from paper_2412_04788_amd import workloads as wl
+from tests import bridge
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-9
+FLOAT_COLS = ("t_prefill", "t_decode", "t_batch", "decode_tok_s", "cost")
+REPORT = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+def _report(name, payload):
+    """Near-tie lists and counts, kept beside the run's other outputs when that folder exists."""
+    print(name, json.dumps(payload))
+    if os.path.isdir(REPORT):
+        with open(os.path.join(REPORT, f"parity_{name}.json"), "w") as fh:
+            json.dump(payload, fh, indent=1)
+
+
+def _close(a, b):
+    return abs(a - b) <= TOL * max(abs(a), abs(b))
+
+
+def topk_near_ties(got_idx, exp_idx, obj, ok, cons):
+    """got_idx / exp_idx: the GPU's and the oracle's top-k rows; obj, ok, cons: the ORACLE's objective column, its
+    pass mask and its (column, cap) constraints.  Returns the list of near-ties that explain every difference,
+    or raises: a row may differ only if its objective is within tolerance of the k-th value, or a constraint of
+    it sits within tolerance of its cap."""
+    ties = []
+    if list(got_idx) == list(exp_idx):
+        return ties
+    kth = max(obj[int(i)] for i in exp_idx if int(i) != bridge.go.NO_INDEX)
+    for pos, (gi, ei) in enumerate(zip(got_idx, exp_idx)):
+        if gi == ei:
+            continue
+        for row in (int(gi), int(ei)):
+            if row == bridge.go.NO_INDEX:
+                continue
+            at_cap = [name for name, (col, cap) in cons.items() if _close(col[row], cap)]
+            tied = _close(obj[row], kth) or any(_close(obj[row], obj[int(j)]) for j in exp_idx
+                                               if int(j) not in (row, bridge.go.NO_INDEX))
+            assert at_cap or tied, ("selection differs beyond a near-tie", pos, int(gi), int(ei), obj[row], kth)
+            ties.append(dict(position=pos, row=row, objective=float(obj[row]), constraint_at_cap=at_cap))
+    return ties
+
+
+def pareto_near_ties(got, exp, x, y, ok):
+    """Fronts as row lists; x, y, ok: the ORACLE's columns and pass mask.  A row in one front only must have a
+    front member whose x or y is within tolerance of its own (the dominance test was decided by a near-equal
+    coordinate)."""
+    ties = []
+    gs, es = set(int(i) for i in got), set(int(i) for i in exp)
+    union = np.array(sorted(gs | es), dtype=np.int64)
+    for row in sorted(gs ^ es):
+        others = union[union != row]
+        near = (np.abs(x[others] - x[row]) <= TOL * np.abs(x[row])) | (np.abs(y[others] - y[row]) <= TOL * np.abs(y[row]))
+        assert ok[row] and near.any(), ("front differs beyond a near-tie", row, x[row], y[row])
+        ties.append(dict(row=row, x=float(x[row]), y=float(y[row]), in_gpu_front=row in gs))
+    return ties
+
+
+# ------------------------------------------------------------------ full grid
+
+def test_full_grid_every_row_and_selections_on_oracle_columns(ora, torch_cuda):
+    torch = torch_cuda
+    from paper_2412_04788_amd import guide
+    g = wl.grid_full()
+    n = g.size
+    ctx = bridge.gpu_context(g)
+    out = bridge.metric_buffers(n)
+    ti = torch.full((3,), -7, dtype=torch.int64, device="cuda")
+    tv = torch.full((3,), -7.0, dtype=torch.float64, device="cuda")
+    tc = torch.full((1,), -7, dtype=torch.int64, device="cuda")
+    pi = torch.full((n,), -7, dtype=torch.int64, device="cuda")
+    pc = torch.full((1,), -7, dtype=torch.int64, device="cuda")
+    sels = [ctx.column_select(guide.SELECT_TOPK, "cost", ti, tv, tc, constraints=[("t_prefill", wl.TTFT_CAP_S)], k=3),
+            ctx.column_select(guide.SELECT_PARETO, "t_prefill", pi, None, pc, objective_y="cost", capacity=n)]
+    ws = torch.empty(ctx.eval_select_workspace_bytes(sels, n), dtype=torch.uint8, device="cuda")
+    ctx.eval_select(bridge.gpu_grid(g), 0, n, out, sels, ws)          # the benchmarked call
+    torch.cuda.synchronize()
+    exp = bridge.ora_eval_grid_all(bridge.ora_grid(g))                  # every row, all host cores
+    worst = {}
+    for k in FLOAT_COLS:
+        e = bridge.rel_err(bridge.to_np(out[k]), exp[k])
+        worst[k] = float(e.max())
+        assert e.max() <= TOL, (k, int(e.argmax()), float(e.max()))
+    np.testing.assert_array_equal(bridge.to_np(out["b_max"], np.uint32), exp["b_max"])
+    np.testing.assert_array_equal(bridge.to_np(out["feasible"]), exp["feasible"])
+    # selections: the oracle selects on ITS columns
+    ok = (exp["feasible"] == 1) & (exp["t_prefill"] <= wl.TTFT_CAP_S)
+    ei, ev, ec = ora.select_topk(exp["cost"], exp["feasible"], [(exp["t_prefill"], wl.TTFT_CAP_S)], k=3)
+    got_idx = bridge.to_np(ti, np.uint64)
+    ties_topk = topk_near_ties(got_idx, ei[0], exp["cost"], ok, {"t_prefill": (exp["t_prefill"], wl.TTFT_CAP_S)})
+    at_cap = int((np.abs(exp["t_prefill"] - wl.TTFT_CAP_S) <= TOL * wl.TTFT_CAP_S).sum())
+    assert abs(int(bridge.to_np(tc, np.uint64)[0]) - int(ec[0])) <= at_cap
+    if not ties_topk:
+        assert bridge.rel_err(bridge.to_np(tv), ev[0]).max() <= TOL
+    front = ora.pareto_sweep(exp["t_prefill"], exp["cost"], exp["feasible"])
+    m = int(bridge.to_np(pc, np.uint64)[0])
+    got_front = bridge.to_np(pi, np.uint64)[:m]
+    ties_front = pareto_near_ties(got_front, front, exp["t_prefill"], exp["cost"], exp["feasible"] == 1)
+    if not ties_front:
+        np.testing.assert_array_equal(got_front, front)
+    _report("full_grid", dict(rows_compared=int(n), max_rel_err=worst, top3_gpu=[int(i) for i in got_idx],
+                              top3_oracle=[int(i) for i in ei[0]], front_size_gpu=m, front_size_oracle=int(len(front)),
+                              near_ties_topk=ties_topk, near_ties_front=ties_front,
+                              rows_with_ttft_at_cap=at_cap))
+
+
+def test_tiny_grid_selections_on_oracle_columns(ora, torch_cuda):
+    """The 1080-row grid: argmin of batch latency under the 200 ms TTFT cap and the (TTFT, cost) front, both
+    against the oracle's selection on its own columns."""
+    torch = torch_cuda
+    from paper_2412_04788_amd import guide
+    g = wl.grid_tiny()
+    n = g.size
+    ctx = bridge.gpu_context(g)
+    out = bridge.metric_buffers(n)
+    ti = torch.full((1,), -7, dtype=torch.int64, device="cuda")
+    tv = torch.full((1,), -7.0, dtype=torch.float64, device="cuda")
+    tc = torch.full((1,), -7, dtype=torch.int64, device="cuda")
+    pi = torch.full((n,), -7, dtype=torch.int64, device="cuda")
+    pc = torch.full((1,), -7, dtype=torch.int64, device="cuda")
+    sels = [ctx.column_select(guide.SELECT_TOPK, "t_batch", ti, tv, tc, constraints=[("t_prefill", wl.TTFT_CAP_S)], k=1),
+            ctx.column_select(guide.SELECT_PARETO, "t_prefill", pi, None, pc, objective_y="cost", capacity=n)]
+    ws = torch.empty(ctx.eval_select_workspace_bytes(sels, n), dtype=torch.uint8, device="cuda")
+    ctx.eval_select(bridge.gpu_grid(g), 0, n, out, sels, ws)
+    torch.cuda.synchronize()
+    exp = ora.eval_grid(bridge.ora_grid(g))
+    ok = (exp["feasible"] == 1) & (exp["t_prefill"] <= wl.TTFT_CAP_S)
+    ei, ev, ec = ora.select_topk(exp["t_batch"], exp["feasible"], [(exp["t_prefill"], wl.TTFT_CAP_S)], k=1)
+    ties = topk_near_ties(bridge.to_np(ti, np.uint64), ei[0], exp["t_batch"], ok,
+                          {"t_prefill": (exp["t_prefill"], wl.TTFT_CAP_S)})
+    front = ora.pareto_brute(exp["t_prefill"], exp["cost"], exp["feasible"])
+    m = int(bridge.to_np(pc, np.uint64)[0])
+    ties_f = pareto_near_ties(bridge.to_np(pi, np.uint64)[:m], front, exp["t_prefill"], exp["cost"], exp["feasible"] == 1)
+    assert not ties and not ties_f                       # none with these inputs
+    assert int(bridge.to_np(ti, np.uint64)[0]) == int(ei[0, 0]) and int(bridge.to_np(tc, np.uint64)[0]) == int(ec[0])
+    np.testing.assert_array_equal(bridge.to_np(pi, np.uint64)[:m], front)
+
+
+# ------------------------------------------------ feasibility on the boundary
+
+@pytest.mark.parametrize("model", [wl.DENSE_34B, wl.MOE_8X, wl.DENSE_13B], ids=lambda m: m.name)
+def test_feasibility_exactly_at_the_capacity_boundary(ora, torch_cuda, model):
+    """Capacity = weights per GPU + b * KV per request: feasible with b_max = b; one byte less: infeasible with
+    b_max = b - 1; for tp 1, 2, 8 x 16-, 8-, 4-bit weights x both block sizes.  Capacities are built from the
+    oracle's (pinned) weight and KV byte counts; the kernels must land on the same side."""
+    torch = torch_cuda
+    b, s_in, s_out = 37, 1000, 200
+    om = bridge.ora_model(model)
+    hws, expect = [], []
+    cases = [(p, wb, blk) for p in (1, 2, 8) for wb in (16, 8, 4) for blk in (16, 32)]
+    for p, wb, blk in cases:
+        tok = -(-(s_in + s_out) // blk) * blk
+        cap = ora.weight_bytes_gpu(om, p, wb) + b * tok * ora.kv_bytes_token(om, p)
+        assert cap < 2 ** 53 and cap == int(cap)
+        hws += [wl.Hardware(1e15, 5e12, cap, 4e11), wl.Hardware(1e15, 5e12, cap - 1.0, 4e11)]
+        expect += [(1, b), (0, b - 1)]
+    g = wl.make_grid([model], hws, wl.Axis.table([b]), wl.Axis.table([s_in]), wl.Axis.table([s_out]),
+                     wl.Axis.table([1, 2, 8]), wl.Axis.table([16, 8, 4]), wl.Axis.table([16, 32]),
+                     wl.Axis.table([2048, 8192]))
+    ctx = bridge.gpu_context(g)
+    out = bridge.metric_buffers(g.size)
+    ctx.eval_grid(bridge.gpu_grid(g), 0, g.size, out=out)
+    torch.cuda.synchronize()
+    fe, bm = bridge.to_np(out["feasible"]), bridge.to_np(out["b_max"], np.uint32)
+    exp = ora.eval_grid(bridge.ora_grid(g))
+    np.testing.assert_array_equal(fe, exp["feasible"])
+    np.testing.assert_array_equal(bm, exp["b_max"])
+    hit = 0
+    for ci, (p, wb, blk) in enumerate(cases):
+        for side in (0, 1):
+            h = 2 * ci + side
+            for imbt in (0, 1):
+                idx = g.flat((0, h, 0, 0, 0, (1, 2, 8).index(p), (16, 8, 4).index(wb), (16, 32).index(blk), imbt))
+                assert (fe[idx], bm[idx]) == expect[h], (p, wb, blk, side, fe[idx], bm[idx])
+                hit += 1
+    assert hit == 2 * 2 * len(cases)
+    # the one-index-per-lane kernel (no tile shape for five token budgets) takes the same decisions
+    g5 = wl.make_grid([model], hws, wl.Axis.table([b]), wl.Axis.table([s_in]), wl.Axis.table([s_out]),
+                      wl.Axis.table([1, 2, 8]), wl.Axis.table([16, 8, 4]), wl.Axis.table([16, 32]),
+                      wl.Axis.table([512, 1024, 2048, 4096, 8192]))
+    ctx5 = bridge.gpu_context(g5)
+    out5 = bridge.metric_buffers(g5.size)
+    ctx5.eval_grid(bridge.gpu_grid(g5), 0, g5.size, out=out5)
+    torch.cuda.synchronize()
+    exp5 = ora.eval_grid(bridge.ora_grid(g5))
+    np.testing.assert_array_equal(bridge.to_np(out5["feasible"]), exp5["feasible"])
+    np.testing.assert_array_equal(bridge.to_np(out5["b_max"], np.uint32), exp5["b_max"])
+    assert 0 < exp5["feasible"].sum() < g5.size
+
+
+# ----------------------------------------------------------------- simulation
+
+@pytest.mark.parametrize("scheduler", [0, 1], ids=["split-fuse", "prefill-first"])
+def test_simulation_every_configuration(ora, torch_cuda, scheduler):
+    """All 65 536 configurations x 1024 requests of the benchmarked launch against the oracle."""
+    torch = torch_cuda
+    from tests.test_gpu_simulate import FLOATS, _run
+    g = wl.grid_full()
+    ctx = bridge.gpu_context(g)
+    tr = wl.request_trace()
+    idx, rate = wl.sim_configs(g, 65536)
+    got = _run(torch, ctx, g, idx, rate, tr, scheduler=scheduler)
+    exp = bridge.ora_simulate_grid_all(bridge.ora_grid(g), idx, rate, tr, scheduler=scheduler)
+    np.testing.assert_array_equal(got["status"], exp["status"])
+    # Integer outputs are exact unless an admission test `arrival <= now` was decided within rounding: such a
+    # configuration may take a different but equally valid schedule; it must then be rare and is listed.
+    same = (got["n_steps"] == exp["n_steps"]) & (got["n_request_steps"] == exp["n_request_steps"])
+    diverged = np.flatnonzero(~same)
+    worst = {}
+    for k in FLOATS:
+        e = bridge.rel_err(got[k][same], exp[k][same])
+        worst[k] = float(e.max())
+        assert e.max() <= TOL, (k, int(e.argmax()), float(e.max()))
+    _report(f"simulate_{scheduler}", dict(configs_compared=int(len(idx)), feasible=int((exp["status"] == 0).sum()),
+                                          max_rel_err=worst, diverged_schedules=[int(i) for i in diverged],
+                                          request_steps=int(exp["n_request_steps"].sum())))
+    assert len(diverged) == 0, diverged[:10]
+
+
+# -------------------------------------------------------------- sampled space
+
+def test_sampled_space_four_million_candidates(ora, torch_cuda):
+    """2^22 candidates: every per-candidate column and the reduced outputs against the oracle."""
+    torch = torch_cuda
+    from tests.test_gpu_sampled import _run
+    ctx = bridge.gpu_context(wl.grid_tiny())
+    n = 1 << 22
+    got = _run(torch, ctx, 0, n, columns=True)
+    exp = bridge.ora_eval_sampled_all(bridge.ora_space(wl.sample_space()), wl.SEED, 0, n, wl.BUCKET_EDGES, wl.TTFT_CAP_S)
+    for k in ("t_prefill", "t_batch", "cost"):
+        e = bridge.rel_err(got[k], exp[k])
+        assert e.max() <= TOL, (k, int(e.argmax()), float(e.max()))
+    np.testing.assert_array_equal(got["b_max"], exp["b_max"])
+    np.testing.assert_array_equal(got["feasible"], exp["feasible"])
+    np.testing.assert_array_equal(got["bucket"], exp["bucket"])
+    assert got["feasible_count"] == exp["feasible_count"]
+    # histogram: exact, except candidates whose latency is within tolerance of a bin edge (bins come from the
+    # top bits of the fp64 pattern, so "near an edge" = the pattern changes bin under a 2e-9 relative nudge)
+    fe = exp["feasible"] == 1
+    tb = exp["t_batch"][fe]
+
+    def bins(t):
+        return np.clip((t.view(np.uint64) >> np.uint64(49)).astype(np.int64) - ((1023 - 12) << 3), 0, 255)
+
+    assert np.array_equal(np.bincount(bins(tb), minlength=256), exp["hist"].astype(np.int64))   # helper = oracle's bins
+    near_edge = int((bins(tb * (1 - 2 * TOL)) != bins(tb * (1 + 2 * TOL))).sum())
+    diff = int(np.abs(got["hist"].astype(np.int64) - exp["hist"].astype(np.int64)).sum())
+    assert diff <= 2 * near_edge, (diff, near_edge)
+    near_cap = fe & (np.abs(exp["t_prefill"] - wl.TTFT_CAP_S) <= 2 * TOL * wl.TTFT_CAP_S)
+    ties = []
+    for b in range(wl.N_BUCKETS):
+        if got["win_idx"][b] == exp["win_idx"][b]:
+            if exp["win_idx"][b] != ora.NO_INDEX:
+                assert bridge.rel_err(got["win_val"][b:b + 1], exp["win_val"][b:b + 1])[0] <= TOL
+            continue
+        assert near_cap[exp["bucket"] == b].any() or _close(got["win_val"][b], exp["win_val"][b]), b
+        ties.append(dict(bucket=b, gpu=int(got["win_idx"][b]), oracle=int(exp["win_idx"][b])))
+    _report("sampled", dict(candidates=n, feasible=int(exp["feasible_count"]), histogram_difference=diff,
+                            candidates_near_a_bin_edge=near_edge, near_tie_winners=ties))
+
+
+# ---------------------------------------------------------- uncertainty sweep
+
+def test_sweep_every_row_of_a_sub_grid_with_selections(ora, torch_cuda):
+    """34 560-row sub-grid of the full factorial (2 models x 2 profiles, every tp / precision / block / budget
+    value): all seven sweep columns of every row against the oracle's 64 evaluations per row; then the (p90 TTFT,
+    cost) front and the argmin of cost under p90-TTFT caps against the oracle's selection on its own columns."""
+    torch = torch_cuda
+    from paper_2412_04788_amd import guide
+    from tests.test_gpu_select import STAT_COLS, _pareto, _topk
+    full = wl.grid_full()
+    g = wl.make_grid([wl.DENSE_7B, wl.MOE_8X], [full.hws[0], full.hws[3]],
+                     wl.Axis.table([1, 4, 16, 64, 256, 1024]), wl.Axis.table([64, 512, 2048, 8192, 32768]),
+                     wl.Axis.table([64, 256, 1024, 8192]), wl.Axis.geom2(1, 4), wl.Axis.table([16, 8, 4]),
+                     wl.Axis.table([16, 32]), wl.Axis.table([2048, 4096, 8192]))
+    n = g.size
+    assert n == 34560
+    e_c, e_b = wl.efficiency_pairs()
+    ctx = bridge.gpu_context(g)
+    st = bridge.metric_buffers(n, names=STAT_COLS + ("b_max", "feasible"))
+    ctx.eval_grid(bridge.gpu_grid(g), 0, n, stats=st, e_c=e_c, e_b=e_b)
+    torch.cuda.synchronize()
+    exp = bridge.ora_eval_sweep_grid_rows(bridge.ora_grid(g), e_c, e_b, range(0, n, 256), 256)
+    worst = {}
+    for k in STAT_COLS:
+        e = bridge.rel_err(bridge.to_np(st[k]), exp[k])
+        worst[k] = float(e.max())
+        assert e.max() <= TOL, (k, int(e.argmax()), float(e.max()))
+    np.testing.assert_array_equal(bridge.to_np(st["b_max"], np.uint32), exp["b_max"])
+    np.testing.assert_array_equal(bridge.to_np(st["feasible"]), exp["feasible"])
+    got_front, m = _pareto(torch, ctx, st["ttft_p90"], st["cost"], feasible=st["feasible"])
+    front = ora.pareto_sweep(exp["ttft_p90"], exp["cost"], exp["feasible"])
+    ties = dict(front=pareto_near_ties(got_front, front, exp["ttft_p90"], exp["cost"], exp["feasible"] == 1))
+    if not ties["front"]:
+        np.testing.assert_array_equal(got_front, front)
+    for cap in wl.SLO_CAPS_S:
+        gi, gv, gc = _topk(torch, ctx, st["cost"], 1, st["feasible"], [(st["ttft_p90"], cap)])
+        ei, ev, ec = ora.select_topk(exp["cost"], exp["feasible"], [(exp["ttft_p90"], cap)], k=1)
+        ok = (exp["feasible"] == 1) & (exp["ttft_p90"] <= cap)
+        ties[f"argmin_cap_{cap}"] = topk_near_ties(gi[0], ei[0], exp["cost"], ok, {"ttft_p90": (exp["ttft_p90"], cap)})
+    _report("sweep", dict(rows_compared=n, samples=64, max_rel_err=worst, near_ties=ties))
+
+
+def test_full_grid_sweep_blocks(ora, torch_cuda):
+    """The 1.9M-row sweep launch (the benchmarked shape): 64 blocks of 256 rows spread over the grid against
+    the oracle (16 384 rows x 64 evaluations)."""
+    torch = torch_cuda
+    from tests.test_gpu_select import STAT_COLS
+    g = wl.grid_full()
+    n = g.size
+    e_c, e_b = wl.efficiency_pairs()
+    ctx = bridge.gpu_context(g)
+    st = bridge.metric_buffers(n, names=STAT_COLS + ("b_max", "feasible"))
+    ctx.eval_grid(bridge.gpu_grid(g), 0, n, stats=st, e_c=e_c, e_b=e_b)
+    torch.cuda.synchronize()
+    starts = np.linspace(0, n - 256, 64).astype(np.int64)
+    exp = bridge.ora_eval_sweep_grid_rows(bridge.ora_grid(g), e_c, e_b, starts, 256)
+    rows = (starts[:, None] + np.arange(256)[None, :]).reshape(-1)
+    for k in STAT_COLS:
+        e = bridge.rel_err(bridge.to_np(st[k])[rows], exp[k])
+        assert e.max() <= TOL, (k, int(rows[e.argmax()]), float(e.max()))
+    np.testing.assert_array_equal(bridge.to_np(st["b_max"], np.uint32)[rows], exp["b_max"])
+    np.testing.assert_array_equal(bridge.to_np(st["feasible"])[rows], exp["feasible"])

@@ -102,8 +102,9 @@ def test_other_seed_edges_and_cap(ora, torch_cuda):
     np.testing.assert_array_equal(got["hist"], exp["hist"])
 
 
-def test_million_candidates_reduced_outputs(ora, torch_cuda):
-    """2^20 candidates: the whole reduced output against the oracle (about a minute of CPU)."""
+def test_quarter_million_candidates_reduced_outputs(ora, torch_cuda):
+    """2^18 candidates: the whole reduced output against the oracle on one core (2^22 candidates on all
+    cores: test_gpu_full_parity.py)."""
     torch = torch_cuda
     ctx = bridge.gpu_context(wl.grid_tiny())
     n = 1 << 18
