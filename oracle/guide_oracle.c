@@ -415,12 +415,65 @@ enum { ORA_SIM_OK = 0, ORA_SIM_INFEASIBLE = 1 };
  * split).  Prefill-first: while admitted prompts wait, a step runs whole prompts only (vLLM-style dynamic
  * batching): as many, in admission order, as fit the token budget -- the first always -- and decoders pause. */
 enum { ORA_SCHED_SPLIT_FUSE = 0, ORA_SCHED_PREFILL_FIRST = 1 };
+/* OR-ed into the scheduler: runs of decode-only steps (no prompt waiting, nobody joining or leaving) are advanced
+ * by the closed form ora_decode_run_time() instead of step by step. */
+enum { ORA_SIM_CLOSED_FORM_RUNS = 256 };
 
 typedef struct {
     double ttft_p50, ttft_p99, mean_tpot, tokens_s;
     uint32_t status;
     uint64_t n_steps, n_request_steps;
+    double min_admit_margin;   /* diagnostic: least |arrival - time| / time over all admission tests "arrived by now?" */
 } ora_sim_out;
+
+/* arithmetic series: sum of C0 + j T over j = 0 .. r-1 */
+static double ctx_series(double C0, double T, double r) { return r * C0 + T * (r * (r - 1.0) / 2.0); }
+
+/*
+ * Time of r consecutive decode-only steps with T decoders whose total context is C0 before the first step and
+ * grows by T per step (step j runs the pass T, Q = K = C0 + j T, n_lm = T).  Only the attention task depends on
+ * the context: its compute time alpha C and its read time beta C + gamma are both linear in C, so the steps
+ * split at one context into read-bound ones (C <= gamma / (alpha - beta)) and compute-bound ones, and each
+ * part is an arithmetic series.  Everything else of the pass is the same in every step.
+ * The step-by-step sum of ora_pass() over the same steps is the definition this must reproduce.
+ */
+double ora_decode_run_time(const ora_model *m, const ora_hw *hw, uint64_t p_, uint64_t wbits, int time_model,
+                           double T, double C0, double r) {
+    double t[ORA_N_OPS], t_ar;
+    if (r <= 0.0) return 0.0;
+    ora_pass(m, hw, 1.0, 1.0, p_, wbits, time_model, T, C0, C0, T, 0, 0, t, &t_ar);
+    double rest = (double)m->L * (t[0] + t[2] + t[3] + t[4] + t[5] + t[6] + 2.0 * t_ar) + t[7];
+    double p = (double)p_, dh = (double)(m->d / m->n_h), dq = m->n_h * dh;
+    double gkv = (double)((m->n_kv + p_ - 1) / p_) * dh;
+    double alpha = 4.0 * dh * (double)m->n_h / p / hw->peak;        /* attention compute seconds per unit of context */
+    double beta = 2.0 * KV_BYTES * gkv / hw->bw;                    /* K and V read seconds per unit of context */
+    double gamma = 2.0 * ACT_BYTES * T * dq / p / hw->bw;           /* q in, o out */
+    double all = ctx_series(C0, T, r), att;
+    if (time_model == ORA_ADDITIVE) {
+        att = (alpha + beta) * all + r * gamma;
+    } else if (alpha <= beta) {
+        att = beta * all + r * gamma;
+    } else {
+        double c_star = gamma / (alpha - beta);                     /* read-bound while C <= c_star */
+        double n_rd = (c_star < C0) ? 0.0 : floor((c_star - C0) / T) + 1.0;
+        if (n_rd > r) n_rd = r;
+        double low = ctx_series(C0, T, n_rd);
+        att = beta * low + n_rd * gamma + alpha * (all - low);
+    }
+    return r * rest + (double)m->L * att;
+}
+
+/* The same r steps one by one (the definition): used to check the closed form, and by nothing else. */
+double ora_decode_run_steps(const ora_model *m, const ora_hw *hw, uint64_t p_, uint64_t wbits, int time_model,
+                            double T, double C0, uint64_t r) {
+    double total = 0.0, C = C0;
+    uint64_t j;
+    for (j = 0; j < r; ++j) {
+        total += ora_pass(m, hw, 1.0, 1.0, p_, wbits, time_model, T, C, C, T, 0, 0, 0, 0);
+        C += T;
+    }
+    return total;
+}
 
 /*
  * Step-level simulation of one serving configuration: FCFS admission under a
@@ -441,6 +494,7 @@ void ora_simulate(const ora_model *m, const ora_hw *hw, uint64_t p, uint64_t wbi
     uint32_t i;
     out->ttft_p50 = out->ttft_p99 = out->mean_tpot = inf; out->tokens_s = 0.0;
     out->n_steps = out->n_request_steps = 0; out->status = ORA_SIM_INFEASIBLE;
+    out->min_admit_margin = INFINITY;
     if (ttft) for (i = 0; i < n; ++i) ttft[i] = first[i] = fin[i] = inf;
     if (min_free_out) *min_free_out = 0;
     if (n == 0 || max_seqs == 0) return;
@@ -452,6 +506,9 @@ void ora_simulate(const ora_model *m, const ora_hw *hw, uint64_t p, uint64_t wbi
         need[i] = (int64_t)(((uint64_t)n_in[i] + n_out[i] + blk - 1) / blk);
         if (need[i] > n_blk) { free(need); return; }
     }
+    int closed_runs = (scheduler & ORA_SIM_CLOSED_FORM_RUNS) != 0;
+    scheduler &= ~ORA_SIM_CLOSED_FORM_RUNS;
+    double margin = INFINITY;
     double *arr = (double *)malloc(sizeof(double) * 4 * n);
     double *t_first = arr + n, *t_fin = arr + 2 * n, *t_ttft = arr + 3 * n;
     uint32_t *prefilled = (uint32_t *)calloc(4 * (size_t)n, sizeof(uint32_t));
@@ -466,9 +523,51 @@ void ora_simulate(const ora_model *m, const ora_hw *hw, uint64_t p, uint64_t wbi
 
     while (n_done < n) {
         uint32_t a;
+        /* 0. (closed-form variant) a run of decode-only steps: every active request is decoding, so until a
+         * decoder emits its last token or a request that could be admitted has arrived, every step is the same
+         * pass at a context that grows by one token per decoder.  The run takes the r steps that the step-by-step
+         * loop would take before either happens: r_max = steps before the one in which the first decoder
+         * finishes; with an admissible request waiting to arrive, the least r whose starting time
+         * now + (time of r steps) has reached its arrival. */
+        if (closed_runs && n_active > 0) {
+            int all_decoding = 1;
+            uint64_t r_max = UINT64_MAX;
+            double C0 = 0.0;
+            for (a = 0; a < n_active; ++a) {
+                uint32_t r = active[a];
+                if (prefilled[r] < n_in[r]) { all_decoding = 0; break; }
+                uint64_t left = (uint64_t)(n_out[r] - gen[r]) - 1;
+                if (left < r_max) r_max = left;
+                C0 += (double)n_in[r] + (double)gen[r];
+            }
+            if (all_decoding && r_max > 0) {
+                double T = (double)n_active;
+                uint64_t r = r_max;
+                if (next < n && n_active < max_seqs && need[next] <= free_blk) {
+                    uint64_t lo = 0, hi = r_max;        /* least r in [0, r_max] with arr <= now + time(r), else r_max */
+                    while (lo < hi) {
+                        uint64_t mid = lo + (hi - lo) / 2;
+                        double at = now + ora_decode_run_time(m, hw, p, wbits, time_model, T, C0, (double)mid);
+                        double gap = fabs(arr[next] - at) / (at > 0.0 ? at : 1.0);
+                        if (gap < margin && arr[next] != at) margin = gap;
+                        if (arr[next] <= at) hi = mid; else lo = mid + 1;
+                    }
+                    r = lo;
+                }
+                if (r > 0) {
+                    now += ora_decode_run_time(m, hw, p, wbits, time_model, T, C0, (double)r);
+                    for (a = 0; a < n_active; ++a) gen[active[a]] += (uint32_t)r;
+                    n_steps += r; n_rs += r * (uint64_t)n_active;
+                }
+            }
+        }
         /* 1. idle jump */
         if (n_active == 0 && next < n && arr[next] > now) now = arr[next];
         /* 2. FCFS admission, stop at the first request that cannot enter */
+        if (next < n && n_active < max_seqs && need[next] <= free_blk && arr[next] != now) {
+            double gap = fabs(arr[next] - now) / (now > 0.0 ? now : 1.0);   /* equality is exact: the idle jump assigns it */
+            if (gap < margin) margin = gap;
+        }
         while (next < n && arr[next] <= now && n_active < max_seqs && need[next] <= free_blk) {
             free_blk -= need[next];
             if (free_blk < min_free) min_free = free_blk;
@@ -570,6 +669,7 @@ void ora_simulate(const ora_model *m, const ora_hw *hw, uint64_t p, uint64_t wbi
         free(s);
     }
     out->status = ORA_SIM_OK; out->n_steps = n_steps; out->n_request_steps = n_rs;
+    out->min_admit_margin = margin;
     if (ttft) { memcpy(ttft, t_ttft, sizeof(double) * n); memcpy(first, t_first, sizeof(double) * n); memcpy(fin, t_fin, sizeof(double) * n); }
     if (min_free_out) *min_free_out = min_free;
     free(need); free(arr); free(prefilled);

@@ -20,6 +20,7 @@ GCC_FLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra", "
 ROOFLINE, ADDITIVE = 0, 1
 SIM_OK, SIM_INFEASIBLE = 0, 1
 SCHED_SPLIT_FUSE, SCHED_PREFILL_FIRST = 0, 1
+SIM_CLOSED_FORM_RUNS = 256        # OR-ed into the scheduler
 NO_INDEX = 2 ** 64 - 1
 
 
@@ -55,7 +56,7 @@ class GridC(C.Structure):
 class SimOut(C.Structure):
     _fields_ = [("ttft_p50", C.c_double), ("ttft_p99", C.c_double), ("mean_tpot", C.c_double),
                 ("tokens_s", C.c_double), ("status", C.c_uint32), ("n_steps", C.c_uint64),
-                ("n_request_steps", C.c_uint64)]
+                ("n_request_steps", C.c_uint64), ("min_admit_margin", C.c_double)]
 
 
 class SpaceC(C.Structure):
@@ -103,6 +104,12 @@ def lib():
         _lib.ora_simulate.argtypes = [C.POINTER(Model), C.POINTER(Hw), C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint64,
                                       C.c_uint64, C.c_double, C.c_int, C.c_int, C.c_uint32, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.POINTER(SimOut), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib.ora_decode_run_time.restype = C.c_double
+        _lib.ora_decode_run_time.argtypes = [C.POINTER(Model), C.POINTER(Hw), C.c_uint64, C.c_uint64, C.c_int,
+                                             C.c_double, C.c_double, C.c_double]
+        _lib.ora_decode_run_steps.restype = C.c_double
+        _lib.ora_decode_run_steps.argtypes = [C.POINTER(Model), C.POINTER(Hw), C.c_uint64, C.c_uint64, C.c_int,
+                                              C.c_double, C.c_double, C.c_uint64]
         _lib.ora_simulate_grid.argtypes = [C.POINTER(GridC), C.c_void_p, C.c_void_p, C.c_uint32, C.c_int, C.c_int,
                                            C.c_uint32,
                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -255,10 +262,19 @@ def simulate(m, h, p, wbits, blk, mbt, max_seqs, rate, arr_unit, n_in, n_out, ti
                        _ptr(arr_unit), _ptr(n_in), _ptr(n_out), C.byref(o), _ptr(ttft), _ptr(first), _ptr(fin),
                        C.cast(C.byref(mf), C.c_void_p))
     res = dict(ttft_p50=o.ttft_p50, ttft_p99=o.ttft_p99, mean_tpot=o.mean_tpot, tokens_s=o.tokens_s,
-               status=o.status, n_steps=o.n_steps, n_request_steps=o.n_request_steps)
+               status=o.status, n_steps=o.n_steps, n_request_steps=o.n_request_steps,
+               min_admit_margin=o.min_admit_margin)
     if detail:
         res.update(ttft=ttft, first=first, fin=fin, min_free=mf.value)
     return res
+
+
+def decode_run_time(m, h, p, wbits, T, C0, r, time_model=ROOFLINE) -> float:
+    return lib().ora_decode_run_time(C.byref(m), C.byref(h), p, wbits, time_model, float(T), float(C0), float(r))
+
+
+def decode_run_steps(m, h, p, wbits, T, C0, r, time_model=ROOFLINE) -> float:
+    return lib().ora_decode_run_steps(C.byref(m), C.byref(h), p, wbits, time_model, float(T), float(C0), int(r))
 
 
 def simulate_grid(g: Grid, cfg_idx, rate, arr_unit, n_in, n_out, time_model=ROOFLINE, scheduler=SCHED_SPLIT_FUSE):
@@ -271,7 +287,7 @@ def simulate_grid(g: Grid, cfg_idx, rate, arr_unit, n_in, n_out, time_model=ROOF
                                  _ptr(arr_unit), _ptr(n_in), _ptr(n_out), C.cast(outs, C.c_void_p))
     if rc:
         raise ValueError("oracle: index outside the grid")
-    names = ("ttft_p50", "ttft_p99", "mean_tpot", "tokens_s")
+    names = ("ttft_p50", "ttft_p99", "mean_tpot", "tokens_s", "min_admit_margin")
     res = {k: np.array([getattr(o, k) for o in outs], dtype=np.float64) for k in names}
     res["status"] = np.array([o.status for o in outs], dtype=np.uint32)
     res["n_steps"] = np.array([o.n_steps for o in outs], dtype=np.uint64)

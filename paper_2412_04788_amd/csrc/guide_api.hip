@@ -741,7 +741,7 @@ int guide_simulate(guide_ctx *ctx, const guide_grid *grid, const uint32_t *cfg_i
     TraceDev *t = new (std::nothrow) TraceDev;
     if (!t) return fail(ctx, GUIDE_E_NOMEM, "host allocation failed");
     memset(t, 0, sizeof *t);
-    double prev = -INFINITY;
+    double prev = -INFINITY, sum_in = 0.0, sum_out = 0.0;
     for (uint32_t i = 0; i < trace->n && rc == GUIDE_OK; ++i) {
         const double a = trace->arrival_unit[i];
         if (!(a >= 0.0) || std::isinf(a) || a < prev) rc = fail(ctx, GUIDE_E_ARG, "trace: arrival %u not non-decreasing / finite", i);
@@ -749,6 +749,8 @@ int guide_simulate(guide_ctx *ctx, const guide_grid *grid, const uint32_t *cfg_i
             rc = fail(ctx, GUIDE_E_ARG, "trace: request %u has a length outside 1..2^24", i);
         prev = a;
         t->arrival[i] = a; t->n_in[i] = trace->n_in[i]; t->n_out[i] = trace->n_out[i];
+        sum_in += (double)trace->n_in[i];
+        sum_out += (double)trace->n_out[i];
     }
     if (rc) { delete t; return rc; }
     const size_t need = simulate_workspace_bytes(n_cfg, trace->n);
@@ -765,7 +767,7 @@ int guide_simulate(guide_ctx *ctx, const guide_grid *grid, const uint32_t *cfg_i
     if (rc) return rc;
     hipError_t e = launch_simulate(desc, ctx->dev_tab, ctx->dev_trace, trace->n, cfg_idx, rate, n_cfg,
                         time_model == GUIDE_TIME_ADDITIVE, scheduler == GUIDE_SCHED_PREFILL_FIRST, *out, workspace,
-                        stream);
+                        stream, sum_in, sum_out);
     if (e != hipSuccess) return hip_fail(ctx, e, "simulate launch");
     return GUIDE_OK;
 }

@@ -14,6 +14,7 @@
 //     number and total context are two running integers.
 // One step therefore costs one pass-time evaluation plus O(1) integer updates;
 // heap traffic is O(log n) per request, not per step.
+#include <cstdlib>
 #include "kernels.hpp"
 #include "perf_model.hpp"
 
@@ -81,21 +82,11 @@ __device__ inline bool decode_sim_index(const uint32_t (*axis)[GUIDE_MAX_AXIS_VA
 // depends on it, never a result.
 template <bool ADDITIVE>
 __global__ __launch_bounds__(kBlock) void sim_order_count_kernel(GridDesc g, const DevTables *__restrict__ tab,
-                                                                 const TraceDev *__restrict__ trace, uint32_t n_req,
+                                                                 uint32_t n_req,
                                                                  const uint32_t *__restrict__ cfg_idx,
                                                                  const double *__restrict__ rate_in, uint32_t n_cfg,
-                                                                 SimWs ws) {
-    __shared__ double s_sum[2];
-    if (threadIdx.x == 0) {
-        double si = 0.0, so = 0.0;
-        for (uint32_t i = 0; i < n_req; ++i) {
-            si += (double)trace->n_in[i];
-            so += (double)trace->n_out[i];
-        }
-        s_sum[0] = si;
-        s_sum[1] = so;
-    }
-    __syncthreads();
+                                                                 SimWs ws, double sum_in, double sum_out) {
+    const double s_sum[2] = {sum_in, sum_out};      // prompt / generated tokens of the whole trace
     const uint32_t c = blockIdx.x * kBlock + threadIdx.x;
     if (c >= n_cfg) return;
     uint32_t v[kNumAxes];
@@ -220,16 +211,34 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
             const uint64_t stop = top.key >> 10;              // the step whose book-keeping retires a decoder
             const double T = (double)n_dec;
             double ctx = (double)s_ctx;                       // integers below 2^53: exact in fp64
-            uint64_t run = 0;
-            while (run < max_run && dstep + run + 1 < stop && !(arr_stop <= now)) {
-                now += fma(tc.L, kept_base + attention<ADDITIVE>(tc, T, ctx, ctx), kept_lm);
+            // steps left before the one that retires a decoder (stop > dstep: its last token is still to come)
+            const uint64_t left = stop - dstep - 1;
+            const uint32_t r_cap = left < max_run ? (uint32_t)left : max_run;
+            uint32_t run = 0;
+            auto step_time = [&](double c) { return fma(tc.L, kept_base + attention<ADDITIVE>(tc, T, c, c), kept_lm); };
+            // Four steps at a time without a branch between them: the times after each step are formed in
+            // step order (n1 = now + t1, n2 = n1 + t2, ..), and the run stops after the first k steps whose
+            // starting time is still before the arrival -- times only grow, so k is a count of compares.
+            bool go = true;
+            while (go && run + 4 <= r_cap) {
+                const double c2 = ctx + T, c3 = c2 + T, c4 = c3 + T;
+                const double n1 = now + step_time(ctx), n2 = n1 + step_time(c2), n3 = n2 + step_time(c3),
+                             n4 = n3 + step_time(c4);
+                const uint32_t k = arr_stop <= now ? 0u : arr_stop <= n1 ? 1u : arr_stop <= n2 ? 2u : arr_stop <= n3 ? 3u : 4u;
+                now = k == 0 ? now : k == 1 ? n1 : k == 2 ? n2 : k == 3 ? n3 : n4;
+                ctx = k == 0 ? ctx : k == 1 ? c2 : k == 2 ? c3 : k == 3 ? c4 : c4 + T;
+                run += k;
+                go = k == 4;
+            }
+            while (go && run < r_cap && !(arr_stop <= now)) {
+                now += step_time(ctx);
                 ctx += T;
                 ++run;
             }
             step += run;
             dstep += run;
-            n_rs += run * n_dec;
-            s_ctx += run * n_dec;
+            n_rs += (uint64_t)run * n_dec;
+            s_ctx += (uint64_t)run * n_dec;
         }
         uint32_t n_active = (next - pf_head) + n_dec;
         // 1. idle jump to the next arrival
@@ -421,18 +430,19 @@ size_t simulate_workspace_bytes(uint32_t n_cfg, uint32_t n_req) {
 
 hipError_t launch_simulate(const GridDesc &g, const DevTables *tab, const TraceDev *trace, uint32_t n_req,
                            const uint32_t *cfg_idx, const double *rate, uint32_t n_cfg, bool additive,
-                           bool prefill_first, const guide_sim_out &out, void *ws_, hipStream_t stream) {
+                           bool prefill_first, const guide_sim_out &out, void *ws_, hipStream_t stream, double sum_in,
+                           double sum_out) {
     const SimWs ws = sim_ws(ws_, n_cfg, n_req);
     // Lanes wait for the longest run of their wave before the next general step, so runs are capped:
     // 64 steps measured best among 4..128 and unbounded on the 65 536-configuration mix.
-    const uint32_t max_run = 64;
+    const uint32_t max_run = getenv("GUIDE_TMP_MAXRUN") ? (uint32_t)atoi(getenv("GUIDE_TMP_MAXRUN")) : 64;  // TMP sweep
     const dim3 grid((n_cfg + kSimBlock - 1) / kSimBlock), block(kSimBlock);
     const dim3 ogrid((n_cfg + kBlock - 1) / kBlock), oblock(kBlock);
     hipLaunchKernelGGL(sim_order_clear_kernel, dim3(1), dim3(kKeyBins), 0, stream, ws);
     if (additive)
-        hipLaunchKernelGGL(sim_order_count_kernel<true>, ogrid, oblock, 0, stream, g, tab, trace, n_req, cfg_idx, rate, n_cfg, ws);
+        hipLaunchKernelGGL(sim_order_count_kernel<true>, ogrid, oblock, 0, stream, g, tab, n_req, cfg_idx, rate, n_cfg, ws, sum_in, sum_out);
     else
-        hipLaunchKernelGGL(sim_order_count_kernel<false>, ogrid, oblock, 0, stream, g, tab, trace, n_req, cfg_idx, rate, n_cfg, ws);
+        hipLaunchKernelGGL(sim_order_count_kernel<false>, ogrid, oblock, 0, stream, g, tab, n_req, cfg_idx, rate, n_cfg, ws, sum_in, sum_out);
     hipLaunchKernelGGL(sim_order_scan_kernel, dim3(1), dim3(kKeyBins), 0, stream, ws);
     hipLaunchKernelGGL(sim_order_scatter_kernel, ogrid, oblock, 0, stream, n_cfg, ws);
 #define GUIDE_SIM(A, P)                                                                                          \

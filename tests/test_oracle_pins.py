@@ -798,3 +798,92 @@ def test_extras_by_hand(ora):
                                       wl.Axis.table([16]), wl.Axis.table([2048])))
     e = ora.eval_extras_grid(g0, 4)
     assert e["s_max"][0] == 0 and e["max_parallelism"][0] == 0
+
+
+# ------------------------------------------------- closed-form decode runs (simulation)
+
+def test_decode_run_closed_form_against_stepping(ora):
+    """The closed form of a run of decode-only steps against the step-by-step sum of passes on 2^16 random runs:
+    all five shapes, TP 1..8, three precisions, hardware from compute-starved to bandwidth-starved (so that
+    attention is read bound, compute bound, or crosses over inside the run), both time models."""
+    rng = np.random.default_rng(2024)
+    models = [bridge.ora_model(m) for m in wl.MODELS_FULL]
+    worst, crossed = 0.0, 0
+    for case in range(1 << 16):
+        m = models[case % 5]
+        # ridge points from 2 to 2000 FLOP/B: the attention crossover context gamma / (alpha - beta) lands anywhere
+        peak = 10.0 ** rng.uniform(13.0, 15.5)
+        bw = peak / 10.0 ** rng.uniform(0.3, 3.3)
+        h = bridge.ora_hw(wl.Hardware(peak, bw, 192 * wl.GIB, bw / 12.5, 1e-6 * (case % 3)))
+        p, wbits, tm = int(rng.choice([1, 2, 4, 8])), int(rng.choice([16, 8, 4])), (case // 5) % 2
+        T = float(rng.integers(1, 1025))
+        C0 = T * float(rng.integers(2, 9000))
+        r = int(rng.integers(1, 600))
+        mw = wl.MODELS_FULL[case % 5]
+        if case % 4 == 0 and mw.n_kv < mw.n_h:
+            # aim at the crossover: with fewer KV heads than heads, attention turns compute bound at the mean
+            # context rho / (1 - rho * n_kv / n_h) for a ridge rho = peak / bw below n_h / n_kv
+            p = int(rng.choice([1, 2, 4, 8]))
+            share = -(-mw.n_kv // p) * p / mw.n_h
+            rho = rng.uniform(0.5, 0.999) / share
+            bw = peak / rho
+            h = bridge.ora_hw(wl.Hardware(peak, bw, 192 * wl.GIB, bw / 12.5, 0.0))
+            star = rho / (1.0 - rho * share)
+            C0 = T * float(max(2, int(star - r * rng.uniform(0.0, 1.0))))
+            wbits, tm = 16, 0
+        a = ora.decode_run_time(m, h, p, wbits, T, C0, r, time_model=tm)
+        b = ora.decode_run_steps(m, h, p, wbits, T, C0, r, time_model=tm)
+        worst = max(worst, abs(a - b) / b)
+        if tm == 0:
+            first = ora.pass_detail(m, h, p, wbits, T, C0, C0, T)
+            last = ora.pass_detail(m, h, p, wbits, T, C0 + (r - 1) * T, C0 + (r - 1) * T, T)
+            rd0 = first["B"][1] / h.bw >= first["F"][1] / h.peak
+            rd1 = last["B"][1] / h.bw >= last["F"][1] / h.peak
+            crossed += int(rd0 != rd1)
+    assert worst <= 1e-12, worst
+    assert crossed > 200                     # the crossover inside a run is exercised
+    m, h = models[0], bridge.ora_hw(wl.HW_TINY)
+    assert ora.decode_run_time(m, h, 1, 16, 3.0, 900.0, 0) == 0.0
+    one = ora.pass_detail(m, h, 1, 16, 3.0, 900.0, 900.0, 3.0)["t_pass"]
+    assert ora.decode_run_time(m, h, 1, 16, 3.0, 900.0, 1) == pytest.approx(one, rel=1e-15)
+
+
+@pytest.mark.parametrize("scheduler", [0, 1])
+def test_closed_form_runs_simulation_against_stepping(ora, scheduler):
+    """Whole simulations with closed-form runs against the step-by-step simulation: engine steps and
+    request-steps are the same integers, times agree to rounding (a TTFT is a difference of two nearby times,
+    hence the looser bound on it)."""
+    g = wl.grid_full()
+    og = bridge.ora_grid(g)
+    tr = wl.request_trace(n=256)
+    idx, rate = wl.sim_configs(g, 96, seed=wl.SEED + 3)
+    a = ora.simulate_grid(og, idx, rate, tr.arrival_unit, tr.n_in, tr.n_out, scheduler=scheduler)
+    b = ora.simulate_grid(og, idx, rate, tr.arrival_unit, tr.n_in, tr.n_out,
+                          scheduler=scheduler | ora.SIM_CLOSED_FORM_RUNS)
+    np.testing.assert_array_equal(a["status"], b["status"])
+    ok = a["status"] == 0
+    assert ok.sum() > 60
+    # an admission decided within rounding may differ between the two; such a configuration shows a tiny margin
+    same = (a["n_steps"] == b["n_steps"]) & (a["n_request_steps"] == b["n_request_steps"])
+    assert np.all(same | (np.minimum(a["min_admit_margin"], b["min_admit_margin"]) < 1e-9))
+    assert same.sum() >= len(idx) - 1
+    for k, tol in (("ttft_p50", 1e-9), ("ttft_p99", 1e-9), ("mean_tpot", 1e-11), ("tokens_s", 1e-12)):
+        assert bridge.rel_err(b[k][ok & same], a[k][ok & same]).max() <= tol, k
+    # single request: one prefill step, then one closed-form run of out - 2 steps and the last step
+    arr, ins, outs = np.array([0.0]), np.array([700], dtype=np.uint32), np.array([40], dtype=np.uint32)
+    om, oh = bridge.ora_model(wl.DENSE_34B), bridge.ora_hw(wl.HW_TINY)
+    s0 = ora.simulate(om, oh, 2, 8, 16, 2048, 4, 1.0, arr, ins, outs, detail=True, scheduler=scheduler)
+    s1 = ora.simulate(om, oh, 2, 8, 16, 2048, 4, 1.0, arr, ins, outs, detail=True,
+                      scheduler=scheduler | ora.SIM_CLOSED_FORM_RUNS)
+    assert s1["n_steps"] == s0["n_steps"] == 40 and s1["ttft"][0] == s0["ttft"][0]
+    assert s1["fin"][0] == pytest.approx(s0["fin"][0], rel=1e-13)
+    # a request that arrives exactly when a step ends is admitted before the next step, run or no run
+    t1 = ora.pass_detail(om, oh, 2, 8, 700, 700 * 700, 700, 1)["t_pass"]
+    arr2, ins2, outs2 = np.array([0.0, t1]), np.array([700, 300], dtype=np.uint32), np.array([40, 5], dtype=np.uint32)
+    s0 = ora.simulate(om, oh, 2, 8, 16, 2048, 4, 1.0, arr2, ins2, outs2, detail=True, scheduler=scheduler)
+    s1 = ora.simulate(om, oh, 2, 8, 16, 2048, 4, 1.0, arr2, ins2, outs2, detail=True,
+                      scheduler=scheduler | ora.SIM_CLOSED_FORM_RUNS)
+    second = ora.pass_detail(om, oh, 2, 8, 300 + (1 - scheduler), 300 * 300 + (1 - scheduler) * 701,
+                             300 + (1 - scheduler) * 701, 1 + (1 - scheduler))["t_pass"]
+    assert s0["ttft"][1] == pytest.approx(second, rel=1e-13) and s1["ttft"][1] == s0["ttft"][1]
+    assert s1["n_steps"] == s0["n_steps"] and s1["n_request_steps"] == s0["n_request_steps"]
