@@ -77,6 +77,7 @@ enum { GUIDE_AXIS_GEOM2 = 0, GUIDE_AXIS_TABLE = 1 };
 enum { GUIDE_SELECT_TOPK = 0, GUIDE_SELECT_PARETO = 1 };
 enum { GUIDE_SIM_OK = 0, GUIDE_SIM_INFEASIBLE = 1, GUIDE_SIM_BAD_INPUT = 2, GUIDE_SIM_INTERNAL = 3 };
 enum { GUIDE_SCHED_SPLIT_FUSE = 0, GUIDE_SCHED_PREFILL_FIRST = 1 };
+enum { GUIDE_SIM_CLOSED_FORM_RUNS = 256 };   /* OR-ed into guide_simulate's scheduler argument */
 
 #define GUIDE_MAX_MODELS 8
 #define GUIDE_MAX_HW 64
@@ -237,6 +238,18 @@ int guide_eval_sampled(guide_ctx *ctx, const guide_space *space, uint64_t seed, 
  *                             always, even if longer), decoders pause; otherwise
  *                             one decode token for every running request
  *                             (dynamic batching without chunking).
+ * With GUIDE_SIM_CLOSED_FORM_RUNS OR-ed into `scheduler`, a run of decode-only
+ * passes (every running request decoding, none waiting for prompt chunks) is
+ * not stepped: until the first decoder emits its last token or a request that
+ * could be admitted has arrived, every pass has the same tokens and a context
+ * that grows by one per decoder, so the r passes the stepped loop would run
+ * (r = passes before the one that retires a decoder, or the least r whose
+ * starting time now + time(r passes) has reached that arrival) are advanced at
+ * once with time(r) = r * (pass without attention) + L * (the attention series
+ * in closed form, split where attention turns from read bound to compute
+ * bound).  Engine steps and request-steps count the same passes; times differ
+ * from the stepped simulation by rounding only, so a result can differ from it
+ * only where an admission test "arrived by now?" is decided within rounding.
  * Outputs (DEVICE, n_cfg each): nearest-rank p50 / p99 of TTFT, mean TPOT over
  * requests with n_out > 1, generated tokens / (last finish - first arrival),
  * status (GUIDE_SIM_INFEASIBLE when weights or one request do not fit,

@@ -23,7 +23,7 @@ struct Div32 {
     uint32_t m, s1, s2, d;
 };
 
-inline Div32 make_div32(uint32_t d) {
+__host__ __device__ inline Div32 make_div32(uint32_t d) {
     Div32 r;
     r.d = d;
     uint32_t l = 0;

@@ -723,6 +723,8 @@ int guide_simulate(guide_ctx *ctx, const guide_grid *grid, const uint32_t *cfg_i
     if (!ctx) return GUIDE_E_ARG;
     hipStream_t stream = (hipStream_t)stream_;
     if (!time_model_ok(time_model)) return fail(ctx, GUIDE_E_ARG, "unknown time model %u", time_model);
+    const bool closed_runs = (scheduler & GUIDE_SIM_CLOSED_FORM_RUNS) != 0;
+    scheduler &= ~(uint32_t)GUIDE_SIM_CLOSED_FORM_RUNS;
     if (scheduler != GUIDE_SCHED_SPLIT_FUSE && scheduler != GUIDE_SCHED_PREFILL_FIRST)
         return fail(ctx, GUIDE_E_ARG, "unknown scheduler %u", scheduler);
     if (!trace || !out) return fail(ctx, GUIDE_E_ARG, "trace or out is NULL");
@@ -766,7 +768,7 @@ int guide_simulate(guide_ctx *ctx, const guide_grid *grid, const uint32_t *cfg_i
     rc = upload_tables(ctx, stream);
     if (rc) return rc;
     hipError_t e = launch_simulate(desc, ctx->dev_tab, ctx->dev_trace, trace->n, cfg_idx, rate, n_cfg,
-                        time_model == GUIDE_TIME_ADDITIVE, scheduler == GUIDE_SCHED_PREFILL_FIRST, *out, workspace,
+                        time_model == GUIDE_TIME_ADDITIVE, scheduler == GUIDE_SCHED_PREFILL_FIRST, closed_runs, *out, workspace,
                         stream, sum_in, sum_out);
     if (e != hipSuccess) return hip_fail(ctx, e, "simulate launch");
     return GUIDE_OK;

@@ -89,7 +89,7 @@ struct TraceDev {
 };
 hipError_t launch_simulate(const GridDesc &g, const DevTables *tab, const TraceDev *trace, uint32_t n_req,
                            const uint32_t *cfg_idx, const double *rate, uint32_t n_cfg, bool additive,
-                           bool prefill_first, const guide_sim_out &out, void *ws, hipStream_t stream,
+                           bool prefill_first, bool closed_runs, const guide_sim_out &out, void *ws, hipStream_t stream,
                            double sum_in, double sum_out);   // sums of the trace's prompt / generated tokens
 
 }  // namespace guide

@@ -14,7 +14,6 @@
 //     number and total context are two running integers.
 // One step therefore costs one pass-time evaluation plus O(1) integer updates;
 // heap traffic is O(log n) per request, not per step.
-#include <cstdlib>
 #include "kernels.hpp"
 #include "perf_model.hpp"
 
@@ -22,8 +21,9 @@ namespace guide {
 
 namespace {
 
-constexpr uint32_t kSimBlock = kWave;    // one wave per block: configurations diverge in step count
+constexpr uint32_t kSimBlock = 256;      // one block per compute unit: the trace is staged once, the rest of LDS holds heaps
 constexpr uint32_t kPctBlock = 256;
+constexpr uint32_t kHeapLdsMax = 64;     // at most this many heap nodes per lane in LDS
 
 struct SimLds {
     uint32_t axis[kNumAxes][GUIDE_MAX_AXIS_VALUES];
@@ -35,26 +35,21 @@ struct SimLds {
 
 constexpr uint32_t kKeyBins = 1024;      // buckets of the expected-step-count ordering
 
-// Decoder record: key = finishing step << 10 | request, and the time of its first token.
-struct HeapEnt {
-    uint64_t key;
-    double first;
-};
-
-// Workspace: heap[position][slot] (16 B records), ttft[cfg][req], then the launch order:
-// perm[position] = configuration, bucket of each configuration, bucket counters.
+// Workspace: heap[position][node] (u64 keys), first[cfg][req] and fin[cfg][req] (time of the first and of the
+// last token), then the launch order: perm[position] = configuration, bucket of each configuration, bucket counters.
 struct SimWs {
-    HeapEnt *heap;
-    double *ttft;
+    uint64_t *heap;
+    double *first, *fin;
     uint32_t *perm;
     uint32_t *bucket;     // [n_cfg]: bucket of each configuration
     uint32_t *bins;       // [kKeyBins]: counts, then scatter cursors
 };
 SimWs sim_ws(void *ws, uint32_t n_cfg, uint32_t n_req) {
     SimWs w;
-    w.heap = (HeapEnt *)ws;
-    w.ttft = (double *)(w.heap + (size_t)n_cfg * n_req);
-    w.perm = (uint32_t *)(w.ttft + (size_t)n_cfg * n_req);
+    w.heap = (uint64_t *)ws;
+    w.first = (double *)(w.heap + (size_t)n_cfg * n_req);
+    w.fin = w.first + (size_t)n_cfg * n_req;
+    w.perm = (uint32_t *)(w.fin + (size_t)n_cfg * n_req);
     w.bucket = w.perm + n_cfg;
     w.bins = w.bucket + n_cfg;
     return w;
@@ -132,13 +127,76 @@ __global__ __launch_bounds__(kBlock) void sim_order_scatter_kernel(uint32_t n_cf
 
 __global__ __launch_bounds__(kKeyBins) void sim_order_clear_kernel(SimWs ws) { ws.bins[threadIdx.x] = 0; }
 
-template <bool ADDITIVE, bool PREFILL_FIRST>
+// Heap of the decoders' finishing steps, one per lane.  Node 0 lives in a register, nodes 1 .. lds_slots in
+// LDS (slot-major, so the lanes of a wave sit in different banks when they touch the same node), deeper nodes in
+// global memory.  4-ary: the children of node i are 4i+1 .. 4i+4.  Key = finishing step << 10 | request.
+struct LaneHeap {
+    uint64_t top;
+    uint64_t *lds;        // this lane's column: node i at lds[(i - 1) * kSimBlock]
+    uint64_t *mem;        // node i at mem[i]
+    uint32_t lds_slots, n;
+    __device__ uint64_t get(uint32_t i) const { return i <= lds_slots ? lds[(size_t)(i - 1) * kSimBlock] : mem[i]; }
+    __device__ void set(uint32_t i, uint64_t k) {
+        if (i <= lds_slots) lds[(size_t)(i - 1) * kSimBlock] = k; else mem[i] = k;
+    }
+    __device__ void push(uint64_t key) {            // the new node rises from the end
+        uint32_t i = n++;
+        while (i > 0) {
+            const uint32_t par = (i - 1) >> 2;
+            const uint64_t pk = par == 0 ? top : get(par);
+            if (pk <= key) break;
+            set(i, pk);
+            i = par;
+        }
+        if (i == 0) top = key; else set(i, key);
+    }
+    __device__ void pop() {                         // the last node sinks from the root
+        --n;
+        if (n == 0) {
+            top = ~0ull;
+            return;
+        }
+        const uint64_t last = get(n);
+        uint32_t i = 0;
+        for (;;) {
+            const uint32_t c0 = 4 * i + 1;
+            if (c0 >= n) break;
+            uint64_t k[4];
+#pragma unroll
+            for (uint32_t j = 0; j < 4; ++j) k[j] = get(c0 + j < n ? c0 + j : c0);      // all four requested at once
+            uint64_t best = k[0];
+            uint32_t bi = c0;
+#pragma unroll
+            for (uint32_t j = 1; j < 4; ++j)
+                if (c0 + j < n && k[j] < best) { best = k[j]; bi = c0 + j; }
+            if (best >= last) break;
+            if (i == 0) top = best; else set(i, best);
+            i = bi;
+        }
+        if (i == 0) top = last; else set(i, last);
+    }
+};
+
+// Time of r consecutive decode-only steps of T decoders whose total context is C0 before the first one:
+// r * (everything but attention) + L * (attention over contexts C0, C0 + T, ..), the latter in closed form.
+template <bool ADDITIVE>
+__device__ inline double run_time(const TimeCoef &tc, double step_const, double T, double r_T, double C0, double r) {
+    const double att = attention_series<ADDITIVE>(tc.c_att, tc.m_att_k, T * tc.m_att_t, C0 - T, T, r_T, r);
+    return fma(r, step_const, tc.L * att);
+}
+
+// CLOSED_RUNS: runs of decode-only steps are advanced by run_time() in one go (GUIDE_SIM_CLOSED_FORM_RUNS);
+// otherwise step by step with the general step's own arithmetic.
+template <bool ADDITIVE, bool PREFILL_FIRST, bool CLOSED_RUNS>
 __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const DevTables *__restrict__ tab,
                                                              const TraceDev *__restrict__ trace, uint32_t n_req,
                                                              const uint32_t *__restrict__ cfg_idx,
                                                              const double *__restrict__ rate_in, uint32_t n_cfg,
-                                                             guide_sim_out out, SimWs ws, uint32_t max_run) {
-    __shared__ SimLds s;
+                                                             guide_sim_out out, SimWs ws, uint32_t max_run,
+                                                             uint32_t lds_slots) {
+    extern __shared__ __align__(16) unsigned char s_raw[];
+    SimLds &s = *(SimLds *)s_raw;
+    uint64_t *s_heap = (uint64_t *)(s_raw + sizeof(SimLds));
     for (uint32_t i = threadIdx.x; i < kNumAxes * GUIDE_MAX_AXIS_VALUES; i += blockDim.x)
         (&s.axis[0][0])[i] = (&tab->axis_vals[0][0])[i];
     for (uint32_t i = threadIdx.x; i < g.n_models * 8u; i += blockDim.x)
@@ -160,80 +218,119 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
     const double rate = rate_in[c];
     const Coef cf = make_coef(s.models[v[AX_MODEL]], p, wbits);
     const TimeCoef tc = make_time_coef(cf, 1.0 / hw.peak_flops, 1.0 / hw.hbm_bw, 1.0 / hw.link_bw, hw.link_lat);
+    const Div32 dblk = make_div32(blk);
+    // KV blocks of a request of `tok` >= 1 tokens: ceil(tok / blk) without the 32-bit overflow of tok + blk - 1
+    auto blocks_of = [&](uint32_t tok) { return (long long)div32(tok - 1, dblk) + 1; };
 
     // KV pool in blocks; every request must fit on its own
     const double c_avail = hw.cap_bytes - cf.w_gpu;
     uint32_t max_tok = 0;
     uint64_t step_bound = n_req;
+    double tokens = 0.0;
     for (uint32_t i = 0; i < n_req; ++i) {
         const uint32_t t = s.n_in[i] + s.n_out[i];
         max_tok = t > max_tok ? t : max_tok;
         step_bound += t;
+        tokens += (double)s.n_out[i];
     }
     long long n_blk = 0;
     if (c_avail > 0.0) {
         const double nb = floor(c_avail / ((double)blk * cf.kv_tok));
         n_blk = nb >= 9.0e18 ? 0x7FFFFFFFFFFFFFFFll : (long long)nb;
     }
-    const long long need_max = (long long)((max_tok + blk - 1) / blk);
-    if (bad_index || !(c_avail > 0.0) || need_max > n_blk || !(rate > 0.0)) {
+    if (bad_index || !(c_avail > 0.0) || blocks_of(max_tok) > n_blk || !(rate > 0.0)) {
         out.ttft_p50[c] = INFINITY; out.ttft_p99[c] = INFINITY; out.mean_tpot[c] = INFINITY; out.tokens_s[c] = 0.0;
         out.status[c] = (bad_index || !(rate > 0.0)) ? GUIDE_SIM_BAD_INPUT : GUIDE_SIM_INFEASIBLE;
         out.n_steps[c] = 0; out.n_request_steps[c] = 0;
-        for (uint32_t i = 0; i < n_req; ++i) ws.ttft[(size_t)c * n_req + i] = INFINITY;
         return;
     }
 
-    // 4-ary heap: node 0 lives in `top`, nodes 1.. in mem[]; the children of node i are 4i+1..4i+4,
-    // 64 contiguous bytes.  A heap of one decoder (sequence cap 1) never touches memory.
-    HeapEnt *mem = ws.heap + (size_t)pos * n_req;
-    HeapEnt top = {~0ull, 0.0};
-    double *ttft = ws.ttft + (size_t)c * n_req;
+    LaneHeap heap;
+    heap.top = ~0ull;
+    heap.lds = s_heap + threadIdx.x;
+    heap.mem = ws.heap + (size_t)pos * n_req;
+    heap.lds_slots = lds_slots;
+    heap.n = 0;
+    double *first = ws.first + (size_t)c * n_req, *fin = ws.fin + (size_t)c * n_req;
 
-    double now = 0.0, sum_tpot = 0.0, max_fin = -INFINITY;
-    uint32_t next = 0, pf_head = 0, pf_done = 0, n_dec = 0, heap_n = 0, n_done = 0, n_tpot = 0;
+    double now = 0.0, max_fin = -INFINITY;
+    uint32_t next = 0, pf_head = 0, pf_done = 0, n_dec = 0, n_done = 0;
     uint64_t s_ctx = 0, step = 0, dstep = 0, n_rs = 0;   // dstep counts the steps in which decoders ran
     long long free_blk = n_blk;
     uint32_t status = GUIDE_SIM_OK;
     double arr_next = s.arrival[0] / rate;   // arrival time of request `next`
-    double kept_base = 0.0, kept_lm = 0.0;   // layer_base / lm_head of the last decode-only step
-    uint32_t kept_dec = 0;                   // its token count (0 = nothing kept)
+    long long need_next = blocks_of(s.n_in[0] + s.n_out[0]);
+    double kept_base = 0.0, kept_lm = 0.0;   // layer_base / lm_head for kept_dec decode tokens (a pure function of the count)
+    uint32_t kept_dec = 0;
 
     while (n_done < n_req) {
-        // Run of decode-only steps: no prompt is waiting for chunks, the decoders' token count has its
-        // pass terms kept, and nothing changes until the first decoder finishes or a request that could
-        // be admitted arrives.  Each step of the run is the general step below with its invariant parts
-        // left out: the same operations in the same order on the same values.
-        if (pf_head == next && n_dec > 0 && kept_dec == n_dec) {
-            bool can_admit = next < n_req && n_dec < max_seqs;
-            if (can_admit) can_admit = (long long)((s.n_in[next] + s.n_out[next] + blk - 1) / blk) <= free_blk;
+        // Run of decode-only steps: no prompt is waiting for chunks, and nothing changes until the first
+        // decoder finishes or a request that could be admitted arrives.
+        if (pf_head == next && n_dec > 0) {
+            if (kept_dec != n_dec) {
+                kept_base = layer_base<ADDITIVE>(tc, (double)n_dec);
+                kept_lm = lm_head<ADDITIVE>(tc, (double)n_dec);
+                kept_dec = n_dec;
+            }
+            const bool can_admit = next < n_req && n_dec < max_seqs && need_next <= free_blk;
             const double arr_stop = can_admit ? arr_next : INFINITY;
-            const uint64_t stop = top.key >> 10;              // the step whose book-keeping retires a decoder
+            const uint64_t stop = heap.top >> 10;             // the step whose book-keeping retires a decoder
+            // steps left before that one (stop > dstep: its last token is still to come)
+            const uint64_t left = stop - dstep - 1;
             const double T = (double)n_dec;
             double ctx = (double)s_ctx;                       // integers below 2^53: exact in fp64
-            // steps left before the one that retires a decoder (stop > dstep: its last token is still to come)
-            const uint64_t left = stop - dstep - 1;
-            const uint32_t r_cap = left < max_run ? (uint32_t)left : max_run;
             uint32_t run = 0;
-            auto step_time = [&](double c) { return fma(tc.L, kept_base + attention<ADDITIVE>(tc, T, c, c), kept_lm); };
-            // Four steps at a time without a branch between them: the times after each step are formed in
-            // step order (n1 = now + t1, n2 = n1 + t2, ..), and the run stops after the first k steps whose
-            // starting time is still before the arrival -- times only grow, so k is a count of compares.
-            bool go = true;
-            while (go && run + 4 <= r_cap) {
-                const double c2 = ctx + T, c3 = c2 + T, c4 = c3 + T;
-                const double n1 = now + step_time(ctx), n2 = n1 + step_time(c2), n3 = n2 + step_time(c3),
-                             n4 = n3 + step_time(c4);
-                const uint32_t k = arr_stop <= now ? 0u : arr_stop <= n1 ? 1u : arr_stop <= n2 ? 2u : arr_stop <= n3 ? 3u : 4u;
-                now = k == 0 ? now : k == 1 ? n1 : k == 2 ? n2 : k == 3 ? n3 : n4;
-                ctx = k == 0 ? ctx : k == 1 ? c2 : k == 2 ? c3 : k == 3 ? c4 : c4 + T;
-                run += k;
-                go = k == 4;
-            }
-            while (go && run < r_cap && !(arr_stop <= now)) {
-                now += step_time(ctx);
-                ctx += T;
-                ++run;
+            if (CLOSED_RUNS) {
+                // The run takes r = min(left, least r with arrival <= now + time of r steps) steps.  The search
+                // walks up from r = 0 without overshooting: the steps still to come each take at most the time
+                // of the last one that could be needed, so floor(remaining / that) of them fit for sure.
+                const uint32_t r_max = left < 0x40000000ull ? (uint32_t)left : 0x40000000u;
+                const double step_const = fma(tc.L, kept_base, kept_lm), r_T = fast_recip(T);
+                auto t_at = [&](double j) {
+                    const double cj = fma(j, T, ctx);
+                    return fma(tc.L, attention<ADDITIVE>(tc, T, cj, cj), step_const);
+                };
+                double s_run = 0.0;
+                if (!can_admit) {
+                    run = r_max;
+                    s_run = run_time<ADDITIVE>(tc, step_const, T, r_T, ctx, (double)run);
+                } else {
+                    for (;;) {
+                        const double rem = arr_stop - (now + s_run);
+                        if (!(rem > 0.0) || run == r_max) break;
+                        const double room = (double)(r_max - run);
+                        const double ub = fmin(ceil(rem * fast_recip(t_at((double)run))), room);
+                        const double t_hi = t_at((double)run + fmax(ub, 1.0) - 1.0);
+                        const double q = fmin(fmax(floor(rem * fast_recip(t_hi)), 1.0), room);
+                        run += (uint32_t)q;
+                        s_run = run_time<ADDITIVE>(tc, step_const, T, r_T, ctx, (double)run);
+                    }
+                }
+                now += s_run;
+            } else {
+                const uint32_t r_cap = left < max_run ? (uint32_t)left : max_run;
+                auto step_time = [&](double cj) { return fma(tc.L, kept_base + attention<ADDITIVE>(tc, T, cj, cj), kept_lm); };
+                // Four steps at a time without a branch between them: the times after each step are formed in
+                // step order (n1 = now + t1, n2 = n1 + t2, ..), and the run stops after the first k steps whose
+                // starting time is still before the arrival -- times only grow, so k is a count of compares.
+                // Each step is the general step below with its invariant parts left out: the same operations
+                // in the same order on the same values.
+                bool go = true;
+                while (go && run + 4 <= r_cap) {
+                    const double c2 = ctx + T, c3 = c2 + T, c4 = c3 + T;
+                    const double n1 = now + step_time(ctx), n2 = n1 + step_time(c2), n3 = n2 + step_time(c3),
+                                 n4 = n3 + step_time(c4);
+                    const uint32_t k = arr_stop <= now ? 0u : arr_stop <= n1 ? 1u : arr_stop <= n2 ? 2u : arr_stop <= n3 ? 3u : 4u;
+                    now = k == 0 ? now : k == 1 ? n1 : k == 2 ? n2 : k == 3 ? n3 : n4;
+                    ctx = k == 0 ? ctx : k == 1 ? c2 : k == 2 ? c3 : k == 3 ? c4 : c4 + T;
+                    run += k;
+                    go = k == 4;
+                }
+                while (go && run < r_cap && !(arr_stop <= now)) {
+                    now += step_time(ctx);
+                    ctx += T;
+                    ++run;
+                }
             }
             step += run;
             dstep += run;
@@ -244,13 +341,16 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
         // 1. idle jump to the next arrival
         if (n_active == 0 && next < n_req) now = arr_next > now ? arr_next : now;
         // 2. FCFS admission; stop at the first request that cannot enter
-        while (next < n_req && n_active < max_seqs && arr_next <= now) {
-            const long long need = (long long)((s.n_in[next] + s.n_out[next] + blk - 1) / blk);
-            if (need > free_blk) break;
-            free_blk -= need;
+        while (next < n_req && n_active < max_seqs && arr_next <= now && need_next <= free_blk) {
+            free_blk -= need_next;
             ++next;
             ++n_active;
-            arr_next = next < n_req ? s.arrival[next] / rate : INFINITY;
+            if (next < n_req) {
+                arr_next = s.arrival[next] / rate;
+                need_next = blocks_of(s.n_in[next] + s.n_out[next]);
+            } else {
+                arr_next = INFINITY;
+            }
         }
         // 3. schedule.  Split-fuse: one token per decoder, then prompt chunks in admission order under
         // the remaining budget.  Prefill-first: while prompts wait, whole prompts only (as many as fit the
@@ -313,66 +413,30 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
             ++dstep;
             s_ctx += n_dec;
         }
-        while (decoders_run && heap_n > 0 && (top.key >> 10) == dstep) {
-            const uint32_t r = (uint32_t)(top.key & 1023u);
-            const double r_first = top.first;
-            // pop: the last node sinks from the root
-            --heap_n;
-            if (heap_n == 0) {
-                top.key = ~0ull;
-            } else {
-                const HeapEnt last = mem[heap_n];
-                uint32_t i = 0;
-                for (;;) {
-                    const uint32_t c0 = 4 * i + 1;
-                    if (c0 >= heap_n) break;
-                    HeapEnt best = mem[c0];
-                    uint32_t bi = c0;
-#pragma unroll
-                    for (uint32_t k = 1; k < 4; ++k) {
-                        if (c0 + k < heap_n) {
-                            const HeapEnt e = mem[c0 + k];
-                            if (e.key < best.key) { best = e; bi = c0 + k; }
-                        }
-                    }
-                    if (best.key >= last.key) break;
-                    if (i == 0) top = best; else mem[i] = best;
-                    i = bi;
-                }
-                if (i == 0) top = last; else mem[i] = last;
-            }
-            // request r is done
-            const uint32_t r_in = s.n_in[r], r_out = s.n_out[r];
-            free_blk += (long long)((r_in + r_out + blk - 1) / blk);
+        while (decoders_run && heap.n > 0 && (heap.top >> 10) == dstep) {
+            const uint32_t r = (uint32_t)(heap.top & 1023u);
+            heap.pop();
+            const uint32_t r_tok = s.n_in[r] + s.n_out[r];
+            free_blk += blocks_of(r_tok);
             --n_dec;
-            s_ctx -= (uint64_t)r_in + r_out;
+            s_ctx -= (uint64_t)r_tok;
             ++n_done;
-            sum_tpot += (now - r_first) / (double)(r_out - 1);
-            ++n_tpot;
+            fin[r] = now;
             max_fin = now;
         }
         // prompts completed in this step emit their first token
         for (uint32_t r = pf_head; r < h; ++r) {
             const uint32_t r_in = s.n_in[r], r_out = s.n_out[r];
-            ttft[r] = now - s.arrival[r] / rate;
+            first[r] = now;
             if (r_out == 1) {
-                free_blk += (long long)((r_in + 1 + blk - 1) / blk);
+                free_blk += blocks_of(r_in + 1);
                 ++n_done;
+                fin[r] = now;
                 max_fin = now;
             } else {
                 ++n_dec;
                 s_ctx += (uint64_t)r_in + 1;
-                // push (finishing step, request): the new node rises from the end
-                const HeapEnt e = {((dstep + r_out - 1) << 10) | r, now};
-                uint32_t i = heap_n++;
-                while (i > 0) {
-                    const uint32_t par = (i - 1) >> 2;
-                    const HeapEnt pe = par == 0 ? top : mem[par];
-                    if (pe.key <= e.key) break;
-                    mem[i] = pe;
-                    i = par;
-                }
-                if (i == 0) top = e; else mem[i] = e;
+                heap.push(((dstep + r_out - 1) << 10) | r);
             }
         }
         pf_head = h;
@@ -383,25 +447,52 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
         }
     }
 
-    double tokens = 0.0;
-    for (uint32_t i = 0; i < n_req; ++i) tokens += (double)s.n_out[i];
-    out.mean_tpot[c] = n_tpot ? sum_tpot / (double)n_tpot : 0.0;
-    out.tokens_s[c] = tokens / (max_fin - s.arrival[0] / rate);
+    out.tokens_s[c] = status == GUIDE_SIM_OK ? tokens / (max_fin - s.arrival[0] / rate) : 0.0;
     out.status[c] = status;
     out.n_steps[c] = step;
     out.n_request_steps[c] = n_rs;
-    if (status != GUIDE_SIM_OK)
-        for (uint32_t i = 0; i < n_req; ++i) ttft[i] = INFINITY;
+    if (status != GUIDE_SIM_OK) {
+        out.ttft_p50[c] = INFINITY; out.ttft_p99[c] = INFINITY; out.mean_tpot[c] = INFINITY;
+    }
 }
 
-// One block per configuration: bitonic sort of its TTFTs in LDS, nearest-rank
-// p50 = sorted[ceil(n/2) - 1] and p99 = sorted[ceil(0.99 n) - 1].
-__global__ __launch_bounds__(kPctBlock) void percentile_kernel(const double *__restrict__ ttft, uint32_t n_req,
+// One block per simulated configuration that ended normally: TTFT of request i = first token time -
+// arrival / rate; bitonic sort in LDS, nearest-rank p50 = sorted[ceil(n/2) - 1] and p99 =
+// sorted[ceil(0.99 n) - 1]; mean TPOT = mean over requests with more than one token of
+// (finish - first token) / (tokens - 1).
+__global__ __launch_bounds__(kPctBlock) void percentile_kernel(SimWs ws, const TraceDev *__restrict__ trace,
+                                                               const double *__restrict__ rate_in, uint32_t n_req,
                                                                guide_sim_out out) {
     __shared__ double v[GUIDE_MAX_REQUESTS];
+    __shared__ double s_sum[kPctBlock / kWave];
+    __shared__ uint32_t s_cnt[kPctBlock / kWave];
     const uint32_t c = blockIdx.x;
-    for (uint32_t i = threadIdx.x; i < GUIDE_MAX_REQUESTS; i += kPctBlock)
-        v[i] = i < n_req ? ttft[(size_t)c * n_req + i] : INFINITY;
+    if (out.status[c] != GUIDE_SIM_OK) return;
+    const double rate = rate_in[c];
+    const double *first = ws.first + (size_t)c * n_req, *fin = ws.fin + (size_t)c * n_req;
+    double tp = 0.0;
+    uint32_t n_tp = 0;
+    for (uint32_t i = threadIdx.x; i < GUIDE_MAX_REQUESTS; i += kPctBlock) {
+        double t = INFINITY;
+        if (i < n_req) {
+            const double f = first[i];
+            t = f - trace->arrival[i] / rate;
+            const uint32_t n_out = trace->n_out[i];
+            if (n_out > 1) {
+                tp += (fin[i] - f) / (double)(n_out - 1);
+                ++n_tp;
+            }
+        }
+        v[i] = t;
+    }
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        tp += __shfl_xor(tp, off, kWave);
+        n_tp += __shfl_xor(n_tp, off, kWave);
+    }
+    if (threadIdx.x % kWave == 0) {
+        s_sum[threadIdx.x / kWave] = tp;
+        s_cnt[threadIdx.x / kWave] = n_tp;
+    }
     __syncthreads();
     for (uint32_t k = 2; k <= GUIDE_MAX_REQUESTS; k <<= 1) {
         for (uint32_t j = k >> 1; j > 0; j >>= 1) {
@@ -419,6 +510,10 @@ __global__ __launch_bounds__(kPctBlock) void percentile_kernel(const double *__r
     if (threadIdx.x == 0) {
         out.ttft_p50[c] = v[(n_req + 1) / 2 - 1];
         out.ttft_p99[c] = v[(99ull * n_req + 99) / 100 - 1];
+        double t = 0.0;
+        uint32_t n = 0;
+        for (uint32_t w = 0; w < kPctBlock / kWave; ++w) { t += s_sum[w]; n += s_cnt[w]; }
+        out.mean_tpot[c] = n ? t / (double)n : 0.0;
     }
 }
 
@@ -430,12 +525,22 @@ size_t simulate_workspace_bytes(uint32_t n_cfg, uint32_t n_req) {
 
 hipError_t launch_simulate(const GridDesc &g, const DevTables *tab, const TraceDev *trace, uint32_t n_req,
                            const uint32_t *cfg_idx, const double *rate, uint32_t n_cfg, bool additive,
-                           bool prefill_first, const guide_sim_out &out, void *ws_, hipStream_t stream, double sum_in,
-                           double sum_out) {
+                           bool prefill_first, bool closed_runs, const guide_sim_out &out, void *ws_, hipStream_t stream,
+                           double sum_in, double sum_out) {
     const SimWs ws = sim_ws(ws_, n_cfg, n_req);
-    // Lanes wait for the longest run of their wave before the next general step, so runs are capped:
-    // 64 steps measured best among 4..128 and unbounded on the 65 536-configuration mix.
-    const uint32_t max_run = getenv("GUIDE_TMP_MAXRUN") ? (uint32_t)atoi(getenv("GUIDE_TMP_MAXRUN")) : 64;  // TMP sweep
+    // Stepped runs: lanes wait for the longest run of their wave before the next general step, so runs are
+    // capped (64 steps measured best among 4..1024 on the 65 536-configuration mix; stopping a run once few
+    // lanes of the wave are still in it measured worse at every setting tried).
+    const uint32_t max_run = 64;
+    // LDS beyond the staged tables holds the upper heap nodes of the block's lanes
+    int dev = 0, lds_max = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
+    if (e != hipSuccess) return e;
+    if ((size_t)lds_max < sizeof(SimLds)) return hipErrorInvalidValue;
+    uint32_t lds_slots = (uint32_t)(((size_t)lds_max - sizeof(SimLds)) / (sizeof(uint64_t) * kSimBlock));
+    lds_slots = lds_slots < kHeapLdsMax ? lds_slots : kHeapLdsMax;
+    const size_t lds_bytes = sizeof(SimLds) + (size_t)lds_slots * sizeof(uint64_t) * kSimBlock;
     const dim3 grid((n_cfg + kSimBlock - 1) / kSimBlock), block(kSimBlock);
     const dim3 ogrid((n_cfg + kBlock - 1) / kBlock), oblock(kBlock);
     hipLaunchKernelGGL(sim_order_clear_kernel, dim3(1), dim3(kKeyBins), 0, stream, ws);
@@ -445,16 +550,23 @@ hipError_t launch_simulate(const GridDesc &g, const DevTables *tab, const TraceD
         hipLaunchKernelGGL(sim_order_count_kernel<false>, ogrid, oblock, 0, stream, g, tab, n_req, cfg_idx, rate, n_cfg, ws, sum_in, sum_out);
     hipLaunchKernelGGL(sim_order_scan_kernel, dim3(1), dim3(kKeyBins), 0, stream, ws);
     hipLaunchKernelGGL(sim_order_scatter_kernel, ogrid, oblock, 0, stream, n_cfg, ws);
-#define GUIDE_SIM(A, P)                                                                                          \
-    hipLaunchKernelGGL((simulate_kernel<A, P>), grid, block, 0, stream, g, tab, trace, n_req, cfg_idx, rate, n_cfg, \
-                       out, ws, max_run)
-    if (additive) {
-        if (prefill_first) GUIDE_SIM(true, true); else GUIDE_SIM(true, false);
-    } else {
-        if (prefill_first) GUIDE_SIM(false, true); else GUIDE_SIM(false, false);
+    const int variant = (additive ? 4 : 0) | (prefill_first ? 2 : 0) | (closed_runs ? 1 : 0);
+#define GUIDE_SIM(A, P, C)                                                                                         \
+    case ((A ? 4 : 0) | (P ? 2 : 0) | (C ? 1 : 0)): {                                                               \
+        auto kern = simulate_kernel<A, P, C>;                                                                       \
+        e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);    \
+        if (e != hipSuccess) return e;                                                                              \
+        hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, g, tab, trace, n_req, cfg_idx, rate, n_cfg, out, ws, \
+                           max_run, lds_slots);                                                                     \
+        break;                                                                                                      \
+    }
+    switch (variant) {
+        GUIDE_SIM(false, false, false) GUIDE_SIM(false, false, true) GUIDE_SIM(false, true, false)
+        GUIDE_SIM(false, true, true) GUIDE_SIM(true, false, false) GUIDE_SIM(true, false, true)
+        GUIDE_SIM(true, true, false) GUIDE_SIM(true, true, true)
     }
 #undef GUIDE_SIM
-    hipLaunchKernelGGL(percentile_kernel, dim3(n_cfg), dim3(kPctBlock), 0, stream, (const double *)ws.ttft, n_req, out);
+    hipLaunchKernelGGL(percentile_kernel, dim3(n_cfg), dim3(kPctBlock), 0, stream, ws, trace, rate, n_req, out);
     return hipGetLastError();
 }
 

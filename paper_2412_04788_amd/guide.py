@@ -20,6 +20,7 @@ AXIS_GEOM2, AXIS_TABLE = 0, 1
 SELECT_TOPK, SELECT_PARETO = 0, 1
 SIM_OK, SIM_INFEASIBLE, SIM_BAD_INPUT, SIM_INTERNAL = 0, 1, 2, 3
 SCHED_SPLIT_FUSE, SCHED_PREFILL_FIRST = 0, 1
+SIM_CLOSED_FORM_RUNS = 256       # OR-ed into simulate()'s scheduler
 NO_INDEX = 2 ** 64 - 1
 MAX_CONSTRAINTS = 4
 STATIC_SELECT_MAX_ROWS = 1 << 21

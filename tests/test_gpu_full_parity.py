@@ -236,6 +236,27 @@ def test_simulation_every_configuration(ora, torch_cuda, scheduler):
     assert len(diverged) == 0, diverged[:10]
 
 
+@pytest.mark.parametrize("scheduler", [0, 1], ids=["split-fuse", "prefill-first"])
+def test_simulation_closed_form_runs_every_configuration(ora, torch_cuda, scheduler):
+    """The same launch with GUIDE_SIM_CLOSED_FORM_RUNS against the oracle's closed-form tier: integer outputs
+    exact except configurations where the oracle saw an admission decided within 1e-9 (listed)."""
+    torch = torch_cuda
+    from paper_2412_04788_amd import guide
+    from tests.test_gpu_simulate import _compare_closed, _run
+    g = wl.grid_full()
+    ctx = bridge.gpu_context(g)
+    tr = wl.request_trace()
+    idx, rate = wl.sim_configs(g, 65536)
+    got = _run(torch, ctx, g, idx, rate, tr, scheduler=scheduler | guide.SIM_CLOSED_FORM_RUNS)
+    exp = bridge.ora_simulate_grid_all(bridge.ora_grid(g), idx, rate, tr, chunk=128,
+                                       scheduler=scheduler | ora.SIM_CLOSED_FORM_RUNS)
+    diverged = _compare_closed(got, exp)
+    _report(f"simulate_closed_runs_{scheduler}",
+            dict(configs_compared=int(len(idx)), near_tie_configurations=[int(i) for i in diverged],
+                 least_admission_margin=float(exp["min_admit_margin"][exp["status"] == 0].min())))
+    assert len(diverged) <= 8
+
+
 # -------------------------------------------------------------- sampled space
 
 def test_sampled_space_four_million_candidates(ora, torch_cuda):

@@ -167,3 +167,56 @@ def test_bad_index_and_errors(torch_cuda):
     zero = wl.Trace(tr.arrival_unit, tr.n_in, np.zeros(8, dtype=np.uint32))
     with pytest.raises(guide.GuideError):
         _run(torch, ctx, g, idx, np.ones(3), zero)
+
+
+def _compare_closed(got, exp):
+    """Closed-form runs: times equal to rounding; integer outputs equal unless the oracle saw an admission test
+    decided within 1e-9 relative (then the configuration is a listed near-tie, not a failure)."""
+    np.testing.assert_array_equal(got["status"], exp["status"])
+    same = (got["n_steps"] == exp["n_steps"]) & (got["n_request_steps"] == exp["n_request_steps"])
+    near = exp["min_admit_margin"] < TOL
+    assert np.all(same | near), np.flatnonzero(~(same | near))[:10]
+    for k in FLOATS:
+        e = bridge.rel_err(got[k][same], exp[k][same])
+        assert e.max() <= TOL, (k, int(e.argmax()), float(e.max()))
+    return np.flatnonzero(~same)
+
+
+@pytest.mark.parametrize("scheduler", [0, 1])
+def test_closed_form_runs(ora, torch_cuda, scheduler):
+    """GUIDE_SIM_CLOSED_FORM_RUNS against the oracle's closed-form tier, and against the stepped oracle."""
+    torch = torch_cuda
+    from paper_2412_04788_amd import guide
+    g = wl.grid_full()
+    ctx = bridge.gpu_context(g)
+    og = bridge.ora_grid(g)
+    flag = scheduler | guide.SIM_CLOSED_FORM_RUNS
+    for n_req, n_cfg, tm in [(1, 3, 0), (2, 64, 0), (37, 65, 1), (200, 130, 0), (1024, 700, 0)]:
+        tr = wl.request_trace(n=n_req)
+        idx, rate = wl.sim_configs(g, n_cfg, seed=wl.SEED + n_req)
+        got = _run(torch, ctx, g, idx, rate, tr, time_model=tm, scheduler=flag)
+        exp = ora.simulate_grid(og, idx, rate, tr.arrival_unit, tr.n_in, tr.n_out, time_model=tm,
+                                scheduler=scheduler | ora.SIM_CLOSED_FORM_RUNS)
+        diverged = _compare_closed(got, exp)
+        stepped = ora.simulate_grid(og, idx, rate, tr.arrival_unit, tr.n_in, tr.n_out, time_model=tm, scheduler=scheduler)
+        diverged0 = _compare_closed(got, stepped)
+        print("closed-form runs", n_req, n_cfg, "near-ties vs closed-form oracle", list(diverged),
+              "vs stepped oracle", list(diverged0))
+        assert (exp["status"] == 0).any()
+    # tight pool, odd values, one-token generations
+    m = wl.DENSE_7B
+    hws = [wl.Hardware(1e15, 5e12, 2 * 6738149376 + 1200 * 16 * 524288, 4e11, 2e-6),
+           wl.Hardware(2e14, 6e12, 40 * wl.GIB, 3e11, 0.0)]
+    g2 = wl.make_grid([m, wl.MOE_8X], hws, wl.Axis.table([1, 3, 50, 1024]), wl.Axis.table([1]), wl.Axis.table([1]),
+                      wl.Axis.table([1, 3]), wl.Axis.table([16, 4]), wl.Axis.table([16, 24]),
+                      wl.Axis.table([100, 1000, 8192]))
+    ctx2 = bridge.gpu_context(g2)
+    tr = wl.request_trace(n=300, seed=7)
+    n_out = tr.n_out.copy(); n_out[::7] = 1
+    tr = wl.Trace(tr.arrival_unit, tr.n_in, n_out)
+    idx = np.arange(g2.size, dtype=np.uint32)
+    rate = np.array([3.0 if i % 2 else 50.0 for i in range(g2.size)])
+    got = _run(torch, ctx2, g2, idx, rate, tr, scheduler=flag)
+    exp = ora.simulate_grid(bridge.ora_grid(g2), idx, rate, tr.arrival_unit, tr.n_in, tr.n_out,
+                            scheduler=scheduler | ora.SIM_CLOSED_FORM_RUNS)
+    _compare_closed(got, exp)
