@@ -20,11 +20,34 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the grid kernel from rocprofv3 counters (profiles/eval_tile_kernel_full_grid_pmc.md):
-# WRITE_SIZE 83531.33 KiB x 1.0 + FETCH_SIZE 198.23 KiB x 2.0 (scales from a 512 MiB device copy).
-# Set to None whenever eval_tile_kernel changes after the counters were taken.
-TRAFFIC_BYTES_PER_LAUNCH = 85_942_057
 BYTES_PER_CONFIG = 45           # 5 fp64 + u32 + u8 written per configuration, nothing read
+VECTOR_ISSUE_PEAK = 256 * 4 * 16 * 2.4e9      # lane-instructions per second: 256 CU x 4 SIMD x 16 lanes x 2.4 GHz
+
+# Figures taken from rocprofv3 counter runs (profiles/*.md), each with the SHA-256 (first 16 hex digits) of the
+# kernel sources it was measured on.  A figure is reported only while those sources are unchanged, else null.
+COUNTERS = {
+    # WRITE_SIZE 83531.33 KiB x 1.0 + FETCH_SIZE 198.23 KiB x 2.0 per launch (scales from a 512 MiB device copy):
+    # profiles/eval_tile_kernel_full_grid_pmc.md
+    "eval_tile_traffic_bytes": {"value": 85_942_057, "sources": ("eval_grid.hip", "perf_model.hpp"),
+                                "sha16": "unset"},
+    # SQ_INSTS_VALU x 64 / duration / peak for simulate_kernel, split-fuse, stepped: profiles/extra_kernels_valu_pmc.md
+    "simulate_vector_issue_frac": {"value": None, "sources": ("simulate.hip", "perf_model.hpp"), "sha16": "unset"},
+}
+
+
+def _sources_sha16(names):
+    import hashlib
+    h = hashlib.sha256()
+    for n in names:
+        with open(os.path.join(ROOT, "paper_2412_04788_amd", "csrc", n), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def counter_figure(key):
+    """The profiled figure, or None once the kernel's sources differ from the ones it was measured on."""
+    c = COUNTERS[key]
+    return c["value"] if _sources_sha16(c["sources"]) == c["sha16"] else None
 
 
 def main():
@@ -104,18 +127,21 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # timed region: K steps; the library attaches a pair of HIP events to the dispatch of the grid-evaluation
-    # kernel of every tenth step, on the launch stream (a timed launch delays the launches around it by a few
-    # microseconds, so not every step carries one)
-    every = 10 if args.steps >= 20 else 1
-    n_timed = (args.steps + every - 1) // every
-    ctx.profile_enable(n_timed, every)
+    # timed region: exactly K steps, nothing else
     t0 = time.perf_counter()
     for k in range(args.steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     total = t1 - t0
+    # Duration of the grid-evaluation kernel INSIDE the step: a second run of the same steps in which the library
+    # attaches a pair of HIP events to the dispatch of every step's evaluation kernel, on the launch stream
+    # (a timed launch delays the launches around it by a few microseconds, so this run is not the throughput run).
+    n_timed = max(args.steps, 32)
+    ctx.profile_enable(n_timed, 1)
+    for k in range(n_timed):
+        step()
+    torch.cuda.synchronize()
     ms_kernel = ctx.profile_read(n_timed)
     assert len(ms_kernel) == n_timed
     ms_eval = float(np.mean(ms_kernel))
@@ -151,6 +177,7 @@ def main():
     torch.cuda.synchronize()
     value = n * args.steps / total
     achieved = BYTES_PER_CONFIG * n / (ms_eval * 1e-3) / 1e9
+    sustained = grid_sustained(torch, guide, wl)
 
     result = {
         "metric": "configs evaluated/sec (fp64 grid)", "value": value, "unit": "configs/s", "n_gpus": 1,
@@ -163,21 +190,78 @@ def main():
                    "selected": [int(v) for v in sel_idx.cpu().numpy().view(np.uint64)],
                    "pareto_front_size": int(par_cnt.item())},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": counter_figure("eval_tile_traffic_bytes"),
                      "kernel": "eval_tile_kernel<false,2,3,false>",
-                     "kernel_ms": ms_eval, "kernel_launches_timed": n_timed,
+                     "kernel_ms": ms_eval, "kernel_ms_min": float(np.min(ms_kernel)),
+                     "kernel_launches_timed": n_timed, "timing": "HIP event pair on the dispatch of every step's kernel",
                      "plain_eval_kernel_ms_back_to_back": ms_eval_b2b,
                      "frac_back_to_back": BYTES_PER_CONFIG * n / (ms_eval_b2b * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "bytes_per_config": BYTES_PER_CONFIG},
+                     "bytes_per_config": BYTES_PER_CONFIG, "grid_sustained": sustained},
         "phases_ms": {"eval_kernel_in_step": ms_eval, "step_as_three_calls": ms_separate,
                       "select_topk_alone": ms_topk, "select_pareto_alone": ms_pareto},
     }
 
+    host = {k: v.cpu().numpy() for k, v in out.items()}
+    front = par_idx.cpu().numpy().view(np.uint64)[:min(int(par_cnt.item()), par_cap)]
+    result["near_ties"] = near_ties(np, host, sel_idx.cpu().numpy().view(np.uint64), front, wl.TTFT_CAP_S)
     if not args.no_extra:
         result["extra"] = extra_timings(ctx, gg, g, torch, np, guide, wl)
     if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(g, np, wl)
+        result["cpu_baseline"] = cpu_baseline(g, np, wl, host, result["config"]["selected"], front)
     print(json.dumps(result))
+
+
+def grid_sustained(torch, guide, wl, n_hw=64, reps=10):
+    """The same evaluation kernel on a grid with 64 hardware rows instead of 6 (20 275 200 configurations, 912 MB
+    of columns per launch), back to back: the fixed cost of a launch is amortised, what is left is the rate at
+    which the kernel computes and stores."""
+    g0 = wl.grid_full()
+    rng_hw = [wl.Hardware(h.peak_flops * (1.0 + 0.01 * (i // 6)), h.hbm_bw, h.cap_bytes, h.link_bw, h.link_lat)
+              for i in range(n_hw) for h in [g0.hws[i % 6]]]
+    g = wl.make_grid(g0.models, rng_hw, *g0.axes[2:])
+    n = g.size
+    ctx = guide.Context(0)
+    ctx.set_models(wl.models_array(g.models))
+    ctx.set_hardware(wl.hw_array(g.hws))
+    gg = guide.GridArg([(a.values, a.geom2_start) for a in g.axes])
+    dt = {"b_max": torch.int32, "feasible": torch.uint8}
+    out = {k: torch.empty(n, dtype=dt.get(k, torch.float64), device="cuda") for k in guide.METRIC_COLUMNS}
+    call = ctx.prepared("eval_grid", gg, 0, n, out=out)
+    s = _timed(torch, call, reps=reps)
+    del out
+    gbs = BYTES_PER_CONFIG * n / s / 1e9
+    # what a plain fill of as many bytes reaches on this GPU (a store-only kernel that computes nothing)
+    flat = torch.empty(BYTES_PER_CONFIG * n // 8, dtype=torch.float64, device="cuda")
+    s_fill = _timed(torch, lambda: flat.fill_(1.0), reps=reps)
+    fill_gbs = flat.numel() * 8 / s_fill / 1e9
+    return {"configs": n, "kernel_ms": s * 1e3, "configs_per_s": n / s, "achieved_GBs": gbs, "frac": gbs / HBM_PEAK_GBS,
+            "plain_fill_same_bytes_GBs": fill_gbs, "frac_of_plain_fill": gbs / fill_gbs}
+
+
+def near_ties(np, host, top_idx, front, ttft_cap, tol=1e-9):
+    """Near-ties of the step's selections on the columns the GPU stored: selected rows whose objective is within
+    `tol` (relative) of the next candidate's, passing or failing rows whose TTFT sits within `tol` of the cap,
+    and front members with a neighbour within `tol` in either coordinate.  Each is a place where a result may
+    differ from a reference evaluation by rounding alone."""
+    cost, ttft, fe = host["cost"], host["t_prefill"], host["feasible"] != 0
+    ok = fe & (ttft <= ttft_cap)
+    cand = np.flatnonzero(ok)
+    order = cand[np.lexsort((cand, cost[cand]))][:len(top_idx) + 1]          # k + 1 best by (cost, row)
+    vals = cost[order]
+    gaps = np.abs(np.diff(vals)) / np.maximum(np.abs(vals[1:]), 1e-300)
+    topk = [dict(rows=[int(order[i]), int(order[i + 1])], relative_gap=float(gp)) for i, gp in enumerate(gaps)
+            if gp <= tol and cost[order[i]] != cost[order[i + 1]]]
+    at_cap = np.flatnonzero(fe & (np.abs(ttft - ttft_cap) <= tol * ttft_cap))
+    fx, fy = ttft[front.astype(np.int64)], cost[front.astype(np.int64)]
+    if len(front) > 1:
+        dx = np.abs(np.diff(fx)) / np.maximum(np.abs(fx[1:]), 1e-300)
+        dy = np.abs(np.diff(fy)) / np.maximum(np.abs(fy[1:]), 1e-300)
+        close = np.flatnonzero(((dx <= tol) & (dx > 0)) | ((dy <= tol) & (dy > 0)))
+    else:
+        close = np.zeros(0, dtype=np.int64)
+    return {"tolerance": tol, "top_k": topk, "rows_with_ttft_at_cap": [int(i) for i in at_cap[:16]],
+            "front_neighbours": [[int(front[i]), int(front[i + 1])] for i in close[:16]],
+            "selection_order_matches_columns": bool(np.array_equal(order[:len(top_idx)], top_idx.astype(np.int64)))}
 
 
 def _timed(torch, fn, reps=1):
@@ -267,7 +351,7 @@ def extra_timings(ctx, gg, g, torch, np, guide, wl, n_sampled=1 << 28, n_sim=655
                          "configs": n_cfg, "requests_per_config": len(tr.n_in), "request_steps": rs,
                          "feasible_configs": int((sim["status"] == 0).sum().item()), "scheduler": "split-fuse",
                          # from rocprofv3 counters, not measured in this run (profiles/extra_kernels_valu_pmc.md)
-                         "vector_issue_frac_profiled": 0.178}
+                         "vector_issue_frac_profiled": counter_figure("simulate_vector_issue_frac")}
     a.record()
     ctx.simulate(gg, d_idx, d_rate, (tr.arrival_unit, tr.n_in, tr.n_out), sim, ws, scheduler=guide.SCHED_PREFILL_FIRST)
     b.record()
@@ -276,11 +360,24 @@ def extra_timings(ctx, gg, g, torch, np, guide, wl, n_sampled=1 << 28, n_sim=655
     rs = int(sim["n_request_steps"].sum().item())
     extra["simulate_prefill_first"] = {"request_steps_per_s": rs / s, "seconds": s, "request_steps": rs,
                                        "engine_steps_per_s": int(sim["n_steps"].sum().item()) / s}
+    # the same simulations with runs of decode-only steps advanced in closed form (same request-steps simulated)
+    for name, sched in (("simulate_closed_form_runs", guide.SCHED_SPLIT_FUSE),
+                        ("simulate_prefill_first_closed_form_runs", guide.SCHED_PREFILL_FIRST)):
+        a.record()
+        ctx.simulate(gg, d_idx, d_rate, (tr.arrival_unit, tr.n_in, tr.n_out), sim, ws,
+                     scheduler=sched | guide.SIM_CLOSED_FORM_RUNS)
+        b.record()
+        torch.cuda.synchronize()
+        s = a.elapsed_time(b) * 1e-3
+        rs = int(sim["n_request_steps"].sum().item())
+        extra[name] = {"request_steps_per_s": rs / s, "seconds": s, "request_steps": rs,
+                       "engine_steps_per_s": int(sim["n_steps"].sum().item()) / s}
     return extra
 
 
-def cpu_baseline(g, np, wl):
-    """The oracle as it stands, single thread, on 96 blocks of 1024 rows spread evenly over the grid."""
+def cpu_baseline(g, np, wl, host, selected, front):
+    """The oracle as it stands, single thread, on 192 blocks of 1024 rows spread evenly over the grid; the rows the
+    step selected (top-3 and front members) are re-evaluated by the oracle one by one."""
     from oracle import guide_oracle as ora
     og = ora.Grid(wl.models_array(g.models), wl.hw_array(g.hws), [a.array() for a in g.axes])
     blocks, rows = 192, 1024
@@ -296,11 +393,18 @@ def cpu_baseline(g, np, wl):
     t0 = time.perf_counter()
     sim = ora.simulate_grid(og, idx[:512], rate[:512], tr.arrival_unit, tr.n_in, tr.n_out)
     dt_sim = time.perf_counter() - t0
+    worst = 0.0
+    for row in list(selected) + [int(i) for i in front]:
+        e = ora.eval_grid(og, int(row), 1)
+        for k in ("t_prefill", "t_decode", "t_batch", "decode_tok_s", "cost"):
+            worst = max(worst, abs(float(host[k][row]) - float(e[k][0])) / max(abs(float(e[k][0])), 1e-300))
+        assert int(host["b_max"].view(np.uint32)[row]) == int(e["b_max"][0]) and int(host["feasible"][row]) == int(e["feasible"][0])
     return {"value": blocks * rows / dt_, "unit": "configs/s", "cores": 1, "kind": "oracle",
             "sample": f"{blocks} blocks of {rows} consecutive configurations spread evenly over the 1900800-row grid "
                       f"(eval_grid only), {dt_:.1f} s", "host_cores_available": os.cpu_count(),
             "simulate_request_steps_per_s": float(sim["n_request_steps"].sum()) / dt_sim,
-            "simulate_sample": f"first 512 of the 65536 simulated configurations x 1024 requests, {dt_sim:.1f} s"}
+            "simulate_sample": f"first 512 of the 65536 simulated configurations x 1024 requests, {dt_sim:.1f} s",
+            "selected_rows_vs_oracle": {"rows": len(selected) + len(front), "max_rel_err": worst}}
 
 
 if __name__ == "__main__":

@@ -16,8 +16,20 @@
  *     the default stream).  The call returns after enqueueing; outputs are
  *     valid once the caller has synchronised the stream.  A launch failure is
  *     returned as GUIDE_E_DEVICE.
- *   - A context serialises its own small device tables; calls on one context
- *     must not overlap on different streams.
+ *   - A context owns small device tables and scratch that its calls share.  A
+ *     call on another stream than the context's previous call first makes its
+ *     stream wait for the previous stream's work (an event, no host wait), so
+ *     calls on one context never overlap on the GPU; use one context per stream
+ *     for concurrency.  guide_select_static shares one scratch per GPU between
+ *     all contexts (see there).
+ *   - The first call on a stream after guide_create, or after the models,
+ *     hardware, grid axes or efficiency samples changed, copies tables to the
+ *     device (a pinned staging slot, a host wait on that slot's last use): such
+ *     a call cannot be captured into a HIP graph.  Repeated calls with unchanged
+ *     tables only launch kernels and can be captured.
+ *   - Output capacity: a Pareto selection writes at most `capacity` indices and
+ *     always reports the full front size in count[0]; a front larger than the
+ *     capacity is not an error, the caller compares the two.
  *
  * Performance model (the reading of the paper implemented here)
  *   One forward pass over T tokens with attention workload Q (query x context
@@ -68,8 +80,7 @@ typedef enum {
     GUIDE_E_ARG = -1,      /* NULL required pointer, zero count, unknown enum            */
     GUIDE_E_RANGE = -2,    /* index range outside the grid, size beyond a stated limit    */
     GUIDE_E_NOMEM = -3,    /* workspace too small / allocation failed                     */
-    GUIDE_E_DEVICE = -4,   /* HIP runtime error                                           */
-    GUIDE_E_CAPACITY = -5  /* reserved: output capacity (see guide_select, Pareto mode)   */
+    GUIDE_E_DEVICE = -4    /* HIP runtime error, or not a gfx950 GPU                      */
 } guide_status;
 
 enum { GUIDE_TIME_ROOFLINE = 0, GUIDE_TIME_ADDITIVE = 1 };
@@ -91,6 +102,7 @@ enum { GUIDE_SIM_CLOSED_FORM_RUNS = 256 };   /* OR-ed into guide_simulate's sche
 #define GUIDE_HIST_BINS 256
 #define GUIDE_LATTICE 1024
 #define GUIDE_NO_INDEX UINT64_MAX
+#define GUIDE_SELECT_MAX_ROWS 0xFFFFF000ull     /* guide_select: at most 2^32 - 4096 rows */
 
 /* Decoder architecture.  E = k = 1 for a dense model; E experts with k active
  * per token otherwise.  n_h must divide d. */
@@ -109,7 +121,9 @@ typedef struct { uint32_t count, kind; uint64_t start; const uint64_t *values; }
 /* Mixed-radix space, slowest axis first: flat index =
  * ((((((((m*N_hw+h)*N_b+ib)*N_in+iin)*N_out+iout)*N_tp+itp)*N_w+iw)*N_blk+iblk)*N_mbt+imbt.
  * wbits = weight bits per parameter (16, 8, 4); kv_block = tokens per KV block;
- * mbt = max batched tokens per pass.  Total size must be < 2^32. */
+ * mbt = max batched tokens per pass.  Total size must be < 2^32; s_in and s_out
+ * values must be < 2^31 and the largest s_in + s_out + kv_block < 2^32
+ * (GUIDE_E_RANGE otherwise). */
 typedef struct { guide_axis model, hw, batch, s_in, s_out, tp, wbits, kv_block, mbt; } guide_grid;
 
 /* Multiplicative efficiency samples (HOST): peak *= e_c[i], bandwidth *= e_b[i].
@@ -167,12 +181,24 @@ int guide_eval_grid(guide_ctx *ctx, const guide_grid *grid, uint64_t first, uint
  *   cluster_tok_s    dp_max * decode throughput (replicas are independent);
  *   paper_tok_s      the paper's multi-GPU throughput N * T_single / (1 + log2 P_TP)
  *                    with N = dp_max * tp GPUs in use, P_TP = tp and T_single the
- *                    decode throughput of the same configuration at tp = 1.
+ *                    decode throughput of the same configuration at tp = 1;
+ *   b_adj            the adjusted batch B = min(B_input, B_max) (Dynamic Batch Size
+ *                    Adjustment);
+ *   n_sub_batches    prefill passes the batch is split into: ceil(b / split_size) with
+ *                    split_size = min(b, floor(mbt / s_in)) prompts per pass, the
+ *                    remainder forming one more pass; b when a prompt exceeds mbt (every
+ *                    request then runs alone, in segments);
+ *   n_segments       ceil(s_in / mbt): the splits of a long prompt (Dynamic Sequence
+ *                    Length Adjustment: input length over split size, rounded up);
+ *   s_adj            the adjusted sequence length min(s_in + s_out, s_max).
+ * The metrics of guide_eval_grid are computed at the nominal batch and lengths;
+ * these columns say what the adjustments would make of them.
  */
 typedef struct {
     uint32_t *s_max, *dp_max;
     uint64_t *max_parallelism;
     double *cluster_tok_s, *paper_tok_s;
+    uint32_t *b_adj, *n_sub_batches, *n_segments, *s_adj;
 } guide_extras;
 
 int guide_eval_extras(guide_ctx *ctx, const guide_grid *grid, uint64_t first, uint64_t count, uint32_t n_gpus,

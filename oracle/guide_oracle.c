@@ -273,6 +273,10 @@ typedef struct {
     uint64_t max_parallelism;  /* DP x (available memory / kv per request) = dp_max * b_max */
     double cluster_tok_s;      /* replicas are independent: dp_max x decode throughput */
     double paper_tok_s;        /* N T_single / (1 + log2 P_TP) with N = dp_max * tp GPUs in use, P_TP = tp */
+    uint32_t b_adj;            /* adjusted batch: min(B_input, B_max) */
+    uint32_t n_sub_batches;    /* prefill passes of the batch: ceil(b / split_size), remainder = one more pass */
+    uint32_t n_segments;       /* splits of a long prompt: ceil(input length / split size) */
+    uint32_t s_adj;            /* adjusted sequence length: min(s_in + s_out, S_max) */
 } ora_extras;
 
 /* Inference Engine Step 1 (maximum parallelism, max batch = parallelism / DP), Step 2 (multi-GPU
@@ -295,6 +299,25 @@ void ora_eval_extras(const ora_model *m, const ora_hw *hw, const ora_knobs *kn, 
     out->max_parallelism = (uint64_t)out->dp_max * (uint64_t)r.b_max;
     out->cluster_tok_s = (double)out->dp_max * r.decode_tok_s;
     out->paper_tok_s = ((double)out->dp_max * (double)kn->p) * r1.decode_tok_s / (1.0 + log2((double)kn->p));
+    /* Model Analyzer: "Dynamic Batch Size Adjustment" (B = min(B_input, B_max); sub-batches of split_size, the
+     * remainder forming one more) and "Dynamic Sequence Length Adjustment" (length capped by S_max; number of
+     * splits = input length / split size rounded up), with the split sizes ora_prefill() uses. */
+    out->b_adj = kn->b < r.b_max ? (uint32_t)kn->b : r.b_max;
+    if (kn->s_in <= kn->mbt) {
+        uint64_t split = kn->mbt / kn->s_in;
+        if (split > kn->b) split = kn->b;
+        uint64_t n_sub = 0, left = kn->b;
+        while (left > 0) { left -= (left < split ? left : split); ++n_sub; }     /* count the passes one by one */
+        out->n_sub_batches = (uint32_t)n_sub;
+        out->n_segments = 1;
+    } else {
+        uint64_t n_seg = 0, left = kn->s_in;
+        while (left > 0) { left -= (left < kn->mbt ? left : kn->mbt); ++n_seg; }
+        out->n_sub_batches = (uint32_t)kn->b;
+        out->n_segments = (uint32_t)n_seg;
+    }
+    uint64_t len = kn->s_in + kn->s_out;
+    out->s_adj = len < out->s_max ? (uint32_t)len : out->s_max;
 }
 
 /* ----------------------------------------------------------------------- grid */
@@ -348,7 +371,7 @@ int ora_eval_grid(const ora_grid *g, uint64_t first, uint64_t count, double e_c,
 
 int ora_eval_extras_grid(const ora_grid *g, uint64_t first, uint64_t count, uint32_t n_gpus, int time_model,
                          uint32_t *s_max, uint32_t *dp_max, uint64_t *max_par, double *cluster_tok_s,
-                         double *paper_tok_s) {
+                         double *paper_tok_s, uint32_t *b_adj, uint32_t *n_sub, uint32_t *n_seg, uint32_t *s_adj) {
     uint64_t i;
     for (i = 0; i < count; ++i) {
         const ora_model *m; const ora_hw *hw; ora_knobs kn; ora_extras e;
@@ -356,6 +379,7 @@ int ora_eval_extras_grid(const ora_grid *g, uint64_t first, uint64_t count, uint
         ora_eval_extras(m, hw, &kn, n_gpus, time_model, &e);
         s_max[i] = e.s_max; dp_max[i] = e.dp_max; max_par[i] = e.max_parallelism;
         cluster_tok_s[i] = e.cluster_tok_s; paper_tok_s[i] = e.paper_tok_s;
+        b_adj[i] = e.b_adj; n_sub[i] = e.n_sub_batches; n_seg[i] = e.n_segments; s_adj[i] = e.s_adj;
     }
     return 0;
 }

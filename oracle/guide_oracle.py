@@ -24,6 +24,15 @@ SIM_CLOSED_FORM_RUNS = 256        # OR-ed into the scheduler
 NO_INDEX = 2 ** 64 - 1
 
 
+# GUIDE_ORACLE_SANITIZE=1: an AddressSanitizer + UndefinedBehaviorSanitizer build (the process must then run with
+# the sanitizer runtime preloaded: LD_PRELOAD=$(gcc -print-file-name=libasan.so)); errors abort the process.
+SANITIZE = os.environ.get("GUIDE_ORACLE_SANITIZE") == "1"
+if SANITIZE:
+    _LIB = os.path.join(_HERE, "libguide_oracle_san.so")
+    GCC_FLAGS = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                 "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra", "-shared", "-fPIC"]
+
+
 def build(force: bool = False) -> str:
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", *GCC_FLAGS, "-o", _LIB, _SRC, "-lm"])
@@ -94,7 +103,7 @@ def lib():
         _lib.ora_eval_grid.argtypes = [C.POINTER(GridC), C.c_uint64, C.c_uint64, C.c_double, C.c_double, C.c_int] + \
                                       [C.c_void_p] * 7
         _lib.ora_eval_extras_grid.argtypes = [C.POINTER(GridC), C.c_uint64, C.c_uint64, C.c_uint32, C.c_int] + \
-                                             [C.c_void_p] * 5
+                                             [C.c_void_p] * 9
         _lib.ora_eval_sweep.argtypes = [C.POINTER(Model), C.POINTER(Hw), C.POINTER(Knobs), C.c_uint32,
                                         C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
                                         C.POINTER(C.c_double), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
@@ -222,12 +231,14 @@ def eval_grid(g: Grid, first=0, count=None, e_c=1.0, e_b=1.0, time_model=ROOFLIN
 
 def eval_extras_grid(g: Grid, n_gpus, first=0, count=None, time_model=ROOFLINE):
     count = g.size - first if count is None else count
-    out = dict(s_max=np.empty(count, dtype=np.uint32), dp_max=np.empty(count, dtype=np.uint32),
-               max_parallelism=np.empty(count, dtype=np.uint64), cluster_tok_s=np.empty(count),
+    u32 = ("s_max", "dp_max", "b_adj", "n_sub_batches", "n_segments", "s_adj")
+    out = {k: np.empty(count, dtype=np.uint32) for k in u32}
+    out.update(max_parallelism=np.empty(count, dtype=np.uint64), cluster_tok_s=np.empty(count),
                paper_tok_s=np.empty(count))
     rc = lib().ora_eval_extras_grid(C.byref(g.c), first, count, n_gpus, time_model,
                                     *[_ptr(out[k]) for k in ("s_max", "dp_max", "max_parallelism", "cluster_tok_s",
-                                                             "paper_tok_s")])
+                                                             "paper_tok_s", "b_adj", "n_sub_batches", "n_segments",
+                                                             "s_adj")])
     if rc:
         raise ValueError("oracle: index outside the grid")
     return out

@@ -11,7 +11,16 @@ namespace guide {
 constexpr int kWave = 64;          // CDNA wavefront width
 constexpr int kBlock = 256;        // threads per workgroup (4 waves, one per SIMD)
 constexpr int kNumAxes = 9;
-constexpr int kNumCU = 256;        // MI355X compute units; launch sizes are multiples of this
+constexpr int kNumCU = 256;        // MI355X compute units (a partitioned GPU reports fewer: see device_cus)
+
+// Compute units of the current device, for sizing persistent launches; kNumCU when the query fails.
+inline uint32_t device_cus() {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+        return (uint32_t)kNumCU;
+    return (uint32_t)n;
+}
 
 enum AxisId { AX_MODEL = 0, AX_HW, AX_BATCH, AX_SIN, AX_SOUT, AX_TP, AX_WBITS, AX_BLK, AX_MBT };
 

@@ -551,14 +551,23 @@ __global__ __launch_bounds__(kBlock) void eval_extras_kernel(GridDesc g, const D
             }
         }
         const double c_avail = hw.cap - cf.w_gpu;
-        if (out.s_max) {
-            const double q = floor(c_avail / ((double)c.kn.b * cf.kv_tok));
-            out.s_max[i] = !(c_avail > 0.0) ? 0u : (q >= 4294967295.0 ? 4294967295u : (uint32_t)q);
-        }
+        const double q = floor(c_avail / ((double)c.kn.b * cf.kv_tok));
+        const uint32_t s_max = !(c_avail > 0.0) ? 0u : (q >= 4294967295.0 ? 4294967295u : (uint32_t)q);
+        if (out.s_max) out.s_max[i] = s_max;
         if (out.dp_max) out.dp_max[i] = dp;
-        if (out.max_parallelism) {
-            const MemResult m = memory_check(cf, hw.cap, c.kn.b, c.kn.s_in, c.kn.s_out, c.kn.blk);
-            out.max_parallelism[i] = (uint64_t)dp * (uint64_t)m.b_max;
+        const MemResult m = memory_check(cf, hw.cap, c.kn.b, c.kn.s_in, c.kn.s_out, c.kn.blk);
+        if (out.max_parallelism) out.max_parallelism[i] = (uint64_t)dp * (uint64_t)m.b_max;
+        if (out.b_adj) out.b_adj[i] = c.kn.b < m.b_max ? c.kn.b : m.b_max;
+        const bool long_prompt = c.kn.s_in > c.kn.mbt;
+        if (out.n_sub_batches) {
+            uint32_t split = c.kn.mbt / c.kn.s_in;                    // prompts per pass (0 for a long prompt)
+            split = split < c.kn.b ? split : c.kn.b;
+            out.n_sub_batches[i] = long_prompt ? c.kn.b : (c.kn.b + split - 1) / split;
+        }
+        if (out.n_segments) out.n_segments[i] = long_prompt ? (c.kn.s_in - 1) / c.kn.mbt + 1 : 1u;
+        if (out.s_adj) {
+            const uint32_t len = c.kn.s_in + c.kn.s_out;              // both below 2^31
+            out.s_adj[i] = len < s_max ? len : s_max;
         }
         if (out.cluster_tok_s) out.cluster_tok_s[i] = (double)dp * tok_s;
         if (out.paper_tok_s)
@@ -568,7 +577,7 @@ __global__ __launch_bounds__(kBlock) void eval_extras_kernel(GridDesc g, const D
 
 static uint32_t blocks_for(uint32_t count) {
     const uint32_t need = (count + kBlock - 1) / kBlock;
-    const uint32_t cap = kNumCU * 8;
+    const uint32_t cap = device_cus() * 8;
     return need < cap ? need : cap;
 }
 
@@ -576,7 +585,10 @@ static uint32_t tile_blocks(uint32_t first, uint32_t count, uint32_t ts) {
     const uint32_t n_tiles = (first + count - 1) / ts - first / ts + 1;
     // two persistent blocks per compute unit: every wave loops over several batches of 64 tiles, so the
     // stores of one batch overlap the arithmetic of the next (measured best among 1..8 blocks per CU)
-    const uint32_t need = (n_tiles + kBlock - 1) / kBlock, cap = 2 * kNumCU;
+    // (every block writes one top-k partial and one sample partial when selections are folded in)
+    uint32_t cap = 2 * device_cus();
+    cap = cap < kMaxSamplePartials ? cap : kMaxSamplePartials;
+    const uint32_t need = (n_tiles + kBlock - 1) / kBlock;
     return need < cap ? need : cap;
 }
 
@@ -588,7 +600,7 @@ static void launch_tile(const GridDesc &g, const DevTables *tab, const void *til
                         uint32_t count, double re_c, double re_b, const guide_metrics &out, const FusedSelect *fs,
                         hipStream_t stream, LaunchTiming tm) {
     const dim3 grid(tile_blocks(first, count, NB * NM)), block(kBlock);
-    static_assert(2 * kNumCU <= kMaxSamplePartials && 2 * kNumCU <= kSelBlocks, "one partial per block");
+    static_assert(kMaxSamplePartials <= kSelBlocks, "one partial per block");
     // with timing events the launch goes through the extended call, which attaches them to the dispatch
     const uint32_t stride = count > kSampleRows ? count / kSampleRows : 1;
     const TileLds *tables = (const TileLds *)tile_tables;

@@ -38,6 +38,10 @@ struct guide_ctx {
     uint32_t prof_used = 0;              // timed launches since the last read
     uint32_t prof_every = 1, prof_seen = 0;   // every prof_every-th launch is timed
     hipStream_t prof_stream = nullptr;
+    // the stream of the last enqueueing call, and the event that orders a call on another stream after it
+    hipStream_t last_stream = nullptr;
+    bool used = false;
+    hipEvent_t order_ev = nullptr;
     char err[256] = {0};
 };
 static_assert(guide_ctx::kSlotBytes >= sizeof(DevTables), "staging slot too small");
@@ -132,6 +136,15 @@ int prepare_grid(guide_ctx *ctx, const guide_grid *grid, GridDesc *desc, uint64_
         total *= ax->count;
         if (total >= (1ull << 32)) return fail(ctx, GUIDE_E_RANGE, "grid has 2^32 or more configurations");
     }
+    // block rounding adds s_in + s_out + kv_block - 1 in 32 bits
+    uint64_t longest = 0;
+    for (int a : {AX_SIN, AX_SOUT, AX_BLK}) {
+        uint32_t m = 0;
+        for (uint32_t i = 0; i < axis_of(grid, a)->count; ++i) m = ctx->host_tab.axis_vals[a][i] > m ? ctx->host_tab.axis_vals[a][i] : m;
+        longest += m;
+    }
+    if (longest >= (1ull << 32))
+        return fail(ctx, GUIDE_E_RANGE, "largest s_in + s_out + kv_block is 2^32 or more");
     desc->n_models = ctx->n_models;
     desc->n_hw = ctx->n_hw;
     *size = total;
@@ -174,6 +187,24 @@ int upload_grid_tables(guide_ctx *ctx, const GridDesc &desc, hipStream_t stream)
     if (e != hipSuccess) return hip_fail(ctx, e, "tile tables launch");
     memcpy(&ctx->tile_desc, &desc, sizeof desc);
     ctx->tile_gen = ctx->tab_gen;
+    return GUIDE_OK;
+}
+
+// Calls on one context share its device tables and scratch.  A call that arrives on another stream than the
+// previous one first makes its stream wait for everything enqueued on the previous stream (no host wait; nothing
+// happens while the stream stays the same).
+int order_after_previous(guide_ctx *ctx, hipStream_t stream) {
+    if (ctx->used && stream != ctx->last_stream) {
+        hipError_t e = hipEventRecord(ctx->order_ev, ctx->last_stream);
+        if (e == hipSuccess) e = hipStreamWaitEvent(stream, ctx->order_ev, 0);
+        if (e != hipSuccess) {                     // e.g. the previous stream no longer exists
+            (void)hipGetLastError();
+            e = hipDeviceSynchronize();
+        }
+        if (e != hipSuccess) return hip_fail(ctx, e, "ordering after the previous stream");
+    }
+    ctx->used = true;
+    ctx->last_stream = stream;
     return GUIDE_OK;
 }
 
@@ -271,6 +302,12 @@ int guide_create(guide_ctx **out, int device) {
         guide_destroy(ctx);
         return GUIDE_E_DEVICE;
     }
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess || strncmp(prop.gcnArchName, "gfx950", 6) != 0 ||
+        prop.multiProcessorCount <= 0 || hipEventCreateWithFlags(&ctx->order_ev, hipEventDisableTiming) != hipSuccess) {
+        guide_destroy(ctx);                        // the kernels are built for gfx950 only
+        return GUIDE_E_DEVICE;
+    }
     // address of this device's copy of the static scratch (the device is current here)
     if (device < kMaxDevices && !g_static_scratch[device]) {
         void *p = nullptr;
@@ -305,6 +342,7 @@ void guide_destroy(guide_ctx *ctx) {
         if (ctx->slot[i]) (void)hipHostFree(ctx->slot[i]);
     }
     for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
+    if (ctx->order_ev) (void)hipEventDestroy(ctx->order_ev);
     delete ctx;
 }
 
@@ -362,6 +400,7 @@ int guide_eval_grid(guide_ctx *ctx, const guide_grid *grid, uint64_t first, uint
     if (count == 0) return GUIDE_OK;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
+    if (int rc_order = order_after_previous(ctx, stream)) return rc_order;
     for (uint32_t i = 0; i < n_eff; ++i) {
         ctx->host_tab.eff_c[i] = eff->e_c[i];
         ctx->host_tab.eff_b[i] = eff->e_b[i];
@@ -463,6 +502,7 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
     }
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
+    if (int rc_order = order_after_previous(ctx, stream)) return rc_order;
     uint32_t n_blocks = 0;
     const bool fold = topk_folded;                      // then the Pareto row sample is taken there as well
     if (count > 0) {
@@ -576,6 +616,7 @@ int guide_eval_extras(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
     if (count == 0) return GUIDE_OK;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
+    if (int rc_order = order_after_previous(ctx, stream)) return rc_order;
     rc = upload_tables(ctx, stream);
     if (rc) return rc;
     const hipError_t e = launch_eval_extras(desc, ctx->dev_tab, (uint32_t)first, (uint32_t)count, n_gpus,
@@ -606,6 +647,7 @@ int guide_select_static(guide_ctx *ctx, const guide_select_spec *spec, uint64_t 
         return fail(ctx, GUIDE_E_DEVICE, "no static scratch on device %d", ctx->device);
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
+    if (int rc_order = order_after_previous(ctx, stream)) return rc_order;
     unsigned char *base = (unsigned char *)g_static_scratch[ctx->device];
     void *tables = base, *workspace = base + kSelectScratchMax;
     const hipError_t e = spec->mode == GUIDE_SELECT_TOPK ? launch_select_topk(*spec, n, *out, workspace, tables, stream)
@@ -625,6 +667,7 @@ int guide_select(guide_ctx *ctx, const guide_select_spec *spec, uint64_t n, cons
         return fail(ctx, GUIDE_E_NOMEM, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
+    if (int rc_order = order_after_previous(ctx, stream)) return rc_order;
     const hipError_t e = spec->mode == GUIDE_SELECT_TOPK
                              ? launch_select_topk(*spec, n, *out, workspace, ctx->select_scratch, stream)
                              : launch_select_pareto(*spec, n, *out, workspace, ctx->select_scratch, stream);
@@ -636,7 +679,8 @@ static int check_select_args(guide_ctx *ctx, const guide_select_spec *spec, uint
     if (!spec || !out) return fail(ctx, GUIDE_E_ARG, "spec or out is NULL");
     if (spec->mode != GUIDE_SELECT_TOPK && spec->mode != GUIDE_SELECT_PARETO)
         return fail(ctx, GUIDE_E_ARG, "unknown select mode %u", spec->mode);
-    if (n >= (1ull << 32)) return fail(ctx, GUIDE_E_RANGE, "2^32 or more rows");
+    if (n > GUIDE_SELECT_MAX_ROWS)               // row indices are 32-bit and blocks read in units of 2048 rows
+        return fail(ctx, GUIDE_E_RANGE, "more than 2^32 - 4096 rows");
     if (spec->n_constraints > GUIDE_MAX_CONSTRAINTS)
         return fail(ctx, GUIDE_E_ARG, "more than %d constraints", GUIDE_MAX_CONSTRAINTS);
     for (uint32_t c = 0; c < spec->n_constraints; ++c)
@@ -704,6 +748,8 @@ int guide_eval_sampled(guide_ctx *ctx, const guide_space *space, uint64_t seed, 
     if (rc) { delete t; return rc; }
     DeviceGuard guard(ctx->device);
     if (!guard.ok) { delete t; return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device); }
+    rc = order_after_previous(ctx, stream);
+    if (rc) { delete t; return rc; }
     rc = stage_upload(ctx, ctx->dev_space, t, sizeof(SpaceTables), stream);
     delete t;
     if (rc) return rc;
@@ -762,6 +808,8 @@ int guide_simulate(guide_ctx *ctx, const guide_grid *grid, const uint32_t *cfg_i
     }
     DeviceGuard guard(ctx->device);
     if (!guard.ok) { delete t; return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device); }
+    rc = order_after_previous(ctx, stream);
+    if (rc) { delete t; return rc; }
     rc = stage_upload(ctx, ctx->dev_trace, t, sizeof(TraceDev), stream);
     delete t;
     if (rc) return rc;

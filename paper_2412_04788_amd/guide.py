@@ -14,7 +14,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libguide.so")
 
-OK, E_ARG, E_RANGE, E_NOMEM, E_DEVICE, E_CAPACITY = 0, -1, -2, -3, -4, -5
+OK, E_ARG, E_RANGE, E_NOMEM, E_DEVICE = 0, -1, -2, -3, -4
 TIME_ROOFLINE, TIME_ADDITIVE = 0, 1
 AXIS_GEOM2, AXIS_TABLE = 0, 1
 SELECT_TOPK, SELECT_PARETO = 0, 1
@@ -61,7 +61,8 @@ class CEff(C.Structure):
 METRIC_COLUMNS = ("t_prefill", "t_decode", "t_batch", "decode_tok_s", "cost", "b_max", "feasible")
 STATS_COLUMNS = ("ttft_mean", "ttft_p10", "ttft_p90", "t_batch_mean", "t_batch_p10", "t_batch_p90", "cost", "b_max",
                  "feasible")
-EXTRAS_COLUMNS = ("s_max", "dp_max", "max_parallelism", "cluster_tok_s", "paper_tok_s")
+EXTRAS_COLUMNS = ("s_max", "dp_max", "max_parallelism", "cluster_tok_s", "paper_tok_s", "b_adj", "n_sub_batches",
+                  "n_segments", "s_adj")
 SAMPLED_COLUMNS = ("feasible_count", "win_val", "win_idx", "hist", "t_prefill", "t_batch", "cost", "b_max",
                    "feasible", "bucket")
 SIM_COLUMNS = ("ttft_p50", "ttft_p99", "mean_tpot", "tokens_s", "status", "n_steps", "n_request_steps")

@@ -216,12 +216,17 @@ def test_cluster_extras(ora, torch_cuda):
                    max_parallelism=torch.empty(count, dtype=torch.int64, device="cuda"),
                    cluster_tok_s=torch.empty(count, dtype=torch.float64, device="cuda"),
                    paper_tok_s=torch.empty(count, dtype=torch.float64, device="cuda"))
+        out.update({k: torch.empty(count, dtype=torch.int32, device="cuda")
+                    for k in ("b_adj", "n_sub_batches", "n_segments", "s_adj")})
         ctx.eval_extras(bridge.gpu_grid(g), first, count, n_gpus, out, time_model=tm)
         torch.cuda.synchronize()
         exp = ora.eval_extras_grid(bridge.ora_grid(g), n_gpus, first, count, time_model=tm)
         np.testing.assert_array_equal(bridge.to_np(out["s_max"], np.uint32), exp["s_max"])
         np.testing.assert_array_equal(bridge.to_np(out["dp_max"], np.uint32), exp["dp_max"])
         np.testing.assert_array_equal(bridge.to_np(out["max_parallelism"], np.uint64), exp["max_parallelism"])
+        for k in ("b_adj", "n_sub_batches", "n_segments", "s_adj"):
+            np.testing.assert_array_equal(bridge.to_np(out[k], np.uint32), exp[k], err_msg=k)
+        assert exp["n_segments"].max() > 1 and exp["n_sub_batches"].max() > 1 and (exp["b_adj"] < 64).any()
         for k in ("cluster_tok_s", "paper_tok_s"):
             assert bridge.rel_err(bridge.to_np(out[k]), exp[k]).max() <= TOL, k
     # NULL columns are skipped

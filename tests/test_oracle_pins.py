@@ -887,3 +887,34 @@ def test_closed_form_runs_simulation_against_stepping(ora, scheduler):
                              300 + (1 - scheduler) * 701, 1 + (1 - scheduler))["t_pass"]
     assert s0["ttft"][1] == pytest.approx(second, rel=1e-13) and s1["ttft"][1] == s0["ttft"][1]
     assert s1["n_steps"] == s0["n_steps"] and s1["n_request_steps"] == s0["n_request_steps"]
+
+
+def test_adjustment_columns_by_hand(ora):
+    """Adjusted batch and length, sub-batch and segment counts (Dynamic Batch Size / Sequence Length Adjustment)."""
+    m = wl.DENSE_13B
+    om = bridge.ora_model(m)
+    w = 2 * ora.params_total(om)
+    kv_tok = 2 * m.L * m.d * 2
+    # capacity for exactly 5 requests of 1000 + 24 tokens; a batch of 8 is adjusted to 5, a batch of 4 stays
+    h = wl.Hardware(1e15, 5e12, w + 5 * 1024 * kv_tok, 4e11)
+    g = wl.make_grid([m], [h], wl.Axis.table([4, 8, 10]), wl.Axis.table([1000, 5000]), wl.Axis.table([24]),
+                     wl.Axis.table([1]), wl.Axis.table([16]), wl.Axis.table([16]), wl.Axis.table([2048, 4096]))
+    e = ora.eval_extras_grid(bridge.ora_grid(g), 8)
+
+    def at(b, s_in, mbt):
+        return g.flat((0, 0, (4, 8, 10).index(b), (1000, 5000).index(s_in), 0, 0, 0, 0, (2048, 4096).index(mbt)))
+
+    assert [e["b_adj"][at(b, 1000, 2048)] for b in (4, 8, 10)] == [4, 5, 5]
+    # 10 prompts of 1000 under 4096 tokens per pass: 4 + 4 + 2; under 2048: five pairs; a batch of 4 under 4096: one pass
+    assert e["n_sub_batches"][at(10, 1000, 4096)] == 3 and e["n_sub_batches"][at(10, 1000, 2048)] == 5
+    assert e["n_sub_batches"][at(4, 1000, 4096)] == 1 and e["n_segments"][at(10, 1000, 4096)] == 1
+    # a 5000-token prompt: 3 segments of 2048 (2048 + 2048 + 904), 2 of 4096; every request runs alone
+    assert e["n_segments"][at(8, 5000, 2048)] == 3 and e["n_segments"][at(8, 5000, 4096)] == 2
+    assert e["n_sub_batches"][at(8, 5000, 2048)] == 8
+    # S_max = floor(5 * 1024 / b) tokens per sequence: 1280 for b = 4 (1024 needed: unchanged), 512 for b = 10
+    assert e["s_max"][at(4, 1000, 2048)] == 1280 and e["s_adj"][at(4, 1000, 2048)] == 1024
+    assert e["s_max"][at(10, 1000, 2048)] == 512 and e["s_adj"][at(10, 1000, 2048)] == 512
+    # the prefill evaluator runs exactly that many passes
+    oh = bridge.ora_hw(h)
+    one = ora.pass_detail(om, oh, 1, 16, 2000, 2 * 1000 * 1000, 2000, 2)["t_pass"]
+    assert ora.prefill(om, oh, ora.knobs(10, 1000, 24, mbt=2048)) == pytest.approx(5 * one, rel=1e-15)
