@@ -72,7 +72,7 @@ int main(int argc, char **argv) {
     EXPECT(guide_eval_grid(ctx, NULL, 0, 1, NULL, 0, &out, NULL, NULL), GUIDE_E_ARG);
     EXPECT(guide_eval_grid(ctx, &grid, 0, 1, NULL, 7, &out, NULL, NULL), GUIDE_E_ARG);     /* unknown time model */
     EXPECT(guide_eval_grid(ctx, &grid, 0, 1, NULL, 0, NULL, NULL, NULL), GUIDE_E_ARG);
-    EXPECT(guide_eval_grid(ctx, &grid, 3, 2, NULL, 0, &out, NULL, NULL), GUIDE_E_RANGE);   /* grid has 4 rows */
+    EXPECT(guide_eval_grid(ctx, &grid, 3, 2, NULL, 0, &out, NULL, NULL), GUIDE_E_RANGE);   /* grid has 2 rows */
     EXPECT(guide_eval_grid(ctx, &grid, 0, 0, NULL, 0, &out, NULL, NULL), GUIDE_OK);        /* count 0: no-op */
     { guide_grid g2 = grid; g2.batch.count = 0; EXPECT(guide_eval_grid(ctx, &g2, 0, 1, NULL, 0, &out, NULL, NULL), GUIDE_E_ARG); }
     { guide_grid g2 = grid; g2.tp.kind = 9; EXPECT(guide_eval_grid(ctx, &g2, 0, 1, NULL, 0, &out, NULL, NULL), GUIDE_E_ARG); }
@@ -144,12 +144,12 @@ int main(int argc, char **argv) {
         guide_column_select cs; memset(&cs, 0, sizeof cs);
         cs.mode = GUIDE_SELECT_TOPK; cs.objective = GUIDE_NUM_COLS; cs.k = 1;
         cs.out.idx = dummy_u64; cs.out.val = dummy_f64; cs.out.count = dummy_u64;
-        EXPECT(guide_eval_select(ctx, &grid, 0, 4, NULL, 0, &out, &cs, 1, dummy_u64, 1 << 20, NULL), GUIDE_E_ARG);   /* column id */
+        EXPECT(guide_eval_select(ctx, &grid, 0, 2, NULL, 0, &out, &cs, 1, dummy_u64, 1 << 20, NULL), GUIDE_E_ARG);   /* column id */
         cs.objective = GUIDE_COL_T_BATCH;
-        EXPECT(guide_eval_select(ctx, &grid, 0, 4, NULL, 0, &out, &cs, 3, dummy_u64, 1 << 20, NULL), GUIDE_E_ARG);   /* n_sel */
-        EXPECT(guide_eval_select(ctx, &grid, 0, 4, NULL, 0, &out, &cs, 1, NULL, 0, NULL), GUIDE_E_NOMEM);
+        EXPECT(guide_eval_select(ctx, &grid, 0, 2, NULL, 0, &out, &cs, 3, dummy_u64, 1 << 20, NULL), GUIDE_E_ARG);   /* n_sel */
+        EXPECT(guide_eval_select(ctx, &grid, 0, 2, NULL, 0, &out, &cs, 1, NULL, 0, NULL), GUIDE_E_NOMEM);
         cs.mode = GUIDE_SELECT_PARETO; cs.objective_y = GUIDE_COL_COST;                                        /* cost column not stored */
-        EXPECT(guide_eval_select(ctx, &grid, 0, 4, NULL, 0, &out, &cs, 1, dummy_u64, 1 << 26, NULL), GUIDE_E_ARG);
+        EXPECT(guide_eval_select(ctx, &grid, 0, 2, NULL, 0, &out, &cs, 1, dummy_u64, 1 << 26, NULL), GUIDE_E_ARG);
     }
     EXPECT(strlen(guide_last_error(ctx)) > 0 ? 0 : 1, 0);
     guide_destroy(ctx);
