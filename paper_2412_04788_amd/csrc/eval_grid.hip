@@ -140,6 +140,70 @@ __global__ __launch_bounds__(kBlock) void tile_tables_kernel(GridDesc g, const D
     }
 }
 
+// Row sample for a Pareto selection over the rows being evaluated, taken by extra blocks of the evaluation kernel
+// (block `rb` of them; kBlock samples each): sample number k is row k * stride of the evaluated range.  The
+// sampled rows are evaluated here from scratch rather than read back, so the sample does not wait for the columns;
+// it only fixes the range of x that the selection's bins slice (any range is correct, a good one is fast).
+// Also puts the tables that the selection's kernels accumulate into in their neutral state.
+template <bool ADDITIVE>
+__device__ inline void sample_rider(const GridLds &s, const GridDesc &g, uint32_t rb, uint32_t n_rider_blocks, uint32_t first,
+                                    uint32_t count, double re_c, double re_b, const FusedSelect &fs) {
+    constexpr int kWaves = kBlock / kWave;
+    __shared__ uint64_t s_lo[kWaves];
+    __shared__ Pair s_best[kWaves];
+    SelectScratch *sc = (SelectScratch *)fs.scratch;
+    const uint32_t k = rb * kBlock + threadIdx.x;
+    const uint32_t n_samples = n_rider_blocks * kBlock;
+    for (uint32_t i = k; i < kBins; i += n_samples) {
+        sc->bin_min[i] = kNone;
+        sc->bin_cnt[i] = 0;
+    }
+    if (k == 0) sc->counters[0] = 0;
+    const uint32_t stride = count > n_samples ? count / n_samples : 1;
+    uint64_t lo = kNone;
+    Pair best = {kNone, kNone};
+    if ((uint64_t)k * stride < count) {
+        const Candidate c = decode_index(s, g, first + k * stride);
+        const Coef cf = make_coef(s.models[c.model], c.kn.p, c.kn.wbits);
+        const HwRecip hw = s.hw[c.hw];
+        const TimeCoef tc = make_time_coef(cf, hw.r_peak * re_c, hw.r_bw * re_b, hw.r_link, hw.lat);
+        const EvalResult r = evaluate_times<ADDITIVE>(tc, c.kn);
+        const double t_batch = r.t_prefill + r.t_decode;
+        const double tok_s = c.kn.s_out > 1 ? (double)c.kn.b * (double)(c.kn.s_out - 1) / r.t_decode : 0.0;
+        const double cost = cost_of(c.kn, t_batch);
+        auto col = [&](uint32_t id) {
+            return id == GUIDE_COL_T_PREFILL ? r.t_prefill
+                   : id == GUIDE_COL_T_DECODE ? r.t_decode
+                   : id == GUIDE_COL_T_BATCH ? t_batch
+                   : id == GUIDE_COL_DECODE_TOK_S ? tok_s : cost;
+        };
+        const double x = col(fs.pareto_x), y = col(fs.pareto_y);
+        bool ok = x == x && y == y;
+        for (uint32_t q = 0; q < fs.pareto_filter.n_con; ++q) ok = ok && col(fs.pareto_filter.col[q]) <= fs.pareto_filter.cap[q];
+        if (ok && fs.pareto_filter.use_feasible)
+            ok = memory_check(cf, hw.cap, c.kn.b, c.kn.s_in, c.kn.s_out, c.kn.blk).feasible;
+        if (ok) {
+            lo = key_of(x);
+            best = Pair{key_of(y), lo};
+        }
+    }
+    lo = wave_min(lo);
+    best = wave_min(best);
+    if (threadIdx.x % kWave == 0) {
+        s_lo[threadIdx.x / kWave] = lo;
+        s_best[threadIdx.x / kWave] = best;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int wv = 1; wv < kWaves; ++wv) {
+            lo = min_u64(lo, s_lo[wv]);
+            best = pair_min(best, s_best[wv]);
+        }
+        sc->sample_lo[rb] = lo;
+        sc->sample_best[rb] = best;
+    }
+}
+
 // FUSED: selections folded in (FusedSelect); every block then writes its top-K partials and / or its
 // sample partial, also when it owns no tile.
 template <bool ADDITIVE, int NB, int NM, bool FUSED>
@@ -188,12 +252,18 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
         }
     }
     __syncthreads();
+    if (!FUSED && fs.rider_blocks && blockIdx.x >= gridDim.x - fs.rider_blocks) {      // block-uniform
+        sample_rider<ADDITIVE>(s.g, g, blockIdx.x - (gridDim.x - fs.rider_blocks), fs.rider_blocks, first, count, re_c,
+                               re_b, fs);
+        return;
+    }
+    const uint32_t n_main_blocks = gridDim.x - (FUSED ? 0u : fs.rider_blocks);
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     double *xw = s_x[wave];
     const uint32_t t_first = first / TS;
     const uint32_t n_tiles = (first + count - 1) / TS - t_first + 1;
     const uint32_t last = first + count;                       // exclusive; count > 0, no overflow (grid < 2^32)
-    for (uint32_t tb = (blockIdx.x * kWaves + wave) * kWave; tb < n_tiles; tb += gridDim.x * kWaves * kWave) {
+    for (uint32_t tb = (blockIdx.x * kWaves + wave) * kWave; tb < n_tiles; tb += n_main_blocks * kWaves * kWave) {
         const uint32_t tl = tb + lane < n_tiles ? tb + lane : n_tiles - 1;   // idle lanes repeat the last tile
         // digits of the seven slow axes
         uint32_t dg[AX_BLK];
@@ -594,17 +664,25 @@ static uint32_t tile_blocks(uint32_t first, uint32_t count, uint32_t ts) {
 
 // Sampling of rows for the Pareto bin range: row i is a sample when i = q * stride with q < kSampleRows.
 constexpr uint32_t kSampleRows = 16384;
+constexpr uint32_t kRiderBlocks = kSampleRows / kBlock;     // sample blocks appended to a plain evaluation
 
 template <bool ADDITIVE, int NB, int NM>
 static void launch_tile(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
                         uint32_t count, double re_c, double re_b, const guide_metrics &out, const FusedSelect *fs,
                         hipStream_t stream, LaunchTiming tm) {
-    const dim3 grid(tile_blocks(first, count, NB * NM)), block(kBlock);
+    const bool rider = fs && fs->rider_blocks;          // a plain evaluation with sample blocks appended
+    const dim3 grid(tile_blocks(first, count, NB * NM) + (rider ? fs->rider_blocks : 0u)), block(kBlock);
     static_assert(kMaxSamplePartials <= kSelBlocks, "one partial per block");
     // with timing events the launch goes through the extended call, which attaches them to the dispatch
     const uint32_t stride = count > kSampleRows ? count / kSampleRows : 1;
     const TileLds *tables = (const TileLds *)tile_tables;
-    if (fs && tm.start)
+    if (rider && tm.start)
+        hipExtLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM, false>), grid, block, 0, stream, tm.start, tm.stop, 0, g,
+                              tab, first, count, re_c, re_b, out, *fs, Div32{}, 0u, tables);
+    else if (rider)
+        hipLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM, false>), grid, block, 0, stream, g, tab, first, count, re_c,
+                           re_b, out, *fs, Div32{}, 0u, tables);
+    else if (fs && tm.start)
         hipExtLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM, true>), grid, block, 0, stream, tm.start, tm.stop, 0, g, tab,
                               first, count, re_c, re_b, out, *fs, make_div32(stride), kSampleRows, tables);
     else if (fs)
@@ -667,11 +745,21 @@ hipError_t launch_eval_grid_fused(const GridDesc &g, const DevTables *tab, const
 
 hipError_t launch_eval_grid(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
                             uint32_t count, double e_c, double e_b, bool additive, const guide_metrics &out,
-                            hipStream_t stream, LaunchTiming tm) {
+                            hipStream_t stream, LaunchTiming tm, const FusedSelect *sample, uint32_t *sample_partials) {
     const dim3 grid(blocks_for(count)), block(kBlock);
     const double re_c = 1.0 / e_c, re_b = 1.0 / e_b;
-    if (additive ? dispatch_tile<true>(g, tab, tile_tables, first, count, re_c, re_b, out, nullptr, stream, nullptr, tm)
-                 : dispatch_tile<false>(g, tab, tile_tables, first, count, re_c, re_b, out, nullptr, stream, nullptr, tm))
+    FusedSelect rider;
+    const FusedSelect *fs = nullptr;
+    if (sample_partials) *sample_partials = 0;
+    if (sample && sample_partials && eval_grid_can_fuse(g)) {
+        rider = *sample;
+        rider.topk = 0;
+        rider.rider_blocks = kRiderBlocks;
+        fs = &rider;
+        *sample_partials = kRiderBlocks;
+    }
+    if (additive ? dispatch_tile<true>(g, tab, tile_tables, first, count, re_c, re_b, out, fs, stream, nullptr, tm)
+                 : dispatch_tile<false>(g, tab, tile_tables, first, count, re_c, re_b, out, fs, stream, nullptr, tm))
         return hipGetLastError();
     if (additive && tm.start)
         hipExtLaunchKernelGGL(eval_grid_kernel<true>, grid, block, 0, stream, tm.start, tm.stop, 0, g, tab, first, count,

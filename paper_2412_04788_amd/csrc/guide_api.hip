@@ -503,7 +503,7 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
     if (int rc_order = order_after_previous(ctx, stream)) return rc_order;
-    uint32_t n_blocks = 0;
+    uint32_t n_blocks = 0, sampled_partials = 0;
     const bool fold = topk_folded;                      // then the Pareto row sample is taken there as well
     if (count > 0) {
         if (n_eff) {
@@ -532,6 +532,17 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
             }
             e = launch_eval_grid_fused(desc, ctx->dev_tab, ctx->dev_tile, (uint32_t)first, (uint32_t)count, e_c, e_b,
                                        additive, *out, fs, stream, &n_blocks, timing);
+        } else if (pareto) {
+            // the row sample of the Pareto selection is taken by extra blocks of the evaluation kernel
+            FusedSelect fs;
+            memset(&fs, 0, sizeof fs);
+            fs.pareto = 1;
+            fs.pareto_x = pareto->objective;
+            fs.pareto_y = pareto->objective_y;
+            fs.pareto_filter = filter_of(*pareto);
+            fs.scratch = ctx->select_scratch;
+            e = launch_eval_grid(desc, ctx->dev_tab, ctx->dev_tile, (uint32_t)first, (uint32_t)count, e_c, e_b, additive,
+                                 *out, stream, timing, &fs, &sampled_partials);
         } else {
             e = launch_eval_grid(desc, ctx->dev_tab, ctx->dev_tile, (uint32_t)first, (uint32_t)count, e_c, e_b, additive,
                                  *out, stream, timing);
@@ -540,9 +551,9 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
     }
     hipError_t e = hipSuccess;
     if (topk && pareto && count > 0 && !fold) {
-        // both selections read stored columns: four launches, the small kernels ride along with the large ones
+        // both selections read stored columns: the small kernels ride along with the large ones
         e = launch_select_both(spec_of(*topk, *out), topk->out, ws_of[topk - sel], spec_of(*pareto, *out), pareto->out,
-                               ws_of[pareto - sel], count, ctx->select_scratch, stream);
+                               ws_of[pareto - sel], count, ctx->select_scratch, stream, sampled_partials);
     } else {
         for (uint32_t i = 0; i < n_sel && e == hipSuccess; ++i) {
             const guide_column_select &c = sel[i];
@@ -556,6 +567,9 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
             } else if (fold) {
                 e = launch_pareto_sampled(spec, count, c.out, ws_of[i], ctx->select_scratch, n_blocks, ws_of[topk - sel],
                                           n_blocks, topk->k, &topk->out, stream);
+            } else if (sampled_partials && count > 0) {
+                e = launch_pareto_sampled(spec, count, c.out, ws_of[i], ctx->select_scratch, sampled_partials, nullptr, 0,
+                                          0, nullptr, stream);
             } else {
                 e = launch_select_pareto(spec, count, c.out, ws_of[i], ctx->select_scratch, stream);
             }

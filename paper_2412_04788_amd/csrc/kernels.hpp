@@ -14,9 +14,6 @@ hipError_t launch_tile_tables(const GridDesc &g, const DevTables *tab, void *til
 struct LaunchTiming {
     hipEvent_t start = nullptr, stop = nullptr;
 };
-hipError_t launch_eval_grid(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
-                            uint32_t count, double e_c, double e_b, bool additive, const guide_metrics &out,
-                            hipStream_t stream, LaunchTiming timing = LaunchTiming());
 hipError_t launch_eval_sweep(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, uint32_t n_eff,
                              bool additive, const guide_stats &out, hipStream_t stream);
 
@@ -30,6 +27,10 @@ struct FusedFilter {
     double cap[GUIDE_MAX_CONSTRAINTS];
 };
 struct FusedSelect {
+    // rider_blocks != 0 (plain evaluation only): that many extra blocks at the end of the grid take the row sample
+    // of a Pareto selection over the evaluated rows (pareto_x, pareto_y, pareto_filter, scratch below) by
+    // evaluating the sampled rows themselves, beside the blocks that evaluate and store the grid.
+    uint32_t rider_blocks;
     uint32_t topk, topk_obj;                    // topk != 0: least kFusedTopK rows by column topk_obj
     FusedFilter topk_filter;
     void *topk_ws;                              // block partials, layout of the top-k pass
@@ -37,6 +38,12 @@ struct FusedSelect {
     FusedFilter pareto_filter;
     void *scratch;                              // scratch of the Pareto kernels
 };
+// sample != nullptr (grids with a tile kernel only): extra blocks sample the rows for the Pareto selection that
+// sample->pareto_* describe; *sample_partials receives the number of block partials they write (0: not taken).
+hipError_t launch_eval_grid(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
+                            uint32_t count, double e_c, double e_b, bool additive, const guide_metrics &out,
+                            hipStream_t stream, LaunchTiming timing = LaunchTiming(), const FusedSelect *sample = nullptr,
+                            uint32_t *sample_partials = nullptr);
 // True when the grid's two fastest axes have a compiled tile kernel (the only one that folds selections in).
 bool eval_grid_can_fuse(const GridDesc &g);
 // As launch_eval_grid; *n_blocks receives the number of blocks that wrote partials.
@@ -50,9 +57,11 @@ hipError_t launch_pareto_sampled(const guide_select_spec &spec, uint64_t n, cons
                                  void *scratch, uint32_t n_partials, void *merge_ws, uint32_t merge_blocks,
                                  uint32_t merge_k, const guide_select_out *merge_out, hipStream_t stream);
 size_t topk_partials_bytes();
+// sampled_partials != 0: the caller's evaluation kernel has already sampled the rows (that many block partials)
+// and reset the bin tables, so no sample is launched.
 hipError_t launch_select_both(const guide_select_spec &topk, const guide_select_out &topk_out, void *topk_ws,
                               const guide_select_spec &pareto, const guide_select_out &pareto_out, void *pareto_ws,
-                              uint64_t n, void *scratch, hipStream_t stream);
+                              uint64_t n, void *scratch, hipStream_t stream, uint32_t sampled_partials = 0);
 
 size_t select_workspace_bytes(const guide_select_spec &spec, uint64_t n);
 hipError_t launch_eval_extras(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, uint32_t n_gpus,

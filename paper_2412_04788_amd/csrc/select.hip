@@ -108,7 +108,11 @@ RowFilter make_filter(const guide_select_spec &s) {
 uint32_t blocks_for(uint64_t n) {
     uint64_t need = (n + kBlock - 1) / kBlock;
     if (need == 0) need = 1;
-    return (uint32_t)(need < kSelBlocks ? need : kSelBlocks);
+    // two blocks per compute unit: with more, the per-block tables (32 KB each in the Pareto passes) cost more
+    // than the extra blocks hide (512 and 768 blocks measured alike on 1.9M rows, 1024 and 256 slower)
+    uint64_t cap = 2 * (uint64_t)device_cus();
+    cap = cap < kSelBlocks ? cap : kSelBlocks;
+    return (uint32_t)(need < cap ? need : cap);
 }
 
 // ------------------------------------------------------- top-k, one group
@@ -1033,17 +1037,19 @@ static bool shares_columns(const guide_select_spec &topk, const guide_select_spe
 // survivors, finish + merge).
 hipError_t launch_select_both(const guide_select_spec &topk, const guide_select_out &topk_out, void *topk_ws,
                               const guide_select_spec &pareto, const guide_select_out &pareto_out, void *pareto_ws_,
-                              uint64_t n, void *scratch, hipStream_t stream) {
+                              uint64_t n, void *scratch, hipStream_t stream, uint32_t sampled_partials) {
     SelectScratch *sc = (SelectScratch *)scratch;
     const int K = partial_width(topk.k);
     SharedTopk shared;
     const bool folded = shares_columns(topk, pareto, &shared);
+    const bool sampled = sampled_partials != 0;         // the caller's own kernel has sampled the rows and reset the tables
     if (folded) {
         shared.w = top1_ws(topk_ws);
-        hipLaunchKernelGGL(pareto_prepare_kernel, dim3(kSampleBlocks), dim3(kBlock), 0, stream, pareto.objective,
-                           pareto.objective_y, make_filter(pareto), (uint32_t)n, sc);
+        if (!sampled)
+            hipLaunchKernelGGL(pareto_prepare_kernel, dim3(kSampleBlocks), dim3(kBlock), 0, stream, pareto.objective,
+                               pareto.objective_y, make_filter(pareto), (uint32_t)n, sc);
     } else {
-        const SampleRider sample{1u, pareto.objective, pareto.objective_y, make_filter(pareto), sc};
+        const SampleRider sample{sampled ? 0u : 1u, pareto.objective, pareto.objective_y, make_filter(pareto), sc};
         launch_top1_pass(topk, n, topk_ws, sample, stream);
     }
     MergeRider rider{};
@@ -1051,8 +1057,8 @@ hipError_t launch_select_both(const guide_select_spec &topk, const guide_select_
         rider = MergeRider{top1_ws(topk_ws), blocks_for(n), topk.k, (uint32_t)K, topk_out.idx, topk_out.val, topk_out.count};
     else
         launch_top1_merge(K, topk_ws, blocks_for(n), topk.k, topk_out, stream);
-    return launch_pareto_passes(pareto, n, pareto_out, pareto_ws_, sc, kSampleBlocks, rider, stream,
-                                folded ? &shared : nullptr, K);
+    return launch_pareto_passes(pareto, n, pareto_out, pareto_ws_, sc, sampled ? sampled_partials : kSampleBlocks, rider,
+                                stream, folded ? &shared : nullptr, K);
 }
 
 // The passes after the sample, for a caller whose own kernel has sampled the rows and reset the tables.
