@@ -726,6 +726,11 @@ bool eval_grid_can_fuse(const GridDesc &g) {
     return false;
 }
 
+// The tile kernels deal batches of kBlock tiles (kBlock * NB * NM consecutive rows) to their blocks round robin.
+uint32_t eval_grid_row_chunk(const GridDesc &g) {
+    return eval_grid_can_fuse(g) ? (uint32_t)kBlock * g.div[AX_BLK].d * g.div[AX_MBT].d : 0u;
+}
+
 size_t tile_tables_bytes() { return sizeof(TileLds); }
 
 hipError_t launch_tile_tables(const GridDesc &g, const DevTables *tab, void *tile_tables, hipStream_t stream) {

@@ -504,6 +504,9 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
     if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
     if (int rc_order = order_after_previous(ctx, stream)) return rc_order;
     uint32_t n_blocks = 0, sampled_partials = 0;
+    // rows [0, count) of the columns are rows [first, first + count) of the grid: the chunks line up when first does
+    const uint32_t chunk_of_eval = eval_grid_row_chunk(desc);
+    const uint32_t row_chunk = (chunk_of_eval && first % chunk_of_eval == 0) ? chunk_of_eval : 0u;
     const bool fold = topk_folded;                      // then the Pareto row sample is taken there as well
     if (count > 0) {
         if (n_eff) {
@@ -553,7 +556,7 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
     if (topk && pareto && count > 0 && !fold) {
         // both selections read stored columns: the small kernels ride along with the large ones
         e = launch_select_both(spec_of(*topk, *out), topk->out, ws_of[topk - sel], spec_of(*pareto, *out), pareto->out,
-                               ws_of[pareto - sel], count, ctx->select_scratch, stream, sampled_partials);
+                               ws_of[pareto - sel], count, ctx->select_scratch, stream, sampled_partials, row_chunk);
     } else {
         for (uint32_t i = 0; i < n_sel && e == hipSuccess; ++i) {
             const guide_column_select &c = sel[i];
@@ -569,7 +572,7 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
                                           n_blocks, topk->k, &topk->out, stream);
             } else if (sampled_partials && count > 0) {
                 e = launch_pareto_sampled(spec, count, c.out, ws_of[i], ctx->select_scratch, sampled_partials, nullptr, 0,
-                                          0, nullptr, stream);
+                                          0, nullptr, stream, row_chunk);
             } else {
                 e = launch_select_pareto(spec, count, c.out, ws_of[i], ctx->select_scratch, stream);
             }

@@ -55,13 +55,19 @@ hipError_t launch_eval_grid_fused(const GridDesc &g, const DevTables *tab, const
 hipError_t launch_topk_merge(void *ws, uint32_t n_blocks, uint32_t k, const guide_select_out &out, hipStream_t stream);
 hipError_t launch_pareto_sampled(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
                                  void *scratch, uint32_t n_partials, void *merge_ws, uint32_t merge_blocks,
-                                 uint32_t merge_k, const guide_select_out *merge_out, hipStream_t stream);
+                                 uint32_t merge_k, const guide_select_out *merge_out, hipStream_t stream,
+                                 uint32_t row_chunk = 0);
 size_t topk_partials_bytes();
 // sampled_partials != 0: the caller's evaluation kernel has already sampled the rows (that many block partials)
 // and reset the bin tables, so no sample is launched.
 hipError_t launch_select_both(const guide_select_spec &topk, const guide_select_out &topk_out, void *topk_ws,
                               const guide_select_spec &pareto, const guide_select_out &pareto_out, void *pareto_ws,
-                              uint64_t n, void *scratch, hipStream_t stream, uint32_t sampled_partials = 0);
+                              uint64_t n, void *scratch, hipStream_t stream, uint32_t sampled_partials = 0,
+                              uint32_t row_chunk = 0);
+// row_chunk: rows are dealt to the blocks of the selection passes in chunks of that many rows, chunk c to block
+// c % blocks (0 = the passes' own batch size).  eval_grid_row_chunk() gives the chunk in which the evaluation
+// kernel deals its rows to blocks the same way, so that a row is read through the L2 that wrote it.
+uint32_t eval_grid_row_chunk(const GridDesc &g);
 
 size_t select_workspace_bytes(const guide_select_spec &spec, uint64_t n);
 hipError_t launch_eval_extras(const GridDesc &g, const DevTables *tab, uint32_t first, uint32_t count, uint32_t n_gpus,

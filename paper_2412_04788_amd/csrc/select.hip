@@ -85,14 +85,33 @@ void with_max_constraints(uint32_t n_con, F &&fn) {
     else fn(std::integral_constant<uint32_t, GUIDE_MAX_CONSTRAINTS>{});
 }
 
-// Block b of the n_blocks row blocks owns the contiguous rows [b * per, (b + 1) * per); per is a multiple of
-// kBlock * kUnroll so that every lane of a wave runs the same trip count.
+// Rows are dealt to blocks in chunks of `chunk` rows (a multiple of kBlock): chunk c goes to block c % gridDim.x.
+// The hardware deals blocks to the dies' L2 caches round robin, so with a grid that is a multiple of the number of
+// dies, chunk c is read through the same L2 as by any other kernel that deals the same chunks the same way -- in
+// particular the evaluation kernel that writes them, which then finds no copies of its lines in other L2s.
+// A block walks its chunks in batches of kBlock * U rows (the last batch of a chunk may be partial), U = rows per
+// thread in flight: 8, or 6 when that divides the chunk evenly and 8 does not.
 constexpr uint32_t kUnroll = 8;
-__device__ inline uint32_t rows_per_block(uint32_t n, uint32_t n_blocks) {
-    const uint32_t unit = kBlock * kUnroll;
-    const uint32_t per = (n + n_blocks - 1) / n_blocks;
-    return (per + unit - 1) / unit * unit;
-}
+constexpr uint32_t kDefaultChunk = kBlock * kUnroll;
+template <uint32_t U>
+struct ChunkWalk {
+    uint32_t chunk, n, n_blocks, c;
+    uint64_t base, end;             // current batch starts at `base`; its chunk ends at `end` (exclusive)
+    __device__ ChunkWalk(uint32_t chunk_, uint32_t n_, uint32_t n_blocks_)
+        : chunk(chunk_), n(n_), n_blocks(n_blocks_), c(blockIdx.x) { enter(); }
+    __device__ void enter() {
+        base = (uint64_t)c * chunk;
+        end = base + chunk < n ? base + chunk : n;
+    }
+    __device__ bool live() const { return base < n; }
+    __device__ void next() {
+        base += kBlock * U;
+        if (base >= end) {
+            c += n_blocks;
+            enter();
+        }
+    }
+};
 
 RowFilter make_filter(const guide_select_spec &s) {
     RowFilter f;
@@ -105,12 +124,17 @@ RowFilter make_filter(const guide_select_spec &s) {
     return f;
 }
 
+// Blocks of a streaming pass over n rows.  Top-k passes: up to four per compute unit.  Pareto passes: two per
+// compute unit -- every block of those fills or loads a 32 KB table, which with more blocks costs more than the
+// extra blocks hide (512 and 768 blocks measured alike on 1.9M rows, 1024 and 256 slower).
 uint32_t blocks_for(uint64_t n) {
     uint64_t need = (n + kBlock - 1) / kBlock;
     if (need == 0) need = 1;
-    // two blocks per compute unit: with more, the per-block tables (32 KB each in the Pareto passes) cost more
-    // than the extra blocks hide (512 and 768 blocks measured alike on 1.9M rows, 1024 and 256 slower)
-    uint64_t cap = 2 * (uint64_t)device_cus();
+    return (uint32_t)(need < kSelBlocks ? need : kSelBlocks);
+}
+uint32_t pareto_blocks(uint64_t n) {
+    uint64_t need = (n + kBlock - 1) / kBlock, cap = 2 * (uint64_t)device_cus();
+    if (need == 0) need = 1;
     cap = cap < kSelBlocks ? cap : kSelBlocks;
     return (uint32_t)(need < cap ? need : cap);
 }
@@ -139,9 +163,10 @@ __device__ void pareto_prepare_body(uint32_t block, const double *__restrict__ x
 
 // One pass over the rows: every lane keeps its K best, the block merges them.  Blocks
 // [0, n_row_blocks) take the rows.
-template <int K, uint32_t MAXC>
+template <int K, uint32_t MAXC, uint32_t U>
 __global__ __launch_bounds__(kBlock) void topk_pass_kernel(const double *__restrict__ obj, RowFilter f, uint32_t n,
-                                                           Top1Ws w, uint32_t n_row_blocks, SampleRider sample) {
+                                                           Top1Ws w, uint32_t n_row_blocks, SampleRider sample,
+                                                           uint32_t chunk) {
     if (blockIdx.x >= n_row_blocks) {
         pareto_prepare_body(blockIdx.x - n_row_blocks, sample.x, sample.y, sample.f, n, sample.sc);
         return;
@@ -151,17 +176,16 @@ __global__ __launch_bounds__(kBlock) void topk_pass_kernel(const double *__restr
     TopList<K> l;
     l.init();
     uint64_t cnt = 0;
-    const uint32_t per = rows_per_block(n, n_row_blocks);
-    const uint64_t begin = (uint64_t)blockIdx.x * per;
-    for (uint64_t base = begin + threadIdx.x; base < begin + per && base < n; base += kBlock * kUnroll) {
-        Row r[kUnroll];
+    for (ChunkWalk<U> cw(chunk, n, n_row_blocks); cw.live(); cw.next()) {
+        const uint32_t base = (uint32_t)cw.base + threadIdx.x, lim = (uint32_t)cw.end;
+        Row r[U];
 #pragma unroll
-        for (uint32_t u = 0; u < kUnroll; ++u) r[u] = load_row<false, MAXC>(obj, nullptr, f, (uint32_t)base + u * kBlock, n);
+        for (uint32_t u = 0; u < U; ++u) r[u] = load_row<false, MAXC>(obj, nullptr, f, base + u * kBlock, lim);
 #pragma unroll
-        for (uint32_t u = 0; u < kUnroll; ++u) {
+        for (uint32_t u = 0; u < U; ++u) {
             if (r[u].pass) {
                 ++cnt;
-                l.insert_ascending(Pair{key_of(r[u].x), (uint32_t)base + u * kBlock});
+                l.insert_ascending(Pair{key_of(r[u].x), base + u * kBlock});
             }
         }
     }
@@ -573,31 +597,29 @@ struct SharedTopk {
 };
 
 // KT: pairs per block partial of the shared top-k (0 = none; then `topk` is ignored).
-template <uint32_t MAXC, int KT>
+template <uint32_t MAXC, int KT, uint32_t U>
 __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__restrict__ x, const double *__restrict__ y,
                                                               RowFilter f, uint32_t n, SelectScratch *sc, uint32_t n_partials,
-                                                              SharedTopk topk) {
+                                                              SharedTopk topk, uint32_t chunk) {
     __shared__ uint64_t s_min[padded_size<kPerPass>()], s_tmp[kWaves], s_rng[2];
     constexpr int KL = KT ? KT : 1;
     TopList<KL> list;
     uint64_t n_pass = 0;
     if (KT) list.init();
-    const uint32_t per = rows_per_block(n, gridDim.x);
-    const uint64_t begin = (uint64_t)blockIdx.x * per;
-    const uint64_t end = begin + per < n ? begin + per : n;
     // the first batch of rows is requested before the set-up below, so that its latency overlaps it
-    RawRow<MAXC> r[kUnroll];
-    uint64_t base = begin;
-    if (base < end) {
+    RawRow<MAXC> r[U];
+    ChunkWalk<U> cw(chunk, n, gridDim.x);
+    if (cw.live()) {
 #pragma unroll
-        for (uint32_t u = 0; u < kUnroll; ++u)
-            r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)base + threadIdx.x + u * kBlock, n);
+        for (uint32_t u = 0; u < U; ++u)
+            r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)cw.base + threadIdx.x + u * kBlock, (uint32_t)cw.end);
     }
     for (uint32_t i = threadIdx.x; i < padded_size<kPerPass>(); i += kBlock) s_min[i] = kNone;
     const Binning bin = sampled_binning(sc, n_partials, s_rng);     // its barrier also covers the table above
-    while (base < end) {
+    while (cw.live()) {
+        const uint32_t base = (uint32_t)cw.base;
 #pragma unroll
-        for (uint32_t u = 0; u < kUnroll; ++u) {
+        for (uint32_t u = 0; u < U; ++u) {
             const Row q = row_of<true, MAXC>(r[u], f);
             if (q.pass) {
                 const uint32_t b = padded<kPerPass>(bin(key_of(q.x)));
@@ -613,15 +635,15 @@ __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__re
                     if (c < topk.n_con) ok = ok && ((topk.con_is_y[c] ? r[u].y : r[u].x) <= topk.cap[c]);
                 if (ok) {
                     ++n_pass;
-                    list.insert_ascending(Pair{key_of(obj), (uint64_t)((uint32_t)base + threadIdx.x + u * kBlock)});
+                    list.insert_ascending(Pair{key_of(obj), (uint64_t)(base + threadIdx.x + u * kBlock)});
                 }
             }
         }
-        base += kBlock * kUnroll;
-        if (base < end) {
+        cw.next();
+        if (cw.live()) {
 #pragma unroll
-            for (uint32_t u = 0; u < kUnroll; ++u)
-                r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)base + threadIdx.x + u * kBlock, n);
+            for (uint32_t u = 0; u < U; ++u)
+                r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)cw.base + threadIdx.x + u * kBlock, (uint32_t)cw.end);
         }
     }
     __syncthreads();
@@ -656,36 +678,34 @@ __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__re
     }
 }
 
-template <uint32_t MAXC>
+template <uint32_t MAXC, uint32_t U>
 __global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *__restrict__ x,
                                                                   const double *__restrict__ y, RowFilter f, uint32_t n,
-                                                                  ParetoWs w, SelectScratch *sc, uint32_t n_partials) {
+                                                                  ParetoWs w, SelectScratch *sc, uint32_t n_partials,
+                                                                  uint32_t chunk) {
     __shared__ uint64_t s_lower[padded_size<kPerPass>()], s_tmp[kWaves], s_rng[2];
     const int lane = threadIdx.x % kWave;
-    const uint32_t per = rows_per_block(n, gridDim.x);
-    const uint64_t begin = (uint64_t)blockIdx.x * per;
-    const uint64_t end = begin + per < n ? begin + per : n;
     // requested first, and in this order: the table, then the first batch of rows, whose latency
     // overlaps the scan of the table
     uint64_t tbl[kPerPass];
 #pragma unroll
     for (uint32_t j = 0; j < kPerPass; ++j) tbl[j] = sc->bin_min[j * kBlock + threadIdx.x];
-    RawRow<MAXC> r[kUnroll];
-    uint64_t base = begin;
-    if (base < end) {
+    RawRow<MAXC> r[U];
+    ChunkWalk<U> cw(chunk, n, gridDim.x);
+    if (cw.live()) {
 #pragma unroll
-        for (uint32_t u = 0; u < kUnroll; ++u)
-            r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)base + threadIdx.x + u * kBlock, n);
+        for (uint32_t u = 0; u < U; ++u)
+            r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)cw.base + threadIdx.x + u * kBlock, (uint32_t)cw.end);
     }
 #pragma unroll
     for (uint32_t j = 0; j < kPerPass; ++j) s_lower[padded<kPerPass>(j * kBlock + threadIdx.x)] = tbl[j];
     const Binning bin = sampled_binning(sc, n_partials, s_rng);     // its barrier also covers the table above
     scan_min_excl<kBlock>(s_lower, s_tmp);              // least y over strictly lower bins
     // wave-uniform trip count: the ballots below need every lane
-    while (base < end) {
+    while (cw.live()) {
 #pragma unroll
-        for (uint32_t u = 0; u < kUnroll; ++u) {
-            const uint32_t i = (uint32_t)base + threadIdx.x + u * kBlock;
+        for (uint32_t u = 0; u < U; ++u) {
+            const uint32_t i = (uint32_t)cw.base + threadIdx.x + u * kBlock;
             const Row q = row_of<true, MAXC>(r[u], f);
             uint32_t b = 0;
             uint64_t kx = 0, ky = 0;
@@ -710,11 +730,11 @@ __global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *
                 }
             }
         }
-        base += kBlock * kUnroll;
-        if (base < end) {
+        cw.next();
+        if (cw.live()) {
 #pragma unroll
-            for (uint32_t u = 0; u < kUnroll; ++u)
-                r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)base + threadIdx.x + u * kBlock, n);
+            for (uint32_t u = 0; u < U; ++u)
+                r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)cw.base + threadIdx.x + u * kBlock, (uint32_t)cw.end);
         }
     }
 }
@@ -906,23 +926,37 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
 
 __global__ void pareto_empty_kernel(uint64_t *out_count) { out_count[0] = 0; }
 
+// A row chunk asked for by the caller is taken when batches of 8 or of 6 rows per thread tile it; otherwise the
+// passes deal their own batches.  Calls fn(chunk, integral_constant<rows per thread>).
+template <typename F>
+void with_row_chunk(uint32_t row_chunk, F &&fn) {
+    if (row_chunk && row_chunk % (kBlock * 8) == 0) fn(row_chunk, std::integral_constant<uint32_t, 8>{});
+    else if (row_chunk && row_chunk % (kBlock * 6) == 0) fn(row_chunk, std::integral_constant<uint32_t, 6>{});
+    else fn(kDefaultChunk, std::integral_constant<uint32_t, 8>{});
+}
+
 template <int K>
-void launch_top1_pass(const guide_select_spec &spec, uint64_t n, void *ws, const SampleRider &sample, hipStream_t stream) {
+void launch_top1_pass(const guide_select_spec &spec, uint64_t n, void *ws, const SampleRider &sample, hipStream_t stream,
+                      uint32_t row_chunk) {
     const uint32_t nb = blocks_for(n);
     with_max_constraints(spec.n_constraints, [&](auto maxc) {
-        hipLaunchKernelGGL((topk_pass_kernel<K, decltype(maxc)::value>), dim3(nb + (sample.on ? kSampleBlocks : 0)),
-                           dim3(kBlock), 0, stream, spec.objective, make_filter(spec), (uint32_t)n, top1_ws(ws), nb, sample);
+        with_row_chunk(row_chunk, [&](uint32_t chunk, auto u) {
+            hipLaunchKernelGGL((topk_pass_kernel<K, decltype(maxc)::value, decltype(u)::value>),
+                               dim3(nb + (sample.on ? kSampleBlocks : 0)), dim3(kBlock), 0, stream, spec.objective,
+                               make_filter(spec), (uint32_t)n, top1_ws(ws), nb, sample, chunk);
+        });
     });
 }
 // Pairs per block partial for a request of k (the pass kernel's template argument).
 int partial_width(uint32_t k) { return k <= 4 ? (int)k : 8; }
-void launch_top1_pass(const guide_select_spec &spec, uint64_t n, void *ws, const SampleRider &sample, hipStream_t stream) {
+void launch_top1_pass(const guide_select_spec &spec, uint64_t n, void *ws, const SampleRider &sample, hipStream_t stream,
+                      uint32_t chunk = 0) {
     switch (partial_width(spec.k)) {
-        case 1: launch_top1_pass<1>(spec, n, ws, sample, stream); break;
-        case 2: launch_top1_pass<2>(spec, n, ws, sample, stream); break;
-        case 3: launch_top1_pass<3>(spec, n, ws, sample, stream); break;
-        case 4: launch_top1_pass<4>(spec, n, ws, sample, stream); break;
-        default: launch_top1_pass<8>(spec, n, ws, sample, stream); break;
+        case 1: launch_top1_pass<1>(spec, n, ws, sample, stream, chunk); break;
+        case 2: launch_top1_pass<2>(spec, n, ws, sample, stream, chunk); break;
+        case 3: launch_top1_pass<3>(spec, n, ws, sample, stream, chunk); break;
+        case 4: launch_top1_pass<4>(spec, n, ws, sample, stream, chunk); break;
+        default: launch_top1_pass<8>(spec, n, ws, sample, stream, chunk); break;
     }
 }
 void launch_top1_merge(int K, void *ws, uint32_t n_blocks, uint32_t k, const guide_select_out &out, hipStream_t stream) {
@@ -972,25 +1006,30 @@ hipError_t launch_select_topk(const guide_select_spec &spec, uint64_t n, const g
 
 static hipError_t launch_pareto_passes(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
                                        SelectScratch *sc, uint32_t n_partials, const MergeRider &rider,
-                                       hipStream_t stream, const SharedTopk *shared = nullptr, int shared_k = 0) {
+                                       hipStream_t stream, const SharedTopk *shared = nullptr, int shared_k = 0,
+                                       uint32_t row_chunk = 0) {
     const ParetoWs w = pareto_ws(ws, n);
     const RowFilter f = make_filter(spec);
-    const uint32_t nb = blocks_for(n), n32 = (uint32_t)n;
+    const uint32_t nb = pareto_blocks(n), n32 = (uint32_t)n;
     const double *x = spec.objective, *y = spec.objective_y;
     const dim3 grid(nb), block(kBlock);
-    if (shared) {       // only offered for a Pareto selection without constraint columns
-        const SharedTopk t = *shared;
-        if (shared_k == 1) hipLaunchKernelGGL((pareto_stair_kernel<0, 1>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t);
-        else if (shared_k == 2) hipLaunchKernelGGL((pareto_stair_kernel<0, 2>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t);
-        else if (shared_k == 3) hipLaunchKernelGGL((pareto_stair_kernel<0, 3>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t);
-        else hipLaunchKernelGGL((pareto_stair_kernel<0, 4>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t);
-    }
-    with_max_constraints(f.n_con, [&](auto maxc) {
-        constexpr uint32_t MAXC = decltype(maxc)::value;
-        if (!shared)
-            hipLaunchKernelGGL((pareto_stair_kernel<MAXC, 0>), grid, block, 0, stream, x, y, f, n32, sc, n_partials,
-                               SharedTopk{});
-        hipLaunchKernelGGL(pareto_survivors_kernel<MAXC>, grid, block, 0, stream, x, y, f, n32, w, sc, n_partials);
+    with_row_chunk(row_chunk, [&](uint32_t chunk, auto u) {
+        constexpr uint32_t U = decltype(u)::value;
+        if (shared) {       // only offered for a Pareto selection without constraint columns
+            const SharedTopk t = *shared;
+            if (shared_k == 1) hipLaunchKernelGGL((pareto_stair_kernel<0, 1, U>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t, chunk);
+            else if (shared_k == 2) hipLaunchKernelGGL((pareto_stair_kernel<0, 2, U>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t, chunk);
+            else if (shared_k == 3) hipLaunchKernelGGL((pareto_stair_kernel<0, 3, U>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t, chunk);
+            else hipLaunchKernelGGL((pareto_stair_kernel<0, 4, U>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t, chunk);
+        }
+        with_max_constraints(f.n_con, [&](auto maxc) {
+            constexpr uint32_t MAXC = decltype(maxc)::value;
+            if (!shared)
+                hipLaunchKernelGGL((pareto_stair_kernel<MAXC, 0, U>), grid, block, 0, stream, x, y, f, n32, sc, n_partials,
+                                   SharedTopk{}, chunk);
+            hipLaunchKernelGGL((pareto_survivors_kernel<MAXC, U>), grid, block, 0, stream, x, y, f, n32, w, sc, n_partials,
+                               chunk);
+        });
     });
     hipLaunchKernelGGL(pareto_finish_kernel, dim3(rider.n_blocks ? 2 : 1), dim3(kFinishThreads), 0, stream, w, n32, sc,
                        n_partials, out.idx, out.capacity, out.count, rider);
@@ -1037,7 +1076,8 @@ static bool shares_columns(const guide_select_spec &topk, const guide_select_spe
 // survivors, finish + merge).
 hipError_t launch_select_both(const guide_select_spec &topk, const guide_select_out &topk_out, void *topk_ws,
                               const guide_select_spec &pareto, const guide_select_out &pareto_out, void *pareto_ws_,
-                              uint64_t n, void *scratch, hipStream_t stream, uint32_t sampled_partials) {
+                              uint64_t n, void *scratch, hipStream_t stream, uint32_t sampled_partials,
+                              uint32_t row_chunk) {
     SelectScratch *sc = (SelectScratch *)scratch;
     const int K = partial_width(topk.k);
     SharedTopk shared;
@@ -1050,15 +1090,16 @@ hipError_t launch_select_both(const guide_select_spec &topk, const guide_select_
                                pareto.objective_y, make_filter(pareto), (uint32_t)n, sc);
     } else {
         const SampleRider sample{sampled ? 0u : 1u, pareto.objective, pareto.objective_y, make_filter(pareto), sc};
-        launch_top1_pass(topk, n, topk_ws, sample, stream);
+        launch_top1_pass(topk, n, topk_ws, sample, stream, row_chunk);
     }
     MergeRider rider{};
     if (K <= 4)
-        rider = MergeRider{top1_ws(topk_ws), blocks_for(n), topk.k, (uint32_t)K, topk_out.idx, topk_out.val, topk_out.count};
+        rider = MergeRider{top1_ws(topk_ws), folded ? pareto_blocks(n) : blocks_for(n), topk.k, (uint32_t)K, topk_out.idx,
+                           topk_out.val, topk_out.count};       // partials: one per block of the kernel that kept the lists
     else
         launch_top1_merge(K, topk_ws, blocks_for(n), topk.k, topk_out, stream);
     return launch_pareto_passes(pareto, n, pareto_out, pareto_ws_, sc, sampled ? sampled_partials : kSampleBlocks, rider,
-                                stream, folded ? &shared : nullptr, K);
+                                stream, folded ? &shared : nullptr, K, row_chunk);
 }
 
 // The passes after the sample, for a caller whose own kernel has sampled the rows and reset the tables.
@@ -1066,12 +1107,13 @@ hipError_t launch_select_both(const guide_select_spec &topk, const guide_select_
 // along with the finishing kernel instead of taking a launch of its own.
 hipError_t launch_pareto_sampled(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
                                  void *scratch, uint32_t n_partials, void *merge_ws, uint32_t merge_blocks,
-                                 uint32_t merge_k, const guide_select_out *merge_out, hipStream_t stream) {
+                                 uint32_t merge_k, const guide_select_out *merge_out, hipStream_t stream,
+                                 uint32_t row_chunk) {
     MergeRider rider{};
     if (merge_ws)
         rider = MergeRider{top1_ws(merge_ws), merge_blocks, merge_k, (uint32_t)kFusedTopK, merge_out->idx, merge_out->val,
                            merge_out->count};
-    return launch_pareto_passes(spec, n, out, ws, (SelectScratch *)scratch, n_partials, rider, stream);
+    return launch_pareto_passes(spec, n, out, ws, (SelectScratch *)scratch, n_partials, rider, stream, nullptr, 0, row_chunk);
 }
 
 size_t topk_partials_bytes() { return top1_ws_bytes(); }
