@@ -14,6 +14,8 @@
 //     number and total context are two running integers.
 // One step therefore costs one pass-time evaluation plus O(1) integer updates;
 // heap traffic is O(log n) per request, not per step.
+#include <type_traits>
+
 #include "kernels.hpp"
 #include "perf_model.hpp"
 
@@ -23,7 +25,7 @@ namespace {
 
 constexpr uint32_t kSimBlock = 256;      // one block per compute unit: the trace is staged once, the rest of LDS holds heaps
 constexpr uint32_t kPctBlock = 256;
-constexpr uint32_t kHeapLdsMax = 64;     // at most this many heap nodes per lane in LDS
+constexpr size_t kSimStaticLds = 2 * kSimBlock * 4 + 64;   // the simulation kernel's own static LDS (segment tables)
 
 struct SimLds {
     uint32_t axis[kNumAxes][GUIDE_MAX_AXIS_VALUES];
@@ -127,23 +129,24 @@ __global__ __launch_bounds__(kBlock) void sim_order_scatter_kernel(uint32_t n_cf
 
 __global__ __launch_bounds__(kKeyBins) void sim_order_clear_kernel(SimWs ws) { ws.bins[threadIdx.x] = 0; }
 
-// Heap of the decoders' finishing steps, one per lane.  Node 0 lives in a register, nodes 1 .. lds_slots in
-// LDS (slot-major, so the lanes of a wave sit in different banks when they touch the same node), deeper nodes in
-// global memory.  4-ary: the children of node i are 4i+1 .. 4i+4.  Key = finishing step << 10 | request.
+// Heap of the decoders' finishing steps, one per lane.  Node 0 lives in a register, nodes 1 .. cap in the lane's
+// segment of LDS, deeper nodes in global memory.  4-ary: the children of node i are 4i+1 .. 4i+4.
+// Key = finishing step << 10 | request; 32-bit keys when every finishing step fits 22 bits (twice the nodes in LDS).
+template <typename KeyT>
 struct LaneHeap {
-    uint64_t top;
-    uint64_t *lds;        // this lane's column: node i at lds[(i - 1) * kSimBlock]
-    uint64_t *mem;        // node i at mem[i]
-    uint32_t lds_slots, n;
-    __device__ uint64_t get(uint32_t i) const { return i <= lds_slots ? lds[(size_t)(i - 1) * kSimBlock] : mem[i]; }
-    __device__ void set(uint32_t i, uint64_t k) {
-        if (i <= lds_slots) lds[(size_t)(i - 1) * kSimBlock] = k; else mem[i] = k;
+    KeyT top;
+    KeyT *lds;            // node i (1 <= i <= cap) at lds[i - 1]
+    KeyT *mem;            // node i (i > cap) at mem[i]
+    uint32_t cap, n;
+    __device__ KeyT get(uint32_t i) const { return i <= cap ? lds[i - 1] : mem[i]; }
+    __device__ void set(uint32_t i, KeyT k) {
+        if (i <= cap) lds[i - 1] = k; else mem[i] = k;
     }
-    __device__ void push(uint64_t key) {            // the new node rises from the end
+    __device__ void push(KeyT key) {                // the new node rises from the end
         uint32_t i = n++;
         while (i > 0) {
             const uint32_t par = (i - 1) >> 2;
-            const uint64_t pk = par == 0 ? top : get(par);
+            const KeyT pk = par == 0 ? top : get(par);
             if (pk <= key) break;
             set(i, pk);
             i = par;
@@ -153,18 +156,18 @@ struct LaneHeap {
     __device__ void pop() {                         // the last node sinks from the root
         --n;
         if (n == 0) {
-            top = ~0ull;
+            top = (KeyT)~(KeyT)0;
             return;
         }
-        const uint64_t last = get(n);
+        const KeyT last = get(n);
         uint32_t i = 0;
         for (;;) {
             const uint32_t c0 = 4 * i + 1;
             if (c0 >= n) break;
-            uint64_t k[4];
+            KeyT k[4];
 #pragma unroll
             for (uint32_t j = 0; j < 4; ++j) k[j] = get(c0 + j < n ? c0 + j : c0);      // all four requested at once
-            uint64_t best = k[0];
+            KeyT best = k[0];
             uint32_t bi = c0;
 #pragma unroll
             for (uint32_t j = 1; j < 4; ++j)
@@ -187,16 +190,22 @@ __device__ inline double run_time(const TimeCoef &tc, double step_const, double 
 
 // CLOSED_RUNS: runs of decode-only steps are advanced by run_time() in one go (GUIDE_SIM_CLOSED_FORM_RUNS);
 // otherwise step by step with the general step's own arithmetic.
-template <bool ADDITIVE, bool PREFILL_FIRST, bool CLOSED_RUNS>
+// ordered: configurations run in the order ws.perm (longest expected first); otherwise as given.
+// heap_slots: keys that the LDS behind the staged tables holds for the whole block; they are shared out among the
+// block's lanes in proportion to the most decoders each can have (its sequence cap), so that a lane that can
+// run a thousand sequences gets a long segment and a lane capped at four next to nothing.
+template <bool ADDITIVE, bool PREFILL_FIRST, bool CLOSED_RUNS, typename KeyT>
 __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const DevTables *__restrict__ tab,
                                                              const TraceDev *__restrict__ trace, uint32_t n_req,
                                                              const uint32_t *__restrict__ cfg_idx,
                                                              const double *__restrict__ rate_in, uint32_t n_cfg,
                                                              guide_sim_out out, SimWs ws, uint32_t max_run,
-                                                             uint32_t lds_slots) {
+                                                             uint32_t heap_slots, uint32_t ordered) {
     extern __shared__ __align__(16) unsigned char s_raw[];
     SimLds &s = *(SimLds *)s_raw;
-    uint64_t *s_heap = (uint64_t *)(s_raw + sizeof(SimLds));
+    KeyT *s_heap = (KeyT *)(s_raw + sizeof(SimLds));
+    __shared__ uint32_t s_cap[kSimBlock], s_off[kSimBlock];
+    __shared__ uint32_t s_total[kSimBlock / kWave];
     for (uint32_t i = threadIdx.x; i < kNumAxes * GUIDE_MAX_AXIS_VALUES; i += blockDim.x)
         (&s.axis[0][0])[i] = (&tab->axis_vals[0][0])[i];
     for (uint32_t i = threadIdx.x; i < g.n_models * 8u; i += blockDim.x)
@@ -207,49 +216,81 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
         s.n_out[i] = trace->n_out[i];
     }
     __syncthreads();
-    const uint32_t pos = blockIdx.x * kSimBlock + threadIdx.x;     // launch position; its configuration is perm[pos]
-    if (pos >= n_cfg) return;
-    const uint32_t c = ws.perm[pos];
+    const uint32_t pos = blockIdx.x * kSimBlock + threadIdx.x;     // launch position
+    const bool in_range = pos < n_cfg;
+    const uint32_t c = in_range ? (ordered ? ws.perm[pos] : pos) : 0u;      // its configuration
 
     uint32_t v[kNumAxes];
-    const bool bad_index = decode_sim_index(s.axis, g, cfg_idx[c], v);
-    const uint32_t max_seqs = v[AX_BATCH], p = v[AX_TP], wbits = v[AX_WBITS], blk = v[AX_BLK], mbt = v[AX_MBT];
-    const guide_hw hw = tab->hw[v[AX_HW]];
-    const double rate = rate_in[c];
-    const Coef cf = make_coef(s.models[v[AX_MODEL]], p, wbits);
-    const TimeCoef tc = make_time_coef(cf, 1.0 / hw.peak_flops, 1.0 / hw.hbm_bw, 1.0 / hw.link_bw, hw.link_lat);
-    const Div32 dblk = make_div32(blk);
+    bool alive = false;                                           // this lane has a simulation to run
+    uint32_t max_seqs = 1, blk = 1, mbt = 1;
+    double rate = 1.0, c_avail = 0.0, tokens = 0.0;
+    uint64_t step_bound = n_req;
+    long long n_blk = 0;
+    Coef cf;
+    TimeCoef tc;
+    Div32 dblk = make_div32(1);
     // KV blocks of a request of `tok` >= 1 tokens: ceil(tok / blk) without the 32-bit overflow of tok + blk - 1
     auto blocks_of = [&](uint32_t tok) { return (long long)div32(tok - 1, dblk) + 1; };
+    if (in_range) {
+        const bool bad_index = decode_sim_index(s.axis, g, cfg_idx[c], v);
+        max_seqs = v[AX_BATCH]; blk = v[AX_BLK]; mbt = v[AX_MBT];
+        const guide_hw hw = tab->hw[v[AX_HW]];
+        rate = rate_in[c];
+        cf = make_coef(s.models[v[AX_MODEL]], v[AX_TP], v[AX_WBITS]);
+        tc = make_time_coef(cf, 1.0 / hw.peak_flops, 1.0 / hw.hbm_bw, 1.0 / hw.link_bw, hw.link_lat);
+        dblk = make_div32(blk);
+        // KV pool in blocks; every request must fit on its own
+        c_avail = hw.cap_bytes - cf.w_gpu;
+        uint32_t max_tok = 0;
+        for (uint32_t i = 0; i < n_req; ++i) {
+            const uint32_t t = s.n_in[i] + s.n_out[i];
+            max_tok = t > max_tok ? t : max_tok;
+            step_bound += t;
+            tokens += (double)s.n_out[i];
+        }
+        if (c_avail > 0.0) {
+            const double nb = floor(c_avail / ((double)blk * cf.kv_tok));
+            n_blk = nb >= 9.0e18 ? 0x7FFFFFFFFFFFFFFFll : (long long)nb;
+        }
+        if (bad_index || !(c_avail > 0.0) || blocks_of(max_tok) > n_blk || !(rate > 0.0)) {
+            out.ttft_p50[c] = INFINITY; out.ttft_p99[c] = INFINITY; out.mean_tpot[c] = INFINITY; out.tokens_s[c] = 0.0;
+            out.status[c] = (bad_index || !(rate > 0.0)) ? GUIDE_SIM_BAD_INPUT : GUIDE_SIM_INFEASIBLE;
+            out.n_steps[c] = 0; out.n_request_steps[c] = 0;
+        } else {
+            alive = true;
+        }
+    }
 
-    // KV pool in blocks; every request must fit on its own
-    const double c_avail = hw.cap_bytes - cf.w_gpu;
-    uint32_t max_tok = 0;
-    uint64_t step_bound = n_req;
-    double tokens = 0.0;
-    for (uint32_t i = 0; i < n_req; ++i) {
-        const uint32_t t = s.n_in[i] + s.n_out[i];
-        max_tok = t > max_tok ? t : max_tok;
-        step_bound += t;
-        tokens += (double)s.n_out[i];
+    // LDS segments of the heaps: a lane can have at most min(sequence cap, requests) decoders, one of them in a
+    // register; when the block's lanes want more than the LDS holds, every segment shrinks by the same factor
+    const uint32_t want = alive ? (max_seqs < n_req ? max_seqs : n_req) - 1u : 0u;
+    {
+        uint32_t t = want;
+        for (int off = kWave / 2; off > 0; off >>= 1) t += __shfl_xor(t, off, kWave);
+        if (threadIdx.x % kWave == 0) s_total[threadIdx.x / kWave] = t;
+        __syncthreads();
+        uint32_t total = 0;
+        for (uint32_t w = 0; w < kSimBlock / kWave; ++w) total += s_total[w];
+        uint32_t cap = want;
+        if (total > heap_slots) cap = (uint32_t)((double)want * ((double)heap_slots / (double)total) * (1.0 - 0x1p-30));
+        s_cap[threadIdx.x] = cap;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t run = 0;
+            for (uint32_t i = 0; i < kSimBlock; ++i) {
+                s_off[i] = run;
+                run += s_cap[i];
+            }
+        }
+        __syncthreads();
     }
-    long long n_blk = 0;
-    if (c_avail > 0.0) {
-        const double nb = floor(c_avail / ((double)blk * cf.kv_tok));
-        n_blk = nb >= 9.0e18 ? 0x7FFFFFFFFFFFFFFFll : (long long)nb;
-    }
-    if (bad_index || !(c_avail > 0.0) || blocks_of(max_tok) > n_blk || !(rate > 0.0)) {
-        out.ttft_p50[c] = INFINITY; out.ttft_p99[c] = INFINITY; out.mean_tpot[c] = INFINITY; out.tokens_s[c] = 0.0;
-        out.status[c] = (bad_index || !(rate > 0.0)) ? GUIDE_SIM_BAD_INPUT : GUIDE_SIM_INFEASIBLE;
-        out.n_steps[c] = 0; out.n_request_steps[c] = 0;
-        return;
-    }
+    if (!alive) return;
 
-    LaneHeap heap;
-    heap.top = ~0ull;
-    heap.lds = s_heap + threadIdx.x;
-    heap.mem = ws.heap + (size_t)pos * n_req;
-    heap.lds_slots = lds_slots;
+    LaneHeap<KeyT> heap;
+    heap.top = (KeyT)~(KeyT)0;
+    heap.lds = s_heap + s_off[threadIdx.x];
+    heap.mem = (KeyT *)(ws.heap + (size_t)pos * n_req);
+    heap.cap = s_cap[threadIdx.x];
     heap.n = 0;
     double *first = ws.first + (size_t)c * n_req, *fin = ws.fin + (size_t)c * n_req;
 
@@ -274,7 +315,7 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
             }
             const bool can_admit = next < n_req && n_dec < max_seqs && need_next <= free_blk;
             const double arr_stop = can_admit ? arr_next : INFINITY;
-            const uint64_t stop = heap.top >> 10;             // the step whose book-keeping retires a decoder
+            const uint64_t stop = (uint64_t)(heap.top >> 10); // the step whose book-keeping retires a decoder
             // steps left before that one (stop > dstep: its last token is still to come)
             const uint64_t left = stop - dstep - 1;
             const double T = (double)n_dec;
@@ -413,7 +454,7 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
             ++dstep;
             s_ctx += n_dec;
         }
-        while (decoders_run && heap.n > 0 && (heap.top >> 10) == dstep) {
+        while (decoders_run && heap.n > 0 && (uint64_t)(heap.top >> 10) == dstep) {
             const uint32_t r = (uint32_t)(heap.top & 1023u);
             heap.pop();
             const uint32_t r_tok = s.n_in[r] + s.n_out[r];
@@ -436,7 +477,7 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
             } else {
                 ++n_dec;
                 s_ctx += (uint64_t)r_in + 1;
-                heap.push(((dstep + r_out - 1) << 10) | r);
+                heap.push((KeyT)(((dstep + r_out - 1) << 10) | r));
             }
         }
         pf_head = h;
@@ -532,38 +573,54 @@ hipError_t launch_simulate(const GridDesc &g, const DevTables *tab, const TraceD
     // capped (64 steps measured best among 4..1024 on the 65 536-configuration mix; stopping a run once few
     // lanes of the wave are still in it measured worse at every setting tried).
     const uint32_t max_run = 64;
-    // LDS beyond the staged tables holds the upper heap nodes of the block's lanes
+    // LDS beyond the staged tables holds heap nodes of the block's lanes; 32-bit keys when every finishing step
+    // (at most the trace's generated tokens) fits 22 bits
+    const bool key32 = sum_out < 4194303.0;
+    const size_t key_bytes = key32 ? sizeof(uint32_t) : sizeof(uint64_t);
     int dev = 0, lds_max = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
     if (e != hipSuccess) return e;
-    if ((size_t)lds_max < sizeof(SimLds)) return hipErrorInvalidValue;
-    uint32_t lds_slots = (uint32_t)(((size_t)lds_max - sizeof(SimLds)) / (sizeof(uint64_t) * kSimBlock));
-    lds_slots = lds_slots < kHeapLdsMax ? lds_slots : kHeapLdsMax;
-    const size_t lds_bytes = sizeof(SimLds) + (size_t)lds_slots * sizeof(uint64_t) * kSimBlock;
+    const size_t fixed = sizeof(SimLds) + kSimStaticLds;
+    if ((size_t)lds_max < fixed) return hipErrorInvalidValue;
+    size_t heap_bytes = (size_t)lds_max - fixed;
+    const size_t most = (size_t)kSimBlock * n_req * key_bytes;          // no lane needs more than n_req - 1 nodes
+    heap_bytes = heap_bytes < most ? heap_bytes : most;
+    heap_bytes -= heap_bytes % 16;
+    const uint32_t heap_slots = (uint32_t)(heap_bytes / key_bytes);
+    const size_t lds_bytes = sizeof(SimLds) + heap_bytes;
     const dim3 grid((n_cfg + kSimBlock - 1) / kSimBlock), block(kSimBlock);
     const dim3 ogrid((n_cfg + kBlock - 1) / kBlock), oblock(kBlock);
-    hipLaunchKernelGGL(sim_order_clear_kernel, dim3(1), dim3(kKeyBins), 0, stream, ws);
-    if (additive)
-        hipLaunchKernelGGL(sim_order_count_kernel<true>, ogrid, oblock, 0, stream, g, tab, n_req, cfg_idx, rate, n_cfg, ws, sum_in, sum_out);
-    else
-        hipLaunchKernelGGL(sim_order_count_kernel<false>, ogrid, oblock, 0, stream, g, tab, n_req, cfg_idx, rate, n_cfg, ws, sum_in, sum_out);
-    hipLaunchKernelGGL(sim_order_scan_kernel, dim3(1), dim3(kKeyBins), 0, stream, ws);
-    hipLaunchKernelGGL(sim_order_scatter_kernel, ogrid, oblock, 0, stream, n_cfg, ws);
-    const int variant = (additive ? 4 : 0) | (prefill_first ? 2 : 0) | (closed_runs ? 1 : 0);
-#define GUIDE_SIM(A, P, C)                                                                                         \
-    case ((A ? 4 : 0) | (P ? 2 : 0) | (C ? 1 : 0)): {                                                               \
-        auto kern = simulate_kernel<A, P, C>;                                                                       \
+    // Stepped runs: configurations run longest first, so that the lanes of a wave end together.  With closed-form
+    // runs every lane does about the same number of rounds (one per event), and the order given mixes lanes with
+    // short and long heaps in a block, which is what the shared LDS wants.
+    const uint32_t ordered = closed_runs ? 0u : 1u;
+    if (ordered) {
+        hipLaunchKernelGGL(sim_order_clear_kernel, dim3(1), dim3(kKeyBins), 0, stream, ws);
+        if (additive)
+            hipLaunchKernelGGL(sim_order_count_kernel<true>, ogrid, oblock, 0, stream, g, tab, n_req, cfg_idx, rate, n_cfg, ws, sum_in, sum_out);
+        else
+            hipLaunchKernelGGL(sim_order_count_kernel<false>, ogrid, oblock, 0, stream, g, tab, n_req, cfg_idx, rate, n_cfg, ws, sum_in, sum_out);
+        hipLaunchKernelGGL(sim_order_scan_kernel, dim3(1), dim3(kKeyBins), 0, stream, ws);
+        hipLaunchKernelGGL(sim_order_scatter_kernel, ogrid, oblock, 0, stream, n_cfg, ws);
+    }
+    const int variant = (additive ? 8 : 0) | (prefill_first ? 4 : 0) | (closed_runs ? 2 : 0) | (key32 ? 1 : 0);
+#define GUIDE_SIM(A, P, C, K32)                                                                                    \
+    case ((A ? 8 : 0) | (P ? 4 : 0) | (C ? 2 : 0) | (K32 ? 1 : 0)): {                                               \
+        auto kern = simulate_kernel<A, P, C, std::conditional<K32, uint32_t, uint64_t>::type>;                      \
         e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);    \
         if (e != hipSuccess) return e;                                                                              \
         hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, g, tab, trace, n_req, cfg_idx, rate, n_cfg, out, ws, \
-                           max_run, lds_slots);                                                                     \
+                           max_run, heap_slots, ordered);                                                           \
         break;                                                                                                      \
     }
     switch (variant) {
-        GUIDE_SIM(false, false, false) GUIDE_SIM(false, false, true) GUIDE_SIM(false, true, false)
-        GUIDE_SIM(false, true, true) GUIDE_SIM(true, false, false) GUIDE_SIM(true, false, true)
-        GUIDE_SIM(true, true, false) GUIDE_SIM(true, true, true)
+        GUIDE_SIM(false, false, false, false) GUIDE_SIM(false, false, false, true) GUIDE_SIM(false, false, true, false)
+        GUIDE_SIM(false, false, true, true) GUIDE_SIM(false, true, false, false) GUIDE_SIM(false, true, false, true)
+        GUIDE_SIM(false, true, true, false) GUIDE_SIM(false, true, true, true) GUIDE_SIM(true, false, false, false)
+        GUIDE_SIM(true, false, false, true) GUIDE_SIM(true, false, true, false) GUIDE_SIM(true, false, true, true)
+        GUIDE_SIM(true, true, false, false) GUIDE_SIM(true, true, false, true) GUIDE_SIM(true, true, true, false)
+        GUIDE_SIM(true, true, true, true)
     }
 #undef GUIDE_SIM
     hipLaunchKernelGGL(percentile_kernel, dim3(n_cfg), dim3(kPctBlock), 0, stream, ws, trace, rate, n_req, out);
