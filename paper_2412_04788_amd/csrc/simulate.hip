@@ -497,23 +497,78 @@ __global__ __launch_bounds__(kSimBlock) void simulate_kernel(GridDesc g, const D
     }
 }
 
-// One block per simulated configuration that ended normally: TTFT of request i = first token time -
-// arrival / rate; bitonic sort in LDS, nearest-rank p50 = sorted[ceil(n/2) - 1] and p99 =
-// sorted[ceil(0.99 n) - 1]; mean TPOT = mean over requests with more than one token of
-// (finish - first token) / (tokens - 1).
+// One wave per simulated configuration that ended normally.  TTFT of request i = first token time - arrival /
+// rate; the 1024 values (absent requests count as +inf) are sorted inside the wave's registers, 16 per lane, by
+// a bitonic network in which every compare-exchange puts the smaller value at the smaller index: element
+// e = 16 * lane + register; a stage pairs e with e ^ m, which is another register of the same lane while m < 16
+// and the same-numbered (or mirrored) register of lane ^ (m / 16) otherwise.  Then nearest-rank
+// p50 = sorted[ceil(n/2) - 1] and p99 = sorted[ceil(0.99 n) - 1]; mean TPOT = mean over requests with more than
+// one token of (finish - first token) / (tokens - 1).
+constexpr uint32_t kPerLane = GUIDE_MAX_REQUESTS / kWave;       // 16
+static_assert(kPerLane == 16, "the network below is written for 16 values per lane");
+
+constexpr uint32_t top_bit(uint32_t x) { return x < 2 ? x : 2 * top_bit(x / 2); }
+// compare-exchange inside a lane: the smaller value to the smaller register
+__device__ inline void cx(double &a, double &b) {
+    const double lo = fmin(a, b), hi = fmax(a, b);
+    a = lo;
+    b = hi;
+}
+// One stage of the network.  MASK: the xor mask on element numbers.
+template <uint32_t MASK>
+__device__ inline void sort_stage(double (&v)[kPerLane], uint32_t lane) {
+    if constexpr (MASK < kPerLane) {
+#pragma unroll
+        for (uint32_t r = 0; r < kPerLane; ++r)
+            if ((r ^ MASK) > r) cx(v[r], v[r ^ MASK]);
+    } else {
+        constexpr uint32_t kLaneMask = MASK / kPerLane, kRegMask = MASK % kPerLane;     // kRegMask: 0 or 15 (mirror)
+        // this lane holds the smaller indices of its pairs when the top bit of the lane mask is clear in its number
+        constexpr uint32_t kTop = top_bit(kLaneMask);
+        const bool keep_min = (lane & kTop) == 0;
+        double o[kPerLane];
+#pragma unroll
+        for (uint32_t r = 0; r < kPerLane; ++r) o[r] = __shfl_xor(v[r ^ kRegMask], (int)kLaneMask, kWave);
+#pragma unroll
+        for (uint32_t r = 0; r < kPerLane; ++r) v[r] = keep_min ? fmin(v[r], o[r]) : fmax(v[r], o[r]);
+    }
+}
+// Merge of sorted runs of K / 2 elements into sorted runs of K: the mirror stage, then halving distances.
+template <uint32_t K>
+__device__ inline void sort_merge(double (&v)[kPerLane], uint32_t lane) {
+    sort_stage<K - 1>(v, lane);
+    if constexpr (K >= 4) sort_stage<K / 4>(v, lane);
+    if constexpr (K >= 8) sort_stage<K / 8>(v, lane);
+    if constexpr (K >= 16) sort_stage<K / 16>(v, lane);
+    if constexpr (K >= 32) sort_stage<K / 32>(v, lane);
+    if constexpr (K >= 64) sort_stage<K / 64>(v, lane);
+    if constexpr (K >= 128) sort_stage<K / 128>(v, lane);
+    if constexpr (K >= 256) sort_stage<K / 256>(v, lane);
+    if constexpr (K >= 512) sort_stage<K / 512>(v, lane);
+    if constexpr (K >= 1024) sort_stage<K / 1024>(v, lane);
+}
+// element `e` of the sorted sequence, in every lane
+__device__ inline double sorted_at(const double (&v)[kPerLane], uint32_t e) {
+    double x = v[0];
+#pragma unroll
+    for (uint32_t r = 1; r < kPerLane; ++r) x = (e % kPerLane) == r ? v[r] : x;
+    return __shfl(x, (int)(e / kPerLane), kWave);
+}
+
 __global__ __launch_bounds__(kPctBlock) void percentile_kernel(SimWs ws, const TraceDev *__restrict__ trace,
                                                                const double *__restrict__ rate_in, uint32_t n_req,
-                                                               guide_sim_out out) {
-    __shared__ double v[GUIDE_MAX_REQUESTS];
-    __shared__ double s_sum[kPctBlock / kWave];
-    __shared__ uint32_t s_cnt[kPctBlock / kWave];
-    const uint32_t c = blockIdx.x;
-    if (out.status[c] != GUIDE_SIM_OK) return;
+                                                               uint32_t n_cfg, guide_sim_out out) {
+    const uint32_t lane = threadIdx.x % kWave;
+    const uint32_t c = blockIdx.x * (kPctBlock / kWave) + threadIdx.x / kWave;      // wave-uniform
+    if (c >= n_cfg || out.status[c] != GUIDE_SIM_OK) return;
     const double rate = rate_in[c];
     const double *first = ws.first + (size_t)c * n_req, *fin = ws.fin + (size_t)c * n_req;
+    double v[kPerLane];
     double tp = 0.0;
     uint32_t n_tp = 0;
-    for (uint32_t i = threadIdx.x; i < GUIDE_MAX_REQUESTS; i += kPctBlock) {
+#pragma unroll
+    for (uint32_t r = 0; r < kPerLane; ++r) {
+        const uint32_t i = r * kWave + lane;                // coalesced; the sort does not care where a value starts
         double t = INFINITY;
         if (i < n_req) {
             const double f = first[i];
@@ -524,37 +579,28 @@ __global__ __launch_bounds__(kPctBlock) void percentile_kernel(SimWs ws, const T
                 ++n_tp;
             }
         }
-        v[i] = t;
+        v[r] = t;
     }
     for (int off = kWave / 2; off > 0; off >>= 1) {
         tp += __shfl_xor(tp, off, kWave);
         n_tp += __shfl_xor(n_tp, off, kWave);
     }
-    if (threadIdx.x % kWave == 0) {
-        s_sum[threadIdx.x / kWave] = tp;
-        s_cnt[threadIdx.x / kWave] = n_tp;
-    }
-    __syncthreads();
-    for (uint32_t k = 2; k <= GUIDE_MAX_REQUESTS; k <<= 1) {
-        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-            for (uint32_t i = threadIdx.x; i < GUIDE_MAX_REQUESTS; i += kPctBlock) {
-                const uint32_t l = i ^ j;
-                if (l > i) {
-                    const double a = v[i], b = v[l];
-                    const bool up = (i & k) == 0;
-                    if ((a > b) == up) { v[i] = b; v[l] = a; }
-                }
-            }
-            __syncthreads();
-        }
-    }
-    if (threadIdx.x == 0) {
-        out.ttft_p50[c] = v[(n_req + 1) / 2 - 1];
-        out.ttft_p99[c] = v[(99ull * n_req + 99) / 100 - 1];
-        double t = 0.0;
-        uint32_t n = 0;
-        for (uint32_t w = 0; w < kPctBlock / kWave; ++w) { t += s_sum[w]; n += s_cnt[w]; }
-        out.mean_tpot[c] = n ? t / (double)n : 0.0;
+    sort_merge<2>(v, lane);
+    sort_merge<4>(v, lane);
+    sort_merge<8>(v, lane);
+    sort_merge<16>(v, lane);
+    sort_merge<32>(v, lane);
+    sort_merge<64>(v, lane);
+    sort_merge<128>(v, lane);
+    sort_merge<256>(v, lane);
+    sort_merge<512>(v, lane);
+    sort_merge<1024>(v, lane);
+    const double p50 = sorted_at(v, (n_req + 1) / 2 - 1);
+    const double p99 = sorted_at(v, (uint32_t)((99ull * n_req + 99) / 100 - 1));
+    if (lane == 0) {
+        out.ttft_p50[c] = p50;
+        out.ttft_p99[c] = p99;
+        out.mean_tpot[c] = n_tp ? tp / (double)n_tp : 0.0;
     }
 }
 
@@ -623,7 +669,8 @@ hipError_t launch_simulate(const GridDesc &g, const DevTables *tab, const TraceD
         GUIDE_SIM(true, true, true, true)
     }
 #undef GUIDE_SIM
-    hipLaunchKernelGGL(percentile_kernel, dim3(n_cfg), dim3(kPctBlock), 0, stream, ws, trace, rate, n_req, out);
+    hipLaunchKernelGGL(percentile_kernel, dim3((n_cfg + kPctBlock / kWave - 1) / (kPctBlock / kWave)), dim3(kPctBlock), 0,
+                       stream, ws, trace, rate, n_req, n_cfg, out);
     return hipGetLastError();
 }
 
