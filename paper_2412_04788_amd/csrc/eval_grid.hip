@@ -158,7 +158,7 @@ __device__ inline void sample_rider(const GridLds &s, const GridDesc &g, uint32_
         sc->bin_min[i] = kNone;
         sc->bin_cnt[i] = 0;
     }
-    if (k == 0) sc->counters[0] = 0;
+    if (k == 0) sc->counters[0] = sc->counters[1] = 0;
     const uint32_t stride = count > n_samples ? count / n_samples : 1;
     uint64_t lo = kNone;
     Pair best = {kNone, kNone};
@@ -248,7 +248,7 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
                 sc->bin_min[i] = kNone;
                 sc->bin_cnt[i] = 0;
             }
-            if (blockIdx.x == 0 && threadIdx.x == 0) sc->counters[0] = 0;
+            if (blockIdx.x == 0 && threadIdx.x == 0) sc->counters[0] = sc->counters[1] = 0;
         }
     }
     __syncthreads();

@@ -51,7 +51,7 @@ static_assert(guide_ctx::kSlotBytes >= sizeof(DevTables), "staging slot too smal
 // selection over GUIDE_STATIC_SELECT_MAX_ROWS rows or any top-k selection).  Every GPU holds its own copy
 // at its own address: host code never uses the array's name as a pointer, only the address that
 // hipGetSymbolAddress returned for the device (static_scratch_of).
-constexpr size_t kStaticWsBytes = (size_t)GUIDE_STATIC_SELECT_MAX_ROWS * 25 + 256;
+constexpr size_t kStaticWsBytes = (size_t)GUIDE_STATIC_SELECT_MAX_ROWS * 29 + 256;
 static __device__ __align__(256) unsigned char scratch[kSelectScratchMax + kStaticWsBytes];
 constexpr int kMaxDevices = 64;
 static void *g_static_scratch[kMaxDevices];      // per device: address of `scratch` there, set by guide_create

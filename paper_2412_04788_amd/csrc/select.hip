@@ -384,16 +384,19 @@ constexpr uint32_t kFinishThreads = 1024;
 struct ParetoWs {
     uint64_t *skx, *sky;  // [n]: keys of surviving rows
     uint32_t *surv;       // [n]: surviving rows, arbitrary order
-    uint32_t *grouped;    // [n]: positions into surv, grouped by bin (large-front path)
-    uint8_t *on_front;    // [n]: flag per grouped survivor (large-front path)
+    // large-front path only:
+    uint32_t *staged;     // [n]: per part of the front, from its first survivor slot on: its front members' rows in order
+    uint32_t *grouped;    // [n]: positions into surv, grouped by bin (parts whose survivors do not fit LDS)
+    uint8_t *on_front;    // [n]: flag per grouped survivor (the same parts)
 };
-size_t pareto_ws_bytes(uint64_t n) { return (size_t)n * (8 + 8 + 4 + 4 + 1) + 256; }
+size_t pareto_ws_bytes(uint64_t n) { return (size_t)n * (8 + 8 + 4 + 4 + 4 + 1) + 256; }
 ParetoWs pareto_ws(void *ws, uint64_t n) {
     ParetoWs w;
     w.skx = (uint64_t *)ws;
     w.sky = w.skx + n;
     w.surv = (uint32_t *)(w.sky + n);
-    w.grouped = w.surv + n;
+    w.staged = w.surv + n;
+    w.grouped = w.staged + n;
     w.on_front = (uint8_t *)(w.grouped + n);
     return w;
 }
@@ -436,7 +439,7 @@ __device__ void pareto_prepare_body(uint32_t block, const double *__restrict__ x
         sc->bin_min[k] = kNone;
         sc->bin_cnt[k] = 0;
     }
-    if (k == 0) sc->counters[0] = 0;
+    if (k == 0) sc->counters[0] = sc->counters[1] = 0;
     const uint32_t stride = n > n_samples ? n / n_samples : 1;
     const Row r = load_row<true, GUIDE_MAX_CONSTRAINTS>(x, y, f, (uint64_t)k * stride < n ? k * stride : n, n);
     uint64_t lo = kNone;
@@ -739,11 +742,286 @@ __global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *
     }
 }
 
+// LDS of the finishing kernel.
+struct FinishLds {
+    uint32_t off[padded_size<kPerFinish>()];    // first survivor slot per bin (exclusive scan of the bin counts)
+    uint32_t foff[padded_size<kPerFinish>()];   // front members per bin, then their exclusive scan
+    uint32_t cur[kBins];                        // fill level per bin while grouping; then the list of front members
+    uint32_t tmp[kFinishThreads / kWave];
+    uint64_t kx[kStage], ky[kStage];            // staged survivor records, grouped by bin
+    uint32_t row[kStage];
+    uint16_t bin[kStage];
+    uint8_t flag[kStage];
+    uint32_t nfront, first, last, is_last;
+    uint32_t part_base[kWave], part_lo[kWave], part_cnt[kWave];
+    uint64_t rng[2];
+};
+
+// The front among `cnt` survivor records staged in LDS, grouped by bin: record i of bin b sits at
+// L.off[b] - base + i.  L.foff must be zero and the staging complete (the function starts with a barrier).
+// Calls emit(position, row) for every front member, position = its rank by (bin, x, y, row) among the
+// front members staged here, and returns their number.
+// Eight lanes per survivor: they share out the members of its bin, four LDS reads in flight each, and
+// meet through a wave ballot.  A survivor's test is a chain of dependent LDS reads, so many survivors
+// are kept in flight; fewer lanes per survivor (one round over all survivors, longer chains) measured
+// slower.
+template <typename Emit>
+__device__ inline uint32_t staged_front(FinishLds &L, uint32_t cnt, uint32_t base, Emit &&emit) {
+    constexpr uint32_t P = kPerFinish, group = 8, q_step = kFinishThreads / group;
+    constexpr uint64_t group_mask = (1ull << group) - 1;
+    const uint32_t t = threadIdx.x, lane = t % kWave, sub = lane % group, shift = lane - sub;
+    __syncthreads();
+    const uint32_t cnt_pad = (cnt + q_step - 1) / q_step * q_step;      // wave-uniform trip count for the ballot
+    for (uint32_t q = t / group; q < cnt_pad; q += q_step) {
+        const bool live = q < cnt;
+        const uint64_t kx = live ? L.kx[q] : 0, ky = live ? L.ky[q] : 0;
+        const uint32_t b = live ? L.bin[q] : 0;
+        const uint32_t beg = live ? L.off[padded<P>(b)] - base : 0, end = live ? L.off[padded<P>(b + 1)] - base : 0;
+        bool dom = false;
+        for (uint32_t j = beg + sub; j < end; j += 4 * group) {
+            uint64_t jx[4], jy[4];
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) {      // past the end: the bin's first member once more
+                const uint32_t jj = j + u * group < end ? j + u * group : beg;
+                jx[u] = L.kx[jj];
+                jy[u] = L.ky[jj];
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u)
+                dom = dom || (jx[u] <= kx && jy[u] <= ky && (jx[u] < kx || jy[u] < ky));
+        }
+        const bool dominated = ((__ballot(dom) >> shift) & group_mask) != 0;
+        if (live && sub == 0) {
+            L.flag[q] = dominated ? 0 : 1;
+            if (!dominated) {
+                atomicAdd(&L.foff[padded<P>(b)], 1u);
+                L.cur[atomicAdd(&L.nfront, 1u)] = q;        // L.cur is free again: list of front members
+            }
+        }
+    }
+    __syncthreads();
+    scan_sum_excl<kFinishThreads, true>(L.foff, L.tmp);
+    const uint32_t nf = L.nfront;
+    const uint32_t f_pad = (nf + q_step - 1) / q_step * q_step;          // wave-uniform trip count for the shuffles
+    for (uint32_t qf = t / group; qf < f_pad; qf += q_step) {
+        const bool live = qf < nf;
+        const uint32_t q = live ? L.cur[qf] : 0;
+        const uint64_t kx = live ? L.kx[q] : 0, ky = live ? L.ky[q] : 0;
+        const uint32_t b = live ? L.bin[q] : 0, i = live ? L.row[q] : 0;
+        const uint32_t beg = live ? L.off[padded<P>(b)] - base : 0, end = live ? L.off[padded<P>(b + 1)] - base : 0;
+        uint32_t rank = 0;                          // front members of the bin that come before this one
+        for (uint32_t j = beg + sub; j < end; j += 4 * group) {
+            uint64_t jx[4], jy[4];
+            uint32_t jr[4];
+            bool on[4];
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) {
+                const uint32_t jj = j + u * group;
+                on[u] = jj < end;
+                const uint32_t jc = on[u] ? jj : beg;
+                on[u] = on[u] && L.flag[jc];
+                jx[u] = L.kx[jc];
+                jy[u] = L.ky[jc];
+                jr[u] = L.row[jc];
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u)
+                rank += (on[u] && (jx[u] < kx || (jx[u] == kx && (jy[u] < ky || (jy[u] == ky && jr[u] < i))))) ? 1u : 0u;
+        }
+        for (uint32_t off = 1; off < group; off <<= 1) rank += __shfl_xor(rank, off, kWave);
+        if (live && sub == 0) emit(L.foff[padded<P>(b)] + rank, i);
+    }
+    return nf;
+}
+
+// The same for a part of the front whose survivors do not fit the staging arrays: the records stay in the
+// workspace, grouped by bin through w.grouped (slots g_lo .. g_lo + cnt), flags in w.on_front.
+template <typename Emit>
+__device__ inline uint32_t unstaged_front(FinishLds &L, const ParetoWs &w, const Binning &bin, uint32_t m, uint32_t b_lo,
+                                          uint32_t b_hi, Emit &&emit) {
+    constexpr uint32_t P = kPerFinish, NT = kFinishThreads, group = 8, q_step = NT / group;
+    constexpr uint64_t group_mask = (1ull << group) - 1;
+    const uint32_t t = threadIdx.x, lane = t % kWave, sub = lane % group, shift = lane - sub;
+    for (uint32_t q = t; q < m; q += NT) {
+        const uint32_t b = bin(w.skx[q]);
+        if (b >= b_lo && b <= b_hi) w.grouped[L.off[padded<P>(b)] + atomicAdd(&L.cur[b], 1u)] = q;
+    }
+    __syncthreads();
+    const uint32_t g_lo = L.off[padded<P>(b_lo)], cnt = L.off[padded<P>(b_hi + 1)] - g_lo;
+    const uint32_t cnt_pad = (cnt + q_step - 1) / q_step * q_step;       // wave-uniform trip counts
+    for (uint32_t k = t / group; k < cnt_pad; k += q_step) {
+        const bool live = k < cnt;
+        const uint32_t g = g_lo + (live ? k : 0), q = w.grouped[g];
+        const uint64_t kx = w.skx[q], ky = w.sky[q];
+        const uint32_t b = bin(kx), beg = L.off[padded<P>(b)], end = L.off[padded<P>(b + 1)];
+        bool dom = false;
+        for (uint32_t j = beg + sub; j < end; j += 2 * group) {
+            const uint32_t j1 = j + group < end ? j + group : beg;       // past the end: the first member again
+            const uint32_t q0 = w.grouped[j], q1 = w.grouped[j1];
+            const uint64_t x0 = w.skx[q0], y0 = w.sky[q0], x1 = w.skx[q1], y1 = w.sky[q1];
+            dom = dom || (x0 <= kx && y0 <= ky && (x0 < kx || y0 < ky)) || (x1 <= kx && y1 <= ky && (x1 < kx || y1 < ky));
+        }
+        const bool dominated = ((__ballot(dom) >> shift) & group_mask) != 0;
+        if (live && sub == 0) {
+            w.on_front[g] = dominated ? 0 : 1;
+            if (!dominated) atomicAdd(&L.foff[padded<P>(b)], 1u);
+        }
+    }
+    __syncthreads();
+    scan_sum_excl<NT, true>(L.foff, L.tmp);
+    for (uint32_t k = t / group; k < cnt_pad; k += q_step) {
+        const bool live = k < cnt;
+        const uint32_t g = g_lo + (live ? k : 0), q = w.grouped[g];
+        const bool front = live && w.on_front[g];
+        uint32_t rank = 0, b = 0;
+        if (front) {
+            const uint64_t kx = w.skx[q], ky = w.sky[q];
+            b = bin(kx);
+            const uint32_t beg = L.off[padded<P>(b)], end = L.off[padded<P>(b + 1)];
+            for (uint32_t j = beg + sub; j < end; j += group) {
+                if (!w.on_front[j]) continue;
+                const uint32_t qj = w.grouped[j];
+                const uint64_t jx = w.skx[qj], jy = w.sky[qj];
+                if (jx < kx || (jx == kx && (jy < ky || (jy == ky && w.surv[qj] < w.surv[q])))) ++rank;
+            }
+        }
+        for (uint32_t off = 1; off < group; off <<= 1) rank += __shfl_xor(rank, off, kWave);
+        if (front && sub == 0) emit(L.foff[padded<P>(b)] + rank, w.surv[q]);
+    }
+    return L.foff[padded<P>(kBins)];
+}
+
+// A front of more than kStage survivors, finished by the n_parts blocks of the launch that call this (part =
+// 0 .. n_parts - 1).  Bins are independent until positions in the output are handed out, so each part takes a
+// run of consecutive bins that holds about m / n_parts survivors (bin b belongs to part floor(first survivor
+// slot of b * n_parts / m)), finds the front members among them, and writes their rows, in order, to the
+// workspace from its first survivor slot on.  No part waits for
+// another: each ends by taking a ticket, and the part that draws the last one lines the parts' runs up in
+// the output.
+constexpr uint32_t kLargeParts = 64;                    // blocks that finish a large front (the finishing block is one)
+static_assert(kLargeParts <= kWave, "the last part scans the parts' counts in one wave");
+static_assert(kLargeParts <= sizeof(SelectScratch::part_cnt) / sizeof(uint32_t), "one scratch entry per part");
+__device__ void pareto_large_front(FinishLds &L, const ParetoWs &w, SelectScratch *sc, const Binning &bin, uint32_t m,
+                                   uint32_t part, uint32_t n_parts, uint64_t *out_idx, uint64_t capacity,
+                                   uint64_t *out_count) {
+    constexpr uint32_t P = kPerFinish, NT = kFinishThreads;
+    const uint32_t t = threadIdx.x;
+#pragma unroll
+    for (uint32_t q = 0; q < P; ++q) {
+        const uint32_t i = q * NT + t;
+        L.off[padded<P>(i)] = sc->bin_cnt[i];
+        L.foff[padded<P>(i)] = 0;
+        L.cur[i] = 0;
+    }
+    if (t == 0) {
+        L.first = kBins;
+        L.last = 0;
+    }
+    __syncthreads();
+    scan_sum_excl<NT, true>(L.off, L.tmp);              // entry kBins = m
+#pragma unroll
+    for (uint32_t q = 0; q < P; ++q) {
+        const uint32_t i = q * NT + t, off = L.off[padded<P>(i)];
+        if (L.off[padded<P>(i + 1)] != off && (uint32_t)((uint64_t)off * n_parts / m) == part) {
+            atomicMin(&L.first, i);
+            atomicMax(&L.last, i);
+        }
+    }
+    __syncthreads();
+    const uint32_t b_lo = L.first, b_hi = L.last;       // this part's bins (non-empty ones in between are all its own)
+    uint32_t g_lo = 0, n_front = 0;
+    if (b_lo <= b_hi) {
+        g_lo = L.off[padded<P>(b_lo)];
+        auto emit = [&](uint32_t pos, uint32_t row) { w.staged[g_lo + n_front + pos] = row; };
+        // In rounds: each takes as many of the part's bins as fit the staging arrays (a single bin that does
+        // not fit is finished in the workspace instead).
+        for (uint32_t r_lo = b_lo; r_lo <= b_hi;) {
+            __syncthreads();                            // the previous round is done with the tables
+            if (t == 0) {
+                L.last = r_lo;
+                L.nfront = 0;
+            }
+            const uint32_t base = L.off[padded<P>(r_lo)];
+#pragma unroll
+            for (uint32_t q = 0; q < P; ++q) {
+                const uint32_t i = q * NT + t;
+                L.foff[padded<P>(i)] = 0;
+                L.cur[i] = 0;
+            }
+            __syncthreads();
+#pragma unroll
+            for (uint32_t q = 0; q < P; ++q) {
+                const uint32_t i = q * NT + t;
+                if (i > r_lo && i <= b_hi && L.off[padded<P>(i + 1)] - base <= kStage) atomicMax(&L.last, i);
+            }
+            __syncthreads();
+            const uint32_t r_hi = L.last, cnt = L.off[padded<P>(r_hi + 1)] - base;
+            uint32_t nf;
+            if (cnt <= kStage) {
+                // four keys requested at a time: the pass over all survivors is a chain of load latencies otherwise
+                for (uint32_t q0 = t; q0 < m; q0 += 4 * NT) {
+                    uint64_t kx[4];
+#pragma unroll
+                    for (uint32_t u = 0; u < 4; ++u) kx[u] = w.skx[q0 + u * NT < m ? q0 + u * NT : q0];
+#pragma unroll
+                    for (uint32_t u = 0; u < 4; ++u) {
+                        const uint32_t q = q0 + u * NT, b = bin(kx[u]);
+                        if (q < m && b >= r_lo && b <= r_hi) {
+                            const uint32_t pos = L.off[padded<P>(b)] - base + atomicAdd(&L.cur[b], 1u);
+                            L.kx[pos] = kx[u];
+                            L.ky[pos] = w.sky[q];
+                            L.row[pos] = w.surv[q];
+                            L.bin[pos] = (uint16_t)b;
+                        }
+                    }
+                }
+                nf = staged_front(L, cnt, base, emit);
+            } else {
+                nf = unstaged_front(L, w, bin, m, r_lo, r_hi, emit);
+            }
+            n_front += nf;
+            r_lo = r_hi + 1;
+        }
+    }
+    if (t == 0) {
+        sc->part_lo[part] = g_lo;
+        sc->part_cnt[part] = n_front;
+    }
+    // the ticket: everything this part wrote is visible to the part that draws the last one
+    __threadfence();
+    __syncthreads();
+    if (t == 0) L.is_last = atomicAdd(&sc->counters[1], 1u) == n_parts - 1 ? 1u : 0u;
+    __syncthreads();
+    if (!L.is_last) return;
+    __threadfence();
+    if (t < kWave) {
+        const uint32_t c = t < n_parts ? sc->part_cnt[t] : 0u;
+        const uint32_t incl = wave_scan_sum(c);
+        L.part_base[t] = incl - c;
+        L.part_cnt[t] = c;
+        L.part_lo[t] = t < n_parts ? sc->part_lo[t] : 0u;
+        if (t == kWave - 1) {
+            out_count[0] = incl;
+            sc->counters[1] = 0;
+        }
+    }
+    __syncthreads();
+    for (uint32_t p = 0; p < n_parts; ++p) {
+        const uint32_t c = L.part_cnt[p], lo = L.part_lo[p];
+        const uint64_t base = L.part_base[p];
+        for (uint32_t i = t; i < c; i += NT)
+            if (base + i < capacity) out_idx[base + i] = w.staged[lo + i];
+    }
+}
+
+// Blocks of the launch: 0 finishes the front; 1 runs a waiting top-k merge (only launched with one); the
+// others return at once unless more than kStage rows survived, and then share the large front with block 0.
 __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs w, uint32_t n, SelectScratch *sc,
                                                                         uint32_t n_partials, uint64_t *out_idx,
                                                                         uint64_t capacity, uint64_t *out_count,
                                                                         MergeRider rider) {
-    if (blockIdx.x == 1) {                              // second block, launched only with a waiting top-k merge
+    const uint32_t first_helper = rider.n_blocks ? 2 : 1;
+    if (rider.n_blocks && blockIdx.x == 1) {
         if (rider.K == 1)
             topk_merge_body<1, kFinishThreads>(rider.w, rider.n_blocks, rider.k, rider.out_idx, rider.out_val, rider.out_cnt);
         else if (rider.K == 2)
@@ -756,172 +1034,57 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
     }
     static_assert(kFinishThreads == 1024, "kPerFinish assumes 1024 threads");
     constexpr uint32_t P = kPerFinish;
-    __shared__ uint32_t s_off[padded_size<P>()], s_foff[padded_size<P>()], s_cur[kBins], s_tmp[kFinishThreads / kWave];
-    __shared__ uint64_t s_kx[kStage], s_ky[kStage];
-    __shared__ uint32_t s_row[kStage];
-    __shared__ uint16_t s_bin[kStage];
-    __shared__ uint8_t s_flag[kStage];
-    __shared__ uint32_t s_nfront;
+    __shared__ FinishLds L;
     const uint32_t t = threadIdx.x;
-    __shared__ uint64_t s_rng[2];
-    if (threadIdx.x == 0) s_nfront = 0;
-    // Everything the block reads from global memory is requested at once, before the survivor count is
-    // known: the first kStage survivor records (index clamped to the workspace's n rows; entries at or
-    // beyond the count are ignored later), the count, the bin counts and the sample partials.
+    const bool helper = blockIdx.x >= first_helper;     // block-uniform
+    if (helper && sc->counters[0] <= kStage) return;
+    if (threadIdx.x == 0) L.nfront = 0;
+    // Everything the finishing block reads from global memory is requested at once, before the survivor
+    // count is known: the first kStage survivor records (index clamped to the workspace's n rows; entries
+    // at or beyond the count are ignored later), the count, the bin counts and the sample partials.
     constexpr uint32_t kPer = kStage / kFinishThreads;
     uint64_t rx[kPer], ry[kPer];
     uint32_t rr[kPer], cnt_in[kPerFinish];
-#pragma unroll
-    for (uint32_t q = 0; q < kPer; ++q) {
-        const uint32_t j = q * kFinishThreads + t, jc = j < n ? j : n - 1;
-        rx[q] = w.skx[jc];
-        ry[q] = w.sky[jc];
-        rr[q] = w.surv[jc];
-    }
-#pragma unroll
-    for (uint32_t q = 0; q < kPerFinish; ++q) cnt_in[q] = sc->bin_cnt[q * kFinishThreads + t];
-    const uint32_t m = sc->counters[0];
-    const Binning bin = sampled_binning(sc, n_partials, s_rng);
-    if (m <= kStage) {
-        // records staged in LDS, grouped by bin
-#pragma unroll
-        for (uint32_t q = 0; q < kPerFinish; ++q) {
-            const uint32_t i = q * kFinishThreads + t;
-            s_off[padded<P>(i)] = cnt_in[q];
-            s_cur[i] = 0;
-            s_foff[padded<P>(i)] = 0;
-        }
-        __syncthreads();
-        scan_sum_excl<kFinishThreads, true>(s_off, s_tmp);
+    if (!helper) {
 #pragma unroll
         for (uint32_t q = 0; q < kPer; ++q) {
-            if (q * kFinishThreads + t < m) {
-                const uint32_t b = bin(rx[q]);
-                const uint32_t pos = s_off[padded<P>(b)] + atomicAdd(&s_cur[b], 1u);
-                s_kx[pos] = rx[q]; s_ky[pos] = ry[q]; s_row[pos] = rr[q]; s_bin[pos] = (uint16_t)b;
-            }
+            const uint32_t j = q * kFinishThreads + t, jc = j < n ? j : n - 1;
+            rx[q] = w.skx[jc];
+            ry[q] = w.sky[jc];
+            rr[q] = w.surv[jc];
         }
-        __syncthreads();
-        // Eight lanes per survivor: they share out the members of its bin, four LDS reads in flight each,
-        // and meet through a wave ballot.  A survivor's test is a chain of dependent LDS reads, so many
-        // survivors are kept in flight; fewer lanes per survivor (one round over all survivors, longer
-        // chains) measured slower.
-        constexpr uint32_t group = 8;
-        const uint32_t lane = t % kWave;
-        {
-            const uint32_t sub = lane % group, shift = lane - sub, q_step = kFinishThreads / group;
-            constexpr uint64_t group_mask = (1ull << group) - 1;
-            const uint32_t m_pad = (m + q_step - 1) / q_step * q_step;   // wave-uniform trip count for the ballot
-            for (uint32_t q = t / group; q < m_pad; q += q_step) {
-                const bool live = q < m;
-                const uint64_t kx = live ? s_kx[q] : 0, ky = live ? s_ky[q] : 0;
-                const uint32_t b = live ? s_bin[q] : 0;
-                const uint32_t beg = live ? s_off[padded<P>(b)] : 0, end = live ? s_off[padded<P>(b + 1)] : 0;
-                bool dom = false;
-                for (uint32_t j = beg + sub; j < end; j += 4 * group) {
-                    uint64_t jx[4], jy[4];
 #pragma unroll
-                    for (uint32_t u = 0; u < 4; ++u) {      // past the end: the bin's first member once more
-                        const uint32_t jj = j + u * group < end ? j + u * group : beg;
-                        jx[u] = s_kx[jj];
-                        jy[u] = s_ky[jj];
-                    }
+        for (uint32_t q = 0; q < kPerFinish; ++q) cnt_in[q] = sc->bin_cnt[q * kFinishThreads + t];
+    }
+    const uint32_t m = sc->counters[0];
+    const Binning bin = sampled_binning(sc, n_partials, L.rng);
+    if (m > kStage) {
+        pareto_large_front(L, w, sc, bin, m, helper ? blockIdx.x - first_helper + 1 : 0, gridDim.x - first_helper + 1,
+                           out_idx, capacity, out_count);
+        return;
+    }
+    // records staged in LDS, grouped by bin
 #pragma unroll
-                    for (uint32_t u = 0; u < 4; ++u)
-                        dom = dom || (jx[u] <= kx && jy[u] <= ky && (jx[u] < kx || jy[u] < ky));
-                }
-                const bool dominated = ((__ballot(dom) >> shift) & group_mask) != 0;
-                if (live && sub == 0) {
-                    s_flag[q] = dominated ? 0 : 1;
-                    if (!dominated) {
-                        atomicAdd(&s_foff[padded<P>(b)], 1u);
-                        s_cur[atomicAdd(&s_nfront, 1u)] = q;        // s_cur is free again: list of front members
-                    }
-                }
-            }
-        }
-        __syncthreads();
-        scan_sum_excl<kFinishThreads, true>(s_foff, s_tmp);
-        if (t == 0) out_count[0] = s_foff[padded<P>(kBins)];
-        const uint32_t nf = s_nfront;
-        {
-            const uint32_t sub = lane % group, q_step = kFinishThreads / group;
-            const uint32_t f_pad = (nf + q_step - 1) / q_step * q_step;  // wave-uniform trip count for the shuffles
-            for (uint32_t qf = t / group; qf < f_pad; qf += q_step) {
-                const bool live = qf < nf;
-                const uint32_t q = live ? s_cur[qf] : 0;
-                const uint64_t kx = live ? s_kx[q] : 0, ky = live ? s_ky[q] : 0;
-                const uint32_t b = live ? s_bin[q] : 0, i = live ? s_row[q] : 0;
-                const uint32_t beg = live ? s_off[padded<P>(b)] : 0, end = live ? s_off[padded<P>(b + 1)] : 0;
-                uint32_t rank = 0;                          // front members of the bin that come before this one
-                for (uint32_t j = beg + sub; j < end; j += 4 * group) {
-                    uint64_t jx[4], jy[4];
-                    uint32_t jr[4];
-                    bool on[4];
+    for (uint32_t q = 0; q < kPerFinish; ++q) {
+        const uint32_t i = q * kFinishThreads + t;
+        L.off[padded<P>(i)] = cnt_in[q];
+        L.cur[i] = 0;
+        L.foff[padded<P>(i)] = 0;
+    }
+    __syncthreads();
+    scan_sum_excl<kFinishThreads, true>(L.off, L.tmp);
 #pragma unroll
-                    for (uint32_t u = 0; u < 4; ++u) {
-                        const uint32_t jj = j + u * group;
-                        on[u] = jj < end;
-                        const uint32_t jc = on[u] ? jj : beg;
-                        on[u] = on[u] && s_flag[jc];
-                        jx[u] = s_kx[jc];
-                        jy[u] = s_ky[jc];
-                        jr[u] = s_row[jc];
-                    }
-#pragma unroll
-                    for (uint32_t u = 0; u < 4; ++u)
-                        rank += (on[u] && (jx[u] < kx || (jx[u] == kx && (jy[u] < ky || (jy[u] == ky && jr[u] < i))))) ? 1u : 0u;
-                }
-                for (uint32_t off = 1; off < group; off <<= 1) rank += __shfl_xor(rank, off, kWave);
-                const uint64_t pos = (uint64_t)s_foff[padded<P>(b)] + rank;
-                if (live && sub == 0 && pos < capacity) out_idx[pos] = i;
-            }
-        }
-    } else {
-        // large front: the same steps through global tables
-        for (uint32_t i = t; i < kBins; i += kFinishThreads) {
-            sc->bin_off[i] = sc->bin_cnt[i];
-            sc->bin_cur[i] = 0;
-            sc->bin_foff[i] = 0;
-        }
-        __syncthreads();
-        scan_sum_excl<kFinishThreads, false>(sc->bin_off, s_tmp);
-        for (uint32_t q = t; q < m; q += kFinishThreads) {
-            const uint32_t b = bin(w.skx[q]);
-            w.grouped[sc->bin_off[b] + atomicAdd(&sc->bin_cur[b], 1u)] = q;
-        }
-        __syncthreads();
-        for (uint32_t g = t; g < m; g += kFinishThreads) {
-            const uint32_t q = w.grouped[g];
-            const uint64_t kx = w.skx[q], ky = w.sky[q];
-            const uint32_t b = bin(kx);
-            bool dominated = false;
-            for (uint32_t h = sc->bin_off[b]; h < sc->bin_off[b + 1] && !dominated; ++h) {
-                const uint64_t jx = w.skx[w.grouped[h]], jy = w.sky[w.grouped[h]];
-                dominated = jx <= kx && jy <= ky && (jx < kx || jy < ky);
-            }
-            w.on_front[g] = dominated ? 0 : 1;
-            if (!dominated) atomicAdd(&sc->bin_foff[b], 1u);
-        }
-        __syncthreads();
-        scan_sum_excl<kFinishThreads, false>(sc->bin_foff, s_tmp);
-        if (t == 0) out_count[0] = sc->bin_foff[kBins];
-        for (uint32_t g = t; g < m; g += kFinishThreads) {
-            if (!w.on_front[g]) continue;
-            const uint32_t q = w.grouped[g];
-            const uint64_t kx = w.skx[q], ky = w.sky[q];
-            const uint32_t b = bin(kx), i = w.surv[q];
-            uint32_t rank = 0;
-            for (uint32_t h = sc->bin_off[b]; h < sc->bin_off[b + 1]; ++h) {
-                if (!w.on_front[h]) continue;
-                const uint32_t qj = w.grouped[h];
-                const uint64_t jx = w.skx[qj], jy = w.sky[qj];
-                if (jx < kx || (jx == kx && (jy < ky || (jy == ky && w.surv[qj] < i)))) ++rank;
-            }
-            const uint64_t pos = (uint64_t)sc->bin_foff[b] + rank;
-            if (pos < capacity) out_idx[pos] = i;
+    for (uint32_t q = 0; q < kPer; ++q) {
+        if (q * kFinishThreads + t < m) {
+            const uint32_t b = bin(rx[q]);
+            const uint32_t pos = L.off[padded<P>(b)] + atomicAdd(&L.cur[b], 1u);
+            L.kx[pos] = rx[q]; L.ky[pos] = ry[q]; L.row[pos] = rr[q]; L.bin[pos] = (uint16_t)b;
         }
     }
+    const uint32_t n_front = staged_front(L, m, 0, [&](uint32_t pos, uint32_t row) {
+        if (pos < capacity) out_idx[pos] = row;
+    });
+    if (t == 0) out_count[0] = n_front;
 }
 
 __global__ void pareto_empty_kernel(uint64_t *out_count) { out_count[0] = 0; }
@@ -1031,8 +1194,9 @@ static hipError_t launch_pareto_passes(const guide_select_spec &spec, uint64_t n
                                chunk);
         });
     });
-    hipLaunchKernelGGL(pareto_finish_kernel, dim3(rider.n_blocks ? 2 : 1), dim3(kFinishThreads), 0, stream, w, n32, sc,
-                       n_partials, out.idx, out.capacity, out.count, rider);
+    const uint32_t helpers = n > kStage ? kLargeParts - 1 : 0;     // no more than kStage rows: the staged path for sure
+    hipLaunchKernelGGL(pareto_finish_kernel, dim3((rider.n_blocks ? 2 : 1) + helpers), dim3(kFinishThreads), 0, stream, w,
+                       n32, sc, n_partials, out.idx, out.capacity, out.count, rider);
     return hipGetLastError();
 }
 

@@ -16,12 +16,12 @@ constexpr uint32_t kSelBlocks = 1024;      // most blocks of a streaming pass (f
 constexpr uint32_t kBins = 4096;
 constexpr uint32_t kMaxSamplePartials = 512;     // blocks of the kernel that samples rows (prepare or evaluation)
 struct SelectScratch {
-    uint32_t counters[4];          // [0] survivors appended
+    uint32_t counters[4];          // [0] survivors appended, [1] tickets drawn by the parts of a large front
     uint64_t sample_lo[kMaxSamplePartials];   // per sampling block: least x key of passing sample rows
     Pair sample_best[kMaxSamplePartials];     // per sampling block: (least y key, its x key)
     uint64_t bin_min[kBins];       // y keys per x bin whose exclusive prefix-min is that of the least y per bin
     uint32_t bin_cnt[kBins];       // survivors per bin
-    uint32_t bin_off[kBins + 1], bin_foff[kBins + 1], bin_cur[kBins];   // large-front path only
+    uint32_t part_lo[64], part_cnt[64];   // large-front path only: per part, its first survivor slot and its front members
 };
 
 // Sorted list of the K least (key, row) pairs seen by one lane.

@@ -232,6 +232,38 @@ def test_pareto_large_front_and_repeated_calls(ora, torch_cuda):
         np.testing.assert_array_equal(got, ora.pareto_brute(xs, ys))
 
 
+def test_pareto_large_front_ties_and_one_crowded_bin(ora, torch_cuda):
+    """Large fronts that the finishing blocks share out by bin: (a) rows in identical triples, all on the front
+    (order among equal points is by row); (b) a staircase of 20000 rows that lies beyond the sampled range, so
+    that one bin, and with it one block, holds more survivors than fit its LDS staging."""
+    torch = torch_cuda
+    ctx = bridge.gpu_context(wl.grid_tiny())
+    n = 30000
+    t = (np.arange(n) // 3).astype(np.float64)
+    rng = np.random.default_rng(23)
+    perm = rng.permutation(n)
+    x, y = t[perm], -t[perm]
+    got, m = _pareto(torch, ctx, _dev(torch, x), _dev(torch, y))
+    exp = ora.pareto_sweep(x, y, None)
+    assert m == n == len(exp)
+    np.testing.assert_array_equal(got, exp)
+    n = 40000                                             # the kernels sample the even rows here
+    x = rng.random(n) * 100.0
+    y = rng.random(n) * 100.0
+    odd = np.arange(1, n, 2)
+    x[odd] = 1000.0 + odd
+    y[odd] = -1.0 * odd
+    x[odd[::7]] = x[odd[::7] - 2 * (odd[::7] > 1)]        # some equal x in the staircase: only the lower y stays
+    got, m = _pareto(torch, ctx, _dev(torch, x), _dev(torch, y))
+    exp = ora.pareto_sweep(x, y, None)
+    assert m == len(exp) > 15000
+    np.testing.assert_array_equal(got, exp)
+    # and a small front straight after, on the same context
+    xs = rng.integers(0, 50, 3000).astype(np.float64); ys = rng.integers(0, 50, 3000).astype(np.float64)
+    got, m = _pareto(torch, ctx, _dev(torch, xs), _dev(torch, ys))
+    np.testing.assert_array_equal(got, ora.pareto_brute(xs, ys))
+
+
 def test_sweep_other_tile_shapes_and_additive(ora, torch_cuda):
     torch = torch_cuda
     hws = [wl.Hardware(3.0e14, 6.0e12, 141 * wl.GIB, 4.5e11, 2.5e-6)]
