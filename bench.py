@@ -26,12 +26,13 @@ VECTOR_ISSUE_PEAK = 256 * 4 * 16 * 2.4e9      # lane-instructions per second: 25
 # Figures taken from rocprofv3 counter runs (profiles/*.md), each with the SHA-256 (first 16 hex digits) of the
 # kernel sources it was measured on.  A figure is reported only while those sources are unchanged, else null.
 COUNTERS = {
-    # WRITE_SIZE 83531.33 KiB x 1.0 + FETCH_SIZE 198.23 KiB x 2.0 per launch (scales from a 512 MiB device copy):
-    # profiles/eval_tile_kernel_full_grid_pmc.md
-    "eval_tile_traffic_bytes": {"value": 85_942_057, "sources": ("eval_grid.hip", "perf_model.hpp"),
-                                "sha16": "unset"},
-    # SQ_INSTS_VALU x 64 / duration / peak for simulate_kernel, split-fuse, stepped: profiles/extra_kernels_valu_pmc.md
-    "simulate_vector_issue_frac": {"value": None, "sources": ("simulate.hip", "perf_model.hpp"), "sha16": "unset"},
+    # in-step launches (with the row-sample blocks): WRITE_SIZE 83584.32 KiB x 1.0 + FETCH_SIZE 240.34 KiB x 2.0 per
+    # launch (scales from a 512 MiB device copy): profiles/eval_tile_kernel_full_grid_pmc.md
+    "eval_tile_traffic_bytes": {"value": 86_082_560, "sources": ("eval_grid.hip", "perf_model.hpp"),
+                                "sha16": "622e6a8a20532b32"},
+    # SQ_INSTS_VALU 5.135e9 x 64 / 40.99 ms / 39.32e12 for simulate_kernel, split-fuse, stepped:
+    # profiles/extra_kernels_valu_pmc.md
+    "simulate_vector_issue_frac": {"value": 0.204, "sources": ("simulate.hip", "perf_model.hpp"), "sha16": "78cd9103d96c831d"},
 }
 
 
@@ -63,6 +64,9 @@ def main():
     ap.add_argument("--probe-extra", action="store_true",
                     help="counter probe: the sweep (1.9M x 64), the sampled space (2^28) and the simulation "
                          "(65 536 configs) only")
+    ap.add_argument("--probe-fronts", action="store_true",
+                    help="times guide_select PARETO over 1 900 800 synthetic rows whose front has 100 ... 1 900 800 "
+                         "members (a dominated cloud plus a staircase), one JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: the library runs on ONE GPU (no sharding, no collectives); use --gpus 1")
@@ -107,6 +111,9 @@ def main():
     call_pareto = ctx.prepared("select", guide.SELECT_PARETO, n, out["t_prefill"], par_idx, None, par_cnt, ws_par,
                                objective_y=out["cost"], feasible=out["feasible"], capacity=par_cap)
 
+    if args.probe_fronts:
+        print(json.dumps({"probe_fronts": front_timings(ctx, n, torch, np, guide)}))
+        return
     if args.probe_extra:
         extra = extra_timings(ctx, gg, g, torch, np, guide, wl)
         print(json.dumps({"probe_extra": extra}))
@@ -274,6 +281,32 @@ def _timed(torch, fn, reps=1):
     b.record()
     torch.cuda.synchronize()
     return a.elapsed_time(b) / reps * 1e-3
+
+
+def front_timings(ctx, n, torch, np, guide, sizes=(100, 1000, 4000, 5000, 20000, 100000, 400000, 1000000, 1900800)):
+    """Pareto selection over n rows: `front` of them form a staircase (x up, y down), the others a cloud that the
+    staircase dominates.  Fronts of more than 4096 rows take the finishing kernel's many-block path."""
+    rng = np.random.default_rng(1)
+    res = []
+    out_idx = torch.empty(n, dtype=torch.int64, device="cuda")
+    cnt = torch.empty(1, dtype=torch.int64, device="cuda")
+    ws = torch.empty(ctx.select_workspace_bytes(guide.SELECT_PARETO, n), dtype=torch.uint8, device="cuda")
+    for front in sizes:
+        front = min(front, n)
+        x = rng.random(n) + 2.0
+        y = rng.random(n) + 2.0
+        idx = rng.choice(n, front, replace=False)
+        t = np.sort(rng.random(front))
+        x[idx] = t
+        y[idx] = 1.0 - t
+        dx, dy = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
+        call = ctx.prepared("select", guide.SELECT_PARETO, n, dx, out_idx, None, cnt, ws, objective_y=dy, capacity=n)
+        s = _timed(torch, call, reps=5)
+        m = int(cnt.item())
+        got = out_idx[:m].cpu().numpy()
+        res.append({"front": front, "ms": s * 1e3, "count": m,
+                    "rows_match": bool(m == front and np.array_equal(np.sort(got), np.sort(idx)))})
+    return res
 
 
 def extra_timings(ctx, gg, g, torch, np, guide, wl, n_sampled=1 << 28, n_sim=65536):

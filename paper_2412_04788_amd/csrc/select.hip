@@ -834,19 +834,15 @@ __device__ inline uint32_t staged_front(FinishLds &L, uint32_t cnt, uint32_t bas
     return nf;
 }
 
-// The same for a part of the front whose survivors do not fit the staging arrays: the records stay in the
-// workspace, grouped by bin through w.grouped (slots g_lo .. g_lo + cnt), flags in w.on_front.
+// The same for bins b_lo .. b_hi when their survivors do not fit the staging arrays: the records stay in the
+// workspace, reached through w.grouped (already grouped by bin: slots L.off[b_lo] .. L.off[b_hi + 1]), flags
+// in w.on_front.
 template <typename Emit>
-__device__ inline uint32_t unstaged_front(FinishLds &L, const ParetoWs &w, const Binning &bin, uint32_t m, uint32_t b_lo,
-                                          uint32_t b_hi, Emit &&emit) {
+__device__ inline uint32_t unstaged_front(FinishLds &L, const ParetoWs &w, const Binning &bin, uint32_t b_lo, uint32_t b_hi,
+                                          Emit &&emit) {
     constexpr uint32_t P = kPerFinish, NT = kFinishThreads, group = 8, q_step = NT / group;
     constexpr uint64_t group_mask = (1ull << group) - 1;
     const uint32_t t = threadIdx.x, lane = t % kWave, sub = lane % group, shift = lane - sub;
-    for (uint32_t q = t; q < m; q += NT) {
-        const uint32_t b = bin(w.skx[q]);
-        if (b >= b_lo && b <= b_hi) w.grouped[L.off[padded<P>(b)] + atomicAdd(&L.cur[b], 1u)] = q;
-    }
-    __syncthreads();
     const uint32_t g_lo = L.off[padded<P>(b_lo)], cnt = L.off[padded<P>(b_hi + 1)] - g_lo;
     const uint32_t cnt_pad = (cnt + q_step - 1) / q_step * q_step;       // wave-uniform trip counts
     for (uint32_t k = t / group; k < cnt_pad; k += q_step) {
@@ -934,7 +930,23 @@ __device__ void pareto_large_front(FinishLds &L, const ParetoWs &w, SelectScratc
         g_lo = L.off[padded<P>(b_lo)];
         auto emit = [&](uint32_t pos, uint32_t row) { w.staged[g_lo + n_front + pos] = row; };
         // In rounds: each takes as many of the part's bins as fit the staging arrays (a single bin that does
-        // not fit is finished in the workspace instead).
+        // not fit is finished in the workspace instead).  A part with one round picks its survivors out of
+        // one pass over all of them; a part with more first groups its survivors by bin in the workspace, in
+        // one such pass, and every round then copies its stretch.  Four keys are requested at a time: the
+        // pass is a chain of load latencies otherwise.
+        const bool grouped = L.off[padded<P>(b_hi + 1)] - g_lo > kStage;
+        if (grouped) {
+            for (uint32_t q0 = t; q0 < m; q0 += 4 * NT) {
+                uint64_t kx[4];
+#pragma unroll
+                for (uint32_t u = 0; u < 4; ++u) kx[u] = w.skx[q0 + u * NT < m ? q0 + u * NT : q0];
+#pragma unroll
+                for (uint32_t u = 0; u < 4; ++u) {
+                    const uint32_t q = q0 + u * NT, b = bin(kx[u]);
+                    if (q < m && b >= b_lo && b <= b_hi) w.grouped[L.off[padded<P>(b)] + atomicAdd(&L.cur[b], 1u)] = q;
+                }
+            }
+        }
         for (uint32_t r_lo = b_lo; r_lo <= b_hi;) {
             __syncthreads();                            // the previous round is done with the tables
             if (t == 0) {
@@ -957,8 +969,17 @@ __device__ void pareto_large_front(FinishLds &L, const ParetoWs &w, SelectScratc
             __syncthreads();
             const uint32_t r_hi = L.last, cnt = L.off[padded<P>(r_hi + 1)] - base;
             uint32_t nf;
-            if (cnt <= kStage) {
-                // four keys requested at a time: the pass over all survivors is a chain of load latencies otherwise
+            if (cnt <= kStage && grouped) {
+                for (uint32_t i = t; i < cnt; i += NT) {
+                    const uint32_t q = w.grouped[base + i];
+                    const uint64_t kx = w.skx[q];
+                    L.kx[i] = kx;
+                    L.ky[i] = w.sky[q];
+                    L.row[i] = w.surv[q];
+                    L.bin[i] = (uint16_t)bin(kx);
+                }
+                nf = staged_front(L, cnt, base, emit);
+            } else if (cnt <= kStage) {
                 for (uint32_t q0 = t; q0 < m; q0 += 4 * NT) {
                     uint64_t kx[4];
 #pragma unroll
@@ -977,7 +998,7 @@ __device__ void pareto_large_front(FinishLds &L, const ParetoWs &w, SelectScratc
                 }
                 nf = staged_front(L, cnt, base, emit);
             } else {
-                nf = unstaged_front(L, w, bin, m, r_lo, r_hi, emit);
+                nf = unstaged_front(L, w, bin, r_lo, r_hi, emit);
             }
             n_front += nf;
             r_lo = r_hi + 1;
@@ -987,13 +1008,19 @@ __device__ void pareto_large_front(FinishLds &L, const ParetoWs &w, SelectScratc
         sc->part_lo[part] = g_lo;
         sc->part_cnt[part] = n_front;
     }
-    // the ticket: everything this part wrote is visible to the part that draws the last one
-    __threadfence();
+    // The ticket: everything this part wrote is visible to the part that draws the last one.  One thread
+    // fences for the block, after every thread's stores have been acknowledged and the block has met (a
+    // fence per wave costs a cache write-back each: 1 024 of them took most of the kernel's time).
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    if (t == 0) L.is_last = atomicAdd(&sc->counters[1], 1u) == n_parts - 1 ? 1u : 0u;
+    if (t == 0) {
+        __threadfence();
+        const bool last = atomicAdd(&sc->counters[1], 1u) == n_parts - 1;
+        if (last) __threadfence();
+        L.is_last = last ? 1u : 0u;
+    }
     __syncthreads();
     if (!L.is_last) return;
-    __threadfence();
     if (t < kWave) {
         const uint32_t c = t < n_parts ? sc->part_cnt[t] : 0u;
         const uint32_t incl = wave_scan_sum(c);
@@ -1009,8 +1036,16 @@ __device__ void pareto_large_front(FinishLds &L, const ParetoWs &w, SelectScratc
     for (uint32_t p = 0; p < n_parts; ++p) {
         const uint32_t c = L.part_cnt[p], lo = L.part_lo[p];
         const uint64_t base = L.part_base[p];
-        for (uint32_t i = t; i < c; i += NT)
-            if (base + i < capacity) out_idx[base + i] = w.staged[lo + i];
+        for (uint32_t i0 = t; i0 < c; i0 += 8 * NT) {   // eight loads in flight per thread
+            uint32_t v[8];
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) v[u] = w.staged[lo + (i0 + u * NT < c ? i0 + u * NT : i0)];
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) {
+                const uint32_t i = i0 + u * NT;
+                if (i < c && base + i < capacity) out_idx[base + i] = v[u];
+            }
+        }
     }
 }
 
