@@ -222,6 +222,17 @@ LaunchTiming next_timing(guide_ctx *ctx) {
     return t;
 }
 
+// Three more pairs for the selection passes of a call whose evaluation kernel is timed (false: too few left).
+bool pass_timing(guide_ctx *ctx, LaunchTiming (&t)[3]) {
+    if (2 * ((size_t)ctx->prof_used + 3) > ctx->prof_ev.size()) return false;
+    for (int i = 0; i < 3; ++i) {
+        t[i].start = ctx->prof_ev[2 * ctx->prof_used];
+        t[i].stop = ctx->prof_ev[2 * ctx->prof_used + 1];
+        ++ctx->prof_used;
+    }
+    return true;
+}
+
 const double *metric_column(const guide_metrics &m, uint32_t id) {
     switch (id) {
         case GUIDE_COL_T_PREFILL: return m.t_prefill;
@@ -504,6 +515,7 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
     if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
     if (int rc_order = order_after_previous(ctx, stream)) return rc_order;
     uint32_t n_blocks = 0, sampled_partials = 0;
+    bool eval_timed = false;
     // rows [0, count) of the columns are rows [first, first + count) of the grid: the chunks line up when first does
     const uint32_t chunk_of_eval = eval_grid_row_chunk(desc);
     const uint32_t row_chunk = (chunk_of_eval && first % chunk_of_eval == 0) ? chunk_of_eval : 0u;
@@ -519,6 +531,7 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
         const bool additive = time_model == GUIDE_TIME_ADDITIVE;
         hipError_t e;
         const LaunchTiming timing = next_timing(ctx);
+        eval_timed = timing.start != nullptr;
         if (fold) {
             FusedSelect fs;
             memset(&fs, 0, sizeof fs);
@@ -555,8 +568,12 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
     hipError_t e = hipSuccess;
     if (topk && pareto && count > 0 && !fold) {
         // both selections read stored columns: the small kernels ride along with the large ones
+        // with a timed evaluation kernel, the three passes are timed as well (when the pairs suffice)
+        LaunchTiming passes[3];
+        const bool timed = eval_timed && pass_timing(ctx, passes);
         e = launch_select_both(spec_of(*topk, *out), topk->out, ws_of[topk - sel], spec_of(*pareto, *out), pareto->out,
-                               ws_of[pareto - sel], count, ctx->select_scratch, stream, sampled_partials, row_chunk);
+                               ws_of[pareto - sel], count, ctx->select_scratch, stream, sampled_partials, row_chunk,
+                               timed ? passes : nullptr);
     } else {
         for (uint32_t i = 0; i < n_sel && e == hipSuccess; ++i) {
             const guide_column_select &c = sel[i];

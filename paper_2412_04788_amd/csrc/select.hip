@@ -10,6 +10,8 @@
 #include "reduce.hpp"
 #include "select_shared.hpp"
 
+#include <hip/hip_ext.h>
+
 #include <cstring>
 #include <type_traits>
 
@@ -1202,10 +1204,18 @@ hipError_t launch_select_topk(const guide_select_spec &spec, uint64_t n, const g
     return hipGetLastError();
 }
 
+// A launch with the timing events attached to its dispatch when there are any.
+template <typename Kernel, typename... Args>
+static void launch_timed(Kernel kernel, dim3 grid, dim3 block, hipStream_t stream, const LaunchTiming *tm, Args... args) {
+    if (tm && tm->start) hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, tm->start, tm->stop, 0, args...);
+    else hipLaunchKernelGGL(kernel, grid, block, 0, stream, args...);
+}
+
 static hipError_t launch_pareto_passes(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
                                        SelectScratch *sc, uint32_t n_partials, const MergeRider &rider,
                                        hipStream_t stream, const SharedTopk *shared = nullptr, int shared_k = 0,
-                                       uint32_t row_chunk = 0) {
+                                       uint32_t row_chunk = 0, const LaunchTiming *tm = nullptr) {
+    const LaunchTiming *tm_stair = tm, *tm_surv = tm ? tm + 1 : nullptr, *tm_fin = tm ? tm + 2 : nullptr;
     const ParetoWs w = pareto_ws(ws, n);
     const RowFilter f = make_filter(spec);
     const uint32_t nb = pareto_blocks(n), n32 = (uint32_t)n;
@@ -1215,23 +1225,22 @@ static hipError_t launch_pareto_passes(const guide_select_spec &spec, uint64_t n
         constexpr uint32_t U = decltype(u)::value;
         if (shared) {       // only offered for a Pareto selection without constraint columns
             const SharedTopk t = *shared;
-            if (shared_k == 1) hipLaunchKernelGGL((pareto_stair_kernel<0, 1, U>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t, chunk);
-            else if (shared_k == 2) hipLaunchKernelGGL((pareto_stair_kernel<0, 2, U>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t, chunk);
-            else if (shared_k == 3) hipLaunchKernelGGL((pareto_stair_kernel<0, 3, U>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t, chunk);
-            else hipLaunchKernelGGL((pareto_stair_kernel<0, 4, U>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, t, chunk);
+            if (shared_k == 1) launch_timed(pareto_stair_kernel<0, 1, U>, grid, block, stream, tm_stair, x, y, f, n32, sc, n_partials, t, chunk);
+            else if (shared_k == 2) launch_timed(pareto_stair_kernel<0, 2, U>, grid, block, stream, tm_stair, x, y, f, n32, sc, n_partials, t, chunk);
+            else if (shared_k == 3) launch_timed(pareto_stair_kernel<0, 3, U>, grid, block, stream, tm_stair, x, y, f, n32, sc, n_partials, t, chunk);
+            else launch_timed(pareto_stair_kernel<0, 4, U>, grid, block, stream, tm_stair, x, y, f, n32, sc, n_partials, t, chunk);
         }
         with_max_constraints(f.n_con, [&](auto maxc) {
             constexpr uint32_t MAXC = decltype(maxc)::value;
             if (!shared)
-                hipLaunchKernelGGL((pareto_stair_kernel<MAXC, 0, U>), grid, block, 0, stream, x, y, f, n32, sc, n_partials,
-                                   SharedTopk{}, chunk);
-            hipLaunchKernelGGL((pareto_survivors_kernel<MAXC, U>), grid, block, 0, stream, x, y, f, n32, w, sc, n_partials,
-                               chunk);
+                launch_timed(pareto_stair_kernel<MAXC, 0, U>, grid, block, stream, tm_stair, x, y, f, n32, sc, n_partials,
+                             SharedTopk{}, chunk);
+            launch_timed(pareto_survivors_kernel<MAXC, U>, grid, block, stream, tm_surv, x, y, f, n32, w, sc, n_partials, chunk);
         });
     });
     const uint32_t helpers = n > kStage ? kLargeParts - 1 : 0;     // no more than kStage rows: the staged path for sure
-    hipLaunchKernelGGL(pareto_finish_kernel, dim3((rider.n_blocks ? 2 : 1) + helpers), dim3(kFinishThreads), 0, stream, w,
-                       n32, sc, n_partials, out.idx, out.capacity, out.count, rider);
+    launch_timed(pareto_finish_kernel, dim3((rider.n_blocks ? 2 : 1) + helpers), dim3(kFinishThreads), stream, tm_fin, w, n32,
+                 sc, n_partials, out.idx, out.capacity, out.count, rider);
     return hipGetLastError();
 }
 
@@ -1276,7 +1285,7 @@ static bool shares_columns(const guide_select_spec &topk, const guide_select_spe
 hipError_t launch_select_both(const guide_select_spec &topk, const guide_select_out &topk_out, void *topk_ws,
                               const guide_select_spec &pareto, const guide_select_out &pareto_out, void *pareto_ws_,
                               uint64_t n, void *scratch, hipStream_t stream, uint32_t sampled_partials,
-                              uint32_t row_chunk) {
+                              uint32_t row_chunk, const LaunchTiming *pass_timing) {
     SelectScratch *sc = (SelectScratch *)scratch;
     const int K = partial_width(topk.k);
     SharedTopk shared;
@@ -1298,7 +1307,7 @@ hipError_t launch_select_both(const guide_select_spec &topk, const guide_select_
     else
         launch_top1_merge(K, topk_ws, blocks_for(n), topk.k, topk_out, stream);
     return launch_pareto_passes(pareto, n, pareto_out, pareto_ws_, sc, sampled ? sampled_partials : kSampleBlocks, rider,
-                                stream, folded ? &shared : nullptr, K, row_chunk);
+                                stream, folded ? &shared : nullptr, K, row_chunk, pass_timing);
 }
 
 // The passes after the sample, for a caller whose own kernel has sampled the rows and reset the tables.
