@@ -375,9 +375,10 @@ __global__ __launch_bounds__(kBlock) void topk_final_kernel(TopkWs w, uint32_t G
 // Survivors: a row survives when its y beats every row of every strictly lower
 // bin (exclusive prefix-min of the table) -- only survivors of its own bin can
 // still dominate it.  Survivors are appended as (row, keys).
-// Finish (one block): survivors are grouped by bin, tested exactly inside their
-// bin, and front members are written at (front members of lower bins) + (rank
-// inside the bin), which orders the output by (x, y, row).
+// Finish: survivors are grouped by bin, tested exactly inside their bin, and front
+// members are written at (front members of lower bins) + (rank inside the bin),
+// which orders the output by (x, y, row).  One block does this in LDS for up to
+// kStage survivors; more are shared out among kLargeParts blocks by runs of bins.
 
 constexpr uint32_t kStage = 4096;        // survivors whose records the finishing block holds in LDS
 constexpr uint32_t kFinishThreads = 1024;
