@@ -76,7 +76,7 @@ def to_np(t, dtype=None):
 
 def host_workers() -> int:
     """Threads for oracle sweeps: the oracle's C entry points hold no global state and ctypes releases the
-    interpreter lock during a call, so independent ranges run side by side (16 = a GPU machine's CPU share)."""
+    interpreter lock during a call, so independent ranges run side by side (at most 16 threads)."""
     import os
     return max(1, min(16, os.cpu_count() or 1))
 

@@ -15,7 +15,9 @@ from tests import bridge
 pytestmark = pytest.mark.gpu
 TOL = 1e-9
 FLOAT_COLS = ("t_prefill", "t_decode", "t_batch", "decode_tok_s", "cost")
-REPORT = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+# the reports (JSON, one per test) go to the directory named by GUIDE_PARITY_REPORT_DIR, else to an untracked one
+REPORT = os.environ.get("GUIDE_PARITY_REPORT_DIR") or os.path.join(
+    os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
 
 
 @pytest.fixture(scope="module")
