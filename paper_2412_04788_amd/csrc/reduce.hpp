@@ -105,6 +105,11 @@ __device__ inline uint32_t wave_scan_sum(uint32_t v) {
     return v;
 }
 
+// Sum over the lanes of a wave, in every lane (every lane active).
+__device__ inline uint32_t wave_sum(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)wave_scan_sum(v), kWave - 1);
+}
+
 // Per-wave LDS slots holding the least (key, row) pair per group.  A wave's LDS
 // operations execute in program order for all its lanes, so one update is: read
 // the key slot, atomic-min the key, read it back; lanes that hold the new

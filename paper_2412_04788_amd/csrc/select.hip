@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kBlock) void topk_pass_kernel(const double *__restr
     __shared__ uint64_t s_cnt[kWaves];
     TopList<K> l;
     l.init();
-    uint64_t cnt = 0;
+    uint32_t cnt = 0;                                   // rows of one lane: fewer than 2^32
     for (ChunkWalk<U> cw(chunk, n, n_row_blocks); cw.live(); cw.next()) {
         const uint32_t base = (uint32_t)cw.base + threadIdx.x, lim = (uint32_t)cw.end;
         Row r[U];
@@ -191,8 +191,8 @@ __global__ __launch_bounds__(kBlock) void topk_pass_kernel(const double *__restr
             }
         }
     }
-    for (int off = kWave / 2; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, kWave);
-    if (threadIdx.x % kWave == 0) s_cnt[threadIdx.x / kWave] = cnt;
+    const uint32_t wave_cnt = wave_sum(cnt);             // a wave's rows: fewer than 2^32 as well
+    if (threadIdx.x % kWave == 0) s_cnt[threadIdx.x / kWave] = wave_cnt;
     block_topk<K, kWaves>(l, s_pairs, [&](int r, const Pair &p) {
         w.key[(size_t)blockIdx.x * K + r] = p.key;
         w.idx[(size_t)blockIdx.x * K + r] = p.idx;
@@ -610,7 +610,7 @@ __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__re
     __shared__ uint64_t s_min[padded_size<kPerPass>()], s_tmp[kWaves], s_rng[2];
     constexpr int KL = KT ? KT : 1;
     TopList<KL> list;
-    uint64_t n_pass = 0;
+    uint32_t n_pass = 0;                                // rows of one lane: fewer than 2^32
     if (KT) list.init();
     // the first batch of rows is requested before the set-up below, so that its latency overlaps it
     RawRow<MAXC> r[U];
@@ -624,6 +624,15 @@ __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__re
     const Binning bin = sampled_binning(sc, n_partials, s_rng);     // its barrier also covers the table above
     while (cw.live()) {
         const uint32_t base = (uint32_t)cw.base;
+        // the next batch is requested before this one is worked on
+        RawRow<MAXC> rn[U];
+        cw.next();
+        const bool more = cw.live();
+        if (more) {
+#pragma unroll
+            for (uint32_t u = 0; u < U; ++u)
+                rn[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)cw.base + threadIdx.x + u * kBlock, (uint32_t)cw.end);
+        }
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
             const Row q = row_of<true, MAXC>(r[u], f);
@@ -645,14 +654,27 @@ __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__re
                 }
             }
         }
-        cw.next();
-        if (cw.live()) {
+        if (more) {
 #pragma unroll
-            for (uint32_t u = 0; u < U; ++u)
-                r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)cw.base + threadIdx.x + u * kBlock, (uint32_t)cw.end);
+            for (uint32_t u = 0; u < U; ++u) r[u] = rn[u];
         }
     }
     __syncthreads();
+    // The block's top-k partial is worked out first and kept in registers: every global access of the tail
+    // (its stores and the table's atomics) is issued after the last barrier, so that no barrier waits for one.
+    constexpr int KLL = KT ? KT : 1;
+    int my_rank = -1;
+    Pair my_pair = {kNone, kNone};
+    __shared__ Pair s_pairs[kWaves][KLL];
+    __shared__ uint64_t s_cnt[kWaves];
+    if (KT) {
+        const uint32_t wave_pass = wave_sum(n_pass);
+        if (threadIdx.x % kWave == 0) s_cnt[threadIdx.x / kWave] = wave_pass;
+        block_topk<KLL, kWaves>(list, s_pairs, [&](int rk, const Pair &p) {
+            my_rank = rk;
+            my_pair = p;
+        });                                             // (contains the barrier that publishes s_cnt)
+    }
     // The table is only read through its exclusive prefix-min, and only a block's running minima
     // (entries below everything in its lower bins) can lower that: the others are not sent.  The
     // atomics return nothing, so no lane waits for them.
@@ -668,14 +690,10 @@ __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__re
         }
     }
     if (KT) {
-        __shared__ Pair s_pairs[kWaves][KL];
-        __shared__ uint64_t s_cnt[kWaves];
-        for (int off = kWave / 2; off > 0; off >>= 1) n_pass += __shfl_xor(n_pass, off, kWave);
-        if (threadIdx.x % kWave == 0) s_cnt[threadIdx.x / kWave] = n_pass;
-        block_topk<KL, kWaves>(list, s_pairs, [&](int rk, const Pair &p) {
-            topk.w.key[(size_t)blockIdx.x * KL + rk] = p.key;
-            topk.w.idx[(size_t)blockIdx.x * KL + rk] = p.idx;
-        });                                             // (contains the barrier that publishes s_cnt)
+        if (my_rank >= 0) {
+            topk.w.key[(size_t)blockIdx.x * KLL + my_rank] = my_pair.key;
+            topk.w.idx[(size_t)blockIdx.x * KLL + my_rank] = my_pair.idx;
+        }
         if (threadIdx.x == 0) {
             uint64_t c = 0;
             for (int wv = 0; wv < kWaves; ++wv) c += s_cnt[wv];
@@ -709,9 +727,19 @@ __global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *
     scan_min_excl<kBlock>(s_lower, s_tmp);              // least y over strictly lower bins
     // wave-uniform trip count: the ballots below need every lane
     while (cw.live()) {
+        const uint32_t base = (uint32_t)cw.base;
+        // the next batch is requested before this one is worked on
+        RawRow<MAXC> rn[U];
+        cw.next();
+        const bool more = cw.live();
+        if (more) {
+#pragma unroll
+            for (uint32_t u = 0; u < U; ++u)
+                rn[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)cw.base + threadIdx.x + u * kBlock, (uint32_t)cw.end);
+        }
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
-            const uint32_t i = (uint32_t)cw.base + threadIdx.x + u * kBlock;
+            const uint32_t i = base + threadIdx.x + u * kBlock;
             const Row q = row_of<true, MAXC>(r[u], f);
             uint32_t b = 0;
             uint64_t kx = 0, ky = 0;
@@ -736,11 +764,9 @@ __global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *
                 }
             }
         }
-        cw.next();
-        if (cw.live()) {
+        if (more) {
 #pragma unroll
-            for (uint32_t u = 0; u < U; ++u)
-                r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)cw.base + threadIdx.x + u * kBlock, (uint32_t)cw.end);
+            for (uint32_t u = 0; u < U; ++u) r[u] = rn[u];
         }
     }
 }

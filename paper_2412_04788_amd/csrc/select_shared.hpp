@@ -71,7 +71,7 @@ struct TopList {
 // The K least pairs over all lanes of the block, in order: emit(r, pair) is called once for every
 // r < K by some lane of wave 0 (an empty pair when fewer than r + 1 exist).  NW = waves of the block.
 // Stage 1, per wave: K rounds of a key-only minimum; the owner is found by ballot, and only tied
-// keys need a second reduction over rows.  Rows are unique, so one lane pops per round.
+// keys need a second reduction over rows (row numbers fit 32 bits).  Rows are unique, so one lane pops per round.
 // Stage 2, wave 0: each of the NW * K candidates counts the candidates before it (lane index
 // breaks the tie between empty ones) -- its rank is its output slot.
 template <int K, int NW, typename Emit>
@@ -86,8 +86,8 @@ __device__ inline void block_topk(TopList<K> &l, Pair (*s_pairs)[K], Emit &&emit
         uint64_t mi = kNone;
         if (__popcll(tied) == 1)
             mi = __shfl(l.v[0].idx, __ffsll((long long)tied) - 1, kWave);
-        else if (tied)
-            mi = wave_min(mine ? l.v[0].idx : kNone);
+        else if (tied)                                  // rows are below 2^32: a 32-bit minimum decides
+            mi = wave_min(mine ? (uint32_t)l.v[0].idx : 0xFFFFFFFFu);
         if (mine && l.v[0].idx == mi) l.pop();
         if (lane == 0) s_pairs[wave][r] = Pair{mi == kNone ? kNone : mk, mi};
     }

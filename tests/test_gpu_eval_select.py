@@ -251,6 +251,39 @@ def test_topk_reduced_inside_the_evaluation_for_other_tile_shapes(ora, torch_cud
             _assert_selections(ora, host, tk1, None, rt, None)
 
 
+def test_topk_carried_by_the_pareto_passes_ties_and_few_passing_rows(ora, torch_cuda):
+    """The top-k that shares the Pareto selection's columns keeps its lists in the staircase kernel: objectives with
+    many equal values (TTFT does not depend on the output length or the KV block), caps that leave fewer rows than
+    k, caps that exactly equal a stored value, ranges that start inside a tile, both time models, k = 1..4, and
+    either column as the objective.  The selections are checked on the columns the GPU stored (their parity with
+    the oracle's is the business of the other tests)."""
+    torch = torch_cuda
+    g = wl.grid_full()
+    ctx, gg = bridge.gpu_context(g), bridge.gpu_grid(g)
+    n = g.size
+    cases = [(0, n, 0), (1536 * 7 + 5, 400_003, 0), (n - 77, 77, 1), (123_456, 20_000, 1)]
+    for first, count, tm in cases:
+        out = bridge.metric_buffers(count)
+        ctx.eval_grid(gg, first, count, out=out, time_model=tm)
+        torch.cuda.synchronize()
+        host = {k: bridge.to_np(out[k]) for k in F64_COLS}
+        host["feasible"] = bridge.to_np(out["feasible"])
+        cost, ttft = host["cost"], host["t_prefill"]
+        ok = host["feasible"] != 0
+        cap_tight = float(np.sort(cost[ok])[2]) if ok.sum() > 2 else 1.0      # exactly three feasible rows at or below
+        cap_exact = float(np.median(ttft))                                     # equals a stored value: "<=" must include it
+        specs = [dict(objective="t_prefill", k=4, constraints=[("cost", float(np.median(cost)))]),
+                 dict(objective="t_prefill", k=3, use_feasible=False),
+                 dict(objective="cost", k=4, constraints=[("cost", cap_tight)]),
+                 dict(objective="cost", k=2, constraints=[("t_prefill", cap_exact)]),
+                 dict(objective="cost", k=1, constraints=[("t_prefill", float(ttft.min()) * 0.5)]),       # nothing passes
+                 dict(objective="t_prefill", k=4, constraints=[("t_prefill", float(ttft.min()))])]         # the ties at the least TTFT
+        for tk in specs:
+            pf = dict(x="t_prefill", y="cost", use_feasible=tk.get("use_feasible", True), capacity=4096)
+            rt, rp = _run(torch, ctx, gg, first, count, out, topk=tk, pareto=pf, time_model=tm)
+            _assert_selections(ora, host, tk, pf, rt, rp)
+
+
 def test_profile_aid_times_the_evaluation_kernel(torch_cuda):
     torch = torch_cuda
     g = wl.grid_full()
