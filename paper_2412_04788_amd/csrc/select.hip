@@ -366,7 +366,8 @@ __global__ __launch_bounds__(kBlock) void topk_final_kernel(TopkWs w, uint32_t G
 
 // --------------------------------------------------------------------- Pareto
 //
-// Four launches (the first can ride along with a top-k pass, and a top-k merge with the last).
+// Four launches.  The first can ride along with a top-k pass or with the kernel that produces the
+// columns; a top-k over the same columns can ride along with the second, and a top-k merge with the last.
 // Prepare: a strided sample of rows fixes the stretch of x that the bins slice; it also resets
 // the tables that the next two kernels accumulate into.
 // Staircase: every block builds in LDS the least y per x-bin over its rows (kBins
