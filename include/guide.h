@@ -391,26 +391,6 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
                       uint32_t time_model, const guide_metrics *out, const guide_column_select *sel, uint32_t n_sel,
                       void *workspace, size_t workspace_bytes, void *stream);
 
-/*
- * Kernel timing aid (diagnostics, not part of the method).  After
- * guide_profile_enable(ctx, capacity, every), every `every`-th grid evaluation
- * kernel launched by guide_eval_grid (one sample) or guide_eval_select (the
- * first, the every+1-th, ...) carries a pair of HIP events on the call's stream
- * that receive the start and the end of that kernel's dispatch.  When such a
- * guide_eval_select call has one top-k and one Pareto selection over stored
- * columns, the three kernels of its selection passes (staircase, survivors,
- * finish) carry a pair each as well, so that every dispatch of the call is
- * observed the same way.  `capacity` is the number of pairs (later launches are
- * not timed); capacity 0 switches it off.  A timed launch delays the launches
- * around it by a few microseconds, which is why a caller that also measures
- * throughput times separate calls.  guide_profile_read waits for the recorded
- * events, writes the elapsed milliseconds of each timed kernel, in launch
- * order (four per such guide_eval_select call, one per other call), to
- * ms[0 .. *n) (HOST, room for `capacity` values) and starts over.
- */
-int guide_profile_enable(guide_ctx *ctx, uint32_t capacity, uint32_t every);
-int guide_profile_read(guide_ctx *ctx, float *ms, uint32_t *n);
-
 #ifdef __cplusplus
 }
 #endif

@@ -37,6 +37,7 @@ def stale() -> bool:
     t = os.path.getmtime(LIB)
     deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".hpp"))]
     deps.append(os.path.join(INCLUDE, "guide.h"))
+    deps.append(os.path.join(INCLUDE, "guide_diag.h"))
     return any(os.path.getmtime(d) > t for d in deps)
 
 

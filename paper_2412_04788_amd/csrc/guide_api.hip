@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "kernels.hpp"
+#include "guide_diag.h"
 
 using namespace guide;
 
