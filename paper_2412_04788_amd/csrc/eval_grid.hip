@@ -616,23 +616,15 @@ __global__ __launch_bounds__(kBlock) void eval_sweep_kernel(GridDesc g, const De
         // and metric.  The samples of a group wait in LDS so that the evaluation is not unrolled eight times.
         uint32_t e = 0;
         for (; e + kSweepGroup <= n_eff; e += kSweepGroup) {
-            for (uint32_t q = 0; q < (uint32_t)kSweepGroup; ++q) {
-                double tp, tb;
-                sample(e + q, tp, tb);
-                s_tp[q][threadIdx.x] = tp;
-                s_tb[q][threadIdx.x] = tb;
-            }
-            double a[kSweepGroup];
+            double a[kSweepGroup], bb[kSweepGroup];
 #pragma unroll
-            for (int q = 0; q < kSweepGroup; ++q) a[q] = s_tp[q][threadIdx.x];
+            for (int q = 0; q < kSweepGroup; ++q) sample(e + q, a[q], bb[q]);
             sort_group(a);
             lo_p.merge(a);
             hi_p.merge(a);
-#pragma unroll
-            for (int q = 0; q < kSweepGroup; ++q) a[q] = s_tb[q][threadIdx.x];
-            sort_group(a);
-            lo_b.merge(a);
-            hi_b.merge(a);
+            sort_group(bb);
+            lo_b.merge(bb);
+            hi_b.merge(bb);
         }
         for (; e < n_eff; ++e) {
             double tp, tb;
