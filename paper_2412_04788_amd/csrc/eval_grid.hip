@@ -568,8 +568,10 @@ __device__ inline void sort_group(double (&a)[kSweepGroup]) {
 // for all block sizes of a configuration at once (rows that differ only in the kv_block digit) and
 // only the memory check is repeated per block size; the split of the prefill into passes does not
 // depend on the sample and is planned once.
+// Two waves per SIMD: the register budget that asks for costs a few spills, and measured 0.44 ms against 0.56 ms
+// with one wave (three and four waves spill far more: 1.5 and 2.7 ms).
 template <bool ADDITIVE>
-__global__ __launch_bounds__(kBlock) void eval_sweep_kernel(GridDesc g, const DevTables *__restrict__ tab,
+__global__ __launch_bounds__(kBlock, 2) void eval_sweep_kernel(GridDesc g, const DevTables *__restrict__ tab,
                                                             uint32_t first, uint32_t count, uint32_t n_eff,
                                                             guide_stats out) {
     __shared__ GridLds s;
