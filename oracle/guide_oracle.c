@@ -37,7 +37,14 @@
  * that leave the link alone, the paper's printed kv formula and B_max,
  * feasibility boundary, monotonicity, scaling laws, single-request simulation
  * == analytic latency, brute-force select, numpy's Philox for the counter-based
- * generator.  Each function has at least one such pin; none is "parity unpinned".
+ * generator; passes of a prefill and a decode written out under both time
+ * models, schedules at the edges of the token budget by hand, the range forms
+ * against the single-row calls.  Each function has at least one such pin; none
+ * is "parity unpinned".  The pins were completed by changing one operator,
+ * comparison or constant of this file at a time (676 such changes) until the
+ * only ones that still pass are changes without effect (a boundary at which
+ * both branches agree, a doubled guard), loop bounds that only read or write
+ * past an array, the diagnostics, and ties of measure zero.
  *
  * Build: gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC (no FMA
  * contraction, so every expression rounds as written).

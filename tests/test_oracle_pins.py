@@ -521,6 +521,8 @@ def test_simulation_infeasible_and_blocking(ora):
     h = wl.Hardware(1e15, 5e12, w + 8 * 16 * kv_tok - 1, 4e11)
     s = ora.simulate(om, bridge.ora_hw(h), 1, 16, 16, 2048, 2, 1.0, np.zeros(2), ins, outs)
     assert s["status"] == ora.SIM_INFEASIBLE and np.isinf(s["ttft_p50"]) and s["n_steps"] == 0
+    s = ora.simulate(om, bridge.ora_hw(h), 1, 16, 16, 2048, 2, 1.0, np.zeros(2), ins, outs, detail=True)
+    assert np.all(np.isinf(s["ttft"])) and np.all(np.isinf(s["first"])) and np.all(np.isinf(s["fin"]))
     # weights do not fit
     h = wl.Hardware(1e15, 5e12, w, 4e11)
     assert ora.simulate(om, bridge.ora_hw(h), 1, 16, 16, 2048, 2, 1.0, np.zeros(2), ins, outs)["status"] == 1
@@ -918,3 +920,148 @@ def test_adjustment_columns_by_hand(ora):
     oh = bridge.ora_hw(h)
     one = ora.pass_detail(om, oh, 1, 16, 2000, 2 * 1000 * 1000, 2000, 2)["t_pass"]
     assert ora.prefill(om, oh, ora.knobs(10, 1000, 24, mbt=2048)) == pytest.approx(5 * one, rel=1e-15)
+
+
+# ------------------------------------------- pins added after operator-level mutation of the oracle
+#
+# Each test below fails for at least one one-token change of oracle/guide_oracle.c (an operator, a comparison, a
+# constant) that every earlier pin let through.
+
+def test_output_projection_split_over_gpus(ora):
+    gold = _gold("op_bytes.txt")
+    om, oh = bridge.ora_model(wl.DENSE_7B), bridge.ora_hw(wl.HW_TINY)
+    for p in (2, 4):
+        r = ora.pass_detail(om, oh, p, 16, 3.0, 9.0, 3.0, 1.0)
+        assert r["F"][2] == gold[f"oproj_flops_7b_tp{p}_T3"]
+        assert r["B"][2] == gold[f"oproj_bytes_7b_tp{p}_T3"]
+
+
+def test_lm_head_only_with_lm_rows(ora):
+    """A pass without LM-head rows (a prompt segment that is not the last) pays nothing for the LM head, not even
+    its weights; with one row it is the weight-bound closed form."""
+    gold = _gold("op_bytes.txt")
+    m = wl.DENSE_7B
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+    r0 = ora.pass_detail(om, oh, 1, 16, 64.0, 64.0 * 64, 64.0, 0.0)
+    assert r0["t"][7] == 0.0
+    assert r0["t_pass"] == pytest.approx(m.L * (r0["t"][:7].sum() + 2 * r0["t_ar"]), rel=1e-15)
+    r1 = ora.pass_detail(om, oh, 1, 16, 64.0, 64.0 * 64, 64.0, 1.0)
+    assert r1["B"][7] == gold["lm_head_bytes_7b_tp1_rows1"]
+    assert r1["t"][7] == gold["lm_head_bytes_7b_tp1_rows1"] / wl.HW_TINY.hbm_bw
+    assert r1["t_pass"] - r0["t_pass"] == pytest.approx(r1["t"][7], rel=1e-9)
+
+
+@pytest.mark.parametrize("time_model", [0, 1])
+def test_prefill_and_decode_pass_arguments_under_both_time_models(ora, time_model):
+    """The passes of a prefill and of a decode, written out with their token, query-context and KV-token counts:
+    under the additive model every one of those counts moves the time, whichever side of the roofline it is on."""
+    m = wl.DENSE_7B
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+
+    def one(T, Q, K, n_lm, p=1):
+        return ora.pass_detail(om, oh, p, 16, T, Q, K, n_lm, time_model=time_model)["t_pass"]
+
+    # sub-batches: 10 prompts of 1000 tokens under 4096 tokens per pass: 4 + 4 + 2
+    t = ora.prefill(om, oh, ora.knobs(10, 1000, 8, mbt=4096), time_model=time_model)
+    assert t == (one(4000, 4 * 1000 * 1000, 4000, 4) + one(4000, 4 * 1000 * 1000, 4000, 4)) + one(2000, 2 * 1000 * 1000, 2000, 2)
+    # a prompt of exactly two, and of exactly three budgets: two and three full segments, the LM head on the last
+    for k in (2, 3):
+        t = ora.prefill(om, oh, ora.knobs(1, k * 2048, 8, mbt=2048), time_model=time_model)
+        tot = 0.0
+        for j in range(k):
+            tot += one(2048, 2048 * (j + 1) * 2048, (j + 1) * 2048, 1 if j == k - 1 else 0)
+        assert t == tot
+    # one token more: a further segment of one token
+    t = ora.prefill(om, oh, ora.knobs(1, 4097, 8, mbt=2048), time_model=time_model)
+    assert t == (one(2048, 2048 * 2048, 2048, 0) + one(2048, 2048 * 4096, 4096, 0)) + one(1, 4097, 4097, 1)
+    # decode: s_out - 1 steps of b tokens at context s_in + j
+    b, s_in, s_out = 3, 100, 6
+    e = ora.evaluate(om, oh, ora.knobs(b, s_in, s_out, p=2), time_model=time_model)
+    td = 0.0
+    for j in range(1, s_out):
+        td += one(b, b * (s_in + j), b * (s_in + j), b, p=2)
+    assert e.t_decode == td
+
+
+def test_grid_wrappers_cover_every_row_of_their_range(ora):
+    """The range forms used by the GPU parity tests (sweep over a grid range, simulation of a list of grid rows)
+    against the single-row calls, for ranges that start inside the grid and hold several rows."""
+    g = wl.grid_tiny()
+    og = bridge.ora_grid(g)
+    e_c, e_b = wl.efficiency_pairs(n=64)
+    first, count = 37, 6
+    s = ora.eval_sweep_grid(og, e_c, e_b, first, count)
+    per = [ora.eval_grid(og, first, count, e_c=float(a), e_b=float(b)) for a, b in zip(e_c, e_b)]
+    tp = np.array([r["t_prefill"] for r in per]); tb = np.array([r["t_batch"] for r in per])      # [sample, row]
+    for i in range(count):
+        assert s["ttft_p10"][i] == np.sort(tp[:, i])[6] and s["ttft_p90"][i] == np.sort(tp[:, i])[57]
+        assert s["t_batch_p10"][i] == np.sort(tb[:, i])[6] and s["t_batch_p90"][i] == np.sort(tb[:, i])[57]
+        assert s["ttft_mean"][i] == pytest.approx(tp[:, i].mean(), rel=1e-14)
+        assert s["t_batch_mean"][i] == pytest.approx(tb[:, i].mean(), rel=1e-14)
+    assert len(set(s["t_batch_p90"].tolist())) == count          # six different rows
+    # simulation of grid rows: the row's model, hardware, TP, precision, block and budget, its batch as the sequence cap
+    tr = wl.request_trace(n=48)
+    rows = np.array([5, 611, 1079], dtype=np.uint32)
+    rates = np.array([2.0, 16.0, 64.0])
+    sg = ora.simulate_grid(og, rows, rates, tr.arrival_unit, tr.n_in, tr.n_out)
+    for j, (row, rate) in enumerate(zip(rows, rates)):
+        mi, hi, b, _, _, p, wbits, blk, mbt = g.values_at(int(row))
+        one = ora.simulate(bridge.ora_model(g.models[mi]), bridge.ora_hw(g.hws[hi]), p, wbits, blk, mbt, b, float(rate),
+                           tr.arrival_unit, tr.n_in, tr.n_out)
+        for k in ("ttft_p50", "ttft_p99", "mean_tpot", "tokens_s", "n_steps", "n_request_steps", "status"):
+            assert sg[k][j] == one[k], (k, j)
+    assert len(set(sg["n_steps"].tolist())) == 3
+    # a model or hardware number equal to the table's length is outside it
+    bad = wl.make_grid([wl.DENSE_7B], [wl.HW_TINY], *g.axes[2:])
+    for axis in (0, 1):
+        axes = list(bad.axes)
+        axes[axis] = wl.Axis.table([1])
+        with pytest.raises(ValueError):
+            ora.eval_grid(bridge.ora_grid(wl.Grid(bad.models, bad.hws, tuple(axes))), 0, 1)
+
+
+def test_scheduler_boundaries_by_hand(ora):
+    m = wl.DENSE_7B
+    om, oh = bridge.ora_model(m), bridge.ora_hw(wl.HW_TINY)
+
+    def one(T, Q, K, n_lm):
+        return ora.pass_detail(om, oh, 1, 16, T, Q, K, n_lm)["t_pass"]
+
+    u32 = lambda *v: np.array(v, dtype=np.uint32)
+    # prefill-first: two prompts that fill the budget exactly share one pass
+    s = ora.simulate(om, oh, 1, 16, 16, 256, 4, 1.0, np.zeros(2), u32(100, 156), u32(2, 2), detail=True,
+                     scheduler=ora.SCHED_PREFILL_FIRST)
+    t1 = one(256, 100 * 100 + 156 * 156, 256, 2)
+    assert s["ttft"][0] == s["ttft"][1] == t1
+    assert s["n_steps"] == 2 and s["n_request_steps"] == 4
+    assert s["fin"][0] == s["fin"][1] == t1 + one(2, 101 + 157, 101 + 157, 2)
+    # one token more and the second prompt waits for the next pass
+    s = ora.simulate(om, oh, 1, 16, 16, 256, 4, 1.0, np.zeros(2), u32(100, 157), u32(2, 2), detail=True,
+                     scheduler=ora.SCHED_PREFILL_FIRST)
+    assert s["ttft"][0] == one(100, 100 * 100, 100, 1) and s["n_steps"] == 3
+    # split-fuse: a running decoder takes one token of the budget, so a prompt of 127 tokens under a budget of 64
+    # goes in chunks of 63, 63 and 1 (request 0 has finished its prompt and decodes throughout)
+    s = ora.simulate(om, oh, 1, 16, 16, 64, 4, 1.0, np.array([0.0, 1e-9]), u32(10, 127), u32(50, 2), detail=True)
+    t = one(10, 10 * 10, 10, 1)                                   # request 0 alone: its whole prompt
+    assert s["ttft"][0] == t
+    ctx0 = 11
+    for c, done in ((63, 63), (63, 126), (1, 127)):
+        t += one(1 + c, ctx0 + c * done, ctx0 + done, 1 + (1 if done == 127 else 0))
+        ctx0 += 1
+    assert s["first"][1] == t
+    # a budget that the decoders use up leaves nothing for a prompt: no chunk is scheduled, and none is counted
+    s = ora.simulate(om, oh, 1, 16, 16, 2, 4, 1.0, np.array([0.0, 0.0, 1e-9]), u32(1, 1, 1), u32(4, 4, 2), detail=True)
+    # step 1: both one-token prompts; steps 2-4: two decoders fill the budget of 2, request 2 waits; then it runs alone
+    assert s["n_steps"] == 1 + 3 + 1 + 1
+    assert s["n_request_steps"] == 2 + 3 * 2 + 1 + 1
+    assert s["first"][2] > s["fin"][0] == s["fin"][1]
+
+
+def test_mean_tpot_over_requests_with_more_than_one_token(ora):
+    om, oh = bridge.ora_model(wl.DENSE_7B), bridge.ora_hw(wl.HW_TINY)
+    ins = np.array([300, 64, 700], dtype=np.uint32); outs = np.array([5, 1, 9], dtype=np.uint32)
+    arr = np.array([0.0, 100.0, 200.0])                           # far apart: each request has the engine to itself
+    s = ora.simulate(om, oh, 1, 16, 16, 2048, 8, 1.0, arr, ins, outs, detail=True)
+    tpot = [ora.evaluate(om, oh, ora.knobs(1, int(i), int(o), mbt=2048)).tpot for i, o in zip(ins, outs)]
+    assert s["mean_tpot"] == pytest.approx((tpot[0] + tpot[2]) / 2.0, rel=1e-12)      # the one-token request is left out
+    assert np.isfinite(s["mean_tpot"]) and tpot[0] != tpot[2]
