@@ -193,12 +193,29 @@ int guide_eval_grid(guide_ctx *ctx, const guide_grid *grid, uint64_t first, uint
  *   s_adj            the adjusted sequence length min(s_in + s_out, s_max).
  * The metrics of guide_eval_grid are computed at the nominal batch and lengths;
  * these columns say what the adjustments would make of them.
+ *
+ * KV-cache reduction (Inference Engine Step 1: the memory analysis takes into
+ * account "user inputs for optimization such as FlashAttention and H2O which
+ * reduce the memory consumption"; the paper gives no formula).  Reading: the user
+ * states kv_keep, the fraction of a request's KV entries that the reduction keeps
+ * (H2O's heavy-hitter budget), 0 < kv_keep <= 1; 0 stands for 1.  A request then
+ * holds ceil(kv_keep * (s_in + s_out)) entries (product in fp64), in whole blocks:
+ *   b_max_kept       floor(available / KV bytes of that many entries), as b_max;
+ *   feasible_kept    != 0 when the weights fit and the batch's kept entries fit;
+ *   s_max_kept       floor(s_max / kv_keep) (division in fp64): the longest
+ *                    sequence whose kept entries fit the batch; saturates.
+ * FlashAttention lowers activation memory, which this analysis (weights + KV
+ * cache) does not count: it has no column.  Other values of kv_keep (negative,
+ * above 1, NaN): GUIDE_E_ARG.
  */
 typedef struct {
     uint32_t *s_max, *dp_max;
     uint64_t *max_parallelism;
     double *cluster_tok_s, *paper_tok_s;
     uint32_t *b_adj, *n_sub_batches, *n_segments, *s_adj;
+    double kv_keep;                             /* INPUT, by value */
+    uint32_t *b_max_kept, *s_max_kept;
+    uint8_t *feasible_kept;
 } guide_extras;
 
 int guide_eval_extras(guide_ctx *ctx, const guide_grid *grid, uint64_t first, uint64_t count, uint32_t n_gpus,

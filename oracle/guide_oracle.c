@@ -284,12 +284,15 @@ typedef struct {
     uint32_t n_sub_batches;    /* prefill passes of the batch: ceil(b / split_size), remainder = one more pass */
     uint32_t n_segments;       /* splits of a long prompt: ceil(input length / split size) */
     uint32_t s_adj;            /* adjusted sequence length: min(s_in + s_out, S_max) */
+    uint32_t b_max_kept;       /* B_max, feasibility and S_max when a KV-cache reduction keeps the fraction */
+    uint32_t feasible_kept;    /* kv_keep of every request's entries (see ora_eval_extras) */
+    uint32_t s_max_kept;
 } ora_extras;
 
 /* Inference Engine Step 1 (maximum parallelism, max batch = parallelism / DP), Step 2 (multi-GPU
  * throughput heuristic), Model Analyzer "Dynamic Sequence Length Adjustment" (S_max). */
 void ora_eval_extras(const ora_model *m, const ora_hw *hw, const ora_knobs *kn, uint32_t n_gpus, int time_model,
-                     ora_extras *out) {
+                     double kv_keep, ora_extras *out) {
     ora_metrics r, r1;
     ora_knobs k1 = *kn;
     k1.p = 1;
@@ -325,6 +328,26 @@ void ora_eval_extras(const ora_model *m, const ora_hw *hw, const ora_knobs *kn, 
     }
     uint64_t len = kn->s_in + kn->s_out;
     out->s_adj = len < out->s_max ? (uint32_t)len : out->s_max;
+    /* Inference Engine Step 1: the memory analysis "takes into account user inputs for optimization such as
+     * FlashAttention and H2O which reduce the memory consumption".  The paper gives no formula; the reading: the
+     * user states the fraction kv_keep (0 < kv_keep <= 1) of a request's KV entries that the reduction keeps
+     * (H2O's heavy-hitter budget).  A request then holds ceil(kv_keep * (s_in + s_out)) entries, in whole blocks.
+     * FlashAttention changes activation memory, which this analysis (weights + KV) does not count. */
+    {
+        uint64_t kept = (uint64_t)ceil(kv_keep * (double)len);
+        uint64_t tok_req = (kept + kn->blk - 1) / kn->blk * kn->blk;
+        double kv_req = (double)tok_req * ora_kv_bytes_token(m, kn->p);
+        if (c_avail > 0.0) {
+            double qb = floor(c_avail / kv_req);
+            out->b_max_kept = qb >= 4294967295.0 ? 4294967295u : (uint32_t)qb;
+            out->feasible_kept = ((double)kn->b * kv_req <= c_avail) ? 1u : 0u;
+            /* longest sequence whose kept entries fit the batch: ceil(kv_keep S) <= S_max  <=>  S <= S_max / kv_keep */
+            double qs = floor(floor(c_avail / ((double)kn->b * ora_kv_bytes_token(m, kn->p))) / kv_keep);
+            out->s_max_kept = qs >= 4294967295.0 ? 4294967295u : (uint32_t)qs;
+        } else {
+            out->b_max_kept = 0; out->feasible_kept = 0; out->s_max_kept = 0;
+        }
+    }
 }
 
 /* ----------------------------------------------------------------------- grid */
@@ -377,16 +400,19 @@ int ora_eval_grid(const ora_grid *g, uint64_t first, uint64_t count, double e_c,
 }
 
 int ora_eval_extras_grid(const ora_grid *g, uint64_t first, uint64_t count, uint32_t n_gpus, int time_model,
+                         double kv_keep,
                          uint32_t *s_max, uint32_t *dp_max, uint64_t *max_par, double *cluster_tok_s,
-                         double *paper_tok_s, uint32_t *b_adj, uint32_t *n_sub, uint32_t *n_seg, uint32_t *s_adj) {
+                         double *paper_tok_s, uint32_t *b_adj, uint32_t *n_sub, uint32_t *n_seg, uint32_t *s_adj,
+                         uint32_t *b_max_kept, uint32_t *feasible_kept, uint32_t *s_max_kept) {
     uint64_t i;
     for (i = 0; i < count; ++i) {
         const ora_model *m; const ora_hw *hw; ora_knobs kn; ora_extras e;
         if (ora_grid_decode(g, first + i, &m, &hw, &kn)) return -1;
-        ora_eval_extras(m, hw, &kn, n_gpus, time_model, &e);
+        ora_eval_extras(m, hw, &kn, n_gpus, time_model, kv_keep, &e);
         s_max[i] = e.s_max; dp_max[i] = e.dp_max; max_par[i] = e.max_parallelism;
         cluster_tok_s[i] = e.cluster_tok_s; paper_tok_s[i] = e.paper_tok_s;
         b_adj[i] = e.b_adj; n_sub[i] = e.n_sub_batches; n_seg[i] = e.n_segments; s_adj[i] = e.s_adj;
+        b_max_kept[i] = e.b_max_kept; feasible_kept[i] = e.feasible_kept; s_max_kept[i] = e.s_max_kept;
     }
     return 0;
 }

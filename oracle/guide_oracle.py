@@ -102,8 +102,8 @@ def lib():
         _lib.ora_grid_size.restype = C.c_uint64
         _lib.ora_eval_grid.argtypes = [C.POINTER(GridC), C.c_uint64, C.c_uint64, C.c_double, C.c_double, C.c_int] + \
                                       [C.c_void_p] * 7
-        _lib.ora_eval_extras_grid.argtypes = [C.POINTER(GridC), C.c_uint64, C.c_uint64, C.c_uint32, C.c_int] + \
-                                             [C.c_void_p] * 9
+        _lib.ora_eval_extras_grid.argtypes = [C.POINTER(GridC), C.c_uint64, C.c_uint64, C.c_uint32, C.c_int,
+                                              C.c_double] + [C.c_void_p] * 12
         _lib.ora_eval_sweep.argtypes = [C.POINTER(Model), C.POINTER(Hw), C.POINTER(Knobs), C.c_uint32,
                                         C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
                                         C.POINTER(C.c_double), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
@@ -229,16 +229,17 @@ def eval_grid(g: Grid, first=0, count=None, e_c=1.0, e_b=1.0, time_model=ROOFLIN
     return cols
 
 
-def eval_extras_grid(g: Grid, n_gpus, first=0, count=None, time_model=ROOFLINE):
+def eval_extras_grid(g: Grid, n_gpus, first=0, count=None, time_model=ROOFLINE, kv_keep=1.0):
     count = g.size - first if count is None else count
-    u32 = ("s_max", "dp_max", "b_adj", "n_sub_batches", "n_segments", "s_adj")
+    u32 = ("s_max", "dp_max", "b_adj", "n_sub_batches", "n_segments", "s_adj", "b_max_kept", "feasible_kept",
+           "s_max_kept")
     out = {k: np.empty(count, dtype=np.uint32) for k in u32}
     out.update(max_parallelism=np.empty(count, dtype=np.uint64), cluster_tok_s=np.empty(count),
                paper_tok_s=np.empty(count))
-    rc = lib().ora_eval_extras_grid(C.byref(g.c), first, count, n_gpus, time_model,
-                                    *[_ptr(out[k]) for k in ("s_max", "dp_max", "max_parallelism", "cluster_tok_s",
-                                                             "paper_tok_s", "b_adj", "n_sub_batches", "n_segments",
-                                                             "s_adj")])
+    rc = lib().ora_eval_extras_grid(C.byref(g.c), first, count, n_gpus, time_model, float(kv_keep),
+           *[_ptr(out[k]) for k in ("s_max", "dp_max", "max_parallelism", "cluster_tok_s", "paper_tok_s", "b_adj",
+                                          "n_sub_batches", "n_segments", "s_adj", "b_max_kept", "feasible_kept",
+                                          "s_max_kept")])
     if rc:
         raise ValueError("oracle: index outside the grid")
     return out

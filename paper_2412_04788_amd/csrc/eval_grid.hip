@@ -700,6 +700,19 @@ __global__ __launch_bounds__(kBlock) void eval_extras_kernel(GridDesc g, const D
             const uint32_t len = c.kn.s_in + c.kn.s_out;              // both below 2^31
             out.s_adj[i] = len < s_max ? len : s_max;
         }
+        if (out.b_max_kept || out.feasible_kept || out.s_max_kept) {
+            // a KV-cache reduction that keeps the fraction kv_keep of every request's entries
+            const double keep = out.kv_keep == 0.0 ? 1.0 : out.kv_keep;
+            const uint32_t len = c.kn.s_in + c.kn.s_out;
+            const uint64_t kept = (uint64_t)ceil(keep * (double)len);
+            const uint64_t tok_req = (kept + c.kn.blk - 1) / c.kn.blk * c.kn.blk;
+            const double kv_req = (double)tok_req * cf.kv_tok;
+            const bool room = c_avail > 0.0;
+            const double qb = floor(c_avail / kv_req), qs = floor(q / keep);
+            if (out.b_max_kept) out.b_max_kept[i] = !room ? 0u : (qb >= 4294967295.0 ? 4294967295u : (uint32_t)qb);
+            if (out.feasible_kept) out.feasible_kept[i] = (room && (double)c.kn.b * kv_req <= c_avail) ? 1 : 0;
+            if (out.s_max_kept) out.s_max_kept[i] = !room ? 0u : (qs >= 4294967295.0 ? 4294967295u : (uint32_t)qs);
+        }
         if (out.cluster_tok_s) out.cluster_tok_s[i] = (double)dp * tok_s;
         if (out.paper_tok_s)
             out.paper_tok_s[i] = ((double)dp * (double)c.kn.p) * tok_s1 / (1.0 + log2((double)c.kn.p));

@@ -641,6 +641,8 @@ int guide_eval_extras(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
     if (!time_model_ok(time_model)) return fail(ctx, GUIDE_E_ARG, "unknown time model %u", time_model);
     if (!out) return fail(ctx, GUIDE_E_ARG, "guide_extras is NULL");
     if (n_gpus == 0) return fail(ctx, GUIDE_E_ARG, "n_gpus is zero");
+    if (!(out->kv_keep >= 0.0 && out->kv_keep <= 1.0))
+        return fail(ctx, GUIDE_E_ARG, "kv_keep must be in (0, 1] (or 0 for none), got %g", out->kv_keep);
     GridDesc desc;
     uint64_t size = 0;
     int rc = prepare_grid(ctx, grid, &desc, &size);

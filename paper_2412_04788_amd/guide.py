@@ -62,7 +62,7 @@ METRIC_COLUMNS = ("t_prefill", "t_decode", "t_batch", "decode_tok_s", "cost", "b
 STATS_COLUMNS = ("ttft_mean", "ttft_p10", "ttft_p90", "t_batch_mean", "t_batch_p10", "t_batch_p90", "cost", "b_max",
                  "feasible")
 EXTRAS_COLUMNS = ("s_max", "dp_max", "max_parallelism", "cluster_tok_s", "paper_tok_s", "b_adj", "n_sub_batches",
-                  "n_segments", "s_adj")
+                  "n_segments", "s_adj", "b_max_kept", "s_max_kept", "feasible_kept")
 SAMPLED_COLUMNS = ("feasible_count", "win_val", "win_idx", "hist", "t_prefill", "t_batch", "cost", "b_max",
                    "feasible", "bucket")
 SIM_COLUMNS = ("ttft_p50", "ttft_p99", "mean_tpot", "tokens_s", "status", "n_steps", "n_request_steps")
@@ -77,7 +77,8 @@ class CStats(C.Structure):
 
 
 class CExtras(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in EXTRAS_COLUMNS]
+    _fields_ = [(n, C.c_void_p) for n in EXTRAS_COLUMNS[:9]] + [("kv_keep", C.c_double)] + \
+               [(n, C.c_void_p) for n in EXTRAS_COLUMNS[9:]]
 
 
 class CSpace(C.Structure):
@@ -369,8 +370,8 @@ class Context:
         return ms[:n.value].copy()
 
     def eval_extras(self, grid: GridArg, first: int, count: int, n_gpus: int, out: dict,
-                    time_model: int = TIME_ROOFLINE, stream=None):
-        ce = CExtras(*[_dev_ptr(out.get(k)) for k in EXTRAS_COLUMNS])
+                    time_model: int = TIME_ROOFLINE, stream=None, kv_keep: float = 0.0):
+        ce = CExtras(**{k: _dev_ptr(out.get(k)) for k in EXTRAS_COLUMNS}, kv_keep=float(kv_keep))
         self._invoke(self._lib.guide_eval_extras, self._h, _Ref(grid.c, grid), first, count, n_gpus, time_model,
                      _Ref(ce), _stream_ptr(stream))
 

@@ -91,6 +91,10 @@ int main(int argc, char **argv) {
     { double e[2] = {1.0, 1.0}; guide_eff eff = {2, e, e};
       EXPECT(guide_eval_grid(ctx, &grid, 0, 1, &eff, 0, &out, NULL, NULL), GUIDE_E_ARG); }    /* sweep without guide_stats */
     EXPECT(guide_eval_extras(ctx, &grid, 0, 1, 0, 0, NULL, NULL), GUIDE_E_ARG);
+    { guide_extras ex; memset(&ex, 0, sizeof ex);
+      ex.kv_keep = 1.5; EXPECT(guide_eval_extras(ctx, &grid, 0, 1, 8, 0, &ex, NULL), GUIDE_E_ARG);
+      ex.kv_keep = -0.25; EXPECT(guide_eval_extras(ctx, &grid, 0, 1, 8, 0, &ex, NULL), GUIDE_E_ARG);
+      ex.kv_keep = 0.0; EXPECT(guide_eval_extras(ctx, &grid, 0, 0, 8, 0, &ex, NULL), GUIDE_OK); }      /* no rows: no-op */
     /* selection */
     {
         guide_select_spec sp; guide_select_out so = {dummy_u64, dummy_f64, dummy_u64, 0};

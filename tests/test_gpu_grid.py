@@ -229,6 +229,27 @@ def test_cluster_extras(ora, torch_cuda):
         assert exp["n_segments"].max() > 1 and exp["n_sub_batches"].max() > 1 and (exp["b_adj"] < 64).any()
         for k in ("cluster_tok_s", "paper_tok_s"):
             assert bridge.rel_err(bridge.to_np(out[k]), exp[k]).max() <= TOL, k
+    # KV-cache reduction: a kept fraction of every request's entries (0 stands for 1); other values are refused
+    from paper_2412_04788_amd import guide
+    count = g.size
+    kept = dict(b_max_kept=torch.empty(count, dtype=torch.int32, device="cuda"),
+                s_max_kept=torch.empty(count, dtype=torch.int32, device="cuda"),
+                feasible_kept=torch.empty(count, dtype=torch.uint8, device="cuda"))
+    grew = 0
+    for keep in (0.0, 1.0, 0.5, 0.2, 1.0 / 3.0, 1e-3):
+        ctx.eval_extras(bridge.gpu_grid(g), 0, count, 8, kept, kv_keep=keep)
+        torch.cuda.synchronize()
+        exp = ora.eval_extras_grid(bridge.ora_grid(g), 8, 0, count, kv_keep=keep if keep else 1.0)
+        np.testing.assert_array_equal(bridge.to_np(kept["b_max_kept"], np.uint32), exp["b_max_kept"], err_msg=str(keep))
+        np.testing.assert_array_equal(bridge.to_np(kept["s_max_kept"], np.uint32), exp["s_max_kept"], err_msg=str(keep))
+        np.testing.assert_array_equal(bridge.to_np(kept["feasible_kept"]), exp["feasible_kept"].astype(np.uint8),
+                                      err_msg=str(keep))
+        grew += int((exp["feasible_kept"] != 0).sum())
+    assert grew > 0
+    for bad in (-0.1, 1.5, float("nan")):
+        with pytest.raises(guide.GuideError) as err:
+            ctx.eval_extras(bridge.gpu_grid(g), 0, count, 8, kept, kv_keep=bad)
+        assert err.value.code == guide.E_ARG
     # NULL columns are skipped
     only = dict(dp_max=torch.empty(16, dtype=torch.int32, device="cuda"))
     ctx.eval_extras(bridge.gpu_grid(g), 0, 16, 8, only)

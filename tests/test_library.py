@@ -32,7 +32,7 @@ def test_binding_structs_match_header_sizes():
     assert ctypes.sizeof(guide.CAxis) == 24 and ctypes.sizeof(guide.CGrid) == 9 * 24
     assert ctypes.sizeof(guide.CSelectSpec) == 4 + 4 + 3 * 8 + 8 + 4 * 16 + 8 + 8
     assert ctypes.sizeof(guide.CSpace) == 12 * 8 + 5 * 4 + 4 + 8
-    assert ctypes.sizeof(guide.CExtras) == 9 * 8
+    assert ctypes.sizeof(guide.CExtras) == 9 * 8 + 8 + 3 * 8
 
 
 def test_binding_structs_match_the_c_compiler(tmp_path):

@@ -1065,3 +1065,35 @@ def test_mean_tpot_over_requests_with_more_than_one_token(ora):
     tpot = [ora.evaluate(om, oh, ora.knobs(1, int(i), int(o), mbt=2048)).tpot for i, o in zip(ins, outs)]
     assert s["mean_tpot"] == pytest.approx((tpot[0] + tpot[2]) / 2.0, rel=1e-12)      # the one-token request is left out
     assert np.isfinite(s["mean_tpot"]) and tpot[0] != tpot[2]
+
+
+def test_kv_cache_reduction_columns(ora):
+    """Inference Engine Step 1 with a KV-cache reduction that keeps a fraction of every request's entries: the whole
+    cache (fraction 1) is the plain analysis; a quarter of 1000 entries is 250, stored in 16 blocks of 16, worked by hand
+    for the 7B shape (524 288 B per entry, 13 476 298 752 B of fp16 weights) on an 80 GiB GPU."""
+    g = wl.grid_tiny()
+    og = bridge.ora_grid(g)
+    base, e1 = ora.eval_grid(og), ora.eval_extras_grid(og, 8, kv_keep=1.0)
+    np.testing.assert_array_equal(e1["b_max_kept"], base["b_max"])
+    np.testing.assert_array_equal(e1["feasible_kept"], base["feasible"])
+    np.testing.assert_array_equal(e1["s_max_kept"], e1["s_max"])
+    h = wl.Hardware(1e15, 5e12, 80 * wl.GIB, 4e11)
+    g1 = wl.make_grid([wl.DENSE_7B], [h], wl.Axis.table([4, 600]), wl.Axis.table([900, 901]), wl.Axis.table([100]),
+                      wl.Axis.table([1]), wl.Axis.table([16]), wl.Axis.table([16, 1]), wl.Axis.table([8192]))
+    e = ora.eval_extras_grid(bridge.ora_grid(g1), 8, kv_keep=0.25)
+    at = lambda b, s_in, blk: g1.flat((0, 0, (4, 600).index(b), (900, 901).index(s_in), 0, 0, 0, (16, 1).index(blk), 0))
+    c_avail = 80 * 2 ** 30 - 13476298752
+    assert c_avail == 72423047168
+    # 250 kept entries -> 256 in blocks of 16: floor(72 423 047 168 / (256 * 524 288)) = 539 requests
+    assert e["b_max_kept"][at(4, 900, 16)] == 539 and e["feasible_kept"][at(4, 900, 16)] == 1
+    assert e["feasible_kept"][at(600, 900, 16)] == 0                      # 600 > 539
+    # blocks of one entry: 250 entries -> floor(c / (250 * 524 288)) = 552; 1001 tokens keep ceil(250.25) = 251 -> 550
+    assert e["b_max_kept"][at(4, 900, 1)] == 552 and e["b_max_kept"][at(4, 901, 1)] == 550
+    assert e["feasible_kept"][at(600, 900, 1)] == 0 and e["b_max_kept"][at(600, 900, 1)] == 552
+    # S_max = floor(c / (4 * 524 288)) = 34 534 entries per request; a quarter kept: sequences of up to 138 136 tokens
+    assert e["s_max"][at(4, 900, 16)] == 34534 and e["s_max_kept"][at(4, 900, 16)] == 138136
+    # keeping less never admits fewer
+    for keep in (0.9, 0.5, 0.1):
+        k = ora.eval_extras_grid(og, 8, kv_keep=keep)
+        assert np.all(k["b_max_kept"] >= base["b_max"]) and np.all(k["feasible_kept"] >= base["feasible"])
+        assert np.all(k["s_max_kept"] >= e1["s_max"])
