@@ -1092,6 +1092,14 @@ def test_kv_cache_reduction_columns(ora):
     assert e["feasible_kept"][at(600, 900, 1)] == 0 and e["b_max_kept"][at(600, 900, 1)] == 552
     # S_max = floor(c / (4 * 524 288)) = 34 534 entries per request; a quarter kept: sequences of up to 138 136 tokens
     assert e["s_max"][at(4, 900, 16)] == 34534 and e["s_max_kept"][at(4, 900, 16)] == 138136
+    # the boundary is inclusive: capacity for exactly 6 requests' kept entries admits a batch of 6, one byte less does not
+    kv_req = 256 * 524288
+    for cap, ok in ((13476298752 + 6 * kv_req, 1), (13476298752 + 6 * kv_req - 1, 0)):
+        gb = wl.make_grid([wl.DENSE_7B], [wl.Hardware(1e15, 5e12, float(cap), 4e11)], wl.Axis.table([6]), wl.Axis.table([900]),
+                          wl.Axis.table([100]), wl.Axis.table([1]), wl.Axis.table([16]), wl.Axis.table([16]),
+                          wl.Axis.table([8192]))
+        eb = ora.eval_extras_grid(bridge.ora_grid(gb), 8, kv_keep=0.25)
+        assert eb["feasible_kept"][0] == ok and eb["b_max_kept"][0] == 5 + ok
     # keeping less never admits fewer
     for keep in (0.9, 0.5, 0.1):
         k = ora.eval_extras_grid(og, 8, kv_keep=keep)
