@@ -791,14 +791,15 @@ struct FinishLds {
 // L.off[b] - base + i.  L.foff must be zero and the staging complete (the function starts with a barrier).
 // Calls emit(position, row) for every front member, position = its rank by (bin, x, y, row) among the
 // front members staged here, and returns their number.
-// Eight lanes per survivor: they share out the members of its bin, four LDS reads in flight each, and
-// meet through a wave ballot.  A survivor's test is a chain of dependent LDS reads, so many survivors
-// are kept in flight; fewer lanes per survivor (one round over all survivors, longer chains) measured
-// slower.
-template <typename Emit>
-__device__ inline uint32_t staged_front(FinishLds &L, uint32_t cnt, uint32_t base, Emit &&emit) {
-    constexpr uint32_t P = kPerFinish, group = 8, q_step = kFinishThreads / group;
-    constexpr uint64_t group_mask = (1ull << group) - 1;
+// GROUP lanes per survivor (8 or 1): they share out the members of its bin, four LDS reads in flight each, and
+// meet through a wave ballot.  A survivor's test is a chain of dependent LDS reads, so many survivors are kept
+// in flight.  Up to 1024 survivors, eight lanes each are fastest (one lane per survivor: one round over all of
+// them but longer chains, +1 to +6 us, the fullest bin setting the pace); beyond, one lane each saves more
+// rounds (a round over 128 survivors costs about as much as one over 1024) than the chains cost.
+template <uint32_t GROUP, typename Emit>
+__device__ inline uint32_t staged_front_by(FinishLds &L, uint32_t cnt, uint32_t base, Emit &&emit) {
+    constexpr uint32_t P = kPerFinish, group = GROUP, q_step = kFinishThreads / group;
+    constexpr uint64_t group_mask = group < 64 ? (1ull << group) - 1 : ~0ull;
     const uint32_t t = threadIdx.x, lane = t % kWave, sub = lane % group, shift = lane - sub;
     __syncthreads();
     const uint32_t cnt_pad = (cnt + q_step - 1) / q_step * q_step;      // wave-uniform trip count for the ballot
@@ -862,6 +863,31 @@ __device__ inline uint32_t staged_front(FinishLds &L, uint32_t cnt, uint32_t bas
         if (live && sub == 0) emit(L.foff[padded<P>(b)] + rank, i);
     }
     return nf;
+}
+// b_lo .. b_hi: the bins that hold the staged survivors.  One lane per survivor only when there are more than
+// 1024 of them and a survivor's bin holds 32 members or fewer on average over the survivors (sum of squared bin
+// counts <= 32 * cnt): crowded bins want the eight lanes (400 000 front rows took 2.2 instead of 2.1 ms,
+// 1 900 800 took 32.5 instead of 31.2 ms with one lane each), sparse ones the fewer rounds (4 000 front rows:
+// 26 instead of 60 us).
+template <typename Emit>
+__device__ inline uint32_t staged_front(FinishLds &L, uint32_t cnt, uint32_t base, uint32_t b_lo, uint32_t b_hi,
+                                        Emit &&emit) {
+    if (cnt <= 1024) return staged_front_by<8>(L, cnt, base, emit);     // block-uniform
+    constexpr uint32_t P = kPerFinish;
+    uint32_t sq = 0;                                    // at most cnt * kStage < 2^32
+#pragma unroll
+    for (uint32_t q = 0; q < P; ++q) {
+        const uint32_t b = q * kFinishThreads + threadIdx.x;
+        const uint32_t n = (b >= b_lo && b <= b_hi) ? L.off[padded<P>(b + 1)] - L.off[padded<P>(b)] : 0u;
+        sq += n * n;
+    }
+    sq = wave_sum(sq);
+    __syncthreads();                                    // L.tmp may still be read by the scan before
+    if (threadIdx.x % kWave == 0) L.tmp[threadIdx.x / kWave] = sq;
+    __syncthreads();
+    uint32_t total = 0;
+    for (uint32_t wv = 0; wv < kFinishThreads / kWave; ++wv) total += L.tmp[wv];
+    return total <= 32 * cnt ? staged_front_by<1>(L, cnt, base, emit) : staged_front_by<8>(L, cnt, base, emit);
 }
 
 // The same for bins b_lo .. b_hi when their survivors do not fit the staging arrays: the records stay in the
@@ -1008,7 +1034,7 @@ __device__ void pareto_large_front(FinishLds &L, const ParetoWs &w, SelectScratc
                     L.row[i] = w.surv[q];
                     L.bin[i] = (uint16_t)bin(kx);
                 }
-                nf = staged_front(L, cnt, base, emit);
+                nf = staged_front(L, cnt, base, r_lo, r_hi, emit);
             } else if (cnt <= kStage) {
                 for (uint32_t q0 = t; q0 < m; q0 += 4 * NT) {
                     uint64_t kx[4];
@@ -1026,7 +1052,7 @@ __device__ void pareto_large_front(FinishLds &L, const ParetoWs &w, SelectScratc
                         }
                     }
                 }
-                nf = staged_front(L, cnt, base, emit);
+                nf = staged_front(L, cnt, base, r_lo, r_hi, emit);
             } else {
                 nf = unstaged_front(L, w, bin, r_lo, r_hi, emit);
             }
@@ -1146,7 +1172,7 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
             L.kx[pos] = rx[q]; L.ky[pos] = ry[q]; L.row[pos] = rr[q]; L.bin[pos] = (uint16_t)b;
         }
     }
-    const uint32_t n_front = staged_front(L, m, 0, [&](uint32_t pos, uint32_t row) {
+    const uint32_t n_front = staged_front(L, m, 0, 0, kBins - 1, [&](uint32_t pos, uint32_t row) {
         if (pos < capacity) out_idx[pos] = row;
     });
     if (t == 0) out_count[0] = n_front;
