@@ -142,17 +142,17 @@ def main():
     t1 = time.perf_counter()
     total = t1 - t0
     # Duration of the grid-evaluation kernel INSIDE the step: a second run of the same steps in which the library
-    # attaches a pair of HIP events to the dispatch of each of the step's four kernels, on the launch stream (every
+    # attaches a pair of HIP events to the dispatch of each of the step's three kernels, on the launch stream (every
     # dispatch observed the same way, as under a kernel trace; a timed launch delays the launches around it by a few
     # microseconds, so this run is not the throughput run).
     n_timed = max(args.steps, 32)
-    ctx.profile_enable(4 * n_timed, 1)
+    ctx.profile_enable(3 * n_timed, 1)
     for k in range(n_timed):
         step()
     torch.cuda.synchronize()
-    ms_all = np.asarray(ctx.profile_read(4 * n_timed), dtype=np.float64)
-    assert ms_all.size == 4 * n_timed
-    ms_all = ms_all.reshape(n_timed, 4)             # evaluation, staircase (+ top-k lists), survivors, finish (+ merge)
+    ms_all = np.asarray(ctx.profile_read(3 * n_timed), dtype=np.float64)
+    assert ms_all.size == 3 * n_timed
+    ms_all = ms_all.reshape(n_timed, 3)             # evaluation (+ row sample), filter (+ top-k lists), finish (+ merge)
     ms_kernel = ms_all[:, 0]
     ms_eval = float(np.mean(ms_kernel))
     ctx.profile_enable(0)
@@ -204,13 +204,12 @@ def main():
                      "kernel": "eval_tile_kernel<false,2,3,false>",
                      "kernel_ms": ms_eval, "kernel_ms_min": float(np.min(ms_kernel)),
                      "kernel_launches_timed": n_timed,
-                     "timing": "HIP event pairs on the dispatches of all four kernels of every step",
+                     "timing": "HIP event pairs on the dispatches of all three kernels of every step",
                      "plain_eval_kernel_ms_back_to_back": ms_eval_b2b,
                      "frac_back_to_back": BYTES_PER_CONFIG * n / (ms_eval_b2b * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "bytes_per_config": BYTES_PER_CONFIG, "grid_sustained": sustained},
-        "phases_ms": {"eval_kernel_in_step": ms_eval, "staircase_topk_kernel_in_step": float(ms_all[:, 1].mean()),
-                      "survivors_kernel_in_step": float(ms_all[:, 2].mean()),
-                      "finish_merge_kernel_in_step": float(ms_all[:, 3].mean()),
+        "phases_ms": {"eval_kernel_in_step": ms_eval, "filter_topk_kernel_in_step": float(ms_all[:, 1].mean()),
+                      "finish_merge_kernel_in_step": float(ms_all[:, 2].mean()),
                       "step_kernels_sum": float(ms_all.sum(axis=1).mean()), "step_as_three_calls": ms_separate,
                       "select_topk_alone": ms_topk, "select_pareto_alone": ms_pareto},
     }

@@ -354,7 +354,7 @@ int guide_select(guide_ctx *ctx, const guide_select_spec *spec, uint64_t n, cons
  * workspace: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  The same selection and the same outputs as guide_select; the
  * workspace and the Pareto tables live in one static device array inside the
- * library (about 50 MiB on every GPU the library runs on, held until the
+ * library (about 60 MiB on every GPU the library runs on, held until the
  * process ends; its address is taken once per device in guide_create).  The
  * call allocates and frees nothing.  Limits: the selection's workspace
  * (guide_select_workspace_bytes) must fit the array, which holds a Pareto

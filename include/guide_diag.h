@@ -19,14 +19,14 @@ extern "C" {
  * first, the every+1-th, ...) carries a pair of HIP events on the call's stream
  * that receive the start and the end of that kernel's dispatch.  When such a
  * guide_eval_select call has one top-k and one Pareto selection over stored
- * columns, the three kernels of its selection passes (staircase, survivors,
- * finish) carry a pair each as well, so that every dispatch of the call is
- * observed the same way.  `capacity` is the number of pairs (later launches are
+ * columns, the two kernels of its selection passes (filter, finish) carry a
+ * pair each as well, so that every dispatch of the call is observed the same
+ * way.  `capacity` is the number of pairs (later launches are
  * not timed); capacity 0 switches it off.  A timed launch delays the launches
  * around it by a few microseconds, which is why a caller that also measures
  * throughput times separate calls.  guide_profile_read waits for the recorded
  * events, writes the elapsed milliseconds of each timed kernel, in launch
- * order (four per such guide_eval_select call, one per other call), to
+ * order (three per such guide_eval_select call, one per other call), to
  * ms[0 .. *n) (HOST, room for `capacity` values) and starts over.
  */
 int guide_profile_enable(guide_ctx *ctx, uint32_t capacity, uint32_t every);

@@ -141,10 +141,12 @@ __global__ __launch_bounds__(kBlock) void tile_tables_kernel(GridDesc g, const D
 }
 
 // Row sample for a Pareto selection over the rows being evaluated, taken by extra blocks of the evaluation kernel
-// (block `rb` of them; kBlock samples each): sample number k is row k * stride of the evaluated range.  The
-// sampled rows are evaluated here from scratch rather than read back, so the sample does not wait for the columns;
-// it only fixes the range of x that the selection's bins slice (any range is correct, a good one is fast).
+// (block `rb` of them; kBlock samples each): sample_number / sample_row give the rows.  The
+// sampled rows are evaluated here from scratch rather than read back, so the sample does not wait for the columns.
+// It fixes the range of x that the selection's bins slice (any range is correct, a good one is fast), and the
+// block hands the front of its sample rows to the selection's filter pass (store_sample_front).
 // Also puts the tables that the selection's kernels accumulate into in their neutral state.
+constexpr uint64_t kSampleMargin = 1ull << 26;      // in key units: 2^-26 relative for a normal number
 template <bool ADDITIVE>
 __device__ inline void sample_rider(const GridLds &s, const GridDesc &g, uint32_t rb, uint32_t n_rider_blocks, uint32_t first,
                                     uint32_t count, double re_c, double re_b, const FusedSelect &fs) {
@@ -152,18 +154,20 @@ __device__ inline void sample_rider(const GridLds &s, const GridDesc &g, uint32_
     __shared__ uint64_t s_lo[kWaves];
     __shared__ Pair s_best[kWaves];
     SelectScratch *sc = (SelectScratch *)fs.scratch;
-    const uint32_t k = rb * kBlock + threadIdx.x;
+    const uint32_t gid = rb * kBlock + threadIdx.x;
     const uint32_t n_samples = n_rider_blocks * kBlock;
-    for (uint32_t i = k; i < kBins; i += n_samples) {
+    for (uint32_t i = gid; i < kBins; i += n_samples) {
         sc->bin_min[i] = kNone;
         sc->bin_cnt[i] = 0;
     }
-    if (k == 0) sc->counters[0] = sc->counters[1] = 0;
+    if (gid == 0) sc->counters[0] = sc->counters[1] = 0;
     const uint32_t stride = count > n_samples ? count / n_samples : 1;
-    uint64_t lo = kNone;
+    const uint32_t k = sample_number(rb, n_rider_blocks);
+    uint64_t lo = kNone, kx = 0, ky = 0;
     Pair best = {kNone, kNone};
+    bool pass = false;
     if ((uint64_t)k * stride < count) {
-        const Candidate c = decode_index(s, g, first + k * stride);
+        const Candidate c = decode_index(s, g, first + sample_row(k, stride));
         const Coef cf = make_coef(s.models[c.model], c.kn.p, c.kn.wbits);
         const HwRecip hw = s.hw[c.hw];
         const TimeCoef tc = make_time_coef(cf, hw.r_peak * re_c, hw.r_bw * re_b, hw.r_link, hw.lat);
@@ -177,14 +181,27 @@ __device__ inline void sample_rider(const GridLds &s, const GridDesc &g, uint32_
                    : id == GUIDE_COL_T_BATCH ? t_batch
                    : id == GUIDE_COL_DECODE_TOK_S ? tok_s : cost;
         };
+        // The values here come from another instruction sequence than the stored columns and may differ
+        // from them in the last bits (every sequence is within 1e-9 relative of the definition), while a
+        // sample row may only prune rows that the stored row dominates.  So the sample row is moved up by
+        // 2^-26 relative in x and y (a point that the stored row dominates prunes no row wrongly), and it
+        // must pass its filter by the same margin (a row that is not a passing row must prune nothing).
         const double x = col(fs.pareto_x), y = col(fs.pareto_y);
         bool ok = x == x && y == y;
-        for (uint32_t q = 0; q < fs.pareto_filter.n_con; ++q) ok = ok && col(fs.pareto_filter.col[q]) <= fs.pareto_filter.cap[q];
-        if (ok && fs.pareto_filter.use_feasible)
-            ok = memory_check(cf, hw.cap, c.kn.b, c.kn.s_in, c.kn.s_out, c.kn.blk).feasible;
+        for (uint32_t q = 0; q < fs.pareto_filter.n_con; ++q) {
+            const double v = col(fs.pareto_filter.col[q]), cap = fs.pareto_filter.cap[q];
+            ok = ok && v == v && cap == cap && key_of(v) + kSampleMargin <= key_of(cap);
+        }
+        if (ok && fs.pareto_filter.use_feasible) {
+            const double c_avail = hw.cap - cf.w_gpu;
+            const uint32_t tok_req = (c.kn.s_in + c.kn.s_out + c.kn.blk - 1) / c.kn.blk * c.kn.blk;
+            ok = c_avail > 0.0 && (double)c.kn.b * ((double)tok_req * cf.kv_tok) * (1.0 + 0x1p-26) <= c_avail;
+        }
         if (ok) {
-            lo = key_of(x);
-            best = Pair{key_of(y), lo};
+            pass = true;
+            lo = kx = key_of(x);
+            ky = key_of(y);
+            best = Pair{ky, kx};
         }
     }
     lo = wave_min(lo);
@@ -193,6 +210,7 @@ __device__ inline void sample_rider(const GridLds &s, const GridDesc &g, uint32_
         s_lo[threadIdx.x / kWave] = lo;
         s_best[threadIdx.x / kWave] = best;
     }
+    store_sample_front(pass, kx + kSampleMargin, ky + kSampleMargin, sc->sample_front + rb * kSampleFrontPer);
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int wv = 1; wv < kWaves; ++wv) {
@@ -739,6 +757,7 @@ static uint32_t tile_blocks(uint32_t first, uint32_t count, uint32_t ts) {
 // Sampling of rows for the Pareto bin range: row i is a sample when i = q * stride with q < kSampleRows.
 constexpr uint32_t kSampleRows = 16384;
 constexpr uint32_t kRiderBlocks = kSampleRows / kBlock;     // sample blocks appended to a plain evaluation
+static_assert(kRiderBlocks == kSampleBlocks, "the scratch holds one sample front per sample block");
 
 template <bool ADDITIVE, int NB, int NM>
 static void launch_tile(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,

@@ -52,7 +52,7 @@ static_assert(guide_ctx::kSlotBytes >= sizeof(DevTables), "staging slot too smal
 // selection over GUIDE_STATIC_SELECT_MAX_ROWS rows or any top-k selection).  Every GPU holds its own copy
 // at its own address: host code never uses the array's name as a pointer, only the address that
 // hipGetSymbolAddress returned for the device (static_scratch_of).
-constexpr size_t kStaticWsBytes = (size_t)GUIDE_STATIC_SELECT_MAX_ROWS * 29 + 256;
+constexpr size_t kStaticWsBytes = (size_t)GUIDE_STATIC_SELECT_MAX_ROWS * 30 + 256;
 static __device__ __align__(256) unsigned char scratch[kSelectScratchMax + kStaticWsBytes];
 constexpr int kMaxDevices = 64;
 static void *g_static_scratch[kMaxDevices];      // per device: address of `scratch` there, set by guide_create
@@ -223,10 +223,10 @@ LaunchTiming next_timing(guide_ctx *ctx) {
     return t;
 }
 
-// Three more pairs for the selection passes of a call whose evaluation kernel is timed (false: too few left).
-bool pass_timing(guide_ctx *ctx, LaunchTiming (&t)[3]) {
-    if (2 * ((size_t)ctx->prof_used + 3) > ctx->prof_ev.size()) return false;
-    for (int i = 0; i < 3; ++i) {
+// Two more pairs for the selection passes of a call whose evaluation kernel is timed (false: too few left).
+bool pass_timing(guide_ctx *ctx, LaunchTiming (&t)[2]) {
+    if (2 * ((size_t)ctx->prof_used + 2) > ctx->prof_ev.size()) return false;
+    for (int i = 0; i < 2; ++i) {
         t[i].start = ctx->prof_ev[2 * ctx->prof_used];
         t[i].stop = ctx->prof_ev[2 * ctx->prof_used + 1];
         ++ctx->prof_used;
@@ -569,8 +569,8 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
     hipError_t e = hipSuccess;
     if (topk && pareto && count > 0 && !fold) {
         // both selections read stored columns: the small kernels ride along with the large ones
-        // with a timed evaluation kernel, the three passes are timed as well (when the pairs suffice)
-        LaunchTiming passes[3];
+        // with a timed evaluation kernel, the two passes are timed as well (when the pairs suffice)
+        LaunchTiming passes[2];
         const bool timed = eval_timed && pass_timing(ctx, passes);
         e = launch_select_both(spec_of(*topk, *out), topk->out, ws_of[topk - sel], spec_of(*pareto, *out), pareto->out,
                                ws_of[pareto - sel], count, ctx->select_scratch, stream, sampled_partials, row_chunk,

@@ -64,7 +64,7 @@ hipError_t launch_select_both(const guide_select_spec &topk, const guide_select_
                               const guide_select_spec &pareto, const guide_select_out &pareto_out, void *pareto_ws,
                               uint64_t n, void *scratch, hipStream_t stream, uint32_t sampled_partials = 0,
                               uint32_t row_chunk = 0, const LaunchTiming *pass_timing = nullptr);
-// pass_timing: three event pairs for the staircase, survivors and finishing kernels (or nullptr).
+// pass_timing: two event pairs for the filter and finishing kernels (or nullptr).
 // row_chunk: rows are dealt to the blocks of the selection passes in chunks of that many rows, chunk c to block
 // c % blocks (0 = the passes' own batch size).  eval_grid_row_chunk() gives the chunk in which the evaluation
 // kernel deals its rows to blocks the same way, so that a row is read through the L2 that wrote it.

@@ -392,8 +392,9 @@ struct ParetoWs {
     uint32_t *staged;     // [n]: per part of the front, from its first survivor slot on: its front members' rows in order
     uint32_t *grouped;    // [n]: positions into surv, grouped by bin (parts whose survivors do not fit LDS)
     uint8_t *on_front;    // [n]: flag per grouped survivor (the same parts)
+    uint8_t *dead;        // [n]: flag per survivor slot: a survivor of a lower bin dominates it
 };
-size_t pareto_ws_bytes(uint64_t n) { return (size_t)n * (8 + 8 + 4 + 4 + 4 + 1) + 256; }
+size_t pareto_ws_bytes(uint64_t n) { return (size_t)n * (8 + 8 + 4 + 4 + 4 + 1 + 1) + 256; }
 ParetoWs pareto_ws(void *ws, uint64_t n) {
     ParetoWs w;
     w.skx = (uint64_t *)ws;
@@ -402,6 +403,7 @@ ParetoWs pareto_ws(void *ws, uint64_t n) {
     w.staged = w.surv + n;
     w.grouped = w.staged + n;
     w.on_front = (uint8_t *)(w.grouped + n);
+    w.dead = w.on_front + n;
     return w;
 }
 
@@ -431,26 +433,27 @@ __device__ inline Binning binning_of(uint64_t lo, uint64_t hi) {
 // beyond it are dominated by that row unless their y is smaller still; they share
 // the last bin).  Any monotone binning is correct -- the sample only decides how
 // finely the interesting stretch of x is resolved.
-constexpr uint32_t kSampleBlocks = 64;
 __device__ void pareto_prepare_body(uint32_t block, const double *__restrict__ x, const double *__restrict__ y,
                                     const RowFilter &f, uint32_t n, SelectScratch *sc) {
     __shared__ uint64_t s_lo[kWaves];
     __shared__ Pair s_best[kWaves];
-    const uint32_t k = block * kBlock + threadIdx.x;                // sample number
+    const uint32_t gid = block * kBlock + threadIdx.x;
     const uint32_t n_samples = kSampleBlocks * kBlock;
     static_assert(kSampleBlocks * kBlock >= kBins, "one table entry per thread");
-    if (k < kBins) {                                                // neutral state for the kernels that follow
-        sc->bin_min[k] = kNone;
-        sc->bin_cnt[k] = 0;
+    if (gid < kBins) {                                              // neutral state for the kernels that follow
+        sc->bin_min[gid] = kNone;
+        sc->bin_cnt[gid] = 0;
     }
-    if (k == 0) sc->counters[0] = sc->counters[1] = 0;
+    if (gid == 0) sc->counters[0] = sc->counters[1] = 0;
     const uint32_t stride = n > n_samples ? n / n_samples : 1;
-    const Row r = load_row<true, GUIDE_MAX_CONSTRAINTS>(x, y, f, (uint64_t)k * stride < n ? k * stride : n, n);
-    uint64_t lo = kNone;
+    const uint32_t k = sample_number(block, kSampleBlocks);
+    const Row r = load_row<true, GUIDE_MAX_CONSTRAINTS>(x, y, f, (uint64_t)k * stride < n ? sample_row(k, stride) : n, n);
+    uint64_t lo = kNone, kx = 0, ky = 0;
     Pair best = {kNone, kNone};                                     // (y key, x key) of the least y
     if (r.pass) {
-        lo = key_of(r.x);
-        best = Pair{key_of(r.y), lo};
+        lo = kx = key_of(r.x);
+        ky = key_of(r.y);
+        best = Pair{ky, kx};
     }
     lo = wave_min(lo);
     best = wave_min(best);
@@ -458,6 +461,7 @@ __device__ void pareto_prepare_body(uint32_t block, const double *__restrict__ x
         s_lo[threadIdx.x / kWave] = lo;
         s_best[threadIdx.x / kWave] = best;
     }
+    store_sample_front(r.pass, kx, ky, sc->sample_front + block * kSampleFrontPer);
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int wv = 1; wv < kWaves; ++wv) {
@@ -603,16 +607,11 @@ struct SharedTopk {
     Top1Ws w;                      // block partials, as written by the top-k pass
 };
 
-// KT: pairs per block partial of the shared top-k (0 = none; then `topk` is ignored).
-template <uint32_t MAXC, int KT, uint32_t U>
+template <uint32_t MAXC, uint32_t U>
 __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__restrict__ x, const double *__restrict__ y,
                                                               RowFilter f, uint32_t n, SelectScratch *sc, uint32_t n_partials,
-                                                              SharedTopk topk, uint32_t chunk) {
+                                                              uint32_t chunk) {
     __shared__ uint64_t s_min[padded_size<kPerPass>()], s_tmp[kWaves], s_rng[2];
-    constexpr int KL = KT ? KT : 1;
-    TopList<KL> list;
-    uint32_t n_pass = 0;                                // rows of one lane: fewer than 2^32
-    if (KT) list.init();
     // the first batch of rows is requested before the set-up below, so that its latency overlaps it
     RawRow<MAXC> r[U];
     ChunkWalk<U> cw(chunk, n, gridDim.x);
@@ -624,7 +623,6 @@ __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__re
     for (uint32_t i = threadIdx.x; i < padded_size<kPerPass>(); i += kBlock) s_min[i] = kNone;
     const Binning bin = sampled_binning(sc, n_partials, s_rng);     // its barrier also covers the table above
     while (cw.live()) {
-        const uint32_t base = (uint32_t)cw.base;
         // the next batch is requested before this one is worked on
         RawRow<MAXC> rn[U];
         cw.next();
@@ -643,17 +641,6 @@ __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__re
                 // the slot only decreases, so a stale read can only let an extra atomic through
                 if (ky < s_min[b]) atomicMin((unsigned long long *)&s_min[b], (unsigned long long)ky);
             }
-            if (KT) {
-                const double obj = topk.obj_is_y ? r[u].y : r[u].x;
-                bool ok = r[u].valid && (!topk.use_feasible || r[u].fe != 0) && obj == obj;
-#pragma unroll
-                for (uint32_t c = 0; c < 2; ++c)
-                    if (c < topk.n_con) ok = ok && ((topk.con_is_y[c] ? r[u].y : r[u].x) <= topk.cap[c]);
-                if (ok) {
-                    ++n_pass;
-                    list.insert_ascending(Pair{key_of(obj), (uint64_t)(base + threadIdx.x + u * kBlock)});
-                }
-            }
         }
         if (more) {
 #pragma unroll
@@ -661,21 +648,6 @@ __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__re
         }
     }
     __syncthreads();
-    // The block's top-k partial is worked out first and kept in registers: every global access of the tail
-    // (its stores and the table's atomics) is issued after the last barrier, so that no barrier waits for one.
-    constexpr int KLL = KT ? KT : 1;
-    int my_rank = -1;
-    Pair my_pair = {kNone, kNone};
-    __shared__ Pair s_pairs[kWaves][KLL];
-    __shared__ uint64_t s_cnt[kWaves];
-    if (KT) {
-        const uint32_t wave_pass = wave_sum(n_pass);
-        if (threadIdx.x % kWave == 0) s_cnt[threadIdx.x / kWave] = wave_pass;
-        block_topk<KLL, kWaves>(list, s_pairs, [&](int rk, const Pair &p) {
-            my_rank = rk;
-            my_pair = p;
-        });                                             // (contains the barrier that publishes s_cnt)
-    }
     // The table is only read through its exclusive prefix-min, and only a block's running minima
     // (entries below everything in its lower bins) can lower that: the others are not sent.  The
     // atomics return nothing, so no lane waits for them.
@@ -688,17 +660,6 @@ __global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__re
         if (v[j] < run) {
             atomicMin((unsigned long long *)&sc->bin_min[threadIdx.x * kPerPass + j], (unsigned long long)v[j]);
             run = v[j];
-        }
-    }
-    if (KT) {
-        if (my_rank >= 0) {
-            topk.w.key[(size_t)blockIdx.x * KLL + my_rank] = my_pair.key;
-            topk.w.idx[(size_t)blockIdx.x * KLL + my_rank] = my_pair.idx;
-        }
-        if (threadIdx.x == 0) {
-            uint64_t c = 0;
-            for (int wv = 0; wv < kWaves; ++wv) c += s_cnt[wv];
-            topk.w.cnt[blockIdx.x] = c;
         }
     }
 }
@@ -772,20 +733,177 @@ __global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *
     }
 }
 
+// The filter pass of the three-launch form: the sampling blocks have handed over the front of their sample
+// rows (SelectScratch::sample_front); every block bins those few rows in LDS (least y per bin, then its
+// exclusive prefix-min) and keeps a row when no sample row of a strictly lower bin has a y at or below its
+// own.  Every row of the front is kept, and every other kept row is dominated by a kept one (its
+// dominators are themselves dominated by a front row, and domination is transitive).  Kept rows are appended
+// as (row, keys), counted per bin, and their least y per bin goes to the global table, whose exclusive
+// prefix-min tells the finishing kernel which kept rows a kept row of a lower bin dominates.
+// KT: pairs per block partial of a top-k that shares the columns (0 = none), as in the staircase kernel.
+template <uint32_t MAXC, int KT, uint32_t U>
+__global__ __launch_bounds__(kBlock) void pareto_filter_kernel(const double *__restrict__ x, const double *__restrict__ y,
+                                                               RowFilter f, uint32_t n, ParetoWs w, SelectScratch *sc,
+                                                               uint32_t n_partials, SharedTopk topk, uint32_t chunk) {
+    __shared__ uint64_t s_lower[padded_size<kPerPass>()], s_tmp[kWaves], s_rng[2];
+    constexpr int KL = KT ? KT : 1;
+    constexpr uint32_t kPerSample = kSampleBlocks * kSampleFrontPer / kBlock;
+    static_assert(kSampleBlocks * kSampleFrontPer % kBlock == 0, "whole sample rows per thread");
+    const int lane = threadIdx.x % kWave;
+    TopList<KL> list;
+    uint32_t n_pass = 0;                                // rows of one lane: fewer than 2^32
+    if (KT) list.init();
+    // requested first, and in this order: the sample rows, then the first batch of rows, whose latency
+    // overlaps the set-up of the table
+    Pair sf[kPerSample];
+#pragma unroll
+    for (uint32_t j = 0; j < kPerSample; ++j) sf[j] = sc->sample_front[j * kBlock + threadIdx.x];
+    RawRow<MAXC> r[U];
+    ChunkWalk<U> cw(chunk, n, gridDim.x);
+    if (cw.live()) {
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u)
+            r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)cw.base + threadIdx.x + u * kBlock, (uint32_t)cw.end);
+    }
+    for (uint32_t i = threadIdx.x; i < padded_size<kPerPass>(); i += kBlock) s_lower[i] = kNone;
+    const Binning bin = sampled_binning(sc, n_partials, s_rng);     // its barrier also covers the table above
+#pragma unroll
+    for (uint32_t j = 0; j < kPerSample; ++j)
+        if (sf[j].idx != kNone)
+            atomicMin((unsigned long long *)&s_lower[padded<kPerPass>(bin(sf[j].idx))], (unsigned long long)sf[j].key);
+    __syncthreads();
+    scan_min_excl<kBlock>(s_lower, s_tmp);              // least y of the sample rows in strictly lower bins
+    // wave-uniform trip count: the ballots below need every lane
+    while (cw.live()) {
+        const uint32_t base = (uint32_t)cw.base;
+        // the next batch is requested before this one is worked on
+        RawRow<MAXC> rn[U];
+        cw.next();
+        const bool more = cw.live();
+        if (more) {
+#pragma unroll
+            for (uint32_t u = 0; u < U; ++u)
+                rn[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)cw.base + threadIdx.x + u * kBlock, (uint32_t)cw.end);
+        }
+        // Kept rows are rare and come in clusters: the wave counts them over the whole batch and appends them
+        // with one atomic (a wave that waits for one atomic per row slot waits several memory round trips).
+        uint32_t keep_bits = 0, total = 0, before[U];
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+            const Row q = row_of<true, MAXC>(r[u], f);
+            const bool keep = q.pass && key_of(q.y) < s_lower[padded<kPerPass>(bin(key_of(q.x)))];
+            const uint64_t mask = __ballot(keep);
+            before[u] = total + (uint32_t)__popcll(mask & ((1ull << lane) - 1));
+            total += (uint32_t)__popcll(mask);
+            keep_bits |= keep ? 1u << u : 0u;
+        }
+        if (total) {                                    // wave-uniform
+            uint32_t at = 0;
+            if (lane == 0) at = atomicAdd(&sc->counters[0], total);
+            at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+#pragma unroll
+            for (uint32_t u = 0; u < U; ++u) {
+                if ((keep_bits >> u) & 1u) {
+                    const Row q = row_of<true, MAXC>(r[u], f);
+                    const uint64_t kx = key_of(q.x), ky = key_of(q.y);
+                    const uint32_t b = bin(kx), slot = at + before[u];
+                    w.surv[slot] = base + threadIdx.x + u * kBlock;
+                    w.skx[slot] = kx;
+                    w.sky[slot] = ky;
+                    atomicAdd(&sc->bin_cnt[b], 1u);
+                    atomicMin((unsigned long long *)&sc->bin_min[b], (unsigned long long)ky);
+                }
+            }
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+            const uint32_t i = base + threadIdx.x + u * kBlock;
+            if (KT) {
+                const double obj = topk.obj_is_y ? r[u].y : r[u].x;
+                bool ok = r[u].valid && (!topk.use_feasible || r[u].fe != 0) && obj == obj;
+#pragma unroll
+                for (uint32_t c = 0; c < 2; ++c)
+                    if (c < topk.n_con) ok = ok && ((topk.con_is_y[c] ? r[u].y : r[u].x) <= topk.cap[c]);
+                if (ok) {
+                    ++n_pass;
+                    list.insert_ascending(Pair{key_of(obj), (uint64_t)i});
+                }
+            }
+        }
+        if (more) {
+#pragma unroll
+            for (uint32_t u = 0; u < U; ++u) r[u] = rn[u];
+        }
+    }
+    if (KT) {
+        __shared__ Pair s_pairs[kWaves][KL];
+        __shared__ uint64_t s_cnt[kWaves];
+        int my_rank = -1;
+        Pair my_pair = {kNone, kNone};
+        const uint32_t wave_pass = wave_sum(n_pass);
+        if (threadIdx.x % kWave == 0) s_cnt[threadIdx.x / kWave] = wave_pass;
+        block_topk<KL, kWaves>(list, s_pairs, [&](int rk, const Pair &p) {
+            my_rank = rk;
+            my_pair = p;
+        });                                             // (contains the barrier that publishes s_cnt)
+        if (my_rank >= 0) {
+            topk.w.key[(size_t)blockIdx.x * KL + my_rank] = my_pair.key;
+            topk.w.idx[(size_t)blockIdx.x * KL + my_rank] = my_pair.idx;
+        }
+        if (threadIdx.x == 0) {
+            uint64_t c = 0;
+            for (int wv = 0; wv < kWaves; ++wv) c += s_cnt[wv];
+            topk.w.cnt[blockIdx.x] = c;
+        }
+    }
+}
+
 // LDS of the finishing kernel.
+constexpr uint16_t kDeadBit = 0x8000;
+static_assert(kBins <= kDeadBit, "a bin number and the flag share 16 bits");
 struct FinishLds {
-    uint32_t off[padded_size<kPerFinish>()];    // first survivor slot per bin (exclusive scan of the bin counts)
-    uint32_t foff[padded_size<kPerFinish>()];   // front members per bin, then their exclusive scan
+    union {
+        struct {
+            uint32_t off[padded_size<kPerFinish>()];    // first survivor slot per bin (exclusive scan of the bin counts)
+            uint32_t foff[padded_size<kPerFinish>()];   // front members per bin, then their exclusive scan
+        };
+        // before the bins are counted: per bin, the least x among its survivors with the bin's least y
+        uint64_t rep[kBins];
+    };
     uint32_t cur[kBins];                        // fill level per bin while grouping; then the list of front members
     uint32_t tmp[kFinishThreads / kWave];
-    uint64_t kx[kStage], ky[kStage];            // staged survivor records, grouped by bin
+    uint64_t tmp64[kFinishThreads / kWave];
+    union {
+        struct {
+            uint64_t kx[kStage], ky[kStage];    // staged survivor records, grouped by bin
+        };
+        // before anything is staged: per bin, the least y among the survivors of strictly lower bins (padded table)
+        uint64_t lower[padded_size<kPerFinish>()];
+    };
     uint32_t row[kStage];
-    uint16_t bin[kStage];
+    uint16_t bin[kStage];                       // bin of the record; kDeadBit: a survivor of a lower bin dominates it
     uint8_t flag[kStage];
     uint32_t nfront, first, last, is_last;
     uint32_t part_base[kWave], part_lo[kWave], part_cnt[kWave];
     uint64_t rng[2];
 };
+
+// Fills L.lower from the global table of least y per bin (all NT = kFinishThreads threads; ends with a barrier).
+// Must run before records are staged (the table shares their LDS), and every read of it must be followed by a
+// barrier before the staging starts.
+__device__ inline void load_lower_table(FinishLds &L, const SelectScratch *sc) {
+    constexpr uint32_t P = kPerFinish;
+    uint64_t v[P];
+#pragma unroll
+    for (uint32_t j = 0; j < P; ++j) v[j] = sc->bin_min[threadIdx.x * P + j];
+    uint64_t run = prefix_min_before<kFinishThreads>(v, L.tmp64);
+#pragma unroll
+    for (uint32_t j = 0; j < P; ++j) {
+        L.lower[threadIdx.x * (P + 1) + j] = run;
+        run = min_u64(run, v[j]);
+    }
+    __syncthreads();
+}
 
 // The front among `cnt` survivor records staged in LDS, grouped by bin: record i of bin b sits at
 // L.off[b] - base + i.  L.foff must be zero and the staging complete (the function starts with a barrier).
@@ -806,9 +924,9 @@ __device__ inline uint32_t staged_front_by(FinishLds &L, uint32_t cnt, uint32_t 
     for (uint32_t q = t / group; q < cnt_pad; q += q_step) {
         const bool live = q < cnt;
         const uint64_t kx = live ? L.kx[q] : 0, ky = live ? L.ky[q] : 0;
-        const uint32_t b = live ? L.bin[q] : 0;
-        const uint32_t beg = live ? L.off[padded<P>(b)] - base : 0, end = live ? L.off[padded<P>(b + 1)] - base : 0;
-        bool dom = false;
+        const uint32_t bq = live ? L.bin[q] : 0, b = bq & (kDeadBit - 1);
+        bool dom = (bq & kDeadBit) != 0;            // then its own bin need not be searched
+        const uint32_t beg = live ? L.off[padded<P>(b)] - base : 0, end = live && !dom ? L.off[padded<P>(b + 1)] - base : beg;
         for (uint32_t j = beg + sub; j < end; j += 4 * group) {
             uint64_t jx[4], jy[4];
 #pragma unroll
@@ -838,7 +956,7 @@ __device__ inline uint32_t staged_front_by(FinishLds &L, uint32_t cnt, uint32_t 
         const bool live = qf < nf;
         const uint32_t q = live ? L.cur[qf] : 0;
         const uint64_t kx = live ? L.kx[q] : 0, ky = live ? L.ky[q] : 0;
-        const uint32_t b = live ? L.bin[q] : 0, i = live ? L.row[q] : 0;
+        const uint32_t b = live ? L.bin[q] & (kDeadBit - 1) : 0, i = live ? L.row[q] : 0;
         const uint32_t beg = live ? L.off[padded<P>(b)] - base : 0, end = live ? L.off[padded<P>(b + 1)] - base : 0;
         uint32_t rank = 0;                          // front members of the bin that come before this one
         for (uint32_t j = beg + sub; j < end; j += 4 * group) {
@@ -905,8 +1023,9 @@ __device__ inline uint32_t unstaged_front(FinishLds &L, const ParetoWs &w, const
         const bool live = k < cnt;
         const uint32_t g = g_lo + (live ? k : 0), q = w.grouped[g];
         const uint64_t kx = w.skx[q], ky = w.sky[q];
-        const uint32_t b = bin(kx), beg = L.off[padded<P>(b)], end = L.off[padded<P>(b + 1)];
-        bool dom = false;
+        const uint32_t b = bin(kx), beg = L.off[padded<P>(b)];
+        bool dom = w.dead[q] != 0;                      // then its own bin need not be searched
+        const uint32_t end = dom ? beg : L.off[padded<P>(b + 1)];
         for (uint32_t j = beg + sub; j < end; j += 2 * group) {
             const uint32_t j1 = j + group < end ? j + group : beg;       // past the end: the first member again
             const uint32_t q0 = w.grouped[j], q1 = w.grouped[j1];
@@ -981,6 +1100,22 @@ __device__ void pareto_large_front(FinishLds &L, const ParetoWs &w, SelectScratc
     }
     __syncthreads();
     const uint32_t b_lo = L.first, b_hi = L.last;       // this part's bins (non-empty ones in between are all its own)
+    // Which of the part's survivors a survivor of a lower bin dominates: one pass over all survivors with the
+    // table of the lower bins' least y in LDS, before anything is staged there.
+    load_lower_table(L, sc);
+    if (b_lo <= b_hi) {
+        for (uint32_t q0 = t; q0 < m; q0 += 4 * NT) {
+            uint64_t kx[4];
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) kx[u] = w.skx[q0 + u * NT < m ? q0 + u * NT : q0];
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) {
+                const uint32_t q = q0 + u * NT, b = bin(kx[u]);
+                if (q < m && b >= b_lo && b <= b_hi) w.dead[q] = w.sky[q] >= L.lower[padded<P>(b)] ? 1 : 0;
+            }
+        }
+    }
+    __syncthreads();
     uint32_t g_lo = 0, n_front = 0;
     if (b_lo <= b_hi) {
         g_lo = L.off[padded<P>(b_lo)];
@@ -1032,7 +1167,7 @@ __device__ void pareto_large_front(FinishLds &L, const ParetoWs &w, SelectScratc
                     L.kx[i] = kx;
                     L.ky[i] = w.sky[q];
                     L.row[i] = w.surv[q];
-                    L.bin[i] = (uint16_t)bin(kx);
+                    L.bin[i] = (uint16_t)(bin(kx) | (w.dead[q] ? kDeadBit : 0));
                 }
                 nf = staged_front(L, cnt, base, r_lo, r_hi, emit);
             } else if (cnt <= kStage) {
@@ -1048,7 +1183,7 @@ __device__ void pareto_large_front(FinishLds &L, const ParetoWs &w, SelectScratc
                             L.kx[pos] = kx[u];
                             L.ky[pos] = w.sky[q];
                             L.row[pos] = w.surv[q];
-                            L.bin[pos] = (uint16_t)b;
+                            L.bin[pos] = (uint16_t)(b | (w.dead[q] ? kDeadBit : 0));
                         }
                     }
                 }
@@ -1132,10 +1267,10 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
     if (threadIdx.x == 0) L.nfront = 0;
     // Everything the finishing block reads from global memory is requested at once, before the survivor
     // count is known: the first kStage survivor records (index clamped to the workspace's n rows; entries
-    // at or beyond the count are ignored later), the count, the bin counts and the sample partials.
+    // at or beyond the count are ignored later), the count and the sample partials.
     constexpr uint32_t kPer = kStage / kFinishThreads;
     uint64_t rx[kPer], ry[kPer];
-    uint32_t rr[kPer], cnt_in[kPerFinish];
+    uint32_t rr[kPer];
     if (!helper) {
 #pragma unroll
         for (uint32_t q = 0; q < kPer; ++q) {
@@ -1144,8 +1279,6 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
             ry[q] = w.sky[jc];
             rr[q] = w.surv[jc];
         }
-#pragma unroll
-        for (uint32_t q = 0; q < kPerFinish; ++q) cnt_in[q] = sc->bin_cnt[q * kFinishThreads + t];
     }
     const uint32_t m = sc->counters[0];
     const Binning bin = sampled_binning(sc, n_partials, L.rng);
@@ -1154,25 +1287,68 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
                            out_idx, capacity, out_count);
         return;
     }
-    // records staged in LDS, grouped by bin
+    // Survivors that are dominated for sure are dropped first (after the staircase and survivors kernels there
+    // are few; the filter pass leaves more): those with a survivor of a strictly lower bin at or below their y,
+    // and those that their own bin's representative dominates -- the survivor with the bin's least y (of those,
+    // the least x); rows often tie in x, and then the representative settles all of them but the ties in y.
+    // Tables: least y per bin in the LDS that the records are staged in afterwards, then its exclusive
+    // prefix-min; the representatives' x in the LDS of the bin counts.
+    for (uint32_t i = t; i < padded_size<P>(); i += kFinishThreads) L.lower[i] = kNone;
 #pragma unroll
     for (uint32_t q = 0; q < kPerFinish; ++q) {
         const uint32_t i = q * kFinishThreads + t;
-        L.off[padded<P>(i)] = cnt_in[q];
+        L.rep[i] = kNone;
         L.cur[i] = 0;
-        L.foff[padded<P>(i)] = 0;
     }
     __syncthreads();
-    scan_sum_excl<kFinishThreads, true>(L.off, L.tmp);
+    uint32_t rb[kPer];
+    bool live[kPer];
 #pragma unroll
     for (uint32_t q = 0; q < kPer; ++q) {
-        if (q * kFinishThreads + t < m) {
-            const uint32_t b = bin(rx[q]);
-            const uint32_t pos = L.off[padded<P>(b)] + atomicAdd(&L.cur[b], 1u);
-            L.kx[pos] = rx[q]; L.ky[pos] = ry[q]; L.row[pos] = rr[q]; L.bin[pos] = (uint16_t)b;
+        rb[q] = bin(rx[q]);
+        live[q] = q * kFinishThreads + t < m;
+        if (live[q]) atomicMin((unsigned long long *)&L.lower[padded<P>(rb[q])], (unsigned long long)ry[q]);
+    }
+    __syncthreads();
+    uint64_t bin_y[kPer];                               // least y of the record's own bin
+#pragma unroll
+    for (uint32_t q = 0; q < kPer; ++q) {
+        bin_y[q] = L.lower[padded<P>(rb[q])];
+        if (live[q] && ry[q] == bin_y[q]) atomicMin((unsigned long long *)&L.rep[rb[q]], (unsigned long long)rx[q]);
+    }
+    __syncthreads();
+    scan_min_excl<kFinishThreads>(L.lower, L.tmp64);
+    bool alive[kPer];
+#pragma unroll
+    for (uint32_t q = 0; q < kPer; ++q) {
+        const uint64_t rep_x = L.rep[rb[q]];
+        const bool by_rep = rep_x <= rx[q] && (rep_x < rx[q] || bin_y[q] < ry[q]);     // bin_y <= ry always
+        alive[q] = live[q] && ry[q] < L.lower[padded<P>(rb[q])] && !by_rep;
+    }
+    __syncthreads();                                    // both tables have been read by everyone
+#pragma unroll
+    for (uint32_t q = 0; q < kPerFinish; ++q) {
+        const uint32_t i = q * kFinishThreads + t;
+        L.off[padded<P>(i)] = 0;
+        L.foff[padded<P>(i)] = 0;
+    }
+    if (t == 0) L.off[padded<P>(kBins)] = 0;
+    __syncthreads();
+#pragma unroll
+    for (uint32_t q = 0; q < kPer; ++q)
+        if (alive[q]) atomicAdd(&L.off[padded<P>(rb[q])], 1u);
+    __syncthreads();                                    // records may be staged from here on
+    scan_sum_excl<kFinishThreads, true>(L.off, L.tmp);
+    const uint32_t m_alive = L.off[padded<P>(kBins)];
+    // records staged in LDS, grouped by bin
+#pragma unroll
+    for (uint32_t q = 0; q < kPer; ++q) {
+        if (alive[q]) {
+            const uint32_t pos = L.off[padded<P>(rb[q])] + atomicAdd(&L.cur[rb[q]], 1u);
+            L.kx[pos] = rx[q]; L.ky[pos] = ry[q]; L.row[pos] = rr[q]; L.bin[pos] = (uint16_t)rb[q];
         }
     }
-    const uint32_t n_front = staged_front(L, m, 0, 0, kBins - 1, [&](uint32_t pos, uint32_t row) {
+    const uint32_t n_front = staged_front(L, m_alive, 0, 0, kBins - 1, [&](uint32_t pos, uint32_t row) {
         if (pos < capacity) out_idx[pos] = row;
     });
     if (t == 0) out_count[0] = n_front;
@@ -1265,11 +1441,15 @@ static void launch_timed(Kernel kernel, dim3 grid, dim3 block, hipStream_t strea
     else hipLaunchKernelGGL(kernel, grid, block, 0, stream, args...);
 }
 
+// The passes after the row sample.  sample_fronts: the sample was taken by kSampleBlocks blocks that handed over the
+// fronts of their sample rows (the prepare kernel or its body as a rider): one filter pass and the finishing kernel.
+// Otherwise (the sample was taken inside another kernel's own loop): staircase, survivors, finish.
+// tm: two event pairs (filter, finish) or none; only used with sample_fronts.
 static hipError_t launch_pareto_passes(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
-                                       SelectScratch *sc, uint32_t n_partials, const MergeRider &rider,
+                                       SelectScratch *sc, uint32_t n_partials, bool sample_fronts, const MergeRider &rider,
                                        hipStream_t stream, const SharedTopk *shared = nullptr, int shared_k = 0,
                                        uint32_t row_chunk = 0, const LaunchTiming *tm = nullptr) {
-    const LaunchTiming *tm_stair = tm, *tm_surv = tm ? tm + 1 : nullptr, *tm_fin = tm ? tm + 2 : nullptr;
+    const LaunchTiming *tm_filter = tm, *tm_fin = tm ? tm + 1 : nullptr;
     const ParetoWs w = pareto_ws(ws, n);
     const RowFilter f = make_filter(spec);
     const uint32_t nb = pareto_blocks(n), n32 = (uint32_t)n;
@@ -1277,19 +1457,24 @@ static hipError_t launch_pareto_passes(const guide_select_spec &spec, uint64_t n
     const dim3 grid(nb), block(kBlock);
     with_row_chunk(row_chunk, [&](uint32_t chunk, auto u) {
         constexpr uint32_t U = decltype(u)::value;
-        if (shared) {       // only offered for a Pareto selection without constraint columns
+        if (sample_fronts && shared) {      // only offered for a Pareto selection without constraint columns
             const SharedTopk t = *shared;
-            if (shared_k == 1) launch_timed(pareto_stair_kernel<0, 1, U>, grid, block, stream, tm_stair, x, y, f, n32, sc, n_partials, t, chunk);
-            else if (shared_k == 2) launch_timed(pareto_stair_kernel<0, 2, U>, grid, block, stream, tm_stair, x, y, f, n32, sc, n_partials, t, chunk);
-            else if (shared_k == 3) launch_timed(pareto_stair_kernel<0, 3, U>, grid, block, stream, tm_stair, x, y, f, n32, sc, n_partials, t, chunk);
-            else launch_timed(pareto_stair_kernel<0, 4, U>, grid, block, stream, tm_stair, x, y, f, n32, sc, n_partials, t, chunk);
+            if (shared_k == 1) launch_timed(pareto_filter_kernel<0, 1, U>, grid, block, stream, tm_filter, x, y, f, n32, w, sc, n_partials, t, chunk);
+            else if (shared_k == 2) launch_timed(pareto_filter_kernel<0, 2, U>, grid, block, stream, tm_filter, x, y, f, n32, w, sc, n_partials, t, chunk);
+            else if (shared_k == 3) launch_timed(pareto_filter_kernel<0, 3, U>, grid, block, stream, tm_filter, x, y, f, n32, w, sc, n_partials, t, chunk);
+            else launch_timed(pareto_filter_kernel<0, 4, U>, grid, block, stream, tm_filter, x, y, f, n32, w, sc, n_partials, t, chunk);
+            return;
         }
         with_max_constraints(f.n_con, [&](auto maxc) {
             constexpr uint32_t MAXC = decltype(maxc)::value;
-            if (!shared)
-                launch_timed(pareto_stair_kernel<MAXC, 0, U>, grid, block, stream, tm_stair, x, y, f, n32, sc, n_partials,
+            if (sample_fronts) {
+                launch_timed(pareto_filter_kernel<MAXC, 0, U>, grid, block, stream, tm_filter, x, y, f, n32, w, sc, n_partials,
                              SharedTopk{}, chunk);
-            launch_timed(pareto_survivors_kernel<MAXC, U>, grid, block, stream, tm_surv, x, y, f, n32, w, sc, n_partials, chunk);
+            } else {
+                hipLaunchKernelGGL((pareto_stair_kernel<MAXC, U>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, chunk);
+                hipLaunchKernelGGL((pareto_survivors_kernel<MAXC, U>), grid, block, 0, stream, x, y, f, n32, w, sc, n_partials,
+                                   chunk);
+            }
         });
     });
     const uint32_t helpers = n > kStage ? kLargeParts - 1 : 0;     // no more than kStage rows: the staged path for sure
@@ -1307,7 +1492,7 @@ hipError_t launch_select_pareto(const guide_select_spec &spec, uint64_t n, const
     SelectScratch *sc = (SelectScratch *)scratch;
     hipLaunchKernelGGL(pareto_prepare_kernel, dim3(kSampleBlocks), dim3(kBlock), 0, stream, spec.objective,
                        spec.objective_y, make_filter(spec), (uint32_t)n, sc);
-    return launch_pareto_passes(spec, n, out, ws, sc, kSampleBlocks, MergeRider{}, stream);
+    return launch_pareto_passes(spec, n, out, ws, sc, kSampleBlocks, true, MergeRider{}, stream);
 }
 
 // True when the top-k selection reads only the Pareto selection's x, y and flag columns (and the Pareto
@@ -1360,8 +1545,8 @@ hipError_t launch_select_both(const guide_select_spec &topk, const guide_select_
                            topk_out.val, topk_out.count};       // partials: one per block of the kernel that kept the lists
     else
         launch_top1_merge(K, topk_ws, blocks_for(n), topk.k, topk_out, stream);
-    return launch_pareto_passes(pareto, n, pareto_out, pareto_ws_, sc, sampled ? sampled_partials : kSampleBlocks, rider,
-                                stream, folded ? &shared : nullptr, K, row_chunk, pass_timing);
+    return launch_pareto_passes(pareto, n, pareto_out, pareto_ws_, sc, sampled ? sampled_partials : kSampleBlocks, true,
+                                rider, stream, folded ? &shared : nullptr, K, row_chunk, pass_timing);
 }
 
 // The passes after the sample, for a caller whose own kernel has sampled the rows and reset the tables.
@@ -1375,7 +1560,9 @@ hipError_t launch_pareto_sampled(const guide_select_spec &spec, uint64_t n, cons
     if (merge_ws)
         rider = MergeRider{top1_ws(merge_ws), merge_blocks, merge_k, (uint32_t)kFusedTopK, merge_out->idx, merge_out->val,
                            merge_out->count};
-    return launch_pareto_passes(spec, n, out, ws, (SelectScratch *)scratch, n_partials, rider, stream, nullptr, 0, row_chunk);
+    // a sample taken by the evaluation kernel's extra blocks comes with the sample fronts; one taken in its loop does not
+    return launch_pareto_passes(spec, n, out, ws, (SelectScratch *)scratch, n_partials, merge_ws == nullptr, rider, stream,
+                                nullptr, 0, row_chunk);
 }
 
 size_t topk_partials_bytes() { return top1_ws_bytes(); }

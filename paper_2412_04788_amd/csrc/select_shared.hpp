@@ -15,6 +15,8 @@ constexpr uint32_t kSelBlocks = 1024;      // most blocks of a streaming pass (f
 // and no call depends on how the previous one ended.
 constexpr uint32_t kBins = 4096;
 constexpr uint32_t kMaxSamplePartials = 512;     // blocks of the kernel that samples rows (prepare or evaluation)
+constexpr uint32_t kSampleBlocks = 64;           // sampling blocks of kBlock rows each when the sample is taken by blocks of its own
+constexpr uint32_t kSampleFrontPer = 32;         // sample rows that one such block hands to the filter pass, at most
 struct SelectScratch {
     uint32_t counters[4];          // [0] survivors appended, [1] tickets drawn by the parts of a large front
     uint64_t sample_lo[kMaxSamplePartials];   // per sampling block: least x key of passing sample rows
@@ -22,7 +24,38 @@ struct SelectScratch {
     uint64_t bin_min[kBins];       // y keys per x bin whose exclusive prefix-min is that of the least y per bin
     uint32_t bin_cnt[kBins];       // survivors per bin
     uint32_t part_lo[64], part_cnt[64];   // large-front path only: per part, its first survivor slot and its front members
+    Pair sample_front[kSampleBlocks * kSampleFrontPer];   // (y key, x key) of sample rows that prune; unused slots kNone
 };
+
+// Sample number -> row for blocks that take a sample of their own: block rb's kBlock samples are spread over
+// the whole range (sample k = thread * n_blocks + rb), and a sample sits at a scrambled place inside its
+// stride, so that no period of the rows' layout lines up with the sample.
+__device__ inline uint32_t sample_number(uint32_t rb, uint32_t n_blocks) { return threadIdx.x * n_blocks + rb; }
+__device__ inline uint32_t sample_row(uint32_t k, uint32_t stride) {
+    return k * stride + ((k * 2654435761u) >> 8) % stride;
+}
+
+// The rows of a sampling block's sample that are worth handing to the filter pass of a Pareto selection: a
+// sample row prunes every row with a larger x (in a higher bin) and y not below its own, so a sample row with
+// another one at or below it in both x and y adds nothing.  Every thread of the block brings one sample row
+// (pass = false: none).  Each wave hands over the front of its rows from the right: the row with the least y
+// (of those, the least x), then the row with the least y among the rows left of it, and so on, at most
+// kSampleFrontPer / waves of them (the rows further left prune the least; any subset is valid).  The wave's
+// unused slots are filled with kNone.
+__device__ inline void store_sample_front(bool pass, uint64_t kx, uint64_t ky, Pair *slots) {
+    constexpr uint32_t kPerWave = kSampleFrontPer / (kBlock / kWave);
+    const uint32_t lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    uint64_t bound = kNone;                             // rows at or right of this x are done with
+    Pair mine = {kNone, kNone};
+    for (uint32_t it = 0; it < kPerWave; ++it) {        // wave-uniform trip count
+        const bool in = pass && kx < bound;
+        const Pair p = wave_min(in ? Pair{ky, kx} : Pair{kNone, kNone});
+        if (p.idx == kNone) break;                      // no row left (x keys of rows are below kNone)
+        if (lane == it) mine = p;
+        bound = p.idx;
+    }
+    if (lane < kPerWave) slots[wave * kPerWave + lane] = mine;
+}
 
 // Sorted list of the K least (key, row) pairs seen by one lane.
 template <int K>

@@ -299,18 +299,18 @@ def test_profile_aid_times_the_evaluation_kernel(torch_cuda):
     for _ in range(7):
         ctx.eval_grid(gg, 0, g.size, out=out)
     assert len(ctx.profile_read(4)) == 3
-    # a step with a top-k and a Pareto selection over stored columns: all four of its kernels are timed
-    ctx.profile_enable(10)
+    # a step with a top-k and a Pareto selection over stored columns: all three of its kernels are timed
+    ctx.profile_enable(8)
     tk = dict(objective="cost", k=3, constraints=[("t_prefill", 0.2)])
     pf = dict(x="t_prefill", y="cost", capacity=256)
     ref = None
-    for _ in range(3):                                    # the third finds two pairs: its evaluation kernel alone
+    for _ in range(3):                                    # the third finds two pairs: its evaluation kernel alone is timed
         rt, rp = _run(torch, ctx, gg, 0, g.size, out, topk=tk, pareto=pf)
         ref = ref or (rt, rp)
         np.testing.assert_array_equal(rt[0], ref[0][0])
         np.testing.assert_array_equal(rp[0], ref[1][0])
-    ms = ctx.profile_read(10)
-    assert len(ms) == 9 and np.all(ms > 0.003) and np.all(ms < 5.0)
+    ms = ctx.profile_read(8)
+    assert len(ms) == 7 and np.all(ms > 0.003) and np.all(ms < 5.0)
     ctx.profile_enable(0)
     rt, rp = _run(torch, ctx, gg, 0, g.size, out, topk=tk, pareto=pf)       # untimed: the same selections
     np.testing.assert_array_equal(rt[0], ref[0][0])
