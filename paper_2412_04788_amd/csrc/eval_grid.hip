@@ -145,7 +145,7 @@ __global__ __launch_bounds__(kBlock) void tile_tables_kernel(GridDesc g, const D
 // sampled rows are evaluated here from scratch rather than read back, so the sample does not wait for the columns.
 // It fixes the range of x that the selection's bins slice (any range is correct, a good one is fast), and the
 // block hands the front of its sample rows to the selection's filter pass (store_sample_front).
-// Also puts the tables that the selection's kernels accumulate into in their neutral state.
+// Also resets the counters that the selection's kernels accumulate into.
 constexpr uint64_t kSampleMargin = 1ull << 26;      // in key units: 2^-26 relative for a normal number
 template <bool ADDITIVE>
 __device__ inline void sample_rider(const GridLds &s, const GridDesc &g, uint32_t rb, uint32_t n_rider_blocks, uint32_t first,
@@ -156,10 +156,6 @@ __device__ inline void sample_rider(const GridLds &s, const GridDesc &g, uint32_
     SelectScratch *sc = (SelectScratch *)fs.scratch;
     const uint32_t gid = rb * kBlock + threadIdx.x;
     const uint32_t n_samples = n_rider_blocks * kBlock;
-    for (uint32_t i = gid; i < kBins; i += n_samples) {
-        sc->bin_min[i] = kNone;
-        sc->bin_cnt[i] = 0;
-    }
     if (gid == 0) sc->counters[0] = sc->counters[1] = 0;
     const uint32_t stride = count > n_samples ? count / n_samples : 1;
     const uint32_t k = sample_number(rb, n_rider_blocks);
@@ -264,7 +260,6 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
             SelectScratch *sc = (SelectScratch *)fs.scratch;
             for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < kBins; i += gridDim.x * kBlock) {
                 sc->bin_min[i] = kNone;
-                sc->bin_cnt[i] = 0;
             }
             if (blockIdx.x == 0 && threadIdx.x == 0) sc->counters[0] = sc->counters[1] = 0;
         }

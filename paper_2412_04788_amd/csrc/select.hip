@@ -439,12 +439,7 @@ __device__ void pareto_prepare_body(uint32_t block, const double *__restrict__ x
     __shared__ Pair s_best[kWaves];
     const uint32_t gid = block * kBlock + threadIdx.x;
     const uint32_t n_samples = kSampleBlocks * kBlock;
-    static_assert(kSampleBlocks * kBlock >= kBins, "one table entry per thread");
-    if (gid < kBins) {                                              // neutral state for the kernels that follow
-        sc->bin_min[gid] = kNone;
-        sc->bin_cnt[gid] = 0;
-    }
-    if (gid == 0) sc->counters[0] = sc->counters[1] = 0;
+    if (gid == 0) sc->counters[0] = sc->counters[1] = 0;         // neutral state for the kernels that follow
     const uint32_t stride = n > n_samples ? n / n_samples : 1;
     const uint32_t k = sample_number(block, kSampleBlocks);
     const Row r = load_row<true, GUIDE_MAX_CONSTRAINTS>(x, y, f, (uint64_t)k * stride < n ? sample_row(k, stride) : n, n);
@@ -722,7 +717,6 @@ __global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *
                     w.surv[at] = i;
                     w.skx[at] = kx;
                     w.sky[at] = ky;
-                    atomicAdd(&sc->bin_cnt[b], 1u);
                 }
             }
         }
@@ -806,12 +800,10 @@ __global__ __launch_bounds__(kBlock) void pareto_filter_kernel(const double *__r
                 if ((keep_bits >> u) & 1u) {
                     const Row q = row_of<true, MAXC>(r[u], f);
                     const uint64_t kx = key_of(q.x), ky = key_of(q.y);
-                    const uint32_t b = bin(kx), slot = at + before[u];
+                    const uint32_t slot = at + before[u];
                     w.surv[slot] = base + threadIdx.x + u * kBlock;
                     w.skx[slot] = kx;
                     w.sky[slot] = ky;
-                    atomicAdd(&sc->bin_cnt[b], 1u);
-                    atomicMin((unsigned long long *)&sc->bin_min[b], (unsigned long long)ky);
                 }
             }
         }
@@ -887,23 +879,6 @@ struct FinishLds {
     uint32_t part_base[kWave], part_lo[kWave], part_cnt[kWave];
     uint64_t rng[2];
 };
-
-// Fills L.lower from the global table of least y per bin (all NT = kFinishThreads threads; ends with a barrier).
-// Must run before records are staged (the table shares their LDS), and every read of it must be followed by a
-// barrier before the staging starts.
-__device__ inline void load_lower_table(FinishLds &L, const SelectScratch *sc) {
-    constexpr uint32_t P = kPerFinish;
-    uint64_t v[P];
-#pragma unroll
-    for (uint32_t j = 0; j < P; ++j) v[j] = sc->bin_min[threadIdx.x * P + j];
-    uint64_t run = prefix_min_before<kFinishThreads>(v, L.tmp64);
-#pragma unroll
-    for (uint32_t j = 0; j < P; ++j) {
-        L.lower[threadIdx.x * (P + 1) + j] = run;
-        run = min_u64(run, v[j]);
-    }
-    __syncthreads();
-}
 
 // The front among `cnt` survivor records staged in LDS, grouped by bin: record i of bin b sits at
 // L.off[b] - base + i.  L.foff must be zero and the staging complete (the function starts with a barrier).
@@ -1077,19 +1052,41 @@ __device__ void pareto_large_front(FinishLds &L, const ParetoWs &w, SelectScratc
                                    uint64_t *out_count) {
     constexpr uint32_t P = kPerFinish, NT = kFinishThreads;
     const uint32_t t = threadIdx.x;
+    // One pass over all survivors: survivors per bin and the least y per bin, both in LDS (the latter where
+    // records are staged afterwards).  Four records are requested at a time.
 #pragma unroll
     for (uint32_t q = 0; q < P; ++q) {
         const uint32_t i = q * NT + t;
-        L.off[padded<P>(i)] = sc->bin_cnt[i];
+        L.off[padded<P>(i)] = 0;
         L.foff[padded<P>(i)] = 0;
         L.cur[i] = 0;
     }
+    for (uint32_t i = t; i < padded_size<P>(); i += NT) L.lower[i] = kNone;
     if (t == 0) {
         L.first = kBins;
         L.last = 0;
     }
     __syncthreads();
+    for (uint32_t q0 = t; q0 < m; q0 += 4 * NT) {
+        uint64_t kx[4], ky[4];
+#pragma unroll
+        for (uint32_t u = 0; u < 4; ++u) {
+            const uint32_t q = q0 + u * NT < m ? q0 + u * NT : q0;
+            kx[u] = w.skx[q];
+            ky[u] = w.sky[q];
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < 4; ++u) {
+            if (q0 + u * NT < m) {
+                const uint32_t b = padded<P>(bin(kx[u]));
+                atomicAdd(&L.off[b], 1u);
+                atomicMin((unsigned long long *)&L.lower[b], (unsigned long long)ky[u]);
+            }
+        }
+    }
+    __syncthreads();
     scan_sum_excl<NT, true>(L.off, L.tmp);              // entry kBins = m
+    scan_min_excl<NT>(L.lower, L.tmp64);                // least y among the survivors of strictly lower bins
 #pragma unroll
     for (uint32_t q = 0; q < P; ++q) {
         const uint32_t i = q * NT + t, off = L.off[padded<P>(i)];
@@ -1100,9 +1097,8 @@ __device__ void pareto_large_front(FinishLds &L, const ParetoWs &w, SelectScratc
     }
     __syncthreads();
     const uint32_t b_lo = L.first, b_hi = L.last;       // this part's bins (non-empty ones in between are all its own)
-    // Which of the part's survivors a survivor of a lower bin dominates: one pass over all survivors with the
-    // table of the lower bins' least y in LDS, before anything is staged there.
-    load_lower_table(L, sc);
+    // Which of the part's survivors a survivor of a lower bin dominates: a second pass, before anything is
+    // staged over the table.
     if (b_lo <= b_hi) {
         for (uint32_t q0 = t; q0 < m; q0 += 4 * NT) {
             uint64_t kx[4];
