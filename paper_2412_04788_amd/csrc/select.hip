@@ -1277,7 +1277,15 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
         }
     }
     const uint32_t m = sc->counters[0];
-    const Binning bin = sampled_binning(sc, n_partials, L.rng);
+    // the tables of the staged path are put into their neutral state while the loads are under way
+    for (uint32_t i = t; i < padded_size<P>(); i += kFinishThreads) L.lower[i] = kNone;
+#pragma unroll
+    for (uint32_t q = 0; q < kPerFinish; ++q) {
+        const uint32_t i = q * kFinishThreads + t;
+        L.rep[i] = kNone;
+        L.cur[i] = 0;
+    }
+    const Binning bin = sampled_binning(sc, n_partials, L.rng);     // its barrier also covers the tables above
     if (m > kStage) {
         pareto_large_front(L, w, sc, bin, m, helper ? blockIdx.x - first_helper + 1 : 0, gridDim.x - first_helper + 1,
                            out_idx, capacity, out_count);
@@ -1289,14 +1297,6 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
     // the least x); rows often tie in x, and then the representative settles all of them but the ties in y.
     // Tables: least y per bin in the LDS that the records are staged in afterwards, then its exclusive
     // prefix-min; the representatives' x in the LDS of the bin counts.
-    for (uint32_t i = t; i < padded_size<P>(); i += kFinishThreads) L.lower[i] = kNone;
-#pragma unroll
-    for (uint32_t q = 0; q < kPerFinish; ++q) {
-        const uint32_t i = q * kFinishThreads + t;
-        L.rep[i] = kNone;
-        L.cur[i] = 0;
-    }
-    __syncthreads();
     uint32_t rb[kPer];
     bool live[kPer];
 #pragma unroll

@@ -195,6 +195,27 @@ def test_feasibility_exactly_at_the_capacity_boundary(ora, torch_cuda, model):
                 assert (fe[idx], bm[idx]) == expect[h], (p, wb, blk, side, fe[idx], bm[idx])
                 hit += 1
     assert hit == 2 * 2 * len(cases)
+    # Evaluate-and-select over the same grid: every row is one of the selection's sample rows, half of them
+    # sit exactly on the boundary and half one byte beyond it, and a sample row may only prune other rows when
+    # it is a passing row itself -- the front and the cheapest rows must be those of the feasible rows.
+    from paper_2412_04788_amd import guide
+    ti = torch.empty(3, dtype=torch.int64, device="cuda"); tv = torch.empty(3, dtype=torch.float64, device="cuda")
+    tc = torch.empty(1, dtype=torch.int64, device="cuda")
+    pi = torch.empty(g.size, dtype=torch.int64, device="cuda"); pc = torch.empty(1, dtype=torch.int64, device="cuda")
+    sels = [ctx.column_select(guide.SELECT_TOPK, "cost", ti, tv, tc, k=3),
+            ctx.column_select(guide.SELECT_PARETO, "t_prefill", pi, None, pc, objective_y="cost", capacity=g.size)]
+    ws = torch.empty(max(ctx.eval_select_workspace_bytes(sels, g.size), 1), dtype=torch.uint8, device="cuda")
+    ctx.eval_select(bridge.gpu_grid(g), 0, g.size, out, sels, ws)
+    torch.cuda.synchronize()
+    x, y = bridge.to_np(out["t_prefill"]), bridge.to_np(out["cost"])
+    np.testing.assert_array_equal(bridge.to_np(out["feasible"]), exp["feasible"])
+    front = ora.pareto_sweep(x, y, exp["feasible"])
+    m = int(bridge.to_np(pc, np.uint64)[0])
+    assert m == len(front)
+    np.testing.assert_array_equal(bridge.to_np(pi, np.uint64)[:m], front)
+    ei, ev, ec = ora.select_topk(y, exp["feasible"], [], k=3)
+    np.testing.assert_array_equal(bridge.to_np(ti, np.uint64), ei[0])
+    assert int(bridge.to_np(tc, np.uint64)[0]) == int(ec[0]) == int(exp["feasible"].sum())
     # the one-index-per-lane kernel (no tile shape for five token budgets) takes the same decisions
     g5 = wl.make_grid([model], hws, wl.Axis.table([b]), wl.Axis.table([s_in]), wl.Axis.table([s_out]),
                       wl.Axis.table([1, 2, 8]), wl.Axis.table([16, 8, 4]), wl.Axis.table([16, 32]),

@@ -232,10 +232,20 @@ def test_pareto_large_front_and_repeated_calls(ora, torch_cuda):
         np.testing.assert_array_equal(got, ora.pareto_brute(xs, ys))
 
 
+def _sample_rows(n):
+    """The rows that the Pareto kernels sample out of n (16 384 strides, one row at a scrambled place in each)."""
+    ns = 16384
+    stride = n // ns if n > ns else 1
+    k = np.arange(min(ns, n), dtype=np.uint64)
+    jitter = (((k * np.uint64(2654435761)) & np.uint64(0xFFFFFFFF)) >> np.uint64(8)) % np.uint64(stride)
+    return (k * np.uint64(stride) + jitter).astype(np.int64)
+
+
 def test_pareto_large_front_ties_and_one_crowded_bin(ora, torch_cuda):
     """Large fronts that the finishing blocks share out by bin: (a) rows in identical triples, all on the front
-    (order among equal points is by row); (b) a staircase of 20000 rows that lies beyond the sampled range, so
-    that one bin, and with it one block, holds more survivors than fit its LDS staging."""
+    (order among equal points is by row); (b) a staircase of about 20000 rows that lies beyond the sampled range,
+    so that one bin, and with it one block, holds more survivors than fit its LDS staging; (c) a flag column that
+    fails every sample row."""
     torch = torch_cuda
     ctx = bridge.gpu_context(wl.grid_tiny())
     n = 30000
@@ -247,16 +257,28 @@ def test_pareto_large_front_ties_and_one_crowded_bin(ora, torch_cuda):
     exp = ora.pareto_sweep(x, y, None)
     assert m == n == len(exp)
     np.testing.assert_array_equal(got, exp)
-    n = 40000                                             # the kernels sample the even rows here
+    n = 40000
     x = rng.random(n) * 100.0
     y = rng.random(n) * 100.0
-    odd = np.arange(1, n, 2)
+    odd = np.setdiff1d(np.arange(n), _sample_rows(n))     # the staircase: the rows that the kernels do not sample
+    assert 15000 < len(odd) < 25000
     x[odd] = 1000.0 + odd
     y[odd] = -1.0 * odd
-    x[odd[::7]] = x[odd[::7] - 2 * (odd[::7] > 1)]        # some equal x in the staircase: only the lower y stays
+    x[odd[7::7]] = x[odd[6::7][:len(odd[7::7])]]          # some equal x in the staircase: only the lower y stays
     got, m = _pareto(torch, ctx, _dev(torch, x), _dev(torch, y))
     exp = ora.pareto_sweep(x, y, None)
     assert m == len(exp) > 15000
+    np.testing.assert_array_equal(got, exp)
+    # no sample row passes the filter: nothing is pruned before the finishing blocks, which then drop what a
+    # kept row of a lower bin dominates
+    n = 300000
+    x = np.round(rng.random(n) * 1000.0, 1)
+    y = np.round(rng.random(n) * 1000.0, 1)
+    fe = np.ones(n, np.uint8)
+    fe[_sample_rows(n)] = 0
+    got, m = _pareto(torch, ctx, _dev(torch, x), _dev(torch, y), _dev(torch, fe))
+    exp = ora.pareto_sweep(x, y, fe)
+    assert m == len(exp) > 3
     np.testing.assert_array_equal(got, exp)
     # and a small front straight after, on the same context
     xs = rng.integers(0, 50, 3000).astype(np.float64); ys = rng.integers(0, 50, 3000).astype(np.float64)
