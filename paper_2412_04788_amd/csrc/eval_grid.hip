@@ -223,8 +223,8 @@ __device__ inline void sample_rider(const GridLds &s, const GridDesc &g, uint32_
 template <bool ADDITIVE, int NB, int NM, bool FUSED>
 __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const DevTables *__restrict__ tab,
                                                            uint32_t first, uint32_t count, double re_c, double re_b,
-                                                           guide_metrics out, FusedSelect fs, Div32 stride_div,
-                                                           uint32_t n_samples, const TileLds *__restrict__ derived) {
+                                                           guide_metrics out, FusedSelect fs,
+                                                           const TileLds *__restrict__ derived) {
     constexpr int TS = NB * NM;
     constexpr int kWaves = kBlock / kWave;
     __shared__ TileLds s;
@@ -251,26 +251,16 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
         }
     }
     TopList<kFusedTopK> top;
-    uint64_t n_pass = 0, smp_lo = kNone, top_bound = kNone;
+    uint64_t n_pass = 0, top_bound = kNone;
     uint32_t batch = 0;
-    Pair smp_best = {kNone, kNone};
-    if (FUSED) {
-        top.init();
-        if (fs.pareto) {                                         // neutral state for the Pareto kernels that follow
-            SelectScratch *sc = (SelectScratch *)fs.scratch;
-            for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < kBins; i += gridDim.x * kBlock) {
-                sc->bin_min[i] = kNone;
-            }
-            if (blockIdx.x == 0 && threadIdx.x == 0) sc->counters[0] = sc->counters[1] = 0;
-        }
-    }
+    if (FUSED) top.init();
     __syncthreads();
-    if (!FUSED && fs.rider_blocks && blockIdx.x >= gridDim.x - fs.rider_blocks) {      // block-uniform
+    if (fs.rider_blocks && blockIdx.x >= gridDim.x - fs.rider_blocks) {                // block-uniform
         sample_rider<ADDITIVE>(s.g, g, blockIdx.x - (gridDim.x - fs.rider_blocks), fs.rider_blocks, first, count, re_c,
                                re_b, fs);
         return;
     }
-    const uint32_t n_main_blocks = gridDim.x - (FUSED ? 0u : fs.rider_blocks);
+    const uint32_t n_main_blocks = gridDim.x - fs.rider_blocks;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     double *xw = s_x[wave];
     const uint32_t t_first = first / TS;
@@ -328,8 +318,7 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
         // memory check: depends on the block size only
         MemResult mem[NB];
         const bool need_mem = out.b_max || out.feasible ||
-                              (FUSED && ((fs.topk && fs.topk_filter.use_feasible) ||
-                                         (fs.pareto && fs.pareto_filter.use_feasible)));
+                              (FUSED && fs.topk && fs.topk_filter.use_feasible);
         if (need_mem) {
             const double c_avail = hw.cap - cf.w_gpu;
             const uint32_t tok = kn.s_in + kn.s_out;
@@ -450,35 +439,13 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
                 if (batch < 4 || (batch & 3) == 0) top_bound = wave_min(top.v[kFusedTopK - 1].key);
                 ++batch;
             }
-            if (fs.pareto) {
-                // sample rows are the multiples of the stride (relative to `first`): visit those inside the tile
-                const uint32_t stride = stride_div.d;
-                const uint32_t lo_row = row0 > first ? row0 : first;              // first candidate row of the tile
-                const uint32_t hi_row = row0 + TS < last ? row0 + TS : last;      // exclusive
-                if (tile_real && lo_row < hi_row) {
-                    uint32_t q = div32(lo_row - first + stride - 1, stride_div);  // first multiple at or after lo_row
-                    for (uint32_t i = q * stride; i < hi_row - first && q < n_samples; i += stride, ++q) {
-                        const int j = (int)(i + first - row0), k = j / NM, m = j % NM;
-                        const double x = col(fs.pareto_x, m), y = col(fs.pareto_y, m);
-                        bool feas = true;
-#pragma unroll
-                        for (int kk = 0; kk < NB; ++kk) feas = kk == k ? mem[kk].feasible : feas;
-                        if (x == x && y == y && passes(fs.pareto_filter, m) && (!fs.pareto_filter.use_feasible || feas)) {
-                            const uint64_t kx = key_of(x);
-                            smp_lo = min_u64(smp_lo, kx);
-                            smp_best = pair_min(smp_best, Pair{key_of(y), kx});
-                        }
-                    }
-                }
-            }
         }
     }
     if (FUSED) {
         constexpr int kCap = 8;
         __shared__ Pair s_pairs[kWaves][kFusedTopK], s_cand[kWaves][kCap];
         __shared__ uint32_t s_n[kWaves];
-        __shared__ uint64_t s_cnt[kWaves], s_lo[kWaves];
-        __shared__ Pair s_best[kWaves];
+        __shared__ uint64_t s_cnt[kWaves];
         if (fs.topk) {
             const Top1Ws w = top1_ws(fs.topk_ws);
             for (int off = kWave / 2; off > 0; off >>= 1) n_pass += __shfl_xor(n_pass, off, kWave);
@@ -492,24 +459,6 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
                 uint64_t c = 0;
                 for (int wv = 0; wv < kWaves; ++wv) c += s_cnt[wv];
                 w.cnt[blockIdx.x] = c;
-            }
-        }
-        if (fs.pareto) {
-            SelectScratch *sc = (SelectScratch *)fs.scratch;
-            smp_lo = wave_min(smp_lo);
-            smp_best = wave_min(smp_best);
-            if (lane == 0) {
-                s_lo[wave] = smp_lo;
-                s_best[wave] = smp_best;
-            }
-            __syncthreads();
-            if (threadIdx.x == 0) {
-                for (int wv = 1; wv < kWaves; ++wv) {
-                    smp_lo = min_u64(smp_lo, s_lo[wv]);
-                    smp_best = pair_min(smp_best, s_best[wv]);
-                }
-                sc->sample_lo[blockIdx.x] = smp_lo;
-                sc->sample_best[blockIdx.x] = smp_best;
             }
         }
     }
@@ -742,14 +691,14 @@ static uint32_t tile_blocks(uint32_t first, uint32_t count, uint32_t ts) {
     const uint32_t n_tiles = (first + count - 1) / ts - first / ts + 1;
     // two persistent blocks per compute unit: every wave loops over several batches of 64 tiles, so the
     // stores of one batch overlap the arithmetic of the next (measured best among 1..8 blocks per CU)
-    // (every block writes one top-k partial and one sample partial when selections are folded in)
+    // (every block writes one top-k partial when a top-k is folded in)
     uint32_t cap = 2 * device_cus();
-    cap = cap < kMaxSamplePartials ? cap : kMaxSamplePartials;
+    cap = cap < kSelBlocks ? cap : kSelBlocks;
     const uint32_t need = (n_tiles + kBlock - 1) / kBlock;
     return need < cap ? need : cap;
 }
 
-// Sampling of rows for the Pareto bin range: row i is a sample when i = q * stride with q < kSampleRows.
+// Rows sampled for a Pareto selection over the evaluated rows.
 constexpr uint32_t kSampleRows = 16384;
 constexpr uint32_t kRiderBlocks = kSampleRows / kBlock;     // sample blocks appended to a plain evaluation
 static_assert(kRiderBlocks == kSampleBlocks, "the scratch holds one sample front per sample block");
@@ -758,30 +707,21 @@ template <bool ADDITIVE, int NB, int NM>
 static void launch_tile(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
                         uint32_t count, double re_c, double re_b, const guide_metrics &out, const FusedSelect *fs,
                         hipStream_t stream, LaunchTiming tm) {
-    const bool rider = fs && fs->rider_blocks;          // a plain evaluation with sample blocks appended
-    const dim3 grid(tile_blocks(first, count, NB * NM) + (rider ? fs->rider_blocks : 0u)), block(kBlock);
-    static_assert(kMaxSamplePartials <= kSelBlocks, "one partial per block");
-    // with timing events the launch goes through the extended call, which attaches them to the dispatch
-    const uint32_t stride = count > kSampleRows ? count / kSampleRows : 1;
+    // fs: a top-k folded into the evaluation (the FUSED kernel) and / or rider_blocks extra blocks that take the
+    // row sample of a Pareto selection
+    const FusedSelect sel = fs ? *fs : FusedSelect{};
+    const dim3 grid(tile_blocks(first, count, NB * NM) + sel.rider_blocks), block(kBlock);
     const TileLds *tables = (const TileLds *)tile_tables;
-    if (rider && tm.start)
-        hipExtLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM, false>), grid, block, 0, stream, tm.start, tm.stop, 0, g,
-                              tab, first, count, re_c, re_b, out, *fs, Div32{}, 0u, tables);
-    else if (rider)
-        hipLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM, false>), grid, block, 0, stream, g, tab, first, count, re_c,
-                           re_b, out, *fs, Div32{}, 0u, tables);
-    else if (fs && tm.start)
-        hipExtLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM, true>), grid, block, 0, stream, tm.start, tm.stop, 0, g, tab,
-                              first, count, re_c, re_b, out, *fs, make_div32(stride), kSampleRows, tables);
-    else if (fs)
-        hipLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM, true>), grid, block, 0, stream, g, tab, first, count, re_c,
-                           re_b, out, *fs, make_div32(stride), kSampleRows, tables);
-    else if (tm.start)
-        hipExtLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM, false>), grid, block, 0, stream, tm.start, tm.stop, 0, g,
-                              tab, first, count, re_c, re_b, out, FusedSelect{}, Div32{}, 0u, tables);
-    else
-        hipLaunchKernelGGL((eval_tile_kernel<ADDITIVE, NB, NM, false>), grid, block, 0, stream, g, tab, first, count, re_c,
-                           re_b, out, FusedSelect{}, Div32{}, 0u, tables);
+    auto launch = [&](auto kernel) {
+        // with timing events the launch goes through the extended call, which attaches them to the dispatch
+        if (tm.start)
+            hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, tm.start, tm.stop, 0, g, tab, first, count, re_c, re_b, out,
+                                  sel, tables);
+        else
+            hipLaunchKernelGGL(kernel, grid, block, 0, stream, g, tab, first, count, re_c, re_b, out, sel, tables);
+    };
+    if (sel.topk) launch(eval_tile_kernel<ADDITIVE, NB, NM, true>);
+    else launch(eval_tile_kernel<ADDITIVE, NB, NM, false>);
 }
 
 // Tile shapes with a compiled kernel (up to four values on each of the two fastest axes); other grids take the
@@ -830,26 +770,28 @@ hipError_t launch_eval_grid_fused(const GridDesc &g, const DevTables *tab, const
                                   uint32_t count, double e_c, double e_b, bool additive, const guide_metrics &out,
                                   const FusedSelect &fs, hipStream_t stream, uint32_t *n_blocks, LaunchTiming tm) {
     const double re_c = 1.0 / e_c, re_b = 1.0 / e_b;
+    FusedSelect sel = fs;
+    sel.rider_blocks = fs.pareto ? kRiderBlocks : 0u;
     const bool done =
-        additive ? dispatch_tile<true>(g, tab, tile_tables, first, count, re_c, re_b, out, &fs, stream, n_blocks, tm)
-                 : dispatch_tile<false>(g, tab, tile_tables, first, count, re_c, re_b, out, &fs, stream, n_blocks, tm);
+        additive ? dispatch_tile<true>(g, tab, tile_tables, first, count, re_c, re_b, out, &sel, stream, n_blocks, tm)
+                 : dispatch_tile<false>(g, tab, tile_tables, first, count, re_c, re_b, out, &sel, stream, n_blocks, tm);
     return done ? hipGetLastError() : hipErrorNotSupported;
 }
 
 hipError_t launch_eval_grid(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
                             uint32_t count, double e_c, double e_b, bool additive, const guide_metrics &out,
-                            hipStream_t stream, LaunchTiming tm, const FusedSelect *sample, uint32_t *sample_partials) {
+                            hipStream_t stream, LaunchTiming tm, const FusedSelect *sample, bool *sampled) {
     const dim3 grid(blocks_for(count)), block(kBlock);
     const double re_c = 1.0 / e_c, re_b = 1.0 / e_b;
     FusedSelect rider;
     const FusedSelect *fs = nullptr;
-    if (sample_partials) *sample_partials = 0;
-    if (sample && sample_partials && eval_grid_can_fuse(g)) {
+    if (sampled) *sampled = false;
+    if (sample && sampled && eval_grid_can_fuse(g)) {
         rider = *sample;
         rider.topk = 0;
         rider.rider_blocks = kRiderBlocks;
         fs = &rider;
-        *sample_partials = kRiderBlocks;
+        *sampled = true;
     }
     if (additive ? dispatch_tile<true>(g, tab, tile_tables, first, count, re_c, re_b, out, fs, stream, nullptr, tm)
                  : dispatch_tile<false>(g, tab, tile_tables, first, count, re_c, re_b, out, fs, stream, nullptr, tm))

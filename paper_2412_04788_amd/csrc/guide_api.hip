@@ -515,7 +515,8 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return fail(ctx, GUIDE_E_DEVICE, "cannot select device %d", ctx->device);
     if (int rc_order = order_after_previous(ctx, stream)) return rc_order;
-    uint32_t n_blocks = 0, sampled_partials = 0;
+    uint32_t n_blocks = 0;
+    bool sampled = false;                               // the evaluation kernel's extra blocks took the Pareto row sample
     bool eval_timed = false;
     // rows [0, count) of the columns are rows [first, first + count) of the grid: the chunks line up when first does
     const uint32_t chunk_of_eval = eval_grid_row_chunk(desc);
@@ -559,7 +560,7 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
             fs.pareto_filter = filter_of(*pareto);
             fs.scratch = ctx->select_scratch;
             e = launch_eval_grid(desc, ctx->dev_tab, ctx->dev_tile, (uint32_t)first, (uint32_t)count, e_c, e_b, additive,
-                                 *out, stream, timing, &fs, &sampled_partials);
+                                 *out, stream, timing, &fs, &sampled);
         } else {
             e = launch_eval_grid(desc, ctx->dev_tab, ctx->dev_tile, (uint32_t)first, (uint32_t)count, e_c, e_b, additive,
                                  *out, stream, timing);
@@ -573,7 +574,7 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
         LaunchTiming passes[2];
         const bool timed = eval_timed && pass_timing(ctx, passes);
         e = launch_select_both(spec_of(*topk, *out), topk->out, ws_of[topk - sel], spec_of(*pareto, *out), pareto->out,
-                               ws_of[pareto - sel], count, ctx->select_scratch, stream, sampled_partials, row_chunk,
+                               ws_of[pareto - sel], count, ctx->select_scratch, stream, sampled, row_chunk,
                                timed ? passes : nullptr);
     } else {
         for (uint32_t i = 0; i < n_sel && e == hipSuccess; ++i) {
@@ -586,10 +587,10 @@ int guide_eval_select(guide_ctx *ctx, const guide_grid *grid, uint64_t first, ui
                     e = launch_topk_merge(ws_of[i], n_blocks, c.k, c.out, stream);
                 // else: merged beside the Pareto front's finishing kernel, below
             } else if (fold) {
-                e = launch_pareto_sampled(spec, count, c.out, ws_of[i], ctx->select_scratch, n_blocks, ws_of[topk - sel],
+                e = launch_pareto_sampled(spec, count, c.out, ws_of[i], ctx->select_scratch, ws_of[topk - sel],
                                           n_blocks, topk->k, &topk->out, stream);
-            } else if (sampled_partials && count > 0) {
-                e = launch_pareto_sampled(spec, count, c.out, ws_of[i], ctx->select_scratch, sampled_partials, nullptr, 0,
+            } else if (sampled && count > 0) {
+                e = launch_pareto_sampled(spec, count, c.out, ws_of[i], ctx->select_scratch, nullptr, 0,
                                           0, nullptr, stream, row_chunk);
             } else {
                 e = launch_select_pareto(spec, count, c.out, ws_of[i], ctx->select_scratch, stream);

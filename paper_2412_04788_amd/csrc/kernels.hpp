@@ -27,26 +27,27 @@ struct FusedFilter {
     double cap[GUIDE_MAX_CONSTRAINTS];
 };
 struct FusedSelect {
-    // rider_blocks != 0 (plain evaluation only): that many extra blocks at the end of the grid take the row sample
-    // of a Pareto selection over the evaluated rows (pareto_x, pareto_y, pareto_filter, scratch below) by
-    // evaluating the sampled rows themselves, beside the blocks that evaluate and store the grid.
+    // rider_blocks != 0: that many extra blocks at the end of the grid take the row sample of a Pareto selection
+    // over the evaluated rows (pareto_x, pareto_y, pareto_filter, scratch below) by evaluating the sampled rows
+    // themselves, beside the blocks that evaluate and store the grid.
     uint32_t rider_blocks;
     uint32_t topk, topk_obj;                    // topk != 0: least kFusedTopK rows by column topk_obj
     FusedFilter topk_filter;
     void *topk_ws;                              // block partials, layout of the top-k pass
-    uint32_t pareto, pareto_x, pareto_y;        // pareto != 0: sample (x, y) rows, reset the bin tables
+    uint32_t pareto, pareto_x, pareto_y;        // pareto != 0: a Pareto selection over (x, y) follows: take its row sample
     FusedFilter pareto_filter;
     void *scratch;                              // scratch of the Pareto kernels
 };
-// sample != nullptr (grids with a tile kernel only): extra blocks sample the rows for the Pareto selection that
-// sample->pareto_* describe; *sample_partials receives the number of block partials they write (0: not taken).
+// sample != nullptr (grids with a tile kernel only): extra blocks take the row sample of the Pareto selection that
+// sample->pareto_* describe; *sampled tells whether they did.
 hipError_t launch_eval_grid(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
                             uint32_t count, double e_c, double e_b, bool additive, const guide_metrics &out,
                             hipStream_t stream, LaunchTiming timing = LaunchTiming(), const FusedSelect *sample = nullptr,
-                            uint32_t *sample_partials = nullptr);
+                            bool *sampled = nullptr);
 // True when the grid's two fastest axes have a compiled tile kernel (the only one that folds selections in).
 bool eval_grid_can_fuse(const GridDesc &g);
-// As launch_eval_grid; *n_blocks receives the number of blocks that wrote partials.
+// The evaluation with a top-k folded in (and the row sample of fs.pareto taken by extra blocks); *n_blocks
+// receives the number of blocks that wrote top-k partials.
 hipError_t launch_eval_grid_fused(const GridDesc &g, const DevTables *tab, const void *tile_tables, uint32_t first,
                                   uint32_t count, double e_c, double e_b, bool additive, const guide_metrics &out,
                                   const FusedSelect &fs, hipStream_t stream, uint32_t *n_blocks,
@@ -54,15 +55,14 @@ hipError_t launch_eval_grid_fused(const GridDesc &g, const DevTables *tab, const
 // Second halves of the folded selections.
 hipError_t launch_topk_merge(void *ws, uint32_t n_blocks, uint32_t k, const guide_select_out &out, hipStream_t stream);
 hipError_t launch_pareto_sampled(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
-                                 void *scratch, uint32_t n_partials, void *merge_ws, uint32_t merge_blocks,
+                                 void *scratch, void *merge_ws, uint32_t merge_blocks,
                                  uint32_t merge_k, const guide_select_out *merge_out, hipStream_t stream,
                                  uint32_t row_chunk = 0);
 size_t topk_partials_bytes();
-// sampled_partials != 0: the caller's evaluation kernel has already sampled the rows (that many block partials)
-// and reset the bin tables, so no sample is launched.
+// sampled: the caller's evaluation kernel has already taken the row sample, so none is launched.
 hipError_t launch_select_both(const guide_select_spec &topk, const guide_select_out &topk_out, void *topk_ws,
                               const guide_select_spec &pareto, const guide_select_out &pareto_out, void *pareto_ws,
-                              uint64_t n, void *scratch, hipStream_t stream, uint32_t sampled_partials = 0,
+                              uint64_t n, void *scratch, hipStream_t stream, bool sampled = false,
                               uint32_t row_chunk = 0, const LaunchTiming *pass_timing = nullptr);
 // pass_timing: two event pairs for the filter and finishing kernels (or nullptr).
 // row_chunk: rows are dealt to the blocks of the selection passes in chunks of that many rows, chunk c to block

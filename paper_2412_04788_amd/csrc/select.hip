@@ -366,20 +366,20 @@ __global__ __launch_bounds__(kBlock) void topk_final_kernel(TopkWs w, uint32_t G
 
 // --------------------------------------------------------------------- Pareto
 //
-// Four launches.  The first can ride along with a top-k pass or with the kernel that produces the
+// Three launches.  The first can ride along with a top-k pass or with the kernel that produces the
 // columns; a top-k over the same columns can ride along with the second, and a top-k merge with the last.
-// Prepare: a strided sample of rows fixes the stretch of x that the bins slice; it also resets
-// the tables that the next two kernels accumulate into.
-// Staircase: every block builds in LDS the least y per x-bin over its rows (kBins
-// equal slices of that stretch, clamped at both ends, so a lower bin means a
-// strictly smaller x) and merges its running minima into the global table with atomic-min.
-// Survivors: a row survives when its y beats every row of every strictly lower
-// bin (exclusive prefix-min of the table) -- only survivors of its own bin can
-// still dominate it.  Survivors are appended as (row, keys).
-// Finish: survivors are grouped by bin, tested exactly inside their bin, and front
-// members are written at (front members of lower bins) + (rank inside the bin),
-// which orders the output by (x, y, row).  One block does this in LDS for up to
-// kStage survivors; more are shared out among kLargeParts blocks by runs of bins.
+// Sample: kSampleBlocks blocks take a scattered sample of rows.  It fixes the stretch of x that the bins
+// slice (kBins equal slices of key space, clamped at both ends, so a lower bin means a strictly smaller x),
+// and every wave hands over the front of its sample rows.  The block that takes sample 0 also resets the
+// counters that the next two kernels accumulate into.
+// Filter: every block bins the handed-over sample rows (least y per bin, exclusive prefix-min) and keeps a
+// row when no sample row of a strictly lower bin has a y at or below its own.  The kept rows contain the
+// front, and every other kept row is dominated by a kept one.  Kept rows are appended as (row, keys).
+// Finish: kept rows are binned; those that a kept row of a strictly lower bin dominates (least y per bin
+// over the kept rows, exclusive prefix-min) or that their own bin's representative dominates are dropped,
+// the rest are grouped by bin and tested exactly inside their bin, and front members are written at (front
+// members of lower bins) + (rank inside the bin), which orders the output by (x, y, row).  One block does
+// this in LDS for up to kStage kept rows; more are shared out among kLargeParts blocks by runs of bins.
 
 constexpr uint32_t kStage = 4096;        // survivors whose records the finishing block holds in LDS
 constexpr uint32_t kFinishThreads = 1024;
@@ -473,30 +473,14 @@ __global__ __launch_bounds__(kBlock) void pareto_prepare_kernel(const double *__
     pareto_prepare_body(blockIdx.x, x, y, f, n, sc);
 }
 
-// Combines the n_partials per-block sample partials (the same result in every block): the
-// first wave loads them, a few per lane, and reduces; s_rng (2 entries) carries the result to
+// Combines the kSampleBlocks per-block sample partials (the same result in every block): the
+// first wave loads them, one per lane, and reduces; s_rng (2 entries) carries the result to
 // the other waves.  Contains a block barrier.
-__device__ inline Binning sampled_binning(const SelectScratch *sc, uint32_t n_partials, uint64_t *s_rng) {
+__device__ inline Binning sampled_binning(const SelectScratch *sc, uint64_t *s_rng) {
+    static_assert(kSampleBlocks == kWave, "one partial per lane of the first wave");
     if (threadIdx.x < kWave) {
-        constexpr uint32_t kPer = kMaxSamplePartials / kWave;
-        uint64_t plo[kPer];
-        Pair pbest[kPer];
-#pragma unroll
-        for (uint32_t q = 0; q < kPer; ++q) {                // all loads first: one memory latency
-            const uint32_t i = q * kWave + threadIdx.x;
-            const bool live = i < n_partials;
-            plo[q] = live ? sc->sample_lo[i] : kNone;
-            pbest[q] = live ? sc->sample_best[i] : Pair{kNone, kNone};
-        }
-        uint64_t lo = plo[0];
-        Pair best = pbest[0];
-#pragma unroll
-        for (uint32_t q = 1; q < kPer; ++q) {
-            lo = min_u64(lo, plo[q]);
-            best = pair_min(best, pbest[q]);
-        }
-        lo = wave_min(lo);
-        best = wave_min(best);
+        uint64_t lo = wave_min(sc->sample_lo[threadIdx.x]);
+        const Pair best = wave_min(sc->sample_best[threadIdx.x]);
         uint64_t hi = best.idx;
         if (lo == kNone || hi < lo) {   // no passing sample row: one slice per 2^52 keys
             lo = 0;
@@ -602,131 +586,6 @@ struct SharedTopk {
     Top1Ws w;                      // block partials, as written by the top-k pass
 };
 
-template <uint32_t MAXC, uint32_t U>
-__global__ __launch_bounds__(kBlock) void pareto_stair_kernel(const double *__restrict__ x, const double *__restrict__ y,
-                                                              RowFilter f, uint32_t n, SelectScratch *sc, uint32_t n_partials,
-                                                              uint32_t chunk) {
-    __shared__ uint64_t s_min[padded_size<kPerPass>()], s_tmp[kWaves], s_rng[2];
-    // the first batch of rows is requested before the set-up below, so that its latency overlaps it
-    RawRow<MAXC> r[U];
-    ChunkWalk<U> cw(chunk, n, gridDim.x);
-    if (cw.live()) {
-#pragma unroll
-        for (uint32_t u = 0; u < U; ++u)
-            r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)cw.base + threadIdx.x + u * kBlock, (uint32_t)cw.end);
-    }
-    for (uint32_t i = threadIdx.x; i < padded_size<kPerPass>(); i += kBlock) s_min[i] = kNone;
-    const Binning bin = sampled_binning(sc, n_partials, s_rng);     // its barrier also covers the table above
-    while (cw.live()) {
-        // the next batch is requested before this one is worked on
-        RawRow<MAXC> rn[U];
-        cw.next();
-        const bool more = cw.live();
-        if (more) {
-#pragma unroll
-            for (uint32_t u = 0; u < U; ++u)
-                rn[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)cw.base + threadIdx.x + u * kBlock, (uint32_t)cw.end);
-        }
-#pragma unroll
-        for (uint32_t u = 0; u < U; ++u) {
-            const Row q = row_of<true, MAXC>(r[u], f);
-            if (q.pass) {
-                const uint32_t b = padded<kPerPass>(bin(key_of(q.x)));
-                const uint64_t ky = key_of(q.y);
-                // the slot only decreases, so a stale read can only let an extra atomic through
-                if (ky < s_min[b]) atomicMin((unsigned long long *)&s_min[b], (unsigned long long)ky);
-            }
-        }
-        if (more) {
-#pragma unroll
-            for (uint32_t u = 0; u < U; ++u) r[u] = rn[u];
-        }
-    }
-    __syncthreads();
-    // The table is only read through its exclusive prefix-min, and only a block's running minima
-    // (entries below everything in its lower bins) can lower that: the others are not sent.  The
-    // atomics return nothing, so no lane waits for them.
-    uint64_t v[kPerPass];
-#pragma unroll
-    for (uint32_t j = 0; j < kPerPass; ++j) v[j] = s_min[threadIdx.x * (kPerPass + 1) + j];
-    uint64_t run = prefix_min_before<kBlock>(v, s_tmp);
-#pragma unroll
-    for (uint32_t j = 0; j < kPerPass; ++j) {
-        if (v[j] < run) {
-            atomicMin((unsigned long long *)&sc->bin_min[threadIdx.x * kPerPass + j], (unsigned long long)v[j]);
-            run = v[j];
-        }
-    }
-}
-
-template <uint32_t MAXC, uint32_t U>
-__global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *__restrict__ x,
-                                                                  const double *__restrict__ y, RowFilter f, uint32_t n,
-                                                                  ParetoWs w, SelectScratch *sc, uint32_t n_partials,
-                                                                  uint32_t chunk) {
-    __shared__ uint64_t s_lower[padded_size<kPerPass>()], s_tmp[kWaves], s_rng[2];
-    const int lane = threadIdx.x % kWave;
-    // requested first, and in this order: the table, then the first batch of rows, whose latency
-    // overlaps the scan of the table
-    uint64_t tbl[kPerPass];
-#pragma unroll
-    for (uint32_t j = 0; j < kPerPass; ++j) tbl[j] = sc->bin_min[j * kBlock + threadIdx.x];
-    RawRow<MAXC> r[U];
-    ChunkWalk<U> cw(chunk, n, gridDim.x);
-    if (cw.live()) {
-#pragma unroll
-        for (uint32_t u = 0; u < U; ++u)
-            r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)cw.base + threadIdx.x + u * kBlock, (uint32_t)cw.end);
-    }
-#pragma unroll
-    for (uint32_t j = 0; j < kPerPass; ++j) s_lower[padded<kPerPass>(j * kBlock + threadIdx.x)] = tbl[j];
-    const Binning bin = sampled_binning(sc, n_partials, s_rng);     // its barrier also covers the table above
-    scan_min_excl<kBlock>(s_lower, s_tmp);              // least y over strictly lower bins
-    // wave-uniform trip count: the ballots below need every lane
-    while (cw.live()) {
-        const uint32_t base = (uint32_t)cw.base;
-        // the next batch is requested before this one is worked on
-        RawRow<MAXC> rn[U];
-        cw.next();
-        const bool more = cw.live();
-        if (more) {
-#pragma unroll
-            for (uint32_t u = 0; u < U; ++u)
-                rn[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)cw.base + threadIdx.x + u * kBlock, (uint32_t)cw.end);
-        }
-#pragma unroll
-        for (uint32_t u = 0; u < U; ++u) {
-            const uint32_t i = base + threadIdx.x + u * kBlock;
-            const Row q = row_of<true, MAXC>(r[u], f);
-            uint32_t b = 0;
-            uint64_t kx = 0, ky = 0;
-            bool keep = false;
-            if (q.pass) {
-                kx = key_of(q.x);
-                ky = key_of(q.y);
-                b = bin(kx);
-                keep = ky < s_lower[padded<kPerPass>(b)];
-            }
-            const uint64_t mask = __ballot(keep);       // wave-aggregated append
-            if (mask) {
-                const int leader = __ffsll((long long)mask) - 1;
-                uint32_t at = 0;
-                if (lane == leader) at = atomicAdd(&sc->counters[0], (uint32_t)__popcll(mask));
-                at = __shfl(at, leader, kWave) + __popcll(mask & ((1ull << lane) - 1));
-                if (keep) {
-                    w.surv[at] = i;
-                    w.skx[at] = kx;
-                    w.sky[at] = ky;
-                }
-            }
-        }
-        if (more) {
-#pragma unroll
-            for (uint32_t u = 0; u < U; ++u) r[u] = rn[u];
-        }
-    }
-}
-
 // The filter pass of the three-launch form: the sampling blocks have handed over the front of their sample
 // rows (SelectScratch::sample_front); every block bins those few rows in LDS (least y per bin, then its
 // exclusive prefix-min) and keeps a row when no sample row of a strictly lower bin has a y at or below its
@@ -738,7 +597,7 @@ __global__ __launch_bounds__(kBlock) void pareto_survivors_kernel(const double *
 template <uint32_t MAXC, int KT, uint32_t U>
 __global__ __launch_bounds__(kBlock) void pareto_filter_kernel(const double *__restrict__ x, const double *__restrict__ y,
                                                                RowFilter f, uint32_t n, ParetoWs w, SelectScratch *sc,
-                                                               uint32_t n_partials, SharedTopk topk, uint32_t chunk) {
+                                                               SharedTopk topk, uint32_t chunk) {
     __shared__ uint64_t s_lower[padded_size<kPerPass>()], s_tmp[kWaves], s_rng[2];
     constexpr int KL = KT ? KT : 1;
     constexpr uint32_t kPerSample = kSampleBlocks * kSampleFrontPer / kBlock;
@@ -760,7 +619,7 @@ __global__ __launch_bounds__(kBlock) void pareto_filter_kernel(const double *__r
             r[u] = load_raw<true, MAXC>(x, y, f, (uint32_t)cw.base + threadIdx.x + u * kBlock, (uint32_t)cw.end);
     }
     for (uint32_t i = threadIdx.x; i < padded_size<kPerPass>(); i += kBlock) s_lower[i] = kNone;
-    const Binning bin = sampled_binning(sc, n_partials, s_rng);     // its barrier also covers the table above
+    const Binning bin = sampled_binning(sc, s_rng);     // its barrier also covers the table above
 #pragma unroll
     for (uint32_t j = 0; j < kPerSample; ++j)
         if (sf[j].idx != kNone)
@@ -1239,7 +1098,7 @@ __device__ void pareto_large_front(FinishLds &L, const ParetoWs &w, SelectScratc
 // Blocks of the launch: 0 finishes the front; 1 runs a waiting top-k merge (only launched with one); the
 // others return at once unless more than kStage rows survived, and then share the large front with block 0.
 __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs w, uint32_t n, SelectScratch *sc,
-                                                                        uint32_t n_partials, uint64_t *out_idx,
+                                                                        uint64_t *out_idx,
                                                                         uint64_t capacity, uint64_t *out_count,
                                                                         MergeRider rider) {
     const uint32_t first_helper = rider.n_blocks ? 2 : 1;
@@ -1285,7 +1144,7 @@ __global__ __launch_bounds__(kFinishThreads) void pareto_finish_kernel(ParetoWs 
         L.rep[i] = kNone;
         L.cur[i] = 0;
     }
-    const Binning bin = sampled_binning(sc, n_partials, L.rng);     // its barrier also covers the tables above
+    const Binning bin = sampled_binning(sc, L.rng);     // its barrier also covers the tables above
     if (m > kStage) {
         pareto_large_front(L, w, sc, bin, m, helper ? blockIdx.x - first_helper + 1 : 0, gridDim.x - first_helper + 1,
                            out_idx, capacity, out_count);
@@ -1437,14 +1296,12 @@ static void launch_timed(Kernel kernel, dim3 grid, dim3 block, hipStream_t strea
     else hipLaunchKernelGGL(kernel, grid, block, 0, stream, args...);
 }
 
-// The passes after the row sample.  sample_fronts: the sample was taken by kSampleBlocks blocks that handed over the
-// fronts of their sample rows (the prepare kernel or its body as a rider): one filter pass and the finishing kernel.
-// Otherwise (the sample was taken inside another kernel's own loop): staircase, survivors, finish.
-// tm: two event pairs (filter, finish) or none; only used with sample_fronts.
+// The passes after the row sample: the filter pass (with the per-lane lists of a top-k that shares the
+// columns) and the finishing kernel.  tm: two event pairs (filter, finish) or none.
 static hipError_t launch_pareto_passes(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
-                                       SelectScratch *sc, uint32_t n_partials, bool sample_fronts, const MergeRider &rider,
-                                       hipStream_t stream, const SharedTopk *shared = nullptr, int shared_k = 0,
-                                       uint32_t row_chunk = 0, const LaunchTiming *tm = nullptr) {
+                                       SelectScratch *sc, const MergeRider &rider, hipStream_t stream,
+                                       const SharedTopk *shared = nullptr, int shared_k = 0, uint32_t row_chunk = 0,
+                                       const LaunchTiming *tm = nullptr) {
     const LaunchTiming *tm_filter = tm, *tm_fin = tm ? tm + 1 : nullptr;
     const ParetoWs w = pareto_ws(ws, n);
     const RowFilter f = make_filter(spec);
@@ -1453,29 +1310,23 @@ static hipError_t launch_pareto_passes(const guide_select_spec &spec, uint64_t n
     const dim3 grid(nb), block(kBlock);
     with_row_chunk(row_chunk, [&](uint32_t chunk, auto u) {
         constexpr uint32_t U = decltype(u)::value;
-        if (sample_fronts && shared) {      // only offered for a Pareto selection without constraint columns
+        if (shared) {       // only offered for a Pareto selection without constraint columns
             const SharedTopk t = *shared;
-            if (shared_k == 1) launch_timed(pareto_filter_kernel<0, 1, U>, grid, block, stream, tm_filter, x, y, f, n32, w, sc, n_partials, t, chunk);
-            else if (shared_k == 2) launch_timed(pareto_filter_kernel<0, 2, U>, grid, block, stream, tm_filter, x, y, f, n32, w, sc, n_partials, t, chunk);
-            else if (shared_k == 3) launch_timed(pareto_filter_kernel<0, 3, U>, grid, block, stream, tm_filter, x, y, f, n32, w, sc, n_partials, t, chunk);
-            else launch_timed(pareto_filter_kernel<0, 4, U>, grid, block, stream, tm_filter, x, y, f, n32, w, sc, n_partials, t, chunk);
+            if (shared_k == 1) launch_timed(pareto_filter_kernel<0, 1, U>, grid, block, stream, tm_filter, x, y, f, n32, w, sc, t, chunk);
+            else if (shared_k == 2) launch_timed(pareto_filter_kernel<0, 2, U>, grid, block, stream, tm_filter, x, y, f, n32, w, sc, t, chunk);
+            else if (shared_k == 3) launch_timed(pareto_filter_kernel<0, 3, U>, grid, block, stream, tm_filter, x, y, f, n32, w, sc, t, chunk);
+            else launch_timed(pareto_filter_kernel<0, 4, U>, grid, block, stream, tm_filter, x, y, f, n32, w, sc, t, chunk);
             return;
         }
         with_max_constraints(f.n_con, [&](auto maxc) {
             constexpr uint32_t MAXC = decltype(maxc)::value;
-            if (sample_fronts) {
-                launch_timed(pareto_filter_kernel<MAXC, 0, U>, grid, block, stream, tm_filter, x, y, f, n32, w, sc, n_partials,
-                             SharedTopk{}, chunk);
-            } else {
-                hipLaunchKernelGGL((pareto_stair_kernel<MAXC, U>), grid, block, 0, stream, x, y, f, n32, sc, n_partials, chunk);
-                hipLaunchKernelGGL((pareto_survivors_kernel<MAXC, U>), grid, block, 0, stream, x, y, f, n32, w, sc, n_partials,
-                                   chunk);
-            }
+            launch_timed(pareto_filter_kernel<MAXC, 0, U>, grid, block, stream, tm_filter, x, y, f, n32, w, sc, SharedTopk{},
+                         chunk);
         });
     });
     const uint32_t helpers = n > kStage ? kLargeParts - 1 : 0;     // no more than kStage rows: the staged path for sure
     launch_timed(pareto_finish_kernel, dim3((rider.n_blocks ? 2 : 1) + helpers), dim3(kFinishThreads), stream, tm_fin, w, n32,
-                 sc, n_partials, out.idx, out.capacity, out.count, rider);
+                 sc, out.idx, out.capacity, out.count, rider);
     return hipGetLastError();
 }
 
@@ -1488,7 +1339,7 @@ hipError_t launch_select_pareto(const guide_select_spec &spec, uint64_t n, const
     SelectScratch *sc = (SelectScratch *)scratch;
     hipLaunchKernelGGL(pareto_prepare_kernel, dim3(kSampleBlocks), dim3(kBlock), 0, stream, spec.objective,
                        spec.objective_y, make_filter(spec), (uint32_t)n, sc);
-    return launch_pareto_passes(spec, n, out, ws, sc, kSampleBlocks, true, MergeRider{}, stream);
+    return launch_pareto_passes(spec, n, out, ws, sc, MergeRider{}, stream);
 }
 
 // True when the top-k selection reads only the Pareto selection's x, y and flag columns (and the Pareto
@@ -1511,21 +1362,20 @@ static bool shares_columns(const guide_select_spec &topk, const guide_select_spe
     return true;
 }
 
-// A top-k selection (one group) and a Pareto selection over the same n > 0 rows in four launches
-// instead of six.  The top-k merge rides along with the finishing kernel of the Pareto front (for block
+// A top-k selection (one group) and a Pareto selection over the same n > 0 rows in three launches
+// instead of five.  The top-k merge rides along with the finishing kernel of the Pareto front (for block
 // partials of up to 4 pairs; wider ones merge alone).  When the top-k reads only the Pareto selection's
-// columns, its pass is folded into the staircase kernel (sample, staircase + lists, survivors, finish +
-// merge); otherwise the Pareto row sample rides along with the top-k pass (pass + sample, staircase,
-// survivors, finish + merge).
+// columns, its pass is folded into the filter pass (sample, filter + lists, finish + merge); otherwise the
+// Pareto row sample rides along with the top-k pass (pass + sample, filter, finish + merge).
+// sampled: the caller's own kernel has taken the row sample.
 hipError_t launch_select_both(const guide_select_spec &topk, const guide_select_out &topk_out, void *topk_ws,
                               const guide_select_spec &pareto, const guide_select_out &pareto_out, void *pareto_ws_,
-                              uint64_t n, void *scratch, hipStream_t stream, uint32_t sampled_partials,
+                              uint64_t n, void *scratch, hipStream_t stream, bool sampled,
                               uint32_t row_chunk, const LaunchTiming *pass_timing) {
     SelectScratch *sc = (SelectScratch *)scratch;
     const int K = partial_width(topk.k);
     SharedTopk shared;
     const bool folded = shares_columns(topk, pareto, &shared);
-    const bool sampled = sampled_partials != 0;         // the caller's own kernel has sampled the rows and reset the tables
     if (folded) {
         shared.w = top1_ws(topk_ws);
         if (!sampled)
@@ -1541,24 +1391,22 @@ hipError_t launch_select_both(const guide_select_spec &topk, const guide_select_
                            topk_out.val, topk_out.count};       // partials: one per block of the kernel that kept the lists
     else
         launch_top1_merge(K, topk_ws, blocks_for(n), topk.k, topk_out, stream);
-    return launch_pareto_passes(pareto, n, pareto_out, pareto_ws_, sc, sampled ? sampled_partials : kSampleBlocks, true,
-                                rider, stream, folded ? &shared : nullptr, K, row_chunk, pass_timing);
+    return launch_pareto_passes(pareto, n, pareto_out, pareto_ws_, sc, rider, stream, folded ? &shared : nullptr, K, row_chunk,
+                                pass_timing);
 }
 
-// The passes after the sample, for a caller whose own kernel has sampled the rows and reset the tables.
+// The passes after the sample, for a caller whose own kernel has taken the row sample.
 // merge_ws != nullptr: the merge of a folded top-k (merge_blocks block partials of kFusedTopK pairs) rides
 // along with the finishing kernel instead of taking a launch of its own.
 hipError_t launch_pareto_sampled(const guide_select_spec &spec, uint64_t n, const guide_select_out &out, void *ws,
-                                 void *scratch, uint32_t n_partials, void *merge_ws, uint32_t merge_blocks,
+                                 void *scratch, void *merge_ws, uint32_t merge_blocks,
                                  uint32_t merge_k, const guide_select_out *merge_out, hipStream_t stream,
                                  uint32_t row_chunk) {
     MergeRider rider{};
     if (merge_ws)
         rider = MergeRider{top1_ws(merge_ws), merge_blocks, merge_k, (uint32_t)kFusedTopK, merge_out->idx, merge_out->val,
                            merge_out->count};
-    // a sample taken by the evaluation kernel's extra blocks comes with the sample fronts; one taken in its loop does not
-    return launch_pareto_passes(spec, n, out, ws, (SelectScratch *)scratch, n_partials, merge_ws == nullptr, rider, stream,
-                                nullptr, 0, row_chunk);
+    return launch_pareto_passes(spec, n, out, ws, (SelectScratch *)scratch, rider, stream, nullptr, 0, row_chunk);
 }
 
 size_t topk_partials_bytes() { return top1_ws_bytes(); }

@@ -11,17 +11,15 @@ constexpr uint32_t kSelBlocks = 1024;      // most blocks of a streaming pass (f
 
 // Context-owned device scratch of the Pareto kernels.  The kernel of a call that takes
 // the row sample puts what the later ones accumulate into (the survivor counter, the
-// ticket counter, bin_min when the staircase kernel follows) into its neutral state, so
-// the scratch needs no set-up and no call depends on how the previous one ended.
+// ticket counter) into its neutral state, so the scratch needs no set-up and no call
+// depends on how the previous one ended.
 constexpr uint32_t kBins = 4096;
-constexpr uint32_t kMaxSamplePartials = 512;     // blocks of the kernel that samples rows (prepare or evaluation)
-constexpr uint32_t kSampleBlocks = 64;           // sampling blocks of kBlock rows each when the sample is taken by blocks of its own
+constexpr uint32_t kSampleBlocks = 64;           // blocks of kBlock rows each that take the row sample (a kernel of their own or riders)
 constexpr uint32_t kSampleFrontPer = 32;         // sample rows that one such block hands to the filter pass, at most
 struct SelectScratch {
     uint32_t counters[4];          // [0] survivors appended, [1] tickets drawn by the parts of a large front
-    uint64_t sample_lo[kMaxSamplePartials];   // per sampling block: least x key of passing sample rows
-    Pair sample_best[kMaxSamplePartials];     // per sampling block: (least y key, its x key)
-    uint64_t bin_min[kBins];       // staircase kernel: y keys per x bin whose exclusive prefix-min is that of the least y per bin
+    uint64_t sample_lo[kSampleBlocks];       // per sampling block: least x key of passing sample rows
+    Pair sample_best[kSampleBlocks];         // per sampling block: (least y key, its x key)
     uint32_t part_lo[64], part_cnt[64];   // large-front path only: per part, its first survivor slot and its front members
     Pair sample_front[kSampleBlocks * kSampleFrontPer];   // (y key, x key) of sample rows that prune; unused slots kNone
 };
