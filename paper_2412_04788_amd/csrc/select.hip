@@ -126,16 +126,17 @@ RowFilter make_filter(const guide_select_spec &s) {
     return f;
 }
 
-// Blocks of a streaming pass over n rows.  Top-k passes: up to four per compute unit.  Pareto passes: two per
-// compute unit -- every block of those fills or loads a 32 KB table, which with more blocks costs more than the
-// extra blocks hide (512 and 768 blocks measured alike on 1.9M rows, 1024 and 256 slower).
+// Blocks of a streaming pass over n rows.  Top-k passes: up to four per compute unit.  The Pareto filter pass:
+// three per compute unit -- every block loads a 32 KB table of sample rows and ends with a block-level top-k
+// merge, which with more blocks costs more than the extra blocks hide (1.9M rows in chunks of 1536: 13.8 us with
+// 768 blocks, 14.5 with 1024, 15.0 with 624, 15.1 - 15.6 with 512, 16.2 with 416).
 uint32_t blocks_for(uint64_t n) {
     uint64_t need = (n + kBlock - 1) / kBlock;
     if (need == 0) need = 1;
     return (uint32_t)(need < kSelBlocks ? need : kSelBlocks);
 }
 uint32_t pareto_blocks(uint64_t n) {
-    uint64_t need = (n + kBlock - 1) / kBlock, cap = 2 * (uint64_t)device_cus();
+    uint64_t need = (n + kBlock - 1) / kBlock, cap = 3 * (uint64_t)device_cus();
     if (need == 0) need = 1;
     cap = cap < kSelBlocks ? cap : kSelBlocks;
     return (uint32_t)(need < cap ? need : cap);
