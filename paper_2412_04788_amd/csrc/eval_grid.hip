@@ -218,9 +218,9 @@ __device__ inline void sample_rider(const GridLds &s, const GridDesc &g, uint32_
     }
 }
 
-// FUSED: selections folded in (FusedSelect); every block then writes its top-K partials and / or its
-// sample partial, also when it owns no tile.
-template <bool ADDITIVE, int NB, int NM, bool FUSED>
+// FUSED: a top-k folded in (FusedSelect); every block then writes its top-K partials, also when it owns no tile.
+// STREAM: full waves store the 8-byte columns with the streaming hint.
+template <bool ADDITIVE, int NB, int NM, bool FUSED, bool STREAM>
 __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const DevTables *__restrict__ tab,
                                                            uint32_t first, uint32_t count, double re_c, double re_b,
                                                            guide_metrics out, FusedSelect fs,
@@ -304,7 +304,10 @@ __global__ __launch_bounds__(kBlock) void eval_tile_kernel(GridDesc g, const Dev
             if (full) {
                 double *dst = col + (cfg0 - first) + lane;
 #pragma unroll
-                for (int it = 0; it < TS; ++it) dst[it * kWave] = xw[it * kWave + lane];
+                for (int it = 0; it < TS; ++it) {
+                    if (STREAM) __builtin_nontemporal_store(xw[it * kWave + lane], &dst[it * kWave]);
+                    else dst[it * kWave] = xw[it * kWave + lane];
+                }
             } else {
 #pragma unroll
                 for (int it = 0; it < TS; ++it) {
@@ -700,6 +703,7 @@ static uint32_t tile_blocks(uint32_t first, uint32_t count, uint32_t ts) {
 
 // Rows sampled for a Pareto selection over the evaluated rows.
 constexpr uint32_t kSampleRows = 16384;
+constexpr uint64_t kStreamBytes = 64ull << 20;      // twice the 8 x 4 MB of L2: five 8-byte columns beyond that are streamed
 constexpr uint32_t kRiderBlocks = kSampleRows / kBlock;     // sample blocks appended to a plain evaluation
 static_assert(kRiderBlocks == kSampleBlocks, "the scratch holds one sample front per sample block");
 
@@ -712,6 +716,12 @@ static void launch_tile(const GridDesc &g, const DevTables *tab, const void *til
     const FusedSelect sel = fs ? *fs : FusedSelect{};
     const dim3 grid(tile_blocks(first, count, NB * NM) + sel.rider_blocks), block(kBlock);
     const TileLds *tables = (const TileLds *)tile_tables;
+    // Columns that together are larger than twice the chip's L2 are stored with the streaming hint: their lines
+    // would not survive in L2 until a reader comes anyway, and not keeping them there leaves the stores of the
+    // launch more room (20M rows: 163 - 166 us against 178 - 179 us; 1.9M rows inside an evaluate-and-select step:
+    // 17.4 against 17.8 us, the filter pass after it 13.4 against 13.1 us; smaller outputs stay cached for their readers).
+    // (a kernel of its own: a run-time choice between the two kinds of store compiles to the plain one)
+    const bool stream_stores = (uint64_t)count * 40 >= kStreamBytes;
     auto launch = [&](auto kernel) {
         // with timing events the launch goes through the extended call, which attaches them to the dispatch
         if (tm.start)
@@ -720,8 +730,9 @@ static void launch_tile(const GridDesc &g, const DevTables *tab, const void *til
         else
             hipLaunchKernelGGL(kernel, grid, block, 0, stream, g, tab, first, count, re_c, re_b, out, sel, tables);
     };
-    if (sel.topk) launch(eval_tile_kernel<ADDITIVE, NB, NM, true>);
-    else launch(eval_tile_kernel<ADDITIVE, NB, NM, false>);
+    if (sel.topk) launch(eval_tile_kernel<ADDITIVE, NB, NM, true, false>);
+    else if (stream_stores) launch(eval_tile_kernel<ADDITIVE, NB, NM, false, true>);
+    else launch(eval_tile_kernel<ADDITIVE, NB, NM, false, false>);
 }
 
 // Tile shapes with a compiled kernel (up to four values on each of the two fastest axes); other grids take the
