@@ -208,7 +208,7 @@ def main():
                    "pareto_front_size": int(par_cnt.item())},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": counter_figure("eval_tile_traffic_bytes"),
-                     "kernel": "eval_tile_kernel<false,2,3,false>",
+                     "kernel": "eval_tile_kernel<false,2,3,false,true>",
                      "kernel_ms": ms_eval, "kernel_ms_min": float(np.min(ms_kernel)),
                      "kernel_launches_timed": n_timed,
                      "timing": "HIP event pairs on the dispatches of the three kernels of every 8th step of a run of 8 x kernel_launches_timed steps",
