@@ -72,6 +72,20 @@ def test_ranges_tails_and_null_columns(ora, torch_cuda):
         ctx.eval_grid(gg, first, count, out=out)
         torch.cuda.synchronize()
         _compare(out, ora.eval_grid(og, first, count), (first, count))
+    # a range large enough for the kernel variant that stores large outputs with the streaming hint, starting and
+    # ending inside a tile: its head, its tail and stretches in between, with canaries around the buffers' ends
+    first, count = 7, g.size - 20
+    out = bridge.metric_buffers(count + 2)
+    for v in out.values():
+        v.fill_(77)
+    view = {k: v[1:count + 1] for k, v in out.items()}
+    ctx.eval_grid(gg, first, count, out=view)
+    torch.cuda.synchronize()
+    for k, v in out.items():
+        assert float(v[0]) == 77 and float(v[count + 1]) == 77, k
+    for lo, n_rows in [(0, 3000), (count - 3000, 3000), (count // 3, 2000), (1234567, 2000)]:
+        part = {k: v[lo:lo + n_rows] for k, v in view.items()}
+        _compare(part, ora.eval_grid(og, first + lo, n_rows), (first, count, lo))
     # NULL columns are skipped, others still written
     out = bridge.metric_buffers(500, names=("t_batch", "feasible"))
     ctx.eval_grid(gg, 5000, 500, out=out)
