@@ -26,10 +26,10 @@ VECTOR_ISSUE_PEAK = 256 * 4 * 16 * 2.4e9      # lane-instructions per second: 25
 # Figures taken from rocprofv3 counter runs (profiles/*.md), each with the SHA-256 (first 16 hex digits) of the
 # kernel sources it was measured on.  A figure is reported only while those sources are unchanged, else null.
 COUNTERS = {
-    # in-step launches (with the row-sample blocks): WRITE_SIZE 83603.79 KiB x 1.0 + FETCH_SIZE 259.31 KiB x 2.0 per
+    # in-step launches (with the row-sample blocks): WRITE_SIZE 83594.39 KiB x 1.0 + FETCH_SIZE 259.32 KiB x 2.0 per
     # launch (scales from a 512 MiB device copy): profiles/eval_tile_kernel_full_grid_pmc.md
-    "eval_tile_traffic_bytes": {"value": 86_141_348, "sources": ("eval_grid.hip", "perf_model.hpp"),
-                                "sha16": "fd2cb5ec0b541d6c"},
+    "eval_tile_traffic_bytes": {"value": 86_131_743, "sources": ("eval_grid.hip", "perf_model.hpp"),
+                                "sha16": "e6fb412dd396ef0b"},
     # SQ_INSTS_VALU 5.138e9 x 64 / 41.08 ms / 39.32e12 for simulate_kernel, split-fuse, stepped:
     # profiles/extra_kernels_valu_pmc.md
     "simulate_vector_issue_frac": {"value": 0.204, "sources": ("simulate.hip", "perf_model.hpp"), "sha16": "78cd9103d96c831d"},

@@ -703,7 +703,7 @@ static uint32_t tile_blocks(uint32_t first, uint32_t count, uint32_t ts) {
 
 // Rows sampled for a Pareto selection over the evaluated rows.
 constexpr uint32_t kSampleRows = 16384;
-constexpr uint64_t kStreamBytes = 64ull << 20;      // twice the 8 x 4 MB of L2: five 8-byte columns beyond that are streamed
+constexpr uint64_t kStreamBytes = 64ull << 20;      // twice the 8 x 4 MB of L2: 8-byte columns that together reach it are streamed
 constexpr uint32_t kRiderBlocks = kSampleRows / kBlock;     // sample blocks appended to a plain evaluation
 static_assert(kRiderBlocks == kSampleBlocks, "the scratch holds one sample front per sample block");
 
@@ -721,7 +721,9 @@ static void launch_tile(const GridDesc &g, const DevTables *tab, const void *til
     // launch more room (20M rows: 163 - 166 us against 178 - 179 us; 1.9M rows inside an evaluate-and-select step:
     // 17.4 against 17.8 us, the filter pass after it 13.4 against 13.1 us; smaller outputs stay cached for their readers).
     // (a kernel of its own: a run-time choice between the two kinds of store compiles to the plain one)
-    const bool stream_stores = (uint64_t)count * 40 >= kStreamBytes;
+    const uint32_t n_f64 = (out.t_prefill ? 1u : 0u) + (out.t_decode ? 1u : 0u) + (out.t_batch ? 1u : 0u) +
+                           (out.decode_tok_s ? 1u : 0u) + (out.cost ? 1u : 0u);
+    const bool stream_stores = (uint64_t)count * 8 * n_f64 >= kStreamBytes;
     auto launch = [&](auto kernel) {
         // with timing events the launch goes through the extended call, which attaches them to the dispatch
         if (tm.start)
